@@ -1,0 +1,221 @@
+"""CPU oracle for the QR-Orth calibration step of DartQuant (arXiv 2511.04063).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain, fp64 statement of what
+one QR-Orth step computes.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import it.  It shares no code with the HIP
+library (no kernels, headers, helpers or tables) and never imports the product
+package; the product path never imports this module.
+
+Everything runs in float64 with NumPy.  Matrix products use ``@`` (a library
+primitive used as one step); everything else is written out.
+
+What the paper fixes and what it leaves open
+--------------------------------------------
+* Alg. 1 (Sec. 4.3), loop body:  R <- qr(Z);  O <- X @ R;  L <- Whip(O);
+  Z <- Z - eta * dL/dZ.
+* Eq. 4 (Sec. 4.2):  Whip(x) = sum_i exp(-|x_i|) for ONE activation vector x.
+* Sec. 4.3: QR of any Z gives an orthogonal R and an upper-triangular U, Z = R U.
+  (The paper calls the orthogonal factor R and the triangular factor U.)
+* Alg. 2 (App. B.1): Householder QR, v = x + sign(x_1) ||x|| e_1, v <- v/||v||,
+  reflect the trailing block and accumulate the orthogonal factor.
+
+Readings taken where the paper is silent (each is also listed in the design notes):
+* sign convention of the QR: diag(U) >= 0 (sign(0) := +1), which makes R unique for
+  nonsingular Z.  Loss and dZ do not depend on this choice.
+* Whip over a block of T tokens: ``reduce="mean"`` -> (1/T) * sum over tokens of the
+  per-token Whip (default);  ``reduce="sum"`` -> plain sum.  Parity unpinned by the
+  paper (a pure scale, equivalent to rescaling eta).
+* d|y|/dy at y = 0 is taken as 0.  Parity unpinned by the paper.
+* dL/dZ is not written in the paper (it says only "dL/dZ", Alg. 1 line 10).  It is
+  derived here from Z = R U:  with B = R^T G, P = strict_lower(B - B^T),
+  dZ = R P U^{-T}.  Pinned by finite differences of the whole map Z -> L, by the
+  structural identities of the true gradient, and by a library autograd route
+  (all in tests/).
+* Alg. 2 as printed updates only a square sub-block of the orthogonal factor and
+  stops at k = n-1; it is read as the textbook Householder QR (right-multiply ALL rows
+  of the accumulated factor, columns k..n), and the last diagonal entry's sign is
+  handled by the sign normalisation above.
+"""
+
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "householder_qr",
+    "qr_orth",
+    "rotate",
+    "whip_loss",
+    "whip_grad",
+    "grad_wrt_rotation",
+    "qr_backward",
+    "sgd_update",
+    "calib_step",
+    "calibrate",
+    "rotate_loss_grad",
+]
+
+
+def _f64(a) -> np.ndarray:
+    return np.array(a, dtype=np.float64, copy=True)
+
+
+def _reduce_scale(reduce: str, n_tokens: int) -> float:
+    """Scale c in L = c * sum_t sum_i exp(-|Y_ti|)  (reading of Alg. 1 line 9)."""
+    if reduce == "mean":
+        return 1.0 / float(n_tokens)
+    if reduce == "sum":
+        return 1.0
+    raise ValueError(f"unknown reduce mode {reduce!r}")
+
+
+def householder_qr(Z):
+    """Unblocked Householder QR, Alg. 2 (App. B.1), read as the textbook algorithm.
+
+    Returns (Q, U0) with Z = Q @ U0, Q orthogonal, U0 upper triangular.  The signs of
+    diag(U0) are whatever the reflections produce (they are fixed by ``qr_orth``).
+
+    Step k (Alg. 2 lines 5-9):  x = A[k:, k];  v = x + sign(x_1) ||x||_2 e_1 with
+    sign(0) = +1;  v <- v / ||v||_2;  A[k:, k:] -= 2 v (v^T A[k:, k:]);
+    Qacc[:, k:] -= 2 (Qacc[:, k:] v) v^T.   A zero column below (and on) the
+    diagonal is skipped (v would be 0).
+    """
+    A = _f64(Z)
+    if A.ndim != 2 or A.shape[0] != A.shape[1]:
+        raise ValueError("Z must be square")
+    n = A.shape[0]
+    Qacc = np.eye(n, dtype=np.float64)
+    for k in range(n):
+        x = A[k:, k].copy()
+        norm_x = np.sqrt(np.sum(x * x))
+        if norm_x == 0.0:
+            continue
+        sgn = 1.0 if x[0] >= 0.0 else -1.0
+        v = x
+        v[0] = v[0] + sgn * norm_x
+        v = v / np.sqrt(np.sum(v * v))
+        # reflect the trailing block of A (Alg. 2 line 8)
+        w = v @ A[k:, k:]
+        A[k:, k:] -= 2.0 * np.outer(v, w)
+        # accumulate the orthogonal factor on the right (Alg. 2 line 9, all rows)
+        q = Qacc[:, k:] @ v
+        Qacc[:, k:] -= 2.0 * np.outer(q, v)
+    U0 = np.triu(A)
+    return Qacc, U0
+
+
+def qr_orth(Z):
+    """Z -> (R, U): orthogonal R, upper-triangular U with diag(U) >= 0, Z = R @ U.
+
+    Sec. 4.3 (QR of the latent Z) followed by the sign normalisation
+    s_i = +1 if U0[i,i] >= 0 else -1;  R = Q diag(s);  U = diag(s) U0.
+    """
+    Q, U0 = householder_qr(Z)
+    s = np.where(np.diag(U0) >= 0.0, 1.0, -1.0)
+    R = Q * s[None, :]
+    U = U0 * s[:, None]
+    return R, U
+
+
+def rotate(X, R):
+    """O = X @ R  (Alg. 1 line 8; rows of X are tokens)."""
+    return _f64(X) @ _f64(R)
+
+
+def whip_loss(Y, reduce: str = "mean") -> float:
+    """L = c * sum_t sum_i exp(-|Y_ti|)  (Eq. 4 summed over the token rows)."""
+    Y = _f64(Y)
+    c = _reduce_scale(reduce, Y.shape[0])
+    return float(c * np.sum(np.exp(-np.abs(Y))))
+
+
+def whip_grad(Y, reduce: str = "mean") -> np.ndarray:
+    """dL/dY_ti = -c * sgn(Y_ti) * exp(-|Y_ti|), with sgn(0) = 0."""
+    Y = _f64(Y)
+    c = _reduce_scale(reduce, Y.shape[0])
+    return -c * np.sign(Y) * np.exp(-np.abs(Y))
+
+
+def grad_wrt_rotation(X, dY) -> np.ndarray:
+    """G = dL/dR = X^T @ dY   (chain rule through O = X @ R)."""
+    return _f64(X).T @ _f64(dY)
+
+
+def _solve_right_upper_transposed(W, U) -> np.ndarray:
+    """Solve M @ U^T = W for M (U upper triangular, so U^T is lower triangular).
+
+    Column j of the product is  sum_{k >= j} M[:, k] * U[j, k], so the columns are
+    found from the last to the first by substitution.
+    """
+    n = U.shape[0]
+    M = np.zeros_like(W)
+    for j in range(n - 1, -1, -1):
+        acc = W[:, j].copy()
+        if j + 1 < n:
+            acc -= M[:, j + 1:] @ U[j, j + 1:]
+        M[:, j] = acc / U[j, j]
+    return M
+
+
+def qr_backward(R, U, G) -> np.ndarray:
+    """dL/dZ from G = dL/dR through Z = R U (diag(U) > 0), no gradient flowing into U.
+
+    Derivation (not in the paper, which writes only dL/dZ in Alg. 1 line 10):
+    dZ = dR U + R dU  =>  R^T dZ U^{-1} = Omega + dU U^{-1}, Omega = R^T dR skew,
+    dU U^{-1} upper triangular  =>  Omega = Lo - Lo^T, Lo = strict_lower(R^T dZ U^{-1}).
+    Then <G, R Omega> = <strict_lower(B - B^T), R^T dZ U^{-1}> with B = R^T G, hence
+        dL/dZ = R @ strict_lower(B - B^T) @ U^{-T}.
+    """
+    R = _f64(R)
+    U = _f64(U)
+    G = _f64(G)
+    if np.any(np.diag(U) == 0.0):
+        raise ZeroDivisionError("U has a zero on its diagonal: Z is singular")
+    B = R.T @ G
+    P = np.tril(B - B.T, k=-1)
+    M = _solve_right_upper_transposed(P, U)
+    return R @ M
+
+
+def sgd_update(Z, dZ, lr: float) -> np.ndarray:
+    """Z <- Z - eta * dL/dZ  (Alg. 1 line 10; plain SGD, no momentum)."""
+    return _f64(Z) - float(lr) * _f64(dZ)
+
+
+def rotate_loss_grad(X, R, reduce: str = "mean"):
+    """(loss, G, Y, dY) for a given rotation R  (Alg. 1 lines 8-9 and dL/dR)."""
+    Y = rotate(X, R)
+    loss = whip_loss(Y, reduce)
+    dY = whip_grad(Y, reduce)
+    G = grad_wrt_rotation(X, dY)
+    return loss, G, Y, dY
+
+
+def calib_step(X, Z, lr: float, reduce: str = "mean"):
+    """One pass of the loop body of Alg. 1 (lines 7-10).
+
+    Returns a dict with the loss and rotation computed from the INPUT Z, the gradient
+    dZ, and the updated latent Z_new.
+    """
+    Z = _f64(Z)
+    R, U = qr_orth(Z)
+    loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
+    dZ = qr_backward(R, U, G)
+    Z_new = sgd_update(Z, dZ, lr)
+    return {"loss": loss, "R": R, "U": U, "G": G, "dZ": dZ, "Z_new": Z_new}
+
+
+def calibrate(X, Z0, steps: int, lr: float, reduce: str = "mean"):
+    """Run ``steps`` passes of the loop of Alg. 1 from Z0.
+
+    Returns (losses, Z_final, R_final) where losses[k] is the loss of the k-th input Z
+    and R_final = qr_orth(Z_final)[0] is the calibrated rotation.
+    """
+    Z = _f64(Z0)
+    losses = []
+    for _ in range(int(steps)):
+        out = calib_step(X, Z, lr, reduce)
+        losses.append(out["loss"])
+        Z = out["Z_new"]
+    R_final, _ = qr_orth(Z)
+    return np.array(losses), Z, R_final

@@ -1,0 +1,410 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the mathematics fix,
+never against itself.  Every test here runs on the CPU in fp64.
+
+Citations: Eq. 4 (Whip), Alg. 1 (calibration loop), Sec. 4.3 (Z = R U), Alg. 2
+(Householder QR), the norm-invariance equation in the appendix on the Whip mechanism.
+"""
+
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dartqr_oracle as orc
+
+
+def rng(seed):
+    return np.random.Generator(np.random.Philox(seed))
+
+
+# ----------------------------------------------------------------------------------
+# QR-Orth: Z -> (R, U)
+# ----------------------------------------------------------------------------------
+
+def mgs_reorth(Z):
+    """Independent route: modified Gram-Schmidt with one re-orthogonalisation pass.
+    For nonsingular Z the factorisation with diag(U) > 0 is unique."""
+    Z = np.asarray(Z, dtype=np.float64)
+    n = Z.shape[0]
+    Q = np.zeros((n, n))
+    U = np.zeros((n, n))
+    for j in range(n):
+        v = Z[:, j].copy()
+        for _pass in range(2):
+            for i in range(j):
+                h = Q[:, i] @ v
+                v -= h * Q[:, i]
+                U[i, j] += h
+        U[j, j] = math.sqrt(v @ v)
+        Q[:, j] = v / U[j, j]
+    return Q, U
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 37, 96])
+def test_qr_invariants(n):
+    Z = rng(100 + n).standard_normal((n, n))
+    R, U = orc.qr_orth(Z)
+    assert np.max(np.abs(R.T @ R - np.eye(n))) < 1e-12
+    assert np.max(np.abs(R @ R.T - np.eye(n))) < 1e-12
+    assert np.max(np.abs(R @ U - Z)) < 1e-12 * max(1.0, np.abs(Z).max()) * n
+    assert np.all(np.tril(U, -1) == 0.0)
+    assert np.all(np.diag(U) > 0.0)
+
+
+@pytest.mark.parametrize("n", [2, 5, 33, 64])
+def test_qr_matches_gram_schmidt_route(n):
+    Z = rng(200 + n).standard_normal((n, n))
+    R, U = orc.qr_orth(Z)
+    Q2, U2 = mgs_reorth(Z)
+    assert np.max(np.abs(R - Q2)) < 1e-10
+    assert np.max(np.abs(U - U2)) < 1e-10
+
+
+@pytest.mark.parametrize("n", [4, 50])
+def test_qr_matches_lapack_after_sign_fix(n):
+    Z = rng(300 + n).standard_normal((n, n))
+    R, U = orc.qr_orth(Z)
+    Ql, Ul = np.linalg.qr(Z)
+    s = np.sign(np.diag(Ul))
+    assert np.max(np.abs(R - Ql * s[None, :])) < 1e-11
+    assert np.max(np.abs(U - Ul * s[:, None])) < 1e-11
+
+
+def test_householder_unnormalised_factors():
+    Z = rng(7).standard_normal((20, 20))
+    Q, U0 = orc.householder_qr(Z)
+    assert np.max(np.abs(Q.T @ Q - np.eye(20))) < 1e-12
+    assert np.max(np.abs(Q @ U0 - Z)) < 1e-12
+    assert np.all(np.tril(U0, -1) == 0.0)
+
+
+def _random_orthogonal(n, seed):
+    # product of Givens rotations and a signed permutation: orthogonal by construction
+    g = rng(seed)
+    Q = np.eye(n)
+    for _ in range(4 * n):
+        i, j = g.choice(n, size=2, replace=False)
+        th = g.uniform(0, 2 * math.pi)
+        c, s = math.cos(th), math.sin(th)
+        Gm = np.eye(n)
+        Gm[i, i], Gm[j, j], Gm[i, j], Gm[j, i] = c, c, -s, s
+        Q = Q @ Gm
+    P = np.eye(n)[g.permutation(n)] * g.choice([-1.0, 1.0], size=n)[None, :]
+    return Q @ P
+
+
+def test_qr_closed_form_orthogonal_input():
+    Zo = _random_orthogonal(12, 1)
+    R, U = orc.qr_orth(Zo)
+    assert np.max(np.abs(R - Zo)) < 1e-13
+    assert np.max(np.abs(U - np.eye(12))) < 1e-13
+
+
+def test_qr_closed_form_hadamard_input():
+    # Sylvester Hadamard matrix / sqrt(n): the paper's initial latent is a Hadamard matrix
+    H = np.array([[1.0]])
+    for _ in range(4):
+        H = np.block([[H, H], [H, -H]])
+    H /= 4.0
+    R, U = orc.qr_orth(H)
+    assert np.max(np.abs(R - H)) < 1e-14
+    assert np.max(np.abs(U - np.eye(16))) < 1e-14
+
+
+def test_qr_closed_form_upper_triangular_input():
+    g = rng(2)
+    Zt = np.triu(g.standard_normal((9, 9)))
+    Zt[np.arange(9), np.arange(9)] = np.abs(np.diag(Zt)) + 0.5
+    R, U = orc.qr_orth(Zt)
+    assert np.max(np.abs(R - np.eye(9))) < 1e-13
+    assert np.max(np.abs(U - Zt)) < 1e-13
+
+
+def test_qr_closed_form_diagonal_input():
+    d = np.array([3.0, -2.0, 0.5, -7.0, 1.0])
+    R, U = orc.qr_orth(np.diag(d))
+    assert np.array_equal(R, np.diag(np.sign(d)))
+    assert np.max(np.abs(U - np.diag(np.abs(d)))) < 1e-15
+
+
+@pytest.mark.parametrize("z", [2.5, -0.3])
+def test_qr_closed_form_n1(z):
+    R, U = orc.qr_orth(np.array([[z]]))
+    assert R[0, 0] == math.copysign(1.0, z)
+    assert abs(U[0, 0] - abs(z)) < 1e-15
+
+
+@pytest.mark.parametrize("Z", [np.array([[1.0, 2.0], [3.0, 4.0]]),
+                               np.array([[-1.0, 0.5], [2.0, 3.0]]),
+                               np.array([[0.3, -2.0], [-0.4, -0.1]])])
+def test_qr_closed_form_n2(Z):
+    a, c = Z[0, 0], Z[1, 0]
+    r = math.hypot(a, c)
+    s = math.copysign(1.0, np.linalg.det(Z))
+    R_expected = np.array([[a / r, -s * c / r], [c / r, s * a / r]])
+    R, U = orc.qr_orth(Z)
+    assert np.max(np.abs(R - R_expected)) < 1e-14
+    assert np.max(np.abs(R_expected.T @ Z - U)) < 1e-14
+
+
+# ----------------------------------------------------------------------------------
+# rotate
+# ----------------------------------------------------------------------------------
+
+def test_rotate_preserves_norms_and_identity():
+    g = rng(11)
+    X = g.standard_t(3.0, size=(40, 16))
+    R, _ = orc.qr_orth(g.standard_normal((16, 16)))
+    Y = orc.rotate(X, R)
+    # norm invariance of a rotation (appendix, norm equation)
+    assert np.max(np.abs(np.sum(Y * Y, axis=1) - np.sum(X * X, axis=1))) < 1e-10 * np.sum(X * X, axis=1).max()
+    assert abs(np.linalg.norm(Y) - np.linalg.norm(X)) < 1e-11 * np.linalg.norm(X)
+    assert np.array_equal(orc.rotate(X, np.eye(16)), X)
+
+
+def test_rotate_is_row_vector_convention():
+    # Y[t, i] = sum_c X[t, c] R[c, i]  (O = X @ R, Alg. 1 line 8), written as loops
+    g = rng(12)
+    X = g.standard_normal((3, 4))
+    R = g.standard_normal((4, 4))
+    Y = orc.rotate(X, R)
+    for t in range(3):
+        for i in range(4):
+            acc = 0.0
+            for c in range(4):
+                acc += X[t, c] * R[c, i]
+            assert abs(Y[t, i] - acc) < 1e-14
+
+
+# ----------------------------------------------------------------------------------
+# Whip loss (Eq. 4) and its gradient
+# ----------------------------------------------------------------------------------
+
+def brute_whip(Y, mean):
+    total = 0.0
+    for t in range(Y.shape[0]):
+        per_token = 0.0
+        for i in range(Y.shape[1]):
+            per_token += math.exp(-abs(float(Y[t, i])))
+        total += per_token
+    return total / Y.shape[0] if mean else total
+
+
+def test_whip_brute_force():
+    Y = rng(21).standard_t(3.0, size=(13, 7)) * 2.0
+    assert abs(orc.whip_loss(Y, "mean") - brute_whip(Y, True)) < 1e-13
+    assert abs(orc.whip_loss(Y, "sum") - brute_whip(Y, False)) < 1e-12
+
+
+def test_whip_closed_forms():
+    n, T = 6, 5
+    assert orc.whip_loss(np.zeros((T, n)), "mean") == pytest.approx(n, abs=1e-15)
+    assert orc.whip_loss(np.zeros((T, n)), "sum") == pytest.approx(n * T, abs=1e-15)
+    a = -1.7
+    Y = np.zeros((1, n))
+    Y[0, 0] = a
+    assert orc.whip_loss(Y, "mean") == pytest.approx(math.exp(-abs(a)) + n - 1, abs=1e-15)
+    # a single vector: Eq. 4 itself
+    x = np.array([[0.5, -2.0, 3.0]])
+    assert orc.whip_loss(x, "sum") == pytest.approx(math.exp(-0.5) + math.exp(-2.0) + math.exp(-3.0), abs=1e-15)
+
+
+def test_whip_invariant_under_signed_permutation_of_rotation_columns():
+    g = rng(22)
+    X = g.standard_normal((30, 8))
+    R, _ = orc.qr_orth(g.standard_normal((8, 8)))
+    perm = g.permutation(8)
+    signs = g.choice([-1.0, 1.0], size=8)
+    R2 = R[:, perm] * signs[None, :]
+    assert abs(orc.whip_loss(orc.rotate(X, R)) - orc.whip_loss(orc.rotate(X, R2))) < 1e-13
+
+
+def test_whip_grad_formula_and_finite_differences():
+    Y = rng(23).standard_normal((5, 4)) * 1.5
+    Y[2, 1] = 0.0
+    for mode, c in (("mean", 1.0 / 5), ("sum", 1.0)):
+        dY = orc.whip_grad(Y, mode)
+        assert dY[2, 1] == 0.0                       # reading: sgn(0) = 0
+        h = 1e-6
+        for t in range(5):
+            for i in range(4):
+                if Y[t, i] == 0.0:
+                    continue
+                # closed form: -c * sgn(y) * exp(-|y|): pushes small |y| away from zero
+                assert dY[t, i] == pytest.approx(-c * math.copysign(1.0, Y[t, i]) * math.exp(-abs(Y[t, i])), abs=1e-15)
+                Yp, Ym = Y.copy(), Y.copy()
+                Yp[t, i] += h
+                Ym[t, i] -= h
+                fd = (orc.whip_loss(Yp, mode) - orc.whip_loss(Ym, mode)) / (2 * h)
+                assert abs(fd - dY[t, i]) < 1e-8
+
+
+def test_grad_wrt_rotation_finite_differences():
+    g = rng(24)
+    T, n = 12, 5
+    X = g.standard_t(3.0, size=(T, n))
+    R = g.standard_normal((n, n))          # entries treated as free variables
+    loss, G, Y, dY = orc.rotate_loss_grad(X, R)
+    assert loss == pytest.approx(brute_whip(X @ R, True), abs=1e-13)
+    h = 1e-6
+    for i in range(n):
+        for j in range(n):
+            Rp, Rm = R.copy(), R.copy()
+            Rp[i, j] += h
+            Rm[i, j] -= h
+            fd = (orc.whip_loss(X @ Rp) - orc.whip_loss(X @ Rm)) / (2 * h)
+            assert abs(fd - G[i, j]) < 2e-8 * max(1.0, abs(G[i, j]))
+
+
+# ----------------------------------------------------------------------------------
+# QR backward: dL/dZ
+# ----------------------------------------------------------------------------------
+
+def loss_of_Z(X, Z, mode="mean"):
+    R, _ = orc.qr_orth(Z)
+    return orc.whip_loss(orc.rotate(X, R), mode)
+
+
+@pytest.mark.parametrize("n,T,seed", [(2, 9, 31), (4, 16, 32), (7, 20, 33)])
+def test_dZ_finite_differences_of_whole_map(n, T, seed):
+    g = rng(seed)
+    X = g.standard_t(3.0, size=(T, n))
+    Z = g.standard_normal((n, n))
+    out = orc.calib_step(X, Z, lr=0.0)
+    dZ = out["dZ"]
+    h = 1e-6
+    fd = np.zeros((n, n))
+    for i in range(n):
+        for j in range(n):
+            Zp, Zm = Z.copy(), Z.copy()
+            Zp[i, j] += h
+            Zm[i, j] -= h
+            fd[i, j] = (loss_of_Z(X, Zp) - loss_of_Z(X, Zm)) / (2 * h)
+    assert np.max(np.abs(fd - dZ)) < 5e-8 * max(1.0, np.abs(dZ).max())
+
+
+def test_dZ_structural_identities():
+    g = rng(34)
+    n, T = 24, 60
+    X = g.standard_t(3.0, size=(T, n))
+    Z = g.standard_normal((n, n))
+    out = orc.calib_step(X, Z, lr=0.0)
+    dZ = out["dZ"]
+    scale = np.linalg.norm(Z) * np.linalg.norm(dZ)
+    # Z -> Z (I + eps*Tu), Tu upper triangular, leaves R unchanged: triu(Z^T dZ) = 0
+    assert np.max(np.abs(np.triu(Z.T @ dZ))) < 1e-12 * scale
+    # scale invariance L(cZ) = L(Z): <Z, dZ> = 0
+    assert abs(np.sum(Z * dZ)) < 1e-12 * scale
+    # the last column of Z only fixes U[:, n-1]: its gradient vanishes
+    assert np.max(np.abs(dZ[:, -1])) < 1e-13 * np.abs(dZ).max()
+    # column j of dZ is orthogonal to columns 0..j of Z
+    for j in range(n):
+        assert np.max(np.abs(Z[:, : j + 1].T @ dZ[:, j])) < 1e-11 * scale
+
+
+def test_dZ_n1_is_zero():
+    X = rng(35).standard_normal((5, 1))
+    out = orc.calib_step(X, np.array([[-0.7]]), lr=0.0)
+    assert out["dZ"][0, 0] == 0.0
+
+
+@pytest.mark.parametrize("Z", [np.array([[1.0, 2.0], [3.0, 4.0]]), np.array([[-1.5, 0.5], [0.7, 3.0]])])
+def test_dZ_closed_form_n2_angle_parametrisation(Z):
+    # R = [[cos, -s sin], [sin, s cos]], theta = atan2(c, a), s = sign(det Z).
+    X = rng(36).standard_t(3.0, size=(11, 2))
+    T = X.shape[0]
+    a, c = Z[0, 0], Z[1, 0]
+    r2 = a * a + c * c
+    th = math.atan2(c, a)
+    s = math.copysign(1.0, np.linalg.det(Z))
+    dL_dth = 0.0
+    for t in range(T):
+        y1 = X[t, 0] * math.cos(th) + X[t, 1] * math.sin(th)
+        y2 = s * (-X[t, 0] * math.sin(th) + X[t, 1] * math.cos(th))
+        dy1 = -X[t, 0] * math.sin(th) + X[t, 1] * math.cos(th)
+        dy2 = s * (-X[t, 0] * math.cos(th) - X[t, 1] * math.sin(th))
+        dL_dth += -math.copysign(1.0, y1) * math.exp(-abs(y1)) * dy1
+        dL_dth += -math.copysign(1.0, y2) * math.exp(-abs(y2)) * dy2
+    dL_dth /= T
+    expected = np.array([[-c / r2 * dL_dth, 0.0], [a / r2 * dL_dth, 0.0]])
+    dZ = orc.calib_step(X, Z, lr=0.0)["dZ"]
+    assert np.max(np.abs(dZ - expected)) < 1e-13
+
+
+def test_dZ_matches_library_autograd_route():
+    torch = pytest.importorskip("torch")
+    g = rng(37)
+    n, T = 10, 40
+    X = g.standard_t(3.0, size=(T, n))
+    Z = g.standard_normal((n, n))
+    Zt = torch.tensor(Z, dtype=torch.float64, requires_grad=True)
+    Q, Rt = torch.linalg.qr(Zt)
+    Y = torch.tensor(X, dtype=torch.float64) @ Q
+    L = torch.exp(-Y.abs()).sum() / T
+    L.backward()
+    out = orc.calib_step(X, Z, lr=0.0)
+    assert abs(out["loss"] - L.item()) < 1e-13
+    assert np.max(np.abs(out["dZ"] - Zt.grad.numpy())) < 1e-12
+
+
+def test_qr_backward_rejects_singular():
+    Z = np.array([[1.0, 2.0], [2.0, 4.0]])
+    R, U = orc.qr_orth(Z)
+    U[1, 1] = 0.0
+    with pytest.raises(ZeroDivisionError):
+        orc.qr_backward(R, U, np.ones((2, 2)))
+
+
+def test_triangular_solve_helper_against_library():
+    g = rng(38)
+    U = np.triu(g.standard_normal((9, 9))) + 3 * np.eye(9)
+    W = g.standard_normal((6, 9))
+    M = orc._solve_right_upper_transposed(W, U)
+    assert np.max(np.abs(M @ U.T - W)) < 1e-12
+    assert np.max(np.abs(M - np.linalg.solve(U, W.T).T)) < 1e-12
+
+
+# ----------------------------------------------------------------------------------
+# SGD step and the loop
+# ----------------------------------------------------------------------------------
+
+def test_sgd_step_norm_identity_and_update():
+    g = rng(41)
+    n, T = 16, 64
+    X = g.standard_t(3.0, size=(T, n))
+    Z = g.standard_normal((n, n))
+    lr = 0.05
+    out = orc.calib_step(X, Z, lr)
+    assert np.array_equal(out["Z_new"], Z - lr * out["dZ"])
+    lhs = np.linalg.norm(out["Z_new"]) ** 2
+    rhs = np.linalg.norm(Z) ** 2 + lr ** 2 * np.linalg.norm(out["dZ"]) ** 2
+    assert abs(lhs - rhs) < 1e-11 * rhs
+
+
+def test_calibration_loop_decreases_loss_and_reports_input_loss():
+    g = rng(42)
+    n, T = 16, 256
+    X = g.standard_normal((T, n))
+    X[:, [3, 9]] *= 30.0
+    Z0 = g.standard_normal((n, n))
+    losses, Zf, Rf = orc.calibrate(X, Z0, steps=8, lr=0.001)
+    assert len(losses) == 8
+    assert losses[0] == pytest.approx(loss_of_Z(X, Z0), abs=1e-14)
+    assert np.all(np.diff(losses) < 0.0)          # small step: monotone decrease
+    assert np.max(np.abs(Rf.T @ Rf - np.eye(n))) < 1e-12
+    assert np.max(np.abs(Rf - orc.qr_orth(Zf)[0])) == 0.0
+
+
+def test_loss_independent_of_qr_sign_convention():
+    g = rng(43)
+    n, T = 9, 30
+    X = g.standard_t(3.0, size=(T, n))
+    Z = g.standard_normal((n, n))
+    Q, U0 = orc.householder_qr(Z)            # raw signs
+    R, U = orc.qr_orth(Z)                    # normalised signs
+    l_raw, G_raw, _, _ = orc.rotate_loss_grad(X, Q)
+    l_nrm, G_nrm, _, _ = orc.rotate_loss_grad(X, R)
+    assert abs(l_raw - l_nrm) < 1e-13
+    dZ_raw = orc.qr_backward(Q, U0, G_raw)
+    dZ_nrm = orc.qr_backward(R, U, G_nrm)
+    assert np.max(np.abs(dZ_raw - dZ_nrm)) < 1e-12
