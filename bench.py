@@ -1,0 +1,176 @@
+"""Benchmark of the QR-Orth calibration step (Alg. 1 lines 7-10 of DartQuant) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|70b|tiny|heads]
+
+A "step" is one dq_calib_step: QR of the latent Z, Y = X R, fused Whip loss/gradient, G = X^T dY,
+the derivative through the QR and the SGD update, on one synthetic activation block that is already
+resident in HBM.  Prints ONE JSON line (metric: steps per second) with a `roofline` object for the
+kernel class that takes most of the step and a `cpu_baseline` object (the fp64 oracle timed on the
+host on a bounded sample).
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_valu_tflops": 157.3}
+
+
+def flops_per_step(n: int, T: int, b: int = 1) -> float:
+    """Dense flop model of one step: two T x n x n products plus (4/3 + 4/3 + 4) n^3 for QR, forming R and
+    the derivative through the QR."""
+    return b * (4.0 * T * n * n + (20.0 / 3.0) * n ** 3)
+
+
+def cpu_baseline(cfg_name: str, n: int, T: int):
+    """Time the oracle as it stands on a bounded sample (a smaller problem with the same value recipe and
+    T/n ratio) and scale to the benchmark's step with the flop model."""
+    import numpy as np
+    from oracle import dartqr_oracle as orc
+    from paper_2511_04063_amd import synth
+
+    ns = min(n, 1536)
+    Ts = max(1, int(round(T * ns / n)))
+    base = cfg_name if cfg_name in ("7b", "13b", "70b") else "7b"
+    inp = synth.make_inputs(synth.scaled_config(base, n=ns, T=Ts, b=1), seed=11)
+    t0 = time.perf_counter()
+    orc.calib_step(inp["X"][0], inp["Z0"][0], 1e-2)
+    dt = time.perf_counter() - t0
+    scale = flops_per_step(ns, Ts) / flops_per_step(n, T)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {
+        "value": (1.0 / dt) * scale, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"one fp64 NumPy oracle step at n={ns}, T={Ts} ({dt:.2f} s), scaled to n={n}, T={T} "
+                   f"with the flop model 4Tn^2 + 20/3 n^3 (extrapolated)"),
+        "sample_seconds": dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="7b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2511_04063_amd import binding as B
+    from paper_2511_04063_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    inp = synth.make_inputs(cfg)
+    bf16 = cfg.x_dtype == "bf16"
+    xdt = B.DQ_BF16 if bf16 else B.DQ_F32
+    X = torch.from_numpy(inp["X"])
+    if bf16:
+        X = X.to(torch.bfloat16)
+    Xd = X.cuda()
+    Z0 = torch.from_numpy(inp["Z0"]).cuda()
+    if cfg.b == 1:
+        Xd, Z0 = Xd[0], Z0[0]
+    del X, inp
+    Zd = Z0.clone()
+    loss = torch.zeros(cfg.b, device="cuda")
+
+    ctx = B.Context()
+    ctx.ensure_workspace(cfg.b, cfg.n, cfg.T, xdt)
+    red = B.DQ_REDUCE_TOKEN_MEAN
+
+    def step():
+        ctx.dq_calib_step(Xd, xdt, Zd, cfg.lr, red, loss)
+
+    # warm-up, with every kernel class bracketed once to find where the step's time goes
+    for _ in range(max(0, args.warmup - 1)):
+        step()
+    torch.cuda.synchronize()
+    ctx.dq_profile_enable((1 << B.DQ_K_COUNT) - 1)
+    step()
+    names = {B.DQ_K_GEMM_F32: "gemm_f32", B.DQ_K_GEMM_BF16: "gemm_bf16", B.DQ_K_WHIP: "whip",
+             B.DQ_K_PANEL: "qr_panel", B.DQ_K_SMALL: "small"}
+    breakdown = {names[k]: ctx.dq_profile_read(k) for k in names}
+    dominant = max(names, key=lambda k: breakdown[names[k]]["ms"])
+    first_loss = float(loss[0].item())
+
+    # timed region: exactly K steps, only the dominant class bracketed with events
+    Zd.copy_(Z0)
+    ctx.dq_profile_enable(1 << dominant)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    dom = ctx.dq_profile_read(dominant)
+    ctx.dq_profile_enable(0)
+    last_loss = float(loss[0].item())
+    flags = ctx.dq_device_flags()
+
+    ms_per_step = dt * 1e3 / args.steps
+    F = flops_per_step(cfg.n, cfg.T, cfg.b)
+    launches = max(1, dom["launches"])
+    avg_ms = dom["ms"] / launches
+    if dominant in (B.DQ_K_GEMM_F32, B.DQ_K_GEMM_BF16):
+        peak = PEAK["fp32_mfma_tflops"] if dominant == B.DQ_K_GEMM_F32 else PEAK["bf16_mfma_tflops"]
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+        roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s"}
+    elif dominant == B.DQ_K_WHIP:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["ms"] > 0 else 0.0
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK["hbm_gbs"], "unit": "GB/s"}
+    else:
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+        roof = {"bound": "alu", "achieved": achieved, "peak": PEAK["fp32_valu_tflops"], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = names[dominant]
+    roof["launches_per_step"] = dom["launches"] / args.steps
+    roof["avg_launch_ms"] = avg_ms
+    roof["class_ms_per_step"] = dom["ms"] / args.steps
+
+    out = {
+        "metric": "QR-Orth calibration steps/sec",
+        "value": args.steps / dt,
+        "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, SGD lr={cfg.lr}",
+                   "n": cfg.n, "T": cfg.T, "b": cfg.b},
+        "model_tflops": F / (ms_per_step * 1e-3) / 1e12,
+        "flops_per_step": F,
+        "loss_first": first_loss, "loss_last": last_loss, "device_flags": flags,
+        "roofline": roof,
+        "stage_ms_one_step": {k: round(v["ms"], 4) for k, v in breakdown.items()},
+        "stage_launches_one_step": {k: v["launches"] for k, v in breakdown.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg.name, cfg.n, cfg.T)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

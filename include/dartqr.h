@@ -1,0 +1,172 @@
+/*
+ * dartqr.h -- C ABI of the MI355X (gfx950) QR-Orth calibration-step library.
+ *
+ * One QR-Orth step is the loop body of Alg. 1 (Sec. 4.3) of DartQuant (arXiv 2511.04063):
+ *     R <- qr(Z);   O <- X @ R;   L <- Whip(O);   Z <- Z - eta * dL/dZ
+ * with Whip(x) = sum_i exp(-|x_i|) (Eq. 4, Sec. 4.2).  The paper names the ORTHOGONAL
+ * factor R and the UPPER-TRIANGULAR factor U (Z = R U, Sec. 4.3); so does this header.
+ *
+ * Conventions shared by every entry point
+ *  - All matrix pointers are DEVICE pointers (HIP device memory of the context's device),
+ *    row-major, leading dimensions ("ld*") counted in ELEMENTS.  Scalars are host values.
+ *  - fp32 matrices: base pointer 16-byte aligned, ld a multiple of 4 and >= the row length.
+ *    bf16 matrices: base pointer 16-byte aligned, ld a multiple of 8 and >= the row length.
+ *    Violations return DQ_ERR_ALIGN / DQ_ERR_SHAPE; there is no silent slow path.
+ *  - Sizes: 1 <= n <= DQ_MAX_N, T >= 1, b >= 0 (b == 0 is a no-op returning DQ_OK).  n and T
+ *    need not be multiples of anything.
+ *  - Batches: problem i of a batch of b lives at  base + i * rows * ld  (its rows follow
+ *    the previous problem's rows); per-problem scalars (loss) at index i.
+ *  - Ownership: the library never allocates or frees device memory.  The caller owns every
+ *    buffer, including the workspace, and keeps it alive until the stream has passed the
+ *    call.  Inputs are read-only unless stated; outputs must not alias inputs.
+ *  - Asynchrony: compute calls only enqueue work on the context's stream and return; results
+ *    (including device scalars) are valid in stream order.  Only dq_device_flags and
+ *    dq_profile_read synchronise.
+ *  - Errors: arguments are checked on the host before anything is enqueued; a non-DQ_OK
+ *    return means nothing was launched and no output was touched.  Numerical trouble
+ *    (singular Z, non-finite values) sets bits in a device status word (dq_device_flags);
+ *    outputs are then unspecified but every kernel still terminates normally.
+ *  - One context per stream; a context is not re-entrant.  Calls on one context are
+ *    serialised by its stream and share its workspace.
+ */
+#ifndef DARTQR_H
+#define DARTQR_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DQ_MAX_N 8192          /* largest rotation size the panel factorisation supports */
+
+typedef struct dq_ctx dq_ctx;  /* opaque; bound to one device and one HIP stream */
+
+typedef enum {
+    DQ_OK = 0,
+    DQ_ERR_NULL = 1,           /* a required pointer is null                                  */
+    DQ_ERR_SHAPE = 2,          /* a size is out of range or a leading dimension too small     */
+    DQ_ERR_DTYPE = 3,          /* unknown dq_dtype / dq_reduce value                          */
+    DQ_ERR_ALIGN = 4,          /* pointer or leading-dimension alignment rule violated         */
+    DQ_ERR_WORKSPACE = 5,      /* no workspace set, or it is smaller than dq_workspace_bytes  */
+    DQ_ERR_HIP = 6,            /* a HIP runtime call failed (launch, event)                   */
+    DQ_ERR_UNSUPPORTED = 7     /* valid request outside the implemented range (n > DQ_MAX_N)  */
+} dq_status;
+
+typedef enum { DQ_F32 = 0, DQ_BF16 = 1 } dq_dtype;
+
+/* How Whip (Eq. 4, defined for one activation vector) is reduced over the T token rows of a
+ * block (Alg. 1 line 9 leaves this open): mean over tokens of the per-token sum, or the sum. */
+typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
+
+/* bits of the device status word */
+#define DQ_FLAG_SINGULAR   1u   /* a zero appeared on diag(U): Z is singular (dZ undefined)  */
+#define DQ_FLAG_NONFINITE  2u   /* a NaN or Inf was seen in a pivot or in the loss           */
+
+/* ---- context and workspace ---------------------------------------------------------- */
+
+/* Create a context on the current HIP device for `hip_stream` (a hipStream_t, may be null for
+ * the default stream).  *out receives the context.  Allocates host memory and HIP events only. */
+dq_status dq_create(dq_ctx** out, void* hip_stream);
+dq_status dq_destroy(dq_ctx* ctx);
+
+/* Bytes of device workspace that any call with these sizes needs (a host computation).
+ * x_dtype is the storage type of X.  *out receives the size; it grows with b only through
+ * max-over-problems, since problems of a batch run one after another. */
+dq_status dq_workspace_bytes(int b, int n, int T, dq_dtype x_dtype, size_t* out);
+
+/* Hand the context a caller-owned device buffer (256-byte aligned).  Enqueues one small kernel
+ * that clears the status word at its start.  May be called again with another buffer. */
+dq_status dq_set_workspace(dq_ctx* ctx, void* dptr, size_t bytes);
+
+const char* dq_status_string(dq_status s);
+
+/* Waits for the stream, copies the device status word to *host_out and clears it on the device. */
+dq_status dq_device_flags(dq_ctx* ctx, unsigned* host_out);
+
+/* ---- the hot path ------------------------------------------------------------------- */
+
+/* Sec. 4.3 / Alg. 1 line 7:  Z (n x n) -> orthogonal R and, optionally, upper-triangular U with
+ * Z = R U.  Computed by blocked Householder QR (Alg. 2 in blocked compact-WY form) followed by
+ * sign normalisation so that diag(U) >= 0, which makes R unique for nonsingular Z.
+ * Z: in, b x (n x n) fp32.  R: out, fp32.  U_or_null: out, fp32, strictly-lower part written as 0. */
+dq_status dq_qr_orth(dq_ctx* ctx, int b, int n,
+                     const float* Z, long ldz, float* R, long ldr,
+                     float* U_or_null, long ldu);
+
+/* Alg. 1 lines 8-9 and the chain rule to R:
+ *   Y = X @ R;   loss = c * sum_t sum_i exp(-|Y_ti|)  (Eq. 4; c = 1/T or 1 per `red`);
+ *   dY = -c * sgn(Y) * exp(-|Y|) with sgn(0) = 0;   G = X^T @ dY = dL/dR.
+ * X: in, b x (T x n), dtype xdt (bf16 X is multiplied on the bf16 matrix cores against R rounded
+ * to bf16, fp32 accumulate; fp32 X uses fp32 matrix cores).  R: in, fp32 (need not be orthogonal).
+ * loss_dev: out, b device floats.  G: out, fp32 n x n.  Y_or_null: out, fp32 T x n, ldy.
+ * dY_or_null: out, T x n in the dtype of X (bf16 or fp32), lddy. */
+dq_status dq_rotate_loss_grad(dq_ctx* ctx, int b, int T, int n,
+                              const void* X, dq_dtype xdt, long ldx,
+                              const float* R, long ldr, dq_reduce red,
+                              float* loss_dev, float* G, long ldg,
+                              float* Y_or_null, long ldy, void* dY_or_null, long lddy);
+
+/* The whole loop body of Alg. 1 (lines 7-10) with plain SGD:  Z is updated IN PLACE to
+ * Z - lr * dL/dZ.  loss_dev (b device floats) and R_or_null receive the loss and the rotation of
+ * the INPUT Z (before the update). */
+dq_status dq_calib_step(dq_ctx* ctx, int b, int T, int n,
+                        const void* X, dq_dtype xdt, long ldx,
+                        float* Z, long ldz, float lr, dq_reduce red,
+                        float* loss_dev, float* R_or_null, long ldr);
+
+/* ---- stages exported on their own (stage-level parity tests, reuse) -------------------- */
+
+/* Eq. 4 and its derivative on an existing Y (fp32, T x n): loss_dev[i] and dY (dtype dydt). */
+dq_status dq_whip_loss_grad(dq_ctx* ctx, int b, int T, int n,
+                            const float* Y, long ldy, dq_reduce red,
+                            float* loss_dev, void* dY, dq_dtype dydt, long lddy);
+
+/* Alg. 1 line 10, the derivative through Z = R U:  with B = R^T G and P = strict_lower(B - B^T),
+ * dZ = R P U^{-T}.  R, U, G: in (U upper triangular, its strictly-lower part is not read).
+ * dZ: out.  A zero on diag(U) sets DQ_FLAG_SINGULAR. */
+dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
+                         const float* R, long ldr, const float* U, long ldu,
+                         const float* G, long ldg, float* dZ, long lddz);
+
+/* Alg. 1 line 10, the update alone:  Z <- Z - lr * dZ  (in place on Z). */
+dq_status dq_sgd_update(dq_ctx* ctx, int b, int n, float* Z, long ldz,
+                        const float* dZ, long lddz, float lr);
+
+/* The matrix-core GEMMs the path is built from, exported for kernel-level parity tests:
+ *   C (M x N, fp32) = alpha * op(A) op(B) + beta * C.
+ * f32: A, B fp32; ta != 0 means A is stored K x M, tb != 0 means B is stored N x K.
+ * bf16: A, B bf16, fp32 accumulate; ta/tb as above. */
+dq_status dq_gemm_f32(dq_ctx* ctx, int M, int N, int K, float alpha,
+                      const float* A, long lda, int ta, const float* B, long ldb, int tb,
+                      float beta, float* C, long ldc);
+dq_status dq_gemm_bf16(dq_ctx* ctx, int M, int N, int K,
+                       const void* A, long lda, int ta, const void* B, long ldb, int tb,
+                       float* C, long ldc);
+
+/* ---- measurement -------------------------------------------------------------------- */
+
+/* Kernel classes whose launches can be bracketed with HIP events on the context's stream. */
+typedef enum {
+    DQ_K_GEMM_F32 = 0,     /* fp32 matrix-core GEMM (QR trailing updates, forming R, backward) */
+    DQ_K_GEMM_BF16 = 1,    /* bf16 matrix-core GEMM (X @ R, X^T @ dY)                          */
+    DQ_K_WHIP = 2,         /* fused Whip loss + gradient pass                                  */
+    DQ_K_PANEL = 3,        /* Householder panel factorisation                                  */
+    DQ_K_SMALL = 4,        /* everything else (T factors, reductions, sign fix, conversions)   */
+    DQ_K_COUNT = 5
+} dq_kernel_class;
+
+/* mask: bit k enables event bracketing of class k launches (0 switches profiling off).  Resets
+ * the accumulated records. */
+dq_status dq_profile_enable(dq_ctx* ctx, unsigned mask);
+
+/* Waits for the stream and returns, for one class, the summed duration (ms) of the bracketed
+ * launches since dq_profile_enable, their count, and the algorithmic flops and bytes the library
+ * attributed to them.  Any out pointer may be null. */
+dq_status dq_profile_read(dq_ctx* ctx, dq_kernel_class k, double* ms, long* launches,
+                          double* flops, double* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DARTQR_H */

@@ -1,0 +1,205 @@
+"""ctypes binding of libdartqr.so: argument marshalling only.
+
+Every method of :class:`Context` has the name of the C entry point it calls (see
+``include/dartqr.h``) and passes raw device pointers of torch tensors plus the current HIP
+stream.  Nothing is computed here; if the HIP library is missing this module raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG_DIR, "libdartqr.so")
+
+DQ_OK = 0
+DQ_ERR_NULL, DQ_ERR_SHAPE, DQ_ERR_DTYPE, DQ_ERR_ALIGN, DQ_ERR_WORKSPACE, DQ_ERR_HIP, DQ_ERR_UNSUPPORTED = range(1, 8)
+DQ_F32, DQ_BF16 = 0, 1
+DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
+DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE = 1, 2
+DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
+DQ_MAX_N = 8192
+
+_c = ctypes
+_vp, _i, _l, _f, _sz = _c.c_void_p, _c.c_int, _c.c_long, _c.c_float, _c.c_size_t
+
+# name -> (restype, argtypes); mirrors include/dartqr.h
+SIGNATURES = {
+    "dq_create": (_i, [_c.POINTER(_vp), _vp]),
+    "dq_destroy": (_i, [_vp]),
+    "dq_workspace_bytes": (_i, [_i, _i, _i, _i, _c.POINTER(_sz)]),
+    "dq_set_workspace": (_i, [_vp, _vp, _sz]),
+    "dq_status_string": (_c.c_char_p, [_i]),
+    "dq_device_flags": (_i, [_vp, _c.POINTER(_c.c_uint)]),
+    "dq_qr_orth": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l]),
+    "dq_rotate_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _i, _vp, _vp, _l, _vp, _l, _vp, _l]),
+    "dq_calib_step": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _f, _i, _vp, _vp, _l]),
+    "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
+    "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
+    "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
+    "dq_gemm_f32": (_i, [_vp, _i, _i, _i, _f, _vp, _l, _i, _vp, _l, _i, _f, _vp, _l]),
+    "dq_gemm_bf16": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _l, _i, _vp, _l]),
+    "dq_profile_enable": (_i, [_vp, _c.c_uint]),
+    "dq_profile_read": (_i, [_vp, _i, _c.POINTER(_c.c_double), _c.POINTER(_l), _c.POINTER(_c.c_double),
+                             _c.POINTER(_c.c_double)]),
+}
+
+_lib = None
+
+
+class DartQRError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = status_string(status) if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+def load_library(path: str | None = None):
+    """Load libdartqr.so and set the prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise RuntimeError(
+            f"{p} is missing: build it first with `python -m paper_2511_04063_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(p)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)          # AttributeError if the symbol is not exported
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().dq_status_string(int(status)).decode()
+
+
+def workspace_bytes(b: int, n: int, T: int, x_dtype: int) -> int:
+    out = _sz(0)
+    st = load_library().dq_workspace_bytes(b, n, T, x_dtype, ctypes.byref(out))
+    if st != DQ_OK:
+        raise DartQRError(st, "dq_workspace_bytes")
+    return int(out.value)
+
+
+def _ptr(t):
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _ld(t):
+    """Leading dimension (elements) of the last two dims of a row-major tensor."""
+    if t is None:
+        return 0
+    assert t.stride(-1) == 1, "matrices must be row-major with unit column stride"
+    return int(t.stride(-2))
+
+
+class Context:
+    """One dq_ctx bound to the current torch HIP stream (or the one given)."""
+
+    def __init__(self, stream=None):
+        import torch
+        self._torch = torch
+        self.lib = load_library()
+        if stream is None:
+            stream = torch.cuda.current_stream()
+        self.stream = stream
+        h = _vp(0)
+        st = self.lib.dq_create(ctypes.byref(h), _vp(stream.cuda_stream))
+        if st != DQ_OK:
+            raise DartQRError(st, "dq_create")
+        self.h = h
+        self._ws = None
+
+    def close(self):
+        if getattr(self, "h", None) is not None:
+            self.lib.dq_destroy(self.h)
+            self.h = None
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- workspace (device memory comes from torch)
+    def dq_set_workspace(self, tensor):
+        st = self.lib.dq_set_workspace(self.h, _vp(_ptr(tensor)), tensor.numel() * tensor.element_size())
+        if st != DQ_OK:
+            raise DartQRError(st, "dq_set_workspace")
+        self._ws = tensor
+
+    def ensure_workspace(self, b, n, T, x_dtype):
+        need = workspace_bytes(b, n, T, x_dtype)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            ws = self._torch.empty(need, dtype=self._torch.uint8, device="cuda")
+            self.dq_set_workspace(ws)
+        return need
+
+    def _check(self, st, where):
+        if st != DQ_OK:
+            raise DartQRError(st, where)
+
+    def dq_device_flags(self) -> int:
+        out = ctypes.c_uint(0)
+        self._check(self.lib.dq_device_flags(self.h, ctypes.byref(out)), "dq_device_flags")
+        return int(out.value)
+
+    # ---- hot path
+    def dq_qr_orth(self, Z, R, U=None):
+        b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
+        self._check(self.lib.dq_qr_orth(self.h, b, n, _ptr(Z), _ld(Z), _ptr(R), _ld(R), _ptr(U), _ld(U)),
+                    "dq_qr_orth")
+
+    def dq_rotate_loss_grad(self, X, x_dtype, R, reduce, loss, G, Y=None, dY=None):
+        b = X.shape[0] if X.dim() == 3 else 1
+        T, n = X.shape[-2], X.shape[-1]
+        self._check(self.lib.dq_rotate_loss_grad(self.h, b, T, n, _ptr(X), x_dtype, _ld(X), _ptr(R), _ld(R), reduce,
+                                                 _ptr(loss), _ptr(G), _ld(G), _ptr(Y), _ld(Y), _ptr(dY), _ld(dY)),
+                    "dq_rotate_loss_grad")
+
+    def dq_calib_step(self, X, x_dtype, Z, lr, reduce, loss, R=None):
+        b = X.shape[0] if X.dim() == 3 else 1
+        T, n = X.shape[-2], X.shape[-1]
+        self._check(self.lib.dq_calib_step(self.h, b, T, n, _ptr(X), x_dtype, _ld(X), _ptr(Z), _ld(Z), float(lr),
+                                           reduce, _ptr(loss), _ptr(R), _ld(R)), "dq_calib_step")
+
+    # ---- stages
+    def dq_whip_loss_grad(self, Y, reduce, loss, dY, dy_dtype):
+        b = Y.shape[0] if Y.dim() == 3 else 1
+        T, n = Y.shape[-2], Y.shape[-1]
+        self._check(self.lib.dq_whip_loss_grad(self.h, b, T, n, _ptr(Y), _ld(Y), reduce, _ptr(loss), _ptr(dY),
+                                               dy_dtype, _ld(dY)), "dq_whip_loss_grad")
+
+    def dq_qr_backward(self, R, U, G, dZ):
+        b, n = (R.shape[0], R.shape[-1]) if R.dim() == 3 else (1, R.shape[-1])
+        self._check(self.lib.dq_qr_backward(self.h, b, n, _ptr(R), _ld(R), _ptr(U), _ld(U), _ptr(G), _ld(G),
+                                            _ptr(dZ), _ld(dZ)), "dq_qr_backward")
+
+    def dq_sgd_update(self, Z, dZ, lr):
+        b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
+        self._check(self.lib.dq_sgd_update(self.h, b, n, _ptr(Z), _ld(Z), _ptr(dZ), _ld(dZ), float(lr)),
+                    "dq_sgd_update")
+
+    def dq_gemm_f32(self, M, N, K, alpha, A, ta, B, tb, beta, C):
+        self._check(self.lib.dq_gemm_f32(self.h, M, N, K, float(alpha), _ptr(A), _ld(A), int(ta), _ptr(B), _ld(B),
+                                         int(tb), float(beta), _ptr(C), _ld(C)), "dq_gemm_f32")
+
+    def dq_gemm_bf16(self, M, N, K, A, ta, B, tb, C):
+        self._check(self.lib.dq_gemm_bf16(self.h, M, N, K, _ptr(A), _ld(A), int(ta), _ptr(B), _ld(B), int(tb),
+                                          _ptr(C), _ld(C)), "dq_gemm_bf16")
+
+    # ---- measurement
+    def dq_profile_enable(self, mask: int):
+        self._check(self.lib.dq_profile_enable(self.h, mask), "dq_profile_enable")
+
+    def dq_profile_read(self, klass: int):
+        ms, cnt, fl, by = _c.c_double(0), _l(0), _c.c_double(0), _c.c_double(0)
+        self._check(self.lib.dq_profile_read(self.h, klass, ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(fl),
+                                             ctypes.byref(by)), "dq_profile_read")
+        return {"ms": ms.value, "launches": int(cnt.value), "flops": fl.value, "bytes": by.value}

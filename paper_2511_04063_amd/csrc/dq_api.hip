@@ -1,0 +1,652 @@
+// C ABI of libdartqr.so: argument checking, workspace carving and the sequencing of the kernels of one
+// QR-Orth step (Alg. 1 lines 7-10) on the caller's HIP stream.  No device memory is allocated here.
+#include <new>
+#include <vector>
+
+#include "dq_internal.h"
+
+namespace dq {
+
+// ---------------------------------------------------------------- profiling
+struct Profiler {
+    unsigned mask = 0;
+    struct Rec { int klass; double flops, bytes; };
+    std::vector<hipEvent_t> ev;   // two per record
+    std::vector<Rec> recs;
+    bool failed = false;
+    int acquire(int klass, double flops, double bytes) {
+        const size_t slot = recs.size();
+        if (slot >= 65536) return -1;
+        while (ev.size() < 2 * (slot + 1)) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) { failed = true; return -1; }
+            ev.push_back(e);
+        }
+        recs.push_back({klass, flops, bytes});
+        return (int)slot;
+    }
+};
+
+LaunchScope::LaunchScope(Profiler* p, hipStream_t s, int k, double flops, double bytes)
+    : prof(p), stream(s), klass(k), slot(-1) {
+    if (prof != nullptr && ((prof->mask >> k) & 1u)) {
+        slot = prof->acquire(k, flops, bytes);
+        if (slot >= 0 && hipEventRecord(prof->ev[2 * slot], stream) != hipSuccess) prof->failed = true;
+    }
+}
+LaunchScope::~LaunchScope() {
+    if (slot >= 0 && hipEventRecord(prof->ev[2 * slot + 1], stream) != hipSuccess) prof->failed = true;
+}
+
+}  // namespace dq
+
+using namespace dq;
+
+struct dq_ctx {
+    hipStream_t stream = nullptr;
+    int device = 0;
+    char* ws = nullptr;
+    size_t ws_bytes = 0;
+    Profiler prof;
+};
+
+namespace {
+
+// ---------------------------------------------------------------- workspace layout
+struct Layout {
+    long ld = 0;          // leading dimension of every internal n x n fp32 matrix
+    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0,
+           vs = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
+    size_t gsplit_floats = 0;
+    size_t total = 0;
+};
+
+size_t bump(size_t& cur, size_t bytes) {
+    const size_t off = cur;
+    cur += (bytes + 255) / 256 * 256;
+    return off;
+}
+
+Layout make_layout(int n, int T) {
+    Layout L;
+    L.ld = round_up(n, 8);
+    const size_t n2 = (size_t)n * L.ld;
+    size_t cur = 0;
+    L.flags = bump(cur, 256);
+    L.A = bump(cur, n2 * 4);
+    L.R = bump(cur, n2 * 4);
+    L.U = bump(cur, n2 * 4);
+    L.G = bump(cur, n2 * 4);
+    L.B = bump(cur, n2 * 4);
+    L.P = bump(cur, n2 * 4);
+    L.M = bump(cur, n2 * 4);
+    L.tau = bump(cur, (size_t)round_up(n, 64) * 4);
+    const size_t npanels = (n + kPanel - 1) / kPanel;
+    L.Tall = bump(cur, npanels * kPanel * kPanel * 4);
+    L.wpart = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
+    L.w2 = bump(cur, (size_t)kPanel * L.ld * 4);
+    L.vs = bump(cur, panel_scratch_floats(n) * 4);
+    const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
+    L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
+    const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
+    L.Y = bump(cur, tn * 4);
+    L.dY = bump(cur, tn * 4);
+    L.rbt = bump(cur, n2 * 2);
+    L.losspart = bump(cur, (size_t)kLossPartials * 8);
+    L.gsplit_floats = (size_t)kMaxSplit * n2;
+    if (L.gsplit_floats > ((size_t)16 << 20)) L.gsplit_floats = (size_t)16 << 20;
+    L.gsplit = bump(cur, L.gsplit_floats * 4);
+    L.total = cur;
+    return L;
+}
+
+template <typename Tp>
+Tp* at(dq_ctx* c, size_t off) { return reinterpret_cast<Tp*>(c->ws + off); }
+
+// ---------------------------------------------------------------- argument checks
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+dq_status check_f32(const void* p, long ld, int cols) {
+    if (p == nullptr) return DQ_ERR_NULL;
+    if (ld < cols) return DQ_ERR_SHAPE;
+    if (!aligned16(p) || (ld & 3) != 0) return DQ_ERR_ALIGN;
+    return DQ_OK;
+}
+dq_status check_bf16(const void* p, long ld, int cols) {
+    if (p == nullptr) return DQ_ERR_NULL;
+    if (ld < cols) return DQ_ERR_SHAPE;
+    if (!aligned16(p) || (ld & 7) != 0) return DQ_ERR_ALIGN;
+    return DQ_OK;
+}
+dq_status check_x(const void* p, dq_dtype dt, long ld, int cols) {
+    if (dt == DQ_F32) return check_f32(p, ld, cols);
+    if (dt == DQ_BF16) return check_bf16(p, ld, cols);
+    return DQ_ERR_DTYPE;
+}
+dq_status check_n(int n) {
+    if (n < 1) return DQ_ERR_SHAPE;
+    if (n > DQ_MAX_N) return DQ_ERR_UNSUPPORTED;
+    return DQ_OK;
+}
+dq_status check_ws(dq_ctx* c, const Layout& L) {
+    if (c->ws == nullptr || c->ws_bytes < L.total) return DQ_ERR_WORKSPACE;
+    return DQ_OK;
+}
+
+#define DQ_TRY(expr)                      \
+    do {                                  \
+        const dq_status _s = (expr);      \
+        if (_s != DQ_OK) return _s;       \
+    } while (0)
+#define DQ_HIP(expr)                              \
+    do {                                          \
+        if ((expr) != hipSuccess) return DQ_ERR_HIP; \
+    } while (0)
+
+// ---------------------------------------------------------------- split-K choice
+// Enough layers to give every compute unit a workgroup when the output has few tiles.
+void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int& kchunk) {
+    splits = 1;
+    if (tiles < 128) {
+        splits = (256 + tiles - 1) / tiles;
+        const int by_k = (K + 255) / 256;   // at least 256 reduction elements per layer
+        if (splits > by_k) splits = by_k;
+        if (splits > max_splits) splits = max_splits;
+        if (splits < 1) splits = 1;
+    }
+    kchunk = (int)round_up((K + splits - 1) / splits, kalign);
+    splits = (K + kchunk - 1) / kchunk;
+    if (splits < 1) splits = 1;
+}
+
+// ---------------------------------------------------------------- block-reflector application
+// Csub (m x nc) <- (I - V op(T) V^T) Csub, V = unit-lower-trapezoid block stored at Vp (m x jb, ldv).
+// With include_gram the first GEMM also produces V^T V in the first jb columns of the partials
+// (Bstart must then be Vp itself and Csub = Bstart + jb) and the T factor is built from it.
+dq_status apply_block_reflector(dq_ctx* c, const Layout& L, const float* Vp, long ldv, int m, int jb,
+                                float* Bstart, long ldb, int ncols_total, int include_gram, const float* tau,
+                                float* Tp, int transT) {
+    hipStream_t s = c->stream;
+    float* wpart = at<float>(c, L.wpart);
+    float* w2 = at<float>(c, L.w2);
+    const long ldw = L.ld;
+    const long stride = (long)kPanel * ldw;
+    int splits, kchunk;
+    choose_split((ncols_total + 127) / 128, m, 16, kMaxSplit, splits, kchunk);
+    {
+        GemmF32 g;
+        g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = 1;
+        g.B = Bstart; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = include_gram ? jb : 0;
+        g.C = wpart; g.ldc = ldw;
+        g.M = jb; g.N = ncols_total; g.K = m;
+        g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * jb * (double)ncols_total * m, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    int col0 = 0;
+    float* Csub = Bstart;
+    int nc = ncols_total;
+    if (include_gram) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_tfactor(wpart, splits, stride, ldw, jb, tau, Tp, s));
+        col0 = jb; Csub = Bstart + jb; nc = ncols_total - jb;
+    }
+    if (nc <= 0) return DQ_OK;
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_wreduce_T(wpart, splits, stride, ldw, col0, jb, nc, Tp, transT, w2, ldw, s));
+    }
+    {
+        GemmF32 g;
+        g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
+        g.B = w2; g.ldb = ldw; g.tb = 0;
+        g.C = Csub; g.ldc = ldb;
+        g.M = m; g.N = nc; g.K = jb;
+        g.alpha = -1.f; g.beta = 1.f;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)nc * jb, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- S1 + S2
+dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
+                      long ldu) {
+    hipStream_t s = c->stream;
+    float* A = at<float>(c, L.A);
+    float* tau = at<float>(c, L.tau);
+    float* Tall = at<float>(c, L.Tall);
+    float* vs = at<float>(c, L.vs);
+    unsigned* flags = at<unsigned>(c, L.flags);
+    const long ld = L.ld;
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
+        DQ_HIP(launch_copy2d(Z, ldz, A, ld, n, n, s));
+    }
+    const int npanels = (n + kPanel - 1) / kPanel;
+    for (int p = 0; p < npanels; ++p) {
+        const int k0 = p * kPanel;
+        const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
+        const int m = n - k0;
+        float* Ap = A + (long)k0 * ld + k0;
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
+            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, flags, s));
+        }
+        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, Ap, ld, m, 1, tau + k0, Tall + (long)p * kPanel * kPanel, 1));
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 4.0 * n * (double)n);
+        DQ_HIP(launch_set_identity(R, ldr, n, s));
+    }
+    for (int p = npanels - 1; p >= 0; --p) {
+        const int k0 = p * kPanel;
+        const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
+        const int m = n - k0;
+        const float* Ap = A + (long)k0 * ld + k0;
+        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, R + (long)k0 * ldr + k0, ldr, m, 0, nullptr,
+                                     Tall + (long)p * kPanel * kPanel, 0));
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 12.0 * n * (double)n);
+        DQ_HIP(launch_sign_normalise(A, ld, n, R, ldr, U, ldu, flags, s));
+    }
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- S3 + S4 + S5
+dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const void* X, dq_dtype xdt, long ldx,
+                               const float* R, long ldr, dq_reduce red, float* loss_dev, float* G, long ldg,
+                               float* Y, long ldy, void* dY, long lddy) {
+    hipStream_t s = c->stream;
+    unsigned* flags = at<unsigned>(c, L.flags);
+    double* lpart = at<double>(c, L.losspart);
+    const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
+    const double gemm_flops = 2.0 * T * (double)n * n;
+    // S3: Y = X @ R
+    if (xdt == DQ_BF16) {
+        bf16_t* rbt = at<bf16_t>(c, L.rbt);
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 6.0 * n * (double)n);
+            DQ_HIP(launch_convert_transpose_bf16(R, ldr, n, rbt, L.ld, s));
+        }
+        GemmBf16 g;
+        g.A = static_cast<const bf16_t*>(X); g.lda = ldx; g.ta = 0;
+        g.B = rbt; g.ldb = L.ld; g.tb = 1;
+        g.C = Y; g.ldc = ldy; g.M = T; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
+        DQ_HIP(launch_gemm_bf16(g, s));
+    } else {
+        GemmF32 g;
+        g.A = static_cast<const float*>(X); g.lda = ldx; g.ta = 0;
+        g.B = R; g.ldb = ldr; g.tb = 0;
+        g.C = Y; g.ldc = ldy; g.M = T; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, gemm_flops, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    // S4: loss and dY in one pass over Y
+    {
+        const int grid = whip_grid(T, n);
+        const double bytes = (double)T * n * (4.0 + (xdt == DQ_BF16 ? 2.0 : 4.0));
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_WHIP, 5.0 * T * (double)n, bytes);
+            DQ_HIP(launch_whip(Y, ldy, T, n, scale, dY, xdt == DQ_BF16, lddy, lpart, grid, s));
+        }
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, s));
+    }
+    // S5: G = X^T @ dY (reduction over the tokens; split when the n x n output has few tiles)
+    {
+        const int tiles = ((n + 127) / 128) * ((n + 127) / 128);
+        int max_splits = (int)(L.gsplit_floats / ((size_t)n * L.ld));
+        if (max_splits > kMaxSplit) max_splits = kMaxSplit;
+        if (max_splits < 1) max_splits = 1;
+        int splits, kchunk;
+        choose_split(tiles, T, 32, max_splits, splits, kchunk);
+        float* gs = at<float>(c, L.gsplit);
+        float* out = splits > 1 ? gs : G;
+        const long ldo = splits > 1 ? L.ld : ldg;
+        const long stride = (long)n * L.ld;
+        if (xdt == DQ_BF16) {
+            GemmBf16 g;
+            g.A = static_cast<const bf16_t*>(X); g.lda = ldx; g.ta = 1;
+            g.B = static_cast<const bf16_t*>(dY); g.ldb = lddy; g.tb = 0;
+            g.C = out; g.ldc = ldo; g.M = n; g.N = n; g.K = T;
+            g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
+            DQ_HIP(launch_gemm_bf16(g, s));
+        } else {
+            GemmF32 g;
+            g.A = static_cast<const float*>(X); g.lda = ldx; g.ta = 1;
+            g.B = static_cast<const float*>(dY); g.ldb = lddy; g.tb = 0;
+            g.C = out; g.ldc = ldo; g.M = n; g.N = n; g.K = T;
+            g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, gemm_flops, 0.0);
+            DQ_HIP(launch_gemm_f32(g, s));
+        }
+        if (splits > 1) {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+            DQ_HIP(launch_splitk_reduce(gs, splits, stride, L.ld, n, n, 1.f, 0.f, G, ldg, s));
+        }
+    }
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- S6 (+ S7 when Zupd != null)
+// dZ = R P U^{-T},  P = strict_lower(R^T G - G^T R).  The triangular solve M U^T = P runs right-looking over
+// column blocks from the last to the first; M is strictly lower triangular, so every product skips its zero part.
+dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, long ldr, const float* U, long ldu,
+                          const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr) {
+    hipStream_t s = c->stream;
+    unsigned* flags = at<unsigned>(c, L.flags);
+    float* Bb = at<float>(c, L.B);
+    float* Pb = at<float>(c, L.P);
+    float* Mb = at<float>(c, L.M);
+    float* uinv = at<float>(c, L.uinv);
+    const long ld = L.ld;
+    const double n3 = (double)n * n * n;
+    {
+        GemmF32 g;
+        g.A = R; g.lda = ldr; g.ta = 1;
+        g.B = G; g.ldb = ldg; g.tb = 0;
+        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * n * (double)n);
+        DQ_HIP(launch_skew_lower(Bb, ld, n, Pb, ld, Mb, ld, s));
+        DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s));
+    }
+    const int nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
+    for (int j = nblk - 1; j >= 0; --j) {
+        const int j0 = j * kTrsmBlock;
+        const int w = (n - j0) < kTrsmBlock ? (n - j0) : kTrsmBlock;
+        const int mrows = n - j0;
+        {
+            GemmF32 g;   // M[j0:, blk] = P[j0:, blk] * inv(U_jj)^T
+            g.A = Pb + (long)j0 * ld + j0; g.lda = ld; g.ta = 0;
+            g.B = uinv + (long)j * kTrsmBlock * kTrsmBlock; g.ldb = kTrsmBlock; g.tb = 1;
+            g.C = Mb + (long)j0 * ld + j0; g.ldc = ld;
+            g.M = mrows; g.N = w; g.K = w;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mrows * (double)w * w, 0.0);
+            DQ_HIP(launch_gemm_f32(g, s));
+        }
+        if (j0 > 0) {
+            GemmF32 g;   // P[j0:, 0:j0] -= M[j0:, blk] * U[0:j0, blk]^T
+            g.A = Mb + (long)j0 * ld + j0; g.lda = ld; g.ta = 0;
+            g.B = U + j0; g.ldb = ldu; g.tb = 1;
+            g.C = Pb + (long)j0 * ld; g.ldc = ld;
+            g.M = mrows; g.N = j0; g.K = w;
+            g.alpha = -1.f; g.beta = 1.f;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mrows * (double)j0 * w, 0.0);
+            DQ_HIP(launch_gemm_f32(g, s));
+        }
+    }
+    {
+        GemmF32 g;   // dZ = R * M  (or Z <- Z - lr * R * M)
+        g.A = R; g.lda = ldr; g.ta = 0;
+        g.B = Mb; g.ldb = ld; g.tb = 0; g.b_strict_lower = 1;
+        g.M = n; g.N = n; g.K = n;
+        if (Zupd != nullptr) { g.C = Zupd; g.ldc = ldz; g.alpha = -lr; g.beta = 1.f; }
+        else { g.C = dZ; g.ldc = lddz; }
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    return DQ_OK;
+}
+
+}  // namespace
+
+// =================================================================== C ABI
+extern "C" {
+
+const char* dq_status_string(dq_status s) {
+    switch (s) {
+        case DQ_OK: return "ok";
+        case DQ_ERR_NULL: return "null pointer";
+        case DQ_ERR_SHAPE: return "bad shape or leading dimension";
+        case DQ_ERR_DTYPE: return "bad dtype or reduce mode";
+        case DQ_ERR_ALIGN: return "pointer or leading dimension misaligned";
+        case DQ_ERR_WORKSPACE: return "workspace missing or too small";
+        case DQ_ERR_HIP: return "HIP runtime error";
+        case DQ_ERR_UNSUPPORTED: return "size outside the supported range";
+    }
+    return "unknown status";
+}
+
+dq_status dq_create(dq_ctx** out, void* hip_stream) {
+    if (out == nullptr) return DQ_ERR_NULL;
+    dq_ctx* c = new (std::nothrow) dq_ctx();
+    if (c == nullptr) return DQ_ERR_HIP;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
+    *out = c;
+    return DQ_OK;
+}
+
+dq_status dq_destroy(dq_ctx* c) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+    delete c;
+    return DQ_OK;
+}
+
+dq_status dq_workspace_bytes(int b, int n, int T, dq_dtype x_dtype, size_t* out) {
+    if (out == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if (x_dtype != DQ_F32 && x_dtype != DQ_BF16) return DQ_ERR_DTYPE;
+    *out = make_layout(n, T).total;
+    return DQ_OK;
+}
+
+dq_status dq_set_workspace(dq_ctx* c, void* dptr, size_t bytes) {
+    if (c == nullptr || dptr == nullptr) return DQ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(dptr) & 255) != 0) return DQ_ERR_ALIGN;
+    if (bytes < 256) return DQ_ERR_WORKSPACE;
+    c->ws = static_cast<char*>(dptr);
+    c->ws_bytes = bytes;
+    DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
+    return DQ_OK;
+}
+
+dq_status dq_device_flags(dq_ctx* c, unsigned* host_out) {
+    if (c == nullptr || host_out == nullptr) return DQ_ERR_NULL;
+    if (c->ws == nullptr) return DQ_ERR_WORKSPACE;
+    DQ_HIP(hipMemcpyAsync(host_out, c->ws, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
+    DQ_HIP(hipStreamSynchronize(c->stream));
+    DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
+    return DQ_OK;
+}
+
+dq_status dq_qr_orth(dq_ctx* c, int b, int n, const float* Z, long ldz, float* R, long ldr, float* U, long ldu) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    DQ_TRY(check_f32(Z, ldz, n));
+    DQ_TRY(check_f32(R, ldr, n));
+    if (U != nullptr) DQ_TRY(check_f32(U, ldu, n));
+    const Layout L = make_layout(n, 1);
+    DQ_TRY(check_ws(c, L));
+    for (int i = 0; i < b; ++i)
+        DQ_TRY(qr_orth_one(c, L, n, Z + (long)i * n * ldz, ldz, R + (long)i * n * ldr, ldr,
+                           U ? U + (long)i * n * ldu : nullptr, ldu));
+    return DQ_OK;
+}
+
+dq_status dq_rotate_loss_grad(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype xdt, long ldx, const float* R,
+                              long ldr, dq_reduce red, float* loss_dev, float* G, long ldg, float* Y, long ldy,
+                              void* dY, long lddy) {
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_x(X, xdt, ldx, n));
+    DQ_TRY(check_f32(R, ldr, n));
+    DQ_TRY(check_f32(G, ldg, n));
+    if (Y != nullptr) DQ_TRY(check_f32(Y, ldy, n));
+    if (dY != nullptr) DQ_TRY(check_x(dY, xdt, lddy, n));
+    const Layout L = make_layout(n, T);
+    DQ_TRY(check_ws(c, L));
+    const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
+    for (int i = 0; i < b; ++i) {
+        float* Yi = Y ? Y + (long)i * T * ldy : at<float>(c, L.Y);
+        const long ldyi = Y ? ldy : L.ld;
+        void* dYi = dY ? static_cast<void*>(static_cast<char*>(dY) + (size_t)i * T * lddy * esz)
+                       : static_cast<void*>(at<char>(c, L.dY));
+        const long lddyi = dY ? lddy : L.ld;
+        const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
+        DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, R + (long)i * n * ldr, ldr, red, loss_dev + i,
+                                    G + (long)i * n * ldg, ldg, Yi, ldyi, dYi, lddyi));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype xdt, long ldx, float* Z, long ldz,
+                        float lr, dq_reduce red, float* loss_dev, float* R, long ldr) {
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_x(X, xdt, ldx, n));
+    DQ_TRY(check_f32(Z, ldz, n));
+    if (R != nullptr) DQ_TRY(check_f32(R, ldr, n));
+    const Layout L = make_layout(n, T);
+    DQ_TRY(check_ws(c, L));
+    const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
+    for (int i = 0; i < b; ++i) {
+        float* Zi = Z + (long)i * n * ldz;
+        float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
+        const long ldri = R ? ldr : L.ld;
+        float* Ui = at<float>(c, L.U);
+        float* Gi = at<float>(c, L.G);
+        const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
+        DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
+                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
+        DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, nullptr, 0, Zi, ldz, lr));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_whip_loss_grad(dq_ctx* c, int b, int T, int n, const float* Y, long ldy, dq_reduce red, float* loss_dev,
+                            void* dY, dq_dtype dydt, long lddy) {
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1 || n < 1) return DQ_ERR_SHAPE;
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_f32(Y, ldy, n));
+    DQ_TRY(check_x(dY, dydt, lddy, n));
+    if (c->ws == nullptr || c->ws_bytes < make_layout(1, 1).total) return DQ_ERR_WORKSPACE;
+    // only the status word and the loss partials are needed: they sit at fixed offsets of the n = 1 layout
+    const Layout L = make_layout(1, 1);
+    unsigned* flags = at<unsigned>(c, L.flags);
+    double* lpart = at<double>(c, L.losspart);
+    const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
+    const size_t esz = (dydt == DQ_BF16) ? 2 : 4;
+    for (int i = 0; i < b; ++i) {
+        const int grid = whip_grid(T, n);
+        {
+            LaunchScope sc(&c->prof, c->stream, DQ_K_WHIP, 5.0 * T * (double)n, (double)T * n * (4.0 + esz));
+            DQ_HIP(launch_whip(Y + (long)i * T * ldy, ldy, T, n, scale,
+                               static_cast<char*>(dY) + (size_t)i * T * lddy * esz, dydt == DQ_BF16, lddy, lpart, grid,
+                               c->stream));
+        }
+        DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev + i, flags, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, const float* U, long ldu, const float* G,
+                         long ldg, float* dZ, long lddz) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    DQ_TRY(check_f32(R, ldr, n));
+    DQ_TRY(check_f32(U, ldu, n));
+    DQ_TRY(check_f32(G, ldg, n));
+    DQ_TRY(check_f32(dZ, lddz, n));
+    const Layout L = make_layout(n, 1);
+    DQ_TRY(check_ws(c, L));
+    for (int i = 0; i < b; ++i)
+        DQ_TRY(qr_backward_one(c, L, n, R + (long)i * n * ldr, ldr, U + (long)i * n * ldu, ldu, G + (long)i * n * ldg,
+                               ldg, dZ + (long)i * n * lddz, lddz, nullptr, 0, 0.f));
+    return DQ_OK;
+}
+
+dq_status dq_sgd_update(dq_ctx* c, int b, int n, float* Z, long ldz, const float* dZ, long lddz, float lr) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || n < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_f32(Z, ldz, n));
+    DQ_TRY(check_f32(dZ, lddz, n));
+    for (int i = 0; i < b; ++i) {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
+        DQ_HIP(launch_axpy2d(Z + (long)i * n * ldz, ldz, dZ + (long)i * n * lddz, lddz, n, -lr, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_gemm_f32(dq_ctx* c, int M, int N, int K, float alpha, const float* A, long lda, int ta, const float* B,
+                      long ldb, int tb, float beta, float* C, long ldc) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (M < 0 || N < 0 || K < 0) return DQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return DQ_OK;
+    DQ_TRY(check_f32(A, lda, ta ? M : K));
+    DQ_TRY(check_f32(B, ldb, tb ? K : N));
+    DQ_TRY(check_f32(C, ldc, N));
+    GemmF32 g;
+    g.A = A; g.lda = lda; g.ta = ta ? 1 : 0;
+    g.B = B; g.ldb = ldb; g.tb = tb ? 1 : 0;
+    g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K; g.alpha = alpha; g.beta = beta;
+    LaunchScope sc(&c->prof, c->stream, DQ_K_GEMM_F32, 2.0 * M * (double)N * K, 0.0);
+    DQ_HIP(launch_gemm_f32(g, c->stream));
+    return DQ_OK;
+}
+
+dq_status dq_gemm_bf16(dq_ctx* c, int M, int N, int K, const void* A, long lda, int ta, const void* B, long ldb,
+                       int tb, float* C, long ldc) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (M < 0 || N < 0 || K < 0) return DQ_ERR_SHAPE;
+    if (M == 0 || N == 0) return DQ_OK;
+    DQ_TRY(check_bf16(A, lda, ta ? M : K));
+    DQ_TRY(check_bf16(B, ldb, tb ? K : N));
+    DQ_TRY(check_f32(C, ldc, N));
+    GemmBf16 g;
+    g.A = static_cast<const bf16_t*>(A); g.lda = lda; g.ta = ta ? 1 : 0;
+    g.B = static_cast<const bf16_t*>(B); g.ldb = ldb; g.tb = tb ? 1 : 0;
+    g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.K = K;
+    LaunchScope sc(&c->prof, c->stream, DQ_K_GEMM_BF16, 2.0 * M * (double)N * K, 0.0);
+    DQ_HIP(launch_gemm_bf16(g, c->stream));
+    return DQ_OK;
+}
+
+dq_status dq_profile_enable(dq_ctx* c, unsigned mask) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    DQ_HIP(hipStreamSynchronize(c->stream));
+    c->prof.mask = mask;
+    c->prof.recs.clear();
+    c->prof.failed = false;
+    return DQ_OK;
+}
+
+dq_status dq_profile_read(dq_ctx* c, dq_kernel_class k, double* ms, long* launches, double* flops, double* bytes) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if ((int)k < 0 || (int)k >= DQ_K_COUNT) return DQ_ERR_DTYPE;
+    DQ_HIP(hipStreamSynchronize(c->stream));
+    if (c->prof.failed) return DQ_ERR_HIP;
+    double tms = 0.0, tf = 0.0, tb = 0.0;
+    long cnt = 0;
+    for (size_t i = 0; i < c->prof.recs.size(); ++i) {
+        if (c->prof.recs[i].klass != (int)k) continue;
+        float one = 0.f;
+        DQ_HIP(hipEventElapsedTime(&one, c->prof.ev[2 * i], c->prof.ev[2 * i + 1]));
+        tms += one; tf += c->prof.recs[i].flops; tb += c->prof.recs[i].bytes; ++cnt;
+    }
+    if (ms) *ms = tms;
+    if (launches) *launches = cnt;
+    if (flops) *flops = tf;
+    if (bytes) *bytes = tb;
+    return DQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,106 @@
+// Internal declarations shared by the translation units of libdartqr.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dartqr.h"
+
+namespace dq {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kPanel = 64;           // QR panel width nb (columns aggregated into one compact-WY block)
+constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
+constexpr int kMaxSplit = 32;        // upper bound on split-K partials
+constexpr int kLossPartials = 2048;  // upper bound on workgroups of the Whip pass (one partial each)
+
+typedef uint16_t bf16_t;             // raw bfloat16 storage
+
+inline __host__ __device__ long round_up(long x, long m) { return (x + m - 1) / m * m; }
+
+// ---- profiling hook ---------------------------------------------------------------
+struct Profiler;   // defined in dq_api.hip
+struct LaunchScope {
+    // Brackets the launches made during its lifetime with a pair of HIP events when the class is
+    // enabled, and attributes `flops` / `bytes` of algorithmic work to it.
+    LaunchScope(Profiler* p, hipStream_t s, int klass, double flops, double bytes);
+    ~LaunchScope();
+    Profiler* prof; hipStream_t stream; int klass; int slot;
+};
+
+// ---- fp32 matrix-core GEMM --------------------------------------------------------
+struct GemmF32 {
+    const float* A = nullptr; long lda = 0;
+    const float* B = nullptr; long ldb = 0;
+    float* C = nullptr; long ldc = 0;
+    int M = 0, N = 0, K = 0;
+    int ta = 0;            // A is stored K x M (the product uses its transpose)
+    int tb = 0;            // B is stored N x K
+    float alpha = 1.f, beta = 0.f;
+    // A's STORAGE is a block of Householder vectors: entry (r, c) is 0 for r < c, 1 for r == c and the
+    // stored value for r > c (the stored upper part belongs to the triangular factor).
+    int a_unit_lower = 0;
+    // The first `b_unit_lower_cols` storage columns of B (tb == 0) get the same treatment.
+    int b_unit_lower_cols = 0;
+    // B(k, n) is known to vanish for k <= n (strictly lower triangular, tb == 0): K loop starts at the tile's n0.
+    int b_strict_lower = 0;
+    // split-K: z-th workgroup layer reduces k in [z*kchunk, (z+1)*kchunk) and writes C + z*split_stride
+    int splits = 1; int kchunk = 0; long split_stride = 0;
+};
+hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s);
+
+// ---- bf16 matrix-core GEMM (fp32 accumulate, fp32 out) ------------------------------
+struct GemmBf16 {
+    const bf16_t* A = nullptr; long lda = 0;
+    const bf16_t* B = nullptr; long ldb = 0;
+    float* C = nullptr; long ldc = 0;
+    int M = 0, N = 0, K = 0;
+    int ta = 0, tb = 0;    // as above
+    int splits = 1; int kchunk = 0; long split_stride = 0;
+};
+hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
+
+// out (rows x cols, ldo) = alpha * sum_z part[z] + beta * out
+hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,
+                                float alpha, float beta, float* out, long ldo, hipStream_t s);
+
+// ---- QR pieces --------------------------------------------------------------------
+// Factor the m x jb panel at A (row-major, lda) in place: reflectors below the diagonal (unit diagonal
+// implied), triangular factor on and above it; tau[0..jb).  vscratch: >= panel_scratch_floats(m) floats.
+size_t panel_scratch_floats(int m);
+hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch,
+                           unsigned* flags, hipStream_t s);
+// T (jb x jb upper, ld kPanel) of the compact-WY form from the Gram partials G = V^T V
+// (gpart[z] at stride, leading dimension ldp, first jb columns) and tau.
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb,
+                          const float* tau, float* Tout, hipStream_t s);
+// W2 (jb x nc, ldw2) = op(T) * sum_z part[z][:, col0 : col0+nc]   (op = transpose when transT != 0)
+hipError_t launch_wreduce_T(const float* part, int splits, long stride, long ldp, int col0, int jb, int nc,
+                            const float* T, int transT, float* W2, long ldw2, hipStream_t s);
+
+hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s);
+hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s);
+hipError_t launch_fill_u32(unsigned* p, long count, unsigned v, hipStream_t s);
+// s_j = sign(Afac[j][j]) (>= 0 -> +1);  R[:, j] *= s_j;  U = diag(s) * triu(Afac) (if U != null)
+hipError_t launch_sign_normalise(const float* Afac, long lda, int n, float* R, long ldr, float* U, long ldu,
+                                 unsigned* flags, hipStream_t s);
+
+// ---- backward pieces --------------------------------------------------------------
+// P = strict_lower(B - B^T); Mzero gets zeros everywhere (if non-null).
+hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp, float* Mzero, long ldm, hipStream_t s);
+// Inverse of every kTrsmBlock x kTrsmBlock diagonal block of the upper-triangular U: Uinv[blk] row-major, ld kTrsmBlock.
+hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s);
+hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s);
+
+// ---- rotate / Whip pieces ---------------------------------------------------------
+// RbT[j][k] = bf16(R[k][j])   (n x n, ldt)
+hipError_t launch_convert_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, hipStream_t s);
+// Fused Whip loss + gradient pass: partial sums to `partials` (double, one per workgroup), then
+// launch_loss_finish adds them up: loss = scale * sum.  dy_is_bf16 selects the dtype of dY.
+int whip_grid(long rows, int cols);
+hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
+                       double* partials, int grid, hipStream_t s);
+hipError_t launch_loss_finish(const double* partials, int count, float scale, float* loss_dev, unsigned* flags,
+                              hipStream_t s);
+
+}  // namespace dq

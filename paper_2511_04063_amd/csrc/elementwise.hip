@@ -1,0 +1,246 @@
+// HBM-bound passes of the step:
+//   * the fused Whip loss + gradient pass over Y (Eq. 4 and its derivative; Alg. 1 line 9),
+//   * fp32 -> bf16 conversion of the rotation with a transpose (operand preparation for X @ R),
+//   * P = strict_lower(B - B^T) of the derivative through Z = R U,
+//   * inverses of the diagonal blocks of U for the blocked triangular solve,
+//   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
+#include "dq_internal.h"
+
+namespace dq {
+namespace {
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// Each thread handles runs of 8 consecutive elements of a row: two 16-byte loads of Y, one 16-byte (bf16)
+// or two 16-byte (fp32) stores of dY.  e = exp(-|y|) contributes to the loss; dY = -scale * sgn(y) * e.
+template <bool BF16OUT>
+__global__ __launch_bounds__(256) void whip_kernel(const float* __restrict__ Y, long ldy, int T, int n, float scale,
+                                                   void* __restrict__ dYv, long lddy, double* __restrict__ partials,
+                                                   int yvec, int dvec) {
+    const int cpr = (n + 7) >> 3;                 // 8-element chunks per row
+    const long chunks = (long)T * cpr;
+    float acc = 0.f;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < chunks; e += (long)gridDim.x * 256) {
+        const int row = (int)(e / cpr);
+        const int c0 = (int)(e - (long)row * cpr) << 3;
+        const float* src = Y + (long)row * ldy + c0;
+        float y[8];
+        const bool full = c0 + 7 < n;
+        if (full && yvec) {
+            const float4 a = *reinterpret_cast<const float4*>(src);
+            const float4 b = *reinterpret_cast<const float4*>(src + 4);
+            y[0] = a.x; y[1] = a.y; y[2] = a.z; y[3] = a.w; y[4] = b.x; y[5] = b.y; y[6] = b.z; y[7] = b.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) y[j] = (c0 + j < n) ? src[j] : 0.f;
+        }
+        float d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float ay = fabsf(y[j]);
+            const float ex = __expf(-ay);
+            if (c0 + j < n) acc += ex;
+            const float sg = (y[j] > 0.f) ? -scale : ((y[j] < 0.f) ? scale : 0.f);
+            d[j] = sg * ex;
+        }
+        if (BF16OUT) {
+            bf16_t* dst = reinterpret_cast<bf16_t*>(dYv) + (long)row * lddy + c0;
+            if (full && dvec) {
+                uint4 o;
+                o.x = f32_to_bf16_rne(d[0]) | (f32_to_bf16_rne(d[1]) << 16);
+                o.y = f32_to_bf16_rne(d[2]) | (f32_to_bf16_rne(d[3]) << 16);
+                o.z = f32_to_bf16_rne(d[4]) | (f32_to_bf16_rne(d[5]) << 16);
+                o.w = f32_to_bf16_rne(d[6]) | (f32_to_bf16_rne(d[7]) << 16);
+                *reinterpret_cast<uint4*>(dst) = o;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (c0 + j < n) dst[j] = (bf16_t)f32_to_bf16_rne(d[j]);
+            }
+        } else {
+            float* dst = reinterpret_cast<float*>(dYv) + (long)row * lddy + c0;
+            if (full && dvec) {
+                *reinterpret_cast<float4*>(dst) = make_float4(d[0], d[1], d[2], d[3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(d[4], d[5], d[6], d[7]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (c0 + j < n) dst[j] = d[j];
+            }
+        }
+    }
+    __shared__ float wsum[4];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3];
+}
+
+__global__ __launch_bounds__(256) void loss_finish_kernel(const double* __restrict__ partials, int count, float scale,
+                                                          float* __restrict__ loss_dev, unsigned* flags) {
+    __shared__ double sh[256];
+    double t = 0.0;
+    for (int i = threadIdx.x; i < count; i += 256) t += partials[i];
+    sh[threadIdx.x] = t;
+    __syncthreads();
+    for (int o = 128; o >= 1; o >>= 1) {
+        if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double L = (double)scale * sh[0];
+        const float Lf = (float)L;
+        *loss_dev = Lf;
+        if (!(fabsf(Lf) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+    }
+}
+
+// RbT[j][k] = bf16(R[k][j]) through a 32 x 33 LDS tile so that both the read and the write are coalesced.
+__global__ __launch_bounds__(256) void convert_transpose_bf16_kernel(const float* __restrict__ R, long ldr, int n,
+                                                                     bf16_t* __restrict__ RbT, long ldt) {
+    __shared__ float tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // bx: column block of R, by: row block of R
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        const int r = by + i, c = bx + tx;
+        tile[i][tx] = (r < n && c < n) ? R[(long)r * ldr + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int j = bx + i, k = by + tx;   // output row j (column of R), output column k (row of R)
+        if (j < n && k < n) RbT[(long)j * ldt + k] = (bf16_t)f32_to_bf16_rne(tile[tx][i]);
+    }
+}
+
+// P[i][j] = B[i][j] - B[j][i] for i > j, else 0.  Mzero (optional) is cleared.
+__global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict__ B, long ldb, int n,
+                                                         float* __restrict__ P, long ldp, float* __restrict__ Mz,
+                                                         long ldm) {
+    __shared__ float tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // output tile: rows by.., cols bx..
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const bool need = by + 31 > bx;   // some i > j in this tile
+    if (need) {
+        // transposed source tile: B[bx + i][by + tx]
+        for (int i = ty; i < 32; i += 8) {
+            const int r = bx + i, c = by + tx;
+            tile[i][tx] = (r < n && c < n) ? B[(long)r * ldb + c] : 0.f;
+        }
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int r = by + i, c = bx + tx;
+        if (r < n && c < n) {
+            float v = 0.f;
+            if (need && r > c) v = B[(long)r * ldb + c] - tile[tx][i];
+            P[(long)r * ldp + c] = v;
+            if (Mz != nullptr) Mz[(long)r * ldm + c] = 0.f;
+        }
+    }
+}
+
+// Inverse of one diagonal block (w x w, w <= kTrsmBlock) of an upper-triangular matrix, by back substitution,
+// one thread per column of the inverse.  A zero pivot raises DQ_FLAG_SINGULAR (the result is then not finite).
+__global__ __launch_bounds__(kTrsmBlock) void trinv_blocks_kernel(const float* __restrict__ U, long ldu, int n,
+                                                                  float* __restrict__ Uinv, unsigned* flags) {
+    __shared__ float Xs[kTrsmBlock][kTrsmBlock];
+    const int blk = blockIdx.x;
+    const int j0 = blk * kTrsmBlock;
+    const int w = (n - j0) < kTrsmBlock ? (n - j0) : kTrsmBlock;
+    const float* Ub = U + (long)j0 * ldu + j0;
+    const int j = threadIdx.x;
+    if (j < w) {
+        const float ujj = Ub[(long)j * ldu + j];
+        if (ujj == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        Xs[j][j] = 1.f / ujj;
+        for (int i = j - 1; i >= 0; --i) {
+            const float* urow = Ub + (long)i * ldu;
+            float acc = 0.f;
+            for (int k = i + 1; k <= j; ++k) acc += urow[k] * Xs[k][j];
+            Xs[i][j] = -acc / urow[i];
+        }
+    }
+    __syncthreads();
+    float* out = Uinv + (long)blk * kTrsmBlock * kTrsmBlock;
+    for (int i = 0; i < kTrsmBlock; ++i)
+        out[(long)i * kTrsmBlock + j] = (i <= j && j < w) ? Xs[i][j] : 0.f;
+}
+
+__global__ __launch_bounds__(256) void axpy2d_kernel(float* __restrict__ Z, long ldz, const float* __restrict__ D,
+                                                     long ldd, int n, float a) {
+    const long total = (long)n * n;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / n), c = (int)(e % n);
+        Z[(long)r * ldz + c] += a * D[(long)r * ldd + c];
+    }
+}
+
+}  // namespace
+
+int whip_grid(long rows, int cols) {
+    const long chunks = rows * (long)((cols + 7) / 8);
+    long g = (chunks + 255) / 256;
+    if (g > kLossPartials) g = kLossPartials;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
+                       double* partials, int grid, hipStream_t s) {
+    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? 1 : 0;
+    if (dy_is_bf16) {
+        const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 7) == 0) ? 1 : 0;
+        hipLaunchKernelGGL((whip_kernel<true>), dim3(grid), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy, partials,
+                           yvec, dvec);
+    } else {
+        const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 3) == 0) ? 1 : 0;
+        hipLaunchKernelGGL((whip_kernel<false>), dim3(grid), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy, partials,
+                           yvec, dvec);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_finish(const double* partials, int count, float scale, float* loss_dev, unsigned* flags,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(256), 0, s, partials, count, scale, loss_dev, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_convert_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, hipStream_t s) {
+    const int tb = (n + 31) / 32;
+    hipLaunchKernelGGL(convert_transpose_bf16_kernel, dim3(tb, tb), dim3(256), 0, s, R, ldr, n, RbT, ldt);
+    return hipGetLastError();
+}
+
+hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp, float* Mzero, long ldm,
+                             hipStream_t s) {
+    const int tb = (n + 31) / 32;
+    hipLaunchKernelGGL(skew_lower_kernel, dim3(tb, tb), dim3(256), 0, s, B, ldb, n, P, ldp, Mzero, ldm);
+    return hipGetLastError();
+}
+
+hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s) {
+    const int nb = (n + kTrsmBlock - 1) / kTrsmBlock;
+    hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb), dim3(kTrsmBlock), 0, s, U, ldu, n, Uinv, flags);
+    return hipGetLastError();
+}
+
+hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s) {
+    long b = ((long)n * n + 255) / 256;
+    if (b > 8192) b = 8192;
+    hipLaunchKernelGGL(axpy2d_kernel, dim3((unsigned)b), dim3(256), 0, s, Z, ldz, D, ldd, n, a);
+    return hipGetLastError();
+}
+
+}  // namespace dq

@@ -1,0 +1,227 @@
+// bf16 x bf16 -> fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), LDS-staged,
+// double-buffered:   C (M x N, fp32) = op(A) * op(B).
+//
+// Serves the two large products of Alg. 1:  O = X @ R (line 8; X bf16, R rounded to bf16 and stored
+// transposed so that both operands are k-contiguous) and G = X^T @ dY (the chain rule to R; both operands
+// are stored with the reduction dimension, the tokens, as rows, and are transposed on their way into LDS).
+//
+// Workgroup: 256 threads = 2 x 2 wavefronts; tile 128 x 128 x 32; wavefront tile 64 x 64 = 2 x 2 MFMA tiles.
+// LDS keeps both operands as [mn][k] with k contiguous (row stride 40 halfwords = 80 bytes).
+//
+// MFMA 32x32x16 bf16 lane layout (lane l of 64): the A operand holds 8 consecutive k of row m = l % 32, the
+// B operand 8 consecutive k of column n = l % 32, both for k group l / 32; accumulator register v holds
+// D[m = 8*(v/4) + 4*(l/32) + v%4][n = l % 32].  Both operands are fetched with the same k assignment, so
+// only the m / n / D mappings matter for correctness.
+#include "dq_internal.h"
+
+namespace dq {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDH = BK + 8;   // LDS row stride in halfwords
+
+struct OperandViewH {
+    const bf16_t* p; long ld;
+    int row_lim, col_lim;
+    int vec;                  // 16-byte loads allowed (k-contiguous path)
+};
+
+union Frag {
+    uint4 q[2];
+    uint32_t w[8];
+};
+
+// k-contiguous storage (mn, k): two 16-byte chunks per thread
+__device__ __forceinline__ void fetch_kc(const OperandViewH& o, int mn0, int k0, int tid, Frag& fr) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        const int sr = mn0 + (f >> 2), sc = k0 + ((f & 3) << 3);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (sr < o.row_lim) {
+            const bf16_t* q = o.p + (long)sr * o.ld + sc;
+            if (o.vec && sc + 7 < o.col_lim) {
+                v = *reinterpret_cast<const uint4*>(q);
+            } else {
+                uint32_t e[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) e[j] = (sc + j < o.col_lim) ? (uint32_t)q[j] : 0u;
+                v.x = e[0] | (e[1] << 16);
+                v.y = e[2] | (e[3] << 16);
+                v.z = e[4] | (e[5] << 16);
+                v.w = e[6] | (e[7] << 16);
+            }
+        }
+        fr.q[i] = v;
+    }
+}
+
+__device__ __forceinline__ void stash_kc(bf16_t (*S)[LDH], int tid, const Frag& fr) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        *reinterpret_cast<uint4*>(&S[f >> 2][(f & 3) << 3]) = fr.q[i];
+    }
+}
+
+// mn-contiguous storage (k, mn): each thread takes a pair of adjacent mn and 8 consecutive k
+// (eight 4-byte loads, each wavefront reading 256 contiguous bytes), then repacks to two k-runs.
+__device__ __forceinline__ void fetch_mc(const OperandViewH& o, int mn0, int k0, int tid, Frag& fr) {
+    const int m2 = tid & 63, kg = tid >> 6;
+    const int sc = mn0 + 2 * m2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int sr = k0 + 8 * kg + j;
+        uint32_t w = 0u;
+        if (sr < o.row_lim) {
+            const bf16_t* q = o.p + (long)sr * o.ld + sc;
+            if (sc + 1 < o.col_lim) {
+                w = *reinterpret_cast<const uint32_t*>(q);
+            } else if (sc < o.col_lim) {
+                w = (uint32_t)q[0];
+            }
+        }
+        fr.w[j] = w;
+    }
+}
+
+__device__ __forceinline__ void stash_mc(bf16_t (*S)[LDH], int tid, const Frag& fr) {
+    const int m2 = tid & 63, kg = tid >> 6;
+    uint4 lo, hi;
+    lo.x = (fr.w[0] & 0xffffu) | (fr.w[1] << 16);
+    lo.y = (fr.w[2] & 0xffffu) | (fr.w[3] << 16);
+    lo.z = (fr.w[4] & 0xffffu) | (fr.w[5] << 16);
+    lo.w = (fr.w[6] & 0xffffu) | (fr.w[7] << 16);
+    hi.x = (fr.w[0] >> 16) | (fr.w[1] & 0xffff0000u);
+    hi.y = (fr.w[2] >> 16) | (fr.w[3] & 0xffff0000u);
+    hi.z = (fr.w[4] >> 16) | (fr.w[5] & 0xffff0000u);
+    hi.w = (fr.w[6] >> 16) | (fr.w[7] & 0xffff0000u);
+    *reinterpret_cast<uint4*>(&S[2 * m2][8 * kg]) = lo;
+    *reinterpret_cast<uint4*>(&S[2 * m2 + 1][8 * kg]) = hi;
+}
+
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m, int tiles_n, int avec, int bvec) {
+    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM][LDH];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN][LDH];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    // XCD-aware tile order (see gemm_f32.hip)
+    const int nt = tiles_m * tiles_n;
+    const int bid = blockIdx.x;
+    const int q8 = nt >> 3, r8 = nt & 7;
+    const int xcd = bid & 7;
+    const int pid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    const int group = 8 * tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * 8;
+    const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int pid_m = first_m + (pid % group) % gsz;
+    const int pid_n = (pid % group) / gsz;
+    const int m0 = pid_m * BM, n0 = pid_n * BN;
+
+    const int z = blockIdx.y;
+    int kb = 0, ke = g.K;
+    if (g.splits > 1) {
+        kb = z * g.kchunk;
+        ke = kb + g.kchunk < g.K ? kb + g.kchunk : g.K;
+    }
+
+    OperandViewH oa, ob;
+    oa.p = g.A; oa.ld = g.lda; oa.vec = avec;
+    if (TA) { oa.row_lim = ke; oa.col_lim = g.M; } else { oa.row_lim = g.M; oa.col_lim = ke; }
+    ob.p = g.B; ob.ld = g.ldb; ob.vec = bvec;
+    if (TB) { ob.row_lim = g.N; ob.col_lim = ke; } else { ob.row_lim = ke; ob.col_lim = g.N; }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    Frag fa, fb;
+    if (nk > 0) {
+        if (TA) fetch_mc(oa, m0, kb, tid, fa); else fetch_kc(oa, m0, kb, tid, fa);
+        if (TB) fetch_kc(ob, n0, kb, tid, fb); else fetch_mc(ob, n0, kb, tid, fb);
+        if (TA) stash_mc(As[0], tid, fa); else stash_kc(As[0], tid, fa);
+        if (TB) stash_kc(Bs[0], tid, fb); else stash_mc(Bs[0], tid, fb);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            const int k0 = kb + (kt + 1) * BK;
+            if (TA) fetch_mc(oa, m0, k0, tid, fa); else fetch_kc(oa, m0, k0, tid, fa);
+            if (TB) fetch_kc(ob, n0, k0, tid, fb); else fetch_mc(ob, n0, k0, tid, fb);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 16) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                a[i] = *reinterpret_cast<const bf16x8*>(&As[cur][wm + i * 32 + lrow][ks + lk * 8]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                b[j] = *reinterpret_cast<const bf16x8*>(&Bs[cur][wn + j * 32 + lrow][ks + lk * 8]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+            if (TA) stash_mc(As[cur ^ 1], tid, fa); else stash_kc(As[cur ^ 1], tid, fa);
+            if (TB) stash_kc(Bs[cur ^ 1], tid, fb); else stash_mc(Bs[cur ^ 1], tid, fb);
+        }
+        __syncthreads();
+    }
+
+    float* C = g.C + (long)z * g.split_stride;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                if (row < g.M && col < g.N) C[(long)row * g.ldc + col] = acc[i][j][v];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0) return hipSuccess;
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 7) == 0) ? 1 : 0;
+    const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0) ? 1 : 0;
+    dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
+    dim3 block(256, 1, 1);
+    if (g.ta && g.tb)
+        hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else if (g.ta)
+        hipLaunchKernelGGL((gemm_bf16_kernel<true, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else if (g.tb)
+        hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else
+        hipLaunchKernelGGL((gemm_bf16_kernel<false, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    return hipGetLastError();
+}
+
+}  // namespace dq

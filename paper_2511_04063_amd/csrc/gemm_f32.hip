@@ -1,0 +1,249 @@
+// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32), LDS-staged, double-buffered.
+//
+//   C (M x N) = alpha * op(A) * op(B) + beta * C
+//
+// Workgroup: 256 threads = 4 wavefronts in a 2 x 2 arrangement; workgroup tile 128 x 128, wavefront
+// tile 64 x 64 = 2 x 2 MFMA tiles of 32 x 32; K step 16.  Both operand tiles live in LDS as [k][mn]
+// (mn contiguous), so every MFMA operand fetch is a conflict-free 32-float row segment.
+//
+// MFMA 32x32x2 f32 lane layout (lane l of 64):  A operand a = A[m = l % 32][k = l / 32],
+// B operand b = B[k = l / 32][n = l % 32], accumulator register v (0..15) holds
+// D[m = 8*(v/4) + 4*(l/32) + v%4][n = l % 32].
+//
+// This kernel serves the trailing updates of the blocked Householder QR (Alg. 2 in compact-WY form),
+// the accumulation of the orthogonal factor, the fp32 X @ R / X^T @ dY products and the three products
+// of the derivative through Z = R U (Alg. 1 line 10).
+#include "dq_internal.h"
+
+namespace dq {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LDT = BM + 4;   // LDS row stride in floats (16-byte aligned rows)
+
+struct OperandView {
+    const float* p; long ld;
+    int row_lim, col_lim;   // storage rows / cols that may be read (others read as 0)
+    int vec;                // 16-byte vector loads allowed
+    int unit_lower_cols;    // storage columns < this get the unit-lower-trapezoid treatment (0: none)
+};
+
+__device__ __forceinline__ float4 load4_guarded(const OperandView& o, int sr, int sc) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (sr < o.row_lim) {
+        const float* q = o.p + (long)sr * o.ld + sc;
+        if (o.vec && sc + 3 < o.col_lim) {
+            v = *reinterpret_cast<const float4*>(q);
+        } else {
+            if (sc + 0 < o.col_lim) v.x = q[0];
+            if (sc + 1 < o.col_lim) v.y = q[1];
+            if (sc + 2 < o.col_lim) v.z = q[2];
+            if (sc + 3 < o.col_lim) v.w = q[3];
+        }
+        if (o.unit_lower_cols > 0) {
+            float* e = reinterpret_cast<float*>(&v);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = sc + j;
+                if (c < o.unit_lower_cols && c < o.col_lim) e[j] = (sr > c) ? e[j] : (sr == c ? 1.f : 0.f);
+            }
+        }
+    }
+    return v;
+}
+
+// KC = true : storage is (mn, k) with k contiguous  -> transposing store into LDS [k][mn]
+// KC = false: storage is (k, mn) with mn contiguous -> straight 16-byte store
+template <bool KC>
+__device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0, int tid, float4 (&frag)[2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        if (KC) {
+            const int r = f >> 2, kq = (f & 3) << 2;
+            frag[i] = load4_guarded(o, mn0 + r, k0 + kq);
+        } else {
+            const int kr = f >> 5, c4 = (f & 31) << 2;
+            frag[i] = load4_guarded(o, k0 + kr, mn0 + c4);
+        }
+    }
+}
+
+template <bool KC>
+__device__ __forceinline__ void stash_tile(float (*S)[LDT], int tid, const float4 (&frag)[2]) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        if (KC) {
+            const int r = f >> 2, kq = (f & 3) << 2;
+            S[kq + 0][r] = frag[i].x;
+            S[kq + 1][r] = frag[i].y;
+            S[kq + 2][r] = frag[i].z;
+            S[kq + 3][r] = frag[i].w;
+        } else {
+            const int kr = f >> 5, c4 = (f & 31) << 2;
+            *reinterpret_cast<float4*>(&S[kr][c4]) = frag[i];
+        }
+    }
+}
+
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, int tiles_n, int avec, int bvec) {
+    __shared__ __attribute__((aligned(16))) float As[2][BK][LDT];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDT];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2): give each XCD a
+    // contiguous run of tiles, and walk tiles in groups of 8 tile-rows so a run shares operand panels.
+    const int nt = tiles_m * tiles_n;
+    const int bid = blockIdx.x;
+    const int q8 = nt >> 3, r8 = nt & 7;
+    const int xcd = bid & 7;
+    const int pid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    const int group = 8 * tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * 8;
+    const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int pid_m = first_m + (pid % group) % gsz;
+    const int pid_n = (pid % group) / gsz;
+    const int m0 = pid_m * BM, n0 = pid_n * BN;
+
+    const int z = blockIdx.y;
+    int kb = 0, ke = g.K;
+    if (g.splits > 1) {
+        kb = z * g.kchunk;
+        ke = kb + g.kchunk < g.K ? kb + g.kchunk : g.K;
+    }
+    if (g.b_strict_lower) {
+        const int lo = (n0 / BK) * BK;
+        kb = kb > lo ? kb : lo;
+    }
+
+    OperandView oa, ob;
+    oa.p = g.A; oa.ld = g.lda; oa.vec = avec;
+    oa.unit_lower_cols = g.a_unit_lower ? 0x7fffffff : 0;
+    if (TA) { oa.row_lim = ke; oa.col_lim = g.M; } else { oa.row_lim = g.M; oa.col_lim = ke; }
+    ob.p = g.B; ob.ld = g.ldb; ob.vec = bvec;
+    ob.unit_lower_cols = g.b_unit_lower_cols;
+    if (TB) { ob.row_lim = g.N; ob.col_lim = ke; } else { ob.row_lim = ke; ob.col_lim = g.N; }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    float4 fa[2], fb[2];
+    if (nk > 0) {
+        fetch_tile<!TA>(oa, m0, kb, tid, fa);
+        fetch_tile<TB>(ob, n0, kb, tid, fb);
+        stash_tile<!TA>(As[0], tid, fa);
+        stash_tile<TB>(Bs[0], tid, fb);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            fetch_tile<!TA>(oa, m0, kb + (kt + 1) * BK, tid, fa);
+            fetch_tile<TB>(ob, n0, kb + (kt + 1) * BK, tid, fb);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = As[cur][kk + lk][wm + i * 32 + lrow];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = Bs[cur][kk + lk][wn + j * 32 + lrow];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) {
+            stash_tile<!TA>(As[cur ^ 1], tid, fa);
+            stash_tile<TB>(Bs[cur ^ 1], tid, fb);
+        }
+        __syncthreads();
+    }
+
+    float* C = g.C + (long)z * g.split_stride;
+    const float alpha = g.alpha, beta = g.beta;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                if (row < g.M && col < g.N) {
+                    float* c = C + (long)row * g.ldc + col;
+                    float r = alpha * acc[i][j][v];
+                    if (beta != 0.f) r += beta * *c;
+                    *c = r;
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, long stride,
+                                                            long ldp, int rows, int cols, float alpha, float beta,
+                                                            float* __restrict__ out, long ldo) {
+    const long total = (long)rows * cols;
+    for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long)gridDim.x * blockDim.x) {
+        const int r = (int)(e / cols), c = (int)(e % cols);
+        float s = 0.f;
+        for (int zz = 0; zz < splits; ++zz) s += part[(long)zz * stride + (long)r * ldp + c];
+        float* o = out + (long)r * ldo + c;
+        float v = alpha * s;
+        if (beta != 0.f) v += beta * *o;
+        *o = v;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0) return hipSuccess;
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 3) == 0) ? 1 : 0;
+    const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 3) == 0) ? 1 : 0;
+    dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
+    dim3 block(256, 1, 1);
+    if (g.ta && g.tb)
+        hipLaunchKernelGGL((gemm_f32_kernel<true, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else if (g.ta)
+        hipLaunchKernelGGL((gemm_f32_kernel<true, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else if (g.tb)
+        hipLaunchKernelGGL((gemm_f32_kernel<false, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    else
+        hipLaunchKernelGGL((gemm_f32_kernel<false, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,
+                                float alpha, float beta, float* out, long ldo, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const long total = (long)rows * cols;
+    long blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, splits, stride, ldp,
+                       rows, cols, alpha, beta, out, ldo);
+    return hipGetLastError();
+}
+
+}  // namespace dq

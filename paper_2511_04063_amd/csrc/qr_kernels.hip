@@ -1,0 +1,442 @@
+// Blocked Householder QR pieces (Alg. 2 of the paper's appendix, in LAPACK-style compact-WY form):
+//   * the panel factorisation (one workgroup, panel columns held in registers slice by slice),
+//   * the triangular T factor of a panel's block reflector  H_1 ... H_jb = I - V T V^T,
+//   * the small "reduce split-K partials and multiply by T / T^T" step of a block-reflector application,
+//   * sign normalisation diag(U) >= 0 (the reading that makes R of Sec. 4.3 unique), and small helpers.
+//
+// Reflector convention: H = I - tau v v^T with v[0] = 1 implied, beta = -sign(alpha) ||x||,
+// tau = (beta - alpha) / beta, v[1:] = x[1:] / (alpha - beta).  This is the same reflection as Alg. 2's
+// normalised v = x + sign(x_1)||x|| e_1 (H = I - 2 v v^T / v^T v), stored without the normalisation.
+#include "dq_internal.h"
+
+namespace dq {
+namespace {
+
+// Sum NV per-lane values over the 64 lanes of a wavefront with a halving butterfly: after the call
+// v[0] of every lane holds the wavefront total of the value whose index is returned.  Written as a
+// compile-time recursion so that every register index is static.
+template <int NV, int N, int OFF>
+__device__ __forceinline__ int wave_reduce_stage(float (&v)[NV], int lane) {
+    if constexpr (N > 1) {
+        constexpr int half = N / 2;
+        const bool up = (lane & OFF) != 0;
+#pragma unroll
+        for (int k = 0; k < half; ++k) {
+            const float keep = up ? v[k + half] : v[k];
+            const float send = up ? v[k] : v[k + half];
+            v[k] = keep + __shfl_xor(send, OFF);
+        }
+        return (up ? half : 0) + wave_reduce_stage<NV, half, OFF / 2>(v, lane);
+    } else if constexpr (OFF >= 1) {
+        v[0] += __shfl_xor(v[0], OFF);
+        return wave_reduce_stage<NV, 1, OFF / 2>(v, lane);
+    } else {
+        return 0;
+    }
+}
+template <int NV>
+__device__ __forceinline__ int wave_reduce_multi(float (&v)[NV], int lane) {
+    static_assert(NV >= 1 && NV <= 64 && (NV & (NV - 1)) == 0, "NV must be a power of two <= 64");
+    return wave_reduce_stage<NV, NV, 32>(v, lane);
+}
+
+// One workgroup of NT threads factors an m x jb panel (m <= NT*Q).  The panel is processed in slices of
+// SW columns; thread t keeps rows t, t+NT, ... of the current slice in registers.  Before a slice is
+// factored, the reflector blocks of the earlier slices of the same panel are applied to it
+// (left-looking), reading them back from `Vs`, a packed copy [slice][row][SW] with the unit diagonal and
+// the zeros above it written out.  Every thread re-reads only rows it wrote itself.
+template <int NT, int Q, int SW>
+__global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, long lda, int m, int jb,
+                                                      float* __restrict__ tau, float* Vs, unsigned* flags, int vec) {
+    constexpr int NW = NT / 64;
+    constexpr int MP = NT * Q;
+    constexpr int NV2 = SW * SW;
+    constexpr int NS = kPanel / SW;
+    __shared__ float red[2][NW][NV2];
+    __shared__ float rowd[2][SW];
+    __shared__ float Wsh[NV2];
+    __shared__ __attribute__((aligned(16))) float W2sh[NV2];
+    __shared__ float Tsh[NS][NV2];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ns = (jb + SW - 1) / SW;
+    int par = 0;
+
+    float a[Q][SW];
+
+    for (int s = 0; s < ns; ++s) {
+        const int col0 = s * SW;
+        const int ncs = (jb - col0) < SW ? (jb - col0) : SW;
+
+        // ---- load the slice
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            const int r = tid + NT * i;
+            const float* src = A + (long)r * lda + col0;
+            if (r < m && vec && ncs == SW) {
+#pragma unroll
+                for (int c4 = 0; c4 < SW; c4 += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(src + c4);
+                    a[i][c4 + 0] = t4.x; a[i][c4 + 1] = t4.y; a[i][c4 + 2] = t4.z; a[i][c4 + 3] = t4.w;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < SW; ++c) a[i][c] = (r < m && c < ncs) ? src[c] : 0.f;
+            }
+        }
+
+        // ---- apply the block reflectors of the earlier slices:  A_s -= V_p (T_p^T (V_p^T A_s))
+        for (int p = 0; p < s; ++p) {
+            float v[Q][SW];
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                const int r = tid + NT * i;
+                const float* src = Vs + ((long)p * MP + r) * SW;
+#pragma unroll
+                for (int c4 = 0; c4 < SW; c4 += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(src + c4);
+                    v[i][c4 + 0] = t4.x; v[i][c4 + 1] = t4.y; v[i][c4 + 2] = t4.z; v[i][c4 + 3] = t4.w;
+                }
+            }
+            float wacc[NV2];
+#pragma unroll
+            for (int e = 0; e < NV2; ++e) wacc[e] = 0.f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i)
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp)
+#pragma unroll
+                    for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[i][cp] * a[i][c];
+            const int idx = wave_reduce_multi<NV2>(wacc, lane);
+            if ((lane & (64 / NV2 > 0 ? (64 / NV2 - 1) : 0)) == 0 || NV2 >= 64) red[0][wave][idx] = wacc[0];
+            __syncthreads();
+            if (tid < NV2) {
+                float t = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) t += red[0][w][tid];
+                Wsh[tid] = t;
+            }
+            __syncthreads();
+            if (tid < NV2) {
+                const int cp = tid / SW, c = tid % SW;
+                float t = 0.f;
+                for (int cq = 0; cq <= cp; ++cq) t += Tsh[p][cq * SW + cp] * Wsh[cq * SW + c];
+                W2sh[tid] = t;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int cp = 0; cp < SW; ++cp) {
+#pragma unroll
+                for (int c = 0; c < SW; ++c) {
+                    const float w2 = W2sh[cp * SW + c];
+#pragma unroll
+                    for (int i = 0; i < Q; ++i) a[i][c] -= v[i][cp] * w2;
+                }
+            }
+        }
+
+        // ---- factor the slice column by column
+        float Tl[SW][SW];
+#pragma unroll
+        for (int x = 0; x < SW; ++x)
+#pragma unroll
+            for (int y = 0; y < SW; ++y) Tl[x][y] = 0.f;
+        float tau_l[SW];
+#pragma unroll
+        for (int c = 0; c < SW; ++c) {
+            tau_l[c] = 0.f;
+            if (c < ncs) {   // uniform over the workgroup
+                const int d = col0 + c;
+                float part[SW];
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp) part[cp] = 0.f;
+#pragma unroll
+                for (int i = 0; i < Q; ++i) {
+                    const int r = tid + NT * i;
+                    if (r > d) {
+#pragma unroll
+                        for (int cp = 0; cp < SW; ++cp) part[cp] += a[i][c] * a[i][cp];
+                    } else if (r == d) {
+#pragma unroll
+                        for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[i][cp];
+                    }
+                }
+                const int idx = wave_reduce_multi<SW>(part, lane);
+                if ((lane & (64 / SW - 1)) == 0) red[par][wave][idx] = part[0];
+                __syncthreads();
+                float sd[SW], rd[SW];
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp) {
+                    float t = 0.f;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) t += red[par][w][cp];
+                    sd[cp] = t;
+                    rd[cp] = rowd[par][cp];
+                }
+                par ^= 1;
+
+                const float alpha = rd[c];
+                const float xn2 = sd[c];
+                float beta, tc, scale;
+                if (xn2 == 0.f) {
+                    beta = alpha; tc = 0.f; scale = 0.f;
+                } else {
+                    const float nrm = sqrtf(alpha * alpha + xn2);
+                    beta = alpha >= 0.f ? -nrm : nrm;
+                    tc = (beta - alpha) / beta;
+                    scale = 1.f / (alpha - beta);
+                }
+                if (tid == 0) {
+                    if (!(fabsf(beta) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+                    else if (beta == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+                }
+                tau_l[c] = tc;
+                float w[SW];
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp) w[cp] = tc * (rd[cp] + scale * sd[cp]);
+#pragma unroll
+                for (int i = 0; i < Q; ++i) {
+                    const int r = tid + NT * i;
+                    if (r > d) {
+                        const float vn = a[i][c] * scale;
+#pragma unroll
+                        for (int cp = c + 1; cp < SW; ++cp) a[i][cp] -= w[cp] * vn;
+                        a[i][c] = vn;
+                    } else if (r == d) {
+#pragma unroll
+                        for (int cp = c + 1; cp < SW; ++cp) a[i][cp] -= w[cp];
+                        a[i][c] = beta;
+                    }
+                }
+                // column c of the slice's T:  T[0:c, c] = -tau * T[0:c, 0:c] * (V[:, 0:c]^T v_c),  T[c, c] = tau
+                Tl[c][c] = tc;
+#pragma unroll
+                for (int cp = 0; cp < c; ++cp) {
+                    float t = 0.f;
+#pragma unroll
+                    for (int cq = cp; cq < c; ++cq) t += Tl[cp][cq] * (rd[cq] + scale * sd[cq]);
+                    Tl[cp][c] = -tc * t;
+                }
+            }
+        }
+
+        // ---- store: in place (triangular factor on/above the diagonal, reflectors below) and the packed copy
+        if (tid == 0) {
+#pragma unroll
+            for (int x = 0; x < SW; ++x)
+#pragma unroll
+                for (int y = 0; y < SW; ++y) Tsh[s][x * SW + y] = Tl[x][y];
+#pragma unroll
+            for (int c = 0; c < SW; ++c)
+                if (c < ncs) tau[col0 + c] = tau_l[c];
+        }
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            const int r = tid + NT * i;
+            float* dst = A + (long)r * lda + col0;
+            float pv[SW];
+#pragma unroll
+            for (int c = 0; c < SW; ++c) {
+                const int d = col0 + c;
+                pv[c] = (r < m && c < ncs) ? (r > d ? a[i][c] : (r == d ? 1.f : 0.f)) : 0.f;
+            }
+            if (r < m) {
+                if (vec && ncs == SW) {
+#pragma unroll
+                    for (int c4 = 0; c4 < SW; c4 += 4)
+                        *reinterpret_cast<float4*>(dst + c4) = make_float4(a[i][c4], a[i][c4 + 1], a[i][c4 + 2], a[i][c4 + 3]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < SW; ++c)
+                        if (c < ncs) dst[c] = a[i][c];
+                }
+            }
+            float* vdst = Vs + ((long)s * MP + r) * SW;
+#pragma unroll
+            for (int c4 = 0; c4 < SW; c4 += 4)
+                *reinterpret_cast<float4*>(vdst + c4) = make_float4(pv[c4], pv[c4 + 1], pv[c4 + 2], pv[c4 + 3]);
+        }
+        __syncthreads();
+    }
+}
+
+// T factor of a panel from the Gram matrix of its reflectors (forward, columnwise):
+//   T[j][j] = tau_j,   T[0:j, j] = -tau_j * T[0:j, 0:j] * G[0:j, j],   G = V^T V.
+// Thread i owns row i of T and reads only its own row, so no synchronisation is needed after the load.
+__global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
+                                                      long ldp, int jb, const float* __restrict__ tau,
+                                                      float* __restrict__ Tout) {
+    __shared__ float Gs[kPanel][kPanel + 1];
+    __shared__ float Ts[kPanel][kPanel + 1];
+    __shared__ float taus[kPanel];
+    const int tid = threadIdx.x;
+    for (int e = tid; e < kPanel * kPanel; e += 256) {
+        const int i = e / kPanel, j = e % kPanel;
+        float t = 0.f;
+        if (i < jb && j < jb)
+            for (int z = 0; z < splits; ++z) t += gpart[(long)z * stride + (long)i * ldp + j];
+        Gs[i][j] = t;
+        Ts[i][j] = 0.f;
+    }
+    if (tid < kPanel) taus[tid] = tid < jb ? tau[tid] : 0.f;
+    __syncthreads();
+    if (tid < jb) {
+        const int i = tid;
+        for (int j = i; j < jb; ++j) {
+            if (j == i) {
+                Ts[i][j] = taus[j];
+            } else {
+                float acc = 0.f;
+                for (int l = i; l < j; ++l) acc += Ts[i][l] * Gs[l][j];
+                Ts[i][j] = -taus[j] * acc;
+            }
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < kPanel * kPanel; e += 256) Tout[e] = Ts[e / kPanel][e % kPanel];
+}
+
+// W2[:, chunk] = op(T) * sum_z part[z][:, col0 + chunk], one workgroup per 64 columns.
+__global__ __launch_bounds__(256) void wreduce_T_kernel(const float* __restrict__ part, int splits, long stride,
+                                                        long ldp, int col0, int jb, int nc,
+                                                        const float* __restrict__ T, int transT,
+                                                        float* __restrict__ W2, long ldw2) {
+    __shared__ float Ts[kPanel][kPanel + 1];   // Ts[r][l] = op(T)[r][l]
+    __shared__ float Ws[kPanel][kPanel + 1];
+    const int tid = threadIdx.x;
+    const int c0 = blockIdx.x * 64;
+    for (int e = tid; e < kPanel * kPanel; e += 256) {
+        const int i = e / kPanel, j = e % kPanel;
+        const float t = T[e];
+        if (transT) Ts[j][i] = t; else Ts[i][j] = t;
+        float w = 0.f;
+        if (i < jb && c0 + j < nc)
+            for (int z = 0; z < splits; ++z) w += part[(long)z * stride + (long)i * ldp + col0 + c0 + j];
+        Ws[i][j] = w;
+    }
+    __syncthreads();
+    const int c = tid & 63, rg = tid >> 6;
+    if (c0 + c < nc) {
+        for (int rr = 0; rr < 16; ++rr) {
+            const int r = rg * 16 + rr;
+            if (r >= jb) break;
+            float acc = 0.f;
+            // op(T) is lower triangular when transposed, upper otherwise; the other half is stored as zeros
+            const int lb = transT ? 0 : r, le = transT ? r + 1 : jb;
+            for (int l = lb; l < le; ++l) acc += Ts[r][l] * Ws[l][c];
+            W2[(long)r * ldw2 + c0 + c] = acc;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void copy2d_kernel(const float* __restrict__ src, long lds, float* __restrict__ dst,
+                                                     long ldd, int rows, int cols) {
+    const long total = (long)rows * cols;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / cols), c = (int)(e % cols);
+        dst[(long)r * ldd + c] = src[(long)r * lds + c];
+    }
+}
+
+__global__ __launch_bounds__(256) void identity_kernel(float* __restrict__ A, long lda, int n) {
+    const long total = (long)n * n;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / n), c = (int)(e % n);
+        A[(long)r * lda + c] = (r == c) ? 1.f : 0.f;
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(unsigned* p, long count, unsigned v) {
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < count; e += (long)gridDim.x * 256) p[e] = v;
+}
+
+// s_j = +1 if Afac[j][j] >= 0 else -1;  R[:, j] *= s_j;  U[i][j] = s_i * Afac[i][j] for j >= i, else 0.
+__global__ __launch_bounds__(256) void sign_normalise_kernel(const float* __restrict__ Afac, long lda, int n,
+                                                             float* __restrict__ R, long ldr, float* __restrict__ U,
+                                                             long ldu, unsigned* flags) {
+    const long total = (long)n * n;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / n), c = (int)(e % n);
+        const float dc = Afac[(long)c * lda + c];
+        const float sc = dc >= 0.f ? 1.f : -1.f;
+        R[(long)r * ldr + c] *= sc;
+        if (U != nullptr) {
+            const float dr = Afac[(long)r * lda + r];
+            const float sr = dr >= 0.f ? 1.f : -1.f;
+            U[(long)r * ldu + c] = (c >= r) ? sr * Afac[(long)r * lda + c] : 0.f;
+        }
+        if (r == c) {
+            if (!(fabsf(dc) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+            else if (dc == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        }
+    }
+}
+
+inline unsigned grid_for(long total) {
+    long b = (total + 255) / 256;
+    if (b > 8192) b = 8192;
+    if (b < 1) b = 1;
+    return (unsigned)b;
+}
+
+}  // namespace
+
+size_t panel_scratch_floats(int /*m*/) { return (size_t)kPanel * 8192; }
+
+hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, unsigned* flags,
+                           hipStream_t s) {
+    if (m <= 0 || jb <= 0) return hipSuccess;
+    if (m > 8192 || jb > kPanel || jb > m) return hipErrorInvalidValue;
+    const int vec = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0) ? 1 : 0;
+    constexpr int NT = 512;
+#define DQ_PANEL(Q, SW) hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, flags, vec)
+    if (m <= NT * 1) DQ_PANEL(1, 8);
+    else if (m <= NT * 2) DQ_PANEL(2, 8);
+    else if (m <= NT * 4) DQ_PANEL(4, 8);
+    else if (m <= NT * 8) DQ_PANEL(8, 8);
+    else DQ_PANEL(16, 4);
+#undef DQ_PANEL
+    return hipGetLastError();
+}
+
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tau,
+                          float* Tout, hipStream_t s) {
+    hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(256), 0, s, gpart, splits, stride, ldp, jb, tau, Tout);
+    return hipGetLastError();
+}
+
+hipError_t launch_wreduce_T(const float* part, int splits, long stride, long ldp, int col0, int jb, int nc,
+                            const float* T, int transT, float* W2, long ldw2, hipStream_t s) {
+    if (nc <= 0) return hipSuccess;
+    hipLaunchKernelGGL(wreduce_T_kernel, dim3((nc + 63) / 64), dim3(256), 0, s, part, splits, stride, ldp, col0, jb, nc,
+                       T, transT, W2, ldw2);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(copy2d_kernel, dim3(grid_for((long)rows * cols)), dim3(256), 0, s, src, lds, dst, ldd, rows, cols);
+    return hipGetLastError();
+}
+
+hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s) {
+    hipLaunchKernelGGL(identity_kernel, dim3(grid_for((long)n * n)), dim3(256), 0, s, A, lda, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(unsigned* p, long count, unsigned v, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(count)), dim3(256), 0, s, p, count, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_sign_normalise(const float* Afac, long lda, int n, float* R, long ldr, float* U, long ldu,
+                                 unsigned* flags, hipStream_t s) {
+    hipLaunchKernelGGL(sign_normalise_kernel, dim3(grid_for((long)n * n)), dim3(256), 0, s, Afac, lda, n, R, ldr, U,
+                       ldu, flags);
+    return hipGetLastError();
+}
+
+}  // namespace dq

@@ -1,0 +1,372 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element on the
+same seeded inputs.  Tolerances (norm-wise relative error unless stated):
+  fp32 loss and dZ <= 1e-4;  max|R^T R - I| <= 1e-5;  bf16-input GEMM outputs <= 2e-2.
+"""
+
+import json
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import dartqr_oracle as orc  # noqa: E402
+from paper_2511_04063_amd import binding as B  # noqa: E402
+from paper_2511_04063_amd import synth  # noqa: E402
+
+
+def rel(a, ref):
+    a = np.asarray(a, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(a - ref) / (den if den > 0 else 1.0))
+
+
+def rng(seed):
+    return np.random.Generator(np.random.Philox(seed))
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def padded(rows, cols, ld, dtype=torch.float32, fill=float("nan")):
+    """A (rows x cols) view with leading dimension ld inside a NaN-filled buffer."""
+    buf = torch.full((rows, ld), fill, dtype=dtype, device="cuda")
+    return buf, buf[:, :cols]
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = B.Context()
+    c.ensure_workspace(1, 1100, 4096, B.DQ_BF16)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+# ----------------------------------------------------------------------------------- GEMM kernels
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 150), (129, 257, 17), (64, 500, 1000), (1, 1, 1)])
+def test_gemm_f32(ctx, ta, tb, M, N, K):
+    g = rng(1000 + 7 * M + N + K + 2 * ta + tb)
+    A = g.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
+    Bm = g.standard_normal((N, K) if tb else (K, N)).astype(np.float32)
+    C0 = g.standard_normal((M, N)).astype(np.float32)
+    lda = -(-A.shape[1] // 4) * 4 + 4
+    ldb = -(-Bm.shape[1] // 4) * 4
+    ldc = -(-N // 4) * 4 + 8
+    _, Ad = padded(A.shape[0], A.shape[1], lda); Ad.copy_(dev(A))
+    _, Bd = padded(Bm.shape[0], Bm.shape[1], ldb); Bd.copy_(dev(Bm))
+    Cbuf, Cd = padded(M, N, ldc, fill=123.0); Cd.copy_(dev(C0))
+    ctx.dq_gemm_f32(M, N, K, 0.5, Ad, ta, Bd, tb, -2.0, Cd)
+    opA = A.T.astype(np.float64) if ta else A.astype(np.float64)
+    opB = Bm.T.astype(np.float64) if tb else Bm.astype(np.float64)
+    ref = 0.5 * (opA @ opB) - 2.0 * C0
+    got = Cd.cpu().numpy()
+    assert rel(got, ref) < 2e-6
+    assert np.abs(got - ref).max() < 2e-5 * max(1.0, np.abs(ref).max())
+    # the padding columns of C were not touched
+    assert torch.all(Cbuf[:, N:] == 123.0)
+
+
+@pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0), (0, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 160), (130, 258, 40), (72, 136, 1000)])
+def test_gemm_bf16(ctx, ta, tb, M, N, K):
+    g = rng(2000 + 7 * M + N + K + 2 * ta + tb)
+    A = synth.round_to_bf16(g.standard_normal((K, M) if ta else (M, K)).astype(np.float32))
+    Bm = synth.round_to_bf16(g.standard_normal((N, K) if tb else (K, N)).astype(np.float32))
+    lda = -(-A.shape[1] // 8) * 8 + 8
+    ldb = -(-Bm.shape[1] // 8) * 8
+    ldc = -(-N // 4) * 4
+    _, Ad = padded(A.shape[0], A.shape[1], lda, torch.bfloat16); Ad.copy_(dev(A, torch.bfloat16))
+    _, Bd = padded(Bm.shape[0], Bm.shape[1], ldb, torch.bfloat16); Bd.copy_(dev(Bm, torch.bfloat16))
+    _, Cd = padded(M, N, ldc)
+    ctx.dq_gemm_bf16(M, N, K, Ad, ta, Bd, tb, Cd)
+    opA = A.T.astype(np.float64) if ta else A.astype(np.float64)
+    opB = Bm.T.astype(np.float64) if tb else Bm.astype(np.float64)
+    ref = opA @ opB
+    # inputs are exact bf16, products exact in fp32, fp32 accumulation: far inside the 2e-2 bar
+    assert rel(Cd.cpu().numpy(), ref) < 1e-5
+
+
+# ----------------------------------------------------------------------------------- Whip pass
+@pytest.mark.parametrize("T,n,ldy", [(37, 101, 104), (64, 256, 256), (5, 3, 8), (1, 1, 4)])
+@pytest.mark.parametrize("mode", ["mean", "sum"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_whip_loss_grad(ctx, T, n, ldy, mode, bf16):
+    g = rng(3000 + T + n)
+    Y = (g.standard_t(3.0, size=(T, n)) * 2.0).astype(np.float32)
+    Y[0, 0] = 0.0
+    _, Yd = padded(T, n, ldy); Yd.copy_(dev(Y))
+    lddy = -(-n // 8) * 8
+    _, dYd = padded(T, n, lddy, torch.bfloat16 if bf16 else torch.float32)
+    loss = torch.zeros(1, device="cuda")
+    red = B.DQ_REDUCE_TOKEN_MEAN if mode == "mean" else B.DQ_REDUCE_SUM
+    ctx.dq_whip_loss_grad(Yd, red, loss, dYd, B.DQ_BF16 if bf16 else B.DQ_F32)
+    ref_loss = orc.whip_loss(Y, mode)
+    ref_dY = orc.whip_grad(Y, mode)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+    got = dYd.float().cpu().numpy()
+    assert got[0, 0] == 0.0
+    assert rel(got, ref_dY) < (4e-3 if bf16 else 2e-6)
+    if bf16:   # the decision "which bf16" is taken from the fp32 value on both sides
+        assert np.abs(got - synth.round_to_bf16(ref_dY.astype(np.float32))).max() <= np.abs(ref_dY).max() * 2.0 ** -8
+
+
+def test_whip_closed_forms(ctx):
+    T, n = 16, 24
+    Yd = torch.zeros((T, n), device="cuda")
+    dYd = torch.ones((T, n), device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    ctx.dq_whip_loss_grad(Yd, B.DQ_REDUCE_TOKEN_MEAN, loss, dYd, B.DQ_F32)
+    assert loss.item() == pytest.approx(n, rel=1e-6)       # Whip of a zero vector is its length
+    assert torch.all(dYd == 0)
+
+
+# ----------------------------------------------------------------------------------- QR-Orth
+def run_qr(ctx, Z, want_u=True, ld=None):
+    n = Z.shape[-1]
+    ld = ld or -(-n // 4) * 4
+    _, Zd = padded(n, n, ld); Zd.copy_(dev(Z.astype(np.float32)))
+    _, Rd = padded(n, n, ld)
+    Ud = None
+    if want_u:
+        _, Ud = padded(n, n, ld)
+    ctx.dq_qr_orth(Zd, Rd, Ud)
+    return Rd.cpu().numpy(), (Ud.cpu().numpy() if want_u else None)
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 63, 64, 65, 100, 256, 520, 1030])
+def test_qr_orth_against_oracle(ctx, n):
+    Z = rng(4000 + n).standard_normal((n, n)).astype(np.float32)
+    R, U = run_qr(ctx, Z)
+    Ro, Uo = orc.qr_orth(Z)
+    assert np.abs(R.astype(np.float64).T @ R - np.eye(n)).max() <= 1e-5
+    assert np.all(np.tril(U, -1) == 0.0)
+    assert np.all(np.diag(U) > 0.0)
+    assert rel(R.astype(np.float64) @ U, Z) < 1e-5
+    assert rel(U, Uo) < 1e-4
+    # R is only as well determined as Z is well conditioned
+    cond = np.linalg.cond(Z.astype(np.float64))
+    assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+    assert ctx.dq_device_flags() == 0
+
+
+def test_qr_orth_without_u_and_with_wide_ld(ctx):
+    n = 200
+    Z = rng(4100).standard_normal((n, n)).astype(np.float32)
+    R1, _ = run_qr(ctx, Z, want_u=False, ld=264)
+    Ro, _ = orc.qr_orth(Z)
+    assert rel(R1, Ro) < 1e-4
+
+
+def test_qr_orth_closed_forms(ctx):
+    n = 128
+    # orthogonal input (Sylvester Hadamard / sqrt(n), the paper's initial latent): R = Z, U = I
+    H = np.array([[1.0]])
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    H = (H / np.sqrt(n)).astype(np.float32)
+    R, U = run_qr(ctx, H)
+    assert np.abs(R - H).max() < 2e-6 and np.abs(U - np.eye(n)).max() < 2e-6
+    # upper-triangular input with positive diagonal: R = I, U = Z
+    g = rng(4200)
+    Zt = np.triu(g.standard_normal((n, n))).astype(np.float32)
+    Zt[np.arange(n), np.arange(n)] = np.abs(np.diag(Zt)) + 0.5
+    R, U = run_qr(ctx, Zt)
+    assert np.array_equal(R, np.eye(n, dtype=np.float32)) and np.array_equal(U, Zt)
+    # diagonal input: R = diag(sign d), U = diag(|d|)
+    d = g.standard_normal(n).astype(np.float32)
+    R, U = run_qr(ctx, np.diag(d))
+    assert np.array_equal(R, np.diag(np.sign(d))) and np.array_equal(U, np.diag(np.abs(d)))
+    assert ctx.dq_device_flags() == 0
+
+
+def test_singular_latent_raises_flag_not_fault(ctx):
+    n = 96
+    Z = rng(4300).standard_normal((n, n)).astype(np.float32)
+    Z[:, 40] = 0.0
+    run_qr(ctx, Z)
+    assert ctx.dq_device_flags() & B.DQ_FLAG_SINGULAR
+    assert ctx.dq_device_flags() == 0          # reading clears the word
+
+
+# ----------------------------------------------------------------------------------- rotate + loss + G
+@pytest.mark.parametrize("T,n,bf16", [(300, 200, False), (1000, 256, False), (300, 200, True), (2048, 520, True),
+                                      (40, 1030, True)])
+def test_rotate_loss_grad(ctx, T, n, bf16):
+    cfg = synth.scaled_config("7b", n=n, T=T, x_dtype="bf16" if bf16 else "f32")
+    inp = synth.make_inputs(cfg, seed=5)
+    X = inp["X"][0]
+    R, _ = orc.qr_orth(inp["Z0"][0])
+    R32 = R.astype(np.float32)
+    ldx = -(-n // 8) * 8
+    _, Xd = padded(T, n, ldx, torch.bfloat16 if bf16 else torch.float32)
+    Xd.copy_(dev(X, torch.bfloat16 if bf16 else None))
+    Rd = dev(R32) if n % 4 == 0 else None
+    if Rd is None:
+        _, Rd = padded(n, n, -(-n // 4) * 4); Rd.copy_(dev(R32))
+    ld4 = -(-n // 4) * 4
+    _, Gd = padded(n, n, ld4)
+    _, Yd = padded(T, n, ld4)
+    _, dYd = padded(T, n, ldx, torch.bfloat16 if bf16 else torch.float32)
+    loss = torch.zeros(1, device="cuda")
+    ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16 if bf16 else B.DQ_F32, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd, Yd, dYd)
+    lo, Go, Yo, dYo = orc.rotate_loss_grad(X, R32)
+    tol = 2e-2 if bf16 else 1e-4
+    assert rel(Yd.cpu().numpy(), Yo) < (2e-2 if bf16 else 1e-5)
+    assert abs(loss.item() - lo) <= 1e-4 * lo
+    assert rel(dYd.float().cpu().numpy(), dYo) < tol
+    assert rel(Gd.cpu().numpy(), Go) < tol
+    # same call without the optional outputs gives the same loss and G
+    _, G2 = padded(n, n, ld4)
+    loss2 = torch.zeros(1, device="cuda")
+    ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16 if bf16 else B.DQ_F32, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss2, G2)
+    assert loss2.item() == loss.item()
+    assert torch.equal(G2, Gd)
+
+
+# ----------------------------------------------------------------------------------- QR backward
+@pytest.mark.parametrize("n", [1, 2, 7, 100, 128, 129, 300, 700])
+def test_qr_backward_stage(ctx, n):
+    g = rng(5000 + n)
+    Z = g.standard_normal((n, n))
+    R, U = orc.qr_orth(Z)
+    G = g.standard_normal((n, n))
+    R32, U32, G32 = (a.astype(np.float32) for a in (R, U, G))
+    ld = -(-n // 4) * 4
+    bufs = []
+    for a in (R32, U32, G32):
+        _, d = padded(n, n, ld); d.copy_(dev(a)); bufs.append(d)
+    _, dZd = padded(n, n, ld)
+    ctx.dq_qr_backward(bufs[0], bufs[1], bufs[2], dZd)
+    ref = orc.qr_backward(R32, U32, G32)
+    assert rel(dZd.cpu().numpy(), ref) < 1e-4
+    assert ctx.dq_device_flags() == 0
+
+
+def test_sgd_update(ctx):
+    n = 77
+    g = rng(5100)
+    Z = g.standard_normal((n, n)).astype(np.float32)
+    D = g.standard_normal((n, n)).astype(np.float32)
+    _, Zd = padded(n, n, 80); Zd.copy_(dev(Z))
+    _, Dd = padded(n, n, 84); Dd.copy_(dev(D))
+    ctx.dq_sgd_update(Zd, Dd, 0.25)
+    assert np.abs(Zd.cpu().numpy() - orc.sgd_update(Z, D, 0.25)).max() < 1e-6
+
+
+# ----------------------------------------------------------------------------------- whole step
+def test_calib_step_tiny_trajectory(ctx):
+    inp = synth.make_inputs("tiny")
+    cfg = inp["cfg"]
+    X = inp["X"][0]
+    Xd = dev(X)
+    Zd = dev(inp["Z0"][0].copy())
+    loss = torch.zeros(1, device="cuda")
+    Rd = torch.empty((cfg.n, cfg.n), device="cuda")
+    with open(os.path.join(os.path.dirname(__file__), "golden", "tiny_trajectory.json")) as f:
+        gold = json.load(f)
+    Zo = inp["Z0"][0].astype(np.float64)
+    for k in range(cfg.steps):
+        Zin = Zd.cpu().numpy().astype(np.float64)
+        ctx.dq_calib_step(Xd, B.DQ_F32, Zd, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss, Rd)
+        # the stored fp64 trajectory
+        assert abs(loss.item() - gold["losses"][k]) <= 1e-4 * gold["losses"][k]
+        # one step from the GPU's own input latent, against the oracle
+        out = orc.calib_step(X, Zin, cfg.lr)
+        assert abs(loss.item() - out["loss"]) <= 1e-4 * out["loss"]
+        dZ_gpu = (Zin - Zd.cpu().numpy().astype(np.float64)) / cfg.lr
+        assert rel(dZ_gpu, out["dZ"]) < 1e-4
+        R = Rd.cpu().numpy().astype(np.float64)
+        assert np.abs(R.T @ R - np.eye(cfg.n)).max() <= 1e-5
+        assert rel(R, out["R"]) < 1e-4
+        Zo = orc.calib_step(X, Zo, cfg.lr)["Z_new"]
+    assert rel(Zd.cpu().numpy(), Zo) < 1e-5
+    assert abs(np.linalg.norm(Zd.cpu().numpy().astype(np.float64)) - gold["Z_final_fro"]) < 1e-5 * gold["Z_final_fro"]
+    assert ctx.dq_device_flags() == 0
+
+
+def test_calib_step_bf16_small(ctx):
+    cfg = synth.scaled_config("7b", n=384, T=1024)
+    inp = synth.make_inputs(cfg, seed=9)
+    X, Z0 = inp["X"][0], inp["Z0"][0]
+    Xd = dev(X, torch.bfloat16)
+    Zd = dev(Z0.copy())
+    loss = torch.zeros(1, device="cuda")
+    ctx.dq_calib_step(Xd, B.DQ_BF16, Zd, 1e-2, B.DQ_REDUCE_TOKEN_MEAN, loss)
+    out = orc.calib_step(X, Z0, 1e-2)
+    assert abs(loss.item() - out["loss"]) <= 1e-4 * out["loss"]
+    dZ_gpu = (Z0.astype(np.float64) - Zd.cpu().numpy().astype(np.float64)) / 1e-2
+    assert rel(dZ_gpu, out["dZ"]) < 2e-2     # bf16 X, R and dY on the matrix cores
+    # structural identities of the true gradient hold for what the GPU applied
+    Z64 = Z0.astype(np.float64)
+    assert np.abs(np.triu(Z64.T @ dZ_gpu)).max() < 1e-3 * np.linalg.norm(Z64, 2) * np.abs(dZ_gpu).max()
+    assert np.abs(dZ_gpu[:, -1]).max() < 1e-3 * np.abs(dZ_gpu).max()
+
+
+def test_batched_heads_like(ctx):
+    cfg = synth.scaled_config("heads", b=3, T=512)
+    inp = synth.make_inputs(cfg, seed=2)
+    X, Z0 = inp["X"], inp["Z0"]
+    Xd = dev(X, torch.bfloat16)
+    Zd = dev(Z0.copy())
+    loss = torch.zeros(3, device="cuda")
+    Rd = torch.empty((3, 128, 128), device="cuda")
+    ctx.dq_calib_step(Xd, B.DQ_BF16, Zd, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, loss, Rd)
+    for i in range(3):
+        out = orc.calib_step(X[i], Z0[i], 1e-3)
+        assert abs(loss[i].item() - out["loss"]) <= 1e-4 * out["loss"]
+        assert rel(Rd[i].cpu().numpy(), out["R"]) < 1e-4
+        dZ_gpu = (Z0[i].astype(np.float64) - Zd[i].cpu().numpy().astype(np.float64)) / 1e-3
+        assert rel(dZ_gpu, out["dZ"]) < 2e-2
+    # a batch equals its problems run one by one
+    Z1 = dev(Z0[1].copy())
+    l1 = torch.zeros(1, device="cuda")
+    ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z1, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l1)
+    assert torch.equal(Z1, Zd[1]) and l1.item() == loss[1].item()
+
+
+# ----------------------------------------------------------------------------------- error paths
+def test_errors_have_no_effect(ctx):
+    n = 64
+    Z = torch.randn(n, n, device="cuda")
+    R = torch.full((n, n), 7.0, device="cuda")
+    lib, h = ctx.lib, ctx.h
+    # misaligned pointer
+    assert lib.dq_qr_orth(h, 1, n, Z.data_ptr() + 4, n, R.data_ptr(), n, None, 0) == B.DQ_ERR_ALIGN
+    # leading dimension too small / not a multiple of 4
+    assert lib.dq_qr_orth(h, 1, n, Z.data_ptr(), n - 4, R.data_ptr(), n, None, 0) == B.DQ_ERR_SHAPE
+    assert lib.dq_qr_orth(h, 1, 62, Z.data_ptr(), 62, R.data_ptr(), 64, None, 0) == B.DQ_ERR_ALIGN
+    assert lib.dq_qr_orth(h, 1, 0, Z.data_ptr(), n, R.data_ptr(), n, None, 0) == B.DQ_ERR_SHAPE
+    assert lib.dq_qr_orth(h, 1, B.DQ_MAX_N + 8, Z.data_ptr(), 8200, R.data_ptr(), 8200, None, 0) == B.DQ_ERR_UNSUPPORTED
+    assert lib.dq_qr_orth(h, 1, n, None, n, R.data_ptr(), n, None, 0) == B.DQ_ERR_NULL
+    # bad enum values
+    loss = torch.zeros(1, device="cuda")
+    X = torch.randn(16, n, device="cuda")
+    G = torch.full((n, n), 7.0, device="cuda")
+    assert lib.dq_rotate_loss_grad(h, 1, 16, n, X.data_ptr(), 5, n, Z.data_ptr(), n, 0, loss.data_ptr(), G.data_ptr(),
+                                   n, None, 0, None, 0) == B.DQ_ERR_DTYPE
+    assert lib.dq_rotate_loss_grad(h, 1, 16, n, X.data_ptr(), 0, n, Z.data_ptr(), n, 9, loss.data_ptr(), G.data_ptr(),
+                                   n, None, 0, None, 0) == B.DQ_ERR_DTYPE
+    # workspace too small for a large problem
+    c2 = B.Context()
+    small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    c2.dq_set_workspace(small)
+    assert c2.lib.dq_qr_orth(c2.h, 1, 1024, Z.data_ptr(), 1024, R.data_ptr(), 1024, None, 0) == B.DQ_ERR_WORKSPACE
+    c3 = B.Context()
+    assert c3.lib.dq_qr_orth(c3.h, 1, n, Z.data_ptr(), n, R.data_ptr(), n, None, 0) == B.DQ_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(R == 7.0) and torch.all(G == 7.0) and loss.item() == 0.0
+    # b == 0 is a no-op
+    assert lib.dq_qr_orth(h, 0, n, Z.data_ptr(), n, R.data_ptr(), n, None, 0) == B.DQ_OK
+    torch.cuda.synchronize()
+    assert torch.all(R == 7.0)
+    c2.close(); c3.close()

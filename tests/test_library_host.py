@@ -1,0 +1,82 @@
+"""Host-side checks of libdartqr.so that need no GPU: it loads, exports every entry point that
+include/dartqr.h declares, and its argument checks refuse bad calls before anything is launched."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_04063_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2511_04063_amd.build import build_library
+        build_library(verbose=False)
+    return B.load_library()
+
+
+def declared_entry_points():
+    text = open(os.path.join(ROOT, "include", "dartqr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported_and_bound(lib):
+    names = declared_entry_points()
+    assert {"dq_qr_orth", "dq_rotate_loss_grad", "dq_calib_step"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in dartqr.h but not exported"
+        assert name in B.SIGNATURES, f"{name} has no binding"
+    assert sorted(B.SIGNATURES) == names
+
+
+def test_status_strings(lib):
+    seen = {B.status_string(s) for s in range(0, 8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert B.status_string(99) == "unknown status"
+
+
+def test_workspace_bytes_rules(lib):
+    small = B.workspace_bytes(1, 256, 2048, B.DQ_F32)
+    big = B.workspace_bytes(1, 4096, 8192, B.DQ_BF16)
+    assert 0 < small < big
+    assert small % 256 == 0
+    # batches run one after another: the workspace does not grow with b
+    assert B.workspace_bytes(64, 128, 16384, B.DQ_BF16) == B.workspace_bytes(1, 128, 16384, B.DQ_BF16)
+    # the 70B-shaped problem fits comfortably in one GPU's HBM
+    assert B.workspace_bytes(1, 8192, 16384, B.DQ_BF16) < 8 * 2 ** 30
+    out = ctypes.c_size_t(0)
+    assert lib.dq_workspace_bytes(1, 0, 16, B.DQ_F32, ctypes.byref(out)) == B.DQ_ERR_SHAPE
+    assert lib.dq_workspace_bytes(1, B.DQ_MAX_N + 1, 16, B.DQ_F32, ctypes.byref(out)) == B.DQ_ERR_UNSUPPORTED
+    assert lib.dq_workspace_bytes(1, 16, 0, B.DQ_F32, ctypes.byref(out)) == B.DQ_ERR_SHAPE
+    assert lib.dq_workspace_bytes(-1, 16, 16, B.DQ_F32, ctypes.byref(out)) == B.DQ_ERR_SHAPE
+    assert lib.dq_workspace_bytes(1, 16, 16, 7, ctypes.byref(out)) == B.DQ_ERR_DTYPE
+    assert lib.dq_workspace_bytes(1, 16, 16, B.DQ_F32, None) == B.DQ_ERR_NULL
+
+
+def test_null_context_is_refused_everywhere(lib):
+    z = ctypes.c_void_p(0)
+    assert lib.dq_destroy(z) == B.DQ_ERR_NULL
+    assert lib.dq_set_workspace(z, z, 0) == B.DQ_ERR_NULL
+    assert lib.dq_device_flags(z, None) == B.DQ_ERR_NULL
+    assert lib.dq_qr_orth(z, 1, 8, z, 8, z, 8, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_rotate_loss_grad(z, 1, 8, 8, z, 0, 8, z, 8, 0, z, z, 8, z, 8, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_calib_step(z, 1, 8, 8, z, 0, 8, z, 8, 0.1, 0, z, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_qr_backward(z, 1, 8, z, 8, z, 8, z, 8, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_whip_loss_grad(z, 1, 8, 8, z, 8, 0, z, z, 0, 8) == B.DQ_ERR_NULL
+    assert lib.dq_sgd_update(z, 1, 8, z, 8, z, 8, 0.1) == B.DQ_ERR_NULL
+    assert lib.dq_gemm_f32(z, 8, 8, 8, 1.0, z, 8, 0, z, 8, 0, 0.0, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_gemm_bf16(z, 8, 8, 8, z, 8, 0, z, 8, 0, z, 8) == B.DQ_ERR_NULL
+    assert lib.dq_profile_enable(z, 1) == B.DQ_ERR_NULL
+    assert lib.dq_profile_read(z, 0, None, None, None, None) == B.DQ_ERR_NULL
+    assert lib.dq_create(None, z) == B.DQ_ERR_NULL
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.load_library(str(tmp_path / "libdartqr.so"))
