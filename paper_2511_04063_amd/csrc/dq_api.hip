@@ -91,7 +91,7 @@ Layout make_layout(int n, int T) {
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
     L.Y = bump(cur, tn * 4);
     L.dY = bump(cur, tn * 4);
-    L.rbt = bump(cur, n2 * 2);
+    L.rbt = bump(cur, (size_t)n * 2 * round_up(n, 32) * 2);
     L.losspart = bump(cur, (size_t)kLossPartials * 8);
     L.gsplit_floats = (size_t)kMaxSplit * n2;
     if (L.gsplit_floats > ((size_t)16 << 20)) L.gsplit_floats = (size_t)16 << 20;
@@ -266,14 +266,18 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
     // S3: Y = X @ R
     if (xdt == DQ_BF16) {
         bf16_t* rbt = at<bf16_t>(c, L.rbt);
+        // R enters the bf16 matrix cores as two planes, R = hi + lo (16 mantissa bits), so that the rotation
+        // keeps close to fp32 accuracy: Y = X @ hi + X @ lo in one pass over the accumulators.
+        const int koff = (int)round_up(n, 32);
         {
-            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 6.0 * n * (double)n);
-            DQ_HIP(launch_convert_transpose_bf16(R, ldr, n, rbt, L.ld, s));
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
+            DQ_HIP(launch_split_transpose_bf16(R, ldr, n, rbt, 2L * koff, koff, s));
         }
         GemmBf16 g;
         g.A = static_cast<const bf16_t*>(X); g.lda = ldx; g.ta = 0;
-        g.B = rbt; g.ldb = L.ld; g.tb = 1;
-        g.C = Y; g.ldc = ldy; g.M = T; g.N = n; g.K = n;
+        g.B = rbt; g.ldb = 2L * koff; g.tb = 1;
+        g.C = Y; g.ldc = ldy; g.M = T; g.N = n; g.K = 2 * koff;
+        g.a_kwrap = koff; g.a_klim = n;
         LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
         DQ_HIP(launch_gemm_bf16(g, s));
     } else {

@@ -57,6 +57,10 @@ struct GemmBf16 {
     int M = 0, N = 0, K = 0;
     int ta = 0, tb = 0;    // as above
     int splits = 1; int kchunk = 0; long split_stride = 0;
+    // a_kwrap > 0: the reduction index k runs over [0, 2*a_kwrap); A is read at k mod a_kwrap (columns
+    // >= a_klim read as zero) while B supplies two planes [hi | lo] of a_kwrap columns each (tb == 1).
+    // Used for X @ (R_hi + R_lo) with one pass over the accumulators.  Not combined with split-K.
+    int a_kwrap = 0; int a_klim = 0;
 };
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
 
@@ -93,8 +97,9 @@ hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, uns
 hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s);
 
 // ---- rotate / Whip pieces ---------------------------------------------------------
-// RbT[j][k] = bf16(R[k][j])   (n x n, ldt)
-hipError_t launch_convert_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, hipStream_t s);
+// Split R into two bf16 planes and transpose:  RbT[j][k] = hi(R[k][j]),  RbT[j][koff + k] = lo(R[k][j]) with
+// hi = bf16(r), lo = bf16(r - hi); columns k in [n, koff) of both planes are written as zero.  ldt >= 2*koff.
+hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, int koff, hipStream_t s);
 // Fused Whip loss + gradient pass: partial sums to `partials` (double, one per workgroup), then
 // launch_loss_finish adds them up: loss = scale * sum.  dy_is_bf16 selects the dtype of dY.
 int whip_grid(long rows, int cols);

@@ -1,6 +1,6 @@
 // HBM-bound passes of the step:
 //   * the fused Whip loss + gradient pass over Y (Eq. 4 and its derivative; Alg. 1 line 9),
-//   * fp32 -> bf16 conversion of the rotation with a transpose (operand preparation for X @ R),
+//   * the two-plane bf16 split of the rotation with a transpose (operand preparation for X @ R),
 //   * P = strict_lower(B - B^T) of the derivative through Z = R U,
 //   * inverses of the diagonal blocks of U for the blocked triangular solve,
 //   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
@@ -106,11 +106,13 @@ __global__ __launch_bounds__(256) void loss_finish_kernel(const double* __restri
     }
 }
 
-// RbT[j][k] = bf16(R[k][j]) through a 32 x 33 LDS tile so that both the read and the write are coalesced.
-__global__ __launch_bounds__(256) void convert_transpose_bf16_kernel(const float* __restrict__ R, long ldr, int n,
-                                                                     bf16_t* __restrict__ RbT, long ldt) {
+// Two-plane bf16 split of R, transposed, through a 32 x 33 LDS tile so that both the read and the writes are
+// coalesced:  RbT[j][k] = hi(R[k][j]),  RbT[j][koff + k] = lo(R[k][j]);  hi + lo carries 16 mantissa bits of R.
+// The grid covers k up to koff, so the padding columns [n, koff) of both planes are written as zero.
+__global__ __launch_bounds__(256) void split_transpose_bf16_kernel(const float* __restrict__ R, long ldr, int n,
+                                                                   bf16_t* __restrict__ RbT, long ldt, int koff) {
     __shared__ float tile[32][33];
-    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // bx: column block of R, by: row block of R
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // bx: column block of R (j), by: row block of R (k)
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     for (int i = ty; i < 32; i += 8) {
         const int r = by + i, c = bx + tx;
@@ -118,8 +120,14 @@ __global__ __launch_bounds__(256) void convert_transpose_bf16_kernel(const float
     }
     __syncthreads();
     for (int i = ty; i < 32; i += 8) {
-        const int j = bx + i, k = by + tx;   // output row j (column of R), output column k (row of R)
-        if (j < n && k < n) RbT[(long)j * ldt + k] = (bf16_t)f32_to_bf16_rne(tile[tx][i]);
+        const int j = bx + i, k = by + tx;
+        if (j < n && k < koff) {
+            const float r = tile[tx][i];
+            const uint32_t hi = f32_to_bf16_rne(r);
+            const float rem = r - __uint_as_float(hi << 16);
+            RbT[(long)j * ldt + k] = (bf16_t)hi;
+            RbT[(long)j * ldt + koff + k] = (bf16_t)f32_to_bf16_rne(rem);
+        }
     }
 }
 
@@ -217,9 +225,10 @@ hipError_t launch_loss_finish(const double* partials, int count, float scale, fl
     return hipGetLastError();
 }
 
-hipError_t launch_convert_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, hipStream_t s) {
-    const int tb = (n + 31) / 32;
-    hipLaunchKernelGGL(convert_transpose_bf16_kernel, dim3(tb, tb), dim3(256), 0, s, R, ldr, n, RbT, ldt);
+hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, int koff,
+                                       hipStream_t s) {
+    hipLaunchKernelGGL(split_transpose_bf16_kernel, dim3((n + 31) / 32, (koff + 31) / 32), dim3(256), 0, s, R, ldr, n,
+                       RbT, ldt, koff);
     return hipGetLastError();
 }
 

@@ -1,8 +1,8 @@
 // bf16 x bf16 -> fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), LDS-staged,
 // double-buffered:   C (M x N, fp32) = op(A) * op(B).
 //
-// Serves the two large products of Alg. 1:  O = X @ R (line 8; X bf16, R rounded to bf16 and stored
-// transposed so that both operands are k-contiguous) and G = X^T @ dY (the chain rule to R; both operands
+// Serves the two large products of Alg. 1:  O = X @ R (line 8; X bf16, R split into two bf16 planes hi + lo
+// and stored transposed so that both operands are k-contiguous) and G = X^T @ dY (the chain rule to R; both operands
 // are stored with the reduction dimension, the tokens, as rows, and are transposed on their way into LDS).
 //
 // Workgroup: 256 threads = 2 x 2 wavefronts; tile 128 x 128 x 32; wavefront tile 64 x 64 = 2 x 2 MFMA tiles.
@@ -137,6 +137,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m,
     OperandViewH oa, ob;
     oa.p = g.A; oa.ld = g.lda; oa.vec = avec;
     if (TA) { oa.row_lim = ke; oa.col_lim = g.M; } else { oa.row_lim = g.M; oa.col_lim = ke; }
+    const int wrap = g.a_kwrap;
+    if (wrap > 0) { if (TA) oa.row_lim = g.a_klim; else oa.col_lim = g.a_klim; }
     ob.p = g.B; ob.ld = g.ldb; ob.vec = bvec;
     if (TB) { ob.row_lim = g.N; ob.col_lim = ke; } else { ob.row_lim = ke; ob.col_lim = g.N; }
 
@@ -154,7 +156,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m,
     const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
     Frag fa, fb;
     if (nk > 0) {
-        if (TA) fetch_mc(oa, m0, kb, tid, fa); else fetch_kc(oa, m0, kb, tid, fa);
+        const int ka = (wrap > 0 && kb >= wrap) ? kb - wrap : kb;
+        if (TA) fetch_mc(oa, m0, ka, tid, fa); else fetch_kc(oa, m0, ka, tid, fa);
         if (TB) fetch_kc(ob, n0, kb, tid, fb); else fetch_mc(ob, n0, kb, tid, fb);
         if (TA) stash_mc(As[0], tid, fa); else stash_kc(As[0], tid, fa);
         if (TB) stash_kc(Bs[0], tid, fb); else stash_mc(Bs[0], tid, fb);
@@ -164,7 +167,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m,
         const int cur = kt & 1;
         if (kt + 1 < nk) {
             const int k0 = kb + (kt + 1) * BK;
-            if (TA) fetch_mc(oa, m0, k0, tid, fa); else fetch_kc(oa, m0, k0, tid, fa);
+            const int ka = (wrap > 0 && k0 >= wrap) ? k0 - wrap : k0;
+            if (TA) fetch_mc(oa, m0, ka, tid, fa); else fetch_kc(oa, m0, ka, tid, fa);
             if (TB) fetch_kc(ob, n0, k0, tid, fb); else fetch_mc(ob, n0, k0, tid, fb);
         }
 #pragma unroll
