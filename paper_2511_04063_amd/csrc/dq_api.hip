@@ -56,7 +56,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0,
-           vs = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
+           vs = 0, tsl = 0, ybuf = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -86,6 +86,8 @@ Layout make_layout(int n, int T) {
     L.wpart = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
     L.w2 = bump(cur, (size_t)kPanel * L.ld * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
+    L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
+    L.ybuf = bump(cur, (size_t)n * kPanel * 4);
     const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
@@ -160,21 +162,23 @@ void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int
 }
 
 // ---------------------------------------------------------------- block-reflector application
-// Csub (m x nc) <- (I - V op(T) V^T) Csub, V = unit-lower-trapezoid block stored at Vp (m x jb, ldv).
-// With include_gram the first GEMM also produces V^T V in the first jb columns of the partials
-// (Bstart must then be Vp itself and Csub = Bstart + jb) and the T factor is built from it.
+// Csub (m x nc) <- (I - V op(T) V^T) Csub = Csub - (V op(T)) (V^T Csub), V = unit-lower-trapezoid block stored
+// at Vp (m x jb, ldv).  With include_gram the first GEMM also produces V^T V in the first jb columns of the
+// partials (Bstart must then be Vp itself and Csub = Bstart + jb) and the T factor is built from it.
 dq_status apply_block_reflector(dq_ctx* c, const Layout& L, const float* Vp, long ldv, int m, int jb,
-                                float* Bstart, long ldb, int ncols_total, int include_gram, const float* tau,
+                                float* Bstart, long ldb, int ncols_total, int include_gram, int slice_width,
                                 float* Tp, int transT) {
     hipStream_t s = c->stream;
     float* wpart = at<float>(c, L.wpart);
     float* w2 = at<float>(c, L.w2);
+    float* ybuf = at<float>(c, L.ybuf);
     const long ldw = L.ld;
     const long stride = (long)kPanel * ldw;
     int splits, kchunk;
-    choose_split((ncols_total + 127) / 128, m, 16, kMaxSplit, splits, kchunk);
+    const int tn = gemm_f32_tile_n(jb, ncols_total);
+    choose_split((ncols_total + tn - 1) / tn, m, 16, kMaxSplit, splits, kchunk);
     {
-        GemmF32 g;
+        GemmF32 g;   // partials of V^T [V | C]
         g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = 1;
         g.B = Bstart; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = include_gram ? jb : 0;
         g.C = wpart; g.ldc = ldw;
@@ -183,23 +187,36 @@ dq_status apply_block_reflector(dq_ctx* c, const Layout& L, const float* Vp, lon
         LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * jb * (double)ncols_total * m, 0.0);
         DQ_HIP(launch_gemm_f32(g, s));
     }
+    // sum the partials once ([G | W], jb x ncols_total) so that the T factor and the update read one copy
+    const float* Wsum = wpart;
+    if (splits > 1) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_splitk_reduce(wpart, splits, stride, ldw, jb, ncols_total, 1.f, 0.f, w2, ldw, s));
+        Wsum = w2;
+    }
     int col0 = 0;
     float* Csub = Bstart;
     int nc = ncols_total;
     if (include_gram) {
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-        DQ_HIP(launch_tfactor(wpart, splits, stride, ldw, jb, tau, Tp, s));
+        DQ_HIP(launch_tfactor(Wsum, 1, 0, ldw, jb, at<float>(c, L.tsl), slice_width, Tp, s));
         col0 = jb; Csub = Bstart + jb; nc = ncols_total - jb;
     }
     if (nc <= 0) return DQ_OK;
+    Wsum += col0;
     {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-        DQ_HIP(launch_wreduce_T(wpart, splits, stride, ldw, col0, jb, nc, Tp, transT, w2, ldw, s));
+        GemmF32 g;   // Y = V op(T)   (m x jb)
+        g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
+        g.B = Tp; g.ldb = kPanel; g.tb = transT ? 1 : 0;
+        g.C = ybuf; g.ldc = kPanel;
+        g.M = m; g.N = jb; g.K = jb;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)jb * jb, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
     }
     {
-        GemmF32 g;
-        g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
-        g.B = w2; g.ldb = ldw; g.tb = 0;
+        GemmF32 g;   // C -= Y W
+        g.A = ybuf; g.lda = kPanel; g.ta = 0;
+        g.B = Wsum; g.ldb = ldw; g.tb = 0;
         g.C = Csub; g.ldc = ldb;
         g.M = m; g.N = nc; g.K = jb;
         g.alpha = -1.f; g.beta = 1.f;
@@ -229,11 +246,12 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
         const int m = n - k0;
         float* Ap = A + (long)k0 * ld + k0;
+        int sw = 8;
         {
             LaunchScope sc(&c->prof, s, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
-            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, flags, s));
+            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, at<float>(c, L.tsl), &sw, flags, s));
         }
-        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, Ap, ld, m, 1, tau + k0, Tall + (long)p * kPanel * kPanel, 1));
+        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, Ap, ld, m, 1, sw, Tall + (long)p * kPanel * kPanel, 1));
     }
     {
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 4.0 * n * (double)n);
@@ -244,7 +262,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
         const int m = n - k0;
         const float* Ap = A + (long)k0 * ld + k0;
-        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, R + (long)k0 * ldr + k0, ldr, m, 0, nullptr,
+        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, R + (long)k0 * ldr + k0, ldr, m, 0, 0,
                                      Tall + (long)p * kPanel * kPanel, 0));
     }
     {

@@ -48,6 +48,7 @@ struct GemmF32 {
     int splits = 1; int kchunk = 0; long split_stride = 0;
 };
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s);
+int gemm_f32_tile_n(int M, int N);   // width of the workgroup tile the launcher picks
 
 // ---- bf16 matrix-core GEMM (fp32 accumulate, fp32 out) ------------------------------
 struct GemmBf16 {
@@ -71,16 +72,14 @@ hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long
 // ---- QR pieces --------------------------------------------------------------------
 // Factor the m x jb panel at A (row-major, lda) in place: reflectors below the diagonal (unit diagonal
 // implied), triangular factor on and above it; tau[0..jb).  vscratch: >= panel_scratch_floats(m) floats.
+// tslices (kPanel*kPanel floats) receives the T factor of every column slice; *slice_width its width.
 size_t panel_scratch_floats(int m);
-hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch,
-                           unsigned* flags, hipStream_t s);
-// T (jb x jb upper, ld kPanel) of the compact-WY form from the Gram partials G = V^T V
-// (gpart[z] at stride, leading dimension ldp, first jb columns) and tau.
-hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb,
-                          const float* tau, float* Tout, hipStream_t s);
-// W2 (jb x nc, ldw2) = op(T) * sum_z part[z][:, col0 : col0+nc]   (op = transpose when transT != 0)
-hipError_t launch_wreduce_T(const float* part, int splits, long stride, long ldp, int col0, int jb, int nc,
-                            const float* T, int transT, float* W2, long ldw2, hipStream_t s);
+hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
+                           int* slice_width, unsigned* flags, hipStream_t s);
+// T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the Gram
+// partials G = V^T V (gpart[z] at stride, leading dimension ldp, first jb columns).
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tslices,
+                          int slice_width, float* Tout, hipStream_t s);
 
 hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s);
 hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s);

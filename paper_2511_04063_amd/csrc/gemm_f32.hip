@@ -2,8 +2,8 @@
 //
 //   C (M x N) = alpha * op(A) * op(B) + beta * C
 //
-// Workgroup: 256 threads = 4 wavefronts in a 2 x 2 arrangement; workgroup tile 128 x 128, wavefront
-// tile 64 x 64 = 2 x 2 MFMA tiles of 32 x 32; K step 16.  Both operand tiles live in LDS as [k][mn]
+// Workgroup: 256 threads = 4 wavefronts; workgroup tile 128 x 128 (64 x 256 for M <= 64, 256 x 64 for N <= 64),
+// wavefront tile 64 x 64 = 2 x 2 MFMA tiles of 32 x 32; K step 16.  Both operand tiles live in LDS as [k][mn]
 // (mn contiguous), so every MFMA operand fetch is a conflict-free 32-float row segment.
 //
 // MFMA 32x32x2 f32 lane layout (lane l of 64):  A operand a = A[m = l % 32][k = l / 32],
@@ -21,8 +21,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int LDT = BM + 4;   // LDS row stride in floats (16-byte aligned rows)
+constexpr int BK = 16;
 
 struct OperandView {
     const float* p; long ld;
@@ -57,25 +56,26 @@ __device__ __forceinline__ float4 load4_guarded(const OperandView& o, int sr, in
 
 // KC = true : storage is (mn, k) with k contiguous  -> transposing store into LDS [k][mn]
 // KC = false: storage is (k, mn) with mn contiguous -> straight 16-byte store
-template <bool KC>
-__device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0, int tid, float4 (&frag)[2]) {
+// ROWS = extent of the tile along mn (64, 128 or 256); every thread moves ROWS / 64 float4.
+template <bool KC, int ROWS>
+__device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0, int tid, float4 (&frag)[ROWS / 64]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < ROWS / 64; ++i) {
         const int f = tid + 256 * i;
         if (KC) {
             const int r = f >> 2, kq = (f & 3) << 2;
             frag[i] = load4_guarded(o, mn0 + r, k0 + kq);
         } else {
-            const int kr = f >> 5, c4 = (f & 31) << 2;
+            const int kr = f / (ROWS / 4), c4 = (f % (ROWS / 4)) << 2;
             frag[i] = load4_guarded(o, k0 + kr, mn0 + c4);
         }
     }
 }
 
-template <bool KC>
-__device__ __forceinline__ void stash_tile(float (*S)[LDT], int tid, const float4 (&frag)[2]) {
+template <bool KC, int ROWS>
+__device__ __forceinline__ void stash_tile(float (*S)[ROWS + 4], int tid, const float4 (&frag)[ROWS / 64]) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < ROWS / 64; ++i) {
         const int f = tid + 256 * i;
         if (KC) {
             const int r = f >> 2, kq = (f & 3) << 2;
@@ -84,16 +84,19 @@ __device__ __forceinline__ void stash_tile(float (*S)[LDT], int tid, const float
             S[kq + 2][r] = frag[i].z;
             S[kq + 3][r] = frag[i].w;
         } else {
-            const int kr = f >> 5, c4 = (f & 31) << 2;
+            const int kr = f / (ROWS / 4), c4 = (f % (ROWS / 4)) << 2;
             *reinterpret_cast<float4*>(&S[kr][c4]) = frag[i];
         }
     }
 }
 
-template <bool TA, bool TB>
+// BM x BN is the workgroup tile: 128 x 128 (waves 2 x 2), 64 x 256 (1 x 4, for M <= 64) or 256 x 64 (4 x 1, for
+// N <= 64); the wavefront tile is always 64 x 64.
+template <bool TA, bool TB, int BM, int BN>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, int tiles_n, int avec, int bvec) {
-    __shared__ __attribute__((aligned(16))) float As[2][BK][LDT];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDT];
+    __shared__ __attribute__((aligned(16))) float As[2][BK][BM + 4];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN + 4];
+    constexpr int WAVES_N = BN / 64;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -141,23 +144,23 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave / WAVES_N) * 64, wn = (wave % WAVES_N) * 64;
     const int lrow = lane & 31, lk = lane >> 5;
 
     const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
-    float4 fa[2], fb[2];
+    float4 fa[BM / 64], fb[BN / 64];
     if (nk > 0) {
-        fetch_tile<!TA>(oa, m0, kb, tid, fa);
-        fetch_tile<TB>(ob, n0, kb, tid, fb);
-        stash_tile<!TA>(As[0], tid, fa);
-        stash_tile<TB>(Bs[0], tid, fb);
+        fetch_tile<!TA, BM>(oa, m0, kb, tid, fa);
+        fetch_tile<TB, BN>(ob, n0, kb, tid, fb);
+        stash_tile<!TA, BM>(As[0], tid, fa);
+        stash_tile<TB, BN>(Bs[0], tid, fb);
     }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         if (kt + 1 < nk) {
-            fetch_tile<!TA>(oa, m0, kb + (kt + 1) * BK, tid, fa);
-            fetch_tile<TB>(ob, n0, kb + (kt + 1) * BK, tid, fb);
+            fetch_tile<!TA, BM>(oa, m0, kb + (kt + 1) * BK, tid, fa);
+            fetch_tile<TB, BN>(ob, n0, kb + (kt + 1) * BK, tid, fb);
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
@@ -173,8 +176,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) {
-            stash_tile<!TA>(As[cur ^ 1], tid, fa);
-            stash_tile<TB>(Bs[cur ^ 1], tid, fb);
+            stash_tile<!TA, BM>(As[cur ^ 1], tid, fa);
+            stash_tile<TB, BN>(Bs[cur ^ 1], tid, fb);
         }
         __syncthreads();
     }
@@ -217,22 +220,31 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 
 }  // namespace
 
-hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
-    if (g.M <= 0 || g.N <= 0) return hipSuccess;
+template <int BM, int BN>
+static hipError_t launch_gemm_f32_tile(const GemmF32& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 3) == 0) ? 1 : 0;
     const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 3) == 0) ? 1 : 0;
     dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
     dim3 block(256, 1, 1);
     if (g.ta && g.tb)
-        hipLaunchKernelGGL((gemm_f32_kernel<true, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<true, true, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else if (g.ta)
-        hipLaunchKernelGGL((gemm_f32_kernel<true, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<true, false, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else if (g.tb)
-        hipLaunchKernelGGL((gemm_f32_kernel<false, true>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<false, true, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<false, false>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<false, false, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     return hipGetLastError();
+}
+
+int gemm_f32_tile_n(int M, int N) { return M <= 64 ? 256 : (N <= 64 ? 64 : 128); }
+
+hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
+    if (g.M <= 0 || g.N <= 0) return hipSuccess;
+    if (g.M <= 64) return launch_gemm_f32_tile<64, 256>(g, s);
+    if (g.N <= 64) return launch_gemm_f32_tile<256, 64>(g, s);
+    return launch_gemm_f32_tile<128, 128>(g, s);
 }
 
 hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,

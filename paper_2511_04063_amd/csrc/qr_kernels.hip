@@ -1,7 +1,6 @@
 // Blocked Householder QR pieces (Alg. 2 of the paper's appendix, in LAPACK-style compact-WY form):
 //   * the panel factorisation (one workgroup, panel columns held in registers slice by slice),
 //   * the triangular T factor of a panel's block reflector  H_1 ... H_jb = I - V T V^T,
-//   * the small "reduce split-K partials and multiply by T / T^T" step of a block-reflector application,
 //   * sign normalisation diag(U) >= 0 (the reading that makes R of Sec. 4.3 unique), and small helpers.
 //
 // Reflector convention: H = I - tau v v^T with v[0] = 1 implied, beta = -sign(alpha) ||x||,
@@ -47,7 +46,8 @@ __device__ __forceinline__ int wave_reduce_multi(float (&v)[NV], int lane) {
 // the zeros above it written out.  Every thread re-reads only rows it wrote itself.
 template <int NT, int Q, int SW>
 __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, long lda, int m, int jb,
-                                                      float* __restrict__ tau, float* Vs, unsigned* flags, int vec) {
+                                                      float* __restrict__ tau, float* Vs, float* __restrict__ tslices,
+                                                      unsigned* flags, int vec) {
     constexpr int NW = NT / 64;
     constexpr int MP = NT * Q;
     constexpr int NV2 = SW * SW;
@@ -227,7 +227,10 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 #pragma unroll
             for (int x = 0; x < SW; ++x)
 #pragma unroll
-                for (int y = 0; y < SW; ++y) Tsh[s][x * SW + y] = Tl[x][y];
+                for (int y = 0; y < SW; ++y) {
+                    Tsh[s][x * SW + y] = Tl[x][y];
+                    tslices[s * NV2 + x * SW + y] = Tl[x][y];
+                }
 #pragma unroll
             for (int c = 0; c < SW; ++c)
                 if (c < ncs) tau[col0 + c] = tau_l[c];
@@ -262,15 +265,15 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
     }
 }
 
-// T factor of a panel from the Gram matrix of its reflectors (forward, columnwise):
-//   T[j][j] = tau_j,   T[0:j, j] = -tau_j * T[0:j, 0:j] * G[0:j, j],   G = V^T V.
-// Thread i owns row i of T and reads only its own row, so no synchronisation is needed after the load.
+// T factor of a panel's block reflector  H_1 ... H_jb = I - V T V^T  from the T factors of its column slices
+// (sw x sw each, from the panel kernel) and the Gram matrix G = V^T V, by merging neighbours level by level:
+//   T = [[T1, -T1 (V1^T V2) T2], [0, T2]].
 __global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
-                                                      long ldp, int jb, const float* __restrict__ tau,
+                                                      long ldp, int jb, const float* __restrict__ tslices, int sw,
                                                       float* __restrict__ Tout) {
     __shared__ float Gs[kPanel][kPanel + 1];
     __shared__ float Ts[kPanel][kPanel + 1];
-    __shared__ float taus[kPanel];
+    __shared__ float Xs[kPanel][kPanel + 1];
     const int tid = threadIdx.x;
     for (int e = tid; e < kPanel * kPanel; e += 256) {
         const int i = e / kPanel, j = e % kPanel;
@@ -278,57 +281,32 @@ __global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ 
         if (i < jb && j < jb)
             for (int z = 0; z < splits; ++z) t += gpart[(long)z * stride + (long)i * ldp + j];
         Gs[i][j] = t;
-        Ts[i][j] = 0.f;
-    }
-    if (tid < kPanel) taus[tid] = tid < jb ? tau[tid] : 0.f;
-    __syncthreads();
-    if (tid < jb) {
-        const int i = tid;
-        for (int j = i; j < jb; ++j) {
-            if (j == i) {
-                Ts[i][j] = taus[j];
-            } else {
-                float acc = 0.f;
-                for (int l = i; l < j; ++l) acc += Ts[i][l] * Gs[l][j];
-                Ts[i][j] = -taus[j] * acc;
-            }
-        }
+        float tv = 0.f;
+        if (i / sw == j / sw && i < jb && j < jb) tv = tslices[(i / sw) * sw * sw + (i % sw) * sw + (j % sw)];
+        Ts[i][j] = tv;
     }
     __syncthreads();
-    for (int e = tid; e < kPanel * kPanel; e += 256) Tout[e] = Ts[e / kPanel][e % kPanel];
-}
-
-// W2[:, chunk] = op(T) * sum_z part[z][:, col0 + chunk], one workgroup per 64 columns.
-__global__ __launch_bounds__(256) void wreduce_T_kernel(const float* __restrict__ part, int splits, long stride,
-                                                        long ldp, int col0, int jb, int nc,
-                                                        const float* __restrict__ T, int transT,
-                                                        float* __restrict__ W2, long ldw2) {
-    __shared__ float Ts[kPanel][kPanel + 1];   // Ts[r][l] = op(T)[r][l]
-    __shared__ float Ws[kPanel][kPanel + 1];
-    const int tid = threadIdx.x;
-    const int c0 = blockIdx.x * 64;
-    for (int e = tid; e < kPanel * kPanel; e += 256) {
-        const int i = e / kPanel, j = e % kPanel;
-        const float t = T[e];
-        if (transT) Ts[j][i] = t; else Ts[i][j] = t;
-        float w = 0.f;
-        if (i < jb && c0 + j < nc)
-            for (int z = 0; z < splits; ++z) w += part[(long)z * stride + (long)i * ldp + col0 + c0 + j];
-        Ws[i][j] = w;
-    }
-    __syncthreads();
-    const int c = tid & 63, rg = tid >> 6;
-    if (c0 + c < nc) {
-        for (int rr = 0; rr < 16; ++rr) {
-            const int r = rg * 16 + rr;
-            if (r >= jb) break;
+    for (int b = sw; b < kPanel; b <<= 1) {
+        const int per_pair = b * b;
+        const int total = (kPanel / (2 * b)) * per_pair;
+        for (int e = tid; e < total; e += 256) {          // X = G12 * T2
+            const int o = (e / per_pair) * 2 * b, r = e % per_pair;
+            const int i = r / b, j = r % b;
             float acc = 0.f;
-            // op(T) is lower triangular when transposed, upper otherwise; the other half is stored as zeros
-            const int lb = transT ? 0 : r, le = transT ? r + 1 : jb;
-            for (int l = lb; l < le; ++l) acc += Ts[r][l] * Ws[l][c];
-            W2[(long)r * ldw2 + c0 + c] = acc;
+            for (int k = 0; k <= j; ++k) acc += Gs[o + i][o + b + k] * Ts[o + b + k][o + b + j];
+            Xs[o + i][o + b + j] = acc;
         }
+        __syncthreads();
+        for (int e = tid; e < total; e += 256) {          // T12 = -T1 * X
+            const int o = (e / per_pair) * 2 * b, r = e % per_pair;
+            const int i = r / b, j = r % b;
+            float acc = 0.f;
+            for (int k = i; k < b; ++k) acc += Ts[o + i][o + k] * Xs[o + k][o + b + j];
+            Ts[o + i][o + b + j] = -acc;
+        }
+        __syncthreads();
     }
+    for (int e = tid; e < kPanel * kPanel; e += 256) Tout[e] = Ts[e / kPanel][e % kPanel];
 }
 
 __global__ __launch_bounds__(256) void copy2d_kernel(const float* __restrict__ src, long lds, float* __restrict__ dst,
@@ -385,13 +363,13 @@ inline unsigned grid_for(long total) {
 
 size_t panel_scratch_floats(int /*m*/) { return (size_t)kPanel * 8192; }
 
-hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, unsigned* flags,
-                           hipStream_t s) {
+hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
+                           int* slice_width, unsigned* flags, hipStream_t s) {
     if (m <= 0 || jb <= 0) return hipSuccess;
     if (m > 8192 || jb > kPanel || jb > m) return hipErrorInvalidValue;
     const int vec = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0) ? 1 : 0;
     constexpr int NT = 512;
-#define DQ_PANEL(Q, SW) hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, flags, vec)
+#define DQ_PANEL(Q, SW) do { *slice_width = SW; hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices, flags, vec); } while (0)
     if (m <= NT * 1) DQ_PANEL(1, 8);
     else if (m <= NT * 2) DQ_PANEL(2, 8);
     else if (m <= NT * 4) DQ_PANEL(4, 8);
@@ -401,17 +379,10 @@ hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float*
     return hipGetLastError();
 }
 
-hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tau,
-                          float* Tout, hipStream_t s) {
-    hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(256), 0, s, gpart, splits, stride, ldp, jb, tau, Tout);
-    return hipGetLastError();
-}
-
-hipError_t launch_wreduce_T(const float* part, int splits, long stride, long ldp, int col0, int jb, int nc,
-                            const float* T, int transT, float* W2, long ldw2, hipStream_t s) {
-    if (nc <= 0) return hipSuccess;
-    hipLaunchKernelGGL(wreduce_T_kernel, dim3((nc + 63) / 64), dim3(256), 0, s, part, splits, stride, ldp, col0, jb, nc,
-                       T, transT, W2, ldw2);
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tslices,
+                          int slice_width, float* Tout, hipStream_t s) {
+    hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(256), 0, s, gpart, splits, stride, ldp, jb, tslices, slice_width,
+                       Tout);
     return hipGetLastError();
 }
 

@@ -53,7 +53,7 @@ def ctx():
 
 # ----------------------------------------------------------------------------------- GEMM kernels
 @pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1), (1, 1)])
-@pytest.mark.parametrize("M,N,K", [(300, 200, 150), (129, 257, 17), (64, 500, 1000), (1, 1, 1)])
+@pytest.mark.parametrize("M,N,K", [(300, 200, 150), (129, 257, 17), (64, 500, 1000), (1, 1, 1), (500, 64, 96), (300, 40, 50)])
 def test_gemm_f32(ctx, ta, tb, M, N, K):
     g = rng(1000 + 7 * M + N + K + 2 * ta + tb)
     A = g.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
