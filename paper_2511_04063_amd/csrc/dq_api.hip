@@ -43,7 +43,10 @@ LaunchScope::~LaunchScope() {
 using namespace dq;
 
 struct dq_ctx {
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;    // the caller's stream: every call starts and ends here
+    hipStream_t stream2 = nullptr;   // internal: trailing updates of the QR run here while the next panel is factored
+    hipStream_t stream3 = nullptr;   // internal: the orthogonal factor is accumulated here, also behind the panels
+    std::vector<hipEvent_t> sync_ev; // 2 per panel: look-ahead part done (even), trailing part done (odd); + 1 join
     int device = 0;
     char* ws = nullptr;
     size_t ws_bytes = 0;
@@ -55,7 +58,7 @@ namespace {
 // ---------------------------------------------------------------- workspace layout
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
-    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0,
+    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, qy = 0,
            vs = 0, tsl = 0, ybuf = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
@@ -85,9 +88,14 @@ Layout make_layout(int n, int T) {
     L.Tall = bump(cur, npanels * kPanel * kPanel * 4);
     L.wpart = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
     L.w2 = bump(cur, (size_t)kPanel * L.ld * 4);
+    L.wpartB = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
+    L.w2B = bump(cur, (size_t)kPanel * L.ld * 4);
+    L.qpart = bump(cur, (size_t)kMaxSplit * n * kPanel * 4);
+    L.qw = bump(cur, (size_t)n * kPanel * 4);
+    L.qy = bump(cur, (size_t)n * kPanel * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
     L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
-    L.ybuf = bump(cur, (size_t)n * kPanel * 4);
+    L.ybuf = bump(cur, (size_t)2 * n * kPanel * 4);   // two copies: look-ahead double buffering
     const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
@@ -149,9 +157,9 @@ dq_status check_ws(dq_ctx* c, const Layout& L) {
 // Enough layers to give every compute unit a workgroup when the output has few tiles.
 void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int& kchunk) {
     splits = 1;
-    if (tiles < 128) {
-        splits = (256 + tiles - 1) / tiles;
-        const int by_k = (K + 255) / 256;   // at least 256 reduction elements per layer
+    if (tiles < 256) {
+        splits = (768 + tiles - 1) / tiles;
+        const int by_k = (K + 127) / 128;   // at least 128 reduction elements per layer
         if (splits > by_k) splits = by_k;
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
@@ -162,112 +170,185 @@ void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int
 }
 
 // ---------------------------------------------------------------- block-reflector application
-// Csub (m x nc) <- (I - V op(T) V^T) Csub = Csub - (V op(T)) (V^T Csub), V = unit-lower-trapezoid block stored
-// at Vp (m x jb, ldv).  With include_gram the first GEMM also produces V^T V in the first jb columns of the
-// partials (Bstart must then be Vp itself and Csub = Bstart + jb) and the T factor is built from it.
-dq_status apply_block_reflector(dq_ctx* c, const Layout& L, const float* Vp, long ldv, int m, int jb,
-                                float* Bstart, long ldb, int ncols_total, int include_gram, int slice_width,
-                                float* Tp, int transT) {
-    hipStream_t s = c->stream;
-    float* wpart = at<float>(c, L.wpart);
-    float* w2 = at<float>(c, L.w2);
-    float* ybuf = at<float>(c, L.ybuf);
+// Pieces of  Csub <- (I - V op(T) V^T) Csub = Csub - (V op(T)) (V^T Csub)  with V the unit-lower-trapezoid block
+// stored at Vp (m x jb, ldv).  Each piece takes the stream and the scratch buffers it may use, so that the look-ahead
+// part and the trailing part of a QR update can run on two streams.
+struct ReflBufs { float* wpart; float* wsum; };
+
+// Wsum (jb x ncols, ld L.ld) = V^T Bmat;  with gram_cols > 0 the first gram_cols columns of Bmat are V itself (masked).
+dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs& bufs, const float* Vp, long ldv,
+                       int m, int jb, const float* Bmat, long ldb, int ncols, int gram_cols, const float** Wsum) {
     const long ldw = L.ld;
     const long stride = (long)kPanel * ldw;
     int splits, kchunk;
-    const int tn = gemm_f32_tile_n(jb, ncols_total);
-    choose_split((ncols_total + tn - 1) / tn, m, 16, kMaxSplit, splits, kchunk);
+    const int tn = gemm_f32_tile_n(jb, ncols);
+    choose_split((ncols + tn - 1) / tn, m, 16, kMaxSplit, splits, kchunk);
     {
-        GemmF32 g;   // partials of V^T [V | C]
+        GemmF32 g;
         g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = 1;
-        g.B = Bstart; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = include_gram ? jb : 0;
-        g.C = wpart; g.ldc = ldw;
-        g.M = jb; g.N = ncols_total; g.K = m;
+        g.B = Bmat; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = gram_cols;
+        g.C = bufs.wpart; g.ldc = ldw;
+        g.M = jb; g.N = ncols; g.K = m;
         g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * jb * (double)ncols_total * m, 0.0);
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * jb * (double)ncols * m, 0.0);
         DQ_HIP(launch_gemm_f32(g, s));
     }
-    // sum the partials once ([G | W], jb x ncols_total) so that the T factor and the update read one copy
-    const float* Wsum = wpart;
+    *Wsum = bufs.wpart;
     if (splits > 1) {
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-        DQ_HIP(launch_splitk_reduce(wpart, splits, stride, ldw, jb, ncols_total, 1.f, 0.f, w2, ldw, s));
-        Wsum = w2;
+        DQ_HIP(launch_splitk_reduce(bufs.wpart, splits, stride, ldw, jb, ncols, 1.f, 0.f, bufs.wsum, ldw, s));
+        *Wsum = bufs.wsum;
     }
-    int col0 = 0;
-    float* Csub = Bstart;
-    int nc = ncols_total;
-    if (include_gram) {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-        DQ_HIP(launch_tfactor(Wsum, 1, 0, ldw, jb, at<float>(c, L.tsl), slice_width, Tp, s));
-        col0 = jb; Csub = Bstart + jb; nc = ncols_total - jb;
-    }
+    return DQ_OK;
+}
+
+// Y (m x jb, ld kPanel) = V op(T)
+dq_status refl_make_y(dq_ctx* c, hipStream_t s, const float* Vp, long ldv, int m, int jb, const float* Tp, int transT,
+                      float* Y) {
+    GemmF32 g;
+    g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
+    g.B = Tp; g.ldb = kPanel; g.tb = transT ? 1 : 0;
+    g.C = Y; g.ldc = kPanel;
+    g.M = m; g.N = jb; g.K = jb;
+    LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)jb * jb, 0.0);
+    DQ_HIP(launch_gemm_f32(g, s));
+    return DQ_OK;
+}
+
+// Csub (m x nc) -= Y W
+dq_status refl_update(dq_ctx* c, hipStream_t s, const Layout& L, const float* Y, const float* W, int m, int jb,
+                      float* Csub, long ldc, int nc) {
     if (nc <= 0) return DQ_OK;
-    Wsum += col0;
+    GemmF32 g;
+    g.A = Y; g.lda = kPanel; g.ta = 0;
+    g.B = W; g.ldb = L.ld; g.tb = 0;
+    g.C = Csub; g.ldc = ldc;
+    g.M = m; g.N = nc; g.K = jb;
+    g.alpha = -1.f; g.beta = 1.f;
+    LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)nc * jb, 0.0);
+    DQ_HIP(launch_gemm_f32(g, s));
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- S1 + S2
+// Q[:, k0:k0+m] <- Q[:, k0:k0+m] (I - V T V^T) for the panel at column k0 (V: m x jb at Vp, T: jb x jb at Tp):
+//   Wq = Qc V (n x jb),  Yq = Wq T,  Qc -= Yq V^T.
+dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0, int m, int jb, const float* Vp,
+                       long ldv, const float* Tp, float* Q, long ldq) {
+    float* qpart = at<float>(c, L.qpart);
+    float* qw = at<float>(c, L.qw);
+    float* qy = at<float>(c, L.qy);
+    float* Qc = Q + k0;
+    const long stride = (long)n * kPanel;
+    int splits, kchunk;
+    const int tm = jb <= 64 ? 256 : 128;
+    choose_split((n + tm - 1) / tm, m, 16, kMaxSplit, splits, kchunk);
     {
-        GemmF32 g;   // Y = V op(T)   (m x jb)
-        g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
-        g.B = Tp; g.ldb = kPanel; g.tb = transT ? 1 : 0;
-        g.C = ybuf; g.ldc = kPanel;
-        g.M = m; g.N = jb; g.K = jb;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)jb * jb, 0.0);
+        GemmF32 g;   // Wq = Qc V
+        g.A = Qc; g.lda = ldq; g.ta = 0;
+        g.B = Vp; g.ldb = ldv; g.tb = 0; g.b_unit_lower_cols = jb;
+        g.C = splits > 1 ? qpart : qw; g.ldc = kPanel;
+        g.M = n; g.N = jb; g.K = m;
+        g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)jb * m, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    if (splits > 1) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_splitk_reduce(qpart, splits, stride, kPanel, n, jb, 1.f, 0.f, qw, kPanel, s));
+    }
+    {
+        GemmF32 g;   // Yq = Wq T
+        g.A = qw; g.lda = kPanel; g.ta = 0;
+        g.B = Tp; g.ldb = kPanel; g.tb = 0;
+        g.C = qy; g.ldc = kPanel;
+        g.M = n; g.N = jb; g.K = jb;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)jb * jb, 0.0);
         DQ_HIP(launch_gemm_f32(g, s));
     }
     {
-        GemmF32 g;   // C -= Y W
-        g.A = ybuf; g.lda = kPanel; g.ta = 0;
-        g.B = Wsum; g.ldb = ldw; g.tb = 0;
-        g.C = Csub; g.ldc = ldb;
-        g.M = m; g.N = nc; g.K = jb;
+        GemmF32 g;   // Qc -= Yq V^T   (V stored m x jb = N x K)
+        g.A = qy; g.lda = kPanel; g.ta = 0;
+        g.B = Vp; g.ldb = ldv; g.tb = 1; g.b_unit_lower_cols = jb;
+        g.C = Qc; g.ldc = ldq;
+        g.M = n; g.N = m; g.K = jb;
         g.alpha = -1.f; g.beta = 1.f;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * m * (double)nc * jb, 0.0);
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)m * jb, 0.0);
         DQ_HIP(launch_gemm_f32(g, s));
     }
     return DQ_OK;
 }
 
-// ---------------------------------------------------------------- S1 + S2
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
                       long ldu) {
-    hipStream_t s = c->stream;
+    hipStream_t sA = c->stream, sB = c->stream2, sC = c->stream3;
     float* A = at<float>(c, L.A);
     float* tau = at<float>(c, L.tau);
     float* Tall = at<float>(c, L.Tall);
     float* vs = at<float>(c, L.vs);
+    float* tsl = at<float>(c, L.tsl);
+    float* ybuf = at<float>(c, L.ybuf);
     unsigned* flags = at<unsigned>(c, L.flags);
+    const ReflBufs bufA{at<float>(c, L.wpart), at<float>(c, L.w2)};
+    const ReflBufs bufB{at<float>(c, L.wpartB), at<float>(c, L.w2B)};
     const long ld = L.ld;
     {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
-        DQ_HIP(launch_copy2d(Z, ldz, A, ld, n, n, s));
+        LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
+        DQ_HIP(launch_copy2d(Z, ldz, A, ld, n, n, sA));
+        DQ_HIP(launch_set_identity(R, ldr, n, sA));
     }
+    // S1.  Panel p is factored on the caller's stream while the trailing update of panel p-1 still runs on the
+    // second stream: after panel p only the columns of panel p+1 ("look-ahead" part) are updated on the caller's
+    // stream; the rest of the trailing matrix goes to the second stream.
     const int npanels = (n + kPanel - 1) / kPanel;
+    int last_trailing = -1;
     for (int p = 0; p < npanels; ++p) {
         const int k0 = p * kPanel;
         const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
         const int m = n - k0;
         float* Ap = A + (long)k0 * ld + k0;
+        float* Tp = Tall + (long)p * kPanel * kPanel;
+        float* Yp = ybuf + (size_t)(p & 1) * n * kPanel;
         int sw = 8;
         {
-            LaunchScope sc(&c->prof, s, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
-            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, at<float>(c, L.tsl), &sw, flags, s));
+            LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
+            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, sA));
         }
-        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, Ap, ld, m, 1, sw, Tall + (long)p * kPanel * kPanel, 1));
+        // the look-ahead columns received update p-1 on the second stream
+        if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+        const int nla = (m - jb) < kPanel ? (m - jb) : kPanel;
+        const float* Wa = nullptr;
+        DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa));
+        {
+            LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 0.0);
+            DQ_HIP(launch_tfactor(Wa, 1, 0, ld, jb, tsl, sw, Tp, sA));
+        }
+        if (nla > 0) {
+            DQ_TRY(refl_make_y(c, sA, Ap, ld, m, jb, Tp, 1, Yp));
+            DQ_TRY(refl_update(c, sA, L, Yp, Wa + jb, m, jb, Ap + jb, ld, nla));
+        }
+        const int rest = m - jb - nla;
+        DQ_HIP(hipEventRecord(c->sync_ev[2 * p], sA));
+        DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
+        if (rest > 0) {
+            DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[2 * p], 0));
+            const float* Wb = nullptr;
+            DQ_TRY(refl_project(c, sB, L, bufB, Ap, ld, m, jb, Ap + jb + nla, ld, rest, 0, &Wb));
+            DQ_TRY(refl_update(c, sB, L, Yp, Wb, m, jb, Ap + jb + nla, ld, rest));
+            DQ_HIP(hipEventRecord(c->sync_ev[2 * p + 1], sB));
+            last_trailing = p;
+        }
+        // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
+        // left to the right, Q[:, k0:] <- Q[:, k0:] (I - V T V^T)  (as Alg. 2 does column by column), on the third
+        // stream.  For p == 0 the accumulated factor is still the identity.
+        DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Tp, R, ldr));
     }
+    if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+    DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));
+    DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev.back(), 0));
     {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 4.0 * n * (double)n);
-        DQ_HIP(launch_set_identity(R, ldr, n, s));
-    }
-    for (int p = npanels - 1; p >= 0; --p) {
-        const int k0 = p * kPanel;
-        const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
-        const int m = n - k0;
-        const float* Ap = A + (long)k0 * ld + k0;
-        DQ_TRY(apply_block_reflector(c, L, Ap, ld, m, jb, R + (long)k0 * ldr + k0, ldr, m, 0, 0,
-                                     Tall + (long)p * kPanel * kPanel, 0));
-    }
-    {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 12.0 * n * (double)n);
-        DQ_HIP(launch_sign_normalise(A, ld, n, R, ldr, U, ldu, flags, s));
+        LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 12.0 * n * (double)n);
+        DQ_HIP(launch_sign_normalise(A, ld, n, R, ldr, U, ldu, flags, sA));
     }
     return DQ_OK;
 }
@@ -443,13 +524,26 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     if (c == nullptr) return DQ_ERR_HIP;
     c->stream = static_cast<hipStream_t>(hip_stream);
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
+    // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream
+    if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }
+    if (hipStreamCreateWithFlags(&c->stream3, hipStreamNonBlocking) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
+    const int nev = 2 * (DQ_MAX_N / kPanelMin) + 1;
+    for (int i = 0; i < nev; ++i) {
+        hipEvent_t e;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
+        c->sync_ev.push_back(e);
+    }
     *out = c;
     return DQ_OK;
 }
 
 dq_status dq_destroy(dq_ctx* c) {
     if (c == nullptr) return DQ_ERR_NULL;
+    (void)hipStreamSynchronize(c->stream);
+    if (c->stream2 != nullptr) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
+    if (c->stream3 != nullptr) { (void)hipStreamSynchronize(c->stream3); (void)hipStreamDestroy(c->stream3); }
     for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->sync_ev) (void)hipEventDestroy(e);
     delete c;
     return DQ_OK;
 }

@@ -11,7 +11,8 @@ namespace dq {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kPanel = 64;           // QR panel width nb (columns aggregated into one compact-WY block)
 constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
-constexpr int kMaxSplit = 32;        // upper bound on split-K partials
+constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
+constexpr int kMaxSplit = 64;        // upper bound on split-K partials
 constexpr int kLossPartials = 2048;  // upper bound on workgroups of the Whip pass (one partial each)
 
 typedef uint16_t bf16_t;             // raw bfloat16 storage
