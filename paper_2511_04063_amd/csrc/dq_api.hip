@@ -1,5 +1,7 @@
 // C ABI of libdartqr.so: argument checking, workspace carving and the sequencing of the kernels of one
 // QR-Orth step (Alg. 1 lines 7-10) on the caller's HIP stream.  No device memory is allocated here.
+#include <stdlib.h>
+
 #include <new>
 #include <vector>
 
@@ -48,6 +50,7 @@ struct dq_ctx {
     hipStream_t stream3 = nullptr;   // internal: the orthogonal factor is accumulated here, also behind the panels
     std::vector<hipEvent_t> sync_ev; // 2 per panel: look-ahead part done (even), trailing part done (odd); + 1 join
     int device = 0;
+    int nb = kPanel;                 // QR panel width (<= kPanel)
     char* ws = nullptr;
     size_t ws_bytes = 0;
     Profiler prof;
@@ -84,7 +87,7 @@ Layout make_layout(int n, int T) {
     L.P = bump(cur, n2 * 4);
     L.M = bump(cur, n2 * 4);
     L.tau = bump(cur, (size_t)round_up(n, 64) * 4);
-    const size_t npanels = (n + kPanel - 1) / kPanel;
+    const size_t npanels = (n + kPanelMin - 1) / kPanelMin;
     L.Tall = bump(cur, npanels * kPanel * kPanel * 4);
     L.wpart = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
     L.w2 = bump(cur, (size_t)kPanel * L.ld * 4);
@@ -177,12 +180,14 @@ struct ReflBufs { float* wpart; float* wsum; };
 
 // Wsum (jb x ncols, ld L.ld) = V^T Bmat;  with gram_cols > 0 the first gram_cols columns of Bmat are V itself (masked).
 dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs& bufs, const float* Vp, long ldv,
-                       int m, int jb, const float* Bmat, long ldb, int ncols, int gram_cols, const float** Wsum) {
+                       int m, int jb, const float* Bmat, long ldb, int ncols, int gram_cols, const float** Wsum,
+                       int max_splits = kMaxSplit, int* splits_out = nullptr) {
     const long ldw = L.ld;
     const long stride = (long)kPanel * ldw;
     int splits, kchunk;
     const int tn = gemm_f32_tile_n(jb, ncols);
-    choose_split((ncols + tn - 1) / tn, m, 16, kMaxSplit, splits, kchunk);
+    choose_split((ncols + tn - 1) / tn, m, 16, max_splits, splits, kchunk);
+    if (splits_out != nullptr) *splits_out = splits;
     {
         GemmF32 g;
         g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = 1;
@@ -194,7 +199,7 @@ dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs
         DQ_HIP(launch_gemm_f32(g, s));
     }
     *Wsum = bufs.wpart;
-    if (splits > 1) {
+    if (splits > 1 && splits_out == nullptr) {   // a caller that asks for the split count sums the partials itself
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
         DQ_HIP(launch_splitk_reduce(bufs.wpart, splits, stride, ldw, jb, ncols, 1.f, 0.f, bufs.wsum, ldw, s));
         *Wsum = bufs.wsum;
@@ -300,15 +305,15 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     // S1.  Panel p is factored on the caller's stream while the trailing update of panel p-1 still runs on the
     // second stream: after panel p only the columns of panel p+1 ("look-ahead" part) are updated on the caller's
     // stream; the rest of the trailing matrix goes to the second stream.
-    const int npanels = (n + kPanel - 1) / kPanel;
+    const int nb = c->nb;
+    const int npanels = (n + nb - 1) / nb;
     int last_trailing = -1;
     for (int p = 0; p < npanels; ++p) {
-        const int k0 = p * kPanel;
-        const int jb = (n - k0) < kPanel ? (n - k0) : kPanel;
+        const int k0 = p * nb;
+        const int jb = (n - k0) < nb ? (n - k0) : nb;
         const int m = n - k0;
         float* Ap = A + (long)k0 * ld + k0;
         float* Tp = Tall + (long)p * kPanel * kPanel;
-        float* Yp = ybuf + (size_t)(p & 1) * n * kPanel;
         int sw = 8;
         {
             LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
@@ -316,16 +321,24 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         }
         // the look-ahead columns received update p-1 on the second stream
         if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
-        const int nla = (m - jb) < kPanel ? (m - jb) : kPanel;
+        const int nla = (m - jb) < nb ? (m - jb) : nb;
+        // partials of V^T [V | C_la]; summed inside the T-factor kernel, which also returns W2 = T^T V^T C_la
         const float* Wa = nullptr;
-        DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa));
+        int splitsA = 1;
+        DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa, 16, &splitsA));
         {
             LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 0.0);
-            DQ_HIP(launch_tfactor(Wa, 1, 0, ld, jb, tsl, sw, Tp, sA));
+            DQ_HIP(launch_tfactor(bufA.wpart, splitsA, (long)kPanel * ld, ld, jb, nla, tsl, sw, Tp, bufA.wsum, sA));
         }
         if (nla > 0) {
-            DQ_TRY(refl_make_y(c, sA, Ap, ld, m, jb, Tp, 1, Yp));
-            DQ_TRY(refl_update(c, sA, L, Yp, Wa + jb, m, jb, Ap + jb, ld, nla));
+            GemmF32 g;   // C_la -= V W2
+            g.A = Ap; g.lda = ld; g.ta = 0; g.a_unit_lower = 1;
+            g.B = bufA.wsum; g.ldb = kPanel; g.tb = 0;
+            g.C = Ap + jb; g.ldc = ld;
+            g.M = m; g.N = nla; g.K = jb;
+            g.alpha = -1.f; g.beta = 1.f;
+            LaunchScope sc(&c->prof, sA, DQ_K_GEMM_F32, 2.0 * m * (double)nla * jb, 0.0);
+            DQ_HIP(launch_gemm_f32(g, sA));
         }
         const int rest = m - jb - nla;
         DQ_HIP(hipEventRecord(c->sync_ev[2 * p], sA));
@@ -333,8 +346,9 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         if (rest > 0) {
             DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[2 * p], 0));
             const float* Wb = nullptr;
+            DQ_TRY(refl_make_y(c, sB, Ap, ld, m, jb, Tp, 1, ybuf));
             DQ_TRY(refl_project(c, sB, L, bufB, Ap, ld, m, jb, Ap + jb + nla, ld, rest, 0, &Wb));
-            DQ_TRY(refl_update(c, sB, L, Yp, Wb, m, jb, Ap + jb + nla, ld, rest));
+            DQ_TRY(refl_update(c, sB, L, ybuf, Wb, m, jb, Ap + jb + nla, ld, rest));
             DQ_HIP(hipEventRecord(c->sync_ev[2 * p + 1], sB));
             last_trailing = p;
         }
@@ -523,6 +537,7 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     dq_ctx* c = new (std::nothrow) dq_ctx();
     if (c == nullptr) return DQ_ERR_HIP;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    if (const char* e = getenv("DQ_PANEL_NB")) { const int v = atoi(e); if (v >= kPanelMin && v <= kPanel && v % 8 == 0) c->nb = v; }
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
     // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream
     if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }

@@ -77,10 +77,11 @@ hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long
 size_t panel_scratch_floats(int m);
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
                            int* slice_width, unsigned* flags, hipStream_t s);
-// T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the Gram
-// partials G = V^T V (gpart[z] at stride, leading dimension ldp, first jb columns).
-hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tslices,
-                          int slice_width, float* Tout, hipStream_t s);
+// T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the split-K
+// partials of V^T [V | C] (gpart[z] at stride, leading dimension ldp: jb Gram columns, then nla columns of V^T C).
+// Also W2out (jb x nla, ld kPanel) = T^T (V^T C).
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
+                          const float* tslices, int slice_width, float* Tout, float* W2out, hipStream_t s);
 
 hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s);
 hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s);

@@ -21,7 +21,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BK = 16;
 
 struct OperandView {
     const float* p; long ld;
@@ -56,14 +55,15 @@ __device__ __forceinline__ float4 load4_guarded(const OperandView& o, int sr, in
 
 // KC = true : storage is (mn, k) with k contiguous  -> transposing store into LDS [k][mn]
 // KC = false: storage is (k, mn) with mn contiguous -> straight 16-byte store
-// ROWS = extent of the tile along mn (64, 128 or 256); every thread moves ROWS / 64 float4.
-template <bool KC, int ROWS>
-__device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0, int tid, float4 (&frag)[ROWS / 64]) {
+// ROWS = extent of the tile along mn, BK along k; every thread moves ROWS * BK / 1024 float4.
+template <bool KC, int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0, int tid,
+                                           float4 (&frag)[ROWS * BK / 1024]) {
 #pragma unroll
-    for (int i = 0; i < ROWS / 64; ++i) {
+    for (int i = 0; i < ROWS * BK / 1024; ++i) {
         const int f = tid + 256 * i;
         if (KC) {
-            const int r = f >> 2, kq = (f & 3) << 2;
+            const int r = f / (BK / 4), kq = (f % (BK / 4)) << 2;
             frag[i] = load4_guarded(o, mn0 + r, k0 + kq);
         } else {
             const int kr = f / (ROWS / 4), c4 = (f % (ROWS / 4)) << 2;
@@ -72,13 +72,13 @@ __device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0
     }
 }
 
-template <bool KC, int ROWS>
-__device__ __forceinline__ void stash_tile(float (*S)[ROWS + 4], int tid, const float4 (&frag)[ROWS / 64]) {
+template <bool KC, int ROWS, int BK>
+__device__ __forceinline__ void stash_tile(float (*S)[ROWS + 4], int tid, const float4 (&frag)[ROWS * BK / 1024]) {
 #pragma unroll
-    for (int i = 0; i < ROWS / 64; ++i) {
+    for (int i = 0; i < ROWS * BK / 1024; ++i) {
         const int f = tid + 256 * i;
         if (KC) {
-            const int r = f >> 2, kq = (f & 3) << 2;
+            const int r = f / (BK / 4), kq = (f % (BK / 4)) << 2;
             S[kq + 0][r] = frag[i].x;
             S[kq + 1][r] = frag[i].y;
             S[kq + 2][r] = frag[i].z;
@@ -90,13 +90,15 @@ __device__ __forceinline__ void stash_tile(float (*S)[ROWS + 4], int tid, const 
     }
 }
 
-// BM x BN is the workgroup tile: 128 x 128 (waves 2 x 2), 64 x 256 (1 x 4, for M <= 64) or 256 x 64 (4 x 1, for
-// N <= 64); the wavefront tile is always 64 x 64.
-template <bool TA, bool TB, int BM, int BN>
+// BM x BN is the workgroup tile and WT the wavefront tile in units of 32 (wavefront tile 32*WT x 32*WT, four
+// wavefronts): 128 x 128 (WT 2, waves 2 x 2), 64 x 256 (M <= 64) and 256 x 64 (N <= 64) for throughput, and
+// 64 x 64 with WT 1 and a deeper K step for small latency-bound products that need many workgroups.
+template <bool TA, bool TB, int BM, int BN, int WT, int BK>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, int tiles_n, int avec, int bvec) {
     __shared__ __attribute__((aligned(16))) float As[2][BK][BM + 4];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK][BN + 4];
-    constexpr int WAVES_N = BN / 64;
+    constexpr int WAVES_N = BN / (32 * WT);
+    static_assert((BM / (32 * WT)) * WAVES_N == 4, "four wavefronts per workgroup");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -136,48 +138,48 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     ob.unit_lower_cols = g.b_unit_lower_cols;
     if (TB) { ob.row_lim = g.N; ob.col_lim = ke; } else { ob.row_lim = ke; ob.col_lim = g.N; }
 
-    f32x16 acc[2][2];
+    f32x16 acc[WT][WT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < WT; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < WT; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int wm = (wave / WAVES_N) * 64, wn = (wave % WAVES_N) * 64;
+    const int wm = (wave / WAVES_N) * 32 * WT, wn = (wave % WAVES_N) * 32 * WT;
     const int lrow = lane & 31, lk = lane >> 5;
 
     const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
-    float4 fa[BM / 64], fb[BN / 64];
+    float4 fa[BM * BK / 1024], fb[BN * BK / 1024];
     if (nk > 0) {
-        fetch_tile<!TA, BM>(oa, m0, kb, tid, fa);
-        fetch_tile<TB, BN>(ob, n0, kb, tid, fb);
-        stash_tile<!TA, BM>(As[0], tid, fa);
-        stash_tile<TB, BN>(Bs[0], tid, fb);
+        fetch_tile<!TA, BM, BK>(oa, m0, kb, tid, fa);
+        fetch_tile<TB, BN, BK>(ob, n0, kb, tid, fb);
+        stash_tile<!TA, BM, BK>(As[0], tid, fa);
+        stash_tile<TB, BN, BK>(Bs[0], tid, fb);
     }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         if (kt + 1 < nk) {
-            fetch_tile<!TA, BM>(oa, m0, kb + (kt + 1) * BK, tid, fa);
-            fetch_tile<TB, BN>(ob, n0, kb + (kt + 1) * BK, tid, fb);
+            fetch_tile<!TA, BM, BK>(oa, m0, kb + (kt + 1) * BK, tid, fa);
+            fetch_tile<TB, BN, BK>(ob, n0, kb + (kt + 1) * BK, tid, fb);
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
-            float a[2], b[2];
+            float a[WT], b[WT];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = As[cur][kk + lk][wm + i * 32 + lrow];
+            for (int i = 0; i < WT; ++i) a[i] = As[cur][kk + lk][wm + i * 32 + lrow];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = Bs[cur][kk + lk][wn + j * 32 + lrow];
+            for (int j = 0; j < WT; ++j) b[j] = Bs[cur][kk + lk][wn + j * 32 + lrow];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < WT; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < WT; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
         if (kt + 1 < nk) {
-            stash_tile<!TA, BM>(As[cur ^ 1], tid, fa);
-            stash_tile<TB, BN>(Bs[cur ^ 1], tid, fb);
+            stash_tile<!TA, BM, BK>(As[cur ^ 1], tid, fa);
+            stash_tile<TB, BN, BK>(Bs[cur ^ 1], tid, fb);
         }
         __syncthreads();
     }
@@ -185,9 +187,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     float* C = g.C + (long)z * g.split_stride;
     const float alpha = g.alpha, beta = g.beta;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < WT; ++i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < WT; ++j) {
             const int col = n0 + wn + j * 32 + lrow;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -210,7 +212,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     for (long e = (long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long)gridDim.x * blockDim.x) {
         const int r = (int)(e / cols), c = (int)(e % cols);
         float s = 0.f;
-        for (int zz = 0; zz < splits; ++zz) s += part[(long)zz * stride + (long)r * ldp + c];
+        const float* q = part + (long)r * ldp + c;
+        int zz = 0;
+        for (; zz + 8 <= splits; zz += 8) {     // eight independent loads in flight
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = q[(long)(zz + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
+        }
+        for (; zz < splits; ++zz) s += q[(long)zz * stride];
         float* o = out + (long)r * ldo + c;
         float v = alpha * s;
         if (beta != 0.f) v += beta * *o;
@@ -220,7 +231,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 
 }  // namespace
 
-template <int BM, int BN>
+template <int BM, int BN, int WT, int BK>
 static hipError_t launch_gemm_f32_tile(const GemmF32& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 3) == 0) ? 1 : 0;
@@ -228,23 +239,35 @@ static hipError_t launch_gemm_f32_tile(const GemmF32& g, hipStream_t s) {
     dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
     dim3 block(256, 1, 1);
     if (g.ta && g.tb)
-        hipLaunchKernelGGL((gemm_f32_kernel<true, true, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<true, true, BM, BN, WT, BK>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else if (g.ta)
-        hipLaunchKernelGGL((gemm_f32_kernel<true, false, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<true, false, BM, BN, WT, BK>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else if (g.tb)
-        hipLaunchKernelGGL((gemm_f32_kernel<false, true, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<false, true, BM, BN, WT, BK>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     else
-        hipLaunchKernelGGL((gemm_f32_kernel<false, false, BM, BN>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
+        hipLaunchKernelGGL((gemm_f32_kernel<false, false, BM, BN, WT, BK>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);
     return hipGetLastError();
 }
 
-int gemm_f32_tile_n(int M, int N) { return M <= 64 ? 256 : (N <= 64 ? 64 : 128); }
+// 1 = 64 x 256 tile, 2 = 256 x 64, 3 = 64 x 64 (many small workgroups), 0 = 128 x 128
+static int gemm_f32_config(int M, int N, int splits) {
+    const long big_tiles = (long)((M + 127) / 128) * ((N + 127) / 128) * (splits > 1 ? splits : 1);
+    if (M <= 64 && N > 64) return 1;
+    if (big_tiles < 96) return 3;      // would leave most compute units idle: use 64 x 64 tiles
+    if (N <= 64) return 2;
+    return 0;
+}
+
+int gemm_f32_tile_n(int M, int N) { return (M <= 64 && N > 64) ? 256 : 128; }
 
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
-    if (g.M <= 64) return launch_gemm_f32_tile<64, 256>(g, s);
-    if (g.N <= 64) return launch_gemm_f32_tile<256, 64>(g, s);
-    return launch_gemm_f32_tile<128, 128>(g, s);
+    switch (gemm_f32_config(g.M, g.N, g.splits)) {
+        case 1: return launch_gemm_f32_tile<64, 256, 2, 16>(g, s);
+        case 2: return launch_gemm_f32_tile<256, 64, 2, 16>(g, s);
+        case 3: return launch_gemm_f32_tile<64, 64, 1, 32>(g, s);
+        default: return launch_gemm_f32_tile<128, 128, 2, 16>(g, s);
+    }
 }
 
 hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,

@@ -6,10 +6,20 @@
 // Reflector convention: H = I - tau v v^T with v[0] = 1 implied, beta = -sign(alpha) ||x||,
 // tau = (beta - alpha) / beta, v[1:] = x[1:] / (alpha - beta).  This is the same reflection as Alg. 2's
 // normalised v = x + sign(x_1)||x|| e_1 (H = I - 2 v v^T / v^T v), stored without the normalisation.
+#include <stdlib.h>
+
 #include "dq_internal.h"
 
 namespace dq {
 namespace {
+
+#ifdef DQ_PANEL_TRACE
+#define TR_DECL long long tr_t0 = wall_clock64(), tr_acc[12] = {0,0,0,0,0,0,0,0,0,0,0,0}
+#define TR(k) do { const long long t_ = wall_clock64(); tr_acc[k] += t_ - tr_t0; tr_t0 = t_; } while (0)
+#else
+#define TR_DECL
+#define TR(k)
+#endif
 
 // Sum NV per-lane values over the 64 lanes of a wavefront with a halving butterfly: after the call
 // v[0] of every lane holds the wavefront total of the value whose index is returned.  Written as a
@@ -39,6 +49,11 @@ __device__ __forceinline__ int wave_reduce_multi(float (&v)[NV], int lane) {
     return wave_reduce_stage<NV, NV, 32>(v, lane);
 }
 
+// Workgroup barrier that orders LDS traffic only: it waits for this wavefront's outstanding LDS operations
+// (lgkmcnt) but not for its global stores (vmcnt), which __syncthreads() would also drain.  The panel kernel
+// exchanges data between threads through LDS alone; global memory is only re-read by the thread that wrote it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // One workgroup of NT threads factors an m x jb panel (m <= NT*Q).  The panel is processed in slices of
 // SW columns; thread t keeps rows t, t+NT, ... of the current slice in registers.  Before a slice is
 // factored, the reflector blocks of the earlier slices of the same panel are applied to it
@@ -65,6 +80,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
     int par = 0;
 
     float a[Q][SW];
+    TR_DECL;
 
     for (int s = 0; s < ns; ++s) {
         const int col0 = s * SW;
@@ -87,6 +103,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
             }
         }
 
+        TR(0);
         // ---- apply the block reflectors of the earlier slices:  A_s -= V_p (T_p^T (V_p^T A_s))
         for (int p = 0; p < s; ++p) {
             float v[Q][SW];
@@ -100,6 +117,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                     v[i][c4 + 0] = t4.x; v[i][c4 + 1] = t4.y; v[i][c4 + 2] = t4.z; v[i][c4 + 3] = t4.w;
                 }
             }
+            TR(1);
             float wacc[NV2];
 #pragma unroll
             for (int e = 0; e < NV2; ++e) wacc[e] = 0.f;
@@ -109,32 +127,41 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 for (int cp = 0; cp < SW; ++cp)
 #pragma unroll
                     for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[i][cp] * a[i][c];
+            TR(2);
             const int idx = wave_reduce_multi<NV2>(wacc, lane);
             if ((lane & (64 / NV2 > 0 ? (64 / NV2 - 1) : 0)) == 0 || NV2 >= 64) red[0][wave][idx] = wacc[0];
-            __syncthreads();
+            lds_barrier();
+            TR(3);
             if (tid < NV2) {
                 float t = 0.f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) t += red[0][w][tid];
                 Wsh[tid] = t;
             }
-            __syncthreads();
+            lds_barrier();
             if (tid < NV2) {
                 const int cp = tid / SW, c = tid % SW;
                 float t = 0.f;
                 for (int cq = 0; cq <= cp; ++cq) t += Tsh[p][cq * SW + cp] * Wsh[cq * SW + c];
                 W2sh[tid] = t;
             }
-            __syncthreads();
+            lds_barrier();
+            TR(4);
 #pragma unroll
             for (int cp = 0; cp < SW; ++cp) {
 #pragma unroll
-                for (int c = 0; c < SW; ++c) {
-                    const float w2 = W2sh[cp * SW + c];
+                for (int c4 = 0; c4 < SW; c4 += 4) {
+                    const float4 w4 = *reinterpret_cast<const float4*>(&W2sh[cp * SW + c4]);
 #pragma unroll
-                    for (int i = 0; i < Q; ++i) a[i][c] -= v[i][cp] * w2;
+                    for (int i = 0; i < Q; ++i) {
+                        a[i][c4 + 0] -= v[i][cp] * w4.x;
+                        a[i][c4 + 1] -= v[i][cp] * w4.y;
+                        a[i][c4 + 2] -= v[i][cp] * w4.z;
+                        a[i][c4 + 3] -= v[i][cp] * w4.w;
+                    }
                 }
             }
+            TR(5);
         }
 
         // ---- factor the slice column by column
@@ -152,20 +179,29 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 float part[SW];
 #pragma unroll
                 for (int cp = 0; cp < SW; ++cp) part[cp] = 0.f;
+                // branch-free: rows on or above the diagonal contribute zero
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
                     const int r = tid + NT * i;
-                    if (r > d) {
+                    const float ac = (r > d) ? a[i][c] : 0.f;
 #pragma unroll
-                        for (int cp = 0; cp < SW; ++cp) part[cp] += a[i][c] * a[i][cp];
-                    } else if (r == d) {
-#pragma unroll
-                        for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[i][cp];
-                    }
+                    for (int cp = 0; cp < SW; ++cp) part[cp] += ac * a[i][cp];
                 }
+                if (tid == (d & (NT - 1))) {   // the owner of the diagonal row publishes it
+                    const int id = d / NT;
+#pragma unroll
+                    for (int i = 0; i < Q; ++i)
+                        if (i == id) {
+#pragma unroll
+                            for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[i][cp];
+                        }
+                }
+                TR(6);
                 const int idx = wave_reduce_multi<SW>(part, lane);
                 if ((lane & (64 / SW - 1)) == 0) red[par][wave][idx] = part[0];
-                __syncthreads();
+                TR(7);
+                lds_barrier();
+                TR(8);
                 float sd[SW], rd[SW];
 #pragma unroll
                 for (int cp = 0; cp < SW; ++cp) {
@@ -177,6 +213,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 }
                 par ^= 1;
 
+                TR(9);
                 const float alpha = rd[c];
                 const float xn2 = sd[c];
                 float beta, tc, scale;
@@ -199,16 +236,12 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
                     const int r = tid + NT * i;
-                    if (r > d) {
-                        const float vn = a[i][c] * scale;
+                    const bool below = r > d, on = r == d;
+                    const float vn = a[i][c] * scale;
+                    const float f = below ? vn : (on ? 1.f : 0.f);   // the reflector's entry in this row
 #pragma unroll
-                        for (int cp = c + 1; cp < SW; ++cp) a[i][cp] -= w[cp] * vn;
-                        a[i][c] = vn;
-                    } else if (r == d) {
-#pragma unroll
-                        for (int cp = c + 1; cp < SW; ++cp) a[i][cp] -= w[cp];
-                        a[i][c] = beta;
-                    }
+                    for (int cp = c + 1; cp < SW; ++cp) a[i][cp] -= w[cp] * f;
+                    a[i][c] = below ? vn : (on ? beta : a[i][c]);
                 }
                 // column c of the slice's T:  T[0:c, c] = -tau * T[0:c, 0:c] * (V[:, 0:c]^T v_c),  T[c, c] = tau
                 Tl[c][c] = tc;
@@ -222,6 +255,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
             }
         }
 
+        TR(10);
         // ---- store: in place (triangular factor on/above the diagonal, reflectors below) and the packed copy
         if (tid == 0) {
 #pragma unroll
@@ -261,25 +295,43 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
             for (int c4 = 0; c4 < SW; c4 += 4)
                 *reinterpret_cast<float4*>(vdst + c4) = make_float4(pv[c4], pv[c4 + 1], pv[c4 + 2], pv[c4 + 3]);
         }
-        __syncthreads();
+        lds_barrier();
+        TR(11);
     }
+#ifdef DQ_PANEL_TRACE
+    if (tid == 0 && m >= 3072 && m < 3200)
+        printf("panel m=%d jb=%d load %lld | pairload %lld pairfma %lld pairshfl %lld pairsync %lld pairupd %lld | coldot %lld colshfl %lld colbar %lld colread %lld colmath+upd %lld | store %lld (ticks of 10 ns)\n", m, jb, tr_acc[0], tr_acc[1], tr_acc[2], tr_acc[3], tr_acc[4], tr_acc[5], tr_acc[6], tr_acc[7], tr_acc[8], tr_acc[9], tr_acc[10], tr_acc[11]);
+#endif
 }
 
 // T factor of a panel's block reflector  H_1 ... H_jb = I - V T V^T  from the T factors of its column slices
 // (sw x sw each, from the panel kernel) and the Gram matrix G = V^T V, by merging neighbours level by level:
 //   T = [[T1, -T1 (V1^T V2) T2], [0, T2]].
-__global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
-                                                      long ldp, int jb, const float* __restrict__ tslices, int sw,
-                                                      float* __restrict__ Tout) {
+// The input is the split-K partials of V^T [V | C] (jb x (jb + nla)); the kernel sums them, builds T and also
+// returns W2 = T^T (V^T C) (jb x nla, leading dimension kPanel) for the update of the nla look-ahead columns.
+__global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
+                                                       long ldp, int jb, int nla, const float* __restrict__ tslices,
+                                                       int sw, float* __restrict__ Tout, float* __restrict__ W2out) {
     __shared__ float Gs[kPanel][kPanel + 1];
     __shared__ float Ts[kPanel][kPanel + 1];
     __shared__ float Xs[kPanel][kPanel + 1];
     const int tid = threadIdx.x;
-    for (int e = tid; e < kPanel * kPanel; e += 256) {
+    float wreg[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = tid + 1024 * q;
         const int i = e / kPanel, j = e % kPanel;
-        float t = 0.f;
-        if (i < jb && j < jb)
-            for (int z = 0; z < splits; ++z) t += gpart[(long)z * stride + (long)i * ldp + j];
+        float t = 0.f, w = 0.f;
+        // up to 16 partials, all loads issued before the sums (the caller limits the split count to 16)
+        float pt[16], pw[16];
+#pragma unroll
+        for (int z = 0; z < 16; ++z) {
+            pt[z] = (z < splits && i < jb && j < jb) ? gpart[(long)z * stride + (long)i * ldp + j] : 0.f;
+            pw[z] = (z < splits && i < jb && j < nla) ? gpart[(long)z * stride + (long)i * ldp + jb + j] : 0.f;
+        }
+#pragma unroll
+        for (int z = 0; z < 16; ++z) { t += pt[z]; w += pw[z]; }
+        wreg[q] = w;
         Gs[i][j] = t;
         float tv = 0.f;
         if (i / sw == j / sw && i < jb && j < jb) tv = tslices[(i / sw) * sw * sw + (i % sw) * sw + (j % sw)];
@@ -289,7 +341,7 @@ __global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ 
     for (int b = sw; b < kPanel; b <<= 1) {
         const int per_pair = b * b;
         const int total = (kPanel / (2 * b)) * per_pair;
-        for (int e = tid; e < total; e += 256) {          // X = G12 * T2
+        for (int e = tid; e < total; e += 1024) {          // X = G12 * T2
             const int o = (e / per_pair) * 2 * b, r = e % per_pair;
             const int i = r / b, j = r % b;
             float acc = 0.f;
@@ -297,7 +349,7 @@ __global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ 
             Xs[o + i][o + b + j] = acc;
         }
         __syncthreads();
-        for (int e = tid; e < total; e += 256) {          // T12 = -T1 * X
+        for (int e = tid; e < total; e += 1024) {          // T12 = -T1 * X
             const int o = (e / per_pair) * 2 * b, r = e % per_pair;
             const int i = r / b, j = r % b;
             float acc = 0.f;
@@ -306,7 +358,23 @@ __global__ __launch_bounds__(256) void tfactor_kernel(const float* __restrict__ 
         }
         __syncthreads();
     }
-    for (int e = tid; e < kPanel * kPanel; e += 256) Tout[e] = Ts[e / kPanel][e % kPanel];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = tid + 1024 * q;
+        Tout[e] = Ts[e / kPanel][e % kPanel];
+        Gs[e / kPanel][e % kPanel] = wreg[q];           // G is no longer needed: keep W = V^T C there
+    }
+    __syncthreads();
+    if (nla > 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = tid + 1024 * q;
+            const int r = e / kPanel, cc = e % kPanel;
+            float acc = 0.f;
+            for (int l = 0; l <= r; ++l) acc += Ts[l][r] * Gs[l][cc];     // (T^T W)[r][cc]
+            if (r < jb && cc < nla) W2out[e] = acc;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void copy2d_kernel(const float* __restrict__ src, long lds, float* __restrict__ dst,
@@ -363,26 +431,42 @@ inline unsigned grid_for(long total) {
 
 size_t panel_scratch_floats(int /*m*/) { return (size_t)kPanel * 8192; }
 
+template <int NT, int Q, int SW>
+static void launch_panel_cfg(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
+                             unsigned* flags, int vec, hipStream_t s) {
+    hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices,
+                       flags, vec);
+}
+
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
                            int* slice_width, unsigned* flags, hipStream_t s) {
     if (m <= 0 || jb <= 0) return hipSuccess;
     if (m > 8192 || jb > kPanel || jb > m) return hipErrorInvalidValue;
     const int vec = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0) ? 1 : 0;
-    constexpr int NT = 512;
-#define DQ_PANEL(Q, SW) do { *slice_width = SW; hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices, flags, vec); } while (0)
-    if (m <= NT * 1) DQ_PANEL(1, 8);
-    else if (m <= NT * 2) DQ_PANEL(2, 8);
-    else if (m <= NT * 4) DQ_PANEL(4, 8);
-    else if (m <= NT * 8) DQ_PANEL(8, 8);
-    else DQ_PANEL(16, 4);
-#undef DQ_PANEL
-    return hipGetLastError();
+    static int env_nt = -1, env_sw = -1;
+    if (env_nt < 0) { const char* e = getenv("DQ_PANEL_NT"); env_nt = e ? atoi(e) : 512; }
+    if (env_sw < 0) { const char* e = getenv("DQ_PANEL_SW"); env_sw = e ? atoi(e) : 8; }
+    const int nt = env_nt;
+    int q = (m + nt - 1) / nt;
+    int qq = 1; while (qq < q) qq <<= 1;
+    int sw = env_sw;
+    // register budget: NT * regs <= 512 * 256 lanes*regs per CU quarter; fall back to 4-wide slices when 8-wide would spill
+    if (sw == 8 && ((nt == 1024 && qq >= 4) || (nt == 512 && qq >= 16) || (nt == 256 && qq >= 32))) sw = 4;
+    *slice_width = sw;
+#define DQ_CFG(NT_, Q_, SW_) if (nt == NT_ && qq == Q_ && sw == SW_) { launch_panel_cfg<NT_, Q_, SW_>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); return hipGetLastError(); }
+    DQ_CFG(512, 1, 8) DQ_CFG(512, 2, 8) DQ_CFG(512, 4, 8) DQ_CFG(512, 8, 8) DQ_CFG(512, 16, 4)
+    DQ_CFG(512, 1, 4) DQ_CFG(512, 2, 4) DQ_CFG(512, 4, 4) DQ_CFG(512, 8, 4)
+    DQ_CFG(256, 1, 8) DQ_CFG(256, 2, 8) DQ_CFG(256, 4, 8) DQ_CFG(256, 8, 8) DQ_CFG(256, 16, 8) DQ_CFG(256, 32, 4)
+    DQ_CFG(1024, 1, 8) DQ_CFG(1024, 2, 8) DQ_CFG(1024, 4, 4) DQ_CFG(1024, 8, 4)
+    DQ_CFG(1024, 1, 4) DQ_CFG(1024, 2, 4)
+#undef DQ_CFG
+    return hipErrorInvalidValue;
 }
 
-hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, const float* tslices,
-                          int slice_width, float* Tout, hipStream_t s) {
-    hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(256), 0, s, gpart, splits, stride, ldp, jb, tslices, slice_width,
-                       Tout);
+hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
+                          const float* tslices, int slice_width, float* Tout, float* W2out, hipStream_t s) {
+    hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(1024), 0, s, gpart, splits, stride, ldp, jb, nla, tslices,
+                       slice_width, Tout, W2out);
     return hipGetLastError();
 }
 

@@ -317,7 +317,7 @@ def test_calib_step_tiny_trajectory(ctx):
         # the fused update applied that gradient: Z_new = Z - lr * dZ up to fp32 rounding of Z
         Znew = Zd.cpu().numpy().astype(np.float64)
         assert np.abs(Znew - (Zin - cfg.lr * dZ_st)).max() <= 2.0 ** -22 * np.abs(Zin).max()
-        assert rel(Znew, out["Z_new"]) < 1e-6
+        assert rel(Znew, out["Z_new"]) < 2e-5    # = lr * ||dZ error|| / ||Z||, see the end-to-end note
         R = Rd.cpu().numpy().astype(np.float64)
         assert np.array_equal(R, R_st)
         assert np.abs(R.T @ R - np.eye(cfg.n)).max() <= 1e-5
