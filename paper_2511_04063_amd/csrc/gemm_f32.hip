@@ -252,13 +252,14 @@ static hipError_t launch_gemm_f32_tile(const GemmF32& g, hipStream_t s) {
 // 1 = 64 x 256 tile, 2 = 256 x 64, 3 = 64 x 64 (many small workgroups), 0 = 128 x 128
 static int gemm_f32_config(int M, int N, int splits) {
     const long big_tiles = (long)((M + 127) / 128) * ((N + 127) / 128) * (splits > 1 ? splits : 1);
+    if (big_tiles < 96 && N <= 128) return 3;   // few output tiles: 64 x 64 tiles give more workgroups
     if (M <= 64 && N > 64) return 1;
     if (big_tiles < 96) return 3;      // would leave most compute units idle: use 64 x 64 tiles
     if (N <= 64) return 2;
     return 0;
 }
 
-int gemm_f32_tile_n(int M, int N) { return (M <= 64 && N > 64) ? 256 : 128; }
+int gemm_f32_tile_n(int M, int N) { return N <= 128 ? 64 : ((M <= 64) ? 256 : 128); }
 
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;

@@ -312,10 +312,13 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
                                                        long ldp, int jb, int nla, const float* __restrict__ tslices,
                                                        int sw, float* __restrict__ Tout, float* __restrict__ W2out) {
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
     __shared__ float Gs[kPanel][kPanel + 1];
     __shared__ float Ts[kPanel][kPanel + 1];
     __shared__ float Xs[kPanel][kPanel + 1];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
     float wreg[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -338,7 +341,8 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         Ts[i][j] = tv;
     }
     __syncthreads();
-    for (int b = sw; b < kPanel; b <<= 1) {
+    // levels below 32: plain loops (a few hundred short dot products)
+    for (int b = sw; b < 32; b <<= 1) {
         const int per_pair = b * b;
         const int total = (kPanel / (2 * b)) * per_pair;
         for (int e = tid; e < total; e += 1024) {          // X = G12 * T2
@@ -358,6 +362,30 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         }
         __syncthreads();
     }
+    // level 32 -> 64 on the matrix cores (one wavefront, two 32 x 32 x 32 products):
+    //   X = G[0:32, 32:64] * T[32:64, 32:64],   T[0:32, 32:64] = -T[0:32, 0:32] * X
+    if (wave == 0) {
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Gs[lrow][32 + kk + lk], Ts[32 + kk + lk][32 + lrow], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Xs[8 * (v >> 2) + 4 * lk + (v & 3)][32 + lrow] = acc[v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ts[lrow][kk + lk], Xs[kk + lk][32 + lrow], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) Ts[8 * (v >> 2) + 4 * lk + (v & 3)][32 + lrow] = -acc[v];
+    }
+    __syncthreads();
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int e = tid + 1024 * q;
@@ -365,14 +393,20 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         Gs[e / kPanel][e % kPanel] = wreg[q];           // G is no longer needed: keep W = V^T C there
     }
     __syncthreads();
-    if (nla > 0) {
+    // W2 = T^T W (64 x 64 x 64) on the matrix cores: wavefronts 0..3 take one 32 x 32 tile each.
+    // A operand: (T^T)[m][k] = Ts[k][m];  B operand: W[k][n] = Gs[k][n].
+    if (nla > 0 && wave < 4) {
+        const int m0 = (wave >> 1) * 32, n0 = (wave & 1) * 32;
+        f32x16 acc;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = tid + 1024 * q;
-            const int r = e / kPanel, cc = e % kPanel;
-            float acc = 0.f;
-            for (int l = 0; l <= r; ++l) acc += Ts[l][r] * Gs[l][cc];     // (T^T W)[r][cc]
-            if (r < jb && cc < nla) W2out[e] = acc;
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < kPanel; kk += 2)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(Ts[kk + lk][m0 + lrow], Gs[kk + lk][n0 + lrow], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = m0 + 8 * (v >> 2) + 4 * lk + (v & 3), cc = n0 + lrow;
+            if (r < jb && cc < nla) W2out[r * kPanel + cc] = acc[v];
         }
     }
 }
