@@ -21,32 +21,80 @@ namespace {
 #define TR(k)
 #endif
 
-// Sum NV per-lane values over the 64 lanes of a wavefront with a halving butterfly: after the call
-// v[0] of every lane holds the wavefront total of the value whose index is returned.  Written as a
-// compile-time recursion so that every register index is static.
-template <int NV, int N, int OFF>
-__device__ __forceinline__ int wave_reduce_stage(float (&v)[NV], int lane) {
-    if constexpr (N > 1) {
-        constexpr int half = N / 2;
-        const bool up = (lane & OFF) != 0;
-#pragma unroll
-        for (int k = 0; k < half; ++k) {
-            const float keep = up ? v[k + half] : v[k];
-            const float send = up ? v[k] : v[k + half];
-            v[k] = keep + __shfl_xor(send, OFF);
-        }
-        return (up ? half : 0) + wave_reduce_stage<NV, half, OFF / 2>(v, lane);
-    } else if constexpr (OFF >= 1) {
-        v[0] += __shfl_xor(v[0], OFF);
-        return wave_reduce_stage<NV, 1, OFF / 2>(v, lane);
+// Value of lane (l ^ OFF) for OFF in {1, 2, 4, 8, 16, 32}.  Distances inside a row of 16 lanes use DPP
+// (quad_perm for 1 and 2, row_ror:8 for 8, a row_shl:4 / row_shr:4 pair masked by bank for 4), distance 16 uses
+// ds_swizzle in bit mode, distance 32 the LDS permute.
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float v) {
+    const int x = __float_as_int(v);
+    int r;
+    if constexpr (OFF == 1) {
+        r = __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false);          // quad_perm:[1,0,3,2]
+    } else if constexpr (OFF == 2) {
+        r = __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false);          // quad_perm:[2,3,0,1]
+    } else if constexpr (OFF == 8) {
+        r = __builtin_amdgcn_update_dpp(x, x, 0x128, 0xF, 0xF, false);         // row_ror:8
+    } else if constexpr (OFF == 4) {
+        r = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xF, 0x5, false);         // row_shl:4 into banks 0 and 2
+        r = __builtin_amdgcn_update_dpp(r, x, 0x114, 0xF, 0xA, false);         // row_shr:4 into banks 1 and 3
+    } else if constexpr (OFF == 16) {
+        r = __builtin_amdgcn_ds_swizzle(x, 0x401F);                            // bit mode: xor 16
     } else {
-        return 0;
+        return __shfl_xor(v, 32);
     }
+    return __int_as_float(r);
+}
+
+// Sum NV per-lane values over the 64 lanes of a wavefront with a halving butterfly: after the call
+// v[0] of every lane holds the wavefront total of the value whose index is returned.  Stage k pairs lanes that
+// differ in bit kStageOff[k]; the stages that move the most values come first and use the cheapest exchanges.
+// Written as a compile-time recursion so that every register index is static.
+template <int S> struct StageOff;
+template <> struct StageOff<0> { static constexpr int v = 1; };
+template <> struct StageOff<1> { static constexpr int v = 2; };
+template <> struct StageOff<2> { static constexpr int v = 8; };
+template <> struct StageOff<3> { static constexpr int v = 4; };
+template <> struct StageOff<4> { static constexpr int v = 16; };
+template <> struct StageOff<5> { static constexpr int v = 32; };
+
+template <int NV, int N, int S>
+__device__ __forceinline__ int wave_reduce_stage(float (&v)[NV], int lane) {
+    if constexpr (S >= 6) {
+        return 0;
+    } else {
+        constexpr int OFF = StageOff<S>::v;
+        if constexpr (N > 1) {
+            constexpr int half = N / 2;
+            const bool up = (lane & OFF) != 0;
+#pragma unroll
+            for (int k = 0; k < half; ++k) {
+                const float keep = up ? v[k + half] : v[k];
+                const float send = up ? v[k] : v[k + half];
+                v[k] = keep + lane_xor<OFF>(send);
+            }
+            return (up ? half : 0) + wave_reduce_stage<NV, half, S + 1>(v, lane);
+        } else {
+            v[0] += lane_xor<OFF>(v[0]);
+            return wave_reduce_stage<NV, 1, S + 1>(v, lane);
+        }
+    }
+}
+// Lanes whose bits of the non-halving stages are all zero hold one copy of each total: they are the writers.
+template <int NV>
+__device__ __forceinline__ bool wave_reduce_writer(int lane) {
+    int mask = 0, n = NV;
+    if (n > 1) n >>= 1; else mask |= 1;
+    if (n > 1) n >>= 1; else mask |= 2;
+    if (n > 1) n >>= 1; else mask |= 8;
+    if (n > 1) n >>= 1; else mask |= 4;
+    if (n > 1) n >>= 1; else mask |= 16;
+    if (n > 1) n >>= 1; else mask |= 32;
+    return (lane & mask) == 0;
 }
 template <int NV>
 __device__ __forceinline__ int wave_reduce_multi(float (&v)[NV], int lane) {
     static_assert(NV >= 1 && NV <= 64 && (NV & (NV - 1)) == 0, "NV must be a power of two <= 64");
-    return wave_reduce_stage<NV, NV, 32>(v, lane);
+    return wave_reduce_stage<NV, NV, 0>(v, lane);
 }
 
 // Workgroup barrier that orders LDS traffic only: it waits for this wavefront's outstanding LDS operations
@@ -67,6 +115,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
     constexpr int MP = NT * Q;
     constexpr int NV2 = SW * SW;
     constexpr int NS = kPanel / SW;
+    static_assert(NT >= kPanel, "the diagonal rows of a panel must belong to the first row set of each thread");
     __shared__ float red[2][NW][NV2];
     __shared__ float rowd[2][SW];
     __shared__ float Wsh[NV2];
@@ -129,7 +178,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                     for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[i][cp] * a[i][c];
             TR(2);
             const int idx = wave_reduce_multi<NV2>(wacc, lane);
-            if ((lane & (64 / NV2 > 0 ? (64 / NV2 - 1) : 0)) == 0 || NV2 >= 64) red[0][wave][idx] = wacc[0];
+            if (wave_reduce_writer<NV2>(lane)) red[0][wave][idx] = wacc[0];
             lds_barrier();
             TR(3);
             if (tid < NV2) {
@@ -187,18 +236,13 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 #pragma unroll
                     for (int cp = 0; cp < SW; ++cp) part[cp] += ac * a[i][cp];
                 }
-                if (tid == (d & (NT - 1))) {   // the owner of the diagonal row publishes it
-                    const int id = d / NT;
+                if (tid == d) {   // d < kPanel <= NT: the diagonal row is row 0 of thread d; it publishes it
 #pragma unroll
-                    for (int i = 0; i < Q; ++i)
-                        if (i == id) {
-#pragma unroll
-                            for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[i][cp];
-                        }
+                    for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[0][cp];
                 }
                 TR(6);
                 const int idx = wave_reduce_multi<SW>(part, lane);
-                if ((lane & (64 / SW - 1)) == 0) red[par][wave][idx] = part[0];
+                if (wave_reduce_writer<SW>(lane)) red[par][wave][idx] = part[0];
                 TR(7);
                 lds_barrier();
                 TR(8);
@@ -261,14 +305,11 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 #pragma unroll
             for (int x = 0; x < SW; ++x)
 #pragma unroll
-                for (int y = 0; y < SW; ++y) {
-                    Tsh[s][x * SW + y] = Tl[x][y];
-                    tslices[s * NV2 + x * SW + y] = Tl[x][y];
-                }
-#pragma unroll
-            for (int c = 0; c < SW; ++c)
-                if (c < ncs) tau[col0 + c] = tau_l[c];
+                for (int y = 0; y < SW; ++y) Tsh[s][x * SW + y] = Tl[x][y];
         }
+#pragma unroll
+        for (int c = 0; c < SW; ++c)
+            if (tid == 64 + c && c < ncs) tau[col0 + c] = tau_l[c];   // every thread holds the same tau_l
 #pragma unroll
         for (int i = 0; i < Q; ++i) {
             const int r = tid + NT * i;
@@ -279,7 +320,9 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 const int d = col0 + c;
                 pv[c] = (r < m && c < ncs) ? (r > d ? a[i][c] : (r == d ? 1.f : 0.f)) : 0.f;
             }
-            if (r < m) {
+            // Rows below the panel's square top block hold reflector entries only; they reach A through
+            // unpack_reflectors_kernel (full 256-byte rows) instead of 32-byte pieces from here.
+            if (r < m && r < jb) {
                 if (vec && ncs == SW) {
 #pragma unroll
                     for (int c4 = 0; c4 < SW; c4 += 4)
@@ -296,12 +339,35 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 *reinterpret_cast<float4*>(vdst + c4) = make_float4(pv[c4], pv[c4 + 1], pv[c4 + 2], pv[c4 + 3]);
         }
         lds_barrier();
+        if (tid < NV2) tslices[s * NV2 + tid] = Tsh[s][tid];
         TR(11);
     }
 #ifdef DQ_PANEL_TRACE
     if (tid == 0 && m >= 3072 && m < 3200)
         printf("panel m=%d jb=%d load %lld | pairload %lld pairfma %lld pairshfl %lld pairsync %lld pairupd %lld | coldot %lld colshfl %lld colbar %lld colread %lld colmath+upd %lld | store %lld (ticks of 10 ns)\n", m, jb, tr_acc[0], tr_acc[1], tr_acc[2], tr_acc[3], tr_acc[4], tr_acc[5], tr_acc[6], tr_acc[7], tr_acc[8], tr_acc[9], tr_acc[10], tr_acc[11]);
 #endif
+}
+
+// Copies rows jb..m-1 of a factored panel from the packed slice-major copy [slice][row][sw] into the matrix
+// (row-major, lda): one 16-byte piece per thread, consecutive threads along a row.
+__global__ __launch_bounds__(256) void unpack_reflectors_kernel(float* __restrict__ A, long lda, int m, int jb,
+                                                                const float* __restrict__ Vs, int mp, int sw, int vec) {
+    const int c4n = (jb + 3) >> 2;                 // 16-byte pieces per row
+    const long total = (long)(m - jb) * c4n;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = jb + (int)(e / c4n);
+        const int c = (int)(e % c4n) << 2;
+        const float4 v = *reinterpret_cast<const float4*>(Vs + ((long)(c / sw) * mp + r) * sw + (c % sw));
+        float* dst = A + (long)r * lda + c;
+        if (vec && c + 3 < jb) {
+            *reinterpret_cast<float4*>(dst) = v;
+        } else {
+            if (c + 0 < jb) dst[0] = v.x;
+            if (c + 1 < jb) dst[1] = v.y;
+            if (c + 2 < jb) dst[2] = v.z;
+            if (c + 3 < jb) dst[3] = v.w;
+        }
+    }
 }
 
 // T factor of a panel's block reflector  H_1 ... H_jb = I - V T V^T  from the T factors of its column slices
@@ -472,6 +538,17 @@ static void launch_panel_cfg(float* A, long lda, int m, int jb, float* tau, floa
                        flags, vec);
 }
 
+static hipError_t finish_panel(float* A, long lda, int m, int jb, const float* vscratch, int mp, int sw, int vec,
+                               hipStream_t s) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || m <= jb) return e;
+    const long total = (long)(m - jb) * ((jb + 3) / 4);
+    long blocks = (total + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(unpack_reflectors_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A, lda, m, jb, vscratch, mp, sw, vec);
+    return hipGetLastError();
+}
+
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
                            int* slice_width, unsigned* flags, hipStream_t s) {
     if (m <= 0 || jb <= 0) return hipSuccess;
@@ -487,7 +564,7 @@ hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float*
     // register budget: NT * regs <= 512 * 256 lanes*regs per CU quarter; fall back to 4-wide slices when 8-wide would spill
     if (sw == 8 && ((nt == 1024 && qq >= 4) || (nt == 512 && qq >= 16) || (nt == 256 && qq >= 32))) sw = 4;
     *slice_width = sw;
-#define DQ_CFG(NT_, Q_, SW_) if (nt == NT_ && qq == Q_ && sw == SW_) { launch_panel_cfg<NT_, Q_, SW_>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); return hipGetLastError(); }
+#define DQ_CFG(NT_, Q_, SW_) if (nt == NT_ && qq == Q_ && sw == SW_) { launch_panel_cfg<NT_, Q_, SW_>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); return finish_panel(A, lda, m, jb, vscratch, NT_ * Q_, SW_, vec, s); }
     DQ_CFG(512, 1, 8) DQ_CFG(512, 2, 8) DQ_CFG(512, 4, 8) DQ_CFG(512, 8, 8) DQ_CFG(512, 16, 4)
     DQ_CFG(512, 1, 4) DQ_CFG(512, 2, 4) DQ_CFG(512, 4, 4) DQ_CFG(512, 8, 4)
     DQ_CFG(256, 1, 8) DQ_CFG(256, 2, 8) DQ_CFG(256, 4, 8) DQ_CFG(256, 8, 8) DQ_CFG(256, 16, 8) DQ_CFG(256, 32, 4)
