@@ -21,6 +21,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM-side traffic per launch (bytes, fetch + write) of each kernel class on the 7b workload, measured with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the readings of a plain copy kernel; the summary and the
+# commands are in profiles/calib_step_7b_hbm_traffic.txt.  Counters cannot be read from inside this script, so the
+# figures are carried here; other workloads report null.
+MEASURED_TRAFFIC_7B = {
+    "gemm_f32": (10173.2 + 5797.6) * 2 ** 20 / 570.0,
+    "gemm_bf16": (1961.1 + 192.0) * 2 ** 20 / 2.0,
+    "whip": (128.0 + 64.1) * 2 ** 20,
+    "qr_panel": (94.7 + 44.8) * 2 ** 20 / 64.0,
+}
+
 # MI355X published peaks
 PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_valu_tflops": 157.3}
 
@@ -152,7 +163,8 @@ def main():
         achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
         roof = {"bound": "alu", "achieved": achieved, "peak": PEAK["fp32_valu_tflops"], "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_7B.get(names[dominant]) if cfg.name == "7b" else None
+    roof["traffic_unit"] = "bytes per launch (fetch + write), from profiles/calib_step_7b_hbm_traffic.txt"
     roof["kernel"] = names[dominant]
     roof["launches_per_step"] = dom["launches"] / args.steps
     roof["avg_launch_ms"] = avg_ms

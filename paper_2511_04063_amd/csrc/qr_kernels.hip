@@ -118,6 +118,7 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
     static_assert(NT >= kPanel, "the diagonal rows of a panel must belong to the first row set of each thread");
     __shared__ float red[2][NW][NV2];
     __shared__ float rowd[2][SW];
+    __shared__ __attribute__((aligned(16))) float wsd[2][NW][SW];
     __shared__ float Wsh[NV2];
     __shared__ __attribute__((aligned(16))) float W2sh[NV2];
     __shared__ float Tsh[NS][NV2];
@@ -247,14 +248,29 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 lds_barrier();
                 TR(8);
                 float sd[SW], rd[SW];
+                if constexpr (NW * SW == 64) {
+                    // one value per lane: lane l takes wavefront l / SW's partial of dot l % SW; the sum over the
+                    // wavefronts is a 3-stage lane exchange; the SW totals go through a per-wavefront LDS row so that
+                    // every lane can read all of them (same wavefront: no workgroup barrier needed)
+                    float t = red[par][lane / SW][lane % SW];
+                    t += lane_xor<8>(t);
+                    t += lane_xor<16>(t);
+                    t += lane_xor<32>(t);
+                    if (lane < SW) wsd[par][wave][lane] = t;
+                    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                for (int cp = 0; cp < SW; ++cp) {
-                    float t = 0.f;
+                    for (int cp = 0; cp < SW; ++cp) sd[cp] = wsd[par][wave][cp];
+                } else {
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) t += red[par][w][cp];
-                    sd[cp] = t;
-                    rd[cp] = rowd[par][cp];
+                    for (int cp = 0; cp < SW; ++cp) {
+                        float t = 0.f;
+#pragma unroll
+                        for (int w = 0; w < NW; ++w) t += red[par][w][cp];
+                        sd[cp] = t;
+                    }
                 }
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp) rd[cp] = rowd[par][cp];
                 par ^= 1;
 
                 TR(9);
@@ -264,10 +280,16 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                 if (xn2 == 0.f) {
                     beta = alpha; tc = 0.f; scale = 0.f;
                 } else {
-                    const float nrm = sqrtf(alpha * alpha + xn2);
+                    // hardware sqrt / reciprocal (1 ulp) with one Newton step on the reciprocals: the factorisation's
+                    // backward error is set by the fp32 updates, not by the last bit of these three scalars
+                    const float nrm = __builtin_amdgcn_sqrtf(alpha * alpha + xn2);
                     beta = alpha >= 0.f ? -nrm : nrm;
-                    tc = (beta - alpha) / beta;
-                    scale = 1.f / (alpha - beta);
+                    float rb = __builtin_amdgcn_rcpf(beta);
+                    rb = rb * (2.f - beta * rb);
+                    tc = (beta - alpha) * rb;
+                    const float dd = alpha - beta;
+                    float rs = __builtin_amdgcn_rcpf(dd);
+                    scale = rs * (2.f - dd * rs);
                 }
                 if (tid == 0) {
                     if (!(fabsf(beta) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
