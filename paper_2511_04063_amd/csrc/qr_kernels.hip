@@ -6,8 +6,6 @@
 // Reflector convention: H = I - tau v v^T with v[0] = 1 implied, beta = -sign(alpha) ||x||,
 // tau = (beta - alpha) / beta, v[1:] = x[1:] / (alpha - beta).  This is the same reflection as Alg. 2's
 // normalised v = x + sign(x_1)||x|| e_1 (H = I - 2 v v^T / v^T v), stored without the normalisation.
-#include <stdlib.h>
-
 #include "dq_internal.h"
 #include "dq_wave.h"
 
@@ -27,7 +25,7 @@ namespace {
 // factored, the reflector blocks of the earlier slices of the same panel are applied to it
 // (left-looking), reading them back from `Vs`, a packed copy [slice][row][SW] with the unit diagonal and
 // the zeros above it written out.  Every thread re-reads only rows it wrote itself.
-template <int NT, int Q, int SW>
+template <int NT, int Q, int SW, int VCH>
 __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, long lda, int m, int jb,
                                                       float* __restrict__ tau, float* Vs, float* __restrict__ tslices,
                                                       unsigned* flags, int vec) {
@@ -76,27 +74,33 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
         TR(0);
         // ---- apply the block reflectors of the earlier slices:  A_s -= V_p (T_p^T (V_p^T A_s))
         for (int p = 0; p < s; ++p) {
-            float v[Q][SW];
-#pragma unroll
-            for (int i = 0; i < Q; ++i) {
-                const int r = tid + NT * i;
-                const float* src = Vs + ((long)p * MP + r) * SW;
-#pragma unroll
-                for (int c4 = 0; c4 < SW; c4 += 4) {
-                    const float4 t4 = *reinterpret_cast<const float4*>(src + c4);
-                    v[i][c4 + 0] = t4.x; v[i][c4 + 1] = t4.y; v[i][c4 + 2] = t4.z; v[i][c4 + 3] = t4.w;
-                }
-            }
-            TR(1);
+            // VCH rows of V_p are held at a time: all of them when they fit the register budget (one read of V_p),
+            // otherwise V_p is streamed twice in chunks (projection, then update).
+            float v[VCH][SW];
             float wacc[NV2];
 #pragma unroll
             for (int e = 0; e < NV2; ++e) wacc[e] = 0.f;
 #pragma unroll
-            for (int i = 0; i < Q; ++i)
+            for (int i0 = 0; i0 < Q; i0 += VCH) {
 #pragma unroll
-                for (int cp = 0; cp < SW; ++cp)
+                for (int ii = 0; ii < VCH; ++ii) {
+                    const int r = tid + NT * (i0 + ii);
+                    const float* src = Vs + ((long)p * MP + r) * SW;
 #pragma unroll
-                    for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[i][cp] * a[i][c];
+                    for (int c4 = 0; c4 < SW; c4 += 4) {
+                        const float4 t4 = *reinterpret_cast<const float4*>(src + c4);
+                        v[ii][c4 + 0] = t4.x; v[ii][c4 + 1] = t4.y; v[ii][c4 + 2] = t4.z; v[ii][c4 + 3] = t4.w;
+                    }
+                }
+                TR(1);
+#pragma unroll
+                for (int ii = 0; ii < VCH; ++ii)
+#pragma unroll
+                    for (int cp = 0; cp < SW; ++cp)
+#pragma unroll
+                        for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[ii][cp] * a[i0 + ii][c];
+                if constexpr (VCH != Q) __builtin_amdgcn_sched_barrier(0);   // keep one chunk of V_p live at a time
+            }
             TR(2);
             const int idx = wave_reduce_multi<NV2>(wacc, lane);
             if (wave_reduce_writer<NV2>(lane)) red[0][wave][idx] = wacc[0];
@@ -118,28 +122,41 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
             lds_barrier();
             TR(4);
 #pragma unroll
-            for (int cp = 0; cp < SW; ++cp) {
+            for (int i0 = 0; i0 < Q; i0 += VCH) {
+                if constexpr (VCH != Q) {
 #pragma unroll
-                for (int c4 = 0; c4 < SW; c4 += 4) {
-                    const float4 w4 = *reinterpret_cast<const float4*>(&W2sh[cp * SW + c4]);
+                    for (int ii = 0; ii < VCH; ++ii) {
+                        const int r = tid + NT * (i0 + ii);
+                        const float* src = Vs + ((long)p * MP + r) * SW;
 #pragma unroll
-                    for (int i = 0; i < Q; ++i) {
-                        a[i][c4 + 0] -= v[i][cp] * w4.x;
-                        a[i][c4 + 1] -= v[i][cp] * w4.y;
-                        a[i][c4 + 2] -= v[i][cp] * w4.z;
-                        a[i][c4 + 3] -= v[i][cp] * w4.w;
+                        for (int c4 = 0; c4 < SW; c4 += 4) {
+                            const float4 t4 = *reinterpret_cast<const float4*>(src + c4);
+                            v[ii][c4 + 0] = t4.x; v[ii][c4 + 1] = t4.y; v[ii][c4 + 2] = t4.z; v[ii][c4 + 3] = t4.w;
+                        }
                     }
                 }
+#pragma unroll
+                for (int cp = 0; cp < SW; ++cp) {
+#pragma unroll
+                    for (int c4 = 0; c4 < SW; c4 += 4) {
+                        const float4 w4 = *reinterpret_cast<const float4*>(&W2sh[cp * SW + c4]);
+#pragma unroll
+                        for (int ii = 0; ii < VCH; ++ii) {
+                            a[i0 + ii][c4 + 0] -= v[ii][cp] * w4.x;
+                            a[i0 + ii][c4 + 1] -= v[ii][cp] * w4.y;
+                            a[i0 + ii][c4 + 2] -= v[ii][cp] * w4.z;
+                            a[i0 + ii][c4 + 3] -= v[ii][cp] * w4.w;
+                        }
+                    }
+                }
+                if constexpr (VCH != Q) __builtin_amdgcn_sched_barrier(0);
             }
             TR(5);
         }
 
         // ---- factor the slice column by column
-        float Tl[SW][SW];
-#pragma unroll
-        for (int x = 0; x < SW; ++x)
-#pragma unroll
-            for (int y = 0; y < SW; ++y) Tl[x][y] = 0.f;
+        if (tid < NV2) Tsh[s][tid] = 0.f;   // the slice's T factor is built in LDS by thread 0 (ordered by the
+                                            // barrier of the first column step)
         float tau_l[SW];
 #pragma unroll
         for (int c = 0; c < SW; ++c) {
@@ -230,25 +247,21 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
                     a[i][c] = below ? vn : (on ? beta : a[i][c]);
                 }
                 // column c of the slice's T:  T[0:c, c] = -tau * T[0:c, 0:c] * (V[:, 0:c]^T v_c),  T[c, c] = tau
-                Tl[c][c] = tc;
+                if (tid == 0) {
+                    Tsh[s][c * SW + c] = tc;
 #pragma unroll
-                for (int cp = 0; cp < c; ++cp) {
-                    float t = 0.f;
+                    for (int cp = 0; cp < c; ++cp) {
+                        float t = 0.f;
 #pragma unroll
-                    for (int cq = cp; cq < c; ++cq) t += Tl[cp][cq] * (rd[cq] + scale * sd[cq]);
-                    Tl[cp][c] = -tc * t;
+                        for (int cq = cp; cq < c; ++cq) t += Tsh[s][cp * SW + cq] * (rd[cq] + scale * sd[cq]);
+                        Tsh[s][cp * SW + c] = -tc * t;
+                    }
                 }
             }
         }
 
         TR(10);
         // ---- store: in place (triangular factor on/above the diagonal, reflectors below) and the packed copy
-        if (tid == 0) {
-#pragma unroll
-            for (int x = 0; x < SW; ++x)
-#pragma unroll
-                for (int y = 0; y < SW; ++y) Tsh[s][x * SW + y] = Tl[x][y];
-        }
 #pragma unroll
         for (int c = 0; c < SW; ++c)
             if (tid == 64 + c && c < ncs) tau[col0 + c] = tau_l[c];   // every thread holds the same tau_l
@@ -473,10 +486,10 @@ inline unsigned grid_for(long total) {
 
 size_t panel_scratch_floats(int /*m*/) { return (size_t)kPanel * (8192 + 64); }
 
-template <int NT, int Q, int SW>
+template <int NT, int Q, int SW, int VCH = Q>
 static void launch_panel_cfg(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
                              unsigned* flags, int vec, hipStream_t s) {
-    hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices,
+    hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW, VCH>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices,
                        flags, vec);
 }
 
@@ -496,24 +509,17 @@ hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float*
     if (m <= 0 || jb <= 0) return hipSuccess;
     if (m > 8192 || jb > kPanel || jb > m) return hipErrorInvalidValue;
     const int vec = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0) ? 1 : 0;
-    static int env_nt = -1, env_sw = -1;
-    if (env_nt < 0) { const char* e = getenv("DQ_PANEL_NT"); env_nt = e ? atoi(e) : 512; }
-    if (env_sw < 0) { const char* e = getenv("DQ_PANEL_SW"); env_sw = e ? atoi(e) : 8; }
-    const int nt = env_nt;
-    int q = (m + nt - 1) / nt;
-    int qq = 1; while (qq < q) qq <<= 1;
-    int sw = env_sw;
-    // register budget: NT * regs <= 512 * 256 lanes*regs per CU quarter; fall back to 4-wide slices when 8-wide would spill
-    if (sw == 8 && ((nt == 1024 && qq >= 4) || (nt == 512 && qq >= 16) || (nt == 256 && qq >= 32))) sw = 4;
+    constexpr int NT = 512;
+    int mp, sw = 8;
+    // rows per thread Q = 1, 2, 4, 8 with 8-column slices; taller panels (m > 4096) use Q = 16 with 4-column slices,
+    // which is what fits the register file (an 8-column slice of 16 rows per thread plus the 64 projection sums spill)
+    if (m <= NT * 1) { launch_panel_cfg<NT, 1, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 1; }
+    else if (m <= NT * 2) { launch_panel_cfg<NT, 2, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 2; }
+    else if (m <= NT * 4) { launch_panel_cfg<NT, 4, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 4; }
+    else if (m <= NT * 8) { launch_panel_cfg<NT, 8, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 8; }
+    else { launch_panel_cfg<NT, 16, 4>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 16; sw = 4; }
     *slice_width = sw;
-#define DQ_CFG(NT_, Q_, SW_) if (nt == NT_ && qq == Q_ && sw == SW_) { launch_panel_cfg<NT_, Q_, SW_>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); return finish_panel(A, lda, m, jb, vscratch, NT_ * Q_, SW_, vec, s); }
-    DQ_CFG(512, 1, 8) DQ_CFG(512, 2, 8) DQ_CFG(512, 4, 8) DQ_CFG(512, 8, 8) DQ_CFG(512, 16, 4)
-    DQ_CFG(512, 1, 4) DQ_CFG(512, 2, 4) DQ_CFG(512, 4, 4) DQ_CFG(512, 8, 4)
-    DQ_CFG(256, 1, 8) DQ_CFG(256, 2, 8) DQ_CFG(256, 4, 8) DQ_CFG(256, 8, 8) DQ_CFG(256, 16, 8) DQ_CFG(256, 32, 4)
-    DQ_CFG(1024, 1, 8) DQ_CFG(1024, 2, 8) DQ_CFG(1024, 4, 4) DQ_CFG(1024, 8, 4)
-    DQ_CFG(1024, 1, 4) DQ_CFG(1024, 2, 4)
-#undef DQ_CFG
-    return hipErrorInvalidValue;
+    return finish_panel(A, lda, m, jb, vscratch, mp, sw, vec, s);
 }
 
 hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
