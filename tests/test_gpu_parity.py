@@ -74,6 +74,12 @@ def test_gemm_f32(ctx, ta, tb, M, N, K):
     assert np.abs(got - ref).max() < 2e-5 * max(1.0, np.abs(ref).max())
     # the padding columns of C were not touched
     assert torch.all(Cbuf[:, N:] == 123.0)
+    # C -= A B has its own accumulator path
+    Cd.copy_(dev(C0))
+    ctx.dq_gemm_f32(M, N, K, -1.0, Ad, ta, Bd, tb, 1.0, Cd)
+    ref2 = C0 - opA @ opB
+    assert rel(Cd.cpu().numpy(), ref2) < 2e-6
+    assert torch.all(Cbuf[:, N:] == 123.0)
 
 
 @pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0), (0, 0), (1, 1)])
