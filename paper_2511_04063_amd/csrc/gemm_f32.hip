@@ -186,6 +186,32 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
 
     float* C = g.C + (long)z * g.split_stride;
     const float alpha = g.alpha, beta = g.beta;
+    // All reads of C are issued before the first write: interleaved they would serialise on possible aliasing and
+    // expose one memory round trip per element.
+    if (beta != 0.f) {
+#pragma unroll
+        for (int i = 0; i < WT; ++i) {
+#pragma unroll
+            for (int j = 0; j < WT; ++j) {
+                const int col = n0 + wn + j * 32 + lrow;
+                float cin[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                    cin[v] = (row < g.M && col < g.N) ? C[(long)row * g.ldc + col] : 0.f;
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = alpha * acc[i][j][v] + beta * cin[v];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+#pragma unroll
+            for (int j = 0; j < WT; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] *= alpha;
+    }
 #pragma unroll
     for (int i = 0; i < WT; ++i) {
 #pragma unroll
@@ -194,12 +220,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < g.M && col < g.N) {
-                    float* c = C + (long)row * g.ldc + col;
-                    float r = alpha * acc[i][j][v];
-                    if (beta != 0.f) r += beta * *c;
-                    *c = r;
-                }
+                if (row < g.M && col < g.N) C[(long)row * g.ldc + col] = acc[i][j][v];
             }
         }
     }

@@ -271,14 +271,17 @@ def test_sgd_update(ctx):
 
 # ----------------------------------------------------------------------------------- whole step
 def gpu_stages(ctx, Xd, xdt, Zd):
-    """loss, R, U, G, dZ of the latent in Zd through the three stage entry points (S1+S2, S3-S5, S6)."""
+    """loss, R, U, G, dZ, Y, dY of the latent in Zd through the three stage entry points (S1+S2, S3-S5, S6)."""
     n = Zd.shape[-1]
+    T = Xd.shape[-2]
     Rd, Ud, Gd, dZd = (torch.empty((n, n), device="cuda") for _ in range(4))
+    Yd = torch.empty((T, n), device="cuda")
+    dYd = torch.empty((T, n), device="cuda", dtype=Xd.dtype)
     loss = torch.zeros(1, device="cuda")
     ctx.dq_qr_orth(Zd, Rd, Ud)
-    ctx.dq_rotate_loss_grad(Xd, xdt, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd)
+    ctx.dq_rotate_loss_grad(Xd, xdt, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd, Yd, dYd)
     ctx.dq_qr_backward(Rd, Ud, Gd, dZd)
-    return (loss.item(),) + tuple(t.cpu().numpy().astype(np.float64) for t in (Rd, Ud, Gd, dZd))
+    return (loss.item(),) + tuple(t.float().cpu().numpy().astype(np.float64) for t in (Rd, Ud, Gd, dZd, Yd, dYd))
 
 
 # End-to-end dZ in fp32 is limited by the conditioning of the chain, not by the kernels.  (i) The forward error
@@ -304,7 +307,7 @@ def test_calib_step_tiny_trajectory(ctx):
     Zo = inp["Z0"][0].astype(np.float64)
     for k in range(cfg.steps):
         Zin = Zd.cpu().numpy().astype(np.float64)
-        loss_st, R_st, U_st, G_st, dZ_st = gpu_stages(ctx, Xd, B.DQ_F32, Zd)
+        loss_st, R_st, U_st, G_st, dZ_st, Y_st, dY_st = gpu_stages(ctx, Xd, B.DQ_F32, Zd)
         ctx.dq_calib_step(Xd, B.DQ_F32, Zd, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss, Rd)
         # the stored fp64 trajectory: the two runs drift apart slowly (see the note above), so the stored
         # values bind only to 1e-3; the same-input comparison below binds to 1e-4 at every step
@@ -314,9 +317,13 @@ def test_calib_step_tiny_trajectory(ctx):
         assert abs(loss.item() - out["loss"]) <= 1e-4 * out["loss"]
         assert loss_st == loss.item()
         # stage by stage, each with the stage's own inputs: the 1e-4 bar with a wide margin
-        lo, Go, _, _ = orc.rotate_loss_grad(X, R_st)
+        # (dY is discontinuous at y = 0, so each stage is fed what the previous GPU stage produced)
+        lo, Go, Yo, _ = orc.rotate_loss_grad(X, R_st)
         assert abs(loss_st - lo) <= 1e-5 * lo
-        assert rel(G_st, Go) < 1e-4
+        assert rel(Y_st, Yo) < 1e-5
+        assert rel(dY_st, orc.whip_grad(Y_st)) < 1e-5
+        assert rel(G_st, orc.grad_wrt_rotation(X, dY_st)) < 1e-4
+        assert rel(G_st, Go) < E2E_DZ_TOL_F32
         assert rel(dZ_st, orc.qr_backward(R_st, U_st, G_st)) < 1e-4
         # end to end
         assert rel(dZ_st, out["dZ"]) < E2E_DZ_TOL_F32
