@@ -62,6 +62,9 @@ typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
 /* bits of the device status word */
 #define DQ_FLAG_SINGULAR   1u   /* a zero appeared on diag(U): Z is singular (dZ undefined)  */
 #define DQ_FLAG_NONFINITE  2u   /* a NaN or Inf was seen in a pivot or in the loss           */
+#define DQ_FLAG_ILLCOND_PANEL 4u /* informational: a tall 64-column panel of the QR was too ill-conditioned for the
+                                   many-CU panel route and was factored by the one-workgroup Householder kernel
+                                   instead; results are valid */
 
 /* ---- context and workspace ---------------------------------------------------------- */
 

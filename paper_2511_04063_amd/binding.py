@@ -17,7 +17,7 @@ DQ_OK = 0
 DQ_ERR_NULL, DQ_ERR_SHAPE, DQ_ERR_DTYPE, DQ_ERR_ALIGN, DQ_ERR_WORKSPACE, DQ_ERR_HIP, DQ_ERR_UNSUPPORTED = range(1, 8)
 DQ_F32, DQ_BF16 = 0, 1
 DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
-DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE = 1, 2
+DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL = 1, 2, 4
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
 DQ_MAX_N = 8192
 

@@ -51,6 +51,8 @@ struct dq_ctx {
     std::vector<hipEvent_t> sync_ev; // 2 per panel: look-ahead part done (even), trailing part done (odd); + 1 join
     int device = 0;
     int nb = kPanel;                 // QR panel width (<= kPanel)
+    int chol_min_m = 512;            // panels at least this tall take the many-CU route (0: never)
+    bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
     char* ws = nullptr;
     size_t ws_bytes = 0;
     Profiler prof;
@@ -62,7 +64,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, qy = 0,
-           vs = 0, tsl = 0, ybuf = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, ybuf = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -97,6 +99,7 @@ Layout make_layout(int n, int T) {
     L.qw = bump(cur, (size_t)n * kPanel * 4);
     L.qy = bump(cur, (size_t)n * kPanel * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
+    L.cq = bump(cur, cholpanel_scratch_floats() * 4);
     L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
     L.ybuf = bump(cur, (size_t)2 * n * kPanel * 4);   // two copies: look-ahead double buffering
     const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
@@ -286,7 +289,8 @@ dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0,
 
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
                       long ldu) {
-    hipStream_t sA = c->stream, sB = c->stream2, sC = c->stream3;
+    hipStream_t sA = c->stream, sB = c->single_stream ? c->stream : c->stream2,
+                sC = c->single_stream ? c->stream : c->stream3;
     float* A = at<float>(c, L.A);
     float* tau = at<float>(c, L.tau);
     float* Tall = at<float>(c, L.Tall);
@@ -315,9 +319,15 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         float* Ap = A + (long)k0 * ld + k0;
         float* Tp = Tall + (long)p * kPanel * kPanel;
         int sw = 8;
+        // Tall full-width panels: CholeskyQR2 + Householder reconstruction over many compute units.  It raises the
+        // device word fb when the panel is too ill-conditioned for it; the one-workgroup Householder panel that
+        // follows is predicated on that word (it runs unconditionally for the other panels).
+        const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
+        unsigned* fb = tall ? flags + 16 : nullptr;
         {
             LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
-            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, sA));
+            if (tall) DQ_HIP(launch_cholqr_panel(Ap, ld, m, Tp, vs, at<float>(c, L.cq), fb, flags, sA));
+            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, fb, sA));
         }
         // the look-ahead columns received update p-1 on the second stream
         if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
@@ -328,7 +338,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa, 16, &splitsA));
         {
             LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 0.0);
-            DQ_HIP(launch_tfactor(bufA.wpart, splitsA, (long)kPanel * ld, ld, jb, nla, tsl, sw, Tp, bufA.wsum, sA));
+            DQ_HIP(launch_tfactor(bufA.wpart, splitsA, (long)kPanel * ld, ld, jb, nla, tsl, sw, Tp, bufA.wsum, fb, sA));
         }
         if (nla > 0) {
             GemmF32 g;   // C_la -= V W2
@@ -538,6 +548,8 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     if (c == nullptr) return DQ_ERR_HIP;
     c->stream = static_cast<hipStream_t>(hip_stream);
     if (const char* e = getenv("DQ_PANEL_NB")) { const int v = atoi(e); if (v >= kPanelMin && v <= kPanel && v % 8 == 0) c->nb = v; }
+    if (const char* e = getenv("DQ_SINGLE_STREAM")) c->single_stream = atoi(e) != 0;
+    if (const char* e = getenv("DQ_TALL_PANEL_MIN_M")) { const int v = atoi(e); if (v >= 0) c->chol_min_m = v; }
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
     // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream
     if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }

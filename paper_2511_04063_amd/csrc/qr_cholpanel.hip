@@ -1,0 +1,670 @@
+// Tall panel factorisation spread over many compute units (a communication-avoiding replacement of the
+// one-workgroup Householder panel for tall m x 64 panels of Alg. 2's blocked form):
+//
+//   1. CholeskyQR, twice:  G = A^T A = U1^T U1,  Q1 = A U1^-1,  G2 = Q1^T Q1 = U2^T U2,  Q = Q1 U2^-1,
+//      Rf = U2 U1  (A = Q Rf, Q orthonormal to rounding when ||G2 - I|| is small; that is checked).
+//   2. Householder reconstruction: with Q_top the first 64 rows of Q, an LU factorisation without pivoting of
+//      Q_top - S (S = diag(s), s_j = -sign of the pivot met at step j, so every pivot has modulus >= 1) gives
+//      Q - [S; 0] = V U_lu with V unit lower trapezoidal.  Then  I - V T V^T  with  T = -U_lu S V_top^-T  maps
+//      [I; 0] S to Q, i.e. A = (I - V T V^T) [S Rf; 0]:  exactly the compact-WY form (V, T) and the triangular
+//      factor S Rf that the Householder panel would hand to the rest of the blocked QR (up to row signs, which
+//      the final sign normalisation removes).
+//
+// Everything that touches the m rows is a tall-skinny product on the matrix cores, spread over m / 128
+// workgroups; the 64 x 64 work (sums of partials, Cholesky, LU, triangular inverses, small products) runs in
+// one workgroup out of LDS.  When the check in step 1 fails (ill-conditioned or rank-deficient panel) the
+// kernels leave the panel untouched and raise a device word; the caller then runs the Householder panel
+// kernel, which is launched predicated on that word.
+#include <stdlib.h>
+
+#include "dq_internal.h"
+
+namespace dq {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int B64 = 64;          // panel width handled here
+constexpr int LS = 65;           // LDS row stride of the 64-column tiles (conflict-free column walks)
+constexpr int RT = 128;          // rows of one tile
+constexpr int NTHR = 256;        // threads per workgroup (4 wavefronts)
+constexpr int NSUM = 512;        // threads of the small-matrix kernels while they sum the partials
+
+#define MFMA32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32((a), (b), (c), 0, 0, 0)
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) z[v] = 0.f;
+    return z;
+}
+
+// rows [row0, row0 + 128) x 64 columns of X (leading dimension ldx, 16-byte aligned rows) -> Xs[r * LS + c];
+// rows >= mrows read as zero.
+__device__ __forceinline__ void load_tile(const float* __restrict__ X, long ldx, int row0, int mrows, float* Xs,
+                                          int tid) {
+    float4 v[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int r = p * 16 + (tid >> 4);
+        const int gr = row0 + r;
+        v[p] = (gr < mrows) ? *reinterpret_cast<const float4*>(X + (long)gr * ldx + 4 * (tid & 15))
+                            : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        float* d = Xs + (p * 16 + (tid >> 4)) * LS + 4 * (tid & 15);
+        d[0] = v[p].x; d[1] = v[p].y; d[2] = v[p].z; d[3] = v[p].w;
+    }
+}
+
+// 64 x 64 matrix (row-major, leading dimension 64) -> Ms[r * 64 + c]
+__device__ __forceinline__ void load_small64(const float* __restrict__ Mg, float* Ms, int tid) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int e = 4 * (tid + NTHR * p);
+        *reinterpret_cast<float4*>(Ms + e) = *reinterpret_cast<const float4*>(Mg + e);
+    }
+}
+
+// acc += (X^T X)[32 qi + ., 32 qj + .] over the 128 rows of the tile
+__device__ __forceinline__ void gram_tile(const float* Xs, f32x16& acc, int qi, int qj, int lrow, int lk) {
+#pragma unroll 8
+    for (int r = 0; r < RT; r += 2) {
+        const float a = Xs[(r + lk) * LS + 32 * qi + lrow];
+        const float b = Xs[(r + lk) * LS + 32 * qj + lrow];
+        acc = MFMA32(a, b, acc);
+    }
+}
+
+__device__ __forceinline__ void store_partial(float* part, const f32x16& acc, int qi, int qj, int lrow, int lk) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int i = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3);
+        part[i * B64 + 32 * qj + lrow] = acc[v];
+    }
+}
+
+// rows [32 wave, 32 wave + 32) of the tile times the upper-triangular 64 x 64 matrix in Ms: two 32 x 32 results
+__device__ __forceinline__ void mul_tile(const float* Xs, const float* Ms, f32x16& acc0, f32x16& acc1, int wave,
+                                         int lrow, int lk) {
+#pragma unroll 8
+    for (int k0 = 0; k0 < 32; k0 += 2) {
+        const float a = Xs[(32 * wave + lrow) * LS + k0 + lk];
+        acc0 = MFMA32(a, Ms[(k0 + lk) * B64 + lrow], acc0);
+        acc1 = MFMA32(a, Ms[(k0 + lk) * B64 + 32 + lrow], acc1);
+    }
+#pragma unroll 8
+    for (int k0 = 32; k0 < 64; k0 += 2) {   // rows >= 32 of an upper-triangular factor only reach columns >= 32
+        const float a = Xs[(32 * wave + lrow) * LS + k0 + lk];
+        acc1 = MFMA32(a, Ms[(k0 + lk) * B64 + 32 + lrow], acc1);
+    }
+}
+
+// part[blockIdx.x] (64 x 64) = sum over this workgroup's rows of A^T A
+__global__ __launch_bounds__(NTHR) void ts_gram_kernel(const float* __restrict__ A, long lda, int m, int tiles_per_wg,
+                                                       float* __restrict__ part) {
+    __shared__ float Xs[RT * LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+    f32x16 acc = zero16();
+    for (int t = 0; t < tiles_per_wg; ++t) {
+        const int row0 = (blockIdx.x * tiles_per_wg + t) * RT;
+        if (row0 >= m) break;
+        if (t > 0) __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        gram_tile(Xs, acc, qi, qj, lrow, lk);
+    }
+    store_partial(part + (long)blockIdx.x * B64 * B64, acc, qi, qj, lrow, lk);
+}
+
+// Q1 = A Minv (written with leading dimension 64) and part[blockIdx.x] = Q1^T Q1 over this workgroup's rows
+__global__ __launch_bounds__(NTHR) void ts_mul_gram_kernel(const float* __restrict__ A, long lda, int m,
+                                                           int tiles_per_wg, const float* __restrict__ Minv,
+                                                           float* __restrict__ Q1, float* __restrict__ part) {
+    __shared__ float Xs[RT * LS];
+    __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+    load_small64(Minv, Ms, tid);
+    f32x16 acc = zero16();
+    for (int t = 0; t < tiles_per_wg; ++t) {
+        const int row0 = (blockIdx.x * tiles_per_wg + t) * RT;
+        if (row0 >= m) break;
+        if (t > 0) __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            Xs[r * LS + lrow] = q0[v];
+            Xs[r * LS + 32 + lrow] = q1[v];
+            if (row0 + r < m) {
+                Q1[(long)(row0 + r) * B64 + lrow] = q0[v];
+                Q1[(long)(row0 + r) * B64 + 32 + lrow] = q1[v];
+            }
+        }
+        __syncthreads();
+        gram_tile(Xs, acc, qi, qj, lrow, lk);
+    }
+    store_partial(part + (long)blockIdx.x * B64 * B64, acc, qi, qj, lrow, lk);
+}
+
+// Out[row_off + r][0:64] = Q1[row_off + r][:] Mm for the rows r >= 0 handled by this workgroup; skipped when *fb != 0.
+__global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ Q1, int m, int row_off,
+                                                      const float* __restrict__ Mm, float* __restrict__ Out, long ldo,
+                                                      const unsigned* __restrict__ fb) {
+    if (*fb != 0u) return;
+    __shared__ float Xs[RT * LS];
+    __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int row0 = row_off + blockIdx.x * RT;
+    load_small64(Mm, Ms, tid);
+    load_tile(Q1, B64, row0, m, Xs, tid);
+    __syncthreads();
+    f32x16 q0 = zero16(), q1 = zero16();
+    mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+        if (r < m) {
+            Out[(long)r * ldo + lrow] = q0[v];
+            Out[(long)r * ldo + 32 + lrow] = q1[v];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// 64 x 64 building blocks in LDS (row stride LS), one workgroup of 256 threads; every function ends with a
+// barrier and must be called by all threads.
+
+// Bm = sum of nparts (<= kCholMaxParts) partials of a symmetric 64 x 64 matrix (contiguous, 4096 floats each);
+// called by NSUM threads.  Only the quadrants on and above the diagonal are read (the lower-left 32 x 32 quadrant
+// of Bm is set to zero): nothing downstream reads below the diagonal.  All loads of a thread are issued before
+// the first add: a single workgroup is bound by latency here, not by bandwidth.
+__device__ __forceinline__ void sum_partials(const float* __restrict__ part, int nparts, float* Bm, int tid) {
+    constexpr int PER = B64 * B64 / NSUM;
+    float s[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) s[q] = 0.f;
+    for (int z0 = 0; z0 < nparts; z0 += 16) {
+        float t[PER][16];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = tid + NSUM * q;
+            const bool used = !((e >> 6) >= 32 && (e & 63) < 32);
+#pragma unroll
+            for (int z = 0; z < 16; ++z)
+                t[q][z] = (used && z0 + z < nparts) ? part[(long)(z0 + z) * B64 * B64 + e] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+#pragma unroll
+            for (int z = 0; z < 16; ++z) s[q] += t[q][z];
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int e = tid + NSUM * q;
+        Bm[(e >> 6) * LS + (e & 63)] = s[q];
+    }
+    __syncthreads();
+}
+
+// In place: the upper triangle of the symmetric positive definite G becomes U with G = U^T U; the strict lower
+// triangle is zeroed.  Blocked by 8: every thread factors the 8 x 8 diagonal block in registers (no exchange),
+// one thread per column solves the block row, then a rank-8 update of the rest.
+__device__ __forceinline__ void chol_upper_64(float* G, int tid) {
+    for (int k0 = 0; k0 < B64; k0 += 8) {
+        float d[8][8], id[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int c = r; c < 8; ++c) d[r][c] = G[(k0 + r) * LS + k0 + c];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            // hardware reciprocal square root (1 ulp): U only has to be consistent with the inverse formed from it
+            id[r] = __builtin_amdgcn_rsqf(d[r][r]);
+            d[r][r] *= id[r];
+#pragma unroll
+            for (int c = r + 1; c < 8; ++c) d[r][c] *= id[r];
+#pragma unroll
+            for (int i = r + 1; i < 8; ++i)
+#pragma unroll
+                for (int c = i; c < 8; ++c) d[i][c] -= d[r][i] * d[r][c];
+        }
+        __syncthreads();   // every thread has read the diagonal block
+        if (tid == 0) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int c = r; c < 8; ++c) G[(k0 + r) * LS + k0 + c] = d[r][c];
+        }
+        const int j = k0 + 8 + tid;
+        if (j < B64) {
+            float x[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) x[r] = G[(k0 + r) * LS + j];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                float t = x[r];
+#pragma unroll
+                for (int q = 0; q < r; ++q) t -= d[q][r] * x[q];
+                x[r] = t * id[r];
+            }
+#pragma unroll
+            for (int r = 0; r < 8; ++r) G[(k0 + r) * LS + j] = x[r];
+        }
+        __syncthreads();
+        const int bi = tid >> 4, bj = tid & 15;
+        if (4 * bi >= k0 + 8 && bj >= bi) {
+            float ui[8][4], uj[8][4];
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    ui[r][a] = G[(k0 + r) * LS + 4 * bi + a];
+                    uj[r][a] = G[(k0 + r) * LS + 4 * bj + a];
+                }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) s += ui[r][a] * uj[r][b];
+                    G[(4 * bi + a) * LS + 4 * bj + b] -= s;
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        if ((e & 63) < (e >> 6)) G[(e >> 6) * LS + (e & 63)] = 0.f;
+    }
+    __syncthreads();
+}
+
+// In place LU without pivoting of W - diag(s), where s_j = -1 if the pivot met at step j is >= 0 and +1 otherwise
+// (decided on the partially eliminated matrix), so that each pivot has modulus >= 1.  On return the strict lower
+// triangle holds L (unit diagonal implied), the upper triangle U, and sg[0..64) the signs.
+__device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
+    for (int k0 = 0; k0 < B64; k0 += 8) {
+        float d[8][8], sv[8], id[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) d[r][c] = W[(k0 + r) * LS + k0 + c];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            sv[r] = d[r][r] >= 0.f ? -1.f : 1.f;
+            d[r][r] -= sv[r];
+            id[r] = __builtin_amdgcn_rcpf(d[r][r]);
+#pragma unroll
+            for (int i = r + 1; i < 8; ++i) d[i][r] *= id[r];
+#pragma unroll
+            for (int i = r + 1; i < 8; ++i)
+#pragma unroll
+                for (int c = r + 1; c < 8; ++c) d[i][c] -= d[i][r] * d[r][c];
+        }
+        __syncthreads();   // every thread has read the diagonal block
+        if (tid == 0) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                sg[k0 + r] = sv[r];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) W[(k0 + r) * LS + k0 + c] = d[r][c];
+            }
+        }
+        if (tid < 64) {                       // block column of L: x U_d = a, one row per thread
+            const int i = k0 + 8 + tid;
+            if (i < B64) {
+                float x[8];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) x[c] = W[i * LS + k0 + c];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    float t = x[c];
+#pragma unroll
+                    for (int q = 0; q < c; ++q) t -= x[q] * d[q][c];
+                    x[c] = t * id[c];
+                }
+#pragma unroll
+                for (int c = 0; c < 8; ++c) W[i * LS + k0 + c] = x[c];
+            }
+        } else if (tid < 128) {               // block row of U: L_d y = a, one column per thread
+            const int j = k0 + 8 + (tid - 64);
+            if (j < B64) {
+                float x[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) x[r] = W[(k0 + r) * LS + j];
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    float t = x[r];
+#pragma unroll
+                    for (int q = 0; q < r; ++q) t -= d[r][q] * x[q];
+                    x[r] = t;
+                }
+#pragma unroll
+                for (int r = 0; r < 8; ++r) W[(k0 + r) * LS + j] = x[r];
+            }
+        }
+        __syncthreads();
+        const int bi = tid >> 4, bj = tid & 15;
+        if (4 * bi >= k0 + 8 && 4 * bj >= k0 + 8) {
+            float l[4][8], u[8][4];
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    l[a][r] = W[(4 * bi + a) * LS + k0 + r];
+                    u[r][a] = W[(k0 + r) * LS + 4 * bj + a];
+                }
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) s += l[a][r] * u[r][b];
+                    W[(4 * bi + a) * LS + 4 * bj + b] -= s;
+                }
+        }
+        __syncthreads();
+    }
+}
+
+// One level of the triangular-inverse merge for diagonal blocks of size BL (8 or 16), see tri_inv_upper_64.
+template <int BL>
+__device__ __forceinline__ void tri_inv_level(const float* U, float* X, int tid) {
+    constexpr int PER_PAIR = BL * BL;
+    constexpr int TOTAL = (B64 / (2 * BL)) * PER_PAIR;
+    constexpr int ITERS = (TOTAL + NTHR - 1) / NTHR;
+    float acc[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {                   // scratch (lower-left block of the pair) = B C^-1
+        const int e = tid + NTHR * it;
+        const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+        const int i = r / BL, j = r % BL;
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < BL; ++k) t += U[(o + i) * LS + o + BL + k] * X[(o + BL + k) * LS + o + BL + j];
+        acc[it] = t;
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + NTHR * it;
+        const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+        if (e < TOTAL) X[(o + BL + r / BL) * LS + o + r % BL] = acc[it];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {                   // X12 = -A^-1 scratch
+        const int e = tid + NTHR * it;
+        const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+        const int i = r / BL, j = r % BL;
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < BL; ++k) t += X[(o + i) * LS + o + k] * X[(o + BL + k) * LS + o + j];
+        acc[it] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int e = tid + NTHR * it;
+        const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+        if (e < TOTAL) {
+            X[(o + r / BL) * LS + o + BL + r % BL] = -acc[it];
+            X[(o + BL + r / BL) * LS + o + r % BL] = 0.f;
+        }
+    }
+    __syncthreads();
+}
+
+// X = inverse of the upper-triangular matrix held in the upper triangle of U (what lies below U's diagonal is
+// ignored); X's strict lower triangle is zero on return.  8 x 8 diagonal blocks by substitution, then neighbours are
+// merged level by level:  inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1], [0, C^-1]], the last level on the matrix
+// cores.  The lower-left block of each merged pair is used as scratch for B C^-1 and cleared afterwards.
+// UNIT: the diagonal of U is taken as 1.
+template <bool UNIT>
+__device__ __forceinline__ void tri_inv_upper_64(const float* U, float* X, int tid) {
+    const int lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        X[(e >> 6) * LS + (e & 63)] = 0.f;
+    }
+    __syncthreads();
+    if (tid < 64) {
+        const int o = 8 * (tid >> 3), c = tid & 7;
+        float u[8][8], x[8], ru[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int q = r; q < 8; ++q) u[r][q] = U[(o + r) * LS + o + q];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) ru[r] = UNIT ? 1.f : 1.f / u[r][r];
+#pragma unroll
+        for (int r = 7; r >= 0; --r) {
+            float t = (r == c) ? 1.f : 0.f;
+#pragma unroll
+            for (int q = r + 1; q < 8; ++q) t -= u[r][q] * x[q];
+            x[r] = t * ru[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) X[(o + r) * LS + o + c] = x[r];
+    }
+    __syncthreads();
+    tri_inv_level<8>(U, X, tid);
+    tri_inv_level<16>(U, X, tid);
+    if (wave == 0) {                                       // scratch (rows 32.., cols 0..31) = U12 C^-1
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = MFMA32(U[lrow * LS + 32 + kk + lk], X[(32 + kk + lk) * LS + 32 + lrow], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) X[(32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + lrow] = acc[v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = MFMA32(X[lrow * LS + kk + lk], X[(32 + kk + lk) * LS + lrow], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * lk + (v & 3);
+            X[r * LS + 32 + lrow] = -acc[v];
+        }
+        // the reads of the scratch block above are complete (their results fed the products): clear it
+#pragma unroll
+        for (int v = 0; v < 16; ++v) X[(32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + lrow] = 0.f;
+    }
+    __syncthreads();
+}
+
+// This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (even bounds), both
+// operands in LDS.  AUPPER: entries of A below its diagonal are taken as zero.
+template <bool AUPPER>
+__device__ __forceinline__ f32x16 lds_mma(const float* A, const float* Bm, const float* kscale, int qi, int qj,
+                                          int klo, int khi, int lrow, int lk) {
+    f32x16 acc = zero16();
+    const int row = 32 * qi + lrow;
+    for (int k0 = klo; k0 < khi; k0 += 16) {               // klo, khi are multiples of 32
+        float a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + 2 * u + lk;
+            a[u] = A[row * LS + k];
+            if (AUPPER && k < row) a[u] = 0.f;
+            if (kscale != nullptr) a[u] *= kscale[k];
+            b[u] = Bm[k * LS + 32 * qj + lrow];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc = MFMA32(a[u], b[u], acc);
+    }
+    return acc;
+}
+
+__device__ __forceinline__ void acc_to_lds(const f32x16& acc, float* Bm, int qi, int qj, int lrow, int lk) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Bm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + 32 * qj + lrow] = acc[v];
+}
+
+// First small step: U1 = chol(sum of partials of A^T A) and its inverse, both 64 x 64 (leading dimension 64).
+__global__ __launch_bounds__(NSUM) void chol_inv_kernel(const float* __restrict__ part, int nparts,
+                                                        float* __restrict__ U1, float* __restrict__ U1inv) {
+    __shared__ float B0[B64 * LS];
+    __shared__ float B1[B64 * LS];
+    const int tid = threadIdx.x;
+    sum_partials(part, nparts, B0, tid);
+    if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
+    chol_upper_64(B0, tid);
+    tri_inv_upper_64<false>(B0, B1, tid);
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        U1[e] = B0[(e >> 6) * LS + (e & 63)];
+        U1inv[e] = B1[(e >> 6) * LS + (e & 63)];
+    }
+}
+
+// Second small step (see the head of this file).  Inputs: partials of G2 = Q1^T Q1, the first 64 rows of Q1, U1.
+// Outputs when the orthogonality check passes (*fb = 0): the top 64 x 64 block of the panel in Atop (V_top strictly
+// below the diagonal, S U2 U1 on and above it), T (64 x 64, ld 64), Mm = (U_lu U2)^-1 (for the rows below the block).
+// Otherwise *fb = 1 and nothing else is written.
+__global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict__ part, int nparts,
+                                                         const float* __restrict__ Q1top,
+                                                         const float* __restrict__ U1, float* __restrict__ Atop,
+                                                         long lda, float* __restrict__ Tout, float* __restrict__ Mm,
+                                                         unsigned* __restrict__ fb, unsigned* __restrict__ status) {
+    __shared__ float B0[B64 * LS];
+    __shared__ float B1[B64 * LS];
+    __shared__ float B2[B64 * LS];
+    __shared__ float sg[B64];
+    __shared__ float redw[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+
+    sum_partials(part, nparts, B0, tid);
+    if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
+    {   // ||G2 - I||_F^2 must be small: then Q1 is well conditioned and the second pass gives orthonormal columns
+        float dev = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            const int i = e >> 6, j = e & 63;
+            const float x = B0[i * LS + j] - ((i == j) ? 1.f : 0.f);
+            if (j >= i) dev += (j > i ? 2.f : 1.f) * x * x;     // only the upper triangle was summed
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) dev += __shfl_xor(dev, off);
+        if (lane == 0) redw[wave] = dev;
+        __syncthreads();
+        const float total = redw[0] + redw[1] + redw[2] + redw[3];
+        const bool ok = total < 0.25f;          // false for NaN as well
+        if (tid == 0) {
+            *fb = ok ? 0u : 1u;
+            if (!ok) atomicOr(status, DQ_FLAG_ILLCOND_PANEL);
+        }
+        if (!ok) return;
+    }
+    chol_upper_64(B0, tid);                     // B0 = U2
+    tri_inv_upper_64<false>(B0, B1, tid);       // B1 = U2^-1
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        B2[(e >> 6) * LS + (e & 63)] = U1[e];
+    }
+    __syncthreads();
+    // Rf = U2 U1 (upper x upper): kept in registers until the row signs are known
+    f32x16 accR = zero16();
+    if (qi <= qj) accR = lds_mma<false>(B0, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        B2[(e >> 6) * LS + (e & 63)] = Q1top[e];
+    }
+    __syncthreads();
+    {   // Q_top = Q1_top U2^-1  -> B0
+        const f32x16 accQ = lds_mma<false>(B2, B1, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
+        acc_to_lds(accQ, B0, qi, qj, lrow, lk);
+    }
+    __syncthreads();
+    lu_signed_64(B0, sg, tid);                  // B0 = L \ U_lu, sg = S
+    tri_inv_upper_64<false>(B0, B2, tid);       // B2 = U_lu^-1
+    {   // Mm = U2^-1 U_lu^-1
+        f32x16 accM = zero16();
+        if (qi <= qj) accM = lds_mma<false>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            Mm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * B64 + 32 * qj + lrow] = accM[v];
+    }
+    __syncthreads();
+    // V_top to the panel; its transpose (unit upper triangular) to B1
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        const int r = e >> 6, c = e & 63;
+        if (c < r) Atop[(long)r * lda + c] = B0[r * LS + c];
+        B1[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
+    }
+    __syncthreads();
+    tri_inv_upper_64<true>(B1, B2, tid);        // B2 = V_top^-T
+    {   // T = -(U_lu S) V_top^-T
+        f32x16 accT = zero16();
+        if (qi <= qj) accT = lds_mma<true>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
+            Tout[r * B64 + c] = (c >= r) ? -accT[v] : 0.f;
+            if (c >= r) Atop[(long)r * lda + c] = sg[r] * accR[v];
+        }
+    }
+}
+
+}  // namespace
+
+size_t cholpanel_scratch_floats() { return (size_t)kCholMaxParts * B64 * B64 + 3 * B64 * B64 + 64; }
+
+bool cholpanel_supported(const float* A, long lda, int m, int jb) {
+    return jb == B64 && m >= 2 * B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
+}
+
+hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* q1, float* scratch, unsigned* fb,
+                               unsigned* status, hipStream_t s) {
+    if (!cholpanel_supported(A, lda, m, B64)) return hipErrorInvalidValue;
+    float* part = scratch;
+    float* U1 = part + (size_t)kCholMaxParts * B64 * B64;
+    float* U1inv = U1 + B64 * B64;
+    float* Mm = U1inv + B64 * B64;
+    const int tiles = (m + RT - 1) / RT;
+    // Gram partials (= workgroups of the tall-skinny kernels): more of them shorten those kernels but lengthen the
+    // one-workgroup sums; 16 balances the two at m = 4096.  DQ_TALL_PANEL_PARTS overrides (tuning only).
+    static const int parts_cap = [] {
+        const char* e = getenv("DQ_TALL_PANEL_PARTS");
+        int v = e ? atoi(e) : 16;
+        return v < 1 ? 1 : (v > kCholMaxParts ? kCholMaxParts : v);
+    }();
+    const int tpw = (tiles + parts_cap - 1) / parts_cap;               // row tiles per workgroup
+    const int nparts = (tiles + tpw - 1) / tpw;
+    hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, part);
+    hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, U1, U1inv);
+    hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, U1inv, q1, part);
+    hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, q1, U1, A, lda, Tout, Mm, fb,
+                       status);
+    const int below = (m - B64 + RT - 1) / RT;
+    hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, Mm, A, lda, fb);
+    return hipGetLastError();
+}
+
+}  // namespace dq

@@ -28,7 +28,8 @@ namespace {
 template <int NT, int Q, int SW, int VCH>
 __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, long lda, int m, int jb,
                                                       float* __restrict__ tau, float* Vs, float* __restrict__ tslices,
-                                                      unsigned* flags, int vec) {
+                                                      unsigned* flags, int vec, const unsigned* __restrict__ pred) {
+    if (pred != nullptr && *pred == 0u) return;
     constexpr int NW = NT / 64;
     constexpr int MP = NT * Q;
     constexpr int NV2 = SW * SW;
@@ -306,7 +307,9 @@ __global__ __launch_bounds__(NT) void qr_panel_kernel(float* __restrict__ A, lon
 // Copies rows jb..m-1 of a factored panel from the packed slice-major copy [slice][row][sw] into the matrix
 // (row-major, lda): one 16-byte piece per thread, consecutive threads along a row.
 __global__ __launch_bounds__(256) void unpack_reflectors_kernel(float* __restrict__ A, long lda, int m, int jb,
-                                                                const float* __restrict__ Vs, int mp, int sw, int vec) {
+                                                                const float* __restrict__ Vs, int mp, int sw, int vec,
+                                                                const unsigned* __restrict__ pred) {
+    if (pred != nullptr && *pred == 0u) return;
     const int c4n = (jb + 3) >> 2;                 // 16-byte pieces per row
     const long total = (long)(m - jb) * c4n;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
@@ -332,7 +335,8 @@ __global__ __launch_bounds__(256) void unpack_reflectors_kernel(float* __restric
 // returns W2 = T^T (V^T C) (jb x nla, leading dimension kPanel) for the update of the nla look-ahead columns.
 __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__ gpart, int splits, long stride,
                                                        long ldp, int jb, int nla, const float* __restrict__ tslices,
-                                                       int sw, float* __restrict__ Tout, float* __restrict__ W2out) {
+                                                       int sw, float* __restrict__ Tout, float* __restrict__ W2out,
+                                                       const unsigned* __restrict__ tready) {
     typedef float f32x16 __attribute__((ext_vector_type(16)));
     __shared__ float Gs[kPanel][kPanel + 1];
     __shared__ float Ts[kPanel][kPanel + 1];
@@ -340,6 +344,7 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
+    const bool have_t = (tready != nullptr) && (*tready == 0u);   // uniform over the workgroup
     float wreg[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -350,7 +355,7 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         float pt[16], pw[16];
 #pragma unroll
         for (int z = 0; z < 16; ++z) {
-            pt[z] = (z < splits && i < jb && j < jb) ? gpart[(long)z * stride + (long)i * ldp + j] : 0.f;
+            pt[z] = (!have_t && z < splits && i < jb && j < jb) ? gpart[(long)z * stride + (long)i * ldp + j] : 0.f;
             pw[z] = (z < splits && i < jb && j < nla) ? gpart[(long)z * stride + (long)i * ldp + jb + j] : 0.f;
         }
 #pragma unroll
@@ -358,12 +363,13 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         wreg[q] = w;
         Gs[i][j] = t;
         float tv = 0.f;
-        if (i / sw == j / sw && i < jb && j < jb) tv = tslices[(i / sw) * sw * sw + (i % sw) * sw + (j % sw)];
+        if (have_t) tv = Tout[e];
+        else if (i / sw == j / sw && i < jb && j < jb) tv = tslices[(i / sw) * sw * sw + (i % sw) * sw + (j % sw)];
         Ts[i][j] = tv;
     }
     __syncthreads();
     // levels below 32: plain loops (a few hundred short dot products)
-    for (int b = sw; b < 32; b <<= 1) {
+    for (int b = have_t ? 32 : sw; b < 32; b <<= 1) {
         const int per_pair = b * b;
         const int total = (kPanel / (2 * b)) * per_pair;
         for (int e = tid; e < total; e += 1024) {          // X = G12 * T2
@@ -385,7 +391,7 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
     }
     // level 32 -> 64 on the matrix cores (one wavefront, two 32 x 32 x 32 products):
     //   X = G[0:32, 32:64] * T[32:64, 32:64],   T[0:32, 32:64] = -T[0:32, 0:32] * X
-    if (wave == 0) {
+    if (wave == 0 && !have_t) {
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -396,7 +402,7 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
         for (int v = 0; v < 16; ++v) Xs[8 * (v >> 2) + 4 * lk + (v & 3)][32 + lrow] = acc[v];
     }
     __syncthreads();
-    if (wave == 0) {
+    if (wave == 0 && !have_t) {
         f32x16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -410,7 +416,7 @@ __global__ __launch_bounds__(1024) void tfactor_kernel(const float* __restrict__
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int e = tid + 1024 * q;
-        Tout[e] = Ts[e / kPanel][e % kPanel];
+        if (!have_t) Tout[e] = Ts[e / kPanel][e % kPanel];
         Gs[e / kPanel][e % kPanel] = wreg[q];           // G is no longer needed: keep W = V^T C there
     }
     __syncthreads();
@@ -488,24 +494,25 @@ size_t panel_scratch_floats(int /*m*/) { return (size_t)kPanel * (8192 + 64); }
 
 template <int NT, int Q, int SW, int VCH = Q>
 static void launch_panel_cfg(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
-                             unsigned* flags, int vec, hipStream_t s) {
+                             unsigned* flags, int vec, const unsigned* pred, hipStream_t s) {
     hipLaunchKernelGGL((qr_panel_kernel<NT, Q, SW, VCH>), dim3(1), dim3(NT), 0, s, A, lda, m, jb, tau, vscratch, tslices,
-                       flags, vec);
+                       flags, vec, pred);
 }
 
 static hipError_t finish_panel(float* A, long lda, int m, int jb, const float* vscratch, int mp, int sw, int vec,
-                               hipStream_t s) {
+                               const unsigned* pred, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || m <= jb) return e;
     const long total = (long)(m - jb) * ((jb + 3) / 4);
     long blocks = (total + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(unpack_reflectors_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A, lda, m, jb, vscratch, mp, sw, vec);
+    hipLaunchKernelGGL(unpack_reflectors_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A, lda, m, jb, vscratch, mp, sw, vec,
+                       pred);
     return hipGetLastError();
 }
 
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
-                           int* slice_width, unsigned* flags, hipStream_t s) {
+                           int* slice_width, unsigned* flags, const unsigned* pred, hipStream_t s) {
     if (m <= 0 || jb <= 0) return hipSuccess;
     if (m > 8192 || jb > kPanel || jb > m) return hipErrorInvalidValue;
     const int vec = ((reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0) ? 1 : 0;
@@ -513,19 +520,20 @@ hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float*
     int mp, sw = 8;
     // rows per thread Q = 1, 2, 4, 8 with 8-column slices; taller panels (m > 4096) use Q = 16 with 4-column slices,
     // which is what fits the register file (an 8-column slice of 16 rows per thread plus the 64 projection sums spill)
-    if (m <= NT * 1) { launch_panel_cfg<NT, 1, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 1; }
-    else if (m <= NT * 2) { launch_panel_cfg<NT, 2, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 2; }
-    else if (m <= NT * 4) { launch_panel_cfg<NT, 4, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 4; }
-    else if (m <= NT * 8) { launch_panel_cfg<NT, 8, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 8; }
-    else { launch_panel_cfg<NT, 16, 4>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, s); mp = NT * 16; sw = 4; }
+    if (m <= NT * 1) { launch_panel_cfg<NT, 1, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, pred, s); mp = NT * 1; }
+    else if (m <= NT * 2) { launch_panel_cfg<NT, 2, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, pred, s); mp = NT * 2; }
+    else if (m <= NT * 4) { launch_panel_cfg<NT, 4, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, pred, s); mp = NT * 4; }
+    else if (m <= NT * 8) { launch_panel_cfg<NT, 8, 8>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, pred, s); mp = NT * 8; }
+    else { launch_panel_cfg<NT, 16, 4>(A, lda, m, jb, tau, vscratch, tslices, flags, vec, pred, s); mp = NT * 16; sw = 4; }
     *slice_width = sw;
-    return finish_panel(A, lda, m, jb, vscratch, mp, sw, vec, s);
+    return finish_panel(A, lda, m, jb, vscratch, mp, sw, vec, pred, s);
 }
 
 hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
-                          const float* tslices, int slice_width, float* Tout, float* W2out, hipStream_t s) {
+                          const float* tslices, int slice_width, float* Tout, float* W2out, const unsigned* tready,
+                          hipStream_t s) {
     hipLaunchKernelGGL(tfactor_kernel, dim3(1), dim3(1024), 0, s, gpart, splits, stride, ldp, jb, nla, tslices,
-                       slice_width, Tout, W2out);
+                       slice_width, Tout, W2out, tready);
     return hipGetLastError();
 }
 

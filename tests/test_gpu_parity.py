@@ -165,6 +165,63 @@ def test_qr_orth_against_oracle(ctx, n):
     assert ctx.dq_device_flags() == 0
 
 
+@pytest.fixture(scope="module")
+def ctx_householder_only():
+    """A context whose QR never takes the many-CU route for tall panels (read from the environment at creation)."""
+    os.environ["DQ_TALL_PANEL_MIN_M"] = "0"
+    try:
+        c = B.Context()
+    finally:
+        del os.environ["DQ_TALL_PANEL_MIN_M"]
+    c.ensure_workspace(1, 2100, 64, B.DQ_F32)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+@pytest.mark.parametrize("n,kind", [(576, "gauss"), (2048, "gauss"), (1100, "near_orthogonal"), (900, "col_scaled")])
+def test_qr_orth_tall_panel_route(ctx, ctx_householder_only, n, kind):
+    """Tall panels (>= 512 rows) are factored by CholeskyQR2 + Householder reconstruction; both routes must meet
+    the same bars against the oracle, and the fast one must not have fallen back on these inputs."""
+    g = rng(4400 + n)
+    Z = g.standard_normal((n, n))
+    if kind == "near_orthogonal":
+        Z = np.linalg.qr(Z)[0] + 0.01 * g.standard_normal((n, n))
+    elif kind == "col_scaled":
+        Z = Z * np.exp(2.0 * g.standard_normal(n))[None, :]
+    Z = Z.astype(np.float32)
+    Ro, Uo = orc.qr_orth(Z)
+    cond = np.linalg.cond(Z.astype(np.float64))
+    ctx.ensure_workspace(1, n, 64, B.DQ_F32)
+    for c in (ctx, ctx_householder_only):
+        R, U = run_qr(c, Z)
+        assert np.abs(R.astype(np.float64).T @ R - np.eye(n)).max() <= 1e-5
+        assert np.all(np.tril(U, -1) == 0.0) and np.all(np.diag(U) > 0.0)
+        assert rel(R.astype(np.float64) @ U, Z) < 1e-5
+        assert rel(U, Uo) < 1e-4
+        assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+        assert c.dq_device_flags() == 0
+
+
+def test_qr_orth_ill_conditioned_panel_falls_back(ctx):
+    """Two nearly parallel columns inside the first panel: the Gram-matrix route cannot factor it in fp32, the
+    Householder kernel takes over (informational flag), and the result still meets the oracle."""
+    n = 640
+    g = rng(4500)
+    Z = g.standard_normal((n, n))
+    Z[:, 5] = Z[:, 3] + 1e-5 * g.standard_normal(n)
+    Z = Z.astype(np.float32)
+    R, U = run_qr(ctx, Z)
+    assert ctx.dq_device_flags() == B.DQ_FLAG_ILLCOND_PANEL
+    Ro, Uo = orc.qr_orth(Z)
+    cond = np.linalg.cond(Z.astype(np.float64))
+    assert np.abs(R.astype(np.float64).T @ R - np.eye(n)).max() <= 1e-5
+    assert rel(R.astype(np.float64) @ U, Z) < 1e-5
+    # the row of U and the column of R that belong to the nearly dependent column are only determined to eps * cond
+    assert rel(U, Uo) < max(1e-4, 2e-7 * cond)
+    assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+
+
 def test_qr_orth_without_u_and_with_wide_ld(ctx):
     n = 200
     Z = rng(4100).standard_normal((n, n)).astype(np.float32)
@@ -202,6 +259,12 @@ def test_singular_latent_raises_flag_not_fault(ctx):
     run_qr(ctx, Z)
     assert ctx.dq_device_flags() & B.DQ_FLAG_SINGULAR
     assert ctx.dq_device_flags() == 0          # reading clears the word
+    # the same through a tall panel: the fast route gives up, the Householder kernel reports the zero pivot
+    n = 600
+    Z = rng(4301).standard_normal((n, n)).astype(np.float32)
+    Z[:, 40] = 0.0
+    run_qr(ctx, Z)
+    assert ctx.dq_device_flags() == (B.DQ_FLAG_SINGULAR | B.DQ_FLAG_ILLCOND_PANEL)
 
 
 # ----------------------------------------------------------------------------------- rotate + loss + G
