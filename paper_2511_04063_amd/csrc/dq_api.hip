@@ -63,8 +63,8 @@ namespace {
 // ---------------------------------------------------------------- workspace layout
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
-    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, qy = 0,
-           vs = 0, cq = 0, tsl = 0, ybuf = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
+    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0,
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -97,11 +97,10 @@ Layout make_layout(int n, int T) {
     L.w2B = bump(cur, (size_t)kPanel * L.ld * 4);
     L.qpart = bump(cur, (size_t)kMaxSplit * n * kPanel * 4);
     L.qw = bump(cur, (size_t)n * kPanel * 4);
-    L.qy = bump(cur, (size_t)n * kPanel * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
     L.cq = bump(cur, cholpanel_scratch_floats() * 4);
     L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
-    L.ybuf = bump(cur, (size_t)2 * n * kPanel * 4);   // two copies: look-ahead double buffering
+    L.yall = bump(cur, npanels * (size_t)n * kPanel * 4);   // V T of every panel (n x 64 slot each)
     const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
@@ -182,9 +181,10 @@ void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int
 struct ReflBufs { float* wpart; float* wsum; };
 
 // Wsum (jb x ncols, ld L.ld) = V^T Bmat;  with gram_cols > 0 the first gram_cols columns of Bmat are V itself (masked).
+// a_unit_lower = 0: the left operand is a plain m x jb matrix (V T) instead of the reflector block.
 dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs& bufs, const float* Vp, long ldv,
                        int m, int jb, const float* Bmat, long ldb, int ncols, int gram_cols, const float** Wsum,
-                       int max_splits = kMaxSplit, int* splits_out = nullptr) {
+                       int max_splits = kMaxSplit, int* splits_out = nullptr, int a_unit_lower = 1) {
     const long ldw = L.ld;
     const long stride = (long)kPanel * ldw;
     int splits, kchunk;
@@ -193,7 +193,7 @@ dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs
     if (splits_out != nullptr) *splits_out = splits;
     {
         GemmF32 g;
-        g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = 1;
+        g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = a_unit_lower;
         g.B = Bmat; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = gram_cols;
         g.C = bufs.wpart; g.ldc = ldw;
         g.M = jb; g.N = ncols; g.K = m;
@@ -223,12 +223,12 @@ dq_status refl_make_y(dq_ctx* c, hipStream_t s, const float* Vp, long ldv, int m
     return DQ_OK;
 }
 
-// Csub (m x nc) -= Y W
-dq_status refl_update(dq_ctx* c, hipStream_t s, const Layout& L, const float* Y, const float* W, int m, int jb,
-                      float* Csub, long ldc, int nc) {
+// Csub (m x nc) -= V W  (V: the unit-lower-trapezoid reflector block in the factored matrix, W: jb x nc, ld L.ld)
+dq_status refl_update(dq_ctx* c, hipStream_t s, const Layout& L, const float* Vp, long ldv, const float* W, int m,
+                      int jb, float* Csub, long ldc, int nc) {
     if (nc <= 0) return DQ_OK;
     GemmF32 g;
-    g.A = Y; g.lda = kPanel; g.ta = 0;
+    g.A = Vp; g.lda = ldv; g.ta = 0; g.a_unit_lower = 1;
     g.B = W; g.ldb = L.ld; g.tb = 0;
     g.C = Csub; g.ldc = ldc;
     g.M = m; g.N = nc; g.K = jb;
@@ -239,22 +239,21 @@ dq_status refl_update(dq_ctx* c, hipStream_t s, const Layout& L, const float* Y,
 }
 
 // ---------------------------------------------------------------- S1 + S2
-// Q[:, k0:k0+m] <- Q[:, k0:k0+m] (I - V T V^T) for the panel at column k0 (V: m x jb at Vp, T: jb x jb at Tp):
-//   Wq = Qc V (n x jb),  Yq = Wq T,  Qc -= Yq V^T.
+// Q[:, k0:k0+m] <- Q[:, k0:k0+m] (I - V T V^T) for the panel at column k0 (V: m x jb at Vp, Yp = V T: m x jb, ld 64):
+//   Wq = Qc Yp (n x jb),  Qc -= Wq V^T.
 dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0, int m, int jb, const float* Vp,
-                       long ldv, const float* Tp, float* Q, long ldq) {
+                       long ldv, const float* Yp, float* Q, long ldq) {
     float* qpart = at<float>(c, L.qpart);
     float* qw = at<float>(c, L.qw);
-    float* qy = at<float>(c, L.qy);
     float* Qc = Q + k0;
     const long stride = (long)n * kPanel;
     int splits, kchunk;
     const int tm = jb <= 64 ? 256 : 128;
     choose_split((n + tm - 1) / tm, m, 16, kMaxSplit, splits, kchunk);
     {
-        GemmF32 g;   // Wq = Qc V
+        GemmF32 g;   // Wq = Qc Yp
         g.A = Qc; g.lda = ldq; g.ta = 0;
-        g.B = Vp; g.ldb = ldv; g.tb = 0; g.b_unit_lower_cols = jb;
+        g.B = Yp; g.ldb = kPanel; g.tb = 0;
         g.C = splits > 1 ? qpart : qw; g.ldc = kPanel;
         g.M = n; g.N = jb; g.K = m;
         g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
@@ -266,17 +265,8 @@ dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0,
         DQ_HIP(launch_splitk_reduce(qpart, splits, stride, kPanel, n, jb, 1.f, 0.f, qw, kPanel, s));
     }
     {
-        GemmF32 g;   // Yq = Wq T
+        GemmF32 g;   // Qc -= Wq V^T   (V stored m x jb = N x K)
         g.A = qw; g.lda = kPanel; g.ta = 0;
-        g.B = Tp; g.ldb = kPanel; g.tb = 0;
-        g.C = qy; g.ldc = kPanel;
-        g.M = n; g.N = jb; g.K = jb;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)jb * jb, 0.0);
-        DQ_HIP(launch_gemm_f32(g, s));
-    }
-    {
-        GemmF32 g;   // Qc -= Yq V^T   (V stored m x jb = N x K)
-        g.A = qy; g.lda = kPanel; g.ta = 0;
         g.B = Vp; g.ldb = ldv; g.tb = 1; g.b_unit_lower_cols = jb;
         g.C = Qc; g.ldc = ldq;
         g.M = n; g.N = m; g.K = jb;
@@ -296,7 +286,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     float* Tall = at<float>(c, L.Tall);
     float* vs = at<float>(c, L.vs);
     float* tsl = at<float>(c, L.tsl);
-    float* ybuf = at<float>(c, L.ybuf);
+    float* yall = at<float>(c, L.yall);
     unsigned* flags = at<unsigned>(c, L.flags);
     const ReflBufs bufA{at<float>(c, L.wpart), at<float>(c, L.w2)};
     const ReflBufs bufB{at<float>(c, L.wpartB), at<float>(c, L.w2B)};
@@ -318,54 +308,66 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         const int m = n - k0;
         float* Ap = A + (long)k0 * ld + k0;
         float* Tp = Tall + (long)p * kPanel * kPanel;
-        int sw = 8;
-        // Tall full-width panels: CholeskyQR2 + Householder reconstruction over many compute units.  It raises the
-        // device word fb when the panel is too ill-conditioned for it; the one-workgroup Householder panel that
-        // follows is predicated on that word (it runs unconditionally for the other panels).
-        const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
-        unsigned* fb = tall ? flags + 16 : nullptr;
-        {
-            LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
-            if (tall) DQ_HIP(launch_cholqr_panel(Ap, ld, m, Tp, vs, at<float>(c, L.cq), fb, flags, sA));
-            DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, fb, sA));
-        }
-        // the look-ahead columns received update p-1 on the second stream
-        if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+        float* Yp = yall + (long)p * n * kPanel;
         const int nla = (m - jb) < nb ? (m - jb) : nb;
-        // partials of V^T [V | C_la]; summed inside the T-factor kernel, which also returns W2 = T^T V^T C_la
-        const float* Wa = nullptr;
-        int splitsA = 1;
-        DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa, 16, &splitsA));
-        {
-            LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 0.0);
-            DQ_HIP(launch_tfactor(bufA.wpart, splitsA, (long)kPanel * ld, ld, jb, nla, tsl, sw, Tp, bufA.wsum, fb, sA));
-        }
-        if (nla > 0) {
-            GemmF32 g;   // C_la -= V W2
-            g.A = Ap; g.lda = ld; g.ta = 0; g.a_unit_lower = 1;
-            g.B = bufA.wsum; g.ldb = kPanel; g.tb = 0;
-            g.C = Ap + jb; g.ldc = ld;
-            g.M = m; g.N = nla; g.K = jb;
-            g.alpha = -1.f; g.beta = 1.f;
-            LaunchScope sc(&c->prof, sA, DQ_K_GEMM_F32, 2.0 * m * (double)nla * jb, 0.0);
-            DQ_HIP(launch_gemm_f32(g, sA));
+        // Tall full-width panels: CholeskyQR2 + Householder reconstruction over many compute units; it returns the
+        // reflectors, T and Yp = V T.  The other panels: the one-workgroup Householder panel kernel, then T from the
+        // Gram matrix of the reflectors.
+        const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
+        if (tall) {
+            {
+                LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
+                DQ_HIP(launch_cholqr_panel(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags, sA));
+            }
+            // the look-ahead columns received update p-1 on the second stream
+            if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+            if (nla > 0) {   // C_la -= V (Yp^T C_la)
+                const float* Wa = nullptr;
+                DQ_TRY(refl_project(c, sA, L, bufA, Yp, kPanel, m, jb, Ap + jb, ld, nla, 0, &Wa, kMaxSplit, nullptr, 0));
+                DQ_TRY(refl_update(c, sA, L, Ap, ld, Wa, m, jb, Ap + jb, ld, nla));
+            }
+        } else {
+            int sw = 8;
+            {
+                LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
+                DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, sA));
+            }
+            if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+            // partials of V^T [V | C_la]; summed inside the T-factor kernel, which also returns W2 = T^T V^T C_la
+            const float* Wa = nullptr;
+            int splitsA = 1;
+            DQ_TRY(refl_project(c, sA, L, bufA, Ap, ld, m, jb, Ap, ld, jb + nla, jb, &Wa, 16, &splitsA));
+            {
+                LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 0.0);
+                DQ_HIP(launch_tfactor(bufA.wpart, splitsA, (long)kPanel * ld, ld, jb, nla, tsl, sw, Tp, bufA.wsum, sA));
+            }
+            if (nla > 0) {
+                GemmF32 g;   // C_la -= V W2
+                g.A = Ap; g.lda = ld; g.ta = 0; g.a_unit_lower = 1;
+                g.B = bufA.wsum; g.ldb = kPanel; g.tb = 0;
+                g.C = Ap + jb; g.ldc = ld;
+                g.M = m; g.N = nla; g.K = jb;
+                g.alpha = -1.f; g.beta = 1.f;
+                LaunchScope sc(&c->prof, sA, DQ_K_GEMM_F32, 2.0 * m * (double)nla * jb, 0.0);
+                DQ_HIP(launch_gemm_f32(g, sA));
+            }
+            DQ_TRY(refl_make_y(c, sA, Ap, ld, m, jb, Tp, 0, Yp));
         }
         const int rest = m - jb - nla;
         DQ_HIP(hipEventRecord(c->sync_ev[2 * p], sA));
         DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
-        if (rest > 0) {
+        if (rest > 0) {   // C -= V (Yp^T C) for the rest of the trailing matrix, behind the next panel
             DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[2 * p], 0));
             const float* Wb = nullptr;
-            DQ_TRY(refl_make_y(c, sB, Ap, ld, m, jb, Tp, 1, ybuf));
-            DQ_TRY(refl_project(c, sB, L, bufB, Ap, ld, m, jb, Ap + jb + nla, ld, rest, 0, &Wb));
-            DQ_TRY(refl_update(c, sB, L, ybuf, Wb, m, jb, Ap + jb + nla, ld, rest));
+            DQ_TRY(refl_project(c, sB, L, bufB, Yp, kPanel, m, jb, Ap + jb + nla, ld, rest, 0, &Wb, kMaxSplit, nullptr, 0));
+            DQ_TRY(refl_update(c, sB, L, Ap, ld, Wb, m, jb, Ap + jb + nla, ld, rest));
             DQ_HIP(hipEventRecord(c->sync_ev[2 * p + 1], sB));
             last_trailing = p;
         }
         // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
         // left to the right, Q[:, k0:] <- Q[:, k0:] (I - V T V^T)  (as Alg. 2 does column by column), on the third
         // stream.  For p == 0 the accumulated factor is still the identity.
-        DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Tp, R, ldr));
+        DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Yp, R, ldr));
     }
     if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
     DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));

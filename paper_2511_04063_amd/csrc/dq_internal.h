@@ -76,25 +76,24 @@ hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long
 // implied), triangular factor on and above it; tau[0..jb).  vscratch: >= panel_scratch_floats(m) floats.
 // tslices (kPanel*kPanel floats) receives the T factor of every column slice; *slice_width its width.
 size_t panel_scratch_floats(int m);
-// pred (device word, may be null): when non-null and *pred == 0 at run time the kernels return at once.
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
-                           int* slice_width, unsigned* flags, const unsigned* pred, hipStream_t s);
-// Tall m x 64 panel by CholeskyQR2 + Householder reconstruction on many compute units: same outputs as
-// launch_qr_panel followed by launch_tfactor (reflectors and triangular factor in A, T in Tout), except that row
-// signs of the triangular factor may differ.  q1: m x 64 floats; scratch: cholpanel_scratch_floats() floats.
-// *fb is set to 0 on success; to 1 when the panel is too ill-conditioned for this route, and then A and Tout are
-// left untouched (the caller runs launch_qr_panel predicated on fb) and DQ_FLAG_ILLCOND_PANEL is or-ed into *status.
+                           int* slice_width, unsigned* flags, hipStream_t s);
+// Tall m x 64 panel by CholeskyQR2 + Householder reconstruction on many compute units.  Outputs: reflectors and
+// triangular factor in A (as launch_qr_panel leaves them, except that row signs of the triangular factor may differ),
+// T (64 x 64, ld 64) in Tout, and Yp = V T (m x 64, ld 64).  q1: m x 64 floats of scratch (also used as the panel
+// kernel's reflector scratch); scratch: cholpanel_scratch_floats() floats; tau, tslices as for launch_qr_panel.
+// A panel that is too ill-conditioned for this route is factored by the Householder panel code inside the same
+// launches (slow but rare; same outputs) and DQ_FLAG_ILLCOND_PANEL is or-ed into *status.
 size_t cholpanel_scratch_floats();
 bool cholpanel_supported(const float* A, long lda, int m, int jb);
-hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* q1, float* scratch, unsigned* fb,
-                               unsigned* status, hipStream_t s);
+hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch,
+                               float* tau, float* tslices, unsigned* status, hipStream_t s);
+
 // T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the split-K
 // partials of V^T [V | C] (gpart[z] at stride, leading dimension ldp: jb Gram columns, then nla columns of V^T C).
 // Also W2out (jb x nla, ld kPanel) = T^T (V^T C).
-// tready (device word, may be null): when non-null and *tready == 0 at run time, Tout already holds T and is only read.
 hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
-                          const float* tslices, int slice_width, float* Tout, float* W2out, const unsigned* tready,
-                          hipStream_t s);
+                          const float* tslices, int slice_width, float* Tout, float* W2out, hipStream_t s);
 
 hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s);
 hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s);

@@ -12,12 +12,15 @@
 //
 // Everything that touches the m rows is a tall-skinny product on the matrix cores, spread over m / 128
 // workgroups; the 64 x 64 work (sums of partials, Cholesky, LU, triangular inverses, small products) runs in
-// one workgroup out of LDS.  When the check in step 1 fails (ill-conditioned or rank-deficient panel) the
-// kernels leave the panel untouched and raise a device word; the caller then runs the Householder panel
-// kernel, which is launched predicated on that word.
+// one workgroup out of LDS.  Besides V, T and the triangular factor the route also returns Yp = V T (m x 64), the
+// operand the trailing updates and the accumulation of the orthogonal factor multiply with.
+// When the check in step 1 fails (ill-conditioned or rank-deficient panel) the same one-workgroup kernel factors
+// the untouched panel with the Householder panel code instead and builds T and Yp itself (slow, rare), so the
+// launch sequence never depends on the data.
 #include <stdlib.h>
 
 #include "dq_internal.h"
+#include "qr_panel_body.h"
 
 namespace dq {
 namespace {
@@ -156,9 +159,11 @@ __global__ __launch_bounds__(NTHR) void ts_mul_gram_kernel(const float* __restri
     store_partial(part + (long)blockIdx.x * B64 * B64, acc, qi, qj, lrow, lk);
 }
 
-// Out[row_off + r][0:64] = Q1[row_off + r][:] Mm for the rows r >= 0 handled by this workgroup; skipped when *fb != 0.
+// For the rows r >= row_off handled by this workgroup:  Vout[r][0:64] = Q1[r][:] Mm  and  Yout[r][0:64] = Q1[r][:] Mm2
+// (both multipliers upper triangular, 64 x 64, ld 64; Yout has ld 64).  Skipped when *fb != 0.
 __global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ Q1, int m, int row_off,
-                                                      const float* __restrict__ Mm, float* __restrict__ Out, long ldo,
+                                                      const float* __restrict__ Mm, const float* __restrict__ Mm2,
+                                                      float* __restrict__ Vout, long ldv, float* __restrict__ Yout,
                                                       const unsigned* __restrict__ fb) {
     if (*fb != 0u) return;
     __shared__ float Xs[RT * LS];
@@ -169,14 +174,31 @@ __global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ 
     load_small64(Mm, Ms, tid);
     load_tile(Q1, B64, row0, m, Xs, tid);
     __syncthreads();
-    f32x16 q0 = zero16(), q1 = zero16();
-    mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+    {
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
-        if (r < m) {
-            Out[(long)r * ldo + lrow] = q0[v];
-            Out[(long)r * ldo + 32 + lrow] = q1[v];
+        for (int v = 0; v < 16; ++v) {
+            const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < m) {
+                Vout[(long)r * ldv + lrow] = q0[v];
+                Vout[(long)r * ldv + 32 + lrow] = q1[v];
+            }
+        }
+    }
+    __syncthreads();
+    load_small64(Mm2, Ms, tid);
+    __syncthreads();
+    {
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < m) {
+                Yout[(long)r * B64 + lrow] = q0[v];
+                Yout[(long)r * B64 + 32 + lrow] = q1[v];
+            }
         }
     }
 }
@@ -490,20 +512,22 @@ __device__ __forceinline__ void tri_inv_upper_64(const float* U, float* X, int t
     __syncthreads();
 }
 
-// This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (even bounds), both
-// operands in LDS.  AUPPER: entries of A below its diagonal are taken as zero.
-template <bool AUPPER>
+// This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (multiples of 32), both
+// operands in LDS.  AMODE 1: entries of A below its diagonal are taken as zero; AMODE 2: A is taken as unit lower
+// triangular (stored diagonal and upper part ignored); AMODE 0: as stored.
+template <int AMODE>
 __device__ __forceinline__ f32x16 lds_mma(const float* A, const float* Bm, const float* kscale, int qi, int qj,
                                           int klo, int khi, int lrow, int lk) {
     f32x16 acc = zero16();
     const int row = 32 * qi + lrow;
-    for (int k0 = klo; k0 < khi; k0 += 16) {               // klo, khi are multiples of 32
+    for (int k0 = klo; k0 < khi; k0 += 16) {
         float a[8], b[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int k = k0 + 2 * u + lk;
             a[u] = A[row * LS + k];
-            if (AUPPER && k < row) a[u] = 0.f;
+            if (AMODE == 1 && k < row) a[u] = 0.f;
+            if (AMODE == 2) a[u] = (k < row) ? a[u] : (k == row ? 1.f : 0.f);
             if (kscale != nullptr) a[u] *= kscale[k];
             b[u] = Bm[k * LS + 32 * qj + lrow];
         }
@@ -536,47 +560,128 @@ __global__ __launch_bounds__(NSUM) void chol_inv_kernel(const float* __restrict_
     }
 }
 
+// Builds what the Householder panel code does not return itself: T of the block reflector from the reflectors in
+// the panel (m x 64 at A, unit lower trapezoidal) and tau, by the column recurrence
+//   T[0:j, j] = -tau_j T[0:j, 0:j] (V[:, 0:j]^T v_j),  T[j, j] = tau_j,
+// and Yp = V T.  One workgroup of NTHR threads; Bs: 3 * 64 * LS floats of LDS.  Slow path.
+__device__ void fallback_finish(const float* __restrict__ A, long lda, int m, const float* __restrict__ tau,
+                                float* __restrict__ Tout, float* __restrict__ Yp, float* Bs, int tid) {
+    const int lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+    float* Xs = Bs;                        // a 128-row tile (2 * 64 * LS floats)
+    float* Ms = Bs + 2 * B64 * LS;         // T, row stride 64
+    f32x16 acc = zero16();
+    for (int row0 = 0; row0 < m; row0 += RT) {
+        if (row0 > 0) __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        if (row0 == 0) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int e = tid + NTHR * q, r = e >> 6, c = e & 63;
+                if (c >= r) Xs[r * LS + c] = (c == r) ? 1.f : 0.f;
+            }
+            __syncthreads();
+        }
+        gram_tile(Xs, acc, qi, qj, lrow, lk);
+    }
+    __syncthreads();
+    acc_to_lds(acc, Xs, qi, qj, lrow, lk);                 // G = V^T V
+#pragma unroll
+    for (int q = 0; q < 16; ++q) Ms[tid + NTHR * q] = 0.f;
+    __syncthreads();
+    for (int j = 0; j < B64; ++j) {
+        const float tj = tau[j];
+        if (tid < j) {
+            float z = 0.f;
+            for (int k = tid; k < j; ++k) z += Ms[tid * B64 + k] * Xs[k * LS + j];
+            Ms[tid * B64 + j] = -tj * z;                   // column j is not read during this step
+        } else if (tid == j) {
+            Ms[j * B64 + j] = tj;
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) Tout[tid + NTHR * q] = Ms[tid + NTHR * q];
+    for (int row0 = 0; row0 < m; row0 += RT) {
+        __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        if (row0 == 0) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int e = tid + NTHR * q, r = e >> 6, c = e & 63;
+                if (c >= r) Xs[r * LS + c] = (c == r) ? 1.f : 0.f;
+            }
+            __syncthreads();
+        }
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < m) {
+                Yp[(long)r * B64 + lrow] = q0[v];
+                Yp[(long)r * B64 + 32 + lrow] = q1[v];
+            }
+        }
+    }
+}
+
 // Second small step (see the head of this file).  Inputs: partials of G2 = Q1^T Q1, the first 64 rows of Q1, U1.
-// Outputs when the orthogonality check passes (*fb = 0): the top 64 x 64 block of the panel in Atop (V_top strictly
-// below the diagonal, S U2 U1 on and above it), T (64 x 64, ld 64), Mm = (U_lu U2)^-1 (for the rows below the block).
-// Otherwise *fb = 1 and nothing else is written.
-__global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict__ part, int nparts,
-                                                         const float* __restrict__ Q1top,
-                                                         const float* __restrict__ U1, float* __restrict__ Atop,
-                                                         long lda, float* __restrict__ Tout, float* __restrict__ Mm,
+// When the orthogonality check passes (*fb = 0) it writes the top 64 x 64 block of the panel (V_top strictly below
+// the diagonal, S U2 U1 on and above it), T (64 x 64, ld 64), the first 64 rows of Yp = V T, and the two multipliers
+// for the rows below the block: Mm = (U_lu U2)^-1 (V = Q1 Mm) and Mm2 = Mm T (Yp = Q1 Mm2).
+// Otherwise (*fb = 1, DQ_FLAG_ILLCOND_PANEL raised) the workgroup factors the whole panel with the Householder
+// panel code and writes V, the triangular factor, tau, T and all of Yp itself.
+__global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict__ part, int nparts, float* q1,
+                                                         const float* __restrict__ U1, float* A, long lda, int m,
+                                                         float* __restrict__ Tout, float* __restrict__ Yp,
+                                                         float* __restrict__ Mm, float* __restrict__ Mm2,
+                                                         float* __restrict__ tau, float* __restrict__ tslices,
                                                          unsigned* __restrict__ fb, unsigned* __restrict__ status) {
-    __shared__ float B0[B64 * LS];
-    __shared__ float B1[B64 * LS];
-    __shared__ float B2[B64 * LS];
+    __shared__ float Bs[3 * B64 * LS];
     __shared__ float sg[B64];
     __shared__ float redw[4];
+    float* B0 = Bs;
+    float* B1 = Bs + B64 * LS;
+    float* B2 = Bs + 2 * B64 * LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
-    const int qi = wave >> 1, qj = wave & 1;
+    const int qi = (wave >> 1) & 1, qj = wave & 1;
 
     sum_partials(part, nparts, B0, tid);
-    if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
     {   // ||G2 - I||_F^2 must be small: then Q1 is well conditioned and the second pass gives orthonormal columns
-        float dev = 0.f;
+        if (tid < NTHR) {
+            float dev = 0.f;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int e = tid + NTHR * q;
-            const int i = e >> 6, j = e & 63;
-            const float x = B0[i * LS + j] - ((i == j) ? 1.f : 0.f);
-            if (j >= i) dev += (j > i ? 2.f : 1.f) * x * x;     // only the upper triangle was summed
+            for (int q = 0; q < 16; ++q) {
+                const int e = tid + NTHR * q;
+                const int i = e >> 6, j = e & 63;
+                const float x = B0[i * LS + j] - ((i == j) ? 1.f : 0.f);
+                if (j >= i) dev += (j > i ? 2.f : 1.f) * x * x;     // only the upper triangle was summed
+            }
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) dev += __shfl_xor(dev, off);
+            if (lane == 0) redw[wave] = dev;
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) dev += __shfl_xor(dev, off);
-        if (lane == 0) redw[wave] = dev;
         __syncthreads();
         const float total = redw[0] + redw[1] + redw[2] + redw[3];
         const bool ok = total < 0.25f;          // false for NaN as well
-        if (tid == 0) {
-            *fb = ok ? 0u : 1u;
-            if (!ok) atomicOr(status, DQ_FLAG_ILLCOND_PANEL);
+        if (tid == 0) *fb = ok ? 0u : 1u;
+        if (!ok) {
+            if (tid == 0) atomicOr(status, DQ_FLAG_ILLCOND_PANEL);
+            // q1 doubles as the packed reflector scratch of the panel code (Q1 is dead now)
+            qr_panel_body<NSUM, 16, 4, 16>(A, lda, m, B64, tau, q1, tslices, status, 1);
+            __syncthreads();
+            unpack_reflectors_body(A, lda, m, B64, q1, NSUM * 16, 4, 1, (long)tid, (long)NSUM);
+            __syncthreads();
+            if (tid >= NTHR) return;
+            fallback_finish(A, lda, m, tau, Tout, Yp, Bs, tid);
+            return;
         }
-        if (!ok) return;
     }
+    if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
     chol_upper_64(B0, tid);                     // B0 = U2
     tri_inv_upper_64<false>(B0, B1, tid);       // B1 = U2^-1
 #pragma unroll
@@ -587,66 +692,83 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     __syncthreads();
     // Rf = U2 U1 (upper x upper): kept in registers until the row signs are known
     f32x16 accR = zero16();
-    if (qi <= qj) accR = lds_mma<false>(B0, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+    if (qi <= qj) accR = lds_mma<0>(B0, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
-        B2[(e >> 6) * LS + (e & 63)] = Q1top[e];
+        B2[(e >> 6) * LS + (e & 63)] = q1[e];
     }
     __syncthreads();
     {   // Q_top = Q1_top U2^-1  -> B0
-        const f32x16 accQ = lds_mma<false>(B2, B1, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
+        const f32x16 accQ = lds_mma<0>(B2, B1, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
         acc_to_lds(accQ, B0, qi, qj, lrow, lk);
     }
     __syncthreads();
     lu_signed_64(B0, sg, tid);                  // B0 = L \ U_lu, sg = S
     tri_inv_upper_64<false>(B0, B2, tid);       // B2 = U_lu^-1
-    {   // Mm = U2^-1 U_lu^-1
-        f32x16 accM = zero16();
-        if (qi <= qj) accM = lds_mma<false>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+    // Mm = U2^-1 U_lu^-1, kept in registers as well: it is multiplied by T further down
+    f32x16 accM = zero16();
+    if (qi <= qj) accM = lds_mma<0>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            Mm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * B64 + 32 * qj + lrow] = accM[v];
-    }
+    for (int v = 0; v < 16; ++v) Mm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * B64 + 32 * qj + lrow] = accM[v];
     __syncthreads();
     // V_top to the panel; its transpose (unit upper triangular) to B1
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
         const int r = e >> 6, c = e & 63;
-        if (c < r) Atop[(long)r * lda + c] = B0[r * LS + c];
+        if (c < r) A[(long)r * lda + c] = B0[r * LS + c];
         B1[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
     }
     __syncthreads();
     tri_inv_upper_64<true>(B1, B2, tid);        // B2 = V_top^-T
-    {   // T = -(U_lu S) V_top^-T
+    {   // T = -(U_lu S) V_top^-T  -> global and B1; the triangular factor S Rf -> panel
         f32x16 accT = zero16();
-        if (qi <= qj) accT = lds_mma<true>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+        if (qi <= qj) accT = lds_mma<1>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+        __syncthreads();                        // every wavefront is done with B2 (and B1 was only read by tri_inv)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
-            Tout[r * B64 + c] = (c >= r) ? -accT[v] : 0.f;
-            if (c >= r) Atop[(long)r * lda + c] = sg[r] * accR[v];
+            const float t = (c >= r) ? -accT[v] : 0.f;
+            Tout[r * B64 + c] = t;
+            B1[r * LS + c] = t;
+            B2[r * LS + c] = accM[v];
+            if (c >= r) A[(long)r * lda + c] = sg[r] * accR[v];
+        }
+    }
+    __syncthreads();
+    {   // Mm2 = Mm T (upper x upper);  Yp_top = V_top T (unit lower x upper)
+        f32x16 acc2 = zero16();
+        if (qi <= qj) acc2 = lds_mma<0>(B2, B1, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+        const int kq = qi < qj ? qi : qj;
+        const f32x16 accY = lds_mma<2>(B0, B1, nullptr, qi, qj, 0, 32 * (kq + 1), lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
+            Mm2[r * B64 + c] = acc2[v];
+            Yp[r * B64 + c] = accY[v];
         }
     }
 }
 
 }  // namespace
 
-size_t cholpanel_scratch_floats() { return (size_t)kCholMaxParts * B64 * B64 + 3 * B64 * B64 + 64; }
+size_t cholpanel_scratch_floats() { return (size_t)kCholMaxParts * B64 * B64 + 4 * B64 * B64 + 64; }
 
 bool cholpanel_supported(const float* A, long lda, int m, int jb) {
     return jb == B64 && m >= 2 * B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
 }
 
-hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* q1, float* scratch, unsigned* fb,
-                               unsigned* status, hipStream_t s) {
+hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch,
+                               float* tau, float* tslices, unsigned* status, hipStream_t s) {
     if (!cholpanel_supported(A, lda, m, B64)) return hipErrorInvalidValue;
     float* part = scratch;
     float* U1 = part + (size_t)kCholMaxParts * B64 * B64;
     float* U1inv = U1 + B64 * B64;
     float* Mm = U1inv + B64 * B64;
+    float* Mm2 = Mm + B64 * B64;
+    unsigned* fb = reinterpret_cast<unsigned*>(Mm2 + B64 * B64);
     const int tiles = (m + RT - 1) / RT;
     // Gram partials (= workgroups of the tall-skinny kernels): more of them shorten those kernels but lengthen the
     // one-workgroup sums; 16 balances the two at m = 4096.  DQ_TALL_PANEL_PARTS overrides (tuning only).
@@ -660,10 +782,10 @@ hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* q1
     hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, part);
     hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, U1, U1inv);
     hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, U1inv, q1, part);
-    hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, q1, U1, A, lda, Tout, Mm, fb,
-                       status);
+    hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, q1, U1, A, lda, m, Tout, Yp, Mm,
+                       Mm2, tau, tslices, fb, status);
     const int below = (m - B64 + RT - 1) / RT;
-    hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, Mm, A, lda, fb);
+    hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, Mm, Mm2, A, lda, Yp, fb);
     return hipGetLastError();
 }
 
