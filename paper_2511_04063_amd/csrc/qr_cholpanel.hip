@@ -35,6 +35,14 @@ constexpr int NSUM = 512;        // threads of the small-matrix kernels while th
 
 #define MFMA32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32((a), (b), (c), 0, 0, 0)
 
+#ifdef DQ_SMALL_TRACE
+#define ST_DECL long long st_t0 = wall_clock64(), st_acc[16] = {0,0,0,0,0,0,0,0,0,0,0,0,0,0,0,0}
+#define ST(k) do { const long long t_ = wall_clock64(); st_acc[k] += t_ - st_t0; st_t0 = t_; } while (0)
+#else
+#define ST_DECL
+#define ST(k)
+#endif
+
 __device__ __forceinline__ f32x16 zero16() {
     f32x16 z;
 #pragma unroll
@@ -212,36 +220,67 @@ __global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ 
 // of Bm is set to zero): nothing downstream reads below the diagonal.  All loads of a thread are issued before
 // the first add: a single workgroup is bound by latency here, not by bandwidth.
 __device__ __forceinline__ void sum_partials(const float* __restrict__ part, int nparts, float* Bm, int tid) {
-    constexpr int PER = B64 * B64 / NSUM;
-    float s[PER];
+    constexpr int PER = B64 * B64 / 4 / NSUM;              // 16-byte pieces per thread
+    float4 s[PER];
 #pragma unroll
-    for (int q = 0; q < PER; ++q) s[q] = 0.f;
+    for (int q = 0; q < PER; ++q) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int z0 = 0; z0 < nparts; z0 += 16) {
-        float t[PER][16];
+        float4 t[PER][16];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const int e = tid + NSUM * q;
+            const int e = 4 * (tid + NSUM * q);
             const bool used = !((e >> 6) >= 32 && (e & 63) < 32);
 #pragma unroll
             for (int z = 0; z < 16; ++z)
-                t[q][z] = (used && z0 + z < nparts) ? part[(long)(z0 + z) * B64 * B64 + e] : 0.f;
+                t[q][z] = (used && z0 + z < nparts)
+                              ? *reinterpret_cast<const float4*>(part + (long)(z0 + z) * B64 * B64 + e)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int q = 0; q < PER; ++q)
 #pragma unroll
-            for (int z = 0; z < 16; ++z) s[q] += t[q][z];
+            for (int z = 0; z < 16; ++z) {
+                s[q].x += t[q][z].x; s[q].y += t[q][z].y; s[q].z += t[q][z].z; s[q].w += t[q][z].w;
+            }
     }
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int e = tid + NSUM * q;
-        Bm[(e >> 6) * LS + (e & 63)] = s[q];
+        const int e = 4 * (tid + NSUM * q);
+        float* d = Bm + (e >> 6) * LS + (e & 63);
+        d[0] = s[q].x; d[1] = s[q].y; d[2] = s[q].z; d[3] = s[q].w;
     }
     __syncthreads();
 }
 
+// Rank-8 update on the matrix cores of the 64 x 64 matrix Wm held in LDS (row stride LS), for the entries with
+// row >= lim and column >= lim only:  Wm[i][j] -= sum_{r<8} Lc(i, k0 + r) * Wm[k0 + r][j],  where Lc(i, k) is
+// Wm[i][k] (SYM = false: the multipliers sit in columns k0.. of the same matrix) or Wm[k][i] (SYM = true: the
+// symmetric case, multipliers are the transposed block row).  One 32 x 32 quadrant per wavefront.
+template <bool SYM>
+__device__ __forceinline__ void rank8_update(float* Wm, int k0, int lim, int qi, int qj, int lrow, int lk) {
+    if (32 * (qi + 1) <= lim || 32 * (qj + 1) <= lim) return;          // quadrant entirely finished
+    if (SYM && qi > qj) return;                                        // below the diagonal: never read
+    const int i = 32 * qi + lrow, j = 32 * qj + lrow;
+    float a[4], b[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        const int k = k0 + 2 * s4 + lk;
+        const float av = SYM ? Wm[k * LS + i] : Wm[i * LS + k];
+        a[s4] = (i >= lim) ? -av : 0.f;
+        b[s4] = (j >= lim) ? Wm[k * LS + j] : 0.f;
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = Wm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + j];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) acc = MFMA32(a[s4], b[s4], acc);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Wm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + j] = acc[v];
+}
+
 // In place: the upper triangle of the symmetric positive definite G becomes U with G = U^T U; the strict lower
 // triangle is zeroed.  Blocked by 8: every thread factors the 8 x 8 diagonal block in registers (no exchange),
-// one thread per column solves the block row, then a rank-8 update of the rest.
+// one thread per column solves the block row, then a rank-8 update of the rest on the matrix cores.
 __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
     for (int k0 = 0; k0 < B64; k0 += 8) {
         float d[8][8], id[8];
@@ -261,13 +300,6 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
 #pragma unroll
                 for (int c = i; c < 8; ++c) d[i][c] -= d[r][i] * d[r][c];
         }
-        __syncthreads();   // every thread has read the diagonal block
-        if (tid == 0) {
-#pragma unroll
-            for (int r = 0; r < 8; ++r)
-#pragma unroll
-                for (int c = r; c < 8; ++c) G[(k0 + r) * LS + k0 + c] = d[r][c];
-        }
         const int j = k0 + 8 + tid;
         if (j < B64) {
             float x[8];
@@ -284,28 +316,18 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
             for (int r = 0; r < 8; ++r) G[(k0 + r) * LS + j] = x[r];
         }
         __syncthreads();
-        const int bi = tid >> 4, bj = tid & 15;
-        if (4 * bi >= k0 + 8 && bj >= bi) {
-            float ui[8][4], uj[8][4];
+        rank8_update<true>(G, k0, k0 + 8, (tid >> 7) & 1, (tid >> 6) & 1, tid & 31, (tid >> 5) & 1);
+        __syncthreads();
+        // The factored diagonal block goes back only now: the update above rewrites whole quadrants, and nothing
+        // reads or writes these entries again before the next barrier.
+        if (tid == NTHR - 1) {
 #pragma unroll
             for (int r = 0; r < 8; ++r)
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    ui[r][a] = G[(k0 + r) * LS + 4 * bi + a];
-                    uj[r][a] = G[(k0 + r) * LS + 4 * bj + a];
-                }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) s += ui[r][a] * uj[r][b];
-                    G[(4 * bi + a) * LS + 4 * bj + b] -= s;
-                }
+                for (int c = r; c < 8; ++c) G[(k0 + r) * LS + k0 + c] = d[r][c];
         }
-        __syncthreads();
     }
+    __syncthreads();
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
@@ -335,15 +357,6 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
             for (int i = r + 1; i < 8; ++i)
 #pragma unroll
                 for (int c = r + 1; c < 8; ++c) d[i][c] -= d[i][r] * d[r][c];
-        }
-        __syncthreads();   // every thread has read the diagonal block
-        if (tid == 0) {
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                sg[k0 + r] = sv[r];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) W[(k0 + r) * LS + k0 + c] = d[r][c];
-            }
         }
         if (tid < 64) {                       // block column of L: x U_d = a, one row per thread
             const int i = k0 + 8 + tid;
@@ -379,28 +392,19 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
             }
         }
         __syncthreads();
-        const int bi = tid >> 4, bj = tid & 15;
-        if (4 * bi >= k0 + 8 && 4 * bj >= k0 + 8) {
-            float l[4][8], u[8][4];
-#pragma unroll
-            for (int r = 0; r < 8; ++r)
-#pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    l[a][r] = W[(4 * bi + a) * LS + k0 + r];
-                    u[r][a] = W[(k0 + r) * LS + 4 * bj + a];
-                }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    float s = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) s += l[a][r] * u[r][b];
-                    W[(4 * bi + a) * LS + 4 * bj + b] -= s;
-                }
-        }
+        rank8_update<false>(W, k0, k0 + 8, (tid >> 7) & 1, (tid >> 6) & 1, tid & 31, (tid >> 5) & 1);
         __syncthreads();
+        // the factored diagonal block goes back only now (see chol_upper_64)
+        if (tid == NTHR - 1) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                sg[k0 + r] = sv[r];
+#pragma unroll
+                for (int c = 0; c < 8; ++c) W[(k0 + r) * LS + k0 + c] = d[r][c];
+            }
+        }
     }
+    __syncthreads();
 }
 
 // One level of the triangular-inverse merge for diagonal blocks of size BL (8 or 16), see tri_inv_upper_64.
@@ -650,7 +654,9 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     const int lrow = lane & 31, lk = lane >> 5;
     const int qi = (wave >> 1) & 1, qj = wave & 1;
 
+    ST_DECL;
     sum_partials(part, nparts, B0, tid);
+    ST(0);
     {   // ||G2 - I||_F^2 must be small: then Q1 is well conditioned and the second pass gives orthonormal columns
         if (tid < NTHR) {
             float dev = 0.f;
@@ -682,8 +688,27 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         }
     }
     if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
-    chol_upper_64(B0, tid);                     // B0 = U2
-    tri_inv_upper_64<false>(B0, B1, tid);       // B1 = U2^-1
+    ST(1);
+    if (redw[0] + redw[1] + redw[2] + redw[3] < 4.0e-8f) {
+        // G2 = I + E with ||E||_F < 2e-4 (the usual case for a well-conditioned panel): the Cholesky factor is
+        // I + X with X = strict_upper(E) + diag(E) / 2 and its inverse I - X, both up to O(||E||^2) < fp32 rounding.
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            const int i = e >> 6, j = e & 63;
+            const float g = B0[i * LS + j];
+            const float x = (j > i) ? g : (j == i ? 0.5f * (g - 1.f) : 0.f);
+            const float dg = (i == j) ? 1.f : 0.f;
+            B0[i * LS + j] = (j >= i) ? dg + x : 0.f;
+            B1[i * LS + j] = (j >= i) ? dg - x : 0.f;
+        }
+        __syncthreads();
+    } else {
+        chol_upper_64(B0, tid);                 // B0 = U2
+        ST(2);
+        tri_inv_upper_64<false>(B0, B1, tid);   // B1 = U2^-1
+    }
+    ST(3);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
@@ -705,8 +730,11 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         acc_to_lds(accQ, B0, qi, qj, lrow, lk);
     }
     __syncthreads();
+    ST(4);
     lu_signed_64(B0, sg, tid);                  // B0 = L \ U_lu, sg = S
+    ST(5);
     tri_inv_upper_64<false>(B0, B2, tid);       // B2 = U_lu^-1
+    ST(6);
     // Mm = U2^-1 U_lu^-1, kept in registers as well: it is multiplied by T further down
     f32x16 accM = zero16();
     if (qi <= qj) accM = lds_mma<0>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
@@ -722,7 +750,9 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         B1[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
     }
     __syncthreads();
+    ST(7);
     tri_inv_upper_64<true>(B1, B2, tid);        // B2 = V_top^-T
+    ST(8);
     {   // T = -(U_lu S) V_top^-T  -> global and B1; the triangular factor S Rf -> panel
         f32x16 accT = zero16();
         if (qi <= qj) accT = lds_mma<1>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
@@ -750,6 +780,11 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
             Yp[r * B64 + c] = accY[v];
         }
     }
+    ST(9);
+#ifdef DQ_SMALL_TRACE
+    if (tid == 0 && m >= 3072 && m < 3200)
+        printf("hr_finish m=%d: sum %lld cert %lld chol %lld inv %lld Rf+Qtop %lld lu %lld inv %lld M+copy %lld inv %lld T+M2+Y %lld (10 ns ticks)\n", m, st_acc[0], st_acc[1], st_acc[2], st_acc[3], st_acc[4], st_acc[5], st_acc[6], st_acc[7], st_acc[8], st_acc[9]);
+#endif
 }
 
 }  // namespace
