@@ -5,6 +5,7 @@
 //   * inverses of the diagonal blocks of U for the blocked triangular solve,
 //   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
 #include "dq_internal.h"
+#include "dq_small64.h"
 
 namespace dq {
 namespace {
@@ -158,31 +159,61 @@ __global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict
     }
 }
 
-// Inverse of one diagonal block (w x w, w <= kTrsmBlock) of an upper-triangular matrix, by back substitution,
-// one thread per column of the inverse.  A zero pivot raises DQ_FLAG_SINGULAR (the result is then not finite).
-__global__ __launch_bounds__(kTrsmBlock) void trinv_blocks_kernel(const float* __restrict__ U, long ldu, int n,
-                                                                  float* __restrict__ Uinv, unsigned* flags) {
-    __shared__ float Xs[kTrsmBlock][kTrsmBlock];
+// Inverse of one 128 x 128 diagonal block (w x w used, w <= kTrsmBlock) of an upper-triangular matrix, one
+// workgroup per block:  inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1], [0, C^-1]]  with the 64 x 64 inverses and the
+// two products done out of LDS on the matrix cores.  Rows and columns beyond w are padded with the identity for
+// the computation and written as zero.  A zero pivot raises DQ_FLAG_SINGULAR (the result is then not finite).
+static_assert(kTrsmBlock == 2 * B64, "the block inverse is built from 64 x 64 pieces");
+__device__ __forceinline__ void load_block64(const float* __restrict__ Ub, long ldu, int w, int r0, int c0, float* dst,
+                                             int tid) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        const int i = r0 + (e >> 6), j = c0 + (e & 63);
+        dst[(e >> 6) * LS + (e & 63)] = (i < w && j < w) ? Ub[(long)i * ldu + j] : (i == j ? 1.f : 0.f);
+    }
+    __syncthreads();
+}
+__device__ __forceinline__ void store_block64(const float* src, float* __restrict__ out, int w, int r0, int c0, int tid) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        const int i = r0 + (e >> 6), j = c0 + (e & 63);
+        out[(long)i * kTrsmBlock + j] = (i < w && j < w) ? src[(e >> 6) * LS + (e & 63)] : 0.f;
+    }
+}
+__global__ __launch_bounds__(NTHR) void trinv_blocks_kernel(const float* __restrict__ U, long ldu, int n,
+                                                            float* __restrict__ Uinv, unsigned* flags) {
+    __shared__ float Bs[3 * B64 * LS];
+    float* B0 = Bs;
+    float* B1 = Bs + B64 * LS;
+    float* B2 = Bs + 2 * B64 * LS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5, qi = wave >> 1, qj = wave & 1;
     const int blk = blockIdx.x;
     const int j0 = blk * kTrsmBlock;
     const int w = (n - j0) < kTrsmBlock ? (n - j0) : kTrsmBlock;
     const float* Ub = U + (long)j0 * ldu + j0;
-    const int j = threadIdx.x;
-    if (j < w) {
-        const float ujj = Ub[(long)j * ldu + j];
-        if (ujj == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
-        Xs[j][j] = 1.f / ujj;
-        for (int i = j - 1; i >= 0; --i) {
-            const float* urow = Ub + (long)i * ldu;
-            float acc = 0.f;
-            for (int k = i + 1; k <= j; ++k) acc += urow[k] * Xs[k][j];
-            Xs[i][j] = -acc / urow[i];
-        }
-    }
-    __syncthreads();
     float* out = Uinv + (long)blk * kTrsmBlock * kTrsmBlock;
-    for (int i = 0; i < kTrsmBlock; ++i)
-        out[(long)i * kTrsmBlock + j] = (i <= j && j < w) ? Xs[i][j] : 0.f;
+    if (tid < w && Ub[(long)tid * ldu + tid] == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+    load_block64(Ub, ldu, w, 0, 0, B0, tid);
+    tri_inv_upper_64<false>(B0, B1, tid);                   // B1 = A^-1
+    store_block64(B1, out, w, 0, 0, tid);
+    load_block64(Ub, ldu, w, B64, B64, B0, tid);
+    tri_inv_upper_64<false>(B0, B2, tid);                   // B2 = C^-1
+    store_block64(B2, out, w, B64, B64, tid);
+    load_block64(Ub, ldu, w, 0, B64, B0, tid);              // B0 = B
+    const f32x16 t = lds_mma<0>(B0, B2, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
+    __syncthreads();
+    acc_to_lds(t, B0, qi, qj, lrow, lk);                    // B0 = B C^-1
+    __syncthreads();
+    const f32x16 x = lds_mma<0>(B1, B0, nullptr, qi, qj, 32 * qi, B64, lrow, lk);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int i = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), j = 32 * qj + lrow;
+        out[(long)i * kTrsmBlock + B64 + j] = (i < w && B64 + j < w) ? -x[v] : 0.f;
+        out[(long)(B64 + i) * kTrsmBlock + j] = 0.f;
+    }
 }
 
 __global__ __launch_bounds__(256) void axpy2d_kernel(float* __restrict__ Z, long ldz, const float* __restrict__ D,
@@ -241,7 +272,7 @@ hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp
 
 hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s) {
     const int nb = (n + kTrsmBlock - 1) / kTrsmBlock;
-    hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb), dim3(kTrsmBlock), 0, s, U, ldu, n, Uinv, flags);
+    hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb), dim3(NTHR), 0, s, U, ldu, n, Uinv, flags);
     return hipGetLastError();
 }
 
