@@ -161,10 +161,12 @@ dq_status check_ws(dq_ctx* c, const Layout& L) {
 // ---------------------------------------------------------------- split-K choice
 // Enough layers to give every compute unit a workgroup when the output has few tiles.
 void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int& kchunk) {
+    static const int target = [] { const char* e = getenv("DQ_SPLIT_TARGET"); return e ? atoi(e) : 768; }();
+    static const int mink = [] { const char* e = getenv("DQ_SPLIT_MINK"); return e ? atoi(e) : 128; }();
     splits = 1;
     if (tiles < 256) {
-        splits = (768 + tiles - 1) / tiles;
-        const int by_k = (K + 127) / 128;   // at least 128 reduction elements per layer
+        splits = (target + tiles - 1) / tiles;
+        const int by_k = (K + mink - 1) / mink;   // at least `mink` reduction elements per layer
         if (splits > by_k) splits = by_k;
         if (splits > max_splits) splits = max_splits;
         if (splits < 1) splits = 1;
@@ -302,6 +304,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     const int nb = c->nb;
     const int npanels = (n + nb - 1) / nb;
     int last_trailing = -1;
+    bool gram_ready = false;   // the Gram partials of the coming panel were left by the previous panel's look-ahead
     for (int p = 0; p < npanels; ++p) {
         const int k0 = p * nb;
         const int jb = (n - k0) < nb ? (n - k0) : nb;
@@ -315,18 +318,31 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         // Gram matrix of the reflectors.
         const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
         if (tall) {
+            // the look-ahead update of the next panel's columns is fused into the last two kernels of the route when
+            // that panel is a full one; they also leave the Gram partials the next tall panel starts from
+            const int m2 = m - jb;
+            const bool fused_la = nla == kPanel;
+            const bool next_tall = fused_la && m2 >= c->chol_min_m &&
+                                   cholpanel_supported(Ap + (long)jb * ld + jb, ld, m2, m2 < nb ? m2 : nb);
             {
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
-                DQ_HIP(launch_cholqr_panel(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags, sA));
+                DQ_HIP(launch_cholqr_factor(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags,
+                                            gram_ready ? 1 : 0, sA));
             }
             // the look-ahead columns received update p-1 on the second stream
             if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
-            if (nla > 0) {   // C_la -= V (Yp^T C_la)
+            {
+                LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 4.0 * m * (double)jb * nla, 0.0);
+                DQ_HIP(launch_cholqr_finish(Ap, ld, m, Yp, vs, at<float>(c, L.cq), fused_la ? 1 : 0, next_tall ? 1 : 0, sA));
+            }
+            gram_ready = next_tall;
+            if (!fused_la && nla > 0) {   // C_la -= V (Yp^T C_la)
                 const float* Wa = nullptr;
                 DQ_TRY(refl_project(c, sA, L, bufA, Yp, kPanel, m, jb, Ap + jb, ld, nla, 0, &Wa, kMaxSplit, nullptr, 0));
                 DQ_TRY(refl_update(c, sA, L, Ap, ld, Wa, m, jb, Ap + jb, ld, nla));
             }
         } else {
+            gram_ready = false;
             int sw = 8;
             {
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);

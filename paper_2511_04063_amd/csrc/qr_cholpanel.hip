@@ -198,6 +198,196 @@ __global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ 
     }
 }
 
+// acc += (X^T C)[32 qi + ., 32 qj + .] over the 128 rows of two tiles
+__device__ __forceinline__ void proj_tile(const float* Xs, const float* Cs, f32x16& acc, int qi, int qj, int lrow,
+                                          int lk) {
+#pragma unroll 8
+    for (int r = 0; r < RT; r += 2) {
+        const float a = Xs[(r + lk) * LS + 32 * qi + lrow];
+        const float b = Cs[(r + lk) * LS + 32 * qj + lrow];
+        acc = MFMA32(a, b, acc);
+    }
+}
+
+// rows [32 wave, 32 wave + 32) of the tile times the full 64 x 64 matrix in Ws (row stride LS)
+__device__ __forceinline__ void mul_tile_full(const float* Xs, const float* Ws, f32x16& acc0, f32x16& acc1, int wave,
+                                              int lrow, int lk) {
+#pragma unroll 8
+    for (int k0 = 0; k0 < B64; k0 += 2) {
+        const float a = Xs[(32 * wave + lrow) * LS + k0 + lk];
+        acc0 = MFMA32(a, Ws[(k0 + lk) * LS + lrow], acc0);
+        acc1 = MFMA32(a, Ws[(k0 + lk) * LS + 32 + lrow], acc1);
+    }
+}
+
+// the first 64 rows of a reflector block as stored in the factored matrix -> unit lower triangular, in place in Xs
+__device__ __forceinline__ void mask_unit_lower(float* Xs, int tid) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q, r = e >> 6, c = e & 63;
+        if (c >= r) Xs[r * LS + c] = (c == r) ? 1.f : 0.f;
+    }
+}
+
+// Last step of the tall-panel route fused with the first half of the look-ahead update of the next 64 columns
+// C = A[:, 64:128]:  for its rows (workgroup 0: the top 64 rows; workgroup b >= 1: tpw tiles of 128 rows from row
+// 64 + (b - 1) tpw 128) it writes V = Q1 Mm and Yp = Q1 Mm2 (rows >= 64; when *fb != 0 both were already written
+// by the fallback and Yp is read back instead) and the partial  wpart[b] = Yp_rows^T C_rows  of the projection.
+__global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restrict__ Q1, int m,
+                                                           const float* __restrict__ Mm, const float* __restrict__ Mm2,
+                                                           float* A, long lda, float* Yp,
+                                                           const unsigned* __restrict__ fb, int tpw,
+                                                           float* __restrict__ wpart) {
+    __shared__ float Xs[RT * LS];
+    __shared__ float Cs[RT * LS];
+    __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+    const float* C = A + B64;
+    f32x16 acc = zero16();
+    if (blockIdx.x == 0) {
+        load_tile(Yp, B64, 0, B64, Xs, tid);
+        load_tile(C, lda, 0, B64, Cs, tid);
+        __syncthreads();
+        proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+    } else {
+        const bool fell_back = *fb != 0u;
+        for (int t = 0; t < tpw; ++t) {
+            const int row0 = B64 + ((blockIdx.x - 1) * tpw + t) * RT;
+            if (row0 >= m) break;
+            if (t > 0) __syncthreads();
+            if (!fell_back) {
+                load_small64(Mm, Ms, tid);
+                load_tile(Q1, B64, row0, m, Xs, tid);
+                __syncthreads();
+                {
+                    f32x16 q0 = zero16(), q1 = zero16();
+                    mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+                        if (r < m) {
+                            A[(long)r * lda + lrow] = q0[v];
+                            A[(long)r * lda + 32 + lrow] = q1[v];
+                        }
+                    }
+                }
+                __syncthreads();
+                load_small64(Mm2, Ms, tid);
+                __syncthreads();
+                f32x16 q0 = zero16(), q1 = zero16();
+                mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+                // each wavefront only read its own 32 rows of the tile: it may overwrite them with Yp right away
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+                    Xs[rl * LS + lrow] = q0[v];
+                    Xs[rl * LS + 32 + lrow] = q1[v];
+                    if (row0 + rl < m) {
+                        Yp[(long)(row0 + rl) * B64 + lrow] = q0[v];
+                        Yp[(long)(row0 + rl) * B64 + 32 + lrow] = q1[v];
+                    }
+                }
+            } else {
+                load_tile(Yp, B64, row0, m, Xs, tid);
+            }
+            load_tile(C, lda, row0, m, Cs, tid);
+            __syncthreads();
+            proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+        }
+    }
+    store_partial(wpart + (long)blockIdx.x * B64 * B64, acc, qi, qj, lrow, lk);
+}
+
+// Second half of the look-ahead update:  W2 = sum of the nproj partials,  C -= V W2  for C = A[:, 64:128] (same row
+// split as ts_mul_proj_kernel) and, when part_next != null, the Gram partials  part_next[b - 1] = C_rows^T C_rows
+// of the updated rows >= 64, which are the next panel: its factorisation then starts from them.
+__global__ __launch_bounds__(NTHR) void la_update_gram_kernel(float* A, long lda, int m,
+                                                              const float* __restrict__ wpart, int nproj, int tpw,
+                                                              float* __restrict__ part_next) {
+    __shared__ float Xs[RT * LS];
+    __shared__ float Ws[B64 * LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = wave >> 1, qj = wave & 1;
+    {   // W2: 4 sixteen-byte pieces per thread, partials in groups of 8 (all loads of a group in flight)
+        float4 s4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int z0 = 0; z0 < nproj; z0 += 8) {
+            float4 t[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+                    t[q][z] = (z0 + z < nproj)
+                                  ? *reinterpret_cast<const float4*>(wpart + (long)(z0 + z) * B64 * B64 + 4 * (tid + NTHR * q))
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int z = 0; z < 8; ++z) {
+                    s4[q].x += t[q][z].x; s4[q].y += t[q][z].y; s4[q].z += t[q][z].z; s4[q].w += t[q][z].w;
+                }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = 4 * (tid + NTHR * q);
+            float* d = Ws + (e >> 6) * LS + (e & 63);
+            d[0] = s4[q].x; d[1] = s4[q].y; d[2] = s4[q].z; d[3] = s4[q].w;
+        }
+    }
+    float* C = A + B64;
+    if (blockIdx.x == 0) {
+        load_tile(A, lda, 0, B64, Xs, tid);
+        __syncthreads();
+        mask_unit_lower(Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < B64) {
+                C[(long)r * lda + lrow] -= q0[v];
+                C[(long)r * lda + 32 + lrow] -= q1[v];
+            }
+        }
+        return;
+    }
+    f32x16 acc = zero16();
+    for (int t = 0; t < tpw; ++t) {
+        const int row0 = B64 + ((blockIdx.x - 1) * tpw + t) * RT;
+        if (row0 >= m) break;
+        if (t > 0) __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
+        // each wavefront only read its own 32 rows of the tile: it replaces them by the updated rows of C
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            const int r = row0 + rl;
+            float c0 = 0.f, c1 = 0.f;
+            if (r < m) {
+                c0 = C[(long)r * lda + lrow] - q0[v];
+                c1 = C[(long)r * lda + 32 + lrow] - q1[v];
+                C[(long)r * lda + lrow] = c0;
+                C[(long)r * lda + 32 + lrow] = c1;
+            }
+            Xs[rl * LS + lrow] = c0;
+            Xs[rl * LS + 32 + lrow] = c1;
+        }
+        if (part_next != nullptr) {
+            __syncthreads();
+            gram_tile(Xs, acc, qi, qj, lrow, lk);
+        }
+    }
+    if (part_next != nullptr) store_partial(part_next + (long)(blockIdx.x - 1) * B64 * B64, acc, qi, qj, lrow, lk);
+}
+
 // ------------------------------------------------------------------------------------------------------------
 // 64 x 64 building blocks in LDS (row stride LS), one workgroup of 256 threads; every function ends with a
 // barrier and must be called by all threads.
@@ -637,38 +827,70 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 
 }  // namespace
 
-size_t cholpanel_scratch_floats() { return (size_t)kCholMaxParts * B64 * B64 + 4 * B64 * B64 + 64; }
+size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 1) * B64 * B64 + 4 * B64 * B64 + 64; }
 
 bool cholpanel_supported(const float* A, long lda, int m, int jb) {
     return jb == B64 && m >= 2 * B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
 }
 
-hipError_t launch_cholqr_panel(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch,
-                               float* tau, float* tslices, unsigned* status, hipStream_t s) {
-    if (!cholpanel_supported(A, lda, m, B64)) return hipErrorInvalidValue;
-    float* part = scratch;
-    float* U1 = part + (size_t)kCholMaxParts * B64 * B64;
-    float* U1inv = U1 + B64 * B64;
-    float* Mm = U1inv + B64 * B64;
-    float* Mm2 = Mm + B64 * B64;
-    unsigned* fb = reinterpret_cast<unsigned*>(Mm2 + B64 * B64);
-    const int tiles = (m + RT - 1) / RT;
-    // Gram partials (= workgroups of the tall-skinny kernels): more of them shorten those kernels but lengthen the
-    // one-workgroup sums; 16 balances the two at m = 4096.  DQ_TALL_PANEL_PARTS overrides (tuning only).
+namespace {
+struct TallScratch {
+    float *part, *U1, *U1inv, *Mm, *Mm2, *wpart;
+    unsigned* fb;
+    explicit TallScratch(float* scratch) {
+        part = scratch;
+        U1 = part + (size_t)kCholMaxParts * B64 * B64;
+        U1inv = U1 + B64 * B64;
+        Mm = U1inv + B64 * B64;
+        Mm2 = Mm + B64 * B64;
+        fb = reinterpret_cast<unsigned*>(Mm2 + B64 * B64);
+        wpart = Mm2 + B64 * B64 + 64;
+    }
+};
+// Row tiles of 128 per workgroup and number of workgroups (= Gram partials) for a panel of m rows.  More partials
+// shorten the tall-skinny kernels but lengthen the one-workgroup sums; 16 balances the two at m = 4096.
+// DQ_TALL_PANEL_PARTS overrides (tuning only).
+void tall_split(int m, int& tpw, int& nparts) {
     static const int parts_cap = [] {
         const char* e = getenv("DQ_TALL_PANEL_PARTS");
         int v = e ? atoi(e) : 16;
         return v < 1 ? 1 : (v > kCholMaxParts ? kCholMaxParts : v);
     }();
-    const int tpw = (tiles + parts_cap - 1) / parts_cap;               // row tiles per workgroup
-    const int nparts = (tiles + tpw - 1) / tpw;
-    hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, part);
-    hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, U1, U1inv);
-    hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, U1inv, q1, part);
-    hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, part, nparts, q1, U1, A, lda, m, Tout, Yp, Mm,
-                       Mm2, tau, tslices, fb, status);
-    const int below = (m - B64 + RT - 1) / RT;
-    hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, Mm, Mm2, A, lda, Yp, fb);
+    const int tiles = (m + RT - 1) / RT;
+    tpw = (tiles + parts_cap - 1) / parts_cap;
+    nparts = (tiles + tpw - 1) / tpw;
+}
+}  // namespace
+
+hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch,
+                                float* tau, float* tslices, unsigned* status, int have_gram, hipStream_t s) {
+    if (!cholpanel_supported(A, lda, m, B64)) return hipErrorInvalidValue;
+    const TallScratch ts(scratch);
+    int tpw, nparts;
+    tall_split(m, tpw, nparts);
+    if (!have_gram) hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.part);
+    hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, ts.U1, ts.U1inv);
+    hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.U1inv, q1, ts.part);
+    hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, q1, ts.U1, A, lda, m, Tout, Yp,
+                       ts.Mm, ts.Mm2, tau, tslices, ts.fb, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1, float* scratch, int lookahead,
+                                int next_gram, hipStream_t s) {
+    const TallScratch ts(scratch);
+    if (!lookahead) {
+        const int below = (m - B64 + RT - 1) / RT;
+        hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb);
+        return hipGetLastError();
+    }
+    // the rows below the top block are split exactly as the next panel (m - 64 rows) splits its own rows
+    int tpw, nparts;
+    tall_split(m - B64, tpw, nparts);
+    hipLaunchKernelGGL(ts_mul_proj_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, q1, m, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb,
+                       tpw, ts.wpart);
+    hipLaunchKernelGGL(la_update_gram_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, A, lda, m, ts.wpart, nparts + 1, tpw,
+                       next_gram ? ts.part : static_cast<float*>(nullptr));
     return hipGetLastError();
 }
 
