@@ -190,11 +190,15 @@ dq_status refl_project(dq_ctx* c, hipStream_t s, const Layout& L, const ReflBufs
     const long ldw = L.ld;
     const long stride = (long)kPanel * ldw;
     int splits, kchunk;
-    const int tn = gemm_f32_tile_n(jb, ncols);
-    choose_split((ncols + tn - 1) / tn, m, 16, max_splits, splits, kchunk);
+    // A plain left operand (V T) streams best through the 64 x 64 tile configuration (4 workgroups per compute unit);
+    // the masked reflector block keeps the shape-chosen one, whose split count the T-factor kernel is sized for.
+    const bool small_tiles = !a_unit_lower;
+    const int tn = small_tiles ? 64 : gemm_f32_tile_n(jb, ncols);
+    choose_split((ncols + tn - 1) / tn, m, small_tiles ? 32 : 16, max_splits, splits, kchunk);
     if (splits_out != nullptr) *splits_out = splits;
     {
         GemmF32 g;
+        if (small_tiles) g.cfg = 3;
         g.A = Vp; g.lda = ldv; g.ta = 1; g.a_unit_lower = a_unit_lower;
         g.B = Bmat; g.ldb = ldb; g.tb = 0; g.b_unit_lower_cols = gram_cols;
         g.C = bufs.wpart; g.ldc = ldw;

@@ -48,6 +48,7 @@ struct GemmF32 {
     int b_strict_lower = 0;
     // split-K: z-th workgroup layer reduces k in [z*kchunk, (z+1)*kchunk) and writes C + z*split_stride
     int splits = 1; int kchunk = 0; long split_stride = 0;
+    int cfg = -1;          // tile configuration (-1: chosen from the shape; 3: 64 x 64 tiles, K step 32)
 };
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s);
 int gemm_f32_tile_n(int M, int N);   // width of the workgroup tile the launcher picks

@@ -284,7 +284,7 @@ int gemm_f32_tile_n(int M, int N) { return N <= 128 ? 64 : ((M <= 64) ? 256 : 12
 
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
-    switch (gemm_f32_config(g.M, g.N, g.splits)) {
+    switch (g.cfg >= 0 ? g.cfg : gemm_f32_config(g.M, g.N, g.splits)) {
         case 1: return launch_gemm_f32_tile<64, 256, 2, 16>(g, s);
         case 2: return launch_gemm_f32_tile<256, 64, 2, 16>(g, s);
         case 3: return launch_gemm_f32_tile<64, 64, 1, 32>(g, s);
