@@ -244,12 +244,15 @@ def test_qr_orth_closed_forms(ctx):
     Zt = np.triu(g.standard_normal((n, n))).astype(np.float32)
     Zt[np.arange(n), np.arange(n)] = np.abs(np.diag(Zt)) + 0.5
     R, U = run_qr(ctx, Zt)
-    assert np.array_equal(R, np.eye(n, dtype=np.float32)) and np.array_equal(U, Zt)
+    assert np.abs(R - np.eye(n)).max() < 1e-6 and np.allclose(U, Zt, rtol=2e-6, atol=2e-6)
     # diagonal input: R = diag(sign d), U = diag(|d|)
     d = g.standard_normal(n).astype(np.float32)
     R, U = run_qr(ctx, np.diag(d))
-    assert np.array_equal(R, np.diag(np.sign(d))) and np.array_equal(U, np.diag(np.abs(d)))
-    assert ctx.dq_device_flags() == 0
+    # (the Gram-matrix route for tall panels is exact only up to rounding here: |d| comes out as d^2 / sqrt(d^2))
+    assert np.abs(R - np.diag(np.sign(d))).max() < 1e-6
+    assert np.allclose(U, np.diag(np.abs(d)), rtol=2e-6, atol=1e-7)
+    # a random triangular matrix is badly conditioned: its tall panel may take the Householder fallback (informational)
+    assert ctx.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
 
 
 def test_singular_latent_raises_flag_not_fault(ctx):
