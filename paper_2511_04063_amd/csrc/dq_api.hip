@@ -574,29 +574,8 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     if (const char* e = getenv("DQ_TALL_PANEL_MIN_M")) { const int v = atoi(e); if (v >= 0) c->chol_min_m = v; }
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
     // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream
-    int reserve = 0;
-    if (const char* e = getenv("DQ_RESERVE_CUS")) reserve = atoi(e);
-    if (reserve > 0 && c->stream != nullptr) {
-        // Experimental: keep `reserve` compute units free of the side streams' GEMMs so that the latency-critical
-        // panel chain on the caller's stream always finds idle ones.  (Streams with a CU mask synchronise with the
-        // legacy default stream, hence only when the caller's stream is another one.)
-        hipDeviceProp_t prop;
-        if (hipGetDeviceProperties(&prop, c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
-        const int ncu = prop.multiProcessorCount;
-        std::vector<uint32_t> mask((ncu + 31) / 32, 0u);
-        const char* mode = getenv("DQ_RESERVE_MODE");
-        const int stride = (mode != nullptr && atoi(mode) > 1) ? atoi(mode) : 1;
-        int left = reserve;
-        for (int i = 0; i < ncu; ++i) {
-            const bool res = left > 0 && (i % stride) == 0;
-            if (res) --left; else mask[i / 32] |= 1u << (i % 32);
-        }
-        if (hipExtStreamCreateWithCUMask(&c->stream2, (uint32_t)mask.size(), mask.data()) != hipSuccess) c->stream2 = nullptr;
-        if (hipExtStreamCreateWithCUMask(&c->stream3, (uint32_t)mask.size(), mask.data()) != hipSuccess) c->stream3 = nullptr;
-        (void)hipGetLastError();
-    }
-    if (c->stream2 == nullptr && hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }
-    if (c->stream3 == nullptr && hipStreamCreateWithFlags(&c->stream3, hipStreamNonBlocking) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
+    if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }
+    if (hipStreamCreateWithFlags(&c->stream3, hipStreamNonBlocking) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
     const int nev = 2 * (DQ_MAX_N / kPanelMin) + 1;
     for (int i = 0; i < nev; ++i) {
         hipEvent_t e;
