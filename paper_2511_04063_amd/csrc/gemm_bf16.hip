@@ -12,6 +12,8 @@
 // B operand 8 consecutive k of column n = l % 32, both for k group l / 32; accumulator register v holds
 // D[m = 8*(v/4) + 4*(l/32) + v%4][n = l % 32].  Both operands are fetched with the same k assignment, so
 // only the m / n / D mappings matter for correctness.
+#include <stdlib.h>
+
 #include "dq_internal.h"
 
 namespace dq {
@@ -208,6 +210,133 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m,
     }
 }
 
+// ---- large "NT" products (both operands k-contiguous: A is M x K, B is N x K) ---------------------------------
+// Same 128 x 128 x 32 tile and wavefront layout as above, but without guards (M, N multiples of 128, K of 128,
+// 16-byte aligned rows; a_kwrap a multiple of 32 with a_klim == a_kwrap) and with FOUR K steps of operands in flight
+// in registers: a K step is only 8 MFMAs per wavefront, far shorter than the memory latency, and two workgroups per
+// compute unit do not hide it.  The loop body has no early exit (K % 128 == 0).
+__device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDH], const bf16_t (*Bsc)[LDH], f32x16 (&acc)[2][2],
+                                              int wm, int wn, int lrow, int lk) {
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+        bf16x8 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&Asc[wm + i * 32 + lrow][ks + lk * 8]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(&Bsc[wn + j * 32 + lrow][ks + lk * 8]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+__global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int tiles_m, int tiles_n) {
+    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM][LDH];
+    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN][LDH];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    // XCD-aware tile order (see gemm_f32.hip)
+    const int nt = tiles_m * tiles_n;
+    const int bid = blockIdx.x;
+    const int q8 = nt >> 3, r8 = nt & 7;
+    const int xcd = bid & 7;
+    const int pid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    const int group = 8 * tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * 8;
+    const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int pid_m = first_m + (pid % group) % gsz;
+    const int pid_n = (pid % group) / gsz;
+    const int m0 = pid_m * BM, n0 = pid_n * BN;
+
+    const int wrap = g.a_kwrap;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    // thread t moves the 16-byte piece (row t / 4 + 64 i, k-offset 8 (t % 4)) of each operand tile, i = 0, 1
+    const int prow = tid >> 2, pk = (tid & 3) << 3;
+    const bf16_t* pa = g.A + (long)(m0 + prow) * g.lda + pk;
+    const bf16_t* pb = g.B + (long)(n0 + prow) * g.ldb + pk;
+    const long sa = 64 * g.lda, sb = 64 * g.ldb;
+
+    const int nk = g.K / BK;
+    struct Stage { uint4 a0, a1, b0, b1; };
+    Stage st0, st1, st2, st3;
+
+#define DQ_FETCH(kt, st)                                                                           \
+    if ((kt) < nk) {                                                                               \
+        const int k0_ = (kt) * BK;                                                                 \
+        const int ka_ = (wrap > 0 && k0_ >= wrap) ? k0_ - wrap : k0_;                              \
+        st.a0 = *reinterpret_cast<const uint4*>(pa + ka_);                                         \
+        st.a1 = *reinterpret_cast<const uint4*>(pa + sa + ka_);                                    \
+        st.b0 = *reinterpret_cast<const uint4*>(pb + k0_);                                         \
+        st.b1 = *reinterpret_cast<const uint4*>(pb + sb + k0_);                                    \
+    }
+#define DQ_STASH(buf, st)                                                                          \
+    {                                                                                              \
+        *reinterpret_cast<uint4*>(&As[buf][prow][pk]) = st.a0;                                     \
+        *reinterpret_cast<uint4*>(&As[buf][prow + 64][pk]) = st.a1;                                \
+        *reinterpret_cast<uint4*>(&Bs[buf][prow][pk]) = st.b0;                                     \
+        *reinterpret_cast<uint4*>(&Bs[buf][prow + 64][pk]) = st.b1;                                \
+    }
+#define DQ_MULTIPLY(cur) multiply_tile(As[cur], Bs[cur], acc, wm, wn, lrow, lk);
+    // tile kt is in LDS buffer `buf`, tile kt+1 in (fa_next, fb_next); tile kt+4 is requested into the registers that
+    // held tile kt
+#define DQ_STEP(kt, buf, st_next, st_free)                                                         \
+    {                                                                                              \
+        DQ_FETCH((kt) + 4, st_free)                                                                \
+        DQ_MULTIPLY(buf)                                                                           \
+        if ((kt) + 1 < nk) { DQ_STASH(1 - (buf), st_next) }                                        \
+        __syncthreads();                                                                           \
+    }
+    st0.a0 = st0.a1 = st0.b0 = st0.b1 = make_uint4(0u, 0u, 0u, 0u);
+    st1 = st0; st2 = st0; st3 = st0;
+    DQ_FETCH(0, st0)
+    DQ_FETCH(1, st1)
+    DQ_FETCH(2, st2)
+    DQ_FETCH(3, st3)
+    DQ_STASH(0, st0)
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 4) {
+        DQ_STEP(kt, 0, st1, st0)
+        DQ_STEP(kt + 1, 1, st2, st1)
+        DQ_STEP(kt + 2, 0, st3, st2)
+        DQ_STEP(kt + 3, 1, st0, st3)
+    }
+#undef DQ_STEP
+#undef DQ_MULTIPLY
+#undef DQ_STASH
+#undef DQ_FETCH
+
+    float* C = g.C;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                C[(long)row * g.ldc + col] = acc[i][j][v];
+            }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
@@ -215,6 +344,15 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 7) == 0) ? 1 : 0;
     const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0) ? 1 : 0;
+    // big NT products without split-K and with round sizes: the unguarded kernel with the deep prefetch
+    static const int use_deep = [] { const char* e = getenv("DQ_BF16_DEEP"); return e ? atoi(e) : 1; }();
+    const bool fits = !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (4 * BK) == 0 &&
+                      tiles_m * tiles_n >= 256 && avec && bvec &&
+                      (g.a_kwrap == 0 || (g.a_kwrap % BK == 0 && g.a_klim == g.a_kwrap));
+    if (use_deep && fits) {
+        hipLaunchKernelGGL(gemm_bf16_nt_deep_kernel, dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m, tiles_n);
+        return hipGetLastError();
+    }
     dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
     dim3 block(256, 1, 1);
     if (g.ta && g.tb)

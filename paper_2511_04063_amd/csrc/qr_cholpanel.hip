@@ -102,6 +102,7 @@ __device__ __forceinline__ void mul_tile(const float* Xs, const float* Ms, f32x1
 // part[blockIdx.x] (64 x 64) = sum over this workgroup's rows of A^T A
 __global__ __launch_bounds__(NTHR) void ts_gram_kernel(const float* __restrict__ A, long lda, int m, int tiles_per_wg,
                                                        float* __restrict__ part) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
@@ -122,6 +123,7 @@ __global__ __launch_bounds__(NTHR) void ts_gram_kernel(const float* __restrict__
 __global__ __launch_bounds__(NTHR) void ts_mul_gram_kernel(const float* __restrict__ A, long lda, int m,
                                                            int tiles_per_wg, const float* __restrict__ Minv,
                                                            float* __restrict__ Q1, float* __restrict__ part) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -160,6 +162,7 @@ __global__ __launch_bounds__(NTHR) void ts_mul_kernel(const float* __restrict__ 
                                                       const float* __restrict__ Mm, const float* __restrict__ Mm2,
                                                       float* __restrict__ Vout, long ldv, float* __restrict__ Yout,
                                                       const unsigned* __restrict__ fb) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     if (*fb != 0u) return;
     __shared__ float Xs[RT * LS];
     __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
@@ -238,6 +241,7 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
                                                            float* A, long lda, float* Yp,
                                                            const unsigned* __restrict__ fb, int tpw,
                                                            float* __restrict__ wpart) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     __shared__ float Cs[RT * LS];
     __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
@@ -306,6 +310,7 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
 __global__ __launch_bounds__(NTHR) void la_update_gram_kernel(float* A, long lda, int m,
                                                               const float* __restrict__ wpart, int nproj, int tpw,
                                                               float* __restrict__ part_next) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     __shared__ float Ws[B64 * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -587,6 +592,7 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
 // First small step: U1 = chol(sum of partials of A^T A) and its inverse, both 64 x 64 (leading dimension 64).
 __global__ __launch_bounds__(NSUM) void chol_inv_kernel(const float* __restrict__ part, int nparts,
                                                         float* __restrict__ U1, float* __restrict__ U1inv) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float B0[B64 * LS];
     __shared__ float B1[B64 * LS];
     const int tid = threadIdx.x;
@@ -682,6 +688,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
                                                          float* __restrict__ Mm, float* __restrict__ Mm2,
                                                          float* __restrict__ tau, float* __restrict__ tslices,
                                                          unsigned* __restrict__ fb, unsigned* __restrict__ status) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Bs[3 * B64 * LS];
     __shared__ float sg[B64];
     __shared__ float redw[4];
