@@ -13,7 +13,7 @@ constexpr int kPanel = 64;           // QR panel width nb (columns aggregated in
 constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
 constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
-constexpr int kLossPartials = 2048;  // upper bound on workgroups of the Whip pass (one partial each)
+constexpr int kLossPartials = 65536; // upper bound on workgroups of the Whip pass (one partial each)
 constexpr int kCholMaxParts = 32;    // upper bound on the Gram partials of the tall-panel path
 
 typedef uint16_t bf16_t;             // raw bfloat16 storage

@@ -4,6 +4,8 @@
 //   * P = strict_lower(B - B^T) of the derivative through Z = R U,
 //   * inverses of the diagonal blocks of U for the blocked triangular solve,
 //   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
+#include <stdlib.h>
+
 #include "dq_internal.h"
 #include "dq_small64.h"
 
@@ -32,6 +34,42 @@ __global__ __launch_bounds__(256) void whip_kernel(const float* __restrict__ Y, 
     const int cpr = (n + 7) >> 3;                 // 8-element chunks per row
     const long chunks = (long)T * cpr;
     float acc = 0.f;
+    if (BF16OUT && yvec > 1 && dvec && (n & 7) == 0 && ldy == n && lddy == n) {
+        // Dense rows: one flat stream, no row/column arithmetic.  Consecutive lanes take consecutive 16-byte pieces
+        // (every load instruction covers 1 KiB without gaps), four pieces per thread in flight, and the hardware's
+        // packed round-to-nearest-even conversion packs 4 results into an 8-byte store.
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const float4* src = reinterpret_cast<const float4*>(Y);
+        uint2* dst = reinterpret_cast<uint2*>(dYv);
+        const long total4 = (long)T * (n >> 2);
+        constexpr int U = 8;
+        const long stride = 256;    // a workgroup takes U consecutive 4 KiB pieces per iteration
+        for (long p0 = (long)blockIdx.x * (256 * U) + threadIdx.x; p0 < total4; p0 += (long)gridDim.x * (256 * U)) {
+            float4 q[U];
+#pragma unroll
+            for (int h = 0; h < U; ++h)
+                q[h] = (p0 + h * stride < total4) ? src[p0 + h * stride] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int h = 0; h < U; ++h) {
+                const bool live = p0 + h * stride < total4;
+                const float yv[4] = {q[h].x, q[h].y, q[h].z, q[h].w};
+                float dv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float ex = __expf(-fabsf(yv[j]));
+                    if (live) acc += ex;
+                    const float sg = (yv[j] > 0.f) ? -scale : ((yv[j] < 0.f) ? scale : 0.f);
+                    dv[j] = sg * ex;
+                }
+                f32x2 a0 = {dv[0], dv[1]}, a1 = {dv[2], dv[3]};
+                const bf16x2 b0 = __builtin_convertvector(a0, bf16x2), b1 = __builtin_convertvector(a1, bf16x2);
+                if (live)
+                    dst[p0 + h * stride] = make_uint2(*reinterpret_cast<const uint32_t*>(&b0),
+                                                      *reinterpret_cast<const uint32_t*>(&b1));
+            }
+        }
+    } else
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < chunks; e += (long)gridDim.x * 256) {
         const int row = (int)(e / cpr);
         const int c0 = (int)(e - (long)row * cpr) << 3;
@@ -230,14 +268,16 @@ __global__ __launch_bounds__(256) void axpy2d_kernel(float* __restrict__ Z, long
 int whip_grid(long rows, int cols) {
     const long chunks = rows * (long)((cols + 7) / 8);
     long g = (chunks + 255) / 256;
-    if (g > kLossPartials) g = kLossPartials;
+    static const int cap = [] { const char* e = getenv("DQ_WHIP_GRID"); int v = e ? atoi(e) : 2048; return v < 1 ? 1 : (v > kLossPartials ? kLossPartials : v); }();
+    if (g > cap) g = cap;
     if (g < 1) g = 1;
     return (int)g;
 }
 
 hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
                        double* partials, int grid, hipStream_t s) {
-    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? 1 : 0;
+    static const int flat = [] { const char* e = getenv("DQ_WHIP_FLAT"); return e ? atoi(e) : 1; }();
+    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? (flat ? 2 : 1) : 0;
     if (dy_is_bf16) {
         const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 7) == 0) ? 1 : 0;
         hipLaunchKernelGGL((whip_kernel<true>), dim3(grid), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy, partials,
