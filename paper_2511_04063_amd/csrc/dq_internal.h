@@ -14,7 +14,7 @@ constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked trian
 constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
 constexpr int kLossPartials = 65536; // upper bound on workgroups of the Whip pass (one partial each)
-constexpr int kCholMaxParts = 32;    // upper bound on the Gram partials of the tall-panel path
+constexpr int kCholMaxParts = 64;    // upper bound on the Gram partials of the tall-panel path
 
 typedef uint16_t bf16_t;             // raw bfloat16 storage
 
