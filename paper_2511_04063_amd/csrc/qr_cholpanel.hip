@@ -855,12 +855,12 @@ struct TallScratch {
     }
 };
 // Row tiles of 128 per workgroup and number of workgroups (= Gram partials) for a panel of m rows.  More partials
-// shorten the tall-skinny kernels but lengthen the one-workgroup sums; 16 balances the two at m = 4096.
+// shorten the tall-skinny kernels but lengthen the one-workgroup sums; 32 was the knee at n = 4096 and 8192 (8: +20 %, 16: +5 %).
 // DQ_TALL_PANEL_PARTS overrides (tuning only).
 void tall_split(int m, int& tpw, int& nparts) {
     static const int parts_cap = [] {
         const char* e = getenv("DQ_TALL_PANEL_PARTS");
-        int v = e ? atoi(e) : 16;
+        int v = e ? atoi(e) : 32;
         return v < 1 ? 1 : (v > kCholMaxParts ? kCholMaxParts : v);
     }();
     const int tiles = (m + RT - 1) / RT;
