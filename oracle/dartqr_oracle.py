@@ -35,6 +35,11 @@ Readings taken where the paper is silent (each is also listed in the design note
   stops at k = n-1; it is read as the textbook Householder QR (right-multiply ALL rows
   of the accumulated factor, columns k..n), and the last diagonal entry's sign is
   handled by the sign normalisation above.
+* Sec. 4.3 and Table 4 say that Z may be driven by "SGD or Adam" and print neither rule
+  nor hyper-parameters.  Adam is taken as the standard rule with bias correction and
+  the usual defaults (beta1 0.9, beta2 0.999, eps 1e-8, step counter from 1); SGD with
+  momentum as the heavy-ball form without dampening.  Both pinned against closed forms
+  and a library optimiser (tests/).
 """
 
 from __future__ import annotations
@@ -50,7 +55,10 @@ __all__ = [
     "grad_wrt_rotation",
     "qr_backward",
     "sgd_update",
+    "sgd_momentum_update",
+    "adam_update",
     "calib_step",
+    "calib_step_adam",
     "calibrate",
     "rotate_loss_grad",
 ]
@@ -182,6 +190,31 @@ def sgd_update(Z, dZ, lr: float) -> np.ndarray:
     return _f64(Z) - float(lr) * _f64(dZ)
 
 
+def sgd_momentum_update(Z, dZ, buf, lr: float, mu: float):
+    """SGD with momentum on the latent (Sec. 4.3: "any optimizer" may drive Z; the paper gives no formula, reading
+    G11: heavy ball without dampening):  buf <- mu * buf + dL/dZ,  Z <- Z - eta * buf.   Returns (Z_new, buf_new)."""
+    buf_new = float(mu) * _f64(buf) + _f64(dZ)
+    return _f64(Z) - float(lr) * buf_new, buf_new
+
+
+def adam_update(Z, dZ, m, v, step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8):
+    """Adam on the latent (Sec. 4.3 and Table 4 name Adam as an optimiser for Z and give no hyper-parameters,
+    reading G10: the standard rule with bias correction and its usual defaults):
+
+        m <- beta1 m + (1 - beta1) g,   v <- beta2 v + (1 - beta2) g^2,
+        Z <- Z - eta * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps),   t = step >= 1.
+
+    Returns (Z_new, m_new, v_new)."""
+    if int(step) < 1:
+        raise ValueError("Adam's step counter starts at 1")
+    g = _f64(dZ)
+    m_new = float(beta1) * _f64(m) + (1.0 - float(beta1)) * g
+    v_new = float(beta2) * _f64(v) + (1.0 - float(beta2)) * g * g
+    m_hat = m_new / (1.0 - float(beta1) ** int(step))
+    v_hat = v_new / (1.0 - float(beta2) ** int(step))
+    return _f64(Z) - float(lr) * m_hat / (np.sqrt(v_hat) + float(eps)), m_new, v_new
+
+
 def rotate_loss_grad(X, R, reduce: str = "mean"):
     """(loss, G, Y, dY) for a given rotation R  (Alg. 1 lines 8-9 and dL/dR)."""
     Y = rotate(X, R)
@@ -203,6 +236,17 @@ def calib_step(X, Z, lr: float, reduce: str = "mean"):
     dZ = qr_backward(R, U, G)
     Z_new = sgd_update(Z, dZ, lr)
     return {"loss": loss, "R": R, "U": U, "G": G, "dZ": dZ, "Z_new": Z_new}
+
+
+def calib_step_adam(X, Z, m, v, step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                    reduce: str = "mean"):
+    """The loop body of Alg. 1 with Adam in place of the SGD update of line 10."""
+    Z = _f64(Z)
+    R, U = qr_orth(Z)
+    loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
+    dZ = qr_backward(R, U, G)
+    Z_new, m_new, v_new = adam_update(Z, dZ, m, v, step, lr, beta1, beta2, eps)
+    return {"loss": loss, "R": R, "U": U, "G": G, "dZ": dZ, "Z_new": Z_new, "m": m_new, "v": v_new}
 
 
 def calibrate(X, Z0, steps: int, lr: float, reduce: str = "mean"):

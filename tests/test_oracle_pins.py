@@ -408,3 +408,92 @@ def test_loss_independent_of_qr_sign_convention():
     dZ_raw = orc.qr_backward(Q, U0, G_raw)
     dZ_nrm = orc.qr_backward(R, U, G_nrm)
     assert np.max(np.abs(dZ_raw - dZ_nrm)) < 1e-12
+
+
+# ----------------------------------------------------------------------------------- optimisers other than plain SGD
+# (Sec. 4.3 / Table 4: the latent may be driven by SGD or Adam; the rules themselves are the standard ones)
+
+
+def test_adam_first_step_closed_form():
+    # from m = v = 0 the bias-corrected moments are g and g^2: the first update is lr * g / (|g| + eps)
+    g = rng(900).standard_normal((6, 6))
+    Z = rng(901).standard_normal((6, 6))
+    Zn, m, v = orc.adam_update(Z, g, np.zeros_like(Z), np.zeros_like(Z), 1, 0.01, 0.9, 0.999, 1e-8)
+    assert np.allclose(Zn, Z - 0.01 * g / (np.abs(g) + 1e-8), rtol=1e-13, atol=0)
+    assert np.allclose(m, 0.1 * g) and np.allclose(v, 0.001 * g * g)
+
+
+def test_adam_constant_gradient_walks_at_unit_speed():
+    # with a constant gradient and eps = 0 every bias-corrected step is exactly lr * sign(g)
+    g = rng(902).standard_normal((5, 5))
+    Z = np.zeros((5, 5)); m = np.zeros_like(Z); v = np.zeros_like(Z)
+    for t in range(1, 8):
+        Z, m, v = orc.adam_update(Z, g, m, v, t, 0.05, 0.9, 0.999, 0.0)
+    assert np.allclose(Z, -7 * 0.05 * np.sign(g), rtol=1e-12, atol=0)
+
+
+def test_adam_is_invariant_to_gradient_scale():
+    g1 = rng(903).standard_normal((4, 4)); g2 = rng(904).standard_normal((4, 4))
+    def run(c):
+        Z = np.ones((4, 4)); m = np.zeros_like(Z); v = np.zeros_like(Z)
+        for t, g in enumerate((g1, g2, g1), start=1):
+            Z, m, v = orc.adam_update(Z, c * g, m, v, t, 0.01, 0.9, 0.999, 0.0)
+        return Z
+    assert np.allclose(run(1.0), run(37.5), rtol=1e-12, atol=1e-15)
+
+
+def test_adam_matches_library_optimiser():
+    torch = pytest.importorskip("torch")
+    gs = [rng(910 + i).standard_normal((5, 3)) for i in range(6)]
+    Z0 = rng(920).standard_normal((5, 3))
+    p = torch.nn.Parameter(torch.tensor(Z0, dtype=torch.float64))
+    opt = torch.optim.Adam([p], lr=0.02, betas=(0.8, 0.95), eps=1e-6)
+    Z = Z0.copy(); m = np.zeros_like(Z); v = np.zeros_like(Z)
+    for t, g in enumerate(gs, start=1):
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        Z, m, v = orc.adam_update(Z, g, m, v, t, 0.02, 0.8, 0.95, 1e-6)
+        assert np.allclose(Z, p.detach().numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_adam_rejects_step_zero():
+    with pytest.raises(ValueError):
+        orc.adam_update(np.zeros((2, 2)), np.zeros((2, 2)), np.zeros((2, 2)), np.zeros((2, 2)), 0, 0.1)
+
+
+def test_momentum_zero_is_plain_sgd_and_geometric_sum():
+    g = rng(930).standard_normal((4, 4)); Z = rng(931).standard_normal((4, 4))
+    Zn, buf = orc.sgd_momentum_update(Z, g, np.zeros_like(Z), 0.1, 0.0)
+    assert np.array_equal(Zn, orc.sgd_update(Z, g, 0.1)) and np.array_equal(buf, g)
+    # constant gradient: buf_k = g (1 - mu^k) / (1 - mu)
+    mu = 0.8; buf = np.zeros_like(Z); Zk = Z.copy(); total = np.zeros_like(Z)
+    for k in range(1, 6):
+        Zk, buf = orc.sgd_momentum_update(Zk, g, buf, 0.1, mu)
+        assert np.allclose(buf, g * (1 - mu ** k) / (1 - mu), rtol=1e-13)
+        total += buf
+    assert np.allclose(Zk, Z - 0.1 * total, rtol=1e-13)
+
+
+def test_momentum_matches_library_optimiser():
+    torch = pytest.importorskip("torch")
+    gs = [rng(940 + i).standard_normal((3, 4)) for i in range(5)]
+    Z0 = rng(950).standard_normal((3, 4))
+    p = torch.nn.Parameter(torch.tensor(Z0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=0.05, momentum=0.9)
+    Z = Z0.copy(); buf = np.zeros_like(Z)
+    for g in gs:
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        Z, buf = orc.sgd_momentum_update(Z, g, buf, 0.05, 0.9)
+        assert np.allclose(Z, p.detach().numpy(), rtol=1e-13, atol=1e-15)
+
+
+def test_calib_step_adam_composes_the_pieces():
+    n, T = 12, 40
+    X = rng(960).standard_normal((T, n)); Z = rng(961).standard_normal((n, n))
+    m = 0.01 * rng(962).standard_normal((n, n)); v = np.abs(rng(963).standard_normal((n, n))) * 1e-4
+    out = orc.calib_step_adam(X, Z, m, v, 3, 0.01)
+    ref = orc.calib_step(X, Z, 0.0)
+    assert np.array_equal(out["dZ"], ref["dZ"]) and out["loss"] == ref["loss"]
+    Zn, mn, vn = orc.adam_update(Z, ref["dZ"], m, v, 3, 0.01)
+    assert np.array_equal(out["Z_new"], Zn) and np.array_equal(out["m"], mn) and np.array_equal(out["v"], vn)
