@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="7b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="update rule of the latent: Alg. 1's SGD (the headline metric) or Adam (Sec. 4.3, Table 4)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -110,8 +112,17 @@ def main():
     ctx.ensure_workspace(cfg.b, cfg.n, cfg.T, xdt)
     red = B.DQ_REDUCE_TOKEN_MEAN
 
-    def step():
-        ctx.dq_calib_step(Xd, xdt, Zd, cfg.lr, red, loss)
+    if args.optimizer == "adam":
+        m_state = torch.zeros_like(Zd)
+        v_state = torch.zeros_like(Zd)
+        counter = [0]
+
+        def step():
+            counter[0] += 1
+            ctx.dq_calib_step_adam(Xd, xdt, Zd, m_state, v_state, counter[0], cfg.lr, red, loss)
+    else:
+        def step():
+            ctx.dq_calib_step(Xd, xdt, Zd, cfg.lr, red, loss)
 
     # warm-up, with every kernel class bracketed once to find where the step's time goes
     for _ in range(max(0, args.warmup - 1)):
@@ -181,7 +192,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, SGD lr={cfg.lr}",
+        "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, "
+                               f"{'Adam' if args.optimizer == 'adam' else 'SGD'} lr={cfg.lr}",
                    "n": cfg.n, "T": cfg.T, "b": cfg.b},
         "model_tflops": F / (ms_per_step * 1e-3) / 1e12,
         "flops_per_step": F,

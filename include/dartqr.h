@@ -136,6 +136,27 @@ dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
 dq_status dq_sgd_update(dq_ctx* ctx, int b, int n, float* Z, long ldz,
                         const float* dZ, long lddz, float lr);
 
+/* Sec. 4.3 / Table 4: the latent may be driven by other optimisers than plain SGD.  The paper prints neither rule;
+ * both are the standard ones.  All matrices n x n fp32, updated in place (Z, m, v, buf); dZ: in.
+ *
+ * Adam with bias correction, step t >= 1 (DQ_ERR_SHAPE otherwise):
+ *   m <- beta1 m + (1 - beta1) dZ,  v <- beta2 v + (1 - beta2) dZ^2,
+ *   Z <- Z - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+ * SGD with momentum (heavy ball, no dampening):  buf <- mu buf + dZ,  Z <- Z - lr * buf. */
+dq_status dq_adam_update(dq_ctx* ctx, int b, int n, float* Z, long ldz, const float* dZ, long lddz,
+                         float* m, long ldm, float* v, long ldv, int step, float lr,
+                         float beta1, float beta2, float eps);
+dq_status dq_sgd_momentum_update(dq_ctx* ctx, int b, int n, float* Z, long ldz, const float* dZ, long lddz,
+                                 float* buf, long ldbuf, float lr, float mu);
+
+/* One QR-Orth step (Alg. 1 lines 7-10) with Adam in place of the SGD update of line 10; arguments as for
+ * dq_calib_step and dq_adam_update (m, v: b stacked n x n matrices of optimiser state, zero before step 1). */
+dq_status dq_calib_step_adam(dq_ctx* ctx, int b, int T, int n,
+                             const void* X, dq_dtype x_dtype, long ldx,
+                             float* Z, long ldz, float* m, long ldm, float* v, long ldv, int step,
+                             float lr, float beta1, float beta2, float eps,
+                             dq_reduce reduce, float* loss_dev, float* R_or_null, long ldr);
+
 /* The matrix-core GEMMs the path is built from, exported for kernel-level parity tests:
  *   C (M x N, fp32) = alpha * op(A) op(B) + beta * C.
  * f32: A, B fp32; ta != 0 means A is stored K x M, tb != 0 means B is stored N x K.

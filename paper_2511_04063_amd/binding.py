@@ -38,6 +38,10 @@ SIGNATURES = {
     "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
+    "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
+    "dq_sgd_momentum_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _f, _f]),
+    "dq_calib_step_adam": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f, _i, _vp,
+                                _vp, _l]),
     "dq_gemm_f32": (_i, [_vp, _i, _i, _i, _f, _vp, _l, _i, _vp, _l, _i, _f, _vp, _l]),
     "dq_gemm_bf16": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _l, _i, _vp, _l]),
     "dq_profile_enable": (_i, [_vp, _c.c_uint]),
@@ -180,6 +184,26 @@ class Context:
         b, n = (R.shape[0], R.shape[-1]) if R.dim() == 3 else (1, R.shape[-1])
         self._check(self.lib.dq_qr_backward(self.h, b, n, _ptr(R), _ld(R), _ptr(U), _ld(U), _ptr(G), _ld(G),
                                             _ptr(dZ), _ld(dZ)), "dq_qr_backward")
+
+    def dq_adam_update(self, Z, dZ, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8):
+        b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
+        self._check(self.lib.dq_adam_update(self.h, b, n, _ptr(Z), _ld(Z), _ptr(dZ), _ld(dZ), _ptr(m), _ld(m), _ptr(v),
+                                            _ld(v), int(step), float(lr), float(beta1), float(beta2), float(eps)),
+                    "dq_adam_update")
+
+    def dq_sgd_momentum_update(self, Z, dZ, buf, lr, mu):
+        b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
+        self._check(self.lib.dq_sgd_momentum_update(self.h, b, n, _ptr(Z), _ld(Z), _ptr(dZ), _ld(dZ), _ptr(buf),
+                                                    _ld(buf), float(lr), float(mu)), "dq_sgd_momentum_update")
+
+    def dq_calib_step_adam(self, X, x_dtype, Z, m, v, step, lr, reduce, loss, beta1=0.9, beta2=0.999, eps=1e-8,
+                           R=None):
+        b = X.shape[0] if X.dim() == 3 else 1
+        T, n = X.shape[-2], X.shape[-1]
+        self._check(self.lib.dq_calib_step_adam(self.h, b, T, n, _ptr(X), x_dtype, _ld(X), _ptr(Z), _ld(Z), _ptr(m),
+                                                _ld(m), _ptr(v), _ld(v), int(step), float(lr), float(beta1),
+                                                float(beta2), float(eps), reduce, _ptr(loss), _ptr(R), _ld(R)),
+                    "dq_calib_step_adam")
 
     def dq_sgd_update(self, Z, dZ, lr):
         b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])

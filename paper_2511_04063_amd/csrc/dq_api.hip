@@ -1,5 +1,6 @@
 // C ABI of libdartqr.so: argument checking, workspace carving and the sequencing of the kernels of one
 // QR-Orth step (Alg. 1 lines 7-10) on the caller's HIP stream.  No device memory is allocated here.
+#include <math.h>
 #include <stdlib.h>
 
 #include <new>
@@ -747,6 +748,75 @@ dq_status dq_sgd_update(dq_ctx* c, int b, int n, float* Z, long ldz, const float
     for (int i = 0; i < b; ++i) {
         LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
         DQ_HIP(launch_axpy2d(Z + (long)i * n * ldz, ldz, dZ + (long)i * n * lddz, lddz, n, -lr, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_adam_update(dq_ctx* c, int b, int n, float* Z, long ldz, const float* dZ, long lddz, float* m, long ldm,
+                         float* v, long ldv, int step, float lr, float beta1, float beta2, float eps) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || n < 1 || step < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_f32(Z, ldz, n));
+    DQ_TRY(check_f32(dZ, lddz, n));
+    DQ_TRY(check_f32(m, ldm, n));
+    DQ_TRY(check_f32(v, ldv, n));
+    const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+    const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    for (int i = 0; i < b; ++i) {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * n * (double)n, 28.0 * n * (double)n);
+        DQ_HIP(launch_adam2d(Z + (long)i * n * ldz, ldz, dZ + (long)i * n * lddz, lddz, m + (long)i * n * ldm, ldm,
+                             v + (long)i * n * ldv, ldv, n, lr, beta1, beta2, eps, c1, c2, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_sgd_momentum_update(dq_ctx* c, int b, int n, float* Z, long ldz, const float* dZ, long lddz, float* buf,
+                                 long ldbuf, float lr, float mu) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || n < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_f32(Z, ldz, n));
+    DQ_TRY(check_f32(dZ, lddz, n));
+    DQ_TRY(check_f32(buf, ldbuf, n));
+    for (int i = 0; i < b; ++i) {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 4.0 * n * (double)n, 20.0 * n * (double)n);
+        DQ_HIP(launch_momentum2d(Z + (long)i * n * ldz, ldz, dZ + (long)i * n * lddz, lddz, buf + (long)i * n * ldbuf,
+                                 ldbuf, n, lr, mu, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype xdt, long ldx, float* Z, long ldz,
+                             float* m, long ldm, float* v, long ldv, int step, float lr, float beta1, float beta2,
+                             float eps, dq_reduce red, float* loss_dev, float* R, long ldr) {
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1 || step < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_x(X, xdt, ldx, n));
+    DQ_TRY(check_f32(Z, ldz, n));
+    DQ_TRY(check_f32(m, ldm, n));
+    DQ_TRY(check_f32(v, ldv, n));
+    if (R != nullptr) DQ_TRY(check_f32(R, ldr, n));
+    const Layout L = make_layout(n, T);
+    DQ_TRY(check_ws(c, L));
+    const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
+    const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+    const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    for (int i = 0; i < b; ++i) {
+        float* Zi = Z + (long)i * n * ldz;
+        float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
+        const long ldri = R ? ldr : L.ld;
+        float* Ui = at<float>(c, L.U);
+        float* Gi = at<float>(c, L.G);
+        float* dZi = at<float>(c, L.B);   // B = R^T G is consumed before the last product writes dZ there
+        const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
+        DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
+                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
+        DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, dZi, L.ld, nullptr, 0, 0.f));
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * n * (double)n, 28.0 * n * (double)n);
+        DQ_HIP(launch_adam2d(Zi, ldz, dZi, L.ld, m + (long)i * n * ldm, ldm, v + (long)i * n * ldv, ldv, n, lr, beta1,
+                             beta2, eps, c1, c2, c->stream));
     }
     return DQ_OK;
 }

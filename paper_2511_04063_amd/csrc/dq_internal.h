@@ -117,6 +117,12 @@ hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp
 // Inverse of every kTrsmBlock x kTrsmBlock diagonal block of the upper-triangular U: Uinv[blk] row-major, ld kTrsmBlock.
 hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s);
 hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s);
+// Adam / heavy-ball updates of an n x n matrix in place (see include/dartqr.h); c1 = 1 / (1 - beta1^t),
+// c2 = 1 / (1 - beta2^t) are formed on the host in double precision.
+hipError_t launch_adam2d(float* Z, long ldz, const float* D, long ldd, float* m, long ldm, float* v, long ldv, int n,
+                         float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s);
+hipError_t launch_momentum2d(float* Z, long ldz, const float* D, long ldd, float* buf, long ldb, int n, float lr,
+                             float mu, hipStream_t s);
 
 // ---- rotate / Whip pieces ---------------------------------------------------------
 // Split R into two bf16 planes and transpose:  RbT[j][k] = hi(R[k][j]),  RbT[j][koff + k] = lo(R[k][j]) with

@@ -335,6 +335,45 @@ def test_sgd_update(ctx):
     assert np.abs(Zd.cpu().numpy() - orc.sgd_update(Z, D, 0.25)).max() < 1e-6
 
 
+def test_adam_update_against_oracle(ctx):
+    """Adam on the latent (Sec. 4.3 / Table 4), three consecutive steps with carried state, padded leading dimensions."""
+    n = 77
+    g = rng(5200)
+    Z = g.standard_normal((n, n)).astype(np.float32)
+    _, Zd = padded(n, n, 80); Zd.copy_(dev(Z))
+    _, md = padded(n, n, 88, fill=0.0)
+    _, vd = padded(n, n, 92, fill=0.0)
+    Zo, mo, vo = Z.astype(np.float64), np.zeros((n, n)), np.zeros((n, n))
+    # the C ABI takes the hyper-parameters as fp32: the oracle gets the same (fp32-representable) values
+    lr, b1, b2, eps = (float(np.float32(x)) for x in (0.01, 0.9, 0.999, 1e-8))
+    for t in range(1, 4):
+        D = (g.standard_normal((n, n)) * 10.0 ** g.integers(-4, 2, (n, n))).astype(np.float32)
+        _, Dd = padded(n, n, 84); Dd.copy_(dev(D))
+        ctx.dq_adam_update(Zd, Dd, md, vd, t, lr, b1, b2, eps)
+        Zo, mo, vo = orc.adam_update(Zo, D, mo, vo, t, lr, b1, b2, eps)
+        # every update is at most lr in size: 1e-6 * lr of absolute error plus fp32 storage of Z itself
+        assert np.abs(Zd.cpu().numpy() - Zo).max() < 1e-6
+        assert rel(md.cpu().numpy(), mo) < 1e-6 and rel(vd.cpu().numpy(), vo) < 1e-6
+    with pytest.raises(B.DartQRError):
+        ctx.dq_adam_update(Zd, Dd, md, vd, 0, 0.01)
+
+
+def test_sgd_momentum_update_against_oracle(ctx):
+    n = 65
+    g = rng(5300)
+    Z = g.standard_normal((n, n)).astype(np.float32)
+    _, Zd = padded(n, n, 68); Zd.copy_(dev(Z))
+    _, bd = padded(n, n, 72, fill=0.0)
+    Zo, bo = Z.astype(np.float64), np.zeros((n, n))
+    for _ in range(3):
+        D = g.standard_normal((n, n)).astype(np.float32)
+        _, Dd = padded(n, n, 76); Dd.copy_(dev(D))
+        ctx.dq_sgd_momentum_update(Zd, Dd, bd, 0.05, 0.9)
+        Zo, bo = orc.sgd_momentum_update(Zo, D, bo, 0.05, 0.9)
+        assert np.abs(Zd.cpu().numpy() - Zo).max() < 2e-6
+        assert rel(bd.cpu().numpy(), bo) < 1e-6
+
+
 # ----------------------------------------------------------------------------------- whole step
 def gpu_stages(ctx, Xd, xdt, Zd):
     """loss, R, U, G, dZ, Y, dY of the latent in Zd through the three stage entry points (S1+S2, S3-S5, S6)."""
@@ -405,6 +444,33 @@ def test_calib_step_tiny_trajectory(ctx):
     # ten steps of drift (kinks of |y|, see above) on a displacement of about 1e-2 of ||Z||
     assert rel(Zd.cpu().numpy(), Zo) < 1e-3
     assert abs(np.linalg.norm(Zd.cpu().numpy().astype(np.float64)) - gold["Z_final_fro"]) < 1e-4 * gold["Z_final_fro"]
+    assert ctx.dq_device_flags() == 0
+
+
+def test_calib_step_adam_tiny(ctx):
+    """Alg. 1 with Adam in place of line 10's SGD update: the loss against the oracle on the same input, the update
+    against the oracle's Adam rule fed with the GPU's own dZ (Adam divides by |g|-like quantities, so entries whose
+    gradient is at rounding level would otherwise decide the comparison), state carried over four steps."""
+    inp = synth.make_inputs("tiny")
+    cfg = inp["cfg"]
+    X, Z0 = inp["X"][0], inp["Z0"][0]
+    n = cfg.n
+    ctx.ensure_workspace(1, n, cfg.T, B.DQ_F32)
+    Xd = dev(X)
+    Zd = dev(Z0.astype(np.float32))
+    md = torch.zeros((n, n), device="cuda"); vd = torch.zeros((n, n), device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    mo = np.zeros((n, n)); vo = np.zeros((n, n))
+    for t in range(1, 5):
+        Zin = Zd.cpu().numpy().astype(np.float64)
+        loss_st, _, _, _, dZ_st, _, _ = gpu_stages(ctx, Xd, B.DQ_F32, Zd)
+        ctx.dq_calib_step_adam(Xd, B.DQ_F32, Zd, md, vd, t, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, loss)
+        ref = orc.calib_step(X, Zin, 0.0)
+        assert abs(loss.item() - ref["loss"]) <= 1e-4 * ref["loss"]
+        assert loss.item() == pytest.approx(loss_st, rel=1e-6)
+        Zo, mo, vo = orc.adam_update(Zin, dZ_st, mo, vo, t, *(float(np.float32(x)) for x in (1e-3, 0.9, 0.999, 1e-8)))
+        assert np.abs(Zd.cpu().numpy() - Zo).max() < 2e-6
+        assert rel(md.cpu().numpy(), mo) < 1e-5 and rel(vd.cpu().numpy(), vo) < 1e-5
     assert ctx.dq_device_flags() == 0
 
 
