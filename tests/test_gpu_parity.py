@@ -493,6 +493,105 @@ def test_calib_step_bf16_small(ctx):
     assert np.abs(dZ_gpu[:, -1]).max() < 1e-3 * np.abs(dZ_gpu).max()
 
 
+@pytest.mark.parametrize("name", ["7b", "70b"])
+def test_full_size_step_sampled(name):
+    """The workloads bench.py times (n = 4096 / 8192 with their token counts, bf16 X), through the same entry point
+    and launch configuration, checked where the oracle can afford it: sampled entries of every stage against fp64
+    dot products of that stage's own inputs, the loss against the oracle's Whip on the GPU's Y, and properties of
+    the factorisation and of the gradient that hold at any size."""
+    inp = synth.make_inputs(name)
+    cfg = inp["cfg"]
+    n, T = cfg.n, cfg.T
+    X = inp["X"][0]                      # float32 holding exact bf16 values
+    Z0 = inp["Z0"][0]
+    ctx = B.Context()
+    ctx.ensure_workspace(1, n, T, B.DQ_BF16)
+    g = rng(7000 + n)
+    try:
+        Xd = dev(X, torch.bfloat16)
+        Zd = dev(Z0.copy())
+        Rd, Ud, Gd, dZd = (torch.empty((n, n), device="cuda") for _ in range(4))
+        Yd = torch.empty((T, n), device="cuda")
+        dYd = torch.empty((T, n), device="cuda", dtype=torch.bfloat16)
+        loss = torch.zeros(1, device="cuda")
+        ctx.dq_qr_orth(Zd, Rd, Ud)
+        ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd, Yd, dYd)
+        ctx.dq_qr_backward(Rd, Ud, Gd, dZd)
+        loss2 = torch.zeros(1, device="cuda")
+        Zstep = Zd.clone()
+        ctx.dq_calib_step(Xd, B.DQ_BF16, Zstep, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss2)
+        assert ctx.dq_device_flags() == 0
+        R = Rd.cpu().numpy().astype(np.float64)
+        U = Ud.cpu().numpy().astype(np.float64)
+        G = Gd.cpu().numpy().astype(np.float64)
+        dZ = dZd.cpu().numpy().astype(np.float64)
+        Z64 = Z0.astype(np.float64)
+
+        # S1 + S2: orthogonality and reconstruction on sampled entries, structure of U
+        ii = g.integers(0, n, 400); jj = g.integers(0, n, 400)
+        gram = np.einsum("ki,ki->i", R[:, ii], R[:, jj]) - (ii == jj)
+        assert np.abs(gram).max() <= 1e-5
+        diag = np.einsum("ki,ki->i", R[:, ii], R[:, ii]) - 1.0
+        assert np.abs(diag).max() <= 1e-5
+        rec = np.einsum("ik,ki->i", R[ii, :], U[:, jj])
+        assert np.abs(rec - Z64[ii, jj]).max() <= 2e-6 * np.sqrt(n)     # |Z|_2 ~ 2 sqrt(n) for a Gaussian latent
+        assert np.all(np.diag(U) > 0.0)
+        assert np.count_nonzero(np.tril(U, -1)) == 0
+
+        # S3: sampled entries of Y against fp64 dot products of the bf16 X rows with the GPU's R
+        tt = g.integers(0, T, 300); cc = g.integers(0, n, 300)
+        X64 = X[tt].astype(np.float64)
+        y_ref = np.einsum("ik,ki->i", X64, R[:, cc])
+        y_gpu = Yd[torch.from_numpy(tt).cuda(), torch.from_numpy(cc).cuda()].cpu().numpy().astype(np.float64)
+        scale_y = np.linalg.norm(X64, axis=1)            # |x_t| * |r_c| with |r_c| = 1
+        assert np.abs(y_gpu - y_ref).max() <= 2e-2 * scale_y.max() / np.sqrt(n) * 3
+        assert np.abs((y_gpu - y_ref) / scale_y).max() <= 1e-5       # far inside the bf16-input bar
+
+        # S4: loss from the GPU's own Y; dY on a slab of rows (both sides decide the bf16 value from the fp32 Y)
+        rows = np.sort(g.choice(T, 64, replace=False))
+        Y_rows = Yd[torch.from_numpy(rows).cuda()].cpu().numpy()
+        acc = 0.0
+        for r0 in range(0, T, 1024):
+            acc += orc.whip_loss(Yd[r0:r0 + 1024].cpu().numpy(), "sum")
+        assert abs(loss.item() - acc / T) <= 1e-5 * acc / T
+        assert loss2.item() == pytest.approx(loss.item(), rel=1e-6)
+        dy_ref = orc.whip_grad(Y_rows.astype(np.float64), "sum") / T
+        dy_gpu = dYd[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        assert rel(dy_gpu, dy_ref) < 4e-3
+        assert np.abs(dy_gpu - dy_ref).max() <= np.abs(dy_ref).max() * 2.0 ** -7
+
+        # S5: sampled entries of G against fp64 dot products over all tokens of the bf16 X and the GPU's bf16 dY
+        ci = g.integers(0, n, 24); cj = g.integers(0, n, 24)
+        Xc = X[:, ci].astype(np.float64)
+        dYc = dYd[:, torch.from_numpy(cj).cuda()].float().cpu().numpy().astype(np.float64)
+        g_ref = np.einsum("ti,ti->i", Xc, dYc)
+        g_bound = np.linalg.norm(Xc, axis=0) * np.linalg.norm(dYc, axis=0)
+        assert np.abs(G[ci, cj] - g_ref).max() <= 1e-5 * g_bound.max()
+
+        # S6: what the true gradient satisfies at any size: triu(Z^T dZ) = 0 (sampled), last column zero,
+        # <Z, dZ> = 0 ...
+        pi = g.integers(0, n, 400); pj = g.integers(0, n, 400)
+        lo, hi = np.minimum(pi, pj), np.maximum(pi, pj)
+        ztdz = np.einsum("ki,ki->i", Z64[:, lo], dZ[:, hi])
+        bound = np.linalg.norm(Z64, axis=0).max() * np.linalg.norm(dZ, axis=0).max()
+        assert np.abs(ztdz).max() <= 2e-3 * bound
+        assert np.abs(dZ[:, -1]).max() <= 1e-3 * np.abs(dZ).max()
+        assert abs(np.sum(Z64 * dZ)) <= 2e-3 * np.linalg.norm(Z64) * np.linalg.norm(dZ)
+        # ... and the strictly lower matrix in dZ = R P U^-T is the one the derivation prescribes,
+        # P = strict_lower(B - B^T) with B = R^T G: rows of P recovered from the GPU's dZ as R[:, i]^T dZ U^T
+        # (n^2 work per row) against the same rows formed from the GPU's R and G in fp64
+        for i in g.choice(np.arange(n // 2, n), 4, replace=False):
+            p_rec = (R[:, i] @ dZ) @ U.T
+            p_ref = np.zeros(n)
+            p_ref[:i] = (R[:, i] @ G)[:i] - (R.T @ G[:, i])[:i]
+            assert np.linalg.norm(p_rec - p_ref) <= 1e-4 * max(np.linalg.norm(p_ref), np.linalg.norm(R[:, i] @ G))
+        # S7: the fused update is Z - lr dZ
+        assert rel(Zstep.cpu().numpy(), Z64 - cfg.lr * dZ) < 1e-6
+    finally:
+        torch.cuda.synchronize()
+        ctx.close()
+
+
 def test_batched_heads_like(ctx):
     cfg = synth.scaled_config("heads", b=3, T=512)
     inp = synth.make_inputs(cfg, seed=2)
