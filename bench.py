@@ -50,7 +50,7 @@ def cpu_baseline(cfg_name: str, n: int, T: int):
     from oracle import dartqr_oracle as orc
     from paper_2511_04063_amd import synth
 
-    ns = min(n, 1536)
+    ns = min(n, 2048)
     Ts = max(1, int(round(T * ns / n)))
     base = cfg_name if cfg_name in ("7b", "13b", "70b") else "7b"
     inp = synth.make_inputs(synth.scaled_config(base, n=ns, T=Ts, b=1), seed=11)
