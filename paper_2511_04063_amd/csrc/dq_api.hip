@@ -54,6 +54,8 @@ struct dq_ctx {
     int nb = kPanel;                 // QR panel width (<= kPanel)
     int chol_min_m = 128;            // panels at least this tall take the many-CU route (0: never)
     bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
+    int accum_panels = 2;            // panels merged per update of the accumulated R (1: panel by panel; 2 measured
+                                     // best at n = 4096, 2 and 4 equal at n = 8192)
     char* ws = nullptr;
     size_t ws_bytes = 0;
     Profiler prof;
@@ -64,7 +66,7 @@ namespace {
 // ---------------------------------------------------------------- workspace layout
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
-    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0,
+    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
            vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
@@ -97,7 +99,9 @@ Layout make_layout(int n, int T) {
     L.wpartB = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
     L.w2B = bump(cur, (size_t)kPanel * L.ld * 4);
     L.qpart = bump(cur, (size_t)kMaxSplit * n * kPanel * 4);
-    L.qw = bump(cur, (size_t)n * kPanel * 4);
+    L.qw = bump(cur, (size_t)n * kAccumPanels * kPanel * 4);
+    L.yblk = bump(cur, (size_t)n * kAccumPanels * kPanel * 4);
+    L.spart = bump(cur, (size_t)(kMaxSplit + 1) * kAccumPanels * kPanel * kPanel * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
     L.cq = bump(cur, cholpanel_scratch_floats() * 4);
     L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
@@ -284,6 +288,102 @@ dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0,
     return DQ_OK;
 }
 
+// The same for a run of np consecutive panels (first one q0) at once: their block reflectors are merged into one of
+// width w = sum of the panel widths,  H_q0 ... H_(q0+np-1) = I - V Yb^T... in the form used here
+//   Q[:, k0:] <- Q[:, k0:] - (Q[:, k0:] Yb) V^T,
+// with V the unit-lower-trapezoid block of the w columns and Yb = V T_merged built column group by column group:
+//   Yb_j = [0; Yp_j] - Yb_{<j} (V_{<j}^T [0; Yp_j]).
+// A K = 256 update reads and writes the accumulated factor once per four panels instead of once per panel (the
+// K = 64 update is bound by that traffic), for a few small products more.
+dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, int nb, int q0, int np, float* A, long ld,
+                             float* yall, float* Q, long ldq) {
+    const int k0 = q0 * nb;
+    const int mb = n - k0;
+    float* Ablk = A + (long)k0 * ld + k0;
+    float* Yb = at<float>(c, L.yblk);
+    const long ldy = (long)kAccumPanels * kPanel;
+    float* spart = at<float>(c, L.spart);
+    float* sred = spart + (size_t)kMaxSplit * kAccumPanels * kPanel * kPanel;
+    int w = 0;
+    for (int j = 0; j < np; ++j) {
+        const int q = q0 + j;
+        const int off = q * nb - k0;
+        const int mq = n - q * nb;
+        const int jq = mq < nb ? mq : nb;
+        const float* Ypq = yall + (long)q * n * kPanel;
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * mb * (double)jq);
+            if (off > 0) DQ_HIP(launch_copy2d(nullptr, 0, Yb + off, ldy, off, jq, s));
+            DQ_HIP(launch_copy2d(Ypq, kPanel, Yb + (long)off * ldy + off, ldy, mq, jq, s));
+        }
+        if (j > 0) {
+            // S = V_{<j}^T [0; Yp_j]: only rows >= off of V_{<j} meet non-zeros, all of them below its diagonal
+            int splits, kchunk;
+            choose_split(((off + 63) / 64) * ((jq + 63) / 64), mq, 32, kMaxSplit, splits, kchunk);
+            const long stride = (long)kAccumPanels * kPanel * kPanel;
+            {
+                GemmF32 g;
+                g.cfg = 3;
+                g.A = Ablk + (long)off * ld; g.lda = ld; g.ta = 1;
+                g.B = Ypq; g.ldb = kPanel; g.tb = 0;
+                g.C = splits > 1 ? spart : sred; g.ldc = kPanel;
+                g.M = off; g.N = jq; g.K = mq;
+                g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * off * (double)jq * mq, 0.0);
+                DQ_HIP(launch_gemm_f32(g, s));
+            }
+            if (splits > 1) {
+                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+                DQ_HIP(launch_splitk_reduce(spart, splits, stride, kPanel, off, jq, 1.f, 0.f, sred, kPanel, s));
+            }
+            {
+                GemmF32 g;   // Yb_j -= Yb_{<j} S
+                g.A = Yb; g.lda = ldy; g.ta = 0;
+                g.B = sred; g.ldb = kPanel; g.tb = 0;
+                g.C = Yb + off; g.ldc = ldy;
+                g.M = mb; g.N = jq; g.K = off;
+                g.alpha = -1.f; g.beta = 1.f;
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mb * (double)jq * off, 0.0);
+                DQ_HIP(launch_gemm_f32(g, s));
+            }
+        }
+        w = off + jq;
+    }
+    float* qpart = at<float>(c, L.qpart);
+    float* qw = at<float>(c, L.qw);
+    float* Qc = Q + k0;
+    const long stride = (long)n * ldy;
+    int splits, kchunk;
+    int max_splits = (int)(((size_t)kMaxSplit * n * kPanel) / ((size_t)n * ldy));   // what the partial buffer holds
+    if (max_splits < 1) max_splits = 1;
+    choose_split(((n + 127) / 128) * ((w + 127) / 128), mb, 16, max_splits, splits, kchunk);
+    {
+        GemmF32 g;   // Wq = Qc Yb
+        g.A = Qc; g.lda = ldq; g.ta = 0;
+        g.B = Yb; g.ldb = ldy; g.tb = 0;
+        g.C = splits > 1 ? qpart : qw; g.ldc = ldy;
+        g.M = n; g.N = w; g.K = mb;
+        g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)w * mb, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    if (splits > 1) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_splitk_reduce(qpart, splits, stride, ldy, n, w, 1.f, 0.f, qw, ldy, s));
+    }
+    {
+        GemmF32 g;   // Qc -= Wq V^T   (V stored mb x w = N x K)
+        g.A = qw; g.lda = ldy; g.ta = 0;
+        g.B = Ablk; g.ldb = ld; g.tb = 1; g.b_unit_lower_cols = w;
+        g.C = Qc; g.ldc = ldq;
+        g.M = n; g.N = mb; g.K = w;
+        g.alpha = -1.f; g.beta = 1.f;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n * (double)mb * w, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    return DQ_OK;
+}
+
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
                       long ldu) {
     hipStream_t sA = c->stream, sB = c->single_stream ? c->stream : c->stream2,
@@ -376,7 +476,6 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         }
         const int rest = m - jb - nla;
         DQ_HIP(hipEventRecord(c->sync_ev[2 * p], sA));
-        DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
         if (rest > 0) {   // C -= V (Yp^T C) for the rest of the trailing matrix, behind the next panel
             DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[2 * p], 0));
             const float* Wb = nullptr;
@@ -387,8 +486,15 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         }
         // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
         // left to the right, Q[:, k0:] <- Q[:, k0:] (I - V T V^T)  (as Alg. 2 does column by column), on the third
-        // stream.  For p == 0 the accumulated factor is still the identity.
-        DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Yp, R, ldr));
+        // stream, several panels at a time.
+        if ((p + 1) % c->accum_panels == 0 || p == npanels - 1) {
+            const int q0 = (p / c->accum_panels) * c->accum_panels;
+            DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
+            if (p - q0 + 1 == 1)
+                DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Yp, R, ldr));
+            else
+                DQ_TRY(accumulate_q_block(c, sC, L, n, nb, q0, p - q0 + 1, A, ld, yall, R, ldr));
+        }
     }
     if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
     DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));
@@ -572,6 +678,7 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     c->stream = static_cast<hipStream_t>(hip_stream);
     if (const char* e = getenv("DQ_PANEL_NB")) { const int v = atoi(e); if (v >= kPanelMin && v <= kPanel && v % 8 == 0) c->nb = v; }
     if (const char* e = getenv("DQ_SINGLE_STREAM")) c->single_stream = atoi(e) != 0;
+    if (const char* e = getenv("DQ_ACCUM_PANELS")) { const int v = atoi(e); if (v >= 1 && v <= kAccumPanels) c->accum_panels = v; }
     if (const char* e = getenv("DQ_TALL_PANEL_MIN_M")) { const int v = atoi(e); if (v >= 0) c->chol_min_m = v; }
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
     // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream

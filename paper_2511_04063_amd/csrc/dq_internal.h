@@ -14,6 +14,7 @@ constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked trian
 constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
 constexpr int kLossPartials = 65536; // upper bound on workgroups of the Whip pass (one partial each)
+constexpr int kAccumPanels = 4;      // panels whose reflectors are merged before they are applied to the accumulated R
 constexpr int kCholMaxParts = 64;    // upper bound on the Gram partials of the tall-panel path
 
 typedef uint16_t bf16_t;             // raw bfloat16 storage
@@ -104,6 +105,7 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
 hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp, int jb, int nla,
                           const float* tslices, int slice_width, float* Tout, float* W2out, hipStream_t s);
 
+// dst (rows x cols, ldd) = src (lds);  src == null writes zeros
 hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s);
 hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s);
 hipError_t launch_fill_u32(unsigned* p, long count, unsigned v, hipStream_t s);

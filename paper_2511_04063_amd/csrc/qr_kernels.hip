@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const float* __restrict__ s
     const long total = (long)rows * cols;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
         const int r = (int)(e / cols), c = (int)(e % cols);
-        dst[(long)r * ldd + c] = src[(long)r * lds + c];
+        dst[(long)r * ldd + c] = (src != nullptr) ? src[(long)r * lds + c] : 0.f;
     }
 }
 
