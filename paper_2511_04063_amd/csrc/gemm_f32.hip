@@ -115,8 +115,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     const int gid = pid / group;
     const int first_m = gid * 8;
     const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
-    const int pid_m = first_m + (pid % group) % gsz;
-    const int pid_n = (pid % group) / gsz;
+    int pid_m = first_m + (pid % group) % gsz;
+    int pid_n = (pid % group) / gsz;
+    if (g.b_strict_lower) {
+        // The K loop of a tile starts at its column offset: tile columns are dealt out whole, longest first, so that
+        // the long tiles do not start late and finish alone.
+        pid_n = bid / tiles_m;
+        pid_m = bid % tiles_m;
+    }
     const int m0 = pid_m * BM, n0 = pid_n * BN;
 
     const int z = blockIdx.y;
