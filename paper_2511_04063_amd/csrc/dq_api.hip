@@ -384,8 +384,12 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
     return DQ_OK;
 }
 
+// normalise = false leaves the factors as the factorisation produced them (column signs of R and row signs of the
+// triangular factor, which then sits in the upper triangle of the workspace matrix L.A, not fixed): loss and dL/dZ do
+// not depend on the sign choice (Y's columns, dY's columns and G's columns flip together, and R P U^-T is invariant),
+// so a step that does not have to report R skips the pass.
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
-                      long ldu) {
+                      long ldu, bool normalise = true) {
     hipStream_t sA = c->stream, sB = c->single_stream ? c->stream : c->stream2,
                 sC = c->single_stream ? c->stream : c->stream3;
     float* A = at<float>(c, L.A);
@@ -499,7 +503,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
     DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));
     DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev.back(), 0));
-    {
+    if (normalise) {
         LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 12.0 * n * (double)n);
         DQ_HIP(launch_sign_normalise(A, ld, n, R, ldr, U, ldu, flags, sA));
     }
@@ -792,10 +796,13 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
-        float* Ui = at<float>(c, L.U);
+        // R is reported only on request: without it the sign normalisation is skipped and the triangular factor is
+        // read in place from the factored matrix
+        const bool report = R != nullptr;
+        float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
         float* Gi = at<float>(c, L.G);
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
-        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
                                     at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, nullptr, 0, Zi, ldz, lr));

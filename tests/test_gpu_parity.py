@@ -610,8 +610,15 @@ def test_batched_heads_like(ctx):
     # a batch equals its problems run one by one
     Z1 = dev(Z0[1].copy())
     l1 = torch.zeros(1, device="cuda")
-    ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z1, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l1)
-    assert torch.equal(Z1, Zd[1]) and l1.item() == loss[1].item()
+    R1 = torch.empty((128, 128), device="cuda")
+    ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z1, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l1, R1)
+    assert torch.equal(Z1, Zd[1]) and l1.item() == loss[1].item() and torch.equal(R1, Rd[1])
+    # without the request for R the step skips the sign normalisation: same loss and update up to rounding
+    Z2 = dev(Z0[1].copy())
+    l2 = torch.zeros(1, device="cuda")
+    ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z2, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l2)
+    assert l2.item() == pytest.approx(l1.item(), rel=1e-6)
+    assert rel(Z2.cpu().numpy(), Z1.cpu().numpy()) < 1e-6
 
 
 # ----------------------------------------------------------------------------------- error paths
