@@ -920,11 +920,12 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
-        float* Ui = at<float>(c, L.U);
+        const bool report = R != nullptr;   // as in dq_calib_step
+        float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
         float* Gi = at<float>(c, L.G);
         float* dZi = at<float>(c, L.B);   // B = R^T G is consumed before the last product writes dZ there
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
-        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
                                     at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, dZi, L.ld, nullptr, 0, 0.f));
