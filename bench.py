@@ -26,11 +26,11 @@ if ROOT not in sys.path:
 # commands are in profiles/calib_step_7b_hbm_traffic.txt.  Counters cannot be read from inside this script, so the
 # figures are carried here; other workloads report null.
 MEASURED_TRAFFIC_7B = {
-    "gemm_f32": (9782.6 + 5416.0) * 2 ** 20 / 319.0,
-    "gemm_bf16": (1964.4 + 192.0) * 2 ** 20 / 2.0,
+    "gemm_f32": (8251.8 + 4144.7) * 2 ** 20 / 319.0,
+    "gemm_bf16": (1023.5 + 659.6 + 128.0 + 64.0) * 2 ** 20 / 2.0,
     "whip": (128.0 + 64.1) * 2 ** 20,
     # panel route: all of its kernels together, per bracketed group of launches (two groups per tall panel)
-    "qr_panel": (316.8 + 167.1) * 2 ** 20 / 121.0,
+    "qr_panel": (371.8 + 185.0) * 2 ** 20 / 127.0,
 }
 
 # MI355X published peaks

@@ -129,6 +129,8 @@ hipError_t launch_momentum2d(float* Z, long ldz, const float* D, long ldd, float
 // ---- rotate / Whip pieces ---------------------------------------------------------
 // Split R into two bf16 planes and transpose:  RbT[j][k] = hi(R[k][j]),  RbT[j][koff + k] = lo(R[k][j]) with
 // hi = bf16(r), lo = bf16(r - hi); columns k in [n, koff) of both planes are written as zero.  ldt >= 2*koff.
+// dst (cols x rows, ldd) = src^T, src rows x cols (lds_); sizes multiples of 64, 16-byte aligned rows
+hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int cols, bf16_t* dst, long ldd, hipStream_t s);
 hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, int koff, hipStream_t s);
 // Fused Whip loss + gradient pass: partial sums to `partials` (double, one per workgroup), then
 // launch_loss_finish adds them up: loss = scale * sum.  dy_is_bf16 selects the dtype of dY.

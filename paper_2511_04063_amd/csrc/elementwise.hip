@@ -170,6 +170,40 @@ __global__ __launch_bounds__(256) void split_transpose_bf16_kernel(const float* 
     }
 }
 
+// dst (cols x rows) = src^T for a rows x cols bf16 matrix, 64 x 64 tiles through LDS with 16-byte loads and stores.
+// rows and cols are multiples of 64, both leading dimensions multiples of 8 and both pointers 16-byte aligned.
+// Operand preparation for G = X^T dY (Alg. 1 line 9): with both operands stored token-contiguous the product reads
+// rows only.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, long lds_, int rows,
+                                                             int cols, bf16_t* __restrict__ dst, long ldd) {
+    constexpr int S = 66;   // row stride of the tile in elements: 33 words, odd
+    __shared__ __align__(16) unsigned short tile[64 * S];
+    const int tiles_c = cols >> 6;
+    const int r0 = (blockIdx.x / tiles_c) << 6, c0 = (blockIdx.x % tiles_c) << 6;
+    const int tid = threadIdx.x;
+    const int part = tid & 7, line = tid >> 3;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int r = line + 32 * h;
+        const uint4 v = *reinterpret_cast<const uint4*>(src + (long)(r0 + r) * lds_ + c0 + part * 8);
+        uint32_t* t = reinterpret_cast<uint32_t*>(tile + r * S + part * 8);
+        t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int c = line + 32 * h;   // column of src = row of dst
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t lo = tile[(part * 8 + 2 * k) * S + c];
+            const uint32_t hi = tile[(part * 8 + 2 * k + 1) * S + c];
+            w[k] = lo | (hi << 16);
+        }
+        *reinterpret_cast<uint4*>(dst + (long)(c0 + c) * ldd + r0 + part * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // P[i][j] = B[i][j] - B[j][i] for i > j, else 0.  Mzero (optional) is cleared.
 __global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict__ B, long ldb, int n,
                                                          float* __restrict__ P, long ldp, float* __restrict__ Mz,
@@ -338,6 +372,17 @@ hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* 
                                        hipStream_t s) {
     hipLaunchKernelGGL(split_transpose_bf16_kernel, dim3((n + 31) / 32, (koff + 31) / 32), dim3(256), 0, s, R, ldr, n,
                        RbT, ldt, koff);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int cols, bf16_t* dst, long ldd,
+                                 hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    if ((rows & 63) || (cols & 63) || (lds_ & 7) || (ldd & 7) || lds_ < cols || ldd < rows ||
+        (reinterpret_cast<uintptr_t>(src) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_bf16_kernel, dim3((rows >> 6) * (cols >> 6)), dim3(256), 0, s, src, lds_, rows, cols,
+                       dst, ldd);
     return hipGetLastError();
 }
 
