@@ -67,7 +67,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
-           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, rbt = 0, losspart = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -111,6 +111,10 @@ Layout make_layout(int n, int T) {
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
     L.Y = bump(cur, tn * 4);
     L.dY = bump(cur, tn * 4);
+    // token-contiguous bf16 copies of X and dY (n x T each) for G = X^T dY
+    const size_t tld = (size_t)round_up(T > 0 ? T : 1, 64);
+    L.xt = bump(cur, (size_t)round_up(n, 64) * tld * 2);
+    L.dyt = bump(cur, (size_t)round_up(n, 64) * tld * 2);
     L.rbt = bump(cur, (size_t)n * 2 * round_up(n, 32) * 2);
     L.losspart = bump(cur, (size_t)kLossPartials * 8);
     L.gsplit_floats = (size_t)kMaxSplit * n2;
@@ -567,6 +571,26 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         float* out = splits > 1 ? gs : G;
         const long ldo = splits > 1 ? L.ld : ldg;
         const long stride = (long)n * L.ld;
+        // Large round bf16 shapes: both operands are first transposed (two HBM-bound passes), so that the product
+        // reads rows only and runs in the unguarded deep-prefetch kernel without a split of the token sum.
+        static const int use_t = [] { const char* e = getenv("DQ_G_TRANSPOSE"); return e ? atoi(e) : 1; }();
+        if (xdt == DQ_BF16 && use_t && n % 128 == 0 && T % 128 == 0 && tiles >= 256 && (ldx & 7) == 0 &&
+            (lddy & 7) == 0 && aligned16(X) && aligned16(dY) && aligned16(G) && (ldg & 3) == 0) {
+            bf16_t* xt = at<bf16_t>(c, L.xt);
+            bf16_t* dyt = at<bf16_t>(c, L.dyt);
+            {
+                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * T * (double)n);
+                DQ_HIP(launch_transpose_bf16(static_cast<const bf16_t*>(X), ldx, T, n, xt, T, s));
+                DQ_HIP(launch_transpose_bf16(static_cast<const bf16_t*>(dY), lddy, T, n, dyt, T, s));
+            }
+            GemmBf16 g;
+            g.A = xt; g.lda = T; g.ta = 0;
+            g.B = dyt; g.ldb = T; g.tb = 1;
+            g.C = G; g.ldc = ldg; g.M = n; g.N = n; g.K = T;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
+            DQ_HIP(launch_gemm_bf16(g, s));
+            return DQ_OK;
+        }
         if (xdt == DQ_BF16) {
             GemmBf16 g;
             g.A = static_cast<const bf16_t*>(X); g.lda = ldx; g.ta = 1;
