@@ -680,6 +680,109 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
     return DQ_OK;
 }
 
+// ---------------------------------------------------------------- batched 128 x 128 rotations
+// Every problem of the batch runs in the same launches.  The path's buffers (b matrices each, row stride 128) sit
+// behind the general layout in the workspace.
+struct HeadsLayout {
+    size_t R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, uinv = 0, gpart = 0, lpart = 0, total = 0;
+};
+
+HeadsLayout make_heads_layout(size_t base, int b, int T) {
+    HeadsLayout H;
+    size_t cur = base;
+    const size_t mat = (size_t)(b > 0 ? b : 1) * kHeadDim * kHeadDim * 4;
+    const size_t sp = (size_t)heads_splits(T > 0 ? T : 1);
+    H.R = bump(cur, mat);
+    H.U = bump(cur, mat);
+    H.G = bump(cur, mat);
+    H.B = bump(cur, mat);
+    H.P = bump(cur, mat);
+    H.M = bump(cur, mat);
+    H.uinv = bump(cur, mat);
+    H.gpart = bump(cur, mat * sp);
+    H.lpart = bump(cur, (size_t)(b > 0 ? b : 1) * sp * 8);
+    H.total = cur;
+    return H;
+}
+
+bool heads_route(int n) {
+    static const int on = [] { const char* e = getenv("DQ_HEADS_BATCHED"); return e ? atoi(e) : 1; }();
+    return on != 0 && n == kHeadDim;
+}
+
+dq_status check_heads_ws(dq_ctx* c, const HeadsLayout& H) {
+    if (c->ws == nullptr || c->ws_bytes < H.total) return DQ_ERR_WORKSPACE;
+    return DQ_OK;
+}
+
+dq_status heads_qr(dq_ctx* c, int b, const float* Z, long ldz, float* R, long ldr, float* U, long ldu) {
+    const int n = kHeadDim;
+    LaunchScope sc(&c->prof, c->stream, DQ_K_PANEL, b * (10.0 / 3.0) * n * (double)n * n, 0.0);
+    DQ_HIP(launch_heads_qr(b, Z, ldz, (long)n * ldz, R, ldr, (long)n * ldr, U, ldu, (long)n * ldu,
+                           at<unsigned>(c, 0), c->stream));
+    return DQ_OK;
+}
+
+dq_status heads_rotate_loss_grad(dq_ctx* c, const HeadsLayout& H, int b, int T, const void* X, long ldx, const float* R,
+                                 long ldr, dq_reduce red, float* loss_dev, float* G, long ldg) {
+    const int n = kHeadDim;
+    const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
+    LaunchScope sc(&c->prof, c->stream, DQ_K_GEMM_BF16, b * 4.0 * T * (double)n * n, b * 2.0 * T * (double)n);
+    DQ_HIP(launch_heads_rlg(b, T, static_cast<const bf16_t*>(X), ldx, (long)T * ldx, R, ldr, (long)n * ldr, scale,
+                            at<float>(c, H.gpart), at<double>(c, H.lpart), G, ldg, (long)n * ldg, loss_dev,
+                            at<unsigned>(c, 0), c->stream));
+    return DQ_OK;
+}
+
+// dZ_i = R_i P_i U_i^{-T} for every problem (or Z_i -= lr dZ_i when Zupd != null): the steps of qr_backward_one with
+// one 128-wide block, as batched launches.
+dq_status heads_backward(dq_ctx* c, const HeadsLayout& H, int b, const float* R, long ldr, const float* U, long ldu,
+                         const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr) {
+    const int n = kHeadDim;
+    const long nn = (long)n * n;
+    hipStream_t s = c->stream;
+    unsigned* flags = at<unsigned>(c, 0);
+    float* Bb = at<float>(c, H.B);
+    float* Pb = at<float>(c, H.P);
+    float* Mb = at<float>(c, H.M);
+    float* uinv = at<float>(c, H.uinv);
+    const double n3 = (double)b * n * n * n;
+    {
+        GemmF32 g;   // B = R^T G
+        g.A = R; g.lda = ldr; g.ta = 1; g.batch_a = (long)n * ldr;
+        g.B = G; g.ldb = ldg; g.tb = 0; g.batch_b = (long)n * ldg;
+        g.C = Bb; g.ldc = n; g.batch_c = nn;
+        g.M = n; g.N = n; g.K = n; g.batch = b;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * b * (double)nn);
+        DQ_HIP(launch_skew_lower(Bb, n, n, Pb, n, nullptr, 0, s, b, nn, nn, 0));
+        DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s, b, (long)n * ldu, nn));
+    }
+    {
+        GemmF32 g;   // M = P inv(U)^T
+        g.A = Pb; g.lda = n; g.ta = 0; g.batch_a = nn;
+        g.B = uinv; g.ldb = kTrsmBlock; g.tb = 1; g.batch_b = nn;
+        g.C = Mb; g.ldc = n; g.batch_c = nn;
+        g.M = n; g.N = n; g.K = n; g.batch = b;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    {
+        GemmF32 g;   // dZ = R M  (or Z <- Z - lr R M)
+        g.A = R; g.lda = ldr; g.ta = 0; g.batch_a = (long)n * ldr;
+        g.B = Mb; g.ldb = n; g.tb = 0; g.b_strict_lower = 1; g.batch_b = nn;
+        g.M = n; g.N = n; g.K = n; g.batch = b;
+        if (Zupd != nullptr) { g.C = Zupd; g.ldc = ldz; g.batch_c = (long)n * ldz; g.alpha = -lr; g.beta = 1.f; }
+        else { g.C = dZ; g.ldc = lddz; g.batch_c = (long)n * lddz; }
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    return DQ_OK;
+}
+
 }  // namespace
 
 // =================================================================== C ABI
@@ -738,7 +841,8 @@ dq_status dq_workspace_bytes(int b, int n, int T, dq_dtype x_dtype, size_t* out)
     if (b < 0 || T < 1) return DQ_ERR_SHAPE;
     DQ_TRY(check_n(n));
     if (x_dtype != DQ_F32 && x_dtype != DQ_BF16) return DQ_ERR_DTYPE;
-    *out = make_layout(n, T).total;
+    const Layout L = make_layout(n, T);
+    *out = heads_route(n) ? make_heads_layout(L.total, b, T).total : L.total;
     return DQ_OK;
 }
 
@@ -770,6 +874,7 @@ dq_status dq_qr_orth(dq_ctx* c, int b, int n, const float* Z, long ldz, float* R
     if (U != nullptr) DQ_TRY(check_f32(U, ldu, n));
     const Layout L = make_layout(n, 1);
     DQ_TRY(check_ws(c, L));
+    if (heads_route(n)) return heads_qr(c, b, Z, ldz, R, ldr, U, ldu);
     for (int i = 0; i < b; ++i)
         DQ_TRY(qr_orth_one(c, L, n, Z + (long)i * n * ldz, ldz, R + (long)i * n * ldr, ldr,
                            U ? U + (long)i * n * ldu : nullptr, ldu));
@@ -790,6 +895,11 @@ dq_status dq_rotate_loss_grad(dq_ctx* c, int b, int T, int n, const void* X, dq_
     if (dY != nullptr) DQ_TRY(check_x(dY, xdt, lddy, n));
     const Layout L = make_layout(n, T);
     DQ_TRY(check_ws(c, L));
+    if (heads_route(n) && xdt == DQ_BF16 && Y == nullptr && dY == nullptr) {
+        const HeadsLayout H = make_heads_layout(L.total, b, T);
+        DQ_TRY(check_heads_ws(c, H));
+        return heads_rotate_loss_grad(c, H, b, T, X, ldx, R, ldr, red, loss_dev, G, ldg);
+    }
     const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
     for (int i = 0; i < b; ++i) {
         float* Yi = Y ? Y + (long)i * T * ldy : at<float>(c, L.Y);
@@ -815,6 +925,17 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
     if (R != nullptr) DQ_TRY(check_f32(R, ldr, n));
     const Layout L = make_layout(n, T);
     DQ_TRY(check_ws(c, L));
+    if (heads_route(n) && xdt == DQ_BF16) {
+        const HeadsLayout H = make_heads_layout(L.total, b, T);
+        DQ_TRY(check_heads_ws(c, H));
+        float* Rh = R ? R : at<float>(c, H.R);
+        const long ldrh = R ? ldr : kHeadDim;
+        float* Uh = at<float>(c, H.U);
+        float* Gh = at<float>(c, H.G);
+        DQ_TRY(heads_qr(c, b, Z, ldz, Rh, ldrh, Uh, kHeadDim));
+        DQ_TRY(heads_rotate_loss_grad(c, H, b, T, X, ldx, Rh, ldrh, red, loss_dev, Gh, kHeadDim));
+        return heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, nullptr, 0, Z, ldz, lr);
+    }
     const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
     for (int i = 0; i < b; ++i) {
         float* Zi = Z + (long)i * n * ldz;
@@ -872,6 +993,11 @@ dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, cons
     DQ_TRY(check_f32(dZ, lddz, n));
     const Layout L = make_layout(n, 1);
     DQ_TRY(check_ws(c, L));
+    if (heads_route(n)) {
+        const HeadsLayout H = make_heads_layout(L.total, b, 1);
+        DQ_TRY(check_heads_ws(c, H));
+        return heads_backward(c, H, b, R, ldr, U, ldu, G, ldg, dZ, lddz, nullptr, 0, 0.f);
+    }
     for (int i = 0; i < b; ++i)
         DQ_TRY(qr_backward_one(c, L, n, R + (long)i * n * ldr, ldr, U + (long)i * n * ldu, ldu, G + (long)i * n * ldg,
                                ldg, dZ + (long)i * n * lddz, lddz, nullptr, 0, 0.f));
@@ -940,6 +1066,22 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
     const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
     const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
     const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    if (heads_route(n) && xdt == DQ_BF16 && ldz == n && ldm == n && ldv == n) {
+        const HeadsLayout H = make_heads_layout(L.total, b, T);
+        DQ_TRY(check_heads_ws(c, H));
+        float* Rh = R ? R : at<float>(c, H.R);
+        const long ldrh = R ? ldr : kHeadDim;
+        float* Uh = at<float>(c, H.U);
+        float* Gh = at<float>(c, H.G);
+        float* dZh = at<float>(c, H.B);   // B = R^T G is consumed before the last product writes dZ there
+        DQ_TRY(heads_qr(c, b, Z, ldz, Rh, ldrh, Uh, kHeadDim));
+        DQ_TRY(heads_rotate_loss_grad(c, H, b, T, X, ldx, Rh, ldrh, red, loss_dev, Gh, kHeadDim));
+        DQ_TRY(heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, dZh, kHeadDim, nullptr, 0, 0.f));
+        // the b problems are stacked row-wise with a common row stride: one elementwise pass over b*n rows
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * b * n * (double)n, 28.0 * b * n * (double)n);
+        DQ_HIP(launch_adam2d(Z, ldz, dZh, kHeadDim, m, ldm, v, ldv, n, lr, beta1, beta2, eps, c1, c2, c->stream, b * n));
+        return DQ_OK;
+    }
     for (int i = 0; i < b; ++i) {
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);

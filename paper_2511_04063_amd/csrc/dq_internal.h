@@ -13,6 +13,8 @@ constexpr int kPanel = 64;           // QR panel width nb (columns aggregated in
 constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
 constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
+constexpr int kHeadDim = 128;         // matrix size served by the batched small-rotation path
+constexpr int kHeadsChunk = 2048;     // tokens per workgroup of its fused rotate / loss / gradient kernel
 constexpr int kLossPartials = 65536; // upper bound on workgroups of the Whip pass (one partial each)
 constexpr int kAccumPanels = 4;      // panels whose reflectors are merged before they are applied to the accumulated R
 constexpr int kCholMaxParts = 64;    // upper bound on the Gram partials of the tall-panel path
@@ -50,6 +52,9 @@ struct GemmF32 {
     // split-K: z-th workgroup layer reduces k in [z*kchunk, (z+1)*kchunk) and writes C + z*split_stride
     int splits = 1; int kchunk = 0; long split_stride = 0;
     int cfg = -1;          // tile configuration (-1: chosen from the shape; 3: 64 x 64 tiles, K step 32)
+    // batch > 1: that many independent products in one launch; problem i reads A + i*batch_a, B + i*batch_b and
+    // writes C + i*batch_c (element offsets)
+    int batch = 1; long batch_a = 0, batch_b = 0, batch_c = 0;
 };
 hipError_t launch_gemm_f32(const GemmF32& g, hipStream_t s);
 int gemm_f32_tile_n(int M, int N);   // width of the workgroup tile the launcher picks
@@ -113,16 +118,30 @@ hipError_t launch_fill_u32(unsigned* p, long count, unsigned v, hipStream_t s);
 hipError_t launch_sign_normalise(const float* Afac, long lda, int n, float* R, long ldr, float* U, long ldu,
                                  unsigned* flags, hipStream_t s);
 
+// ---- batched 128 x 128 rotations (all problems of a batch in one launch) -------------
+// R (orthogonal, diag(U) >= 0) and U (optional) of b latents; problem i at Z + i*sz etc. (element strides).
+hipError_t launch_heads_qr(int b, const float* Z, long ldz, long sz, float* R, long ldr, long sr, float* U, long ldu,
+                           long su, unsigned* flags, hipStream_t s);
+// loss[i] = scale * sum exp(-|X_i R_i|) and G_i = X_i^T dY_i for bf16 X_i (T x 128), fused.  Gpart needs
+// b * heads_splits(T) * 128 * 128 floats, lpart b * heads_splits(T) doubles.
+int heads_splits(int T);
+hipError_t launch_heads_rlg(int b, int T, const bf16_t* X, long ldx, long sx, const float* R, long ldr, long sr,
+                            float scale, float* Gpart, double* lpart, float* G, long ldg, long sg, float* loss,
+                            unsigned* flags, hipStream_t s);
+
 // ---- backward pieces --------------------------------------------------------------
 // P = strict_lower(B - B^T); Mzero gets zeros everywhere (if non-null).
-hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp, float* Mzero, long ldm, hipStream_t s);
+// batch > 1: that many problems in one launch, problem i at the given element strides.
+hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp, float* Mzero, long ldm, hipStream_t s,
+                             int batch = 1, long stride_b = 0, long stride_p = 0, long stride_m = 0);
 // Inverse of every kTrsmBlock x kTrsmBlock diagonal block of the upper-triangular U: Uinv[blk] row-major, ld kTrsmBlock.
-hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s);
+hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s,
+                               int batch = 1, long stride_u = 0, long stride_inv = 0);
 hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s);
 // Adam / heavy-ball updates of an n x n matrix in place (see include/dartqr.h); c1 = 1 / (1 - beta1^t),
 // c2 = 1 / (1 - beta2^t) are formed on the host in double precision.
 hipError_t launch_adam2d(float* Z, long ldz, const float* D, long ldd, float* m, long ldm, float* v, long ldv, int n,
-                         float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s);
+                         float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s, int rows = -1);
 hipError_t launch_momentum2d(float* Z, long ldz, const float* D, long ldd, float* buf, long ldb, int n, float lr,
                              float mu, hipStream_t s);
 

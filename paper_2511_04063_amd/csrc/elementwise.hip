@@ -204,11 +204,14 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
     }
 }
 
-// P[i][j] = B[i][j] - B[j][i] for i > j, else 0.  Mzero (optional) is cleared.
+// P[i][j] = B[i][j] - B[j][i] for i > j, else 0.  Mzero (optional) is cleared.  blockIdx.z: problem of a batch.
 __global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict__ B, long ldb, int n,
                                                          float* __restrict__ P, long ldp, float* __restrict__ Mz,
-                                                         long ldm) {
+                                                         long ldm, long sb, long sp, long sm) {
     __shared__ float tile[32][33];
+    B += (long)blockIdx.z * sb;
+    P += (long)blockIdx.z * sp;
+    if (Mz != nullptr) Mz += (long)blockIdx.z * sm;
     const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // output tile: rows by.., cols bx..
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const bool need = by + 31 > bx;   // some i > j in this tile
@@ -255,7 +258,10 @@ __device__ __forceinline__ void store_block64(const float* src, float* __restric
     }
 }
 __global__ __launch_bounds__(NTHR) void trinv_blocks_kernel(const float* __restrict__ U, long ldu, int n,
-                                                            float* __restrict__ Uinv, unsigned* flags) {
+                                                            float* __restrict__ Uinv, unsigned* flags, long su,
+                                                            long sinv) {
+    U += (long)blockIdx.y * su;       // problem of a batch
+    Uinv += (long)blockIdx.y * sinv;
     __shared__ float Bs[3 * B64 * LS];
     float* B0 = Bs;
     float* B1 = Bs + B64 * LS;
@@ -301,11 +307,11 @@ __global__ __launch_bounds__(256) void axpy2d_kernel(float* __restrict__ Z, long
 // (Adam: 16 B read + 12 B written per element).  Row/column indexing because every matrix has its own leading
 // dimension.
 __global__ __launch_bounds__(256) void adam2d_kernel(float* __restrict__ Z, long ldz, const float* __restrict__ D, long ldd,
-                                                     float* __restrict__ m, long ldm, float* __restrict__ v, long ldv, int n,
-                                                     float lr, float beta1, float beta2, float omb1, float omb2, float eps, float c1,
+                                                     float* __restrict__ m, long ldm, float* __restrict__ v, long ldv, int rows,
+                                                     int n, float lr, float beta1, float beta2, float omb1, float omb2, float eps, float c1,
                                                      float c2) {
     const int q = (n + 3) >> 2;
-    const long total = (long)n * q;
+    const long total = (long)rows * q;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
         const int r = (int)(e / q), c0 = (int)(e % q) << 2;
 #pragma unroll
@@ -387,25 +393,32 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int col
 }
 
 hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp, float* Mzero, long ldm,
-                             hipStream_t s) {
+                             hipStream_t s, int batch, long stride_b, long stride_p, long stride_m) {
     const int tb = (n + 31) / 32;
-    hipLaunchKernelGGL(skew_lower_kernel, dim3(tb, tb), dim3(256), 0, s, B, ldb, n, P, ldp, Mzero, ldm);
+    if (batch < 1) return hipSuccess;
+    hipLaunchKernelGGL(skew_lower_kernel, dim3(tb, tb, batch), dim3(256), 0, s, B, ldb, n, P, ldp, Mzero, ldm,
+                       stride_b, stride_p, stride_m);
     return hipGetLastError();
 }
 
-hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s) {
+hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s,
+                               int batch, long stride_u, long stride_inv) {
     const int nb = (n + kTrsmBlock - 1) / kTrsmBlock;
-    hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb), dim3(NTHR), 0, s, U, ldu, n, Uinv, flags);
+    if (batch < 1) return hipSuccess;
+    hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb, batch), dim3(NTHR), 0, s, U, ldu, n, Uinv, flags, stride_u,
+                       stride_inv);
     return hipGetLastError();
 }
 
 hipError_t launch_adam2d(float* Z, long ldz, const float* D, long ldd, float* m, long ldm, float* v, long ldv, int n,
-                         float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s) {
+                         float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s, int rows) {
+    if (rows < 0) rows = n;
     // 1 - beta in double: in fp32 the difference 1 - 0.999 alone is off by 6e-5 relative
     const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
-    long b = ((long)n * ((n + 3) / 4) + 255) / 256;
+    long b = ((long)rows * ((n + 3) / 4) + 255) / 256;
     if (b > 8192) b = 8192;
-    hipLaunchKernelGGL(adam2d_kernel, dim3((unsigned)b), dim3(256), 0, s, Z, ldz, D, ldd, m, ldm, v, ldv, n, lr, beta1,
+    if (b < 1) return hipSuccess;
+    hipLaunchKernelGGL(adam2d_kernel, dim3((unsigned)b), dim3(256), 0, s, Z, ldz, D, ldd, m, ldm, v, ldv, rows, n, lr, beta1,
                        beta2, omb1, omb2, eps, c1, c2);
     return hipGetLastError();
 }

@@ -137,10 +137,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     }
 
     OperandView oa, ob;
-    oa.p = g.A; oa.ld = g.lda; oa.vec = avec;
+    const long bz = blockIdx.z;   // independent problem of a batched launch
+    oa.p = g.A + bz * g.batch_a; oa.ld = g.lda; oa.vec = avec;
     oa.unit_lower_cols = g.a_unit_lower ? 0x7fffffff : 0;
     if (TA) { oa.row_lim = ke; oa.col_lim = g.M; } else { oa.row_lim = g.M; oa.col_lim = ke; }
-    ob.p = g.B; ob.ld = g.ldb; ob.vec = bvec;
+    ob.p = g.B + bz * g.batch_b; ob.ld = g.ldb; ob.vec = bvec;
     ob.unit_lower_cols = g.b_unit_lower_cols;
     if (TB) { ob.row_lim = g.N; ob.col_lim = ke; } else { ob.row_lim = ke; ob.col_lim = g.N; }
 
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
         __syncthreads();
     }
 
-    float* C = g.C + (long)z * g.split_stride;
+    float* C = g.C + bz * g.batch_c + (long)z * g.split_stride;
     const float alpha = g.alpha, beta = g.beta;
     // All reads of C are issued before the first write: interleaved they would serialise on possible aliasing and
     // expose one memory round trip per element.
@@ -261,9 +262,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 template <int BM, int BN, int WT, int BK>
 static hipError_t launch_gemm_f32_tile(const GemmF32& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-    const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 3) == 0) ? 1 : 0;
-    const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 3) == 0) ? 1 : 0;
-    dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);
+    const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 3) == 0 && (g.batch_a & 3) == 0) ? 1 : 0;
+    const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 3) == 0 && (g.batch_b & 3) == 0) ? 1 : 0;
+    dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, g.batch > 1 ? g.batch : 1);
     dim3 block(256, 1, 1);
     if (g.ta && g.tb)
         hipLaunchKernelGGL((gemm_f32_kernel<true, true, BM, BN, WT, BK>), grid, block, 0, s, g, tiles_m, tiles_n, avec, bvec);

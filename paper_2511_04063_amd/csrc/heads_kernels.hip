@@ -1,0 +1,323 @@
+// Batched path for many small rotations of size 128 (per-head rotations; the "heads" workload): every problem of a
+// batch runs in the same launch.
+//   * heads_qr_kernel: R, U = qr(Z) for one 128 x 128 latent per workgroup, entirely in LDS.  Alg. 2 as printed:
+//     column by column, the reflector is applied to the trailing columns of the matrix and accumulated into the
+//     orthogonal factor in the same step (A <- H A, Q <- Q H); the signs are then fixed so that diag(U) >= 0.
+//   * heads_rlg_kernel: Alg. 1 lines 8-9 fused for bf16 activations.  A workgroup streams 64-token tiles of X once;
+//     Y = X R (R as two bf16 planes held in registers), the Whip loss and its gradient (Eq. 4) and the tile's
+//     contribution to G = X^T dY are formed on chip: Y and dY never reach HBM.
+//   * heads_reduce_kernel: sums the per-workgroup partial G and loss.
+// The derivative through the QR runs through the batched forms of the general kernels.
+#include "dq_internal.h"
+
+namespace dq {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int HN = kHeadDim;     // matrix size of this path
+constexpr int HS = HN + 1;       // LDS row stride of the fp32 matrices (conflict-free row and column walks)
+
+__device__ __forceinline__ float wave_total(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ uint32_t to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// ------------------------------------------------------------------------------------------------ S1 + S2
+// Reflector convention as in the panel kernels: H = I - tau v v^T, v[j] = 1, beta = -sign(alpha) ||x||,
+// tau = (beta - alpha) / beta, v[i] = x[i] / (alpha - beta); a column that is already zero below the diagonal gets
+// H = I.  Threads 0..127 own one column of A each (rows of the reflector applied from the left), threads 128..255
+// one row of Q each (the same reflector applied from the right); every wavefront forms the column norm itself, so a
+// step needs one barrier.
+__global__ __launch_bounds__(256) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
+                                                       float* __restrict__ R, long ldr, long sr,
+                                                       float* __restrict__ U, long ldu, long su, unsigned* flags) {
+    __shared__ float As[HN * HS];
+    __shared__ float Qs[HN * HS];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const float* Zp = Z + (long)blockIdx.x * sz;
+    for (int e = tid; e < HN * HN / 4; e += 256) {
+        const int r = e >> 5, c = (e & 31) << 2;
+        const float4 v = *reinterpret_cast<const float4*>(Zp + (long)r * ldz + c);
+        float* a = As + r * HS + c;
+        a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w;
+        float* q = Qs + r * HS + c;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) q[k] = (r == c + k) ? 1.f : 0.f;
+    }
+    __syncthreads();
+    for (int j = 0; j < HN; ++j) {
+        float s = 0.f;
+        for (int i = j + 1 + lane; i < HN; i += 64) {
+            const float x = As[i * HS + j];
+            s += x * x;
+        }
+        s = wave_total(s);
+        const float alpha = As[j * HS + j];
+        float tau = 0.f, vs = 0.f, beta = alpha;
+        if (s != 0.f) {
+            const float nrm = sqrtf(alpha * alpha + s);
+            beta = alpha >= 0.f ? -nrm : nrm;
+            tau = (beta - alpha) / beta;
+            vs = 1.f / (alpha - beta);
+        }
+        if (tau != 0.f) {
+            if (tid < HN) {
+                const int c = tid;
+                if (c > j) {
+                    float dot = As[j * HS + c];
+                    for (int i = j + 1; i < HN; ++i) dot += (As[i * HS + j] * vs) * As[i * HS + c];
+                    const float f = tau * dot;
+                    As[j * HS + c] -= f;
+                    for (int i = j + 1; i < HN; ++i) As[i * HS + c] -= f * (As[i * HS + j] * vs);
+                }
+            } else {
+                const int r = tid - HN;
+                float dot = Qs[r * HS + j];
+                for (int i = j + 1; i < HN; ++i) dot += Qs[r * HS + i] * (As[i * HS + j] * vs);
+                const float f = tau * dot;
+                Qs[r * HS + j] -= f;
+                for (int i = j + 1; i < HN; ++i) Qs[r * HS + i] -= f * (As[i * HS + j] * vs);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) As[j * HS + j] = beta;   // nothing reads this entry again before the loop ends
+    }
+    __syncthreads();
+    if (tid < HN) {
+        const float d = As[tid * HS + tid];
+        if (!(fabsf(d) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+        else if (d == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+    }
+    float* Rp = R + (long)blockIdx.x * sr;
+    float* Up = U != nullptr ? U + (long)blockIdx.x * su : nullptr;
+    for (int e = tid; e < HN * HN; e += 256) {
+        const int r = e >> 7, c = e & (HN - 1);
+        const float sc = As[c * HS + c] >= 0.f ? 1.f : -1.f;
+        Rp[(long)r * ldr + c] = Qs[r * HS + c] * sc;
+        if (Up != nullptr) {
+            const float sr_ = As[r * HS + r] >= 0.f ? 1.f : -1.f;
+            Up[(long)r * ldu + c] = (c >= r) ? sr_ * As[r * HS + c] : 0.f;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ S3 + S4 + S5
+constexpr int TT = 64;            // tokens per tile
+constexpr int XLD = HN + 8;       // halfwords per LDS row of an X tile (272 bytes: 16-byte rows, 4-bank skew)
+constexpr int DLD = TT + 8;       // halfwords per LDS row of the transposed dY tile (144 bytes)
+
+struct XRegs { uint4 q0, q1, q2, q3; };
+
+// tile rows [t0, t0 + 64) of X (tokens >= tend read as zero): 16 threads per row, 16 bytes each
+__device__ __forceinline__ XRegs fetch_x(const bf16_t* __restrict__ Xp, long ldx, int t0, int tend, int tid) {
+    const int col = (tid & 15) * 8, row = t0 + (tid >> 4);
+    const bf16_t* p = Xp + (long)row * ldx + col;
+    XRegs r;
+    r.q0 = r.q1 = r.q2 = r.q3 = make_uint4(0u, 0u, 0u, 0u);
+    if (row < tend) r.q0 = *reinterpret_cast<const uint4*>(p);
+    if (row + 16 < tend) r.q1 = *reinterpret_cast<const uint4*>(p + 16 * ldx);
+    if (row + 32 < tend) r.q2 = *reinterpret_cast<const uint4*>(p + 32 * ldx);
+    if (row + 48 < tend) r.q3 = *reinterpret_cast<const uint4*>(p + 48 * ldx);
+    return r;
+}
+__device__ __forceinline__ void stash_x(bf16_t* Xs, int tid, const XRegs r) {
+    bf16_t* p = Xs + (tid >> 4) * XLD + (tid & 15) * 8;
+    *reinterpret_cast<uint4*>(p) = r.q0;
+    *reinterpret_cast<uint4*>(p + 16 * XLD) = r.q1;
+    *reinterpret_cast<uint4*>(p + 32 * XLD) = r.q2;
+    *reinterpret_cast<uint4*>(p + 48 * XLD) = r.q3;
+}
+
+// One 64-token tile.  Wavefront w forms Y[:, 32w .. 32w+32) (two 32 x 32 accumulators), applies Eq. 4 and its
+// derivative, leaves dY transposed in LDS; after the barrier it adds X_tile^T dY_tile to its 32 rows of G.
+// Matrix-core operand layout (32x32x16 bf16): lane l supplies row/column (l & 31) and the 8 consecutive reduction
+// indices 8 (l >> 5) ..; the 32 x 32 result holds row 8 (v >> 2) + 4 (l >> 5) + (v & 3), column (l & 31) in register v.
+__device__ __forceinline__ void heads_tile(const bf16_t* Xs, bf16_t* dYs, const bf16x8 (&rhi)[8], const bf16x8 (&rlo)[8],
+                                           f32x16 (&accG)[4], float& lsum, float scale, int tok_base, int tend,
+                                           int wave, int lrow, int lk) {
+    f32x16 y0, y1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { y0[v] = 0.f; y1[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Xs + lrow * XLD + ks * 16 + lk * 8);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Xs + (32 + lrow) * XLD + ks * 16 + lk * 8);
+        y0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, rhi[ks], y0, 0, 0, 0);
+        y1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, rhi[ks], y1, 0, 0, 0);
+        y0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, rlo[ks], y0, 0, 0, 0);
+        y1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, rlo[ks], y1, 0, 0, 0);
+    }
+    const int j = 32 * wave + lrow;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int tok0 = i * 32 + 8 * g + 4 * lk;
+            u32x4 h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float y = i == 0 ? y0[4 * g + q] : y1[4 * g + q];
+                const float ex = __expf(-fabsf(y));
+                if (tok_base + tok0 + q < tend) lsum += ex;
+                const float sg = (y > 0.f) ? -scale : ((y < 0.f) ? scale : 0.f);
+                h[q] = to_bf16_rne(sg * ex);
+            }
+            *reinterpret_cast<uint2*>(dYs + j * DLD + tok0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+        }
+    }
+    __syncthreads();
+    const int ch = 32 * wave + lrow;   // this lane's row of G
+#pragma unroll
+    for (int kt = 0; kt < TT / 16; ++kt) {
+        u32x4 au;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lo = Xs[(kt * 16 + lk * 8 + 2 * e) * XLD + ch];
+            const uint32_t hi = Xs[(kt * 16 + lk * 8 + 2 * e + 1) * XLD + ch];
+            au[e] = lo | (hi << 16);
+        }
+        const bf16x8 afr = __builtin_bit_cast(bf16x8, au);
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(dYs + (jb * 32 + lrow) * DLD + kt * 16 + lk * 8);
+            accG[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr, bfr, accG[jb], 0, 0, 0);
+        }
+    }
+}
+
+// grid (splits, b): workgroup (s, p) handles tokens [s * chunk, min(T, (s+1) * chunk)) of problem p and writes its
+// partial G to Gpart[(p * splits + s) * 128 * 128 ..] and its partial sum of exp(-|y|) to lpart[p * splits + s].
+__global__ __launch_bounds__(256) void heads_rlg_kernel(const bf16_t* __restrict__ X, long ldx, long sx, int T,
+                                                        const float* __restrict__ R, long ldr, long sr, float scale,
+                                                        float* __restrict__ Gpart, double* __restrict__ lpart,
+                                                        int chunk) {
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[2][TT * XLD];
+    __shared__ __attribute__((aligned(16))) bf16_t dYs[HN * DLD];
+    __shared__ float wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lk = lane >> 5;
+    const int split = blockIdx.x, prob = blockIdx.y, splits = gridDim.x;
+    const bf16_t* Xp = X + (long)prob * sx;
+    const float* Rp = R + (long)prob * sr;
+    const int tbeg = split * chunk;
+    const int tend = (tbeg + chunk < T) ? tbeg + chunk : T;
+    const int ntiles = tend > tbeg ? (tend - tbeg + TT - 1) / TT : 0;
+
+    // this wavefront's 32 columns of R as matrix-core operands: R = hi + lo, 16 mantissa bits
+    bf16x8 rhi[8], rlo[8];
+    {
+        const int j = 32 * wave + lrow;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 hi, lo;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float r0 = Rp[(long)(ks * 16 + lk * 8 + 2 * e) * ldr + j];
+                const float r1 = Rp[(long)(ks * 16 + lk * 8 + 2 * e + 1) * ldr + j];
+                const uint32_t h0 = to_bf16_rne(r0), h1 = to_bf16_rne(r1);
+                const uint32_t l0 = to_bf16_rne(r0 - __uint_as_float(h0 << 16));
+                const uint32_t l1 = to_bf16_rne(r1 - __uint_as_float(h1 << 16));
+                hi[e] = h0 | (h1 << 16);
+                lo[e] = l0 | (l1 << 16);
+            }
+            rhi[ks] = __builtin_bit_cast(bf16x8, hi);
+            rlo[ks] = __builtin_bit_cast(bf16x8, lo);
+        }
+    }
+
+    f32x16 accG[4];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accG[jb][v] = 0.f;
+    float lsum = 0.f;
+
+    XRegs p0 = fetch_x(Xp, ldx, tbeg, tend, tid);
+    XRegs p1 = fetch_x(Xp, ldx, tbeg + TT, tend, tid);
+    stash_x(Xs[0], tid, p0);
+    __syncthreads();
+    for (int it = 0; it < ntiles; it += 2) {
+        // tile `it` is in Xs[0], tile it+1 in p1; tile it+2 is requested into p0
+        p0 = fetch_x(Xp, ldx, tbeg + (it + 2) * TT, tend, tid);
+        heads_tile(Xs[0], dYs, rhi, rlo, accG, lsum, scale, tbeg + it * TT, tend, wave, lrow, lk);
+        stash_x(Xs[1], tid, p1);
+        __syncthreads();
+        if (it + 1 < ntiles) {
+            p1 = fetch_x(Xp, ldx, tbeg + (it + 3) * TT, tend, tid);
+            heads_tile(Xs[1], dYs, rhi, rlo, accG, lsum, scale, tbeg + (it + 1) * TT, tend, wave, lrow, lk);
+        }
+        stash_x(Xs[0], tid, p0);
+        __syncthreads();
+    }
+
+    float* Gp = Gpart + ((long)prob * splits + split) * (HN * HN);
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            Gp[(32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3)) * HN + jb * 32 + lrow] = accG[jb][v];
+    lsum = wave_total(lsum);
+    if (lane == 0) wsum[wave] = lsum;
+    __syncthreads();
+    if (tid == 0)
+        lpart[(long)prob * splits + split] = (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3];
+}
+
+// grid (16, b): G[p] = sum_s Gpart[p][s];  loss[p] = scale * sum_s lpart[p][s]
+__global__ __launch_bounds__(256) void heads_reduce_kernel(const float* __restrict__ Gpart, const double* __restrict__ lpart,
+                                                           int splits, float scale, float* __restrict__ G, long ldg,
+                                                           long sg, float* __restrict__ loss, unsigned* flags) {
+    const int prob = blockIdx.y;
+    const int e = (blockIdx.x * 256 + threadIdx.x) * 4;   // 16 x 256 x 4 = 128 x 128
+    const float* src = Gpart + (long)prob * splits * (HN * HN) + e;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < splits; ++s) {
+        const float4 v = *reinterpret_cast<const float4*>(src + (long)s * (HN * HN));
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *reinterpret_cast<float4*>(G + (long)prob * sg + (long)(e >> 7) * ldg + (e & (HN - 1))) = acc;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        double t = 0.0;
+        for (int s = 0; s < splits; ++s) t += lpart[(long)prob * splits + s];
+        const float Lf = (float)((double)scale * t);
+        loss[prob] = Lf;
+        if (!(fabsf(Lf) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_heads_qr(int b, const float* Z, long ldz, long sz, float* R, long ldr, long sr, float* U, long ldu,
+                           long su, unsigned* flags, hipStream_t s) {
+    if (b < 1) return hipSuccess;
+    hipLaunchKernelGGL(heads_qr_kernel, dim3(b), dim3(256), 0, s, Z, ldz, sz, R, ldr, sr, U, ldu, su, flags);
+    return hipGetLastError();
+}
+
+int heads_splits(int T) { return (T + kHeadsChunk - 1) / kHeadsChunk; }
+
+hipError_t launch_heads_rlg(int b, int T, const bf16_t* X, long ldx, long sx, const float* R, long ldr, long sr,
+                            float scale, float* Gpart, double* lpart, float* G, long ldg, long sg, float* loss,
+                            unsigned* flags, hipStream_t s) {
+    if (b < 1) return hipSuccess;
+    const int splits = heads_splits(T);
+    hipLaunchKernelGGL(heads_rlg_kernel, dim3(splits, b), dim3(256), 0, s, X, ldx, sx, T, R, ldr, sr, scale, Gpart,
+                       lpart, kHeadsChunk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(heads_reduce_kernel, dim3(16, b), dim3(256), 0, s, Gpart, lpart, splits, scale, G, ldg, sg, loss,
+                       flags);
+    return hipGetLastError();
+}
+
+}  // namespace dq

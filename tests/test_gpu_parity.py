@@ -621,6 +621,141 @@ def test_batched_heads_like(ctx):
     assert rel(Z2.cpu().numpy(), Z1.cpu().numpy()) < 1e-6
 
 
+# ----------------------------------------------------------------------------------- batched 128 x 128 path
+def padded3(b, rows, cols, ld, dtype=torch.float32):
+    buf = torch.full((b, rows, ld), float("nan"), dtype=dtype, device="cuda")
+    return buf, buf[:, :, :cols]
+
+
+def heads_latents(b, seed):
+    """Gaussian latents, one near-orthogonal one (what a calibration run holds after its first steps) and one with
+    columns of very different scale."""
+    g = rng(seed)
+    Z = g.standard_normal((b, 128, 128))
+    if b > 1:
+        Z[1] = np.linalg.qr(Z[1])[0] + 0.01 * g.standard_normal((128, 128))
+    if b > 2:
+        Z[2] *= np.exp(3.0 * g.standard_normal(128))[None, :]
+    return Z.astype(np.float32)
+
+
+@pytest.mark.parametrize("ld", [128, 136])
+def test_heads_qr_batched(ctx, ld):
+    b, n = 5, 128
+    Z = heads_latents(b, 7100)
+    _, Zd = padded3(b, n, n, ld); Zd.copy_(dev(Z))
+    _, Rd = padded3(b, n, n, ld)
+    _, Ud = padded3(b, n, n, ld)
+    ctx.dq_qr_orth(Zd, Rd, Ud)
+    R, U = Rd.cpu().numpy(), Ud.cpu().numpy()
+    for i in range(b):
+        Ro, Uo = orc.qr_orth(Z[i])
+        assert np.abs(R[i].astype(np.float64).T @ R[i] - np.eye(n)).max() <= 1e-5
+        assert np.all(np.tril(U[i], -1) == 0.0) and np.all(np.diag(U[i]) > 0.0)
+        assert rel(R[i].astype(np.float64) @ U[i], Z[i]) < 1e-5
+        assert rel(U[i], Uo) < 1e-4
+        assert rel(R[i], Ro) < max(1e-4, 2e-7 * np.linalg.cond(Z[i].astype(np.float64)))
+    # R alone: same values
+    _, R2 = padded3(b, n, n, ld)
+    ctx.dq_qr_orth(Zd, R2, None)
+    assert torch.equal(R2, Rd)
+    assert ctx.dq_device_flags() == 0
+    # closed forms: the identity and a diagonal with mixed signs
+    D = np.diag(np.where(np.arange(n) % 3 == 0, -2.0, 0.5)).astype(np.float32)
+    Zc = dev(np.stack([np.eye(n, dtype=np.float32), D]))
+    Rc = torch.empty_like(Zc); Uc = torch.empty_like(Zc)
+    ctx.dq_qr_orth(Zc, Rc, Uc)
+    assert torch.equal(Rc[0].cpu(), torch.eye(n)) and torch.equal(Uc[0].cpu(), torch.eye(n))
+    assert np.array_equal(Rc[1].cpu().numpy(), np.sign(D)) and np.array_equal(Uc[1].cpu().numpy(), np.abs(D))
+    # a zero column: flagged, no fault
+    Zs = Z[:1].copy(); Zs[0][:, 40] = 0.0
+    ctx.dq_qr_orth(dev(Zs), Rc[:1], Uc[:1])
+    assert ctx.dq_device_flags() & B.DQ_FLAG_SINGULAR
+
+
+@pytest.mark.parametrize("T,mode", [(2048 + 2048 + 300, B.DQ_REDUCE_TOKEN_MEAN), (70, B.DQ_REDUCE_SUM),
+                                    (64, B.DQ_REDUCE_TOKEN_MEAN)])
+def test_heads_rotate_loss_grad_fused(ctx, T, mode):
+    """The fused kernel (Y and dY stay on chip) against the oracle; T spans several workgroup chunks and a ragged
+    last tile."""
+    b, n = 3, 128
+    cfg = synth.scaled_config("heads", b=b, T=T)
+    inp = synth.make_inputs(cfg, seed=9)
+    X = inp["X"]
+    Rs = np.stack([orc.qr_orth(z)[0] for z in heads_latents(b, 7200)]).astype(np.float32)
+    _, Xd = padded3(b, T, n, 136, torch.bfloat16); Xd.copy_(dev(X, torch.bfloat16))
+    Rd = dev(Rs)
+    _, Gd = padded3(b, n, n, 132)
+    loss = torch.zeros(b, device="cuda")
+    ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, mode, loss, Gd)
+    G = Gd.cpu().numpy()
+    for i in range(b):
+        lo, Go, _, _ = orc.rotate_loss_grad(X[i], Rs[i], reduce="mean" if mode == B.DQ_REDUCE_TOKEN_MEAN else "sum")
+        assert abs(loss[i].item() - lo) <= 1e-4 * lo
+        assert rel(G[i], Go) < 2e-2
+    # the unfused route (taken when Y and dY are requested) forms the same quantities kernel by kernel
+    _, G2 = padded3(b, n, n, 132)
+    Yd = torch.empty((b, T, n), device="cuda")
+    dYd = torch.empty((b, T, n), device="cuda", dtype=torch.bfloat16)
+    loss2 = torch.zeros(b, device="cuda")
+    ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, mode, loss2, G2, Yd, dYd)
+    assert torch.allclose(loss2, loss, rtol=1e-5, atol=0)
+    assert rel(G2.cpu().numpy(), G) < 1e-3
+    assert ctx.dq_device_flags() == 0
+
+
+def test_heads_backward_batched(ctx):
+    b, n = 4, 128
+    Z = heads_latents(b, 7300)
+    g = rng(7301)
+    G = g.standard_normal((b, n, n)).astype(np.float32)
+    RU = [orc.qr_orth(z) for z in Z]
+    R32 = np.stack([r for r, _ in RU]).astype(np.float32)
+    U32 = np.stack([u for _, u in RU]).astype(np.float32)
+    _, dZd = padded3(b, n, n, 132)
+    ctx.dq_qr_backward(dev(R32), dev(U32), dev(G), dZd)
+    dZ = dZd.cpu().numpy()
+    for i in range(b):
+        assert rel(dZ[i], orc.qr_backward(R32[i], U32[i], G[i])) < 1e-4
+    assert ctx.dq_device_flags() == 0
+
+
+def test_heads_full_size_step():
+    """The heads workload at its full size (64 problems, T = 16384): problems 0, 31 and 63 against the oracle,
+    every problem for orthogonality, and the Adam step against the SGD step's gradient."""
+    cfg = synth.CONFIGS["heads"]
+    inp = synth.make_inputs(cfg)
+    X, Z0 = inp["X"], inp["Z0"]
+    c = B.Context()
+    try:
+        c.ensure_workspace(cfg.b, cfg.n, cfg.T, B.DQ_BF16)
+        Xd = dev(X, torch.bfloat16)
+        Zd = dev(Z0.copy())
+        loss = torch.zeros(cfg.b, device="cuda")
+        Rd = torch.empty((cfg.b, cfg.n, cfg.n), device="cuda")
+        c.dq_calib_step(Xd, B.DQ_BF16, Zd, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss, Rd)
+        R = Rd.cpu().numpy().astype(np.float64)
+        Zn = Zd.cpu().numpy().astype(np.float64)
+        assert np.abs(np.einsum("bki,bkj->bij", R, R) - np.eye(cfg.n)).max() <= 1e-5
+        for i in (0, 31, 63):
+            out = orc.calib_step(X[i], Z0[i], cfg.lr)
+            assert abs(loss[i].item() - out["loss"]) <= 1e-4 * out["loss"]
+            assert rel(Rd[i].cpu().numpy(), out["R"]) < 1e-4
+            assert rel((Z0[i].astype(np.float64) - Zn[i]) / cfg.lr, out["dZ"]) < 2e-2
+        # Adam from zero state, first step: Z moves by lr * sign(dZ) (up to eps), the moments hold the gradient
+        Za = dev(Z0.copy())
+        m = torch.zeros_like(Za); v = torch.zeros_like(Za)
+        la = torch.zeros(cfg.b, device="cuda")
+        c.dq_calib_step_adam(Xd, B.DQ_BF16, Za, m, v, 1, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, la)
+        assert torch.allclose(la, loss, rtol=1e-6, atol=0)
+        dZ_sgd = (Z0.astype(np.float64) - Zn) / cfg.lr
+        assert rel(m.cpu().numpy().astype(np.float64) / np.float64(np.float32(1.0) - np.float32(0.9)), dZ_sgd) < 2e-2
+        assert c.dq_device_flags() == 0
+    finally:
+        torch.cuda.synchronize()
+        c.close()
+
+
 # ----------------------------------------------------------------------------------- error paths
 def test_errors_have_no_effect(ctx):
     n = 64

@@ -46,8 +46,12 @@ def test_workspace_bytes_rules(lib):
     big = B.workspace_bytes(1, 4096, 8192, B.DQ_BF16)
     assert 0 < small < big
     assert small % 256 == 0
-    # batches run one after another: the workspace does not grow with b
-    assert B.workspace_bytes(64, 128, 16384, B.DQ_BF16) == B.workspace_bytes(1, 128, 16384, B.DQ_BF16)
+    # batches run one after another: the workspace does not grow with b ...
+    assert B.workspace_bytes(64, 256, 16384, B.DQ_BF16) == B.workspace_bytes(1, 256, 16384, B.DQ_BF16)
+    # ... except for 128 x 128 rotations, whose problems all run in the same launches: 7 matrices and
+    # ceil(T / 2048) partial gradients per problem
+    w1, w64 = B.workspace_bytes(1, 128, 16384, B.DQ_BF16), B.workspace_bytes(64, 128, 16384, B.DQ_BF16)
+    assert w1 < w64 and w64 - w1 == 63 * (7 + 8) * 128 * 128 * 4 + (64 * 8 * 8 - 256)
     # the 70B-shaped problem fits comfortably in one GPU's HBM
     assert B.workspace_bytes(1, 8192, 16384, B.DQ_BF16) < 8 * 2 ** 30
     out = ctypes.c_size_t(0)
