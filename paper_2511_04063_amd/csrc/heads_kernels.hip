@@ -9,6 +9,7 @@
 //   * heads_reduce_kernel: sums the per-workgroup partial G and loss.
 // The derivative through the QR runs through the batched forms of the general kernels.
 #include "dq_internal.h"
+#include "dq_wave.h"
 
 namespace dq {
 namespace {
@@ -16,9 +17,10 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int HN = kHeadDim;     // matrix size of this path
-constexpr int HS = HN + 1;       // LDS row stride of the fp32 matrices (conflict-free row and column walks)
 
 __device__ __forceinline__ float wave_total(float v) {
 #pragma unroll
@@ -34,80 +36,145 @@ __device__ __forceinline__ uint32_t to_bf16_rne(float f) {
 }
 
 // ------------------------------------------------------------------------------------------------ S1 + S2
-// Reflector convention as in the panel kernels: H = I - tau v v^T, v[j] = 1, beta = -sign(alpha) ||x||,
-// tau = (beta - alpha) / beta, v[i] = x[i] / (alpha - beta); a column that is already zero below the diagonal gets
-// H = I.  Threads 0..127 own one column of A each (rows of the reflector applied from the left), threads 128..255
-// one row of Q each (the same reflector applied from the right); every wavefront forms the column norm itself, so a
-// step needs one barrier.
+// Alg. 2 with the unnormalised reflector vector: for column j, x = A[j:, j], beta = -sign(x_0) ||x||,
+// u = x - beta e_0, H = I - gamma u u^T with gamma = 2 / u^T u = -1 / (beta u_0)  (the same reflection as the
+// paper's normalised v); a column that is already zero below the diagonal gets H = I.
+// Threads 0..127 hold one column of A each, threads 128..255 one row of Q each, in registers; both apply
+// x <- x - gamma (u . x) u, the columns only for c > j.  The owner of column j + 1 publishes it in LDS at the end of
+// step j (entries above the diagonal written as zero), so a step needs one barrier; every wavefront forms the column
+// norm itself.  Rows are handled in blocks of 16: blocks above the diagonal block are skipped, the diagonal block
+// substitutes u_0 for the raw pivot.  gamma is formed as 2 / (sigma + u_0^2).
+constexpr int QB = 16;            // rows per block
+constexpr int NQB = HN / QB;
+
+__device__ __forceinline__ void publish_column(float* cb, const float (&x)[HN], int j) {
+    const int jb = j / QB;
+#pragma unroll
+    for (int blk = 0; blk < NQB; ++blk) {
+        if (blk > jb) {
+#pragma unroll
+            for (int k = 0; k < QB; k += 4)
+                *reinterpret_cast<float4*>(cb + blk * QB + k) =
+                    make_float4(x[blk * QB + k], x[blk * QB + k + 1], x[blk * QB + k + 2], x[blk * QB + k + 3]);
+        } else if (blk == jb) {
+#pragma unroll
+            for (int k = 0; k < QB; k += 4) {
+                const int i = blk * QB + k;
+                *reinterpret_cast<float4*>(cb + i) =
+                    make_float4(i >= j ? x[i] : 0.f, i + 1 >= j ? x[i + 1] : 0.f, i + 2 >= j ? x[i + 2] : 0.f,
+                                i + 3 >= j ? x[i + 3] : 0.f);
+            }
+        }
+    }
+}
+
+// x <- x - gamma (u . x) u over rows >= j, with u read from cb (raw column j: u_j is substituted for the pivot);
+// JB = j / 16 is a template parameter so that every register index is static and the code of a step is straight-line.
+template <int JB>
+__device__ __forceinline__ void reflect_column(const float* cb, float (&x)[HN], int j, float uj, float gamma) {
+    float4 ub[QB / 4];
+#pragma unroll
+    for (int k = 0; k < QB / 4; ++k) {
+        const int i = JB * QB + 4 * k;
+        const float4 u = *reinterpret_cast<const float4*>(cb + i);
+        ub[k] = make_float4(i == j ? uj : u.x, i + 1 == j ? uj : u.y, i + 2 == j ? uj : u.z, i + 3 == j ? uj : u.w);
+    }
+    float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+    for (int k = 0; k < QB / 4; ++k) {
+        const int i = JB * QB + 4 * k;
+        d0 += ub[k].x * x[i] + ub[k].y * x[i + 1];
+        d1 += ub[k].z * x[i + 2] + ub[k].w * x[i + 3];
+    }
+#pragma unroll
+    for (int i = (JB + 1) * QB; i < HN; i += 4) {
+        const float4 u = *reinterpret_cast<const float4*>(cb + i);
+        d0 += u.x * x[i] + u.y * x[i + 1];
+        d1 += u.z * x[i + 2] + u.w * x[i + 3];
+    }
+    const float f = gamma * (d0 + d1);
+#pragma unroll
+    for (int k = 0; k < QB / 4; ++k) {
+        const int i = JB * QB + 4 * k;
+        x[i] -= f * ub[k].x; x[i + 1] -= f * ub[k].y; x[i + 2] -= f * ub[k].z; x[i + 3] -= f * ub[k].w;
+    }
+#pragma unroll
+    for (int i = (JB + 1) * QB; i < HN; i += 4) {
+        const float4 u = *reinterpret_cast<const float4*>(cb + i);
+        x[i] -= f * u.x; x[i + 1] -= f * u.y; x[i + 2] -= f * u.z; x[i + 3] -= f * u.w;
+    }
+}
+
 __global__ __launch_bounds__(256) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
                                                        float* __restrict__ R, long ldr, long sr,
                                                        float* __restrict__ U, long ldu, long su, unsigned* flags) {
-    __shared__ float As[HN * HS];
-    __shared__ float Qs[HN * HS];
+    __shared__ __attribute__((aligned(16))) float cbuf[2][HN];
+    __shared__ __attribute__((aligned(16))) float sgn[HN];
     const int tid = threadIdx.x, lane = tid & 63;
+    const bool is_col = tid < HN;              // uniform per wavefront
+    const int idx = is_col ? tid : tid - HN;   // column of A / row of Q held by this thread
     const float* Zp = Z + (long)blockIdx.x * sz;
-    for (int e = tid; e < HN * HN / 4; e += 256) {
-        const int r = e >> 5, c = (e & 31) << 2;
-        const float4 v = *reinterpret_cast<const float4*>(Zp + (long)r * ldz + c);
-        float* a = As + r * HS + c;
-        a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w;
-        float* q = Qs + r * HS + c;
+    float x[HN];
+    if (is_col) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) q[k] = (r == c + k) ? 1.f : 0.f;
+        for (int i = 0; i < HN; ++i) x[i] = Zp[(long)i * ldz + idx];
+    } else {
+#pragma unroll
+        for (int i = 0; i < HN; ++i) x[i] = (i == idx) ? 1.f : 0.f;
     }
+    float mydiag = 0.f;
+    if (tid == 0) publish_column(cbuf[0], x, 0);
     __syncthreads();
     for (int j = 0; j < HN; ++j) {
-        float s = 0.f;
-        for (int i = j + 1 + lane; i < HN; i += 64) {
-            const float x = As[i * HS + j];
-            s += x * x;
+        const float* cb = cbuf[j & 1];
+        float sv[1];
+        {
+            const float a0 = cb[lane], a1 = cb[lane + 64];
+            sv[0] = (lane > j ? a0 * a0 : 0.f) + (lane + 64 > j ? a1 * a1 : 0.f);
         }
-        s = wave_total(s);
-        const float alpha = As[j * HS + j];
-        float tau = 0.f, vs = 0.f, beta = alpha;
+        const float alpha = cb[j];
+        wave_reduce_multi<1>(sv, lane);
+        const float s = sv[0];
+        float beta = alpha;
         if (s != 0.f) {
             const float nrm = sqrtf(alpha * alpha + s);
             beta = alpha >= 0.f ? -nrm : nrm;
-            tau = (beta - alpha) / beta;
-            vs = 1.f / (alpha - beta);
-        }
-        if (tau != 0.f) {
-            if (tid < HN) {
-                const int c = tid;
-                if (c > j) {
-                    float dot = As[j * HS + c];
-                    for (int i = j + 1; i < HN; ++i) dot += (As[i * HS + j] * vs) * As[i * HS + c];
-                    const float f = tau * dot;
-                    As[j * HS + c] -= f;
-                    for (int i = j + 1; i < HN; ++i) As[i * HS + c] -= f * (As[i * HS + j] * vs);
+            const float uj = alpha - beta;
+            // 2 / u^T u from the vector that is applied, so that H is orthogonal whatever the rounding of beta
+            const float gamma = 2.f * __builtin_amdgcn_rcpf(s + uj * uj);
+            if (!is_col || idx > j) {
+                switch (j / QB) {
+                    case 0: reflect_column<0>(cb, x, j, uj, gamma); break;
+                    case 1: reflect_column<1>(cb, x, j, uj, gamma); break;
+                    case 2: reflect_column<2>(cb, x, j, uj, gamma); break;
+                    case 3: reflect_column<3>(cb, x, j, uj, gamma); break;
+                    case 4: reflect_column<4>(cb, x, j, uj, gamma); break;
+                    case 5: reflect_column<5>(cb, x, j, uj, gamma); break;
+                    case 6: reflect_column<6>(cb, x, j, uj, gamma); break;
+                    default: reflect_column<7>(cb, x, j, uj, gamma); break;
                 }
-            } else {
-                const int r = tid - HN;
-                float dot = Qs[r * HS + j];
-                for (int i = j + 1; i < HN; ++i) dot += Qs[r * HS + i] * (As[i * HS + j] * vs);
-                const float f = tau * dot;
-                Qs[r * HS + j] -= f;
-                for (int i = j + 1; i < HN; ++i) Qs[r * HS + i] -= f * (As[i * HS + j] * vs);
             }
         }
+        if (is_col && idx == j) mydiag = beta;
+        if (tid == 0) sgn[j] = beta >= 0.f ? 1.f : -1.f;
+        if (is_col && idx == j + 1) publish_column(cbuf[(j + 1) & 1], x, j + 1);
         __syncthreads();
-        if (tid == 0) As[j * HS + j] = beta;   // nothing reads this entry again before the loop ends
     }
-    __syncthreads();
-    if (tid < HN) {
-        const float d = As[tid * HS + tid];
-        if (!(fabsf(d) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
-        else if (d == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
-    }
-    float* Rp = R + (long)blockIdx.x * sr;
-    float* Up = U != nullptr ? U + (long)blockIdx.x * su : nullptr;
-    for (int e = tid; e < HN * HN; e += 256) {
-        const int r = e >> 7, c = e & (HN - 1);
-        const float sc = As[c * HS + c] >= 0.f ? 1.f : -1.f;
-        Rp[(long)r * ldr + c] = Qs[r * HS + c] * sc;
-        if (Up != nullptr) {
-            const float sr_ = As[r * HS + r] >= 0.f ? 1.f : -1.f;
-            Up[(long)r * ldu + c] = (c >= r) ? sr_ * As[r * HS + c] : 0.f;
+    if (is_col) {
+        if (!(fabsf(mydiag) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+        else if (mydiag == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        if (U != nullptr) {   // U[i][c] = s_i A[i][c] above the diagonal, |diag| on it
+            float* Up = U + (long)blockIdx.x * su;
+#pragma unroll
+            for (int i = 0; i < HN; ++i)
+                Up[(long)i * ldu + idx] = i < idx ? sgn[i] * x[i] : (i == idx ? fabsf(mydiag) : 0.f);
+        }
+    } else {                  // R[r][c] = s_c Q[r][c]
+        float* Rp = R + (long)blockIdx.x * sr + (long)idx * ldr;
+#pragma unroll
+        for (int c = 0; c < HN; c += 4) {
+            const float4 sg = *reinterpret_cast<const float4*>(sgn + c);
+            *reinterpret_cast<float4*>(Rp + c) = make_float4(x[c] * sg.x, x[c + 1] * sg.y, x[c + 2] * sg.z, x[c + 3] * sg.w);
         }
     }
 }
@@ -144,8 +211,7 @@ __device__ __forceinline__ void stash_x(bf16_t* Xs, int tid, const XRegs r) {
 // Matrix-core operand layout (32x32x16 bf16): lane l supplies row/column (l & 31) and the 8 consecutive reduction
 // indices 8 (l >> 5) ..; the 32 x 32 result holds row 8 (v >> 2) + 4 (l >> 5) + (v & 3), column (l & 31) in register v.
 __device__ __forceinline__ void heads_tile(const bf16_t* Xs, bf16_t* dYs, const bf16x8 (&rhi)[8], const bf16x8 (&rlo)[8],
-                                           f32x16 (&accG)[4], float& lsum, float scale, int tok_base, int tend,
-                                           int wave, int lrow, int lk) {
+                                           f32x16 (&accG)[4], float& lsum, float scale, int wave, int lrow, int lk) {
     f32x16 y0, y1;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { y0[v] = 0.f; y1[v] = 0.f; }
@@ -164,16 +230,19 @@ __device__ __forceinline__ void heads_tile(const bf16_t* Xs, bf16_t* dYs, const 
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int tok0 = i * 32 + 8 * g + 4 * lk;
-            u32x4 h;
+            float d[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const float y = i == 0 ? y0[4 * g + q] : y1[4 * g + q];
                 const float ex = __expf(-fabsf(y));
-                if (tok_base + tok0 + q < tend) lsum += ex;
+                lsum += ex;   // rows past the end of the chunk hold y = 0 and add exactly 1 each: removed by the caller
                 const float sg = (y > 0.f) ? -scale : ((y < 0.f) ? scale : 0.f);
-                h[q] = to_bf16_rne(sg * ex);
+                d[q] = sg * ex;
             }
-            *reinterpret_cast<uint2*>(dYs + j * DLD + tok0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            const f32x2 d01 = {d[0], d[1]}, d23 = {d[2], d[3]};
+            const bf16x2 b01 = __builtin_convertvector(d01, bf16x2), b23 = __builtin_convertvector(d23, bf16x2);
+            *reinterpret_cast<uint2*>(dYs + j * DLD + tok0) =
+                make_uint2(__builtin_bit_cast(uint32_t, b01), __builtin_bit_cast(uint32_t, b23));
         }
     }
     __syncthreads();
@@ -198,7 +267,7 @@ __device__ __forceinline__ void heads_tile(const bf16_t* Xs, bf16_t* dYs, const 
 
 // grid (splits, b): workgroup (s, p) handles tokens [s * chunk, min(T, (s+1) * chunk)) of problem p and writes its
 // partial G to Gpart[(p * splits + s) * 128 * 128 ..] and its partial sum of exp(-|y|) to lpart[p * splits + s].
-__global__ __launch_bounds__(256) void heads_rlg_kernel(const bf16_t* __restrict__ X, long ldx, long sx, int T,
+__global__ __launch_bounds__(256, 2) void heads_rlg_kernel(const bf16_t* __restrict__ X, long ldx, long sx, int T,
                                                         const float* __restrict__ R, long ldr, long sr, float scale,
                                                         float* __restrict__ Gpart, double* __restrict__ lpart,
                                                         int chunk) {
@@ -249,12 +318,12 @@ __global__ __launch_bounds__(256) void heads_rlg_kernel(const bf16_t* __restrict
     for (int it = 0; it < ntiles; it += 2) {
         // tile `it` is in Xs[0], tile it+1 in p1; tile it+2 is requested into p0
         p0 = fetch_x(Xp, ldx, tbeg + (it + 2) * TT, tend, tid);
-        heads_tile(Xs[0], dYs, rhi, rlo, accG, lsum, scale, tbeg + it * TT, tend, wave, lrow, lk);
+        heads_tile(Xs[0], dYs, rhi, rlo, accG, lsum, scale, wave, lrow, lk);
         stash_x(Xs[1], tid, p1);
         __syncthreads();
         if (it + 1 < ntiles) {
             p1 = fetch_x(Xp, ldx, tbeg + (it + 3) * TT, tend, tid);
-            heads_tile(Xs[1], dYs, rhi, rlo, accG, lsum, scale, tbeg + (it + 1) * TT, tend, wave, lrow, lk);
+            heads_tile(Xs[1], dYs, rhi, rlo, accG, lsum, scale, wave, lrow, lk);
         }
         stash_x(Xs[0], tid, p0);
         __syncthreads();
@@ -269,8 +338,12 @@ __global__ __launch_bounds__(256) void heads_rlg_kernel(const bf16_t* __restrict
     lsum = wave_total(lsum);
     if (lane == 0) wsum[wave] = lsum;
     __syncthreads();
-    if (tid == 0)
-        lpart[(long)prob * splits + split] = (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3];
+    if (tid == 0) {
+        // the zero rows that pad the last tile contributed exp(0) = 1 per element
+        const double pad = (double)(ntiles * TT - (tend > tbeg ? tend - tbeg : 0)) * HN;
+        lpart[(long)prob * splits + split] =
+            (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3] - pad;
+    }
 }
 
 // grid (16, b): G[p] = sum_s Gpart[p][s];  loss[p] = scale * sum_s lpart[p][s]
