@@ -11,6 +11,10 @@
 #include "dq_internal.h"
 #include "dq_wave.h"
 
+#ifndef DQ_HEADS_QR_SPLIT
+#define DQ_HEADS_QR_SPLIT 2
+#endif
+
 namespace dq {
 namespace {
 
@@ -37,93 +41,97 @@ __device__ __forceinline__ uint32_t to_bf16_rne(float f) {
 
 // ------------------------------------------------------------------------------------------------ S1 + S2
 // Alg. 2 with the unnormalised reflector vector: for column j, x = A[j:, j], beta = -sign(x_0) ||x||,
-// u = x - beta e_0, H = I - gamma u u^T with gamma = 2 / u^T u = -1 / (beta u_0)  (the same reflection as the
-// paper's normalised v); a column that is already zero below the diagonal gets H = I.
-// Threads 0..127 hold one column of A each, threads 128..255 one row of Q each, in registers; both apply
-// x <- x - gamma (u . x) u, the columns only for c > j.  The owner of column j + 1 publishes it in LDS at the end of
-// step j (entries above the diagonal written as zero), so a step needs one barrier; every wavefront forms the column
-// norm itself.  Rows are handled in blocks of 16: blocks above the diagonal block are skipped, the diagonal block
-// substitutes u_0 for the raw pivot.  gamma is formed as 2 / (sigma + u_0^2).
-constexpr int QB = 16;            // rows per block
-constexpr int NQB = HN / QB;
+// u = x - beta e_0, H = I - gamma u u^T with gamma = 2 / u^T u  (the same reflection as the paper's normalised v);
+// a column that is already zero below the diagonal gets H = I.
+// Every column of A and every row of Q lives in the registers of QS adjacent lanes (lane part h holds the 4-row
+// groups g with g % QS == h); both kinds apply x <- x - gamma (u . x) u, the columns only for c > j, the partial dot
+// products of the QS lanes meeting through DPP.  The owners of column j + 1 publish it in LDS at the end of step j, so
+// a step needs one barrier; every wavefront forms the column norm itself.  Rows are handled in blocks of 16: blocks
+// above the diagonal block are skipped (the block index is a template parameter, so register indices are static and
+// a step runs straight-line code), the diagonal block substitutes u_0 for the raw pivot and zero above it.
+constexpr int QS = DQ_HEADS_QR_SPLIT;   // lanes per column / row
+constexpr int QB = 16;                  // rows per block
+constexpr int NG = HN / 4 / QS;         // 4-row groups held by a thread
+constexpr int GPB = QB / 4 / QS;        // of which per block
+static_assert(QS == 2 || QS == 4, "a block of 16 rows must hold a whole number of groups per lane");
 
-__device__ __forceinline__ void publish_column(float* cb, const float (&x)[HN], int j) {
-    const int jb = j / QB;
+// rows of this thread's k-th group: 4 * (k * QS + h) .. + 3
+template <int JB>
+__device__ __forceinline__ void publish_from(float* cb, const float (&x)[4 * NG], int h, int j) {
 #pragma unroll
-    for (int blk = 0; blk < NQB; ++blk) {
-        if (blk > jb) {
-#pragma unroll
-            for (int k = 0; k < QB; k += 4)
-                *reinterpret_cast<float4*>(cb + blk * QB + k) =
-                    make_float4(x[blk * QB + k], x[blk * QB + k + 1], x[blk * QB + k + 2], x[blk * QB + k + 3]);
-        } else if (blk == jb) {
-#pragma unroll
-            for (int k = 0; k < QB; k += 4) {
-                const int i = blk * QB + k;
-                *reinterpret_cast<float4*>(cb + i) =
-                    make_float4(i >= j ? x[i] : 0.f, i + 1 >= j ? x[i + 1] : 0.f, i + 2 >= j ? x[i + 2] : 0.f,
-                                i + 3 >= j ? x[i + 3] : 0.f);
-            }
+    for (int k = JB * GPB; k < NG; ++k) {
+        const int i = 4 * (k * QS + h);
+        float4 v = make_float4(x[4 * k], x[4 * k + 1], x[4 * k + 2], x[4 * k + 3]);
+        if (k < (JB + 1) * GPB) {   // diagonal block: entries above the diagonal are published as zero
+            v.x = i >= j ? v.x : 0.f; v.y = i + 1 >= j ? v.y : 0.f; v.z = i + 2 >= j ? v.z : 0.f; v.w = i + 3 >= j ? v.w : 0.f;
         }
+        *reinterpret_cast<float4*>(cb + i) = v;
     }
 }
 
-// x <- x - gamma (u . x) u over rows >= j, with u read from cb (raw column j: u_j is substituted for the pivot);
-// JB = j / 16 is a template parameter so that every register index is static and the code of a step is straight-line.
 template <int JB>
-__device__ __forceinline__ void reflect_column(const float* cb, float (&x)[HN], int j, float uj, float gamma) {
-    float4 ub[QB / 4];
+__device__ __forceinline__ void reflect_from(const float* cb, float (&x)[4 * NG], int h, int j, float uj, float gamma) {
+    float4 u[NG - JB * GPB];
 #pragma unroll
-    for (int k = 0; k < QB / 4; ++k) {
-        const int i = JB * QB + 4 * k;
-        const float4 u = *reinterpret_cast<const float4*>(cb + i);
-        ub[k] = make_float4(i == j ? uj : u.x, i + 1 == j ? uj : u.y, i + 2 == j ? uj : u.z, i + 3 == j ? uj : u.w);
+    for (int k = JB * GPB; k < NG; ++k) {
+        const int i = 4 * (k * QS + h);
+        float4 v = *reinterpret_cast<const float4*>(cb + i);
+        if (k < (JB + 1) * GPB) {
+            v.x = i == j ? uj : v.x; v.y = i + 1 == j ? uj : v.y; v.z = i + 2 == j ? uj : v.z; v.w = i + 3 == j ? uj : v.w;
+        }
+        u[k - JB * GPB] = v;
     }
     float d0 = 0.f, d1 = 0.f;
 #pragma unroll
-    for (int k = 0; k < QB / 4; ++k) {
-        const int i = JB * QB + 4 * k;
-        d0 += ub[k].x * x[i] + ub[k].y * x[i + 1];
-        d1 += ub[k].z * x[i + 2] + ub[k].w * x[i + 3];
+    for (int k = JB * GPB; k < NG; ++k) {
+        const float4 v = u[k - JB * GPB];
+        d0 += v.x * x[4 * k] + v.y * x[4 * k + 1];
+        d1 += v.z * x[4 * k + 2] + v.w * x[4 * k + 3];
     }
+    float d = d0 + d1;
+    d += lane_xor<1>(d);
+    if (QS == 4) d += lane_xor<2>(d);
+    const float f = gamma * d;
 #pragma unroll
-    for (int i = (JB + 1) * QB; i < HN; i += 4) {
-        const float4 u = *reinterpret_cast<const float4*>(cb + i);
-        d0 += u.x * x[i] + u.y * x[i + 1];
-        d1 += u.z * x[i + 2] + u.w * x[i + 3];
-    }
-    const float f = gamma * (d0 + d1);
-#pragma unroll
-    for (int k = 0; k < QB / 4; ++k) {
-        const int i = JB * QB + 4 * k;
-        x[i] -= f * ub[k].x; x[i + 1] -= f * ub[k].y; x[i + 2] -= f * ub[k].z; x[i + 3] -= f * ub[k].w;
-    }
-#pragma unroll
-    for (int i = (JB + 1) * QB; i < HN; i += 4) {
-        const float4 u = *reinterpret_cast<const float4*>(cb + i);
-        x[i] -= f * u.x; x[i + 1] -= f * u.y; x[i + 2] -= f * u.z; x[i + 3] -= f * u.w;
+    for (int k = JB * GPB; k < NG; ++k) {
+        const float4 v = u[k - JB * GPB];
+        x[4 * k] -= f * v.x; x[4 * k + 1] -= f * v.y; x[4 * k + 2] -= f * v.z; x[4 * k + 3] -= f * v.w;
     }
 }
 
-__global__ __launch_bounds__(256) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
-                                                       float* __restrict__ R, long ldr, long sr,
-                                                       float* __restrict__ U, long ldu, long su, unsigned* flags) {
+#define DQ_BLOCK_SWITCH(jb, CALL)                                                                  \
+    switch (jb) {                                                                                  \
+        case 0: CALL(0); break;                                                                    \
+        case 1: CALL(1); break;                                                                    \
+        case 2: CALL(2); break;                                                                    \
+        case 3: CALL(3); break;                                                                    \
+        case 4: CALL(4); break;                                                                    \
+        case 5: CALL(5); break;                                                                    \
+        case 6: CALL(6); break;                                                                    \
+        default: CALL(7); break;                                                                   \
+    }
+
+__global__ __launch_bounds__(2 * HN * QS) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
+                                                               float* __restrict__ R, long ldr, long sr,
+                                                               float* __restrict__ U, long ldu, long su,
+                                                               unsigned* flags) {
     __shared__ __attribute__((aligned(16))) float cbuf[2][HN];
     __shared__ __attribute__((aligned(16))) float sgn[HN];
     const int tid = threadIdx.x, lane = tid & 63;
-    const bool is_col = tid < HN;              // uniform per wavefront
-    const int idx = is_col ? tid : tid - HN;   // column of A / row of Q held by this thread
+    const bool is_col = tid < HN * QS;                       // uniform per wavefront
+    const int idx = (is_col ? tid : tid - HN * QS) / QS;     // column of A / row of Q held by this thread
+    const int h = tid % QS;                                  // which of its row groups
     const float* Zp = Z + (long)blockIdx.x * sz;
-    float x[HN];
-    if (is_col) {
+    float x[4 * NG];
 #pragma unroll
-        for (int i = 0; i < HN; ++i) x[i] = Zp[(long)i * ldz + idx];
-    } else {
+    for (int k = 0; k < NG; ++k)
 #pragma unroll
-        for (int i = 0; i < HN; ++i) x[i] = (i == idx) ? 1.f : 0.f;
-    }
+        for (int e = 0; e < 4; ++e) {
+            const int i = 4 * (k * QS + h) + e;
+            x[4 * k + e] = is_col ? Zp[(long)i * ldz + idx] : (i == idx ? 1.f : 0.f);
+        }
     float mydiag = 0.f;
-    if (tid == 0) publish_column(cbuf[0], x, 0);
+    if (is_col && idx == 0) publish_from<0>(cbuf[0], x, h, 0);
     __syncthreads();
     for (int j = 0; j < HN; ++j) {
         const float* cb = cbuf[j & 1];
@@ -143,41 +151,48 @@ __global__ __launch_bounds__(256) void heads_qr_kernel(const float* __restrict__
             // 2 / u^T u from the vector that is applied, so that H is orthogonal whatever the rounding of beta
             const float gamma = 2.f * __builtin_amdgcn_rcpf(s + uj * uj);
             if (!is_col || idx > j) {
-                switch (j / QB) {
-                    case 0: reflect_column<0>(cb, x, j, uj, gamma); break;
-                    case 1: reflect_column<1>(cb, x, j, uj, gamma); break;
-                    case 2: reflect_column<2>(cb, x, j, uj, gamma); break;
-                    case 3: reflect_column<3>(cb, x, j, uj, gamma); break;
-                    case 4: reflect_column<4>(cb, x, j, uj, gamma); break;
-                    case 5: reflect_column<5>(cb, x, j, uj, gamma); break;
-                    case 6: reflect_column<6>(cb, x, j, uj, gamma); break;
-                    default: reflect_column<7>(cb, x, j, uj, gamma); break;
-                }
+#define DQ_CALL(JB) reflect_from<JB>(cb, x, h, j, uj, gamma)
+                DQ_BLOCK_SWITCH(j / QB, DQ_CALL)
+#undef DQ_CALL
             }
         }
         if (is_col && idx == j) mydiag = beta;
         if (tid == 0) sgn[j] = beta >= 0.f ? 1.f : -1.f;
-        if (is_col && idx == j + 1) publish_column(cbuf[(j + 1) & 1], x, j + 1);
+        if (is_col && idx == j + 1) {
+            float* nb = cbuf[(j + 1) & 1];
+#define DQ_CALL(JB) publish_from<JB>(nb, x, h, j + 1)
+            DQ_BLOCK_SWITCH((j + 1) / QB, DQ_CALL)
+#undef DQ_CALL
+        }
         __syncthreads();
     }
     if (is_col) {
-        if (!(fabsf(mydiag) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
-        else if (mydiag == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        if (h == 0) {
+            if (!(fabsf(mydiag) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+            else if (mydiag == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        }
         if (U != nullptr) {   // U[i][c] = s_i A[i][c] above the diagonal, |diag| on it
             float* Up = U + (long)blockIdx.x * su;
 #pragma unroll
-            for (int i = 0; i < HN; ++i)
-                Up[(long)i * ldu + idx] = i < idx ? sgn[i] * x[i] : (i == idx ? fabsf(mydiag) : 0.f);
+            for (int k = 0; k < NG; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = 4 * (k * QS + h) + e;
+                    Up[(long)i * ldu + idx] = i < idx ? sgn[i] * x[4 * k + e] : (i == idx ? fabsf(mydiag) : 0.f);
+                }
         }
     } else {                  // R[r][c] = s_c Q[r][c]
         float* Rp = R + (long)blockIdx.x * sr + (long)idx * ldr;
 #pragma unroll
-        for (int c = 0; c < HN; c += 4) {
+        for (int k = 0; k < NG; ++k) {
+            const int c = 4 * (k * QS + h);
             const float4 sg = *reinterpret_cast<const float4*>(sgn + c);
-            *reinterpret_cast<float4*>(Rp + c) = make_float4(x[c] * sg.x, x[c + 1] * sg.y, x[c + 2] * sg.z, x[c + 3] * sg.w);
+            *reinterpret_cast<float4*>(Rp + c) =
+                make_float4(x[4 * k] * sg.x, x[4 * k + 1] * sg.y, x[4 * k + 2] * sg.z, x[4 * k + 3] * sg.w);
         }
     }
 }
+#undef DQ_BLOCK_SWITCH
 
 // ------------------------------------------------------------------------------------------------ S3 + S4 + S5
 constexpr int TT = 64;            // tokens per tile
@@ -373,7 +388,7 @@ __global__ __launch_bounds__(256) void heads_reduce_kernel(const float* __restri
 hipError_t launch_heads_qr(int b, const float* Z, long ldz, long sz, float* R, long ldr, long sr, float* U, long ldu,
                            long su, unsigned* flags, hipStream_t s) {
     if (b < 1) return hipSuccess;
-    hipLaunchKernelGGL(heads_qr_kernel, dim3(b), dim3(256), 0, s, Z, ldz, sz, R, ldr, sr, U, ldu, su, flags);
+    hipLaunchKernelGGL(heads_qr_kernel, dim3(b), dim3(2 * HN * QS), 0, s, Z, ldz, sz, R, ldr, sr, U, ldu, su, flags);
     return hipGetLastError();
 }
 
