@@ -74,8 +74,11 @@ dq_status dq_create(dq_ctx** out, void* hip_stream);
 dq_status dq_destroy(dq_ctx* ctx);
 
 /* Bytes of device workspace that any call with these sizes needs (a host computation).
- * x_dtype is the storage type of X.  *out receives the size; it grows with b only through
- * max-over-problems, since problems of a batch run one after another. */
+ * x_dtype is the storage type of X.  *out receives the size.  Problems of a batch run one after
+ * another and share the workspace, except for n == 128 (per-head rotations): there all b problems
+ * run in the same kernel launches and the size grows with b (7 matrices of 64 KiB and
+ * ceil(T/2048) partial gradients per problem).  A batch gives the same bits as its problems
+ * run one by one. */
 dq_status dq_workspace_bytes(int b, int n, int T, dq_dtype x_dtype, size_t* out);
 
 /* Hand the context a caller-owned device buffer (256-byte aligned).  Enqueues one small kernel
