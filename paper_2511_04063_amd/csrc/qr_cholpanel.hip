@@ -460,56 +460,37 @@ __device__ __forceinline__ void rank8_update(float* Wm, int k0, int lim, int qi,
     for (int v = 0; v < 16; ++v) Wm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + j] = acc[v];
 }
 
+__device__ __forceinline__ float lane_value(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+
 // In place: the upper triangle of the symmetric positive definite G becomes U with G = U^T U; the strict lower
-// triangle is zeroed.  Blocked by 8: every thread factors the 8 x 8 diagonal block in registers (no exchange),
-// one thread per column solves the block row, then a rank-8 update of the rest on the matrix cores.
+// triangle is zeroed.  Blocked by 8.  The first wavefront holds the block row k0 .. k0+7 in registers, one column per
+// lane, and factors it with lane broadcasts only (the diagonal block and the block row to its right in the same
+// eight steps); then a rank-8 update of the rest on the matrix cores by all four wavefronts.
 __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
+    const int lane = tid & 63;
     for (int k0 = 0; k0 < B64; k0 += 8) {
-        float d[8][8], id[8];
+        if (tid < 64) {
+            float p[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
-#pragma unroll
-            for (int c = r; c < 8; ++c) d[r][c] = G[(k0 + r) * LS + k0 + c];
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            // hardware reciprocal square root (1 ulp): U only has to be consistent with the inverse formed from it
-            id[r] = __builtin_amdgcn_rsqf(d[r][r]);
-            d[r][r] *= id[r];
-#pragma unroll
-            for (int c = r + 1; c < 8; ++c) d[r][c] *= id[r];
-#pragma unroll
-            for (int i = r + 1; i < 8; ++i)
-#pragma unroll
-                for (int c = i; c < 8; ++c) d[i][c] -= d[r][i] * d[r][c];
-        }
-        const int j = k0 + 8 + tid;
-        if (j < B64) {
-            float x[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) x[r] = G[(k0 + r) * LS + j];
+            for (int r = 0; r < 8; ++r) p[r] = G[(k0 + r) * LS + lane];
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
-                float t = x[r];
+                // hardware reciprocal square root (1 ulp): U only has to be consistent with the inverse formed from it
+                const float id = __builtin_amdgcn_rsqf(lane_value(p[r], k0 + r));
+                p[r] *= id;
 #pragma unroll
-                for (int q = 0; q < r; ++q) t -= d[q][r] * x[q];
-                x[r] = t * id[r];
+                for (int i = r + 1; i < 8; ++i) p[i] -= lane_value(p[r], k0 + i) * p[r];
             }
 #pragma unroll
-            for (int r = 0; r < 8; ++r) G[(k0 + r) * LS + j] = x[r];
+            for (int r = 0; r < 8; ++r)
+                if (lane >= k0 + r) G[(k0 + r) * LS + lane] = p[r];
         }
         __syncthreads();
         rank8_update<true>(G, k0, k0 + 8, (tid >> 7) & 1, (tid >> 6) & 1, tid & 31, (tid >> 5) & 1);
         __syncthreads();
-        // The factored diagonal block goes back only now: the update above rewrites whole quadrants, and nothing
-        // reads or writes these entries again before the next barrier.
-        if (tid == NTHR - 1) {
-#pragma unroll
-            for (int r = 0; r < 8; ++r)
-#pragma unroll
-                for (int c = r; c < 8; ++c) G[(k0 + r) * LS + k0 + c] = d[r][c];
-        }
     }
-    __syncthreads();
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
@@ -521,72 +502,61 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
 // In place LU without pivoting of W - diag(s), where s_j = -1 if the pivot met at step j is >= 0 and +1 otherwise
 // (decided on the partially eliminated matrix), so that each pivot has modulus >= 1.  On return the strict lower
 // triangle holds L (unit diagonal implied), the upper triangle U, and sg[0..64) the signs.
+// Blocked by 8.  The first wavefront holds the block column k0 .. k0+7 in registers, one row per lane, and eliminates
+// it with lane broadcasts; the same wavefront then solves the block row to the right (one column per lane, the 8 x 8
+// unit-lower block read from the registers of the lanes that hold it); then a rank-8 update on the matrix cores.
 __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
+    const int lane = tid & 63;
     for (int k0 = 0; k0 < B64; k0 += 8) {
-        float d[8][8], sv[8], id[8];
+        if (tid < 64) {
+            float p[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
+            for (int c = 0; c < 8; ++c) p[c] = W[lane * LS + k0 + c];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) d[r][c] = W[(k0 + r) * LS + k0 + c];
+            for (int c = 0; c < 8; ++c) {
+                const int pr = k0 + c;
+                const float piv = lane_value(p[c], pr);
+                const float sv = piv >= 0.f ? -1.f : 1.f;
+                const float pv = piv - sv;
+                const float inv = __builtin_amdgcn_rcpf(pv);
+                const bool below = lane > pr;
+                if (lane == pr) { p[c] = pv; sg[pr] = sv; }
+                p[c] = below ? p[c] * inv : p[c];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            sv[r] = d[r][r] >= 0.f ? -1.f : 1.f;
-            d[r][r] -= sv[r];
-            id[r] = __builtin_amdgcn_rcpf(d[r][r]);
-#pragma unroll
-            for (int i = r + 1; i < 8; ++i) d[i][r] *= id[r];
-#pragma unroll
-            for (int i = r + 1; i < 8; ++i)
-#pragma unroll
-                for (int c = r + 1; c < 8; ++c) d[i][c] -= d[i][r] * d[r][c];
-        }
-        if (tid < 64) {                       // block column of L: x U_d = a, one row per thread
-            const int i = k0 + 8 + tid;
-            if (i < B64) {
-                float x[8];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) x[c] = W[i * LS + k0 + c];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    float t = x[c];
-#pragma unroll
-                    for (int q = 0; q < c; ++q) t -= x[q] * d[q][c];
-                    x[c] = t * id[c];
+                for (int c2 = c + 1; c2 < 8; ++c2) {
+                    const float u = lane_value(p[c2], pr);
+                    p[c2] = below ? p[c2] - p[c] * u : p[c2];
                 }
-#pragma unroll
-                for (int c = 0; c < 8; ++c) W[i * LS + k0 + c] = x[c];
             }
-        } else if (tid < 128) {               // block row of U: L_d y = a, one column per thread
-            const int j = k0 + 8 + (tid - 64);
-            if (j < B64) {
+            // the unit-lower diagonal block, as wavefront-uniform values
+            float l[8][8];
+#pragma unroll
+            for (int r = 1; r < 8; ++r)
+#pragma unroll
+                for (int q = 0; q < r; ++q) l[r][q] = lane_value(p[q], k0 + r);
+            if (lane >= k0) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) W[lane * LS + k0 + c] = p[c];
+            }
+            if (lane >= k0 + 8) {                 // block row of U: L_d y = a, one column per lane
                 float x[8];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) x[r] = W[(k0 + r) * LS + j];
+                for (int r = 0; r < 8; ++r) x[r] = W[(k0 + r) * LS + lane];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) {
+                for (int r = 1; r < 8; ++r) {
                     float t = x[r];
 #pragma unroll
-                    for (int q = 0; q < r; ++q) t -= d[r][q] * x[q];
+                    for (int q = 0; q < r; ++q) t -= l[r][q] * x[q];
                     x[r] = t;
                 }
 #pragma unroll
-                for (int r = 0; r < 8; ++r) W[(k0 + r) * LS + j] = x[r];
+                for (int r = 1; r < 8; ++r) W[(k0 + r) * LS + lane] = x[r];
             }
         }
         __syncthreads();
         rank8_update<false>(W, k0, k0 + 8, (tid >> 7) & 1, (tid >> 6) & 1, tid & 31, (tid >> 5) & 1);
         __syncthreads();
-        // the factored diagonal block goes back only now (see chol_upper_64)
-        if (tid == NTHR - 1) {
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                sg[k0 + r] = sv[r];
-#pragma unroll
-                for (int c = 0; c < 8; ++c) W[(k0 + r) * LS + k0 + c] = d[r][c];
-            }
-        }
     }
-    __syncthreads();
 }
 
 // First small step: U1 = chol(sum of partials of A^T A) and its inverse, both 64 x 64 (leading dimension 64).
