@@ -517,12 +517,18 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
 // ---------------------------------------------------------------- S3 + S4 + S5
 dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const void* X, dq_dtype xdt, long ldx,
                                const float* R, long ldr, dq_reduce red, float* loss_dev, float* G, long ldg,
-                               float* Y, long ldy, void* dY, long lddy) {
+                               float* Y, long ldy, void* dY, long lddy, bool keep_y_dy = true) {
     hipStream_t s = c->stream;
     unsigned* flags = at<unsigned>(c, L.flags);
     double* lpart = at<double>(c, L.losspart);
     const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
     const double gemm_flops = 2.0 * T * (double)n * n;
+    static const int use_t = [] { const char* e = getenv("DQ_G_TRANSPOSE"); return e ? atoi(e) : 1; }();
+    static const int use_fused = [] { const char* e = getenv("DQ_FUSED_WHIP"); return e ? atoi(e) : 1; }();
+    // large round bf16 shapes: S5 reads token-contiguous copies of both operands (see below)
+    const bool g_transposed = xdt == DQ_BF16 && use_t && n % 128 == 0 && T % 128 == 0 && (n / 128) * (n / 128) >= 256 &&
+                              (ldx & 7) == 0 && aligned16(X) && aligned16(G) && (ldg & 3) == 0;
+    bool fused = false;   // S4 done in the epilogue of S3
     // S3: Y = X @ R
     if (xdt == DQ_BF16) {
         bf16_t* rbt = at<bf16_t>(c, L.rbt);
@@ -538,8 +544,22 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         g.B = rbt; g.ldb = 2L * koff; g.tb = 1;
         g.C = Y; g.ldc = ldy; g.M = T; g.N = n; g.K = 2 * koff;
         g.a_kwrap = koff; g.a_klim = n;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
-        DQ_HIP(launch_gemm_bf16(g, s));
+        // A caller that needs neither Y nor dY gets Eq. 4 and its derivative applied to the accumulators: Y is never
+        // written and dY leaves the kernel already transposed for S5.
+        fused = use_fused && !keep_y_dy && g_transposed && gemm_bf16_deep_fits(g) &&
+                (T / 128) * (n / 128) <= kLossPartials;
+        if (fused) {
+            g.C = nullptr;
+            g.whip_dyt = at<bf16_t>(c, L.dyt); g.whip_ldt = T; g.whip_scale = scale; g.whip_partials = lpart;
+        }
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, gemm_flops, 0.0);
+            DQ_HIP(launch_gemm_bf16(g, s));
+        }
+        if (fused) {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+            DQ_HIP(launch_loss_finish(lpart, (T / 128) * (n / 128), scale, loss_dev, flags, s));
+        }
     } else {
         GemmF32 g;
         g.A = static_cast<const float*>(X); g.lda = ldx; g.ta = 0;
@@ -549,7 +569,7 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         DQ_HIP(launch_gemm_f32(g, s));
     }
     // S4: loss and dY in one pass over Y
-    {
+    if (!fused) {
         const int grid = whip_grid(T, n);
         const double bytes = (double)T * n * (4.0 + (xdt == DQ_BF16 ? 2.0 : 4.0));
         {
@@ -573,15 +593,13 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         const long stride = (long)n * L.ld;
         // Large round bf16 shapes: both operands are first transposed (two HBM-bound passes), so that the product
         // reads rows only and runs in the unguarded deep-prefetch kernel without a split of the token sum.
-        static const int use_t = [] { const char* e = getenv("DQ_G_TRANSPOSE"); return e ? atoi(e) : 1; }();
-        if (xdt == DQ_BF16 && use_t && n % 128 == 0 && T % 128 == 0 && tiles >= 256 && (ldx & 7) == 0 &&
-            (lddy & 7) == 0 && aligned16(X) && aligned16(dY) && aligned16(G) && (ldg & 3) == 0) {
+        if (g_transposed && (fused || ((lddy & 7) == 0 && aligned16(dY)))) {
             bf16_t* xt = at<bf16_t>(c, L.xt);
             bf16_t* dyt = at<bf16_t>(c, L.dyt);
             {
-                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * T * (double)n);
+                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, (fused ? 4.0 : 8.0) * T * (double)n);
                 DQ_HIP(launch_transpose_bf16(static_cast<const bf16_t*>(X), ldx, T, n, xt, T, s));
-                DQ_HIP(launch_transpose_bf16(static_cast<const bf16_t*>(dY), lddy, T, n, dyt, T, s));
+                if (!fused) DQ_HIP(launch_transpose_bf16(static_cast<const bf16_t*>(dY), lddy, T, n, dyt, T, s));
             }
             GemmBf16 g;
             g.A = xt; g.lda = T; g.ta = 0;
@@ -909,7 +927,7 @@ dq_status dq_rotate_loss_grad(dq_ctx* c, int b, int T, int n, const void* X, dq_
         const long lddyi = dY ? lddy : L.ld;
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, R + (long)i * n * ldr, ldr, red, loss_dev + i,
-                                    G + (long)i * n * ldg, ldg, Yi, ldyi, dYi, lddyi));
+                                    G + (long)i * n * ldg, ldg, Yi, ldyi, dYi, lddyi, Y != nullptr || dY != nullptr));
     }
     return DQ_OK;
 }
@@ -949,7 +967,7 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
         DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
-                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
+                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld, false));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, nullptr, 0, Zi, ldz, lr));
     }
     return DQ_OK;
@@ -1093,7 +1111,7 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
         DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
-                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld));
+                                    at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld, false));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, dZi, L.ld, nullptr, 0, 0.f));
         LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * n * (double)n, 28.0 * n * (double)n);
         DQ_HIP(launch_adam2d(Zi, ldz, dZi, L.ld, m + (long)i * n * ldm, ldm, v + (long)i * n * ldv, ldv, n, lr, beta1,

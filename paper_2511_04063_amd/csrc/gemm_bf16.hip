@@ -232,9 +232,15 @@ __device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDH], const bf
     }
 }
 
+// WHIP: the epilogue applies the Whip loss and its derivative (Eq. 4; Alg. 1 line 9) to the accumulators instead of
+// (or beside) writing them: per-workgroup partial sums of exp(-|y|) go to g.whip_partials[workgroup], and
+// dY = -scale sgn(y) exp(-|y|) is written TRANSPOSED in bf16 (g.whip_dyt: N x M, token-contiguous), staged through
+// the operand buffers in LDS so that every row of 128 tokens leaves as one 256-byte run.
+template <bool WHIP>
 __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int tiles_m, int tiles_n) {
-    __shared__ __attribute__((aligned(16))) bf16_t As[2][BM][LDH];
-    __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN][LDH];
+    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * LDH + 2 * BN * LDH];
+    bf16_t (*As)[BM][LDH] = reinterpret_cast<bf16_t (*)[BM][LDH]>(smem);
+    bf16_t (*Bs)[BN][LDH] = reinterpret_cast<bf16_t (*)[BN][LDH]>(smem + 2 * BM * LDH);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -323,21 +329,78 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int 
 #undef DQ_FETCH
 
     float* C = g.C;
+    if (!WHIP || C != nullptr) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn + j * 32 + lrow;
+            for (int j = 0; j < 2; ++j) {
+                const int col = n0 + wn + j * 32 + lrow;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                C[(long)row * g.ldc + col] = acc[i][j][v];
+                for (int v = 0; v < 16; ++v) {
+                    const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                    C[(long)row * g.ldc + col] = acc[i][j][v];
+                }
             }
         }
+    }
+    if constexpr (WHIP) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        constexpr int SLD = BM + 8;          // halfwords per staged row (272 bytes)
+        static_assert(BN * SLD <= 2 * BM * LDH + 2 * BN * LDH, "the staged tile must fit the operand buffers");
+        bf16_t* stage = smem;                // [BN][SLD]; the K loop ended with a barrier: the buffers are free
+        const float scale = g.whip_scale;
+        float lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int c = wn + j * 32 + lrow;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int r0 = wm + i * 32 + 8 * q4 + 4 * lk;
+                    float d[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float y = acc[i][j][4 * q4 + q];
+                        const float ex = __expf(-fabsf(y));
+                        lsum += ex;
+                        const float sg = (y > 0.f) ? -scale : ((y < 0.f) ? scale : 0.f);
+                        d[q] = sg * ex;
+                    }
+                    const f32x2 d01 = {d[0], d[1]}, d23 = {d[2], d[3]};
+                    const bf16x2 b01 = __builtin_convertvector(d01, bf16x2), b23 = __builtin_convertvector(d23, bf16x2);
+                    *reinterpret_cast<uint2*>(stage + c * SLD + r0) =
+                        make_uint2(__builtin_bit_cast(uint32_t, b01), __builtin_bit_cast(uint32_t, b23));
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int pass = 0; pass < BN / 16; ++pass) {
+            const int row = pass * 16 + (tid >> 4), piece = (tid & 15) * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + row * SLD + piece);
+            *reinterpret_cast<uint4*>(g.whip_dyt + (long)(n0 + row) * g.whip_ldt + m0 + piece) = v;
+        }
+        __shared__ float wsum[4];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) lsum += __shfl_xor(lsum, o);
+        if (lane == 0) wsum[wave] = lsum;
+        __syncthreads();
+        if (tid == 0)
+            g.whip_partials[bid] = (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3];
     }
 }
 
 }  // namespace
+
+bool gemm_bf16_deep_fits(const GemmBf16& g) {
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const bool avec = (reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 7) == 0;
+    const bool bvec = (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0;
+    return !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (4 * BK) == 0 &&
+           tiles_m * tiles_n >= 256 && avec && bvec && (g.a_kwrap == 0 || (g.a_kwrap % BK == 0 && g.a_klim == g.a_kwrap));
+}
 
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
@@ -346,11 +409,18 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
     const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0) ? 1 : 0;
     // big NT products without split-K and with round sizes: the unguarded kernel with the deep prefetch
     static const int use_deep = [] { const char* e = getenv("DQ_BF16_DEEP"); return e ? atoi(e) : 1; }();
-    const bool fits = !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (4 * BK) == 0 &&
-                      tiles_m * tiles_n >= 256 && avec && bvec &&
-                      (g.a_kwrap == 0 || (g.a_kwrap % BK == 0 && g.a_klim == g.a_kwrap));
+    const bool fits = gemm_bf16_deep_fits(g);
+    if (g.whip_dyt != nullptr) {   // the fused epilogue exists in the unguarded kernel only: the caller checks first
+        if (!fits || g.whip_partials == nullptr || (g.whip_ldt & 7) != 0 || g.whip_ldt < g.M ||
+            (reinterpret_cast<uintptr_t>(g.whip_dyt) & 15) != 0)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemm_bf16_nt_deep_kernel<true>), dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m,
+                           tiles_n);
+        return hipGetLastError();
+    }
     if (use_deep && fits) {
-        hipLaunchKernelGGL(gemm_bf16_nt_deep_kernel, dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m, tiles_n);
+        hipLaunchKernelGGL((gemm_bf16_nt_deep_kernel<false>), dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m,
+                           tiles_n);
         return hipGetLastError();
     }
     dim3 grid(tiles_m * tiles_n, g.splits > 1 ? g.splits : 1, 1);

@@ -305,6 +305,40 @@ def test_rotate_loss_grad(ctx, T, n, bf16):
     assert torch.equal(G2, Gd)
 
 
+def test_rotate_loss_grad_fused_epilogue():
+    """Large round bf16 shapes: a caller that asks for neither Y nor dY gets Eq. 4 applied in the epilogue of the
+    rotation product (dY leaves it transposed for the gradient product).  Against the oracle, and against the
+    kernel-by-kernel route of the same call with Y and dY requested."""
+    T, n = 2048, 2048
+    cfg = synth.scaled_config("7b", n=n, T=T)
+    inp = synth.make_inputs(cfg, seed=6)
+    X = inp["X"][0]
+    R32 = orc.qr_orth(inp["Z0"][0])[0].astype(np.float32)
+    c = B.Context()
+    try:
+        c.ensure_workspace(1, n, T, B.DQ_BF16)
+        Xd = dev(X, torch.bfloat16)
+        Rd = dev(R32)
+        Gf = torch.empty((n, n), device="cuda")
+        lf = torch.zeros(1, device="cuda")
+        c.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, lf, Gf)
+        Gu = torch.empty((n, n), device="cuda")
+        lu = torch.zeros(1, device="cuda")
+        Yd = torch.empty((T, n), device="cuda")
+        dYd = torch.empty((T, n), device="cuda", dtype=torch.bfloat16)
+        c.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, lu, Gu, Yd, dYd)
+        lo, Go, _, _ = orc.rotate_loss_grad(X, R32)
+        assert abs(lf.item() - lo) <= 1e-4 * lo
+        assert rel(Gf.cpu().numpy(), Go) < 2e-2
+        assert lf.item() == pytest.approx(lu.item(), rel=1e-6)
+        # the same bf16 dY enters both gradient products: they differ by the order of the fp32 sums only
+        assert rel(Gf.cpu().numpy(), Gu.cpu().numpy()) < 1e-5
+        assert c.dq_device_flags() == 0
+    finally:
+        torch.cuda.synchronize()
+        c.close()
+
+
 # ----------------------------------------------------------------------------------- QR backward
 @pytest.mark.parametrize("n", [1, 2, 7, 100, 128, 129, 300, 700])
 def test_qr_backward_stage(ctx, n):
