@@ -65,6 +65,7 @@ typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
 #define DQ_FLAG_ILLCOND_PANEL 4u /* informational: a tall 64-column panel of the QR was too ill-conditioned for the
                                    many-CU panel route and was factored by the one-workgroup Householder kernel
                                    instead; results are valid */
+#define DQ_FLAG_BAD_INDEX  8u   /* dq_gather_rows met an index outside [0, T_all): that row was not written  */
 
 /* ---- context and workspace ---------------------------------------------------------- */
 
@@ -134,6 +135,15 @@ dq_status dq_whip_loss_grad(dq_ctx* ctx, int b, int T, int n,
 dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
                          const float* R, long ldr, const float* U, long ldu,
                          const float* G, long ldg, float* dZ, long lddz);
+
+/* Alg. 1 line 5, token sampling: X_out[i][t][:] = X_all[i][idx[i*T_out + t]][:] for t < T_out, b independent
+ * problems (X_all: b blocks of T_all rows, X_out: b blocks of T_out rows, both with n columns of `dtype`).
+ * Which tokens are kept (the paper samples 10 % of them at random) is the caller's choice: idx is a DEVICE array of
+ * b*T_out int32 row numbers in [0, T_all), repeats allowed.  Rows must be 16-byte multiples and 16-byte aligned
+ * (n a multiple of 8 for bf16, of 4 for fp32, with the usual leading-dimension rules).  An index out of range leaves
+ * its output row untouched and raises DQ_FLAG_BAD_INDEX.  Needs a workspace only for the status word. */
+dq_status dq_gather_rows(dq_ctx* ctx, int b, int T_all, int T_out, int n, const void* X_all, dq_dtype dtype,
+                         long ldx_all, const int* idx, void* X_out, long ldx_out);
 
 /* Alg. 1 line 10, the update alone:  Z <- Z - lr * dZ  (in place on Z). */
 dq_status dq_sgd_update(dq_ctx* ctx, int b, int n, float* Z, long ldz,

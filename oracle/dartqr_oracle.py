@@ -40,6 +40,10 @@ Readings taken where the paper is silent (each is also listed in the design note
   the usual defaults (beta1 0.9, beta2 0.999, eps 1e-8, step counter from 1); SGD with
   momentum as the heavy-ball form without dampening.  Both pinned against closed forms
   and a library optimiser (tests/).
+* Alg. 1 line 5, token_sampling(X): the paper keeps a random 10 % of the tokens (App.,
+  sample-size analysis) and does not say how they are drawn.  The draw is an INPUT here
+  (a list of row numbers, repeats allowed); the step itself is the selection of those
+  rows, in the given order.  Pinned by its invariants (tests/).
 """
 
 from __future__ import annotations
@@ -61,6 +65,7 @@ __all__ = [
     "calib_step_adam",
     "calibrate",
     "rotate_loss_grad",
+    "token_sampling",
 ]
 
 
@@ -123,6 +128,21 @@ def qr_orth(Z):
     R = Q * s[None, :]
     U = U0 * s[:, None]
     return R, U
+
+
+def token_sampling(X, idx) -> np.ndarray:
+    """Alg. 1 line 5: the activation rows named by idx, in that order (values untouched)."""
+    X = np.asarray(X)
+    idx = np.asarray(idx)
+    if idx.ndim != 1:
+        raise ValueError("idx must be a list of row numbers")
+    out = np.empty((idx.shape[0],) + X.shape[1:], dtype=X.dtype)
+    for t in range(idx.shape[0]):
+        r = int(idx[t])
+        if r < 0 or r >= X.shape[0]:
+            raise IndexError(f"row {r} outside [0, {X.shape[0]})")
+        out[t] = X[r]
+    return out
 
 
 def rotate(X, R):

@@ -17,7 +17,7 @@ DQ_OK = 0
 DQ_ERR_NULL, DQ_ERR_SHAPE, DQ_ERR_DTYPE, DQ_ERR_ALIGN, DQ_ERR_WORKSPACE, DQ_ERR_HIP, DQ_ERR_UNSUPPORTED = range(1, 8)
 DQ_F32, DQ_BF16 = 0, 1
 DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
-DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL = 1, 2, 4
+DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX = 1, 2, 4, 8
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
 DQ_MAX_N = 8192
 
@@ -38,6 +38,7 @@ SIGNATURES = {
     "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
+    "dq_gather_rows": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _l, _vp, _vp, _l]),
     "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
     "dq_sgd_momentum_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _f, _f]),
     "dq_calib_step_adam": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f, _i, _vp,
@@ -204,6 +205,13 @@ class Context:
                                                 _ld(m), _ptr(v), _ld(v), int(step), float(lr), float(beta1),
                                                 float(beta2), float(eps), reduce, _ptr(loss), _ptr(R), _ld(R)),
                     "dq_calib_step_adam")
+
+    def dq_gather_rows(self, X_all, dtype, idx, X_out):
+        b = X_all.shape[0] if X_all.dim() == 3 else 1
+        T_all, n = X_all.shape[-2], X_all.shape[-1]
+        T_out = X_out.shape[-2]
+        self._check(self.lib.dq_gather_rows(self.h, b, T_all, T_out, n, _ptr(X_all), dtype, _ld(X_all), _ptr(idx),
+                                            _ptr(X_out), _ld(X_out)), "dq_gather_rows")
 
     def dq_sgd_update(self, Z, dZ, lr):
         b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])

@@ -1022,6 +1022,26 @@ dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, cons
     return DQ_OK;
 }
 
+dq_status dq_gather_rows(dq_ctx* c, int b, int T_all, int T_out, int n, const void* X_all, dq_dtype dtype,
+                         long ldx_all, const int* idx, void* X_out, long ldx_out) {
+    if (c == nullptr || idx == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T_all < 1 || T_out < 0 || n < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_x(X_all, dtype, ldx_all, n));
+    DQ_TRY(check_x(X_out, dtype, ldx_out, n));
+    const size_t esz = (dtype == DQ_BF16) ? 2 : 4;
+    if (((size_t)n * esz) % 16 != 0) return DQ_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(idx) & 3) != 0) return DQ_ERR_ALIGN;
+    if (c->ws == nullptr) return DQ_ERR_WORKSPACE;
+    for (int i = 0; i < b; ++i) {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 0.0, 2.0 * T_out * (double)n * esz);
+        DQ_HIP(launch_gather_rows(static_cast<const char*>(X_all) + (size_t)i * T_all * ldx_all * esz,
+                                  (long)(ldx_all * esz), T_all, idx + (long)i * T_out, T_out, (int)(n * esz),
+                                  static_cast<char*>(X_out) + (size_t)i * T_out * ldx_out * esz, (long)(ldx_out * esz),
+                                  at<unsigned>(c, 0), c->stream));
+    }
+    return DQ_OK;
+}
+
 dq_status dq_sgd_update(dq_ctx* c, int b, int n, float* Z, long ldz, const float* dZ, long lddz, float lr) {
     if (c == nullptr) return DQ_ERR_NULL;
     if (b < 0 || n < 1) return DQ_ERR_SHAPE;

@@ -204,6 +204,29 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
     }
 }
 
+// out[t][:] = src[idx[t]][:] for t < rows_out: the token-sampling step in front of the loop (Alg. 1 line 5) as a
+// gather of whole rows, 16 bytes per lane (row_bytes is a multiple of 16, rows 16-byte aligned).  An index outside
+// [0, rows_in) copies nothing for that row and raises the flag.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ src, long src_stride, int rows_in,
+                                                          const int* __restrict__ idx, int rows_out, int row_bytes,
+                                                          char* __restrict__ out, long out_stride, int rows_per_block,
+                                                          unsigned* flags) {
+    const int pieces = row_bytes >> 4;
+    const int tpr = 256 / rows_per_block;             // threads per row
+    const int rsub = threadIdx.x / tpr, lane = threadIdx.x % tpr;
+    if (rsub >= rows_per_block) return;
+    for (long t = (long)blockIdx.x * rows_per_block + rsub; t < rows_out; t += (long)gridDim.x * rows_per_block) {
+        const int r = idx[t];
+        if (r < 0 || r >= rows_in) {
+            if (lane == 0) atomicOr(flags, DQ_FLAG_BAD_INDEX);
+            continue;
+        }
+        const uint4* s4 = reinterpret_cast<const uint4*>(src + (long)r * src_stride);
+        uint4* d4 = reinterpret_cast<uint4*>(out + t * out_stride);
+        for (int p = lane; p < pieces; p += tpr) d4[p] = s4[p];
+    }
+}
+
 // P[i][j] = B[i][j] - B[j][i] for i > j, else 0.  Mzero (optional) is cleared.  blockIdx.z: problem of a batch.
 __global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict__ B, long ldb, int n,
                                                          float* __restrict__ P, long ldp, float* __restrict__ Mz,
@@ -389,6 +412,19 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int col
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((rows >> 6) * (cols >> 6)), dim3(256), 0, s, src, lds_, rows, cols,
                        dst, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void* src, long src_stride_bytes, int rows_in, const int* idx, int rows_out,
+                              int row_bytes, void* out, long out_stride_bytes, unsigned* flags, hipStream_t s) {
+    if (rows_out <= 0 || row_bytes <= 0) return hipSuccess;
+    const int pieces = row_bytes >> 4;
+    const int rpb = pieces >= 256 ? 1 : 256 / pieces;
+    long blocks = ((long)rows_out + rpb - 1) / rpb;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<const char*>(src),
+                       src_stride_bytes, rows_in, idx, rows_out, row_bytes, static_cast<char*>(out), out_stride_bytes,
+                       rpb, flags);
     return hipGetLastError();
 }
 

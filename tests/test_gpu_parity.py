@@ -790,6 +790,42 @@ def test_heads_full_size_step():
         c.close()
 
 
+# ----------------------------------------------------------------------------------- token sampling
+@pytest.mark.parametrize("bf16", [True, False])
+def test_gather_rows_bit_exact(ctx, bf16):
+    b, T_all, T_out, n = 2, 333, 70, 136 if bf16 else 100
+    g = rng(8100 + int(bf16))
+    X = synth.round_to_bf16(g.standard_normal((b, T_all, n)).astype(np.float32)) if bf16 else \
+        g.standard_normal((b, T_all, n)).astype(np.float32)
+    idx = g.integers(0, T_all, (b, T_out)).astype(np.int32)
+    idx[0, :3] = [5, 5, T_all - 1]          # repeats and the last row
+    dt = torch.bfloat16 if bf16 else torch.float32
+    _, Xd = padded3(b, T_all, n, n + 8, dt); Xd.copy_(dev(X, dt))
+    obuf, Od = padded3(b, T_out, n, n + 16, dt)
+    ctx.dq_gather_rows(Xd, B.DQ_BF16 if bf16 else B.DQ_F32, dev(idx), Od)
+    out = Od.float().cpu().numpy()
+    for i in range(b):
+        assert np.array_equal(out[i], orc.token_sampling(X[i], idx[i]))
+    assert torch.isnan(obuf[:, :, n:].float()).all()      # the padding of the output rows is not written
+    assert ctx.dq_device_flags() == 0
+    # an index out of range: flagged, its row untouched, the others written
+    bad = idx.copy(); bad[1, 7] = T_all; bad[0, 2] = -1
+    obuf2, Od2 = padded3(b, T_out, n, n + 16, dt)
+    ctx.dq_gather_rows(Xd, B.DQ_BF16 if bf16 else B.DQ_F32, dev(bad), Od2)
+    assert ctx.dq_device_flags() == B.DQ_FLAG_BAD_INDEX
+    o2 = Od2.float().cpu().numpy()
+    assert np.isnan(o2[1, 7]).all() and np.isnan(o2[0, 2]).all()
+    ok = np.ones((b, T_out), bool); ok[1, 7] = False; ok[0, 2] = False
+    assert np.array_equal(o2[ok], out[ok])
+    # the sampled block feeds the step like any other activation block
+    if bf16:
+        lib, h = ctx.lib, ctx.h
+        assert lib.dq_gather_rows(h, 1, T_all, T_out, 100, Xd.data_ptr(), B.DQ_BF16, n + 8, dev(idx).data_ptr(),
+                                  Od.data_ptr(), n + 16) == B.DQ_ERR_ALIGN      # 200-byte rows
+        assert lib.dq_gather_rows(h, 1, T_all, 0, n, Xd.data_ptr(), B.DQ_BF16, n + 8, dev(idx).data_ptr(),
+                                  Od.data_ptr(), n + 16) == B.DQ_OK
+
+
 # ----------------------------------------------------------------------------------- error paths
 def test_errors_have_no_effect(ctx):
     n = 64

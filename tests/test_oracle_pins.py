@@ -497,3 +497,32 @@ def test_calib_step_adam_composes_the_pieces():
     assert np.array_equal(out["dZ"], ref["dZ"]) and out["loss"] == ref["loss"]
     Zn, mn, vn = orc.adam_update(Z, ref["dZ"], m, v, 3, 0.01)
     assert np.array_equal(out["Z_new"], Zn) and np.array_equal(out["m"], mn) and np.array_equal(out["v"], vn)
+
+
+# ----------------------------------------------------------------------------------- token sampling (Alg. 1 line 5)
+def test_token_sampling_invariants():
+    g = np.random.Generator(np.random.Philox(901))
+    T, n = 57, 12
+    X = g.standard_normal((T, n))
+    R, _ = orc.qr_orth(g.standard_normal((n, n)))
+    idx = g.integers(0, T, 23)
+    Xs = orc.token_sampling(X, idx)
+    assert Xs.shape == (23, n) and Xs.dtype == X.dtype
+    # the rows are the named ones, bit for bit, repeats included
+    assert all(np.array_equal(Xs[t], X[idx[t]]) for t in range(23))
+    assert np.array_equal(orc.token_sampling(X, np.arange(T)), X)
+    assert np.array_equal(orc.token_sampling(X, np.arange(T)[::-1]), X[::-1])
+    # selecting rows commutes with everything the loop does row by row: the rotation ...
+    assert np.array_equal(orc.rotate(Xs, R), orc.token_sampling(orc.rotate(X, R), idx))
+    # ... and the summed loss of the sample is the sum of the per-token Whip values of the chosen tokens
+    per_token = np.array([orc.whip_loss(orc.rotate(X[t:t + 1], R), "sum") for t in range(T)])
+    assert orc.whip_loss(orc.rotate(Xs, R), "sum") == pytest.approx(per_token[idx].sum(), rel=1e-14)
+    # a full permutation leaves the mean loss and G = X^T dY unchanged
+    perm = g.permutation(T)
+    l0, G0, _, _ = orc.rotate_loss_grad(X, R)
+    l1, G1, _, _ = orc.rotate_loss_grad(orc.token_sampling(X, perm), R)
+    assert l1 == pytest.approx(l0, rel=1e-14) and np.allclose(G1, G0, rtol=0, atol=1e-14)
+    with pytest.raises(IndexError):
+        orc.token_sampling(X, [0, T])
+    with pytest.raises(IndexError):
+        orc.token_sampling(X, [-1])
