@@ -5,8 +5,9 @@
 A "step" is one dq_calib_step: QR of the latent Z, Y = X R, fused Whip loss/gradient, G = X^T dY,
 the derivative through the QR and the SGD update, on one synthetic activation block that is already
 resident in HBM.  Prints ONE JSON line (metric: steps per second) with a `roofline` object for the
-kernel class that takes most of the step and a `cpu_baseline` object (the fp64 oracle timed on the
-host on a bounded sample).
+kernel class that takes most of the step, a `stage_roofline` object (every stage entry point timed on its
+own after the timed region: share of the fp32 / bf16 matrix-core peak and, for the Whip pass, of the HBM peak)
+and a `cpu_baseline` object (the fp64 oracle timed on the host on a bounded sample).
 """
 
 from __future__ import annotations
@@ -160,6 +161,46 @@ def main():
     ctx.dq_profile_enable(0)
     flags = ctx.dq_device_flags()
 
+    # the stages one by one (same entry points the step is made of), for the per-stage share of the matrix-core and
+    # HBM peaks; outside the timed region
+    def stage_times():
+        shp = (cfg.b, cfg.n, cfg.n) if cfg.b > 1 else (cfg.n, cfg.n)
+        Rb, Ub, Gb, dZb = (torch.empty(shp, device="cuda") for _ in range(4))
+        Yb = torch.empty(Xd.shape, device="cuda")
+        dYb = torch.empty(Xd.shape, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
+        lossb = torch.zeros(cfg.b, device="cuda")
+        Zs = Z0.clone()
+
+        def tm(f, reps=5):
+            f(); f()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(reps):
+                f()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / reps * 1e3
+
+        n, T, b = cfg.n, cfg.T, cfg.b
+        out = {}
+        ms = tm(lambda: ctx.dq_qr_orth(Zs, Rb, Ub))
+        fl = b * (8.0 / 3.0) * n ** 3
+        out["qr_orth"] = {"ms": ms, "model_tflops": fl / ms / 1e9, "frac_fp32_mfma_peak": fl / ms / 1e9 / PEAK["fp32_mfma_tflops"]}
+        ms = tm(lambda: ctx.dq_rotate_loss_grad(Xd, xdt, Rb, red, lossb, Gb))
+        fl = b * 4.0 * T * n * n
+        peak = PEAK["bf16_mfma_tflops"] if bf16 else PEAK["fp32_mfma_tflops"]
+        out["rotate_loss_grad"] = {"ms": ms, "model_tflops": fl / ms / 1e9,
+                                   ("frac_bf16_mfma_peak" if bf16 else "frac_fp32_mfma_peak"): fl / ms / 1e9 / peak}
+        ms = tm(lambda: ctx.dq_qr_backward(Rb, Ub, Gb, dZb))
+        fl = b * 4.0 * n ** 3
+        out["qr_backward"] = {"ms": ms, "model_tflops": fl / ms / 1e9, "frac_fp32_mfma_peak": fl / ms / 1e9 / PEAK["fp32_mfma_tflops"]}
+        ctx.dq_rotate_loss_grad(Xd, xdt, Rb, red, lossb, Gb, Yb, dYb)
+        ms = tm(lambda: ctx.dq_whip_loss_grad(Yb, red, lossb, dYb, xdt))
+        by = b * T * n * (4.0 + (2.0 if bf16 else 4.0))
+        out["whip_loss_grad"] = {"ms": ms, "bytes": by, "gbs": by / ms / 1e6, "frac_hbm_peak": by / ms / 1e6 / PEAK["hbm_gbs"]}
+        return out
+
+    stages = stage_times()
+
     ms_per_step = dt * 1e3 / args.steps
     F = flops_per_step(cfg.n, cfg.T, cfg.b)
     launches = max(1, dom["launches"])
@@ -199,6 +240,7 @@ def main():
         "flops_per_step": F,
         "loss_first": first_loss, "loss_last": last_loss, "device_flags": flags,
         "roofline": roof,
+        "stage_roofline": stages,
         "stage_ms_one_step": {k: round(v["ms"], 4) for k, v in breakdown.items()},
         "stage_launches_one_step": {k: v["launches"] for k, v in breakdown.items()},
     }
