@@ -211,14 +211,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16 g, int tiles_m,
 }
 
 // ---- large "NT" products (both operands k-contiguous: A is M x K, B is N x K) ---------------------------------
-// Same 128 x 128 x 32 tile and wavefront layout as above, but without guards (M, N multiples of 128, K of 128,
-// 16-byte aligned rows; a_kwrap a multiple of 32 with a_klim == a_kwrap) and with FOUR K steps of operands in flight
-// in registers: a K step is only 8 MFMAs per wavefront, far shorter than the memory latency, and two workgroups per
-// compute unit do not hide it.  The loop body has no early exit (K % 128 == 0).
-__device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDH], const bf16_t (*Bsc)[LDH], f32x16 (&acc)[2][2],
+// Same 128 x 128 tile and wavefront layout as above, but a K step of 64 (16 MFMAs per wavefront between two
+// barriers), without guards (M, N multiples of 128, K of 128, 16-byte aligned rows; a_kwrap a multiple of 64 with
+// a_klim == a_kwrap) and with TWO K steps (128 reduction indices) of operands in flight in registers: a K step is far
+// shorter than the memory latency, and two workgroups per compute unit do not hide it.  The loop body has no early
+// exit (K % 128 == 0).
+constexpr int BKD = 64;
+constexpr int LDD = BKD + 8;   // LDS row stride in halfwords (144 bytes)
+__device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDD], const bf16_t (*Bsc)[LDD], f32x16 (&acc)[2][2],
                                               int wm, int wn, int lrow, int lk) {
 #pragma unroll
-    for (int ks = 0; ks < BK; ks += 16) {
+    for (int ks = 0; ks < BKD; ks += 16) {
         bf16x8 a[2], b[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(&Asc[wm + i * 32 + lrow][ks + lk * 8]);
@@ -238,9 +241,9 @@ __device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDH], const bf
 // the operand buffers in LDS so that every row of 128 tokens leaves as one 256-byte run.
 template <bool WHIP>
 __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int tiles_m, int tiles_n) {
-    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * LDH + 2 * BN * LDH];
-    bf16_t (*As)[BM][LDH] = reinterpret_cast<bf16_t (*)[BM][LDH]>(smem);
-    bf16_t (*Bs)[BN][LDH] = reinterpret_cast<bf16_t (*)[BN][LDH]>(smem + 2 * BM * LDH);
+    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * BM * LDD + 2 * BN * LDD];
+    bf16_t (*As)[BM][LDD] = reinterpret_cast<bf16_t (*)[BM][LDD]>(smem);
+    bf16_t (*Bs)[BN][LDD] = reinterpret_cast<bf16_t (*)[BN][LDD]>(smem + 2 * BM * LDD);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -273,55 +276,58 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int 
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int lrow = lane & 31, lk = lane >> 5;
 
-    // thread t moves the 16-byte piece (row t / 4 + 64 i, k-offset 8 (t % 4)) of each operand tile, i = 0, 1
-    const int prow = tid >> 2, pk = (tid & 3) << 3;
+    // thread t moves the 16-byte piece (row t / 8 + 32 i, k-offset 8 (t % 8)) of each operand tile, i = 0 .. 3
+    const int prow = tid >> 3, pk = (tid & 7) << 3;
     const bf16_t* pa = g.A + (long)(m0 + prow) * g.lda + pk;
     const bf16_t* pb = g.B + (long)(n0 + prow) * g.ldb + pk;
-    const long sa = 64 * g.lda, sb = 64 * g.ldb;
+    const long sa = 32 * g.lda, sb = 32 * g.ldb;
 
-    const int nk = g.K / BK;
-    struct Stage { uint4 a0, a1, b0, b1; };
-    Stage st0, st1, st2, st3;
+    const int nk = g.K / BKD;
+    struct Stage { uint4 a0, a1, a2, a3, b0, b1, b2, b3; };
+    Stage st0, st1;
 
 #define DQ_FETCH(kt, st)                                                                           \
     if ((kt) < nk) {                                                                               \
-        const int k0_ = (kt) * BK;                                                                 \
+        const int k0_ = (kt) * BKD;                                                                \
         const int ka_ = (wrap > 0 && k0_ >= wrap) ? k0_ - wrap : k0_;                              \
         st.a0 = *reinterpret_cast<const uint4*>(pa + ka_);                                         \
         st.a1 = *reinterpret_cast<const uint4*>(pa + sa + ka_);                                    \
+        st.a2 = *reinterpret_cast<const uint4*>(pa + 2 * sa + ka_);                                \
+        st.a3 = *reinterpret_cast<const uint4*>(pa + 3 * sa + ka_);                                \
         st.b0 = *reinterpret_cast<const uint4*>(pb + k0_);                                         \
         st.b1 = *reinterpret_cast<const uint4*>(pb + sb + k0_);                                    \
+        st.b2 = *reinterpret_cast<const uint4*>(pb + 2 * sb + k0_);                                \
+        st.b3 = *reinterpret_cast<const uint4*>(pb + 3 * sb + k0_);                                \
     }
 #define DQ_STASH(buf, st)                                                                          \
     {                                                                                              \
         *reinterpret_cast<uint4*>(&As[buf][prow][pk]) = st.a0;                                     \
-        *reinterpret_cast<uint4*>(&As[buf][prow + 64][pk]) = st.a1;                                \
+        *reinterpret_cast<uint4*>(&As[buf][prow + 32][pk]) = st.a1;                                \
+        *reinterpret_cast<uint4*>(&As[buf][prow + 64][pk]) = st.a2;                                \
+        *reinterpret_cast<uint4*>(&As[buf][prow + 96][pk]) = st.a3;                                \
         *reinterpret_cast<uint4*>(&Bs[buf][prow][pk]) = st.b0;                                     \
-        *reinterpret_cast<uint4*>(&Bs[buf][prow + 64][pk]) = st.b1;                                \
+        *reinterpret_cast<uint4*>(&Bs[buf][prow + 32][pk]) = st.b1;                                \
+        *reinterpret_cast<uint4*>(&Bs[buf][prow + 64][pk]) = st.b2;                                \
+        *reinterpret_cast<uint4*>(&Bs[buf][prow + 96][pk]) = st.b3;                                \
     }
 #define DQ_MULTIPLY(cur) multiply_tile(As[cur], Bs[cur], acc, wm, wn, lrow, lk);
-    // tile kt is in LDS buffer `buf`, tile kt+1 in (fa_next, fb_next); tile kt+4 is requested into the registers that
-    // held tile kt
+    // tile kt is in LDS buffer `buf`, tile kt+1 in st_next; tile kt+2 is requested into the registers that held tile kt
 #define DQ_STEP(kt, buf, st_next, st_free)                                                         \
     {                                                                                              \
-        DQ_FETCH((kt) + 4, st_free)                                                                \
+        DQ_FETCH((kt) + 2, st_free)                                                                \
         DQ_MULTIPLY(buf)                                                                           \
         if ((kt) + 1 < nk) { DQ_STASH(1 - (buf), st_next) }                                        \
         __syncthreads();                                                                           \
     }
-    st0.a0 = st0.a1 = st0.b0 = st0.b1 = make_uint4(0u, 0u, 0u, 0u);
-    st1 = st0; st2 = st0; st3 = st0;
+    st0.a0 = st0.a1 = st0.a2 = st0.a3 = st0.b0 = st0.b1 = st0.b2 = st0.b3 = make_uint4(0u, 0u, 0u, 0u);
+    st1 = st0;
     DQ_FETCH(0, st0)
     DQ_FETCH(1, st1)
-    DQ_FETCH(2, st2)
-    DQ_FETCH(3, st3)
     DQ_STASH(0, st0)
     __syncthreads();
-    for (int kt = 0; kt < nk; kt += 4) {
+    for (int kt = 0; kt < nk; kt += 2) {
         DQ_STEP(kt, 0, st1, st0)
-        DQ_STEP(kt + 1, 1, st2, st1)
-        DQ_STEP(kt + 2, 0, st3, st2)
-        DQ_STEP(kt + 3, 1, st0, st3)
+        DQ_STEP(kt + 1, 1, st0, st1)
     }
 #undef DQ_STEP
 #undef DQ_MULTIPLY
@@ -347,7 +353,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int 
         typedef float f32x2 __attribute__((ext_vector_type(2)));
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         constexpr int SLD = BM + 8;          // halfwords per staged row (272 bytes)
-        static_assert(BN * SLD <= 2 * BM * LDH + 2 * BN * LDH, "the staged tile must fit the operand buffers");
+        static_assert(BN * SLD <= 2 * BM * LDD + 2 * BN * LDD, "the staged tile must fit the operand buffers");
         bf16_t* stage = smem;                // [BN][SLD]; the K loop ended with a barrier: the buffers are free
         const float scale = g.whip_scale;
         float lsum = 0.f;
@@ -398,8 +404,8 @@ bool gemm_bf16_deep_fits(const GemmBf16& g) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const bool avec = (reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 7) == 0;
     const bool bvec = (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0;
-    return !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (4 * BK) == 0 &&
-           tiles_m * tiles_n >= 256 && avec && bvec && (g.a_kwrap == 0 || (g.a_kwrap % BK == 0 && g.a_klim == g.a_kwrap));
+    return !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (2 * BKD) == 0 &&
+           tiles_m * tiles_n >= 256 && avec && bvec && (g.a_kwrap == 0 || (g.a_kwrap % BKD == 0 && g.a_klim == g.a_kwrap));
 }
 
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
