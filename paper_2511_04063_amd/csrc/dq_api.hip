@@ -735,6 +735,7 @@ dq_status check_heads_ws(dq_ctx* c, const HeadsLayout& H) {
 
 dq_status heads_qr(dq_ctx* c, int b, const float* Z, long ldz, float* R, long ldr, float* U, long ldu) {
     const int n = kHeadDim;
+    if (b < 1) return DQ_OK;
     LaunchScope sc(&c->prof, c->stream, DQ_K_PANEL, b * (10.0 / 3.0) * n * (double)n * n, 0.0);
     DQ_HIP(launch_heads_qr(b, Z, ldz, (long)n * ldz, R, ldr, (long)n * ldr, U, ldu, (long)n * ldu,
                            at<unsigned>(c, 0), c->stream));
@@ -744,6 +745,7 @@ dq_status heads_qr(dq_ctx* c, int b, const float* Z, long ldz, float* R, long ld
 dq_status heads_rotate_loss_grad(dq_ctx* c, const HeadsLayout& H, int b, int T, const void* X, long ldx, const float* R,
                                  long ldr, dq_reduce red, float* loss_dev, float* G, long ldg) {
     const int n = kHeadDim;
+    if (b < 1) return DQ_OK;
     const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
     LaunchScope sc(&c->prof, c->stream, DQ_K_GEMM_BF16, b * 4.0 * T * (double)n * n, b * 2.0 * T * (double)n);
     DQ_HIP(launch_heads_rlg(b, T, static_cast<const bf16_t*>(X), ldx, (long)T * ldx, R, ldr, (long)n * ldr, scale,
@@ -758,6 +760,7 @@ dq_status heads_backward(dq_ctx* c, const HeadsLayout& H, int b, const float* R,
                          const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr) {
     const int n = kHeadDim;
     const long nn = (long)n * n;
+    if (b < 1) return DQ_OK;
     hipStream_t s = c->stream;
     unsigned* flags = at<unsigned>(c, 0);
     float* Bb = at<float>(c, H.B);

@@ -857,8 +857,13 @@ def test_errors_have_no_effect(ctx):
     assert c3.lib.dq_qr_orth(c3.h, 1, n, Z.data_ptr(), n, R.data_ptr(), n, None, 0) == B.DQ_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.all(R == 7.0) and torch.all(G == 7.0) and loss.item() == 0.0
-    # b == 0 is a no-op
+    # b == 0 is a no-op, on the general route and on the batched 128 x 128 one
     assert lib.dq_qr_orth(h, 0, n, Z.data_ptr(), n, R.data_ptr(), n, None, 0) == B.DQ_OK
+    assert lib.dq_qr_orth(h, 0, 128, Z.data_ptr(), 128, R.data_ptr(), 128, None, 0) == B.DQ_OK
+    assert lib.dq_qr_backward(h, 0, 128, Z.data_ptr(), 128, Z.data_ptr(), 128, Z.data_ptr(), 128, R.data_ptr(), 128) == B.DQ_OK
+    Xh = torch.zeros(8, 128, device="cuda", dtype=torch.bfloat16)
+    assert lib.dq_calib_step(h, 0, 8, 128, Xh.data_ptr(), B.DQ_BF16, 128, Z.data_ptr(), 128, 0.1, 0, loss.data_ptr(),
+                             None, 0) == B.DQ_OK
     torch.cuda.synchronize()
     assert torch.all(R == 7.0)
     c2.close(); c3.close()
