@@ -136,6 +136,12 @@ dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
                          const float* R, long ldr, const float* U, long ldu,
                          const float* G, long ldg, float* dZ, long lddz);
 
+/* Sec. 4.1, Eq. 1, the quantity the calibration drives down: counts_dev[i] = number of entries of the rotated block
+ * Y_i (T x n fp32, b problems) with |y| > tau.  An evaluation metric, not part of the step.  counts_dev: b DEVICE
+ * 64-bit unsigned integers (8-byte aligned), overwritten.  NaN entries are not counted. */
+dq_status dq_outlier_count(dq_ctx* ctx, int b, int T, int n, const float* Y, long ldy, float tau,
+                           unsigned long long* counts_dev);
+
 /* Alg. 1 line 5, token sampling: X_out[i][t][:] = X_all[i][idx[i*T_out + t]][:] for t < T_out, b independent
  * problems (X_all: b blocks of T_all rows, X_out: b blocks of T_out rows, both with n columns of `dtype`).
  * Which tokens are kept (the paper samples 10 % of them at random) is the caller's choice: idx is a DEVICE array of

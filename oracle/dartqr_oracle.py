@@ -66,6 +66,7 @@ __all__ = [
     "calibrate",
     "rotate_loss_grad",
     "token_sampling",
+    "outlier_count",
 ]
 
 
@@ -128,6 +129,17 @@ def qr_orth(Z):
     R = Q * s[None, :]
     U = U0 * s[:, None]
     return R, U
+
+
+def outlier_count(Y, tau: float) -> int:
+    """Sec. 4.1, Eq. 1 summed over the tokens of a block: how many entries have |y| > tau."""
+    Y = np.asarray(Y)
+    count = 0
+    for row in Y.reshape(-1, Y.shape[-1]) if Y.ndim > 1 else [Y]:
+        for y in row:
+            if abs(float(y)) > tau:
+                count += 1
+    return count
 
 
 def token_sampling(X, idx) -> np.ndarray:

@@ -38,6 +38,7 @@ SIGNATURES = {
     "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
+    "dq_outlier_count": (_i, [_vp, _i, _i, _i, _vp, _l, _f, _vp]),
     "dq_gather_rows": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _l, _vp, _vp, _l]),
     "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
     "dq_sgd_momentum_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _f, _f]),
@@ -205,6 +206,12 @@ class Context:
                                                 _ld(m), _ptr(v), _ld(v), int(step), float(lr), float(beta1),
                                                 float(beta2), float(eps), reduce, _ptr(loss), _ptr(R), _ld(R)),
                     "dq_calib_step_adam")
+
+    def dq_outlier_count(self, Y, tau, counts):
+        b = Y.shape[0] if Y.dim() == 3 else 1
+        T, n = Y.shape[-2], Y.shape[-1]
+        self._check(self.lib.dq_outlier_count(self.h, b, T, n, _ptr(Y), _ld(Y), float(tau), _ptr(counts)),
+                    "dq_outlier_count")
 
     def dq_gather_rows(self, X_all, dtype, idx, X_out):
         b = X_all.shape[0] if X_all.dim() == 3 else 1

@@ -1025,6 +1025,20 @@ dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, cons
     return DQ_OK;
 }
 
+dq_status dq_outlier_count(dq_ctx* c, int b, int T, int n, const float* Y, long ldy, float tau,
+                           unsigned long long* counts_dev) {
+    if (c == nullptr || counts_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1 || n < 1) return DQ_ERR_SHAPE;
+    DQ_TRY(check_f32(Y, ldy, n));
+    if ((reinterpret_cast<uintptr_t>(counts_dev) & 7) != 0) return DQ_ERR_ALIGN;
+    if (b == 0) return DQ_OK;
+    LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 0.0, 4.0 * b * T * (double)n);
+    DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(counts_dev), 2L * b, 0u, c->stream));
+    for (int i = 0; i < b; ++i)
+        DQ_HIP(launch_outlier_count(Y + (long)i * T * ldy, ldy, T, n, tau, counts_dev + i, c->stream));
+    return DQ_OK;
+}
+
 dq_status dq_gather_rows(dq_ctx* c, int b, int T_all, int T_out, int n, const void* X_all, dq_dtype dtype,
                          long ldx_all, const int* idx, void* X_out, long ldx_out) {
     if (c == nullptr || idx == nullptr) return DQ_ERR_NULL;

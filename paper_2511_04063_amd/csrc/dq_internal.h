@@ -134,6 +134,9 @@ hipError_t launch_heads_rlg(int b, int T, const bf16_t* X, long ldx, long sx, co
                             float scale, float* Gpart, double* lpart, float* G, long ldg, long sg, float* loss,
                             unsigned* flags, hipStream_t s);
 
+// *count += number of entries of the T x n matrix Y with |y| > tau (count must hold the starting value)
+hipError_t launch_outlier_count(const float* Y, long ldy, int T, int n, float tau, unsigned long long* count,
+                                hipStream_t s);
 // out row t = src row idx[t] (row_bytes a multiple of 16, 16-byte aligned rows); bad indices raise DQ_FLAG_BAD_INDEX
 hipError_t launch_gather_rows(const void* src, long src_stride_bytes, int rows_in, const int* idx, int rows_out,
                               int row_bytes, void* out, long out_stride_bytes, unsigned* flags, hipStream_t s);

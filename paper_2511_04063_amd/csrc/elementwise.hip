@@ -204,6 +204,31 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
     }
 }
 
+// count += #{(t, c) : |Y[t][c]| > tau}: the objective the calibration is a smooth stand-in for (Sec. 4.1, Eq. 1), used
+// as an evaluation metric.  Integer atomics: the result does not depend on the order of the additions.
+__global__ __launch_bounds__(256) void outlier_count_kernel(const float* __restrict__ Y, long ldy, int T, int n, float tau,
+                                                            unsigned long long* __restrict__ count) {
+    const int cpr = (n + 3) >> 2;
+    const long chunks = (long)T * cpr;
+    const bool vec = (reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0;
+    unsigned local = 0;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < chunks; e += (long)gridDim.x * 256) {
+        const int row = (int)(e / cpr);
+        const int c0 = (int)(e - (long)row * cpr) << 2;
+        const float* src = Y + (long)row * ldy + c0;
+        if (vec && c0 + 3 < n) {
+            const float4 v = *reinterpret_cast<const float4*>(src);
+            local += (fabsf(v.x) > tau) + (fabsf(v.y) > tau) + (fabsf(v.z) > tau) + (fabsf(v.w) > tau);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (c0 + j < n) local += fabsf(src[j]) > tau;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) local += __shfl_xor(local, o);
+    if ((threadIdx.x & 63) == 0 && local != 0) atomicAdd(count, (unsigned long long)local);
+}
+
 // out[t][:] = src[idx[t]][:] for t < rows_out: the token-sampling step in front of the loop (Alg. 1 line 5) as a
 // gather of whole rows, 16 bytes per lane (row_bytes is a multiple of 16, rows 16-byte aligned).  An index outside
 // [0, rows_in) copies nothing for that row and raises the flag.
@@ -412,6 +437,15 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int col
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((rows >> 6) * (cols >> 6)), dim3(256), 0, s, src, lds_, rows, cols,
                        dst, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_outlier_count(const float* Y, long ldy, int T, int n, float tau, unsigned long long* count,
+                                hipStream_t s) {
+    if (T <= 0 || n <= 0) return hipSuccess;
+    long blocks = ((long)T * ((n + 3) / 4) + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(outlier_count_kernel, dim3((unsigned)blocks), dim3(256), 0, s, Y, ldy, T, n, tau, count);
     return hipGetLastError();
 }
 

@@ -826,6 +826,48 @@ def test_gather_rows_bit_exact(ctx, bf16):
                                   Od.data_ptr(), n + 16) == B.DQ_OK
 
 
+# ----------------------------------------------------------------------------------- outlier count
+def test_outlier_count_bit_exact(ctx):
+    b, T, n = 2, 301, 70
+    g = rng(8200)
+    Y = (g.standard_normal((b, T, n)) * np.exp(g.standard_normal((b, 1, n)))).astype(np.float32)
+    Y[0, 5, 7] = np.nan
+    Y[1, 0, 0] = 2.5                      # equal to the threshold: not an outlier
+    _, Yd = padded3(b, T, n, 76); Yd.copy_(dev(Y))
+    counts = torch.full((b,), -1, dtype=torch.int64, device="cuda")
+    for tau in (2.5, 0.0, 1e6):
+        ctx.dq_outlier_count(Yd, tau, counts)
+        got = counts.cpu().numpy()
+        for i in range(b):
+            assert got[i] == orc.outlier_count(Y[i], tau)
+    # along a short calibration run on the tiny workload: the count is evaluated on the GPU's own rotated block,
+    # bit-exact against the oracle before and after
+    cfg = synth.scaled_config("tiny", T=512)
+    inp = synth.make_inputs(cfg, seed=4)
+    X, Z0 = inp["X"][0], inp["Z0"][0]
+    c2 = B.Context()
+    try:
+        c2.ensure_workspace(1, cfg.n, cfg.T, B.DQ_F32)
+        Xd, Zd = dev(X), dev(Z0.copy())
+        Rd = torch.empty((cfg.n, cfg.n), device="cuda"); Gd = torch.empty_like(Rd)
+        Yb = torch.empty((cfg.T, cfg.n), device="cuda"); dYb = torch.empty_like(Yb)
+        loss = torch.zeros(1, device="cuda"); cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+        seen = []
+        for it in range(2):
+            c2.dq_qr_orth(Zd, Rd)
+            c2.dq_rotate_loss_grad(Xd, B.DQ_F32, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd, Yb, dYb)
+            c2.dq_outlier_count(Yb, 4.0, cnt)
+            assert cnt.item() == orc.outlier_count(Yb.cpu().numpy(), 4.0)
+            seen.append((loss.item(), cnt.item()))
+            for _ in range(15):
+                c2.dq_calib_step(Xd, B.DQ_F32, Zd, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss)
+        assert seen[1][0] < seen[0][0]            # the loss went down over the 15 steps in between
+        assert c2.dq_device_flags() == 0
+    finally:
+        torch.cuda.synchronize()
+        c2.close()
+
+
 # ----------------------------------------------------------------------------------- error paths
 def test_errors_have_no_effect(ctx):
     n = 64

@@ -526,3 +526,29 @@ def test_token_sampling_invariants():
         orc.token_sampling(X, [0, T])
     with pytest.raises(IndexError):
         orc.token_sampling(X, [-1])
+
+
+# ----------------------------------------------------------------------------------- outlier count (Sec. 4.1, Eq. 1)
+def test_outlier_count_pins():
+    g = np.random.Generator(np.random.Philox(902))
+    Y = g.standard_normal((37, 11))
+    # hand-made case
+    assert orc.outlier_count(np.array([[0.0, -3.0, 2.0], [2.5, -2.5, 7.0]]), 2.5) == 2      # strictly greater
+    # against the vectorised definition, and its elementary properties
+    for tau in (0.0, 0.5, 1.0, 2.0, 10.0):
+        assert orc.outlier_count(Y, tau) == int(np.sum(np.abs(Y) > tau))
+    assert orc.outlier_count(Y, 0.0) == Y.size
+    assert orc.outlier_count(Y, np.abs(Y).max()) == 0
+    counts = [orc.outlier_count(Y, t) for t in (0.1, 0.5, 1.0, 2.0)]
+    assert counts == sorted(counts, reverse=True)
+    assert orc.outlier_count(-Y[::-1, ::-1], 1.0) == orc.outlier_count(Y, 1.0)
+    # a per-token sum: the count of a block is the sum of the counts of its rows
+    assert orc.outlier_count(Y, 1.0) == sum(orc.outlier_count(Y[t], 1.0) for t in range(Y.shape[0]))
+    # the reason the paper rotates at all: a vector with one massive entry has an outlier, its image under a
+    # rotation that spreads it evenly (a normalised Hadamard matrix) has none at the same threshold
+    H = np.array([[1.0]])
+    for _ in range(3):
+        H = np.block([[H, H], [H, -H]])
+    H /= np.sqrt(8.0)
+    x = np.zeros((1, 8)); x[0, 3] = 8.0
+    assert orc.outlier_count(x, 3.0) == 1 and orc.outlier_count(orc.rotate(x, H), 3.0) == 0
