@@ -52,7 +52,7 @@ struct dq_ctx {
     std::vector<hipEvent_t> sync_ev; // 2 per panel: look-ahead part done (even), trailing part done (odd); + 1 join
     int device = 0;
     int nb = kPanel;                 // QR panel width (<= kPanel)
-    int chol_min_m = 128;            // panels at least this tall take the many-CU route (0: never)
+    int chol_min_m = 64;             // full-width panels at least this tall take the many-CU route (0: never)
     bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
     int accum_panels = 2;            // panels merged per update of the accumulated R (1: panel by panel; 2 measured
                                      // best at n = 4096, 2 and 4 equal at n = 8192)

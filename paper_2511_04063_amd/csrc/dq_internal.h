@@ -90,12 +90,13 @@ hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long
 size_t panel_scratch_floats(int m);
 hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float* vscratch, float* tslices,
                            int* slice_width, unsigned* flags, hipStream_t s);
-// Tall m x 64 panel by CholeskyQR2 + Householder reconstruction on many compute units, in two calls.
+// m x 64 panel (m >= 64) by CholeskyQR2 + Householder reconstruction on many compute units, in two calls.
 // launch_cholqr_factor: everything up to the top 64 x 64 block: triangular factor and the first 64 rows of the
 //   reflectors in A (as launch_qr_panel leaves them, except that row signs of the triangular factor may differ), T
 //   (64 x 64, ld 64) in Tout, the first 64 rows of Yp = V T (m x 64, ld 64).  have_gram != 0: the Gram partials of
 //   the panel are already in the scratch (left there by the previous panel's launch_cholqr_finish).
-// launch_cholqr_finish: the rows of V and Yp below the block.  lookahead != 0 (needs m >= 128): it also applies the
+// launch_cholqr_finish: the rows of V and Yp below the block (none for m == 64).  lookahead != 0 (needs m >= 128):
+//   it also applies the
 //   panel's block reflector to the next 64 columns A[:, 64:128] (so these must have received every earlier update
 //   before this call), and with next_gram != 0 leaves the Gram partials of the next panel A[64:, 64:128] behind.
 // q1: m x 64 floats of scratch (also the panel kernel's reflector scratch); scratch: cholpanel_scratch_floats()

@@ -807,7 +807,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 1) * B64 * B64 + 4 * B64 * B64 + 64; }
 
 bool cholpanel_supported(const float* A, long lda, int m, int jb) {
-    return jb == B64 && m >= 2 * B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
+    return jb == B64 && m >= B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
 }
 
 namespace {
@@ -857,8 +857,9 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
                                 int next_gram, hipStream_t s) {
     const TallScratch ts(scratch);
     if (!lookahead) {
-        const int below = (m - B64 + RT - 1) / RT;
-        hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb);
+        const int below = (m - B64 + RT - 1) / RT;   // a square last panel has no rows below its top block
+        if (below > 0)
+            hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb);
         return hipGetLastError();
     }
     // the rows below the top block are split exactly as the next panel (m - 64 rows) splits its own rows

@@ -222,6 +222,31 @@ def test_qr_orth_ill_conditioned_panel_falls_back(ctx):
     assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
 
 
+def test_qr_orth_ill_conditioned_last_panel_falls_back(ctx):
+    """The same inside the last, square 64 x 64 panel (which also takes the Gram-matrix route): nearly parallel
+    columns there make the route hand over to the Householder code in the same kernel."""
+    n = 192
+    g = rng(4600)
+    Z = g.standard_normal((n, n))
+    Z[:, 190] = Z[:, 187] + 1e-5 * g.standard_normal(n)
+    Z = Z.astype(np.float32)
+    R, U = run_qr(ctx, Z)
+    assert ctx.dq_device_flags() == B.DQ_FLAG_ILLCOND_PANEL
+    Ro, Uo = orc.qr_orth(Z)
+    cond = np.linalg.cond(Z.astype(np.float64))
+    assert np.abs(R.astype(np.float64).T @ R - np.eye(n)).max() <= 1e-5
+    assert rel(R.astype(np.float64) @ U, Z) < 1e-5
+    assert rel(U, Uo) < max(1e-4, 2e-7 * cond)
+    assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+    # and a well-conditioned square panel alone (n = 64): the whole factorisation is that one panel
+    Z64 = g.standard_normal((64, 64)).astype(np.float32)
+    R, U = run_qr(ctx, Z64)
+    Ro, Uo = orc.qr_orth(Z64)
+    assert ctx.dq_device_flags() == 0
+    assert np.abs(R.astype(np.float64).T @ R - np.eye(64)).max() <= 1e-5
+    assert rel(U, Uo) < 1e-4 and rel(R, Ro) < max(1e-4, 2e-7 * np.linalg.cond(Z64.astype(np.float64)))
+
+
 def test_qr_orth_without_u_and_with_wide_ld(ctx):
     n = 200
     Z = rng(4100).standard_normal((n, n)).astype(np.float32)
