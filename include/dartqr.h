@@ -136,6 +136,13 @@ dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
                          const float* R, long ldr, const float* U, long ldu,
                          const float* G, long ldg, float* dZ, long lddz);
 
+/* The initial latent of the paper's runs (App., hyper-parameter settings: "a random Hadamard matrix"), read as
+ * Z0_i = diag(s_i) H_n / sqrt(n) with H_n the Sylvester Hadamard matrix, H[r][c] = (-1)^popcount(r & c): an
+ * orthogonal matrix for signs s = +-1.  n must be a power of two (DQ_ERR_UNSUPPORTED otherwise).  The random signs
+ * are the caller's: signs_dev holds b*n DEVICE floats (row r of problem i is scaled by signs_dev[i*n + r]).
+ * Z: out, b matrices. */
+dq_status dq_hadamard_init(dq_ctx* ctx, int b, int n, const float* signs_dev, float* Z, long ldz);
+
 /* Sec. 4.1, Eq. 1, the quantity the calibration drives down: counts_dev[i] = number of entries of the rotated block
  * Y_i (T x n fp32, b problems) with |y| > tau.  An evaluation metric, not part of the step.  counts_dev: b DEVICE
  * 64-bit unsigned integers (8-byte aligned), overwritten.  NaN entries are not counted. */

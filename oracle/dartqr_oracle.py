@@ -44,6 +44,9 @@ Readings taken where the paper is silent (each is also listed in the design note
   sample-size analysis) and does not say how they are drawn.  The draw is an INPUT here
   (a list of row numbers, repeats allowed); the step itself is the selection of those
   rows, in the given order.  Pinned by its invariants (tests/).
+* App. (hyper-parameter settings): "Z0 is initialized using a random Hadamard matrix", construction not given.  Read
+  as diag(s) H_n / sqrt(n) with Sylvester's H_n and random signs s supplied by the caller.  Pinned by orthogonality,
+  the Kronecker form and the bit-count form of the entries (tests/).
 """
 
 from __future__ import annotations
@@ -67,6 +70,7 @@ __all__ = [
     "rotate_loss_grad",
     "token_sampling",
     "outlier_count",
+    "hadamard_latent",
 ]
 
 
@@ -129,6 +133,19 @@ def qr_orth(Z):
     R = Q * s[None, :]
     U = U0 * s[:, None]
     return R, U
+
+
+def hadamard_latent(signs) -> np.ndarray:
+    """The initial latent of the paper's runs (App., hyper-parameter settings), read as diag(s) H_n / sqrt(n) with H_n
+    built by Sylvester's doubling  H_1 = [1],  H_2m = [[H_m, H_m], [H_m, -H_m]];  n = len(s) a power of two."""
+    s = _f64(signs)
+    n = s.shape[0]
+    if n < 1 or n & (n - 1):
+        raise ValueError("n must be a power of two")
+    H = np.array([[1.0]])
+    while H.shape[0] < n:
+        H = np.block([[H, H], [H, -H]])
+    return (s[:, None] * H) / np.sqrt(float(n))
 
 
 def outlier_count(Y, tau: float) -> int:

@@ -38,6 +38,7 @@ SIGNATURES = {
     "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
+    "dq_hadamard_init": (_i, [_vp, _i, _i, _vp, _vp, _l]),
     "dq_outlier_count": (_i, [_vp, _i, _i, _i, _vp, _l, _f, _vp]),
     "dq_gather_rows": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _l, _vp, _vp, _l]),
     "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
@@ -206,6 +207,10 @@ class Context:
                                                 _ld(m), _ptr(v), _ld(v), int(step), float(lr), float(beta1),
                                                 float(beta2), float(eps), reduce, _ptr(loss), _ptr(R), _ld(R)),
                     "dq_calib_step_adam")
+
+    def dq_hadamard_init(self, signs, Z):
+        b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
+        self._check(self.lib.dq_hadamard_init(self.h, b, n, _ptr(signs), _ptr(Z), _ld(Z)), "dq_hadamard_init")
 
     def dq_outlier_count(self, Y, tau, counts):
         b = Y.shape[0] if Y.dim() == 3 else 1

@@ -1025,6 +1025,19 @@ dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, cons
     return DQ_OK;
 }
 
+dq_status dq_hadamard_init(dq_ctx* c, int b, int n, const float* signs_dev, float* Z, long ldz) {
+    if (c == nullptr || signs_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if ((n & (n - 1)) != 0) return DQ_ERR_UNSUPPORTED;
+    DQ_TRY(check_f32(Z, ldz, n));
+    for (int i = 0; i < b; ++i) {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 0.0, 4.0 * n * (double)n);
+        DQ_HIP(launch_hadamard_init(signs_dev + (long)i * n, n, Z + (long)i * n * ldz, ldz, c->stream));
+    }
+    return DQ_OK;
+}
+
 dq_status dq_outlier_count(dq_ctx* c, int b, int T, int n, const float* Y, long ldy, float tau,
                            unsigned long long* counts_dev) {
     if (c == nullptr || counts_dev == nullptr) return DQ_ERR_NULL;

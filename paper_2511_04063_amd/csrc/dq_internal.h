@@ -135,6 +135,8 @@ hipError_t launch_heads_rlg(int b, int T, const bf16_t* X, long ldx, long sx, co
                             float scale, float* Gpart, double* lpart, float* G, long ldg, long sg, float* loss,
                             unsigned* flags, hipStream_t s);
 
+// Z = diag(sgn) H_n / sqrt(n), H_n the Sylvester Hadamard matrix (n a power of two)
+hipError_t launch_hadamard_init(const float* sgn, int n, float* Z, long ldz, hipStream_t s);
 // *count += number of entries of the T x n matrix Y with |y| > tau (count must hold the starting value)
 hipError_t launch_outlier_count(const float* Y, long ldy, int T, int n, float tau, unsigned long long* count,
                                 hipStream_t s);

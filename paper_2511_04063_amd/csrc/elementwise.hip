@@ -4,6 +4,7 @@
 //   * P = strict_lower(B - B^T) of the derivative through Z = R U,
 //   * inverses of the diagonal blocks of U for the blocked triangular solve,
 //   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
+#include <math.h>
 #include <stdlib.h>
 
 #include "dq_internal.h"
@@ -213,6 +214,18 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __res
             w[k] = lo | (hi << 16);
         }
         *reinterpret_cast<uint4*>(dst + (long)(c0 + c) * ldd + r0 + part * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// Z[i][j] = s[i] * (-1)^popcount(i & j) * c  with c = 1 / sqrt(n): a randomised Hadamard matrix (Sylvester construction,
+// n a power of two), the initial latent of the paper's runs (App., hyper-parameter settings).  The signs are an input.
+__global__ __launch_bounds__(256) void hadamard_init_kernel(const float* __restrict__ sgn, int n, float c,
+                                                            float* __restrict__ Z, long ldz) {
+    const long total = (long)n * n;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int i = (int)(e / n), j = (int)(e % n);
+        const float h = (__popc((unsigned)(i & j)) & 1) ? -c : c;
+        Z[(long)i * ldz + j] = sgn[i] * h;
     }
 }
 
@@ -453,6 +466,14 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds_, int rows, int col
         return hipErrorInvalidValue;
     hipLaunchKernelGGL(transpose_bf16_kernel, dim3((rows >> 6) * (cols >> 6)), dim3(256), 0, s, src, lds_, rows, cols,
                        dst, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_hadamard_init(const float* sgn, int n, float* Z, long ldz, hipStream_t s) {
+    long blocks = ((long)n * n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    const float c = (float)(1.0 / sqrt((double)n));
+    hipLaunchKernelGGL(hadamard_init_kernel, dim3((unsigned)blocks), dim3(256), 0, s, sgn, n, c, Z, ldz);
     return hipGetLastError();
 }
 

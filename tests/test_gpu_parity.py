@@ -893,6 +893,28 @@ def test_outlier_count_bit_exact(ctx):
         c2.close()
 
 
+# ----------------------------------------------------------------------------------- Hadamard initial latent
+def test_hadamard_init_bit_exact(ctx):
+    g = rng(8300)
+    for b, n, ld in ((1, 1, 4), (2, 64, 64), (3, 256, 264)):
+        s = g.choice([-1.0, 1.0], (b, n)).astype(np.float32)
+        _, Zd = padded3(b, n, n, ld)
+        ctx.dq_hadamard_init(dev(s), Zd)
+        Z = Zd.cpu().numpy()
+        for i in range(b):
+            assert np.array_equal(Z[i], orc.hadamard_latent(s[i]).astype(np.float32))
+    # the paper's starting point: the rotation of a Hadamard latent is the latent itself, U = I
+    n = 256
+    s = g.choice([-1.0, 1.0], n).astype(np.float32)
+    Zd = torch.empty((n, n), device="cuda")
+    ctx.dq_hadamard_init(dev(s), Zd)
+    Rd = torch.empty_like(Zd); Ud = torch.empty_like(Zd)
+    ctx.dq_qr_orth(Zd, Rd, Ud)
+    assert (Rd - Zd).abs().max().item() < 2e-6 and (Ud - torch.eye(n, device="cuda")).abs().max().item() < 2e-6
+    assert ctx.dq_device_flags() == 0
+    assert ctx.lib.dq_hadamard_init(ctx.h, 1, 96, dev(s).data_ptr(), Zd.data_ptr(), n) == B.DQ_ERR_UNSUPPORTED
+
+
 # ----------------------------------------------------------------------------------- error paths
 def test_errors_have_no_effect(ctx):
     n = 64

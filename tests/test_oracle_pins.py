@@ -552,3 +552,29 @@ def test_outlier_count_pins():
     H /= np.sqrt(8.0)
     x = np.zeros((1, 8)); x[0, 3] = 8.0
     assert orc.outlier_count(x, 3.0) == 1 and orc.outlier_count(orc.rotate(x, H), 3.0) == 0
+
+
+# ----------------------------------------------------------------------------------- Hadamard initial latent
+def test_hadamard_latent_pins():
+    g = np.random.Generator(np.random.Philox(903))
+    for n in (1, 2, 8, 64):
+        s = g.choice([-1.0, 1.0], n)
+        Z = orc.hadamard_latent(s)
+        assert Z.shape == (n, n)
+        assert np.allclose(Z.T @ Z, np.eye(n), atol=1e-14) and np.allclose(Z @ Z.T, np.eye(n), atol=1e-14)
+        assert np.allclose(np.abs(Z), 1.0 / np.sqrt(n), rtol=1e-15)
+        # entries by the bit-count form, H[r][c] = (-1)^popcount(r & c)
+        r, c = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+        par = np.array([[bin(int(a) & int(b)).count("1") & 1 for b in range(n)] for a in range(n)])
+        assert np.array_equal(np.sign(Z), s[:, None] * np.where(par == 1, -1.0, 1.0))
+        # Kronecker power of H_2
+        K = np.array([[1.0]])
+        for _ in range(int(np.log2(n))):
+            K = np.kron(np.array([[1.0, 1.0], [1.0, -1.0]]), K)
+        assert np.allclose(Z, s[:, None] * K / np.sqrt(n), rtol=1e-15)
+    # an orthogonal latent is its own rotation up to the sign normalisation: R = Z diag(sign of the first ... ) and U = I
+    Z = orc.hadamard_latent(g.choice([-1.0, 1.0], 16))
+    R, U = orc.qr_orth(Z)
+    assert np.allclose(U, np.eye(16), atol=1e-13) and np.allclose(R, Z, atol=1e-13)
+    with pytest.raises(ValueError):
+        orc.hadamard_latent(np.ones(12))
