@@ -990,16 +990,17 @@ dq_status dq_whip_loss_grad(dq_ctx* c, int b, int T, int n, const float* Y, long
     double* lpart = at<double>(c, L.losspart);
     const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
     const size_t esz = (dydt == DQ_BF16) ? 2 : 4;
-    for (int i = 0; i < b; ++i) {
-        const int grid = whip_grid(T, n);
-        {
-            LaunchScope sc(&c->prof, c->stream, DQ_K_WHIP, 5.0 * T * (double)n, (double)T * n * (4.0 + esz));
-            DQ_HIP(launch_whip(Y + (long)i * T * ldy, ldy, T, n, scale,
-                               static_cast<char*>(dY) + (size_t)i * T * lddy * esz, dydt == DQ_BF16, lddy, lpart, grid,
-                               c->stream));
-        }
-        DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev + i, flags, c->stream));
+    if (b == 0) return DQ_OK;
+    // every problem of the batch in the same two launches; the partial sums of problem i sit at lpart + i * grid
+    int grid = whip_grid(T, n);
+    if ((long)grid * b > kLossPartials) grid = kLossPartials / b;
+    if (grid < 1) return DQ_ERR_UNSUPPORTED;
+    {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_WHIP, 5.0 * b * T * (double)n, (double)b * T * n * (4.0 + esz));
+        DQ_HIP(launch_whip(Y, ldy, T, n, scale, dY, dydt == DQ_BF16, lddy, lpart, grid, c->stream, b, (long)T * ldy,
+                           (long)T * lddy));
     }
+    DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, c->stream, b));
     return DQ_OK;
 }
 

@@ -170,8 +170,8 @@ hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* 
 // launch_loss_finish adds them up: loss = scale * sum.  dy_is_bf16 selects the dtype of dY.
 int whip_grid(long rows, int cols);
 hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
-                       double* partials, int grid, hipStream_t s);
+                       double* partials, int grid, hipStream_t s, int batch = 1, long stride_y = 0, long stride_dy = 0);
 hipError_t launch_loss_finish(const double* partials, int count, float scale, float* loss_dev, unsigned* flags,
-                              hipStream_t s);
+                              hipStream_t s, int batch = 1);
 
 }  // namespace dq

@@ -31,7 +31,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <bool BF16OUT>
 __global__ __launch_bounds__(256) void whip_kernel(const float* __restrict__ Y, long ldy, int T, int n, float scale,
                                                    void* __restrict__ dYv, long lddy, double* __restrict__ partials,
-                                                   int yvec, int dvec) {
+                                                   int yvec, int dvec, long sy, long sdy) {
+    // blockIdx.y: problem of a batch (element strides sy, sdy; gridDim.x partials per problem)
+    Y += (long)blockIdx.y * sy;
+    dYv = static_cast<char*>(dYv) + (long)blockIdx.y * sdy * (BF16OUT ? 2 : 4);
+    partials += (long)blockIdx.y * gridDim.x;
     const int cpr = (n + 7) >> 3;                 // 8-element chunks per row
     const long chunks = (long)T * cpr;
     float acc = 0.f;
@@ -142,6 +146,8 @@ __global__ __launch_bounds__(256) void whip_kernel(const float* __restrict__ Y, 
 __global__ __launch_bounds__(256) void loss_finish_kernel(const double* __restrict__ partials, int count, float scale,
                                                           float* __restrict__ loss_dev, unsigned* flags) {
     __shared__ double sh[256];
+    partials += (long)blockIdx.x * count;   // one workgroup per problem of a batch
+    loss_dev += blockIdx.x;
     double t = 0.0;
     for (int i = threadIdx.x; i < count; i += 256) t += partials[i];
     sh[threadIdx.x] = t;
@@ -426,28 +432,30 @@ int whip_grid(long rows, int cols) {
 }
 
 hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
-                       double* partials, int grid, hipStream_t s) {
+                       double* partials, int grid, hipStream_t s, int batch, long stride_y, long stride_dy) {
+    if (batch < 1) return hipSuccess;
     static const int flat = [] { const char* e = getenv("DQ_WHIP_FLAT"); return e ? atoi(e) : 1; }();
     // yvec: 0 scalar loads, 1 16-byte loads, 2 the flat path for dense rows, 3 the same with nontemporal loads
     // (Y beyond the 256 MiB last-level cache)
     static const long nt_bytes = [] { const char* e = getenv("DQ_WHIP_NT_MIB"); return (e ? atol(e) : 192L) << 20; }();
-    const bool big = (long)T * n * 4 > nt_bytes;
+    const bool big = (long)batch * T * n * 4 > nt_bytes;   // the whole batch streams through the cache
     const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? (flat ? (big ? 3 : 2) : 1) : 0;
     if (dy_is_bf16) {
         const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 7) == 0) ? 1 : 0;
-        hipLaunchKernelGGL((whip_kernel<true>), dim3(grid), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy, partials,
-                           yvec, dvec);
+        hipLaunchKernelGGL((whip_kernel<true>), dim3(grid, batch), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy,
+                           partials, yvec, dvec, stride_y, stride_dy);
     } else {
         const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 3) == 0) ? 1 : 0;
-        hipLaunchKernelGGL((whip_kernel<false>), dim3(grid), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy, partials,
-                           yvec, dvec);
+        hipLaunchKernelGGL((whip_kernel<false>), dim3(grid, batch), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy,
+                           partials, yvec, dvec, stride_y, stride_dy);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_loss_finish(const double* partials, int count, float scale, float* loss_dev, unsigned* flags,
-                              hipStream_t s) {
-    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(256), 0, s, partials, count, scale, loss_dev, flags);
+                              hipStream_t s, int batch) {
+    if (batch < 1) return hipSuccess;
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(batch), dim3(256), 0, s, partials, count, scale, loss_dev, flags);
     return hipGetLastError();
 }
 
