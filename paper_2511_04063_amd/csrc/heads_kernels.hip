@@ -11,9 +11,6 @@
 #include "dq_internal.h"
 #include "dq_wave.h"
 
-#ifndef DQ_HEADS_QR_SPLIT
-#define DQ_HEADS_QR_SPLIT 2
-#endif
 
 namespace dq {
 namespace {
@@ -32,6 +29,10 @@ __device__ __forceinline__ float wave_total(float v) {
     return v;
 }
 
+__device__ __forceinline__ float lane_value(float v, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+
 __device__ __forceinline__ uint32_t to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
@@ -43,59 +44,67 @@ __device__ __forceinline__ uint32_t to_bf16_rne(float f) {
 // Alg. 2 with the unnormalised reflector vector: for column j, x = A[j:, j], beta = -sign(x_0) ||x||,
 // u = x - beta e_0, H = I - gamma u u^T with gamma = 2 / u^T u  (the same reflection as the paper's normalised v);
 // a column that is already zero below the diagonal gets H = I.
-// Every column of A and every row of Q lives in the registers of QS adjacent lanes (lane part h holds the 4-row
-// groups g with g % QS == h); both kinds apply x <- x - gamma (u . x) u, the columns only for c > j, the partial dot
-// products of the QS lanes meeting through DPP.  The owners of column j + 1 publish it in LDS at the end of step j, so
-// a step needs one barrier; every wavefront forms the column norm itself.  Rows are handled in blocks of 16: blocks
-// above the diagonal block are skipped (the block index is a template parameter, so register indices are static and
-// a step runs straight-line code), the diagonal block substitutes u_0 for the raw pivot and zero above it.
-constexpr int QS = DQ_HEADS_QR_SPLIT;   // lanes per column / row
-constexpr int QB = 16;                  // rows per block
-constexpr int NG = HN / 4 / QS;         // 4-row groups held by a thread
-constexpr int GPB = QB / 4 / QS;        // of which per block
-static_assert(QS == 2 || QS == 4, "a block of 16 rows must hold a whole number of groups per lane");
+// 512 threads: four adjacent lanes ("item" i = tid / 4, part h = tid % 4) hold one column of A AND one row of Q in
+// registers, lane part h owning the 4-row groups g with g % 4 == h of both.  Both get x <- x - gamma (u . x) u (the
+// column only if it lies right of j), with ONE read of u from LDS for the two, the partial dot products of the four
+// lanes meeting through DPP.  Columns are dealt to the items round-robin over the wavefronts (item i holds column
+// 8 (i % 16) + i / 16), so that every wavefront keeps live columns to the end.  The owners of column j + 1 publish it in
+// LDS at the end of step j, so a step needs one barrier; every wavefront forms the column norm itself.  Rows are handled
+// in blocks of 16: blocks above the diagonal block are skipped (the block index is a template parameter, so register
+// indices are static and a step runs straight-line code), the diagonal block substitutes u_0 for the raw pivot and
+// zero above it.
+constexpr int QS = 4;                   // lanes per column / row
+constexpr int QB = 16;                  // rows per block = 4 groups, one per lane part
+constexpr int NG = HN / 4 / QS;         // 4-row groups held by a thread (of its column and of its row)
+
+__device__ __forceinline__ int item_column(int item) { return 8 * (item & 15) + (item >> 4); }
+__device__ __forceinline__ int column_item(int c) { return 16 * (c & 7) + (c >> 3); }
 
 // rows of this thread's k-th group: 4 * (k * QS + h) .. + 3
 template <int JB>
 __device__ __forceinline__ void publish_from(float* cb, const float (&x)[4 * NG], int h, int j) {
 #pragma unroll
-    for (int k = JB * GPB; k < NG; ++k) {
+    for (int k = JB; k < NG; ++k) {
         const int i = 4 * (k * QS + h);
         float4 v = make_float4(x[4 * k], x[4 * k + 1], x[4 * k + 2], x[4 * k + 3]);
-        if (k < (JB + 1) * GPB) {   // diagonal block: entries above the diagonal are published as zero
+        if (k == JB) {   // diagonal block: entries above the diagonal are published as zero
             v.x = i >= j ? v.x : 0.f; v.y = i + 1 >= j ? v.y : 0.f; v.z = i + 2 >= j ? v.z : 0.f; v.w = i + 3 >= j ? v.w : 0.f;
         }
         *reinterpret_cast<float4*>(cb + i) = v;
     }
 }
 
+// x <- x - gamma (u . x) u for this thread's part of its column (if live) and of its row of Q, for block row JB = j / 16
+// of the pivot; u is the published column with u_0 = uj in place of the raw pivot.
 template <int JB>
-__device__ __forceinline__ void reflect_from(const float* cb, float (&x)[4 * NG], int h, int j, float uj, float gamma) {
-    float4 u[NG - JB * GPB];
+__device__ __forceinline__ void reflect_from(const float* cb, float (&xc)[4 * NG], float (&xq)[4 * NG], bool col_live,
+                                             int h, int j, float uj, float gamma) {
+    float4 u[NG - JB];
 #pragma unroll
-    for (int k = JB * GPB; k < NG; ++k) {
-        const int i = 4 * (k * QS + h);
-        float4 v = *reinterpret_cast<const float4*>(cb + i);
-        if (k < (JB + 1) * GPB) {
-            v.x = i == j ? uj : v.x; v.y = i + 1 == j ? uj : v.y; v.z = i + 2 == j ? uj : v.z; v.w = i + 3 == j ? uj : v.w;
-        }
-        u[k - JB * GPB] = v;
+    for (int k = JB; k < NG; ++k) u[k - JB] = *reinterpret_cast<const float4*>(cb + 4 * (k * QS + h));
+    {   // diagonal block: the pivot entry becomes u_0 (the entries above it were published as zero)
+        const int i = 4 * (JB * QS + h);
+        float4& v = u[0];
+        v.x = i == j ? uj : v.x; v.y = i + 1 == j ? uj : v.y; v.z = i + 2 == j ? uj : v.z; v.w = i + 3 == j ? uj : v.w;
     }
-    float d0 = 0.f, d1 = 0.f;
+    // four independent partial sums per dot product: a lone dependent chain of 32 FMAs would set the pace of the step
+    float c0 = 0.f, c1 = 0.f, c2 = 0.f, c3 = 0.f, q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f;
 #pragma unroll
-    for (int k = JB * GPB; k < NG; ++k) {
-        const float4 v = u[k - JB * GPB];
-        d0 += v.x * x[4 * k] + v.y * x[4 * k + 1];
-        d1 += v.z * x[4 * k + 2] + v.w * x[4 * k + 3];
+    for (int k = JB; k < NG; ++k) {
+        const float4 v = u[k - JB];
+        c0 += v.x * xc[4 * k]; c1 += v.y * xc[4 * k + 1]; c2 += v.z * xc[4 * k + 2]; c3 += v.w * xc[4 * k + 3];
+        q0 += v.x * xq[4 * k]; q1 += v.y * xq[4 * k + 1]; q2 += v.z * xq[4 * k + 2]; q3 += v.w * xq[4 * k + 3];
     }
-    float d = d0 + d1;
-    d += lane_xor<1>(d);
-    if (QS == 4) d += lane_xor<2>(d);
-    const float f = gamma * d;
+    float dc = (c0 + c1) + (c2 + c3), dq = (q0 + q1) + (q2 + q3);
+    dc += lane_xor<1>(dc); dq += lane_xor<1>(dq);
+    dc += lane_xor<2>(dc); dq += lane_xor<2>(dq);
+    const float fc = col_live ? gamma * dc : 0.f;
+    const float fq = gamma * dq;
 #pragma unroll
-    for (int k = JB * GPB; k < NG; ++k) {
-        const float4 v = u[k - JB * GPB];
-        x[4 * k] -= f * v.x; x[4 * k + 1] -= f * v.y; x[4 * k + 2] -= f * v.z; x[4 * k + 3] -= f * v.w;
+    for (int k = JB; k < NG; ++k) {
+        const float4 v = u[k - JB];
+        xc[4 * k] -= fc * v.x; xc[4 * k + 1] -= fc * v.y; xc[4 * k + 2] -= fc * v.z; xc[4 * k + 3] -= fc * v.w;
+        xq[4 * k] -= fq * v.x; xq[4 * k + 1] -= fq * v.y; xq[4 * k + 2] -= fq * v.z; xq[4 * k + 3] -= fq * v.w;
     }
 }
 
@@ -111,84 +120,83 @@ __device__ __forceinline__ void reflect_from(const float* cb, float (&x)[4 * NG]
         default: CALL(7); break;                                                                   \
     }
 
-__global__ __launch_bounds__(2 * HN * QS) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
-                                                               float* __restrict__ R, long ldr, long sr,
-                                                               float* __restrict__ U, long ldu, long su,
-                                                               unsigned* flags) {
+__global__ __launch_bounds__(HN * QS) void heads_qr_kernel(const float* __restrict__ Z, long ldz, long sz,
+                                                           float* __restrict__ R, long ldr, long sr,
+                                                           float* __restrict__ U, long ldu, long su,
+                                                           unsigned* flags) {
     __shared__ __attribute__((aligned(16))) float cbuf[2][HN];
     __shared__ __attribute__((aligned(16))) float sgn[HN];
     const int tid = threadIdx.x, lane = tid & 63;
-    const bool is_col = tid < HN * QS;                       // uniform per wavefront
-    const int idx = (is_col ? tid : tid - HN * QS) / QS;     // column of A / row of Q held by this thread
-    const int h = tid % QS;                                  // which of its row groups
+    const int item = tid / QS, h = tid % QS;
+    const int col = item_column(item);   // this thread's column of A; its row of Q is `item`
     const float* Zp = Z + (long)blockIdx.x * sz;
-    float x[4 * NG];
+    float xc[4 * NG], xq[4 * NG];
 #pragma unroll
     for (int k = 0; k < NG; ++k)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int i = 4 * (k * QS + h) + e;
-            x[4 * k + e] = is_col ? Zp[(long)i * ldz + idx] : (i == idx ? 1.f : 0.f);
+            xc[4 * k + e] = Zp[(long)i * ldz + col];
+            xq[4 * k + e] = (i == item) ? 1.f : 0.f;
         }
     float mydiag = 0.f;
-    if (is_col && idx == 0) publish_from<0>(cbuf[0], x, h, 0);
+    if (col == 0) publish_from<0>(cbuf[0], xc, h, 0);
     __syncthreads();
     for (int j = 0; j < HN; ++j) {
         const float* cb = cbuf[j & 1];
-        float sv[1];
-        {
-            const float a0 = cb[lane], a1 = cb[lane + 64];
-            sv[0] = (lane > j ? a0 * a0 : 0.f) + (lane + 64 > j ? a1 * a1 : 0.f);
-        }
+        // column norm below the pivot: DPP inside the rows of 16 lanes, then the four row sums through scalar registers
+        const float a0 = cb[lane], a1 = cb[lane + 64];
         const float alpha = cb[j];
-        wave_reduce_multi<1>(sv, lane);
-        const float s = sv[0];
-        float beta = alpha;
+        float sr_ = (lane > j ? a0 * a0 : 0.f) + (lane + 64 > j ? a1 * a1 : 0.f);
+        sr_ += lane_xor<1>(sr_);
+        sr_ += lane_xor<2>(sr_);
+        sr_ += lane_xor<4>(sr_);
+        sr_ += lane_xor<8>(sr_);
+        const float s = (lane_value(sr_, 0) + lane_value(sr_, 16)) + (lane_value(sr_, 32) + lane_value(sr_, 48));
+        float beta = alpha;   // nothing below the pivot: H = I
         if (s != 0.f) {
-            const float nrm = sqrtf(alpha * alpha + s);
+            // hardware square root (1 ulp): beta only decides how exactly the column is annihilated; gamma is formed
+            // from the u that is applied, so that H is orthogonal whatever the rounding of beta
+            const float nrm = __builtin_amdgcn_sqrtf(alpha * alpha + s);
             beta = alpha >= 0.f ? -nrm : nrm;
             const float uj = alpha - beta;
-            // 2 / u^T u from the vector that is applied, so that H is orthogonal whatever the rounding of beta
             const float gamma = 2.f * __builtin_amdgcn_rcpf(s + uj * uj);
-            if (!is_col || idx > j) {
-#define DQ_CALL(JB) reflect_from<JB>(cb, x, h, j, uj, gamma)
-                DQ_BLOCK_SWITCH(j / QB, DQ_CALL)
+#define DQ_CALL(JB) reflect_from<JB>(cb, xc, xq, col > j, h, j, uj, gamma)
+            DQ_BLOCK_SWITCH(j / QB, DQ_CALL)
 #undef DQ_CALL
-            }
         }
-        if (is_col && idx == j) mydiag = beta;
+        if (col == j) mydiag = beta;
         if (tid == 0) sgn[j] = beta >= 0.f ? 1.f : -1.f;
-        if (is_col && idx == j + 1) {
+        if (col == j + 1) {
             float* nb = cbuf[(j + 1) & 1];
-#define DQ_CALL(JB) publish_from<JB>(nb, x, h, j + 1)
+#define DQ_CALL(JB) publish_from<JB>(nb, xc, h, j + 1)
             DQ_BLOCK_SWITCH((j + 1) / QB, DQ_CALL)
 #undef DQ_CALL
         }
         __syncthreads();
     }
-    if (is_col) {
-        if (h == 0) {
-            if (!(fabsf(mydiag) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
-            else if (mydiag == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
-        }
-        if (U != nullptr) {   // U[i][c] = s_i A[i][c] above the diagonal, |diag| on it
-            float* Up = U + (long)blockIdx.x * su;
+    if (h == 0) {
+        if (!(fabsf(mydiag) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+        else if (mydiag == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+    }
+    if (U != nullptr) {   // U[i][c] = s_i A[i][c] above the diagonal, |diag| on it
+        float* Up = U + (long)blockIdx.x * su;
 #pragma unroll
-            for (int k = 0; k < NG; ++k)
+        for (int k = 0; k < NG; ++k)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = 4 * (k * QS + h) + e;
-                    Up[(long)i * ldu + idx] = i < idx ? sgn[i] * x[4 * k + e] : (i == idx ? fabsf(mydiag) : 0.f);
-                }
-        }
-    } else {                  // R[r][c] = s_c Q[r][c]
-        float* Rp = R + (long)blockIdx.x * sr + (long)idx * ldr;
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * (k * QS + h) + e;
+                Up[(long)i * ldu + col] = i < col ? sgn[i] * xc[4 * k + e] : (i == col ? fabsf(mydiag) : 0.f);
+            }
+    }
+    {                     // R[r][c] = s_c Q[r][c]
+        float* Rp = R + (long)blockIdx.x * sr + (long)item * ldr;
 #pragma unroll
         for (int k = 0; k < NG; ++k) {
             const int c = 4 * (k * QS + h);
             const float4 sg = *reinterpret_cast<const float4*>(sgn + c);
             *reinterpret_cast<float4*>(Rp + c) =
-                make_float4(x[4 * k] * sg.x, x[4 * k + 1] * sg.y, x[4 * k + 2] * sg.z, x[4 * k + 3] * sg.w);
+                make_float4(xq[4 * k] * sg.x, xq[4 * k + 1] * sg.y, xq[4 * k + 2] * sg.z, xq[4 * k + 3] * sg.w);
         }
     }
 }
@@ -388,7 +396,7 @@ __global__ __launch_bounds__(256) void heads_reduce_kernel(const float* __restri
 hipError_t launch_heads_qr(int b, const float* Z, long ldz, long sz, float* R, long ldr, long sr, float* U, long ldu,
                            long su, unsigned* flags, hipStream_t s) {
     if (b < 1) return hipSuccess;
-    hipLaunchKernelGGL(heads_qr_kernel, dim3(b), dim3(2 * HN * QS), 0, s, Z, ldz, sz, R, ldr, sr, U, ldu, su, flags);
+    hipLaunchKernelGGL(heads_qr_kernel, dim3(b), dim3(HN * QS), 0, s, Z, ldz, sz, R, ldr, sr, U, ldu, su, flags);
     return hipGetLastError();
 }
 
