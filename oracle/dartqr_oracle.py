@@ -47,6 +47,20 @@ Readings taken where the paper is silent (each is also listed in the design note
 * App. (hyper-parameter settings): "Z0 is initialized using a random Hadamard matrix", construction not given.  Read
   as diag(s) H_n / sqrt(n) with Sylvester's H_n and random signs s supplied by the caller.  Pinned by orthogonality,
   the Kronecker form and the bit-count form of the entries (tests/).
+* Sec. 4.1 and the ablation of Sec. 5 (comparison of four objectives) name variance, kurtosis and the quantisation loss
+  as alternatives to Eq. 4 and print no formula for any of them.  PARITY UNPINNED BY THE PAPER; the readings taken, each
+  per token row y of n channels and combined over the rows like Eq. 4 (sum, or mean over tokens):
+    variance      m2 = (1/n) sum_i (y_i - mu)^2, mu the row mean;
+    kurtosis      m4 / m2^2 with m_k = (1/n) sum_i (y_i - mu)^k (Pearson's, 3 for a Gaussian); 0 for a constant row;
+    quantisation  (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser the paper's experiments
+                  use for activations (Sec. 5: per-token asymmetric, 4 bits): lo = min_i y_i, hi = max_i y_i,
+                  delta = (hi - lo) / (2^bits - 1), code q_i = round((y_i - lo) / delta) (ties to even),
+                  yhat_i = lo + delta q_i; 0 for a constant row.  The codes are decided in float32 (subtract, divide,
+                  round, each rounded to float32), the precision the GPU path decides them in.  Gradient: the codes are
+                  held fixed (the derivative that exists almost everywhere), lo and hi carry gradient to the first
+                  position of the row minimum and maximum.
+  Pinned by library routines (numpy.var, scipy.stats.kurtosis), closed forms, a brute-force nearest-level search,
+  invariances and central finite differences (tests/).
 """
 
 from __future__ import annotations
@@ -71,6 +85,10 @@ __all__ = [
     "token_sampling",
     "outlier_count",
     "hadamard_latent",
+    "variance_objective",
+    "kurtosis_objective",
+    "quant_objective",
+    "objective_loss_grad",
 ]
 
 
@@ -193,6 +211,102 @@ def whip_grad(Y, reduce: str = "mean") -> np.ndarray:
     return -c * np.sign(Y) * np.exp(-np.abs(Y))
 
 
+def variance_objective(Y, reduce: str = "mean"):
+    """Per-token variance as the objective (Sec. 4.1 names it; formula: reading above).
+
+    L = c * sum_t m2_t,  m2_t = (1/n) sum_i (Y_ti - mu_t)^2;   dL/dY_ti = c * (2/n) * (Y_ti - mu_t).
+    Returns (loss, dY)."""
+    Y = _f64(Y)
+    T, n = Y.shape
+    c = _reduce_scale(reduce, T)
+    loss = 0.0
+    dY = np.zeros_like(Y)
+    for t in range(T):
+        mu = np.sum(Y[t]) / n
+        d = Y[t] - mu
+        loss += np.sum(d * d) / n
+        dY[t] = c * (2.0 / n) * d
+    return float(c * loss), dY
+
+
+def kurtosis_objective(Y, reduce: str = "mean"):
+    """Per-token kurtosis as the objective (Sec. 4.1 names it; formula: reading above).
+
+    kappa_t = m4 / m2^2 with central moments m_k = (1/n) sum_i d_i^k, d = Y_t - mu_t.  Since d m4 / d y_i =
+    (4/n) (d_i^3 - m3) and d m2 / d y_i = (2/n) d_i,
+        d kappa / d y_i = (4/n) * ( (d_i^3 - m3) / m2^2 - m4 * d_i / m2^3 ).
+    A constant row (m2 = 0) contributes 0 and gets no gradient.  Returns (loss, dY)."""
+    Y = _f64(Y)
+    T, n = Y.shape
+    c = _reduce_scale(reduce, T)
+    loss = 0.0
+    dY = np.zeros_like(Y)
+    for t in range(T):
+        mu = np.sum(Y[t]) / n
+        d = Y[t] - mu
+        m2 = np.sum(d ** 2) / n
+        if m2 == 0.0:
+            continue
+        m3 = np.sum(d ** 3) / n
+        m4 = np.sum(d ** 4) / n
+        loss += m4 / (m2 * m2)
+        dY[t] = c * (4.0 / n) * ((d ** 3 - m3) / (m2 * m2) - m4 * d / (m2 ** 3))
+    return float(c * loss), dY
+
+
+def quant_objective(Y, bits: int = 4, reduce: str = "mean"):
+    """Per-token asymmetric uniform quantisation error as the objective (Sec. 5 names the quantiser and the objective;
+    formula: reading above).
+
+    Per row: lo, hi = min, max;  delta = (hi - lo) / L with L = 2^bits - 1;  q_i = round((y_i - lo) / delta);
+    yhat_i = lo + delta q_i = lo (1 - q_i / L) + hi q_i / L;  e_i = y_i - yhat_i;  loss_t = (1/n) sum_i e_i^2.
+    With the codes held fixed,
+        d loss_t / d y_j = (2/n) * ( e_j - [j = jmin] sum_i e_i (1 - q_i / L) - [j = jmax] sum_i e_i q_i / L ),
+    jmin / jmax the first positions of the minimum / maximum.  Returns (loss, dY, codes)."""
+    Y32 = np.asarray(Y, dtype=np.float32)
+    if not np.array_equal(Y32.astype(np.float64), np.asarray(Y, dtype=np.float64)):
+        raise ValueError("the quantiser decides its codes in float32: pass float32-representable values")
+    T, n = Y32.shape
+    levels = (1 << int(bits)) - 1
+    c = _reduce_scale(reduce, T)
+    loss = 0.0
+    dY = np.zeros((T, n), dtype=np.float64)
+    codes = np.zeros((T, n), dtype=np.int64)
+    for t in range(T):
+        y = Y32[t]
+        lo, hi = np.float32(np.min(y)), np.float32(np.max(y))
+        delta = np.float32(np.float32(hi - lo) / np.float32(levels))
+        if not delta > 0:
+            continue
+        # the decision, step by step in float32
+        q32 = np.rint(((y - lo).astype(np.float32) / delta).astype(np.float32))
+        q32 = np.minimum(np.maximum(q32, np.float32(0)), np.float32(levels))
+        q = q32.astype(np.float64)
+        codes[t] = q32.astype(np.int64)
+        y64 = y.astype(np.float64)
+        e = y64 - (float(lo) + float(delta) * q)
+        loss += np.sum(e * e) / n
+        g = e.copy()
+        g[int(np.argmin(y))] -= np.sum(e * (1.0 - q / levels))
+        g[int(np.argmax(y))] -= np.sum(e * (q / levels))
+        dY[t] = c * (2.0 / n) * g
+    return float(c * loss), dY, codes
+
+
+def objective_loss_grad(Y, objective: str = "whip", reduce: str = "mean", bits: int = 4):
+    """(loss, dY) of one of the four objectives the paper compares (Sec. 5, ablation of the optimisation objective)."""
+    if objective == "whip":
+        return whip_loss(Y, reduce), whip_grad(Y, reduce)
+    if objective == "variance":
+        return variance_objective(Y, reduce)
+    if objective == "kurtosis":
+        return kurtosis_objective(Y, reduce)
+    if objective == "quant":
+        loss, dY, _ = quant_objective(Y, bits, reduce)
+        return loss, dY
+    raise ValueError(f"unknown objective {objective!r}")
+
+
 def grad_wrt_rotation(X, dY) -> np.ndarray:
     """G = dL/dR = X^T @ dY   (chain rule through O = X @ R)."""
     return _f64(X).T @ _f64(dY)
@@ -264,16 +378,18 @@ def adam_update(Z, dZ, m, v, step: int, lr: float, beta1: float = 0.9, beta2: fl
     return _f64(Z) - float(lr) * m_hat / (np.sqrt(v_hat) + float(eps)), m_new, v_new
 
 
-def rotate_loss_grad(X, R, reduce: str = "mean"):
-    """(loss, G, Y, dY) for a given rotation R  (Alg. 1 lines 8-9 and dL/dR)."""
+def rotate_loss_grad(X, R, reduce: str = "mean", objective: str = "whip", bits: int = 4):
+    """(loss, G, Y, dY) for a given rotation R  (Alg. 1 lines 8-9 and dL/dR).  The quantisation objective decides
+    its codes on Y rounded to float32 (the precision the GPU path holds Y in)."""
     Y = rotate(X, R)
-    loss = whip_loss(Y, reduce)
-    dY = whip_grad(Y, reduce)
+    if objective == "quant":
+        Y = Y.astype(np.float32).astype(np.float64)
+    loss, dY = objective_loss_grad(Y, objective, reduce, bits)
     G = grad_wrt_rotation(X, dY)
     return loss, G, Y, dY
 
 
-def calib_step(X, Z, lr: float, reduce: str = "mean"):
+def calib_step(X, Z, lr: float, reduce: str = "mean", objective: str = "whip", bits: int = 4):
     """One pass of the loop body of Alg. 1 (lines 7-10).
 
     Returns a dict with the loss and rotation computed from the INPUT Z, the gradient
@@ -281,7 +397,7 @@ def calib_step(X, Z, lr: float, reduce: str = "mean"):
     """
     Z = _f64(Z)
     R, U = qr_orth(Z)
-    loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
+    loss, G, Y, dY = rotate_loss_grad(X, R, reduce, objective, bits)
     dZ = qr_backward(R, U, G)
     Z_new = sgd_update(Z, dZ, lr)
     return {"loss": loss, "R": R, "U": U, "G": G, "dZ": dZ, "Z_new": Z_new}

@@ -578,3 +578,157 @@ def test_hadamard_latent_pins():
     assert np.allclose(U, np.eye(16), atol=1e-13) and np.allclose(R, Z, atol=1e-13)
     with pytest.raises(ValueError):
         orc.hadamard_latent(np.ones(12))
+
+
+# ------------------------------------------------------------------------------------------------
+# Alternative objectives (Sec. 4.1 and the objective ablation of Sec. 5 name them, no formulas printed)
+
+def _fd_grad(f, Y, h=1e-6):
+    g = np.zeros_like(Y)
+    for idx in np.ndindex(*Y.shape):
+        Yp, Ym = Y.copy(), Y.copy()
+        Yp[idx] += h
+        Ym[idx] -= h
+        g[idx] = (f(Yp) - f(Ym)) / (2 * h)
+    return g
+
+
+def test_variance_objective_pins():
+    rng = np.random.default_rng(301)
+    Y = rng.standard_normal((5, 12)) * rng.uniform(0.5, 3.0, (5, 1)) + rng.standard_normal((5, 1))
+    for reduce, c in (("mean", 1.0 / 5), ("sum", 1.0)):
+        loss, dY = orc.variance_objective(Y, reduce)
+        # library route: numpy's population variance, row by row
+        assert loss == pytest.approx(c * sum(np.var(Y[t]) for t in range(5)), rel=1e-13)
+        np.testing.assert_allclose(dY, _fd_grad(lambda A: orc.variance_objective(A, reduce)[0], Y), atol=1e-8)
+        # shifting a row changes nothing: the gradient of every row sums to zero
+        np.testing.assert_allclose(dY.sum(axis=1), 0.0, atol=1e-14)
+    # n * (variance + mean^2) of a row is its squared norm, which no rotation changes (the paper's reason for
+    # rejecting the objective, Sec. 4.1)
+    X = rng.standard_normal((7, 16))
+    Q, _ = np.linalg.qr(rng.standard_normal((16, 16)))
+    for A in (X, X @ Q):
+        loss, _ = orc.variance_objective(A, "sum")
+        mu = A.mean(axis=1)
+        assert 16 * (loss + np.sum(mu * mu)) == pytest.approx(np.sum(X * X), rel=1e-12)
+    # closed form: the row (0, 2) has mean 1 and variance 1
+    assert orc.variance_objective(np.array([[0.0, 2.0]]), "sum")[0] == pytest.approx(1.0)
+    assert orc.variance_objective(np.full((2, 6), 3.5), "sum")[0] == 0.0
+
+
+def test_kurtosis_objective_pins():
+    from scipy import stats
+    rng = np.random.default_rng(302)
+    Y = rng.standard_t(4.0, size=(4, 20)) + rng.standard_normal((4, 1))
+    for reduce, c in (("mean", 0.25), ("sum", 1.0)):
+        loss, dY = orc.kurtosis_objective(Y, reduce)
+        assert loss == pytest.approx(c * sum(stats.kurtosis(Y[t], fisher=False, bias=True) for t in range(4)), rel=1e-12)
+        np.testing.assert_allclose(dY, _fd_grad(lambda A: orc.kurtosis_objective(A, reduce)[0], Y), atol=2e-7)
+        # kurtosis ignores shift and scale of a row: the gradient is orthogonal to 1 and to the row itself
+        np.testing.assert_allclose(dY.sum(axis=1), 0.0, atol=1e-13)
+        np.testing.assert_allclose(np.sum(dY * Y, axis=1), 0.0, atol=1e-12)
+    a, b = orc.kurtosis_objective(Y, "sum")[0], orc.kurtosis_objective(-3.0 * Y + 7.0, "sum")[0]
+    assert a == pytest.approx(b, rel=1e-12)
+    # closed forms: two equally likely values -> 1; a large Gaussian sample -> 3; uniform grid -> 9/5 in the limit
+    assert orc.kurtosis_objective(np.array([[1.0, -1.0, 1.0, -1.0]]), "sum")[0] == pytest.approx(1.0)
+    big = np.random.default_rng(5).standard_normal((1, 400000))
+    assert orc.kurtosis_objective(big, "sum")[0] == pytest.approx(3.0, abs=0.03)
+    grid = np.linspace(-1, 1, 20001)[None, :]
+    assert orc.kurtosis_objective(grid, "sum")[0] == pytest.approx(1.8, abs=1e-3)
+    # a constant row counts as zero and gets no gradient
+    loss, dY = orc.kurtosis_objective(np.vstack([np.full(6, 2.0), Y[0, :6]]), "sum")
+    assert loss == pytest.approx(stats.kurtosis(Y[0, :6], fisher=False)) and not dY[0].any()
+
+
+def _nearest_level_error(y, bits):
+    """Brute force: squared distance of every value to the nearest of the 2^bits levels between min and max."""
+    y = y.astype(np.float64)
+    lo, hi = y.min(), y.max()
+    lev = lo + (hi - lo) * np.arange(1 << bits) / ((1 << bits) - 1)
+    return np.min((y[:, None] - lev[None, :]) ** 2, axis=1)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quant_objective_pins(bits):
+    rng = np.random.default_rng(303 + bits)
+    Y = (rng.standard_t(3.0, size=(6, 40)) * 2.0).astype(np.float32)
+    L = (1 << bits) - 1
+    loss, dY, codes = orc.quant_objective(Y, bits, "sum")
+    assert codes.min() == 0 and codes.max() == L
+    # every code is the nearest level (brute force over all levels; float32 rounding of the grid moves a level by
+    # parts in 1e7 of the range, far less than the distance of these values to a decision boundary)
+    ref = sum(_nearest_level_error(Y[t], bits).sum() / 40 for t in range(6))
+    assert loss == pytest.approx(ref, rel=1e-5)
+    # error bound of a uniform quantiser: |e| <= delta / 2
+    for t in range(6):
+        y = Y[t].astype(np.float64)
+        delta = (y.max() - y.min()) / L
+        e = y - (y.min() + np.float64(np.float32(delta)) * codes[t])
+        assert np.max(np.abs(e)) <= delta / 2 * (1 + 1e-5)
+        assert codes[t][np.argmin(y)] == 0 and codes[t][np.argmax(y)] == L
+    # mean over tokens is the sum divided by T
+    assert orc.quant_objective(Y, bits, "mean")[0] == pytest.approx(loss / 6, rel=1e-14)
+    # finite differences with the codes held fixed (the stated reading of the derivative): the piecewise-quadratic loss
+    # written out for given codes
+    def fixed_code_loss(A):
+        tot = 0.0
+        for t in range(6):
+            lo, hi = A[t].min(), A[t].max()
+            yhat = lo + (hi - lo) * codes[t] / L
+            tot += np.sum((A[t] - yhat) ** 2) / 40
+        return tot
+    np.testing.assert_allclose(dY, _fd_grad(fixed_code_loss, Y.astype(np.float64)), atol=2e-6)
+    # and the true loss agrees with it for steps that cross no rounding boundary
+    t, i = 2, int(np.argsort(Y[2])[20])
+    frac = ((Y[t, i] - Y[t].min()) / ((Y[t].max() - Y[t].min()) / L)) % 1.0
+    h = np.float32(2.0 ** -12)
+    if 0.05 < frac < 0.45 or 0.55 < frac < 0.95:
+        Yp, Ym = Y.copy(), Y.copy()
+        Yp[t, i] += h
+        Ym[t, i] -= h
+        fd = (orc.quant_objective(Yp, bits, "sum")[0] - orc.quant_objective(Ym, bits, "sum")[0]) / (
+            float(Yp[t, i]) - float(Ym[t, i]))
+        assert fd == pytest.approx(dY[t, i], rel=1e-3, abs=1e-7)
+
+
+def test_quant_objective_closed_forms():
+    # values on the grid quantise without error; the midpoint of two levels has error delta / 2
+    row = np.array([[0.0, 1.0, 2.0, 3.0]], dtype=np.float32)
+    loss, dY, codes = orc.quant_objective(row, 2, "sum")
+    assert loss == 0.0 and not dY.any() and codes.tolist() == [[0, 1, 2, 3]]
+    row = np.array([[0.0, 3.0, 1.25]], dtype=np.float32)       # delta = 1, 1.25 -> level 1, error 0.25
+    loss, dY, codes = orc.quant_objective(row, 2, "sum")
+    assert codes.tolist() == [[0, 3, 1]] and loss == pytest.approx(0.25 ** 2 / 3)
+    # d/dy of the middle value: (2/3) e; the minimum carries -(2/3) e (1 - 1/3), the maximum -(2/3) e / 3
+    np.testing.assert_allclose(dY[0], (2.0 / 3) * 0.25 * np.array([-(2.0 / 3), -(1.0 / 3), 1.0]), rtol=1e-12)
+    # ties round to even: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2
+    row = np.array([[0.0, 3.0, 0.5, 1.5, 2.5]], dtype=np.float32)
+    assert orc.quant_objective(row, 2, "sum")[2].tolist() == [[0, 3, 0, 2, 2]]
+    # a constant row has no range: zero loss, zero gradient
+    loss, dY, _ = orc.quant_objective(np.full((2, 5), 1.5, dtype=np.float32), 4, "sum")
+    assert loss == 0.0 and not dY.any()
+    with pytest.raises(ValueError):
+        orc.quant_objective(np.array([[0.1, 0.2]]), 4)     # 0.1 is not a float32 value
+
+
+def test_objective_dispatch_and_step():
+    rng = np.random.default_rng(304)
+    Y = rng.standard_normal((3, 8)).astype(np.float32).astype(np.float64)
+    assert orc.objective_loss_grad(Y, "whip")[0] == orc.whip_loss(Y)
+    assert orc.objective_loss_grad(Y, "variance", "sum")[0] == orc.variance_objective(Y, "sum")[0]
+    assert orc.objective_loss_grad(Y, "kurtosis")[0] == orc.kurtosis_objective(Y)[0]
+    assert orc.objective_loss_grad(Y, "quant", bits=3)[0] == orc.quant_objective(Y, 3)[0]
+    with pytest.raises(ValueError):
+        orc.objective_loss_grad(Y, "entropy")
+    # a kurtosis-driven step lowers the kurtosis of a heavy-tailed block (small step, exact gradient)
+    X = rng.standard_t(3.0, size=(64, 8))
+    Z = rng.standard_normal((8, 8))
+    out = orc.calib_step(X, Z, 1e-3, "mean", "kurtosis")
+    after = orc.calib_step(X, out["Z_new"], 1e-3, "mean", "kurtosis")["loss"]
+    assert after < out["loss"]
+    # the variance objective is blind to the rotation up to the row means: G pairs to zero with every skew direction
+    # only through the mean term
+    Xc = X - X.mean(axis=1, keepdims=True)
+    R, _ = orc.qr_orth(Z)
+    l1 = orc.rotate_loss_grad(Xc, R, "sum", "variance")[0]
+    assert l1 + np.sum((Xc @ R).mean(axis=1) ** 2) == pytest.approx(np.sum(Xc * Xc) / 8, rel=1e-12)
