@@ -59,6 +59,18 @@ typedef enum { DQ_F32 = 0, DQ_BF16 = 1 } dq_dtype;
  * block (Alg. 1 line 9 leaves this open): mean over tokens of the per-token sum, or the sum. */
 typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
 
+/* The objective S4 evaluates on the rotated block.  DQ_OBJ_WHIP is the paper's (Eq. 4).  The other three are the
+ * alternatives it compares against (Sec. 4.1; Sec. 5, ablation of the optimisation objective), named there without
+ * formulas; per token row y of n channels, with mu the row mean, d = y - mu and m_k = (1/n) sum_i d_i^k:
+ *   DQ_OBJ_VARIANCE  m2
+ *   DQ_OBJ_KURTOSIS  m4 / m2^2  (a constant row counts 0)
+ *   DQ_OBJ_QUANT     (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser of Sec. 5:
+ *                    lo = min y, hi = max y, delta = (hi - lo) / (2^bits - 1), q_i = round((y_i - lo) / delta) in fp32
+ *                    (ties to even), yhat_i = lo + delta q_i; the derivative holds the codes fixed and sends the
+ *                    dependence on lo / hi to the first position of the minimum / maximum (a constant row counts 0)
+ * Rows are combined like Eq. 4 (dq_reduce).  These three need n <= DQ_MAX_N. */
+typedef enum { DQ_OBJ_WHIP = 0, DQ_OBJ_VARIANCE = 1, DQ_OBJ_KURTOSIS = 2, DQ_OBJ_QUANT = 3 } dq_objective;
+
 /* bits of the device status word */
 #define DQ_FLAG_SINGULAR   1u   /* a zero appeared on diag(U): Z is singular (dZ undefined)  */
 #define DQ_FLAG_NONFINITE  2u   /* a NaN or Inf was seen in a pivot or in the loss           */
@@ -128,6 +140,18 @@ dq_status dq_calib_step(dq_ctx* ctx, int b, int T, int n,
 dq_status dq_whip_loss_grad(dq_ctx* ctx, int b, int T, int n,
                             const float* Y, long ldy, dq_reduce red,
                             float* loss_dev, void* dY, dq_dtype dydt, long lddy);
+
+/* The same stage for any dq_objective (Sec. 5, objective ablation): loss_dev[i] and dY = d loss / dY on an existing
+ * Y (fp32, b blocks of T x n).  quant_bits (1..16) is read by DQ_OBJ_QUANT only.  DQ_OBJ_WHIP is dq_whip_loss_grad. */
+dq_status dq_objective_loss_grad(dq_ctx* ctx, dq_objective objective, int quant_bits, int b, int T, int n,
+                                 const float* Y, long ldy, dq_reduce red,
+                                 float* loss_dev, void* dY, dq_dtype dydt, long lddy);
+
+/* Selects the objective that dq_rotate_loss_grad, dq_calib_step and dq_calib_step_adam evaluate from now on
+ * (default DQ_OBJ_WHIP; Sec. 5, objective ablation).  With another objective Y and dY always pass through the
+ * workspace (no fused epilogue, no batched 128-wide route).  DQ_ERR_DTYPE for an unknown objective, DQ_ERR_SHAPE for
+ * quant_bits outside 1..16; the setting is unchanged on error. */
+dq_status dq_set_objective(dq_ctx* ctx, dq_objective objective, int quant_bits);
 
 /* Alg. 1 line 10, the derivative through Z = R U:  with B = R^T G and P = strict_lower(B - B^T),
  * dZ = R P U^{-T}.  R, U, G: in (U upper triangular, its strictly-lower part is not read).

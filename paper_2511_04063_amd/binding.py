@@ -17,6 +17,7 @@ DQ_OK = 0
 DQ_ERR_NULL, DQ_ERR_SHAPE, DQ_ERR_DTYPE, DQ_ERR_ALIGN, DQ_ERR_WORKSPACE, DQ_ERR_HIP, DQ_ERR_UNSUPPORTED = range(1, 8)
 DQ_F32, DQ_BF16 = 0, 1
 DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
+DQ_OBJ_WHIP, DQ_OBJ_VARIANCE, DQ_OBJ_KURTOSIS, DQ_OBJ_QUANT = 0, 1, 2, 3
 DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX = 1, 2, 4, 8
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
 DQ_MAX_N = 8192
@@ -39,6 +40,8 @@ SIGNATURES = {
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
     "dq_hadamard_init": (_i, [_vp, _i, _i, _vp, _vp, _l]),
+    "dq_objective_loss_grad": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
+    "dq_set_objective": (_i, [_vp, _i, _i]),
     "dq_outlier_count": (_i, [_vp, _i, _i, _i, _vp, _l, _f, _vp]),
     "dq_gather_rows": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _l, _vp, _vp, _l]),
     "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
@@ -182,6 +185,15 @@ class Context:
         T, n = Y.shape[-2], Y.shape[-1]
         self._check(self.lib.dq_whip_loss_grad(self.h, b, T, n, _ptr(Y), _ld(Y), reduce, _ptr(loss), _ptr(dY),
                                                dy_dtype, _ld(dY)), "dq_whip_loss_grad")
+
+    def dq_objective_loss_grad(self, objective, quant_bits, Y, reduce, loss, dY, dy_dtype):
+        b = Y.shape[0] if Y.dim() == 3 else 1
+        T, n = Y.shape[-2], Y.shape[-1]
+        self._check(self.lib.dq_objective_loss_grad(self.h, objective, quant_bits, b, T, n, _ptr(Y), _ld(Y), reduce,
+                                                    _ptr(loss), _ptr(dY), dy_dtype, _ld(dY)), "dq_objective_loss_grad")
+
+    def dq_set_objective(self, objective, quant_bits=4):
+        self._check(self.lib.dq_set_objective(self.h, objective, quant_bits), "dq_set_objective")
 
     def dq_qr_backward(self, R, U, G, dZ):
         b, n = (R.shape[0], R.shape[-1]) if R.dim() == 3 else (1, R.shape[-1])

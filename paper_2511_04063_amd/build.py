@@ -15,7 +15,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdartqr.so")
 
 SOURCES = ["dq_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "qr_kernels.hip", "qr_cholpanel.hip", "elementwise.hip",
-           "heads_kernels.hip"]
+           "heads_kernels.hip", "objective_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

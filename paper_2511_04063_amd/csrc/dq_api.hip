@@ -56,6 +56,8 @@ struct dq_ctx {
     bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
     int accum_panels = 2;            // panels merged per update of the accumulated R (1: panel by panel; 2 measured
                                      // best at n = 4096, 2 and 4 equal at n = 8192)
+    int objective = DQ_OBJ_WHIP;     // what S4 evaluates (dq_set_objective)
+    int quant_bits = 4;
     char* ws = nullptr;
     size_t ws_bytes = 0;
     Profiler prof;
@@ -546,7 +548,7 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         g.a_kwrap = koff; g.a_klim = n;
         // A caller that needs neither Y nor dY gets Eq. 4 and its derivative applied to the accumulators: Y is never
         // written and dY leaves the kernel already transposed for S5.
-        fused = use_fused && !keep_y_dy && g_transposed && gemm_bf16_deep_fits(g) &&
+        fused = use_fused && !keep_y_dy && g_transposed && gemm_bf16_deep_fits(g) && c->objective == DQ_OBJ_WHIP &&
                 (T / 128) * (n / 128) <= kLossPartials;
         if (fused) {
             g.C = nullptr;
@@ -570,11 +572,14 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
     }
     // S4: loss and dY in one pass over Y
     if (!fused) {
-        const int grid = whip_grid(T, n);
+        const bool whip = c->objective == DQ_OBJ_WHIP;
+        const int grid = whip ? whip_grid(T, n) : objective_grid(T, n);
         const double bytes = (double)T * n * (4.0 + (xdt == DQ_BF16 ? 2.0 : 4.0));
         {
             LaunchScope sc(&c->prof, s, DQ_K_WHIP, 5.0 * T * (double)n, bytes);
-            DQ_HIP(launch_whip(Y, ldy, T, n, scale, dY, xdt == DQ_BF16, lddy, lpart, grid, s));
+            if (whip) DQ_HIP(launch_whip(Y, ldy, T, n, scale, dY, xdt == DQ_BF16, lddy, lpart, grid, s));
+            else DQ_HIP(launch_objective(c->objective, c->quant_bits, Y, ldy, T, n, scale, dY, xdt == DQ_BF16, lddy,
+                                         lpart, grid, s));
         }
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
         DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, s));
@@ -727,6 +732,8 @@ bool heads_route(int n) {
     static const int on = [] { const char* e = getenv("DQ_HEADS_BATCHED"); return e ? atoi(e) : 1; }();
     return on != 0 && n == kHeadDim;
 }
+// the fused rotate + loss + gradient kernel of the batched route evaluates Eq. 4 only
+bool heads_fused_route(const dq_ctx* c, int n) { return heads_route(n) && c->objective == DQ_OBJ_WHIP; }
 
 dq_status check_heads_ws(dq_ctx* c, const HeadsLayout& H) {
     if (c->ws == nullptr || c->ws_bytes < H.total) return DQ_ERR_WORKSPACE;
@@ -916,7 +923,7 @@ dq_status dq_rotate_loss_grad(dq_ctx* c, int b, int T, int n, const void* X, dq_
     if (dY != nullptr) DQ_TRY(check_x(dY, xdt, lddy, n));
     const Layout L = make_layout(n, T);
     DQ_TRY(check_ws(c, L));
-    if (heads_route(n) && xdt == DQ_BF16 && Y == nullptr && dY == nullptr) {
+    if (heads_fused_route(c, n) && xdt == DQ_BF16 && Y == nullptr && dY == nullptr) {
         const HeadsLayout H = make_heads_layout(L.total, b, T);
         DQ_TRY(check_heads_ws(c, H));
         return heads_rotate_loss_grad(c, H, b, T, X, ldx, R, ldr, red, loss_dev, G, ldg);
@@ -946,7 +953,7 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
     if (R != nullptr) DQ_TRY(check_f32(R, ldr, n));
     const Layout L = make_layout(n, T);
     DQ_TRY(check_ws(c, L));
-    if (heads_route(n) && xdt == DQ_BF16) {
+    if (heads_fused_route(c, n) && xdt == DQ_BF16) {
         const HeadsLayout H = make_heads_layout(L.total, b, T);
         DQ_TRY(check_heads_ws(c, H));
         float* Rh = R ? R : at<float>(c, H.R);
@@ -963,8 +970,9 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
         // R is reported only on request: without it the sign normalisation is skipped and the triangular factor is
-        // read in place from the factored matrix
-        const bool report = R != nullptr;
+        // read in place from the factored matrix.  That holds for Eq. 4 only: the other objectives see the signs of
+        // Y's columns (row means, row extremes), so they always get the normalised rotation.
+        const bool report = R != nullptr || c->objective != DQ_OBJ_WHIP;
         float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
         float* Gi = at<float>(c, L.G);
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
@@ -1001,6 +1009,46 @@ dq_status dq_whip_loss_grad(dq_ctx* c, int b, int T, int n, const float* Y, long
                            (long)T * lddy));
     }
     DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, c->stream, b));
+    return DQ_OK;
+}
+
+dq_status dq_objective_loss_grad(dq_ctx* c, dq_objective objective, int quant_bits, int b, int T, int n, const float* Y,
+                                 long ldy, dq_reduce red, float* loss_dev, void* dY, dq_dtype dydt, long lddy) {
+    if (objective == DQ_OBJ_WHIP) return dq_whip_loss_grad(c, b, T, n, Y, ldy, red, loss_dev, dY, dydt, lddy);
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (objective != DQ_OBJ_VARIANCE && objective != DQ_OBJ_KURTOSIS && objective != DQ_OBJ_QUANT) return DQ_ERR_DTYPE;
+    if (b < 0 || T < 1 || n < 1 || quant_bits < 1 || quant_bits > 16) return DQ_ERR_SHAPE;
+    if (n > DQ_MAX_N) return DQ_ERR_UNSUPPORTED;
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_f32(Y, ldy, n));
+    DQ_TRY(check_x(dY, dydt, lddy, n));
+    if (c->ws == nullptr || c->ws_bytes < make_layout(1, 1).total) return DQ_ERR_WORKSPACE;
+    const Layout L = make_layout(1, 1);
+    unsigned* flags = at<unsigned>(c, L.flags);
+    double* lpart = at<double>(c, L.losspart);
+    const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
+    const size_t esz = (dydt == DQ_BF16) ? 2 : 4;
+    if (b == 0) return DQ_OK;
+    int grid = objective_grid(T, n);
+    if ((long)grid * b > kLossPartials) grid = kLossPartials / b;
+    if (grid < 1) return DQ_ERR_UNSUPPORTED;
+    {
+        LaunchScope sc(&c->prof, c->stream, DQ_K_WHIP, 8.0 * b * T * (double)n, (double)b * T * n * (4.0 + esz));
+        DQ_HIP(launch_objective(objective, quant_bits, Y, ldy, T, n, scale, dY, dydt == DQ_BF16, lddy, lpart, grid,
+                                c->stream, b, (long)T * ldy, (long)T * lddy));
+    }
+    DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, c->stream, b));
+    return DQ_OK;
+}
+
+dq_status dq_set_objective(dq_ctx* c, dq_objective objective, int quant_bits) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (objective != DQ_OBJ_WHIP && objective != DQ_OBJ_VARIANCE && objective != DQ_OBJ_KURTOSIS &&
+        objective != DQ_OBJ_QUANT)
+        return DQ_ERR_DTYPE;
+    if (quant_bits < 1 || quant_bits > 16) return DQ_ERR_SHAPE;
+    c->objective = objective;
+    c->quant_bits = quant_bits;
     return DQ_OK;
 }
 
@@ -1135,7 +1183,7 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
     const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
     const float c1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
     const float c2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
-    if (heads_route(n) && xdt == DQ_BF16 && ldz == n && ldm == n && ldv == n) {
+    if (heads_fused_route(c, n) && xdt == DQ_BF16 && ldz == n && ldm == n && ldv == n) {
         const HeadsLayout H = make_heads_layout(L.total, b, T);
         DQ_TRY(check_heads_ws(c, H));
         float* Rh = R ? R : at<float>(c, H.R);
@@ -1155,7 +1203,7 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
-        const bool report = R != nullptr;   // as in dq_calib_step
+        const bool report = R != nullptr || c->objective != DQ_OBJ_WHIP;   // as in dq_calib_step
         float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
         float* Gi = at<float>(c, L.G);
         float* dZi = at<float>(c, L.B);   // B = R^T G is consumed before the last product writes dZ there

@@ -174,4 +174,10 @@ hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void
 hipError_t launch_loss_finish(const double* partials, int count, float scale, float* loss_dev, unsigned* flags,
                               hipStream_t s, int batch = 1);
 
+// Row-wise objectives (1 variance, 2 kurtosis, 3 quantisation error): one partial per workgroup like the Whip pass.
+int objective_grid(int T, int n);
+hipError_t launch_objective(int objective, int bits, const float* Y, long ldy, int T, int n, float scale, void* dY,
+                            int dy_is_bf16, long lddy, double* partials, int grid, hipStream_t s, int batch = 1,
+                            long stride_y = 0, long stride_dy = 0);
+
 }  // namespace dq

@@ -136,6 +136,163 @@ def test_whip_closed_forms(ctx):
     assert torch.all(dYd == 0)
 
 
+# ----------------------------------------------------------------------------------- alternative objectives
+OBJECTIVES = {"variance": B.DQ_OBJ_VARIANCE, "kurtosis": B.DQ_OBJ_KURTOSIS, "quant": B.DQ_OBJ_QUANT}
+
+
+def objective_block(T, n, seed):
+    """Heavy-tailed rows with the degenerate cases of the row statistics: a constant row, a repeated minimum, a
+    repeated maximum."""
+    Y = (rng(seed).standard_t(3.0, size=(T, n)) * 2.0).astype(np.float32)
+    if T > 1:
+        Y[1, :] = 2.5
+    if T > 2 and n > 8:
+        Y[2, 3] = Y[2, 7] = -100.0
+        Y[2, 5] = Y[2, 8] = 90.0
+    return Y
+
+
+# the shapes span every register layout of the row kernel (one wavefront or one workgroup per row, 4 to 32 values per
+# thread), rows with a ragged tail, and rows that are not 16-byte aligned
+@pytest.mark.parametrize("T,n,ldy", [(37, 101, 104), (64, 256, 256), (5, 3, 8), (1, 1, 4), (33, 1000, 1000),
+                                     (19, 1500, 1504), (9, 4096, 4096), (5, 8192, 8192), (7, 5001, 5004),
+                                     (300, 512, 520)])
+@pytest.mark.parametrize("name", ["variance", "kurtosis", "quant"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_objective_loss_grad(ctx, name, T, n, ldy, bf16):
+    mode = "mean" if (T + n) % 2 else "sum"
+    Y = objective_block(T, n, 3100 + T + n)
+    _, Yd = padded(T, n, ldy); Yd.copy_(dev(Y))
+    lddy = -(-n // 8) * 8
+    _, dYd = padded(T, n, lddy, torch.bfloat16 if bf16 else torch.float32)
+    loss = torch.zeros(1, device="cuda")
+    red = B.DQ_REDUCE_TOKEN_MEAN if mode == "mean" else B.DQ_REDUCE_SUM
+    ctx.dq_objective_loss_grad(OBJECTIVES[name], 4, Yd, red, loss, dYd, B.DQ_BF16 if bf16 else B.DQ_F32)
+    ref_loss, ref_dY = orc.objective_loss_grad(Y, name, mode, 4)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss) + 1e-30
+    got = dYd.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    # fp32 statistics of rows of up to 8192 heavy-tailed values against fp64: 1e-5; the quantiser's e = y - yhat is a
+    # difference of nearby fp32 numbers, a 2^bits-th of the range: 1e-4 (both far inside the bar where nothing rounds)
+    tol = 4e-3 if bf16 else (1e-4 if name == "quant" else 1e-5)
+    if name == "kurtosis" and n <= 3:
+        # the kurtosis of one, two or three values is the constant 0, 1 or 3/2: the exact gradient vanishes and the
+        # fp32 result is rounding noise around it
+        assert np.abs(ref_dY).max() < 1e-12 and np.abs(got).max() < 1e-5
+    else:
+        assert rel(got, ref_dY) < tol
+    if T > 1:
+        assert not got[1].any()          # constant row: no gradient under any of the three
+    if name != "quant" and n > 3:
+        assert np.abs(got.astype(np.float64).sum(axis=1)).max() <= 3e-3 * np.abs(ref_dY).sum(axis=1).max() + 1e-30
+
+
+@pytest.mark.parametrize("bits", [2, 8])
+def test_objective_quant_bits_and_batch(ctx, bits):
+    b, T, n = 3, 45, 640
+    Y = np.stack([objective_block(T, n, 3200 + i) for i in range(b)])
+    Yd = dev(Y)
+    dYd = torch.full((b, T, n), float("nan"), device="cuda")
+    loss = torch.zeros(b, device="cuda")
+    ctx.dq_objective_loss_grad(B.DQ_OBJ_QUANT, bits, Yd, B.DQ_REDUCE_SUM, loss, dYd, B.DQ_F32)
+    got = dYd.cpu().numpy()
+    for i in range(b):
+        ref_loss, ref_dY, codes = orc.quant_objective(Y[i], bits, "sum")
+        assert abs(loss[i].item() - ref_loss) <= 1e-5 * ref_loss
+        assert rel(got[i], ref_dY) < 1e-4 * max(1.0, 2.0 ** bits / 16)
+        # the codes themselves, read back from the gradient of untouched positions: e = y - (lo + delta q)
+        lo, hi = Y[i].min(axis=1, keepdims=True).astype(np.float64), Y[i].max(axis=1, keepdims=True).astype(np.float64)
+        delta = (hi - lo) / (2 ** bits - 1)
+        rows = [t for t in range(T) if delta[t] > 0]
+        e = got[i][rows].astype(np.float64) * n / 2.0
+        q = (Y[i][rows] - e - lo[rows]) / delta[rows]
+        inner = np.ones_like(q, dtype=bool)
+        inner[np.arange(len(rows)), Y[i][rows].argmin(axis=1)] = False
+        inner[np.arange(len(rows)), Y[i][rows].argmax(axis=1)] = False
+        assert np.array_equal(np.rint(q)[inner], codes[rows][inner])
+
+
+@pytest.mark.parametrize("name", ["variance", "kurtosis", "quant"])
+def test_calib_step_with_objective(ctx, name):
+    cfg = synth.scaled_config("tiny", n=96, T=320)
+    inp = synth.make_inputs(cfg, seed=21)
+    X, Z0 = inp["X"][0], inp["Z0"][0]
+    Xd, Zd = dev(X), dev(Z0.copy())
+    n, T = 96, 320
+    R = torch.empty((n, n), device="cuda"); U = torch.empty((n, n), device="cuda")
+    G = torch.empty((n, n), device="cuda"); Yd = torch.empty((T, n), device="cuda"); dYd = torch.empty((T, n), device="cuda")
+    loss = torch.zeros(1, device="cuda"); loss2 = torch.zeros(1, device="cuda")
+    try:
+        ctx.dq_set_objective(OBJECTIVES[name], 4)
+        ctx.dq_qr_orth(Zd, R, U)
+        ctx.dq_rotate_loss_grad(Xd, B.DQ_F32, R, B.DQ_REDUCE_TOKEN_MEAN, loss, G, Yd, dYd)
+        ctx.dq_calib_step(Xd, B.DQ_F32, Zd, 1e-2, B.DQ_REDUCE_TOKEN_MEAN, loss2)
+    finally:
+        ctx.dq_set_objective(B.DQ_OBJ_WHIP, 4)
+    out = orc.calib_step(X, Z0, 1e-2, "mean", name)
+    assert abs(loss.item() - out["loss"]) <= 1e-4 * abs(out["loss"])
+    assert loss2.item() == loss.item()
+    # stage-wise on the GPU's own Y (the quantiser's codes are decided on the fp32 Y the GPU holds)
+    Yg = Yd.cpu().numpy()
+    ref_loss, ref_dY = orc.objective_loss_grad(Yg, name, "mean", 4)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+    assert rel(dYd.cpu().numpy(), ref_dY) < 1e-4
+    # whole step.  The quantiser's gradient jumps by a quantiser step where a code flips, and the GPU's Y differs from
+    # the oracle's in the last fp32 bits: a handful of flipped codes among T n entries moves G = X^T dY (a sum of
+    # quantisation noise with heavy cancellation) by a per cent.  Its G is therefore checked against the oracle's dY
+    # on the GPU's own Y; the two smooth objectives against the oracle's whole step.
+    if name == "quant":
+        assert rel(G.cpu().numpy(), X.astype(np.float64).T @ ref_dY) < 1e-4
+    else:
+        assert rel(G.cpu().numpy(), out["G"]) < 1e-4
+    assert rel(Zd.cpu().numpy(), out["Z_new"]) < 1e-5
+    # the setting is back to Eq. 4
+    ctx.dq_rotate_loss_grad(Xd, B.DQ_F32, R, B.DQ_REDUCE_TOKEN_MEAN, loss, G, None, None)
+    assert abs(loss.item() - orc.whip_loss(orc.rotate(X, out["R"]))) <= 1e-4 * abs(loss.item())
+
+
+def test_objective_on_head_sized_batch_takes_the_general_route(ctx):
+    b, T, n = 2, 256, 128
+    cfg = synth.scaled_config("heads", b=b, T=T)
+    inp = synth.make_inputs(cfg, seed=5)
+    X, Z0 = inp["X"], inp["Z0"]
+    Xd, Zd = dev(X, torch.bfloat16), dev(Z0.copy())
+    loss = torch.zeros(b, device="cuda")
+    c = B.Context(); c.ensure_workspace(b, n, T, B.DQ_BF16)
+    try:
+        c.dq_set_objective(B.DQ_OBJ_KURTOSIS, 4)
+        c.dq_calib_step(Xd, B.DQ_BF16, Zd, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, loss)
+        torch.cuda.synchronize()
+    finally:
+        c.close()
+    for i in range(b):
+        out = orc.calib_step(X[i], Z0[i], 1e-3, "mean", "kurtosis")
+        assert abs(loss[i].item() - out["loss"]) <= 1e-4 * out["loss"]
+        assert rel(Zd[i].cpu().numpy(), out["Z_new"]) < 1e-5
+
+
+def test_objective_errors(ctx):
+    Yd = torch.zeros((4, 8), device="cuda"); dYd = torch.full((4, 8), 7.0, device="cuda")
+    loss = torch.full((1,), 5.0, device="cuda")
+    for obj, bits, status in ((7, 4, B.DQ_ERR_DTYPE), (B.DQ_OBJ_QUANT, 0, B.DQ_ERR_SHAPE), (B.DQ_OBJ_QUANT, 17, B.DQ_ERR_SHAPE)):
+        with pytest.raises(B.DartQRError) as e:
+            ctx.dq_objective_loss_grad(obj, bits, Yd, B.DQ_REDUCE_SUM, loss, dYd, B.DQ_F32)
+        assert e.value.status == status
+        with pytest.raises(B.DartQRError) as e:
+            ctx.dq_set_objective(obj, bits)
+        assert e.value.status == status
+    wide = torch.zeros((1, B.DQ_MAX_N + 8), device="cuda")
+    with pytest.raises(B.DartQRError) as e:
+        ctx.dq_objective_loss_grad(B.DQ_OBJ_VARIANCE, 4, wide, B.DQ_REDUCE_SUM, loss, torch.empty_like(wide), B.DQ_F32)
+    assert e.value.status == B.DQ_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert loss.item() == 5.0 and torch.all(dYd == 7.0)
+    # all-zero block: zero loss and zero gradient under the three objectives
+    for obj in OBJECTIVES.values():
+        ctx.dq_objective_loss_grad(obj, 4, Yd, B.DQ_REDUCE_SUM, loss, dYd, B.DQ_F32)
+        assert loss.item() == 0.0 and not dYd.any()
+
+
 # ----------------------------------------------------------------------------------- QR-Orth
 def run_qr(ctx, Z, want_u=True, ld=None):
     n = Z.shape[-1]

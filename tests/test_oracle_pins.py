@@ -635,6 +635,10 @@ def test_kurtosis_objective_pins():
     assert orc.kurtosis_objective(big, "sum")[0] == pytest.approx(3.0, abs=0.03)
     grid = np.linspace(-1, 1, 20001)[None, :]
     assert orc.kurtosis_objective(grid, "sum")[0] == pytest.approx(1.8, abs=1e-3)
+    # two values always give 1 and three values always 3/2, so their gradients vanish
+    for k, val in ((2, 1.0), (3, 1.5)):
+        loss, dY = orc.kurtosis_objective(rng.standard_normal((5, k)) * 3.0 + 1.0, "sum")
+        assert loss == pytest.approx(5 * val, rel=1e-12) and np.abs(dY).max() < 1e-12
     # a constant row counts as zero and gets no gradient
     loss, dY = orc.kurtosis_objective(np.vstack([np.full(6, 2.0), Y[0, :6]]), "sum")
     assert loss == pytest.approx(stats.kurtosis(Y[0, :6], fisher=False)) and not dY[0].any()
