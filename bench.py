@@ -87,6 +87,9 @@ def main():
                          "the trace holds calibration steps only)")
     ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
                     help="update rule of the latent: Alg. 1's SGD (the headline metric) or Adam (Sec. 4.3, Table 4)")
+    ap.add_argument("--objective", choices=["whip", "variance", "kurtosis", "quant"], default="whip",
+                    help="what S4 evaluates: Eq. 4 (the headline metric) or one of the objectives the paper compares "
+                         "it with (Sec. 5, objective ablation)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -118,6 +121,9 @@ def main():
     ctx = B.Context()
     ctx.ensure_workspace(cfg.b, cfg.n, cfg.T, xdt)
     red = B.DQ_REDUCE_TOKEN_MEAN
+    objectives = {"whip": B.DQ_OBJ_WHIP, "variance": B.DQ_OBJ_VARIANCE, "kurtosis": B.DQ_OBJ_KURTOSIS,
+                  "quant": B.DQ_OBJ_QUANT}
+    ctx.dq_set_objective(objectives[args.objective], 4)
 
     if args.optimizer == "adam":
         m_state = torch.zeros_like(Zd)
@@ -203,6 +209,11 @@ def main():
         ms = tm(lambda: ctx.dq_whip_loss_grad(Yb, red, lossb, dYb, xdt))
         by = b * T * n * (4.0 + (2.0 if bf16 else 4.0))
         out["whip_loss_grad"] = {"ms": ms, "bytes": by, "gbs": by / ms / 1e6, "frac_hbm_peak": by / ms / 1e6 / PEAK["hbm_gbs"]}
+        # the row-wise objectives of the ablation: the same bytes per element as the Whip pass
+        for name in ("variance", "kurtosis", "quant"):
+            ms = tm(lambda: ctx.dq_objective_loss_grad(objectives[name], 4, Yb, red, lossb, dYb, xdt))
+            out[name + "_loss_grad"] = {"ms": ms, "bytes": by, "gbs": by / ms / 1e6,
+                                        "frac_hbm_peak": by / ms / 1e6 / PEAK["hbm_gbs"]}
         return out
 
     stages = None if args.no_stage_roofline else stage_times()
@@ -240,7 +251,8 @@ def main():
         "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, "
-                               f"{'Adam' if args.optimizer == 'adam' else 'SGD'} lr={cfg.lr}",
+                               f"{'Adam' if args.optimizer == 'adam' else 'SGD'} lr={cfg.lr}"
+                               + ("" if args.objective == "whip" else f", objective {args.objective}"),
                    "n": cfg.n, "T": cfg.T, "b": cfg.b},
         "model_tflops": F / (ms_per_step * 1e-3) / 1e12,
         "flops_per_step": F,

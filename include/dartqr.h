@@ -65,7 +65,7 @@ typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
  *   DQ_OBJ_VARIANCE  m2
  *   DQ_OBJ_KURTOSIS  m4 / m2^2  (a constant row counts 0)
  *   DQ_OBJ_QUANT     (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser of Sec. 5:
- *                    lo = min y, hi = max y, delta = (hi - lo) / (2^bits - 1), q_i = round((y_i - lo) / delta) in fp32
+ *                    lo = min y, hi = max y, delta = (hi - lo) / (2^bits - 1), q_i = round((y_i - lo) * (1 / delta)) in fp32
  *                    (ties to even), yhat_i = lo + delta q_i; the derivative holds the codes fixed and sends the
  *                    dependence on lo / hi to the first position of the minimum / maximum (a constant row counts 0)
  * Rows are combined like Eq. 4 (dq_reduce).  These three need n <= DQ_MAX_N. */

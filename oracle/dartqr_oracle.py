@@ -54,9 +54,9 @@ Readings taken where the paper is silent (each is also listed in the design note
     kurtosis      m4 / m2^2 with m_k = (1/n) sum_i (y_i - mu)^k (Pearson's, 3 for a Gaussian); 0 for a constant row;
     quantisation  (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser the paper's experiments
                   use for activations (Sec. 5: per-token asymmetric, 4 bits): lo = min_i y_i, hi = max_i y_i,
-                  delta = (hi - lo) / (2^bits - 1), code q_i = round((y_i - lo) / delta) (ties to even),
-                  yhat_i = lo + delta q_i; 0 for a constant row.  The codes are decided in float32 (subtract, divide,
-                  round, each rounded to float32), the precision the GPU path decides them in.  Gradient: the codes are
+                  delta = (hi - lo) / (2^bits - 1), code q_i = round((y_i - lo) * s) with the scale s = 1 / delta (ties
+                  to even), yhat_i = lo + delta q_i; 0 for a constant row.  The codes are decided in float32 (delta, s,
+                  the subtraction and the product each rounded to float32), the precision the GPU path decides them in.  Gradient: the codes are
                   held fixed (the derivative that exists almost everywhere), lo and hi carry gradient to the first
                   position of the row minimum and maximum.
   Pinned by library routines (numpy.var, scipy.stats.kurtosis), closed forms, a brute-force nearest-level search,
@@ -258,7 +258,7 @@ def quant_objective(Y, bits: int = 4, reduce: str = "mean"):
     """Per-token asymmetric uniform quantisation error as the objective (Sec. 5 names the quantiser and the objective;
     formula: reading above).
 
-    Per row: lo, hi = min, max;  delta = (hi - lo) / L with L = 2^bits - 1;  q_i = round((y_i - lo) / delta);
+    Per row: lo, hi = min, max;  delta = (hi - lo) / L with L = 2^bits - 1;  q_i = round((y_i - lo) * (1 / delta));
     yhat_i = lo + delta q_i = lo (1 - q_i / L) + hi q_i / L;  e_i = y_i - yhat_i;  loss_t = (1/n) sum_i e_i^2.
     With the codes held fixed,
         d loss_t / d y_j = (2/n) * ( e_j - [j = jmin] sum_i e_i (1 - q_i / L) - [j = jmax] sum_i e_i q_i / L ),
@@ -279,7 +279,8 @@ def quant_objective(Y, bits: int = 4, reduce: str = "mean"):
         if not delta > 0:
             continue
         # the decision, step by step in float32
-        q32 = np.rint(((y - lo).astype(np.float32) / delta).astype(np.float32))
+        scale = np.float32(np.float32(1.0) / delta)
+        q32 = np.rint(((y - lo).astype(np.float32) * scale).astype(np.float32))
         q32 = np.minimum(np.maximum(q32, np.float32(0)), np.float32(levels))
         q = q32.astype(np.float64)
         codes[t] = q32.astype(np.int64)

@@ -7,6 +7,7 @@
 #include "dq_wave.h"
 
 #include <climits>
+#include <cstdlib>
 
 namespace dq {
 namespace {
@@ -26,9 +27,12 @@ __device__ __forceinline__ float wave_min(float v) {
     v = fminf(v, lane_xor<8>(v)); v = fminf(v, lane_xor<16>(v)); v = fminf(v, lane_xor<32>(v));
     return v;
 }
+// the exchanges move bit patterns, so an integer travels as the float with its bits
+template <int OFF>
+__device__ __forceinline__ int lane_xor_int(int v) { return __float_as_int(lane_xor<OFF>(__int_as_float(v))); }
 __device__ __forceinline__ int wave_min(int v) {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { const int w = __shfl_xor(v, o); v = w < v ? w : v; }
+    v = min(v, lane_xor_int<1>(v)); v = min(v, lane_xor_int<2>(v)); v = min(v, lane_xor_int<4>(v));
+    v = min(v, lane_xor_int<8>(v)); v = min(v, lane_xor_int<16>(v)); v = min(v, lane_xor_int<32>(v));
     return v;
 }
 
@@ -89,17 +93,21 @@ struct RowReducer {
 //   mu = (1/n) sum_i y_i,  d_i = y_i - mu,  m_k = (1/n) sum_i d_i^k:
 //   variance   loss_t = m2                    dY_i = c (2/n) d_i
 //   kurtosis   loss_t = m4 / m2^2             dY_i = c (4/n) ((d_i^3 - m3) / m2^2 - m4 d_i / m2^3)     (0 if m2 = 0)
-//   quant      lo = min y, hi = max y, delta = (hi - lo) / L, L = 2^bits - 1, q_i = rint((y_i - lo) / delta) in fp32
-//              with IEEE subtract and divide and ties to even, e_i = y_i - (lo + delta q_i), loss_t = (1/n) sum e_i^2,
+//   quant      lo = min y, hi = max y, delta = (hi - lo) / L, L = 2^bits - 1, s = 1 / delta,
+//              q_i = rint((y_i - lo) * s) in fp32 (IEEE subtract, divide and multiply, ties to even),
+//              e_i = y_i - (lo + delta q_i), loss_t = (1/n) sum e_i^2,
 //              dY_j = c (2/n) (e_j - [j = jmin] sum_i e_i (1 - q_i / L) - [j = jmax] sum_i e_i q_i / L), the codes held
 //              fixed and jmin / jmax the first positions of the minimum / maximum        (0 if delta = 0)
 // partials[blockIdx.y * gridDim.x + blockIdx.x] receives the workgroup's sum of loss_t (the caller applies c).
-// Element index of register (k, e): vectorised rows 4 (k TPR + t) + e (16-byte loads), else (4 k + e) TPR + t.
-template <int OBJ, int V, int TPR, bool BF16OUT>
+// Element index of register (k, e): VEC (rows and strides of Y and dY 16-byte aligned, n % 4 == 0) 4 (k TPR + t) + e
+// with 16-byte loads and 8- or 16-byte stores, else (4 k + e) TPR + t with 4-byte accesses.
+// The row is transformed in place in its registers (y -> d or e -> dY), which keeps the kernel at 8 wavefronts per
+// SIMD up to n = 8192.
+template <int OBJ, int V, int TPR, bool BF16OUT, bool VEC>
 __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __restrict__ Y, long ldy, int T, int n,
                                                              float scale, float levels, void* __restrict__ dYv,
-                                                             long lddy, double* __restrict__ partials, int yvec,
-                                                             int dvec, long sy, long sdy) {
+                                                             long lddy, double* __restrict__ partials, long sy,
+                                                             long sdy) {
     __shared__ float red[64];
     __shared__ float tot[4];
     Y += (long)blockIdx.y * sy;
@@ -110,53 +118,64 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
     RowReducer rr{red, 0};
     const float inv_n = 1.f / (float)n;
     float acc = 0.f;                               // this thread's share of sum_t loss_t
-    for (long row = (long)blockIdx.x * RPW + sub; row < T; row += (long)gridDim.x * RPW) {
+    // index of register 4 k + e in the row, and whether it lies inside the row
+    auto at_index = [&](int k, int e) { return VEC ? 4 * (k * TPR + t) + e : (4 * k + e) * TPR + t; };
+    auto load_row = [&](float (&r)[4 * V], long row) {
         const float* src = Y + row * ldy;
-        float x[4 * V];
-        bool live[4 * V];
-        int idx[4 * V];
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-            if (yvec) {
+            if constexpr (VEC) {
                 const int i0 = 4 * (k * TPR + t);
                 float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (i0 < n) q = *reinterpret_cast<const float4*>(src + i0);     // n % 4 == 0 on this route
-                x[4 * k] = q.x; x[4 * k + 1] = q.y; x[4 * k + 2] = q.z; x[4 * k + 3] = q.w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { idx[4 * k + e] = i0 + e; live[4 * k + e] = i0 < n; }
+                r[4 * k] = q.x; r[4 * k + 1] = q.y; r[4 * k + 2] = q.z; r[4 * k + 3] = q.w;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i = (4 * k + e) * TPR + t;
-                    idx[4 * k + e] = i; live[4 * k + e] = i < n;
-                    x[4 * k + e] = i < n ? src[i] : 0.f;
+                    r[4 * k + e] = i < n ? src[i] : 0.f;
                 }
             }
         }
-        float g[4 * V];
+    };
+    const long row_step = (long)gridDim.x * RPW;
+    long row = (long)blockIdx.x * RPW + sub;
+    float x[4 * V], xn[4 * V];
+    if (row < T) load_row(xn, row);
+#pragma unroll 1
+    for (; row < T; row += row_step) {
+#pragma unroll
+        for (int i = 0; i < 4 * V; ++i) x[i] = xn[i];
+        if (row + row_step < T) load_row(xn, row + row_step);      // the next row travels while this one is worked on
         if constexpr (OBJ == OBJ_VARIANCE || OBJ == OBJ_KURTOSIS) {
             float s[1] = {0.f};
 #pragma unroll
-            for (int i = 0; i < 4 * V; ++i) s[0] += x[i];                       // dead entries are zero
+            for (int i = 0; i < 4 * V; ++i) s[0] += x[i];                       // entries outside the row are zero
             rr.sum<TPR, 1>(s, tid);
             const float mu = s[0] / (float)n;   // exact for a constant row whose sum is exact
             if constexpr (OBJ == OBJ_VARIANCE) {
                 const float f = scale * 2.f * inv_n;
+                float ss = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4 * V; ++i) {
-                    const float d = live[i] ? x[i] - mu : 0.f;
-                    acc += d * d * inv_n;
-                    g[i] = f * d;
-                }
+                for (int k = 0; k < V; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float d = at_index(k, e) < n ? x[4 * k + e] - mu : 0.f;
+                        ss += d * d;
+                        x[4 * k + e] = f * d;
+                    }
+                acc += ss * inv_n;
             } else {
                 float m[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 4 * V; ++i) {
-                    const float d = live[i] ? x[i] - mu : 0.f;
-                    const float d2 = d * d;
-                    x[i] = d;
-                    m[0] += d2; m[1] += d2 * d; m[2] += d2 * d2;
-                }
+                for (int k = 0; k < V; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float d = at_index(k, e) < n ? x[4 * k + e] - mu : 0.f;
+                        const float d2 = d * d;
+                        x[4 * k + e] = d;
+                        m[0] += d2; m[1] += d2 * d; m[2] += d2 * d2;
+                    }
                 rr.sum<TPR, 4>(m, tid);
                 const float m2 = m[0] * inv_n, m3 = m[1] * inv_n, m4 = m[2] * inv_n;
                 const bool flat = !(m2 > 0.f);
@@ -166,72 +185,103 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
                 const float f = scale * 4.f * inv_n;
                 const float a = f * r2, b = flat ? 0.f : f * kap / m2;          // f m4 / m2^3
 #pragma unroll
-                for (int i = 0; i < 4 * V; ++i) {
-                    const float d = x[i];
-                    g[i] = live[i] ? a * (d * d * d - m3) - b * d : 0.f;
-                }
+                for (int k = 0; k < V; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float d = x[4 * k + e];
+                        x[4 * k + e] = at_index(k, e) < n ? a * (d * d * d - m3) - b * d : 0.f;
+                    }
             }
         } else {
             float lo = 3.0e38f, nhi = 3.0e38f;
 #pragma unroll
-            for (int i = 0; i < 4 * V; ++i)
-                if (live[i]) { lo = fminf(lo, x[i]); nhi = fminf(nhi, -x[i]); }
+            for (int k = 0; k < V; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (at_index(k, e) < n) { lo = fminf(lo, x[4 * k + e]); nhi = fminf(nhi, -x[4 * k + e]); }
+            const float own_lo = lo, own_nhi = nhi;
             rr.min2<TPR>(lo, nhi, tid);
             const float hi = -nhi;
             const float delta = __fdiv_rn(__fsub_rn(hi, lo), levels);
             const bool flat = !(delta > 0.f);
+            const float inv_delta = flat ? 0.f : __fdiv_rn(1.f, delta);
             const float inv_l = 1.f / levels;
-            float s0 = 0.f, s1 = 0.f;
+            // first position of the row minimum and maximum: only a wavefront that holds one of them looks for it
             int jmin = INT_MAX, jmax = INT_MAX;
+            if (own_lo == lo || own_nhi == nhi) {
 #pragma unroll
-            for (int i = 0; i < 4 * V; ++i) {
-                float q = rintf(__fdiv_rn(__fsub_rn(x[i], lo), flat ? 1.f : delta));
-                q = fminf(fmaxf(q, 0.f), levels);
-                const float e = (live[i] && !flat) ? x[i] - (lo + delta * q) : 0.f;
-                acc += e * e * inv_n;
-                const float w = q * inv_l;
-                s0 += e * (1.f - w);
-                s1 += e * w;
-                if (live[i] && x[i] == lo) jmin = min(jmin, idx[i]);
-                if (live[i] && x[i] == hi) jmax = min(jmax, idx[i]);
-                g[i] = e;
+                for (int k = 0; k < V; ++k)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = at_index(k, e);
+                        if (i < n && x[4 * k + e] == lo) jmin = min(jmin, i);
+                        if (i < n && x[4 * k + e] == hi) jmax = min(jmax, i);
+                    }
             }
-            rr.sum2_min2<TPR>(s0, s1, jmin, jmax, tid);
+            float se = 0.f, sq = 0.f, ss = 0.f;     // sums of e, e q, e^2
             const float f = scale * 2.f * inv_n;
 #pragma unroll
-            for (int i = 0; i < 4 * V; ++i) {
-                float v = g[i];
-                if (idx[i] == jmin) v -= s0;
-                if (idx[i] == jmax) v -= s1;
-                g[i] = (live[i] && !flat) ? f * v : 0.f;
+            for (int k = 0; k < V; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float y = x[4 * k + e];
+                    const bool in = at_index(k, e) < n && !flat;
+                    // 0 <= (y - lo) / delta <= L up to one rounding, far from L + 1/2: the code needs no clamp
+                    const float q = rintf(__fmul_rn(__fsub_rn(y, lo), inv_delta));
+                    const float er = in ? y - (lo + delta * q) : 0.f;
+                    ss += er * er;
+                    se += er;
+                    sq += er * q;
+                    x[4 * k + e] = f * er;
+                }
+            acc += ss * inv_n;
+            rr.sum2_min2<TPR>(se, sq, jmin, jmax, tid);
+            // The two entries that also carry the dependence of lo and hi: every position of the minimum has e = 0 and
+            // every position of the maximum the same e, so their values are known without looking them up.  Only a
+            // wavefront that holds one of the two positions walks its registers.
+            const float s1 = sq * inv_l, s0 = se - s1;      // sum e q / L and sum e (1 - q / L)
+            const float q_hi = rintf(__fmul_rn(__fsub_rn(hi, lo), inv_delta));
+            const float fix_lo = f * (0.f - s0);
+            const float fix_hi = f * ((hi - (lo + delta * q_hi)) - s1);
+            const bool mine_lo = !flat && jmin != INT_MAX && (VEC ? (jmin >> 2) % TPR : jmin % TPR) == t;
+            const bool mine_hi = !flat && jmax != INT_MAX && (VEC ? (jmax >> 2) % TPR : jmax % TPR) == t;
+            if (mine_lo || mine_hi) {
+                // register position 4 k + e of a row index
+                const int pos_lo = mine_lo ? (VEC ? 4 * ((jmin >> 2) / TPR) + (jmin & 3) : jmin / TPR) : -1;
+                const int pos_hi = mine_hi ? (VEC ? 4 * ((jmax >> 2) / TPR) + (jmax & 3) : jmax / TPR) : -1;
+#pragma unroll
+                for (int p = 0; p < 4 * V; ++p) {
+                    x[p] = p == pos_lo ? fix_lo : x[p];
+                    x[p] = p == pos_hi ? fix_hi : x[p];
+                }
             }
         }
         // dY from the registers, in the element order of the loads
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-            if (yvec && dvec) {
+            if constexpr (VEC) {
                 const int i0 = 4 * (k * TPR + t);
                 if (i0 < n) {
                     if constexpr (BF16OUT) {
-                        f32x2 a0 = {g[4 * k], g[4 * k + 1]}, a1 = {g[4 * k + 2], g[4 * k + 3]};
+                        f32x2 a0 = {x[4 * k], x[4 * k + 1]}, a1 = {x[4 * k + 2], x[4 * k + 3]};
                         const bf16x2 b0 = __builtin_convertvector(a0, bf16x2), b1 = __builtin_convertvector(a1, bf16x2);
                         *reinterpret_cast<uint2*>(static_cast<bf16_t*>(dYv) + row * lddy + i0) =
                             make_uint2(__builtin_bit_cast(uint32_t, b0), __builtin_bit_cast(uint32_t, b1));
                     } else {
                         *reinterpret_cast<float4*>(static_cast<float*>(dYv) + row * lddy + i0) =
-                            make_float4(g[4 * k], g[4 * k + 1], g[4 * k + 2], g[4 * k + 3]);
+                            make_float4(x[4 * k], x[4 * k + 1], x[4 * k + 2], x[4 * k + 3]);
                     }
                 }
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int i = idx[4 * k + e];
-                    if (live[4 * k + e]) {
+                    const int i = at_index(k, e);
+                    if (i < n) {
                         if constexpr (BF16OUT) {
-                            const __bf16 hv = (__bf16)g[4 * k + e];
+                            const __bf16 hv = (__bf16)x[4 * k + e];
                             static_cast<bf16_t*>(dYv)[row * lddy + i] = __builtin_bit_cast(bf16_t, hv);
                         } else {
-                            static_cast<float*>(dYv)[row * lddy + i] = g[4 * k + e];
+                            static_cast<float*>(dYv)[row * lddy + i] = x[4 * k + e];
                         }
                     }
                 }
@@ -250,16 +300,15 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
 template <int OBJ, int V, int TPR>
 hipError_t launch_rows(const float* Y, long ldy, int T, int n, float scale, float levels, void* dY, int dy_is_bf16,
                        long lddy, double* partials, int grid, int batch, long sy, long sdy, hipStream_t s) {
-    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0 && (sy & 3) == 0 && (n & 3) == 0) ? 1 : 0;
-    if (dy_is_bf16) {
-        const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 7) == 0 && (lddy & 3) == 0 && (sdy & 3) == 0) ? 1 : 0;
-        hipLaunchKernelGGL((objective_rows_kernel<OBJ, V, TPR, true>), dim3(grid, batch), dim3(256), 0, s, Y, ldy, T, n,
-                           scale, levels, dY, lddy, partials, yvec, dvec, sy, sdy);
-    } else {
-        const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 3) == 0 && (sdy & 3) == 0) ? 1 : 0;
-        hipLaunchKernelGGL((objective_rows_kernel<OBJ, V, TPR, false>), dim3(grid, batch), dim3(256), 0, s, Y, ldy, T, n,
-                           scale, levels, dY, lddy, partials, yvec, dvec, sy, sdy);
-    }
+    const bool yvec = (reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0 && (sy & 3) == 0 && (n & 3) == 0;
+    const bool dvec = (reinterpret_cast<uintptr_t>(dY) & (dy_is_bf16 ? 7 : 15)) == 0 && (lddy & 3) == 0 && (sdy & 3) == 0;
+    const dim3 g(grid, batch), b(256);
+#define DQ_LAUNCH(BF, VEC)                                                                                        \
+    hipLaunchKernelGGL((objective_rows_kernel<OBJ, V, TPR, BF, VEC>), g, b, 0, s, Y, ldy, T, n, scale, levels, dY, \
+                       lddy, partials, sy, sdy)
+    if (yvec && dvec) { if (dy_is_bf16) DQ_LAUNCH(true, true); else DQ_LAUNCH(false, true); }
+    else              { if (dy_is_bf16) DQ_LAUNCH(true, false); else DQ_LAUNCH(false, false); }
+#undef DQ_LAUNCH
     return hipGetLastError();
 }
 
@@ -272,7 +321,10 @@ hipError_t launch_rows_shape(const float* Y, long ldy, int T, int n, float scale
     if (n <= 512) return DQ_ROWS(2, 64);
     if (n <= 1024) return DQ_ROWS(4, 64);
     if (n <= 2048) return DQ_ROWS(2, 256);
+    if (n <= 3072) return DQ_ROWS(3, 256);
     if (n <= 4096) return DQ_ROWS(4, 256);
+    if (n <= 5120) return DQ_ROWS(5, 256);
+    if (n <= 6144) return DQ_ROWS(6, 256);
     if (n <= 8192) return DQ_ROWS(8, 256);
 #undef DQ_ROWS
     return hipErrorInvalidValue;
@@ -283,7 +335,11 @@ hipError_t launch_rows_shape(const float* Y, long ldy, int T, int n, float scale
 int objective_grid(int T, int n) {
     const int rpw = n <= 1024 ? 4 : 1;
     long g = ((long)T + rpw - 1) / rpw;
-    if (g > 4096) g = 4096;
+    // measured at T = 8192..16384: rows of n > 1024 (one workgroup per row) run best with about 1024 workgroups
+    // that each walk several rows (the next row is fetched while one is worked on), short rows with 8192
+    static const long env_cap = [] { const char* e = getenv("DQ_OBJ_GRID"); return e ? atol(e) : 0L; }();
+    const long cap = env_cap > 0 ? env_cap : (n <= 1024 ? 8192L : 1024L);
+    if (g > cap) g = cap;
     return (int)(g < 1 ? 1 : g);
 }
 

@@ -251,6 +251,32 @@ def test_calib_step_with_objective(ctx, name):
     assert abs(loss.item() - orc.whip_loss(orc.rotate(X, out["R"]))) <= 1e-4 * abs(loss.item())
 
 
+@pytest.mark.parametrize("name", ["variance", "kurtosis", "quant"])
+def test_objective_full_size_rows(name):
+    """The 7B-shaped block in the launch shape the step uses (workspace Y and dY, bf16 dY): every row against the
+    oracle (the objectives are row-wise, so the oracle walks all 8192 rows in a few seconds)."""
+    T, n = 8192, 4096
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    Yd = torch.randn((T, n), device="cuda", generator=g) * (1.0 + 3.0 * torch.rand((T, 1), device="cuda", generator=g))
+    Yd[:, 17] *= 30.0                                  # an outlier channel
+    dYd = torch.empty((T, n), device="cuda", dtype=torch.bfloat16)
+    loss = torch.zeros(1, device="cuda")
+    c = B.Context(); c.ensure_workspace(1, 64, 64, B.DQ_F32)
+    try:
+        c.dq_objective_loss_grad(OBJECTIVES[name], 4, Yd, B.DQ_REDUCE_TOKEN_MEAN, loss, dYd, B.DQ_BF16)
+        torch.cuda.synchronize()
+    finally:
+        c.close()
+    Y = Yd.cpu().numpy()
+    ref_loss, ref_dY = orc.objective_loss_grad(Y, name, "mean", 4)
+    assert abs(loss.item() - ref_loss) <= 1e-5 * abs(ref_loss)
+    got = dYd.float().cpu().numpy()
+    assert rel(got, ref_dY) < 4e-3
+    # bf16 rounding of the fp32 gradient, entry by entry
+    scale = np.abs(ref_dY).max(axis=1, keepdims=True)
+    assert (np.abs(got - ref_dY) <= np.abs(ref_dY) * 2.0 ** -8 + scale * 1e-5).all()
+
+
 def test_objective_on_head_sized_batch_takes_the_general_route(ctx):
     b, T, n = 2, 256, 128
     cfg = synth.scaled_config("heads", b=b, T=T)
