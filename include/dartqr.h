@@ -142,7 +142,9 @@ dq_status dq_whip_loss_grad(dq_ctx* ctx, int b, int T, int n,
                             float* loss_dev, void* dY, dq_dtype dydt, long lddy);
 
 /* The same stage for any dq_objective (Sec. 5, objective ablation): loss_dev[i] and dY = d loss / dY on an existing
- * Y (fp32, b blocks of T x n).  quant_bits (1..16) is read by DQ_OBJ_QUANT only.  DQ_OBJ_WHIP is dq_whip_loss_grad. */
+ * Y (fp32, b blocks of T x n).  quant_bits (1..16) is read by DQ_OBJ_QUANT only.  DQ_OBJ_WHIP is dq_whip_loss_grad.
+ * With the three row objectives dY may be null: then only loss_dev is written, e.g. the per-token quantisation error
+ * of a rotated block as an evaluation metric (Sec. 5 measures activation quantisation error along the calibration). */
 dq_status dq_objective_loss_grad(dq_ctx* ctx, dq_objective objective, int quant_bits, int b, int T, int n,
                                  const float* Y, long ldy, dq_reduce red,
                                  float* loss_dev, void* dY, dq_dtype dydt, long lddy);

@@ -1021,13 +1021,14 @@ dq_status dq_objective_loss_grad(dq_ctx* c, dq_objective objective, int quant_bi
     if (n > DQ_MAX_N) return DQ_ERR_UNSUPPORTED;
     if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
     DQ_TRY(check_f32(Y, ldy, n));
-    DQ_TRY(check_x(dY, dydt, lddy, n));
+    if (dY != nullptr) DQ_TRY(check_x(dY, dydt, lddy, n));     // no dY: the loss alone (an evaluation metric)
+    else if (dydt != DQ_F32 && dydt != DQ_BF16) return DQ_ERR_DTYPE;
     if (c->ws == nullptr || c->ws_bytes < make_layout(1, 1).total) return DQ_ERR_WORKSPACE;
     const Layout L = make_layout(1, 1);
     unsigned* flags = at<unsigned>(c, L.flags);
     double* lpart = at<double>(c, L.losspart);
     const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
-    const size_t esz = (dydt == DQ_BF16) ? 2 : 4;
+    const size_t esz = dY == nullptr ? 0 : ((dydt == DQ_BF16) ? 2 : 4);
     if (b == 0) return DQ_OK;
     int grid = objective_grid(T, n);
     if ((long)grid * b > kLossPartials) grid = kLossPartials / b;

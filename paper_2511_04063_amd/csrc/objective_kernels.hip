@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
     __shared__ float red[64];
     __shared__ float tot[4];
     Y += (long)blockIdx.y * sy;
-    dYv = static_cast<char*>(dYv) + (long)blockIdx.y * sdy * (BF16OUT ? 2 : 4);
+    if (dYv != nullptr) dYv = static_cast<char*>(dYv) + (long)blockIdx.y * sdy * (BF16OUT ? 2 : 4);
     const int tid = threadIdx.x;
     constexpr int RPW = 256 / TPR;                 // rows a workgroup holds at a time
     const int t = tid % TPR, sub = tid / TPR;
@@ -256,7 +256,8 @@ __global__ __launch_bounds__(256) void objective_rows_kernel(const float* __rest
                 }
             }
         }
-        // dY from the registers, in the element order of the loads
+        // dY from the registers, in the element order of the loads (a caller that wants the loss only passes no dY)
+        if (dYv != nullptr)
 #pragma unroll
         for (int k = 0; k < V; ++k) {
             if constexpr (VEC) {

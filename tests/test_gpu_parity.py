@@ -313,6 +313,12 @@ def test_objective_errors(ctx):
     assert e.value.status == B.DQ_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert loss.item() == 5.0 and torch.all(dYd == 7.0)
+    # without dY the call is the metric alone
+    Y = objective_block(20, 300, 3300)
+    for name, obj in OBJECTIVES.items():
+        ctx.dq_objective_loss_grad(obj, 4, dev(Y), B.DQ_REDUCE_TOKEN_MEAN, loss, None, B.DQ_F32)
+        ref = orc.objective_loss_grad(Y, name, "mean", 4)[0]
+        assert abs(loss.item() - ref) <= 1e-5 * abs(ref)
     # all-zero block: zero loss and zero gradient under the three objectives
     for obj in OBJECTIVES.values():
         ctx.dq_objective_loss_grad(obj, 4, Yd, B.DQ_REDUCE_SUM, loss, dYd, B.DQ_F32)
