@@ -90,6 +90,10 @@ def main():
     ap.add_argument("--objective", choices=["whip", "variance", "kurtosis", "quant"], default="whip",
                     help="what S4 evaluates: Eq. 4 (the headline metric) or one of the objectives the paper compares "
                          "it with (Sec. 5, objective ablation)")
+    ap.add_argument("--host-batches", type=int, default=0,
+                    help="also time the mini-batch loop with this many batches in pinned HOST memory "
+                         "(dq_calib_run_host_batches: copies overlap the steps); reported beside the headline value, "
+                         "which always has its inputs resident in HBM")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -218,6 +222,24 @@ def main():
 
     stages = None if args.no_stage_roofline else stage_times()
 
+    host_loop = None
+    if args.host_batches > 0 and cfg.b == 1 and args.optimizer == "sgd":
+        host = [Xd.cpu().pin_memory() for _ in range(args.host_batches)]
+        staging = torch.empty((2,) + tuple(Xd.shape), device="cuda", dtype=Xd.dtype)
+        hl = torch.zeros(max(args.steps, 2), device="cuda")
+        Zh = Z0.clone()
+        ctx.dq_calib_run_host_batches(host, xdt, staging, Zh, cfg.lr, red, 2, hl)
+        Zh.copy_(Z0)
+        torch.cuda.synchronize()
+        th = time.perf_counter()
+        ctx.dq_calib_run_host_batches(host, xdt, staging, Zh, cfg.lr, red, args.steps, hl)
+        torch.cuda.synchronize()
+        th = time.perf_counter() - th
+        host_loop = {"batches": args.host_batches, "bytes_per_batch": Xd.numel() * Xd.element_size(),
+                     "ms_per_step": th * 1e3 / args.steps, "steps_per_s": args.steps / th,
+                     "note": "one batch crosses PCIe per step, overlapped with the previous step"}
+        del host, staging
+
     ms_per_step = dt * 1e3 / args.steps
     F = flops_per_step(cfg.n, cfg.T, cfg.b)
     launches = max(1, dom["launches"])
@@ -259,6 +281,7 @@ def main():
         "loss_first": first_loss, "loss_last": last_loss, "device_flags": flags,
         "roofline": roof,
         "stage_roofline": stages,
+        "host_batch_loop": host_loop,
         "stage_ms_one_step": {k: round(v["ms"], 4) for k, v in breakdown.items()},
         "stage_launches_one_step": {k: v["launches"] for k, v in breakdown.items()},
     }

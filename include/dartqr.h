@@ -134,6 +134,20 @@ dq_status dq_calib_step(dq_ctx* ctx, int b, int T, int n,
                         float* Z, long ldz, float lr, dq_reduce red,
                         float* loss_dev, float* R_or_null, long ldr);
 
+/* Alg. 1 lines 3-11, the loop over mini-batches with the calibration set in HOST memory: step k (k = 0 .. steps-1) is
+ * dq_calib_step on batch k % num_batches, and batch k + 1 travels to the device on an internal stream while step k
+ * runs (two staging slots).  One problem (b = 1).
+ * X_host: HOST array of num_batches HOST pointers, each a T x n block of dtype xdt with leading dimension ldx.  Pinned
+ *   buffers (hipHostMalloc) make the copies asynchronous; pageable ones work and serialise.  The blocks must stay
+ *   valid and unchanged until the context's stream has finished the call's work.
+ * staging_dev: DEVICE memory for two batches, 2 * T * ldx elements of xdt, 16-byte aligned; contents are overwritten.
+ * Z: in/out, fp32 n x n.  losses_dev: out, `steps` DEVICE floats, the loss of each step's input Z.
+ * The workspace is that of dq_workspace_bytes(1, n, T, xdt).  steps == 0 is a no-op. */
+dq_status dq_calib_run_host_batches(dq_ctx* ctx, int T, int n,
+                                    const void* const* X_host, int num_batches, dq_dtype xdt, long ldx,
+                                    void* staging_dev, float* Z, long ldz, float lr, dq_reduce red,
+                                    int steps, float* losses_dev);
+
 /* ---- stages exported on their own (stage-level parity tests, reuse) -------------------- */
 
 /* Eq. 4 and its derivative on an existing Y (fp32, T x n): loss_dev[i] and dY (dtype dydt). */

@@ -89,6 +89,7 @@ __all__ = [
     "kurtosis_objective",
     "quant_objective",
     "objective_loss_grad",
+    "calibrate_batches",
 ]
 
 
@@ -429,3 +430,15 @@ def calibrate(X, Z0, steps: int, lr: float, reduce: str = "mean"):
         Z = out["Z_new"]
     R_final, _ = qr_orth(Z)
     return np.array(losses), Z, R_final
+
+
+def calibrate_batches(X_batches, Z0, steps: int, lr: float, reduce: str = "mean"):
+    """The loop of Alg. 1 over mini-batches (lines 3-11): step k runs the loop body on batch k mod len(X_batches),
+    epoch after epoch in the given order.  Returns (losses, Z_final)."""
+    Z = _f64(Z0)
+    losses = []
+    for k in range(int(steps)):
+        out = calib_step(X_batches[k % len(X_batches)], Z, lr, reduce)
+        losses.append(out["loss"])
+        Z = out["Z_new"]
+    return np.array(losses), Z

@@ -42,6 +42,7 @@ SIGNATURES = {
     "dq_hadamard_init": (_i, [_vp, _i, _i, _vp, _vp, _l]),
     "dq_objective_loss_grad": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_set_objective": (_i, [_vp, _i, _i]),
+    "dq_calib_run_host_batches": (_i, [_vp, _i, _i, _vp, _i, _i, _l, _vp, _vp, _l, _f, _i, _i, _vp]),
     "dq_outlier_count": (_i, [_vp, _i, _i, _i, _vp, _l, _f, _vp]),
     "dq_gather_rows": (_i, [_vp, _i, _i, _i, _i, _vp, _i, _l, _vp, _vp, _l]),
     "dq_adam_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f]),
@@ -178,6 +179,18 @@ class Context:
         T, n = X.shape[-2], X.shape[-1]
         self._check(self.lib.dq_calib_step(self.h, b, T, n, _ptr(X), x_dtype, _ld(X), _ptr(Z), _ld(Z), float(lr),
                                            reduce, _ptr(loss), _ptr(R), _ld(R)), "dq_calib_step")
+
+    def dq_calib_run_host_batches(self, X_host_batches, x_dtype, staging, Z, lr, reduce, steps, losses):
+        """X_host_batches: list of host tensors (T x n, ideally pinned); staging: device tensor (2, T, n)."""
+        T, n = X_host_batches[0].shape
+        for x in X_host_batches:
+            assert not x.is_cuda and tuple(x.shape) == (T, n) and _ld(x) == _ld(X_host_batches[0])
+        ptrs = (_c.c_void_p * len(X_host_batches))(*[int(x.data_ptr()) for x in X_host_batches])
+        assert staging.is_cuda and staging.numel() >= 2 * T * _ld(X_host_batches[0])
+        self._check(self.lib.dq_calib_run_host_batches(self.h, T, n, ptrs, len(X_host_batches), x_dtype,
+                                                       _ld(X_host_batches[0]), _ptr(staging), _ptr(Z), _ld(Z),
+                                                       float(lr), reduce, int(steps), _ptr(losses)),
+                    "dq_calib_run_host_batches")
 
     # ---- stages
     def dq_whip_loss_grad(self, Y, reduce, loss, dY, dy_dtype):

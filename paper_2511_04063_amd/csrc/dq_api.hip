@@ -50,6 +50,9 @@ struct dq_ctx {
     hipStream_t stream2 = nullptr;   // internal: trailing updates of the QR run here while the next panel is factored
     hipStream_t stream3 = nullptr;   // internal: the orthogonal factor is accumulated here, also behind the panels
     std::vector<hipEvent_t> sync_ev; // 2 per panel: look-ahead part done (even), trailing part done (odd); + 1 join
+    hipStream_t copy_stream = nullptr;   // internal, created on first use: host-to-device copies of the next mini-batch
+    hipEvent_t batch_ready[2] = {nullptr, nullptr};   // staging slot holds its batch (recorded on copy_stream)
+    hipEvent_t batch_done[2] = {nullptr, nullptr};    // the step that read the slot has run (recorded on stream)
     int device = 0;
     int nb = kPanel;                 // QR panel width (<= kPanel)
     int chol_min_m = 64;             // full-width panels at least this tall take the many-CU route (0: never)
@@ -858,6 +861,11 @@ dq_status dq_destroy(dq_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     if (c->stream2 != nullptr) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->stream3 != nullptr) { (void)hipStreamSynchronize(c->stream3); (void)hipStreamDestroy(c->stream3); }
+    if (c->copy_stream != nullptr) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamDestroy(c->copy_stream); }
+    for (int i = 0; i < 2; ++i) {
+        if (c->batch_ready[i] != nullptr) (void)hipEventDestroy(c->batch_ready[i]);
+        if (c->batch_done[i] != nullptr) (void)hipEventDestroy(c->batch_done[i]);
+    }
     for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->sync_ev) (void)hipEventDestroy(e);
     delete c;
@@ -980,6 +988,54 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
                                     at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld, false));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, nullptr, 0, Zi, ldz, lr));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_calib_run_host_batches(dq_ctx* c, int T, int n, const void* const* X_host, int num_batches, dq_dtype xdt,
+                                    long ldx, void* staging_dev, float* Z, long ldz, float lr, dq_reduce red, int steps,
+                                    float* losses_dev) {
+    if (c == nullptr || X_host == nullptr || staging_dev == nullptr || Z == nullptr || losses_dev == nullptr)
+        return DQ_ERR_NULL;
+    if (T < 1 || num_batches < 1 || steps < 0) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    DQ_TRY(check_x(staging_dev, xdt, ldx, n));
+    DQ_TRY(check_f32(Z, ldz, n));
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    for (int i = 0; i < num_batches; ++i)
+        if (X_host[i] == nullptr) return DQ_ERR_NULL;
+    size_t need = 0;
+    DQ_TRY(dq_workspace_bytes(1, n, T, xdt, &need));
+    if (c->ws == nullptr || c->ws_bytes < need) return DQ_ERR_WORKSPACE;
+    if (steps == 0) return DQ_OK;
+    if (c->copy_stream == nullptr) {
+        // default priority, like every stream of this library
+        if (hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) != hipSuccess) return DQ_ERR_HIP;
+        for (int i = 0; i < 2; ++i) {
+            DQ_HIP(hipEventCreateWithFlags(&c->batch_ready[i], hipEventDisableTiming));
+            DQ_HIP(hipEventCreateWithFlags(&c->batch_done[i], hipEventDisableTiming));
+        }
+    }
+    const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
+    const size_t batch_bytes = (size_t)T * ldx * esz;
+    char* slot[2] = {static_cast<char*>(staging_dev), static_cast<char*>(staging_dev) + batch_bytes};
+    // whatever the caller's stream still does with the staging memory comes first
+    DQ_HIP(hipEventRecord(c->batch_done[0], c->stream));
+    DQ_HIP(hipStreamWaitEvent(c->copy_stream, c->batch_done[0], 0));
+    DQ_HIP(hipMemcpyAsync(slot[0], X_host[0], batch_bytes, hipMemcpyHostToDevice, c->copy_stream));
+    DQ_HIP(hipEventRecord(c->batch_ready[0], c->copy_stream));
+    for (int k = 0; k < steps; ++k) {
+        const int cur = k & 1, nxt = cur ^ 1;
+        if (k + 1 < steps) {
+            // the other slot was last read by step k - 1
+            if (k >= 1) DQ_HIP(hipStreamWaitEvent(c->copy_stream, c->batch_done[nxt], 0));
+            DQ_HIP(hipMemcpyAsync(slot[nxt], X_host[(k + 1) % num_batches], batch_bytes, hipMemcpyHostToDevice,
+                                  c->copy_stream));
+            DQ_HIP(hipEventRecord(c->batch_ready[nxt], c->copy_stream));
+        }
+        DQ_HIP(hipStreamWaitEvent(c->stream, c->batch_ready[cur], 0));
+        DQ_TRY(dq_calib_step(c, 1, T, n, slot[cur], xdt, ldx, Z, ldz, lr, red, losses_dev + k, nullptr, 0));
+        DQ_HIP(hipEventRecord(c->batch_done[cur], c->stream));
     }
     return DQ_OK;
 }

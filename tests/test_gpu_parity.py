@@ -325,6 +325,50 @@ def test_objective_errors(ctx):
         assert loss.item() == 0.0 and not dYd.any()
 
 
+# ----------------------------------------------------------------------------------- mini-batch loop from host memory
+@pytest.mark.parametrize("bf16,pinned", [(False, True), (True, True), (False, False)])
+def test_calib_run_host_batches(bf16, pinned):
+    n, T, nb, steps = 192, 512, 3, 7
+    cfg = synth.scaled_config("7b" if bf16 else "tiny", n=n, T=T)
+    batches = [synth.make_inputs(cfg, seed=40 + i)["X"][0] for i in range(nb)]
+    Z0 = synth.make_inputs(cfg, seed=40)["Z0"][0]
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    xdt = B.DQ_BF16 if bf16 else B.DQ_F32
+    host = []
+    for x in batches:
+        t = torch.from_numpy(x).to(tdt)
+        host.append(t.pin_memory() if pinned else t.contiguous())
+    c = B.Context(); c.ensure_workspace(1, n, T, xdt)
+    try:
+        # reference on the GPU: the same steps on batches that already sit in device memory
+        Zr = dev(Z0.copy()); lr_ = 1e-2
+        ref_losses = torch.zeros(steps, device="cuda")
+        devb = [h.cuda() for h in host]
+        for k in range(steps):
+            c.dq_calib_step(devb[k % nb], xdt, Zr, lr_, B.DQ_REDUCE_TOKEN_MEAN, ref_losses[k:k + 1])
+        staging = torch.full((2, T, n), float("nan"), device="cuda", dtype=tdt)
+        Zd = dev(Z0.copy())
+        losses = torch.zeros(steps, device="cuda")
+        c.dq_calib_run_host_batches(host, xdt, staging, Zd, lr_, B.DQ_REDUCE_TOKEN_MEAN, steps, losses)
+        torch.cuda.synchronize()
+        assert torch.equal(losses, ref_losses) and torch.equal(Zd, Zr)      # same kernels on the same bytes
+        # a second call on the same context (events and staging reused), fewer steps than slots
+        Z2 = dev(Z0.copy()); l2 = torch.zeros(1, device="cuda")
+        c.dq_calib_run_host_batches(host, xdt, staging, Z2, lr_, B.DQ_REDUCE_TOKEN_MEAN, 1, l2)
+        torch.cuda.synchronize()
+        assert l2.item() == ref_losses[0].item()
+        assert c.dq_device_flags() == 0
+    finally:
+        c.close()
+    o_losses, o_Z = orc.calibrate_batches(batches, Z0, steps, 1e-2)
+    got = losses.cpu().numpy()
+    # first step to the stage bar; a trajectory of several steps drifts from the fp64 one (entries of Y near zero take the
+    # other sign of the discontinuous dY, see the end-to-end tolerances of the single-step tests)
+    assert abs(got[0] - o_losses[0]) <= 1e-4 * o_losses[0]
+    assert np.abs(got - o_losses).max() <= 5e-3 * o_losses.max()
+    assert rel(Zd.cpu().numpy(), o_Z) < 5e-3
+
+
 # ----------------------------------------------------------------------------------- QR-Orth
 def run_qr(ctx, Z, want_u=True, ld=None):
     n = Z.shape[-1]

@@ -75,6 +75,7 @@ def test_null_context_is_refused_everywhere(lib):
     assert lib.dq_whip_loss_grad(z, 1, 8, 8, z, 8, 0, z, z, 0, 8) == B.DQ_ERR_NULL
     assert lib.dq_objective_loss_grad(z, 1, 4, 1, 8, 8, z, 8, 0, z, z, 0, 8) == B.DQ_ERR_NULL
     assert lib.dq_set_objective(z, 1, 4) == B.DQ_ERR_NULL
+    assert lib.dq_calib_run_host_batches(z, 8, 8, z, 1, 0, 8, z, z, 8, 0.1, 0, 1, z) == B.DQ_ERR_NULL
     assert lib.dq_sgd_update(z, 1, 8, z, 8, z, 8, 0.1) == B.DQ_ERR_NULL
     assert lib.dq_gemm_f32(z, 8, 8, 8, 1.0, z, 8, 0, z, 8, 0, 0.0, z, 8) == B.DQ_ERR_NULL
     assert lib.dq_gemm_bf16(z, 8, 8, 8, z, 8, 0, z, 8, 0, z, 8) == B.DQ_ERR_NULL

@@ -736,3 +736,25 @@ def test_objective_dispatch_and_step():
     R, _ = orc.qr_orth(Z)
     l1 = orc.rotate_loss_grad(Xc, R, "sum", "variance")[0]
     assert l1 + np.sum((Xc @ R).mean(axis=1) ** 2) == pytest.approx(np.sum(Xc * Xc) / 8, rel=1e-12)
+
+
+def test_calibrate_batches_pins():
+    rng = np.random.default_rng(401)
+    Xs = [rng.standard_normal((24, 6)) for _ in range(3)]
+    Z0 = rng.standard_normal((6, 6))
+    # one batch: the plain loop
+    l1, Z1 = orc.calibrate_batches(Xs[:1], Z0, 4, 1e-2)
+    l2, Z2, _ = orc.calibrate(Xs[0], Z0, 4, 1e-2)
+    assert np.array_equal(l1, l2) and np.array_equal(Z1, Z2)
+    # three batches, five steps: batch order 0 1 2 0 1, written out
+    losses, Z = orc.calibrate_batches(Xs, Z0, 5, 1e-2)
+    Zm = Z0.copy()
+    for k, j in enumerate([0, 1, 2, 0, 1]):
+        out = orc.calib_step(Xs[j], Zm, 1e-2)
+        assert out["loss"] == losses[k]
+        Zm = out["Z_new"]
+    assert np.array_equal(Z, Zm)
+    # with the sum reduction, one step on the stacked batches is the sum of the per-batch gradients at the same Z
+    g_all = orc.calib_step(np.vstack(Xs), Z0, 1.0, "sum")["dZ"]
+    g_sum = sum(orc.calib_step(x, Z0, 1.0, "sum")["dZ"] for x in Xs)
+    np.testing.assert_allclose(g_all, g_sum, rtol=1e-10, atol=1e-12)
