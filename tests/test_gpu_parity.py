@@ -82,6 +82,40 @@ def test_gemm_f32(ctx, ta, tb, M, N, K):
     assert torch.all(Cbuf[:, N:] == 123.0)
 
 
+# the shape of the QR's trailing updates and of the accumulation of the rotation: a short reduction over a large
+# output (a full wave of tiles and more), ragged K, ragged edges of C, both operand layouts, with and without the read
+# of C
+@pytest.mark.parametrize("ta,tb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(2049, 2055, 64), (2060, 2048, 130), (2048, 2176, 256), (2048, 2048, 7)])
+def test_gemm_f32_rank_update(ta, tb, M, N, K):
+    g = rng(1500 + M + N + K + 2 * ta + tb)
+    A = g.standard_normal((K, M) if ta else (M, K)).astype(np.float32)
+    Bm = g.standard_normal((N, K) if tb else (K, N)).astype(np.float32)
+    C0 = g.standard_normal((M, N)).astype(np.float32)
+    lda = -(-A.shape[1] // 4) * 4 + 4
+    ldb = -(-Bm.shape[1] // 4) * 4
+    ldc = -(-N // 4) * 4 + 8
+    _, Ad = padded(A.shape[0], A.shape[1], lda); Ad.copy_(dev(A))
+    _, Bd = padded(Bm.shape[0], Bm.shape[1], ldb); Bd.copy_(dev(Bm))
+    Cbuf, Cd = padded(M, N, ldc, fill=123.0); Cd.copy_(dev(C0))
+    c = B.Context(); c.ensure_workspace(1, 64, 64, B.DQ_F32)
+    try:
+        c.dq_gemm_f32(M, N, K, -1.0, Ad, ta, Bd, tb, 1.0, Cd)
+        opA = A.T.astype(np.float64) if ta else A.astype(np.float64)
+        opB = Bm.T.astype(np.float64) if tb else Bm.astype(np.float64)
+        prod = opA @ opB
+        got = Cd.cpu().numpy()
+        assert rel(got, C0 - prod) < 2e-6
+        assert np.abs(got - (C0 - prod)).max() < 2e-5 * max(1.0, np.abs(prod).max())
+        assert torch.all(Cbuf[:, N:] == 123.0)
+        Cd.fill_(float("nan"))                      # beta == 0 must not read C
+        c.dq_gemm_f32(M, N, K, 0.5, Ad, ta, Bd, tb, 0.0, Cd)
+        assert rel(Cd.cpu().numpy(), 0.5 * prod) < 2e-6
+        torch.cuda.synchronize()
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("ta,tb", [(0, 1), (1, 0), (0, 0), (1, 1)])
 @pytest.mark.parametrize("M,N,K", [(300, 200, 160), (130, 258, 40), (72, 136, 1000)])
 def test_gemm_bf16(ctx, ta, tb, M, N, K):
