@@ -72,6 +72,23 @@ __device__ __forceinline__ void fetch_tile(const OperandView& o, int mn0, int k0
     }
 }
 
+// The same for a tile that lies inside the operand with 16-byte aligned rows and needs no mask: plain 16-byte loads.
+template <bool KC, int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile_inner(const float* __restrict__ p, long ld, int mn0, int k0, int tid,
+                                                 float4 (&frag)[ROWS * BK / 1024]) {
+#pragma unroll
+    for (int i = 0; i < ROWS * BK / 1024; ++i) {
+        const int f = tid + 256 * i;
+        if (KC) {
+            const int r = f / (BK / 4), kq = (f % (BK / 4)) << 2;
+            frag[i] = *reinterpret_cast<const float4*>(p + (long)(mn0 + r) * ld + k0 + kq);
+        } else {
+            const int kr = f / (ROWS / 4), c4 = (f % (ROWS / 4)) << 2;
+            frag[i] = *reinterpret_cast<const float4*>(p + (long)(k0 + kr) * ld + mn0 + c4);
+        }
+    }
+}
+
 template <bool KC, int ROWS, int BK>
 __device__ __forceinline__ void stash_tile(float (*S)[ROWS + 4], int tid, const float4 (&frag)[ROWS * BK / 1024]) {
 #pragma unroll
@@ -157,20 +174,30 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     const int lrow = lane & 31, lk = lane >> 5;
 
     const int nk = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    // A tile whose operand blocks and output block lie wholly inside the matrices, with aligned rows and out of reach
+    // of the unit-lower masks, takes loaders and an epilogue without bounds checks: the checks cost more instructions
+    // than the products of a short K loop.
+    const bool inner = avec && bvec && m0 + BM <= g.M && n0 + BN <= g.N && ke > kb && (ke - kb) % BK == 0 &&
+                       (!g.a_unit_lower || (!TA && m0 >= ke)) && (g.b_unit_lower_cols == 0 || (TB && n0 >= ke));
     float4 fa[BM * BK / 1024], fb[BN * BK / 1024];
+    auto fetch_both = [&](int k0) {
+        if (inner) {
+            fetch_tile_inner<!TA, BM, BK>(oa.p, oa.ld, m0, k0, tid, fa);
+            fetch_tile_inner<TB, BN, BK>(ob.p, ob.ld, n0, k0, tid, fb);
+        } else {
+            fetch_tile<!TA, BM, BK>(oa, m0, k0, tid, fa);
+            fetch_tile<TB, BN, BK>(ob, n0, k0, tid, fb);
+        }
+    };
     if (nk > 0) {
-        fetch_tile<!TA, BM, BK>(oa, m0, kb, tid, fa);
-        fetch_tile<TB, BN, BK>(ob, n0, kb, tid, fb);
+        fetch_both(kb);
         stash_tile<!TA, BM, BK>(As[0], tid, fa);
         stash_tile<TB, BN, BK>(Bs[0], tid, fb);
     }
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            fetch_tile<!TA, BM, BK>(oa, m0, kb + (kt + 1) * BK, tid, fa);
-            fetch_tile<TB, BN, BK>(ob, n0, kb + (kt + 1) * BK, tid, fb);
-        }
+        if (kt + 1 < nk) fetch_both(kb + (kt + 1) * BK);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
             float a[WT], b[WT];
@@ -193,6 +220,42 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
 
     float* C = g.C + bz * g.batch_c + (long)z * g.split_stride;
     const float alpha = g.alpha, beta = g.beta;
+    if (inner) {
+        // one base pointer per 32 x 32 block and constant row offsets from it
+        float* cb[WT][WT];
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+#pragma unroll
+            for (int j = 0; j < WT; ++j) cb[i][j] = C + (long)(m0 + wm + i * 32 + 4 * lk) * g.ldc + n0 + wn + j * 32 + lrow;
+        if (beta != 0.f) {
+            float cin[WT][WT][16];
+#pragma unroll
+            for (int i = 0; i < WT; ++i)
+#pragma unroll
+                for (int j = 0; j < WT; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) cin[i][j][v] = cb[i][j][(long)(8 * (v >> 2) + (v & 3)) * g.ldc];
+#pragma unroll
+            for (int i = 0; i < WT; ++i)
+#pragma unroll
+                for (int j = 0; j < WT; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = alpha * acc[i][j][v] + beta * cin[i][j][v];
+        } else {
+#pragma unroll
+            for (int i = 0; i < WT; ++i)
+#pragma unroll
+                for (int j = 0; j < WT; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] *= alpha;
+        }
+#pragma unroll
+        for (int i = 0; i < WT; ++i)
+#pragma unroll
+            for (int j = 0; j < WT; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cb[i][j][(long)(8 * (v >> 2) + (v & 3)) * g.ldc] = acc[i][j][v];
+    } else {
     // All reads of C are issued before the first write: interleaved they would serialise on possible aliasing and
     // expose one memory round trip per element.
     if (beta != 0.f) {
@@ -231,6 +294,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
             }
         }
     }
+    }   // guarded epilogue
 }
 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, long stride,
