@@ -57,8 +57,8 @@ struct dq_ctx {
     int nb = kPanel;                 // QR panel width (<= kPanel)
     int chol_min_m = 64;             // full-width panels at least this tall take the many-CU route (0: never)
     bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
-    int accum_panels = 2;            // panels merged per update of the accumulated R (1: panel by panel; 2 measured
-                                     // best at n = 4096, 2 and 4 equal at n = 8192)
+    int accum_panels = 0;            // panels merged per update of the accumulated R (0: by size, 2 below n = 8192 and
+                                     // 4 from there on, each measured best there; 1: panel by panel)
     int objective = DQ_OBJ_WHIP;     // what S4 evaluates (dq_set_objective)
     int quant_bits = 4;
     char* ws = nullptr;
@@ -500,8 +500,9 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
         // left to the right, Q[:, k0:] <- Q[:, k0:] (I - V T V^T)  (as Alg. 2 does column by column), on the third
         // stream, several panels at a time.
-        if ((p + 1) % c->accum_panels == 0 || p == npanels - 1) {
-            const int q0 = (p / c->accum_panels) * c->accum_panels;
+        const int ap = c->accum_panels > 0 ? c->accum_panels : (n >= 8192 ? 4 : 2);
+        if ((p + 1) % ap == 0 || p == npanels - 1) {
+            const int q0 = (p / ap) * ap;
             DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
             if (p - q0 + 1 == 1)
                 DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Yp, R, ldr));

@@ -830,11 +830,13 @@ struct TallScratch {
 void tall_split(int m, int& tpw, int& nparts) {
     static const int parts_cap = [] {
         const char* e = getenv("DQ_TALL_PANEL_PARTS");
-        int v = e ? atoi(e) : 32;
-        return v < 1 ? 1 : (v > kCholMaxParts ? kCholMaxParts : v);
+        int v = e ? atoi(e) : 0;
+        return v < 1 ? 0 : (v > kCholMaxParts ? kCholMaxParts : v);
     }();
+    // by size unless overridden: 32 up to m = 4096, 64 above (30.4 against 31.0 ms for the QR at n = 8192)
+    const int cap = parts_cap > 0 ? parts_cap : (m > 4096 ? 64 : 32);
     const int tiles = (m + RT - 1) / RT;
-    tpw = (tiles + parts_cap - 1) / parts_cap;
+    tpw = (tiles + cap - 1) / cap;
     nparts = (tiles + tpw - 1) / tpw;
 }
 }  // namespace
