@@ -670,6 +670,12 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     const int qi = (wave >> 1) & 1, qj = wave & 1;
 
     ST_DECL;
+    // U1 and the top block of Q1 are needed well after the partials are summed: requested now, they arrive meanwhile
+    float u1r[16], q1r[16];
+    if (tid < NTHR) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) { u1r[q] = U1[tid + NTHR * q]; q1r[q] = q1[tid + NTHR * q]; }
+    }
     sum_partials(part, nparts, B0, tid);
     ST(0);
     {   // ||G2 - I||_F^2 must be small: then Q1 is well conditioned and the second pass gives orthonormal columns
@@ -727,7 +733,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
-        B2[(e >> 6) * LS + (e & 63)] = U1[e];
+        B2[(e >> 6) * LS + (e & 63)] = u1r[q];
     }
     __syncthreads();
     // Rf = U2 U1 (upper x upper): kept in registers until the row signs are known
@@ -737,7 +743,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
-        B2[(e >> 6) * LS + (e & 63)] = q1[e];
+        B2[(e >> 6) * LS + (e & 63)] = q1r[q];
     }
     __syncthreads();
     {   // Q_top = Q1_top U2^-1  -> B0
