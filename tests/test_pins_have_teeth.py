@@ -9,7 +9,10 @@ import numpy as np
 import pytest
 
 from oracle import dartqr_oracle as orc
-from tests import test_oracle_pins as pins
+try:                                    # pytest's default import mode puts tests/ itself on the path
+    import test_oracle_pins as pins
+except ImportError:                     # other import modes: through the repository root
+    from tests import test_oracle_pins as pins
 
 
 def _f64(a):
