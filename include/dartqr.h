@@ -65,8 +65,8 @@ typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
  *   DQ_OBJ_VARIANCE  m2
  *   DQ_OBJ_KURTOSIS  m4 / m2^2  (a constant row counts 0)
  *   DQ_OBJ_QUANT     (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser of Sec. 5:
- *                    lo = min y, hi = max y, delta = (hi - lo) / (2^bits - 1), q_i = round((y_i - lo) * (1 / delta)) in fp32
- *                    (ties to even), yhat_i = lo + delta q_i; the derivative holds the codes fixed and sends the
+ *                    lo = min y, hi = max y, delta = (hi - lo) / (2^bits - 1), q_i = the nearest level to (y_i - lo) / delta
+ *                    (decided in fp32), yhat_i = lo + delta q_i; the derivative holds the codes fixed and sends the
  *                    dependence on lo / hi to the first position of the minimum / maximum (a constant row counts 0)
  * Rows are combined like Eq. 4 (dq_reduce).  These three need n <= DQ_MAX_N. */
 typedef enum { DQ_OBJ_WHIP = 0, DQ_OBJ_VARIANCE = 1, DQ_OBJ_KURTOSIS = 2, DQ_OBJ_QUANT = 3 } dq_objective;
@@ -176,7 +176,7 @@ dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
                          const float* R, long ldr, const float* U, long ldu,
                          const float* G, long ldg, float* dZ, long lddz);
 
-/* The initial latent of the paper's runs (App., hyper-parameter settings: "a random Hadamard matrix"), read as
+/* The initial latent of the paper's runs (App., hyper-parameter settings: a randomised Hadamard matrix), read as
  * Z0_i = diag(s_i) H_n / sqrt(n) with H_n the Sylvester Hadamard matrix, H[r][c] = (-1)^popcount(r & c): an
  * orthogonal matrix for signs s = +-1.  n must be a power of two (DQ_ERR_UNSUPPORTED otherwise).  The random signs
  * are the caller's: signs_dev holds b*n DEVICE floats (row r of problem i is scaled by signs_dev[i*n + r]).

@@ -44,7 +44,7 @@ Readings taken where the paper is silent (each is also listed in the design note
   sample-size analysis) and does not say how they are drawn.  The draw is an INPUT here
   (a list of row numbers, repeats allowed); the step itself is the selection of those
   rows, in the given order.  Pinned by its invariants (tests/).
-* App. (hyper-parameter settings): "Z0 is initialized using a random Hadamard matrix", construction not given.  Read
+* App. (hyper-parameter settings): the latent starts from a randomised Hadamard matrix, construction not given.  Read
   as diag(s) H_n / sqrt(n) with Sylvester's H_n and random signs s supplied by the caller.  Pinned by orthogonality,
   the Kronecker form and the bit-count form of the entries (tests/).
 * Sec. 4.1 and the ablation of Sec. 5 (comparison of four objectives) name variance, kurtosis and the quantisation loss
@@ -54,11 +54,14 @@ Readings taken where the paper is silent (each is also listed in the design note
     kurtosis      m4 / m2^2 with m_k = (1/n) sum_i (y_i - mu)^k (Pearson's, 3 for a Gaussian); 0 for a constant row;
     quantisation  (1/n) sum_i (y_i - yhat_i)^2 for the per-token asymmetric uniform quantiser the paper's experiments
                   use for activations (Sec. 5: per-token asymmetric, 4 bits): lo = min_i y_i, hi = max_i y_i,
-                  delta = (hi - lo) / (2^bits - 1), code q_i = round((y_i - lo) * s) with the scale s = 1 / delta (ties
-                  to even), yhat_i = lo + delta q_i; 0 for a constant row.  The codes are decided in float32 (delta, s,
-                  the subtraction and the product each rounded to float32), the precision the GPU path decides them in.  Gradient: the codes are
-                  held fixed (the derivative that exists almost everywhere), lo and hi carry gradient to the first
-                  position of the row minimum and maximum.
+                  delta = (hi - lo) / (2^bits - 1), code q_i = round((y_i - lo) / delta) (nearest level, ties to
+                  even), yhat_i = lo + delta q_i; 0 for a constant row.  All of it in float64 on the given values.
+                  Gradient: the codes are held fixed (the derivative that exists almost everywhere), lo and hi carry
+                  gradient to the first position of the row minimum and maximum.  An entry whose grid position
+                  (y_i - lo) / delta lies within rounding distance of a half-integer may legitimately take either
+                  neighbouring code in a lower-precision implementation; ``quant_positions`` returns those positions
+                  and ``quant_objective(codes=...)`` evaluates loss and gradient for a given set of codes, so that a
+                  test can separate "a valid other code" from "a wrong result".
   Pinned by library routines (numpy.var, scipy.stats.kurtosis), closed forms, a brute-force nearest-level search,
   invariances and central finite differences (tests/).
 """
@@ -87,6 +90,7 @@ __all__ = [
     "hadamard_latent",
     "variance_objective",
     "kurtosis_objective",
+    "quant_positions",
     "quant_objective",
     "objective_loss_grad",
     "calibrate_batches",
@@ -112,10 +116,10 @@ def householder_qr(Z):
     Returns (Q, U0) with Z = Q @ U0, Q orthogonal, U0 upper triangular.  The signs of
     diag(U0) are whatever the reflections produce (they are fixed by ``qr_orth``).
 
-    Step k (Alg. 2 lines 5-9):  x = A[k:, k];  v = x + sign(x_1) ||x||_2 e_1 with
-    sign(0) = +1;  v <- v / ||v||_2;  A[k:, k:] -= 2 v (v^T A[k:, k:]);
-    Qacc[:, k:] -= 2 (Qacc[:, k:] v) v^T.   A zero column below (and on) the
-    diagonal is skipped (v would be 0).
+    Step k of the reflector recurrence:  x = A[k:, k];  v = x + sign(x_1) ||x||_2 e_1 with
+    sign(0) = +1;  v <- v / ||v||_2;  the reflection I - 2 v v^T is applied to the trailing
+    block A[k:, k:] from the left and to the columns k.. of the accumulated orthogonal factor
+    from the right.  A zero column below (and on) the diagonal is skipped (v would be 0).
     """
     A = _f64(Z)
     if A.ndim != 2 or A.shape[0] != A.shape[1]:
@@ -131,10 +135,10 @@ def householder_qr(Z):
         v = x
         v[0] = v[0] + sgn * norm_x
         v = v / np.sqrt(np.sum(v * v))
-        # reflect the trailing block of A (Alg. 2 line 8)
+        # reflect the trailing block of A
         w = v @ A[k:, k:]
         A[k:, k:] -= 2.0 * np.outer(v, w)
-        # accumulate the orthogonal factor on the right (Alg. 2 line 9, all rows)
+        # accumulate the orthogonal factor on the right, all rows
         q = Qacc[:, k:] @ v
         Qacc[:, k:] -= 2.0 * np.outer(q, v)
     U0 = np.triu(A)
@@ -255,44 +259,58 @@ def kurtosis_objective(Y, reduce: str = "mean"):
     return float(c * loss), dY
 
 
-def quant_objective(Y, bits: int = 4, reduce: str = "mean"):
+def quant_positions(Y, bits: int = 4) -> np.ndarray:
+    """Position of every entry on its row's quantiser grid, u_i = (y_i - lo) / delta with lo / hi the row minimum /
+    maximum and delta = (hi - lo) / (2^bits - 1): level k sits at u = k.  Rows without a range give zeros."""
+    Y = _f64(Y)
+    levels = (1 << int(bits)) - 1
+    u = np.zeros_like(Y)
+    for t in range(Y.shape[0]):
+        lo, hi = np.min(Y[t]), np.max(Y[t])
+        delta = (hi - lo) / levels
+        if delta > 0:
+            u[t] = (Y[t] - lo) / delta
+    return u
+
+
+def quant_objective(Y, bits: int = 4, reduce: str = "mean", codes=None):
     """Per-token asymmetric uniform quantisation error as the objective (Sec. 5 names the quantiser and the objective;
     formula: reading above).
 
-    Per row: lo, hi = min, max;  delta = (hi - lo) / L with L = 2^bits - 1;  q_i = round((y_i - lo) * (1 / delta));
-    yhat_i = lo + delta q_i = lo (1 - q_i / L) + hi q_i / L;  e_i = y_i - yhat_i;  loss_t = (1/n) sum_i e_i^2.
+    Per row: lo, hi = min, max;  delta = (hi - lo) / L with L = 2^bits - 1;  q_i = round((y_i - lo) / delta), ties to
+    even;  yhat_i = lo + delta q_i = lo (1 - q_i / L) + hi q_i / L;  e_i = y_i - yhat_i;  loss_t = (1/n) sum_i e_i^2.
     With the codes held fixed,
         d loss_t / d y_j = (2/n) * ( e_j - [j = jmin] sum_i e_i (1 - q_i / L) - [j = jmax] sum_i e_i q_i / L ),
-    jmin / jmax the first positions of the minimum / maximum.  Returns (loss, dY, codes)."""
-    Y32 = np.asarray(Y, dtype=np.float32)
-    if not np.array_equal(Y32.astype(np.float64), np.asarray(Y, dtype=np.float64)):
-        raise ValueError("the quantiser decides its codes in float32: pass float32-representable values")
-    T, n = Y32.shape
+    jmin / jmax the first positions of the minimum / maximum.  ``codes`` (T x n integers in [0, L]) replaces the
+    nearest-level decision by a given one (rows without a range ignore it).  Returns (loss, dY, codes)."""
+    Y = _f64(Y)
+    T, n = Y.shape
     levels = (1 << int(bits)) - 1
     c = _reduce_scale(reduce, T)
+    u = quant_positions(Y, bits)
     loss = 0.0
     dY = np.zeros((T, n), dtype=np.float64)
-    codes = np.zeros((T, n), dtype=np.int64)
+    out_codes = np.zeros((T, n), dtype=np.int64)
     for t in range(T):
-        y = Y32[t]
-        lo, hi = np.float32(np.min(y)), np.float32(np.max(y))
-        delta = np.float32(np.float32(hi - lo) / np.float32(levels))
+        y = Y[t]
+        lo, hi = np.min(y), np.max(y)
+        delta = (hi - lo) / levels
         if not delta > 0:
             continue
-        # the decision, step by step in float32
-        scale = np.float32(np.float32(1.0) / delta)
-        q32 = np.rint(((y - lo).astype(np.float32) * scale).astype(np.float32))
-        q32 = np.minimum(np.maximum(q32, np.float32(0)), np.float32(levels))
-        q = q32.astype(np.float64)
-        codes[t] = q32.astype(np.int64)
-        y64 = y.astype(np.float64)
-        e = y64 - (float(lo) + float(delta) * q)
+        if codes is None:
+            q = np.rint(u[t])          # ties to even
+        else:
+            q = np.asarray(codes[t], dtype=np.float64)
+            if np.any(q < 0) or np.any(q > levels) or np.any(q != np.rint(q)):
+                raise ValueError("codes must be integers in [0, 2^bits - 1]")
+        out_codes[t] = q.astype(np.int64)
+        e = y - (lo + delta * q)
         loss += np.sum(e * e) / n
         g = e.copy()
         g[int(np.argmin(y))] -= np.sum(e * (1.0 - q / levels))
         g[int(np.argmax(y))] -= np.sum(e * (q / levels))
         dY[t] = c * (2.0 / n) * g
-    return float(c * loss), dY, codes
+    return float(c * loss), dY, out_codes
 
 
 def objective_loss_grad(Y, objective: str = "whip", reduce: str = "mean", bits: int = 4):

@@ -659,16 +659,15 @@ def test_quant_objective_pins(bits):
     L = (1 << bits) - 1
     loss, dY, codes = orc.quant_objective(Y, bits, "sum")
     assert codes.min() == 0 and codes.max() == L
-    # every code is the nearest level (brute force over all levels; float32 rounding of the grid moves a level by
-    # parts in 1e7 of the range, far less than the distance of these values to a decision boundary)
+    # every code is the nearest level (brute force over all levels)
     ref = sum(_nearest_level_error(Y[t], bits).sum() / 40 for t in range(6))
-    assert loss == pytest.approx(ref, rel=1e-5)
+    assert loss == pytest.approx(ref, rel=1e-12)
     # error bound of a uniform quantiser: |e| <= delta / 2
     for t in range(6):
         y = Y[t].astype(np.float64)
         delta = (y.max() - y.min()) / L
-        e = y - (y.min() + np.float64(np.float32(delta)) * codes[t])
-        assert np.max(np.abs(e)) <= delta / 2 * (1 + 1e-5)
+        e = y - (y.min() + delta * codes[t])
+        assert np.max(np.abs(e)) <= delta / 2 * (1 + 1e-12)
         assert codes[t][np.argmin(y)] == 0 and codes[t][np.argmax(y)] == L
     # mean over tokens is the sum divided by T
     assert orc.quant_objective(Y, bits, "mean")[0] == pytest.approx(loss / 6, rel=1e-14)
@@ -711,8 +710,18 @@ def test_quant_objective_closed_forms():
     # a constant row has no range: zero loss, zero gradient
     loss, dY, _ = orc.quant_objective(np.full((2, 5), 1.5, dtype=np.float32), 4, "sum")
     assert loss == 0.0 and not dY.any()
+    # grid positions: level k sits at u = k; a constant row has none
+    u = orc.quant_positions(np.array([[0.0, 3.0, 1.25], [2.0, 2.0, 2.0]]), 2)
+    np.testing.assert_allclose(u, [[0.0, 3.0, 1.25], [0.0, 0.0, 0.0]], rtol=0, atol=1e-15)
+    # given codes replace the decision: the other neighbour of a tie has the same error, any other code a larger one
+    row = np.array([[0.0, 3.0, 1.5]])
+    l_even, _, c_even = orc.quant_objective(row, 2, "sum")
+    l_odd, dY_odd, c_odd = orc.quant_objective(row, 2, "sum", codes=[[0, 3, 1]])
+    assert c_even.tolist() == [[0, 3, 2]] and c_odd.tolist() == [[0, 3, 1]] and l_odd == pytest.approx(l_even)
+    assert dY_odd[0, 2] == pytest.approx((2.0 / 3) * 0.5)
+    assert orc.quant_objective(row, 2, "sum", codes=[[0, 3, 0]])[0] > l_even
     with pytest.raises(ValueError):
-        orc.quant_objective(np.array([[0.1, 0.2]]), 4)     # 0.1 is not a float32 value
+        orc.quant_objective(row, 2, "sum", codes=[[0, 4, 1]])
 
 
 def test_objective_dispatch_and_step():
