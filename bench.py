@@ -4,10 +4,16 @@
 
 A "step" is one dq_calib_step: QR of the latent Z, Y = X R, fused Whip loss/gradient, G = X^T dY,
 the derivative through the QR and the SGD update, on one synthetic activation block that is already
-resident in HBM.  Prints ONE JSON line (metric: steps per second) with a `roofline` object for the
-kernel class that takes most of the step, a `stage_roofline` object (every stage entry point timed on its
-own after the timed region: share of the fp32 / bf16 matrix-core peak and, for the Whip pass, of the HBM peak)
-and a `cpu_baseline` object (the fp64 oracle timed on the host on a bounded sample).
+resident in HBM.  Prints ONE JSON line (metric: steps per second).
+
+Without --config the line covers both sizes the metric is quoted on: the headline fields are those of the 7b shape
+(n = 4096, T = 8192) and `also` holds the same measurement of the 70b shape (n = 8192, T = 16384), each with
+ * `roofline`: the kernel class that takes most of the step, algorithmic work over the summed duration of its
+   launches (HIP events around every launch inside a repeat of the timed steps, minus the calibrated cost of an
+   event bracket),
+ * `stage_roofline`: every stage entry point timed on its own after the timed region (share of the fp32 / bf16
+   matrix-core peak and, for the Whip pass, of the HBM peak).
+`cpu_baseline` is the fp64 oracle timed on the host on a bounded sample.
 """
 
 from __future__ import annotations
@@ -15,6 +21,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -22,23 +29,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM-side traffic per launch (bytes, fetch + write) of each kernel class on the 7b workload, measured with
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by the readings of a plain copy kernel; the summary and the
-# commands are in profiles/calib_step_7b_hbm_traffic.txt.  Counters cannot be read from inside this script, so the
-# figures are carried here; other workloads report null.
-MEASURED_TRAFFIC_7B = {
-    "gemm_f32": (8233.7 + 4144.7) * 2 ** 20 / 317.0,
-    # the rotation product with the fused loss epilogue and the gradient product
-    "gemm_bf16": (1781.8 + 128.1) * 2 ** 20 / 2.0,
-    # whip_kernel is not part of the 7b step any more (the loss is fused into the rotation product there); the
-    # figure is the one measured for its launch on the same shape
-    "whip": (128.0 + 64.1) * 2 ** 20,
-    # panel route: all of its kernels together, per bracketed group of launches (two groups per tall panel)
-    "qr_panel": (374.7 + 185.0) * 2 ** 20 / 127.0,
-}
+# MI355X published peaks.  The vector-ALU figure is 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz without packed
+# fp32 instructions, which this build keeps the compiler from forming.
+PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_valu_tflops": 78.6}
 
-# MI355X published peaks
-PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_valu_tflops": 157.3}
+# kernel whose launches make up each bracketed class (as named in the rocprofv3 summaries under profiles/)
+CLASS_KERNEL = {"gemm_f32": "gemm_f32_kernel", "gemm_bf16": "gemm_bf16_nt_deep_kernel", "whip": "whip_kernel"}
 
 
 def flops_per_step(n: int, T: int, b: int = 1) -> float:
@@ -47,10 +43,25 @@ def flops_per_step(n: int, T: int, b: int = 1) -> float:
     return b * (4.0 * T * n * n + (20.0 / 3.0) * n ** 3)
 
 
+def measured_traffic(cfg_name: str, kernel: str | None):
+    """HBM bytes per launch (fetch + write) of `kernel` from the committed counter summary of this workload
+    (profiles/calib_step_<workload>_hbm_traffic.txt, written from two rocprofv3 --pmc passes); None if there is none.
+    Counters cannot be read from inside this script."""
+    if kernel is None:
+        return None, None
+    path = os.path.join(ROOT, "profiles", f"calib_step_{cfg_name}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        m = re.match(r"\s*(\S+)\s+([\d.]+)\s+([\d.]+)\s+([\d.]+)\s+([\d.]+)\s+([\d.]+)\s*$", line)
+        if m and m.group(1) == kernel:
+            return (float(m.group(5)) + float(m.group(6))) * 1024.0, os.path.relpath(path, ROOT)
+    return None, None
+
+
 def cpu_baseline(cfg_name: str, n: int, T: int):
     """Time the oracle as it stands on a bounded sample (a smaller problem with the same value recipe and
-    T/n ratio) and scale to the benchmark's step with the flop model."""
-    import numpy as np
+    T/n ratio, about 10-30 s of host work) and scale to the benchmark's step with the flop model."""
     from oracle import dartqr_oracle as orc
     from paper_2511_04063_amd import synth
 
@@ -75,39 +86,14 @@ def cpu_baseline(cfg_name: str, n: int, T: int):
     }
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="7b")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-stage-roofline", action="store_true",
-                    help="skip the separate timing of the stage entry points (used when the run is profiled, so that "
-                         "the trace holds calibration steps only)")
-    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
-                    help="update rule of the latent: Alg. 1's SGD (the headline metric) or Adam (Sec. 4.3, Table 4)")
-    ap.add_argument("--objective", choices=["whip", "variance", "kurtosis", "quant"], default="whip",
-                    help="what S4 evaluates: Eq. 4 (the headline metric) or one of the objectives the paper compares "
-                         "it with (Sec. 5, objective ablation)")
-    ap.add_argument("--host-batches", type=int, default=0,
-                    help="also time the mini-batch loop with this many batches in pinned HOST memory "
-                         "(dq_calib_run_host_batches: copies overlap the steps); reported beside the headline value, "
-                         "which always has its inputs resident in HBM")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
+def run_config(cfg_name: str, args):
+    """Everything measured on one workload; returns the fields of the JSON line that belong to it."""
     import torch
 
     from paper_2511_04063_amd import binding as B
     from paper_2511_04063_amd import synth
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
+    cfg = synth.CONFIGS[cfg_name]
     inp = synth.make_inputs(cfg)
     bf16 = cfg.x_dtype == "bf16"
     xdt = B.DQ_BF16 if bf16 else B.DQ_F32
@@ -164,7 +150,7 @@ def main():
     dt = time.perf_counter() - t0
     last_loss = float(loss[0].item())
 
-    # the same K steps again with HIP events around every launch of the dominant class (roofline figures)
+    # the same K steps again with HIP events around every launch of the dominant class (roofline figures) ...
     Zd.copy_(Z0)
     ctx.dq_profile_enable(1 << dominant)
     torch.cuda.synchronize()
@@ -174,6 +160,16 @@ def main():
     torch.cuda.synchronize()
     dt_bracketed = time.perf_counter() - t1
     dom = ctx.dq_profile_read(dominant)
+    # ... and what an event bracket costs by itself: the same brackets around a kernel that does next to nothing (one
+    # update of a 4 x 4 matrix).  A bracket spans the dispatch of its kernel as well as the kernel, so this figure is
+    # taken off every bracket of the class to obtain kernel time, which is what a kernel trace reports.
+    tiny_z = torch.zeros((4, 4), device="cuda")
+    tiny_d = torch.zeros((4, 4), device="cuda")
+    ctx.dq_profile_enable(1 << B.DQ_K_SMALL)
+    for _ in range(256):
+        ctx.dq_sgd_update(tiny_z, tiny_d, 0.0)
+    cal = ctx.dq_profile_read(B.DQ_K_SMALL)
+    bracket_ms = cal["ms"] / max(1, cal["launches"])
     ctx.dq_profile_enable(0)
     flags = ctx.dq_device_flags()
 
@@ -241,53 +237,116 @@ def main():
         del host, staging
 
     ms_per_step = dt * 1e3 / args.steps
-    F = flops_per_step(cfg.n, cfg.T, cfg.b)
+    n, T, b = cfg.n, cfg.T, cfg.b
+    F = flops_per_step(n, T, b)
     launches = max(1, dom["launches"])
-    avg_ms = dom["ms"] / launches
-    if dominant in (B.DQ_K_GEMM_F32, B.DQ_K_GEMM_BF16):
-        peak = PEAK["fp32_mfma_tflops"] if dominant == B.DQ_K_GEMM_F32 else PEAK["bf16_mfma_tflops"]
-        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
-        roof = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s"}
+    raw_ms = dom["ms"] / launches
+    avg_ms = max(raw_ms - bracket_ms, 1e-6)
+    class_s = avg_ms * launches * 1e-3            # summed kernel time of the class over the K steps
+    # algorithmic work of the class per step (the model's, not what the launches issue: forming R forward issues
+    # 2 n^3 where the model counts 4/3 n^3, the rotation product issues its flops twice for the two planes of R)
+    if dominant == B.DQ_K_GEMM_F32:
+        work = b * ((20.0 / 3.0) * n ** 3 + (0.0 if bf16 else 4.0 * T * n * n))
+        roof = {"bound": "mfma", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["fp32_mfma_tflops"],
+                "unit": "TFLOP/s"}
+    elif dominant == B.DQ_K_GEMM_BF16:
+        work = b * 4.0 * T * n * n
+        roof = {"bound": "mfma", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["bf16_mfma_tflops"],
+                "unit": "TFLOP/s"}
     elif dominant == B.DQ_K_WHIP:
-        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9 if dom["ms"] > 0 else 0.0
-        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK["hbm_gbs"], "unit": "GB/s"}
+        work = dom["bytes"] / args.steps
+        roof = {"bound": "hbm", "achieved": work * args.steps / class_s / 1e9, "peak": PEAK["hbm_gbs"], "unit": "GB/s"}
     else:
-        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
-        roof = {"bound": "alu", "achieved": achieved, "peak": PEAK["fp32_valu_tflops"], "unit": "TFLOP/s"}
+        work = dom["flops"] / args.steps
+        roof = {"bound": "alu", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["fp32_valu_tflops"],
+                "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_7B.get(names[dominant]) if cfg.name == "7b" else None
-    roof["traffic_unit"] = "bytes per launch (fetch + write), from profiles/calib_step_7b_hbm_traffic.txt"
-    roof["kernel"] = names[dominant]
+    traffic, traffic_src = measured_traffic(cfg.name, CLASS_KERNEL.get(names[dominant]))
+    roof["traffic"] = traffic
+    roof["traffic_unit"] = ("bytes per launch (fetch + write), from " + traffic_src) if traffic_src else None
+    roof["kernel"] = CLASS_KERNEL.get(names[dominant], names[dominant])
+    roof["algorithmic_work_per_step"] = work
     roof["launches_per_step"] = dom["launches"] / args.steps
     roof["avg_launch_ms"] = avg_ms
-    roof["class_ms_per_step"] = dom["ms"] / args.steps
+    roof["avg_bracket_ms"] = raw_ms
+    roof["bracket_overhead_ms"] = bracket_ms
+    roof["class_ms_per_step"] = class_s * 1e3 / args.steps
     roof["ms_per_step_with_events"] = dt_bracketed * 1e3 / args.steps
 
     out = {
-        "metric": "QR-Orth calibration steps/sec",
         "value": args.steps / dt,
         "unit": "steps/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
-        "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, "
                                f"{'Adam' if args.optimizer == 'adam' else 'SGD'} lr={cfg.lr}"
                                + ("" if args.objective == "whip" else f", objective {args.objective}"),
                    "n": cfg.n, "T": cfg.T, "b": cfg.b},
+        "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
         "model_tflops": F / (ms_per_step * 1e-3) / 1e12,
         "flops_per_step": F,
-        "loss_first": first_loss, "loss_last": last_loss, "device_flags": flags,
+        "loss_first": first_loss, "loss_last": last_loss,
+        "device_flags": flags & ~B.DQ_FLAG_ILLCOND_PANEL,
+        "panel_fallback_seen": bool(flags & B.DQ_FLAG_ILLCOND_PANEL),
         "roofline": roof,
         "stage_roofline": stages,
         "host_batch_loop": host_loop,
         "stage_ms_one_step": {k: round(v["ms"], 4) for k, v in breakdown.items()},
         "stage_launches_one_step": {k: v["launches"] for k, v in breakdown.items()},
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg.name, cfg.n, cfg.T)
     ctx.close()
+    del Xd, Zd, Z0
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default=None,
+                    help="one workload; default: the 7b shape as the headline and the 70b shape beside it")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-roofline", action="store_true",
+                    help="skip the separate timing of the stage entry points (used when the run is profiled, so that "
+                         "the trace holds calibration steps only)")
+    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
+                    help="update rule of the latent: Alg. 1's SGD (the headline metric) or Adam (Sec. 4.3, Table 4)")
+    ap.add_argument("--objective", choices=["whip", "variance", "kurtosis", "quant"], default="whip",
+                    help="what S4 evaluates: Eq. 4 (the headline metric) or one of the objectives the paper compares "
+                         "it with (Sec. 5, objective ablation)")
+    ap.add_argument("--host-batches", type=int, default=0,
+                    help="also time the mini-batch loop with this many batches in pinned HOST memory "
+                         "(dq_calib_run_host_batches: copies overlap the steps); reported beside the headline value, "
+                         "which always has its inputs resident in HBM")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    head_name = args.config or "7b"
+    head = run_config(head_name, args)
+    out = {
+        "metric": "QR-Orth calibration steps/sec",
+        "value": head.pop("value"), "unit": head.pop("unit"),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head.pop("dtype"), "data": "synthetic",
+    }
+    out.update(head)
+    if args.config is None:
+        # the other size the metric is quoted on, measured the same way (same step count, same warm-up)
+        out["also"] = {"70b": run_config("70b", args)}
+    if not args.no_cpu_baseline:
+        from paper_2511_04063_amd import synth
+        cfg = synth.CONFIGS[head_name]
+        out["cpu_baseline"] = cpu_baseline(cfg.name, cfg.n, cfg.T)
     print(json.dumps(out))
 
 

@@ -393,12 +393,8 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
     return DQ_OK;
 }
 
-// normalise = false leaves the factors as the factorisation produced them (column signs of R and row signs of the
-// triangular factor, which then sits in the upper triangle of the workspace matrix L.A, not fixed): loss and dL/dZ do
-// not depend on the sign choice (Y's columns, dY's columns and G's columns flip together, and R P U^-T is invariant),
-// so a step that does not have to report R skips the pass.
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
-                      long ldu, bool normalise = true) {
+                      long ldu) {
     hipStream_t sA = c->stream, sB = c->single_stream ? c->stream : c->stream2,
                 sC = c->single_stream ? c->stream : c->stream3;
     float* A = at<float>(c, L.A);
@@ -513,7 +509,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
     DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));
     DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev.back(), 0));
-    if (normalise) {
+    {
         LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 12.0 * n * (double)n);
         DQ_HIP(launch_sign_normalise(A, ld, n, R, ldr, U, ldu, flags, sA));
     }
@@ -978,14 +974,14 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
-        // R is reported only on request: without it the sign normalisation is skipped and the triangular factor is
-        // read in place from the factored matrix.  That holds for Eq. 4 only: the other objectives see the signs of
-        // Y's columns (row means, row extremes), so they always get the normalised rotation.
-        const bool report = R != nullptr || c->objective != DQ_OBJ_WHIP;
-        float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
+        // The rotation is sign-normalised whether or not it is reported.  Loss and dL/dZ do not depend on the column
+        // signs in exact arithmetic, but the bf16 matrix cores do not round sign-symmetrically, and dY is discontinuous
+        // at y = 0: a step on R S would differ from the staged calls (which see the normalised R) by the entries of Y
+        // at rounding level.  One pass over three n x n matrices keeps the two routes identical.
+        float* Ui = at<float>(c, L.U);
         float* Gi = at<float>(c, L.G);
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
-        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
                                     at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld, false));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, nullptr, 0, Zi, ldz, lr));
@@ -1261,12 +1257,11 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         float* Zi = Z + (long)i * n * ldz;
         float* Ri = R ? R + (long)i * n * ldr : at<float>(c, L.R);
         const long ldri = R ? ldr : L.ld;
-        const bool report = R != nullptr || c->objective != DQ_OBJ_WHIP;   // as in dq_calib_step
-        float* Ui = report ? at<float>(c, L.U) : at<float>(c, L.A);
+        float* Ui = at<float>(c, L.U);   // sign-normalised always, as in dq_calib_step
         float* Gi = at<float>(c, L.G);
         float* dZi = at<float>(c, L.B);   // B = R^T G is consumed before the last product writes dZ there
         const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
-        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, report ? Ui : nullptr, L.ld, report));
+        DQ_TRY(qr_orth_one(c, L, n, Zi, ldz, Ri, ldri, Ui, L.ld));
         DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldri, red, loss_dev + i, Gi, L.ld,
                                     at<float>(c, L.Y), L.ld, at<char>(c, L.dY), L.ld, false));
         DQ_TRY(qr_backward_one(c, L, n, Ri, ldri, Ui, L.ld, Gi, L.ld, dZi, L.ld, nullptr, 0, 0.f));

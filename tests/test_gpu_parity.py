@@ -370,7 +370,19 @@ def test_objective_full_size_rows(name):
     assert rel(got, ref_dY) < 4e-3
     # bf16 rounding of the fp32 gradient, entry by entry
     scale = np.abs(ref_dY).max(axis=1, keepdims=True)
-    assert (np.abs(got - ref_dY) <= np.abs(ref_dY) * 2.0 ** -8 + scale * 1e-5).all()
+    tol = np.abs(ref_dY) * 2.0 ** -8 + scale * 1e-5
+    if name == "quant":
+        # The two entries per row that carry the dependence on lo / hi are sums over the row of e_i (1 - q_i / L) and
+        # e_i q_i / L, which cancel heavily.  The kernel's delta is an fp32 number (two roundings: up to 2^-23 relative),
+        # so every e_i = y_i - (lo + delta q_i) is off by up to q_i delta 2^-23 with one sign, and the sums by up to
+        # n L delta 2^-23: in dY = c (2/n) (...) that is c 2 L delta 2^-23, whatever is left of the sum itself.
+        L = 15.0
+        delta = (Y.max(axis=1).astype(np.float64) - Y.min(axis=1).astype(np.float64)) / L
+        extra = (1.0 / T) * 2.0 * L * delta * 2.0 ** -23
+        r = np.arange(T)
+        tol[r, Y.argmin(axis=1)] += extra
+        tol[r, Y.argmax(axis=1)] += extra
+    assert (np.abs(got - ref_dY) <= tol).all()
 
 
 def test_objective_on_head_sized_batch_takes_the_general_route(ctx):
@@ -780,11 +792,13 @@ def gpu_stages(ctx, Xd, xdt, Zd):
 # End-to-end dZ in fp32 is limited by the conditioning of the chain, not by the kernels.  (i) The forward error
 # of an fp32 Householder QR (about 1e-6 in R at n = 256, the same as LAPACK's sgeqrf/sorgqr on this input) is
 # amplified through Y = X R (outlier channels x50), dY = -sgn(y) e^{-|y|} / T and G = X^T dY by a factor of about
-# 160, so a LAPACK-grade fp32 pipeline lands at 1e-4 .. 2e-4 itself.  (ii) dY is discontinuous at y = 0: an
-# element with |y| below the error of Y takes the other sign and moves G by 2/T times its token row; with 5e5
-# elements a handful do so in some steps, which shows up as a few 1e-3 in dZ.  The 1e-4 bar is therefore asserted
-# stage by stage with oracle-exact stage inputs, and end to end only with the loose bound below.
-E2E_DZ_TOL_F32 = 2e-2
+# 160, so a LAPACK-grade fp32 pipeline lands at 1e-4 .. 2e-4 itself (this library: 1e-4 .. 4.4e-4 over the ten
+# steps of the tiny workload).  (ii) dY is discontinuous at y = 0: an element with |y| below the error of Y takes the
+# other sign and moves G by 2/T times its token row.  The 1e-4 bar is therefore asserted stage by stage with
+# oracle-exact stage inputs; end to end the bound is 1e-3 (twice the largest value measured), with the number of
+# entries of Y whose sign differs from the oracle's counted and bounded beside it.
+E2E_DZ_TOL_F32 = 1e-3
+E2E_MAX_SIGN_FLIPS = 4
 
 
 def test_calib_step_tiny_trajectory(ctx):
@@ -819,7 +833,11 @@ def test_calib_step_tiny_trajectory(ctx):
         assert rel(G_st, Go) < E2E_DZ_TOL_F32
         assert rel(dZ_st, orc.qr_backward(R_st, U_st, G_st)) < 1e-4
         # end to end
-        assert rel(dZ_st, out["dZ"]) < E2E_DZ_TOL_F32
+        flips = int(np.count_nonzero(np.sign(Y_st) != np.sign(Yo)))
+        e2e = rel(dZ_st, out["dZ"])
+        print(f"tiny step {k}: end-to-end dZ rel {e2e:.3e}, G rel {rel(G_st, Go):.3e}, sign flips of Y {flips}", flush=True)
+        assert flips <= E2E_MAX_SIGN_FLIPS
+        assert e2e < E2E_DZ_TOL_F32
         # the fused update applied that gradient: Z_new = Z - lr * dZ up to fp32 rounding of Z
         Znew = Zd.cpu().numpy().astype(np.float64)
         assert np.abs(Znew - (Zin - cfg.lr * dZ_st)).max() <= 2.0 ** -22 * np.abs(Zin).max()
@@ -881,12 +899,18 @@ def test_calib_step_bf16_small(ctx):
     assert np.abs(dZ_gpu[:, -1]).max() < 1e-3 * np.abs(dZ_gpu).max()
 
 
-@pytest.mark.parametrize("name", ["7b", "70b"])
+def max_abs_fp64(t):
+    return float(t.abs().max().item())
+
+
+@pytest.mark.parametrize("name", ["7b", "13b", "70b"])
 def test_full_size_step_sampled(name):
-    """The workloads bench.py times (n = 4096 / 8192 with their token counts, bf16 X), through the same entry point
-    and launch configuration, checked where the oracle can afford it: sampled entries of every stage against fp64
-    dot products of that stage's own inputs, the loss against the oracle's Whip on the GPU's Y, and properties of
-    the factorisation and of the gradient that hold at any size."""
+    """The workloads bench.py times (n = 4096 / 5120 / 8192 with their token counts, bf16 X), through the same entry
+    points and launch configuration, checked where the oracle can afford it: the factorisation over ALL entries
+    (orthogonality and reconstruction, formed in fp64 with torch on the device as a checker), sampled entries of every
+    other stage against fp64 dot products of that stage's own inputs, the loss against the oracle's Whip on the GPU's
+    Y, properties of the gradient that hold at any size, and the fused route the benchmark times (Whip in the
+    epilogue of the rotation, un-normalised factors, update folded into the last product) against the staged one."""
     inp = synth.make_inputs(name)
     cfg = inp["cfg"]
     n, T = cfg.n, cfg.T
@@ -905,24 +929,33 @@ def test_full_size_step_sampled(name):
         ctx.dq_qr_orth(Zd, Rd, Ud)
         ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd, Yd, dYd)
         ctx.dq_qr_backward(Rd, Ud, Gd, dZd)
-        loss2 = torch.zeros(1, device="cuda")
-        Zstep = Zd.clone()
-        ctx.dq_calib_step(Xd, B.DQ_BF16, Zstep, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss2)
-        assert ctx.dq_device_flags() == 0
+        # the informational bit (a panel took the Householder fallback) does not invalidate anything
+        assert ctx.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+        print(f"{name}: stages done", flush=True)
+
+        # S1 + S2 over all n^2 entries, in fp64 on the device (torch as the checker, not as the product)
+        R64, U64, Z64d = Rd.double(), Ud.double(), Zd.double()
+        gram = R64.T @ R64
+        gram.diagonal().sub_(1.0)
+        orth = max_abs_fp64(gram)
+        del gram
+        rec = R64 @ U64
+        rec.sub_(Z64d)
+        recon = max_abs_fp64(rec)
+        recon_f = float(rec.norm().item() / Z64d.norm().item())
+        del rec, R64, U64, Z64d
+        print(f"{name}: max|R^T R - I| = {orth:.3e}, max|R U - Z| = {recon:.3e}, |R U - Z|_F / |Z|_F = {recon_f:.3e}",
+              flush=True)
+        assert orth <= 1e-5
+        # backward error of the factorisation: a few units of n * 2^-24 norm-wise would be the textbook worst case;
+        # entry by entry, against |Z|_2 ~ 2 sqrt(n) for a Gaussian latent
+        assert recon_f <= 1e-5
+        assert recon <= 4e-6 * np.sqrt(n)
         R = Rd.cpu().numpy().astype(np.float64)
         U = Ud.cpu().numpy().astype(np.float64)
         G = Gd.cpu().numpy().astype(np.float64)
         dZ = dZd.cpu().numpy().astype(np.float64)
         Z64 = Z0.astype(np.float64)
-
-        # S1 + S2: orthogonality and reconstruction on sampled entries, structure of U
-        ii = g.integers(0, n, 400); jj = g.integers(0, n, 400)
-        gram = np.einsum("ki,ki->i", R[:, ii], R[:, jj]) - (ii == jj)
-        assert np.abs(gram).max() <= 1e-5
-        diag = np.einsum("ki,ki->i", R[:, ii], R[:, ii]) - 1.0
-        assert np.abs(diag).max() <= 1e-5
-        rec = np.einsum("ik,ki->i", R[ii, :], U[:, jj])
-        assert np.abs(rec - Z64[ii, jj]).max() <= 2e-6 * np.sqrt(n)     # |Z|_2 ~ 2 sqrt(n) for a Gaussian latent
         assert np.all(np.diag(U) > 0.0)
         assert np.count_nonzero(np.tril(U, -1)) == 0
 
@@ -942,7 +975,6 @@ def test_full_size_step_sampled(name):
         for r0 in range(0, T, 1024):
             acc += orc.whip_loss(Yd[r0:r0 + 1024].cpu().numpy(), "sum")
         assert abs(loss.item() - acc / T) <= 1e-5 * acc / T
-        assert loss2.item() == pytest.approx(loss.item(), rel=1e-6)
         dy_ref = orc.whip_grad(Y_rows.astype(np.float64), "sum") / T
         dy_gpu = dYd[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
         assert rel(dy_gpu, dy_ref) < 4e-3
@@ -973,8 +1005,113 @@ def test_full_size_step_sampled(name):
             p_ref = np.zeros(n)
             p_ref[:i] = (R[:, i] @ G)[:i] - (R.T @ G[:, i])[:i]
             assert np.linalg.norm(p_rec - p_ref) <= 1e-4 * max(np.linalg.norm(p_ref), np.linalg.norm(R[:, i] @ G))
-        # S7: the fused update is Z - lr dZ
-        assert rel(Zstep.cpu().numpy(), Z64 - cfg.lr * dZ) < 1e-6
+        print(f"{name}: staged route checked", flush=True)
+
+        # The fused route, which is what bench.py times.  (i) dq_rotate_loss_grad without Y / dY applies Eq. 4 in the
+        # epilogue of the rotation product: same loss and the same G over all n^2 entries.
+        G2d = torch.empty((n, n), device="cuda")
+        loss_f = torch.zeros(1, device="cuda")
+        ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss_f, G2d)
+        assert loss_f.item() == pytest.approx(loss.item(), rel=1e-6)
+        g_fused = rel(G2d.cpu().numpy(), G)
+        print(f"{name}: rel(G fused, G staged) = {g_fused:.3e}", flush=True)
+        assert g_fused < 1e-5
+        # (ii) dq_calib_step folds the update into the last product.  With the configured learning rate the update is
+        # lost in the fp32 rounding of Z (lr |dZ| / |Z| is 1e-6 .. 1e-7), so the step is taken with a learning rate that
+        # moves Z by a quarter of its norm and the gradient it applied is recovered as (Z - Z_new) / lr, which adds
+        # 4 * 2^-24 |dZ| of rounding.  With R requested the step runs the staged arithmetic (same rotation, same G):
+        lr_big = 0.25 * float(np.linalg.norm(Z64) / np.linalg.norm(dZ))
+        Zstep = Zd.clone()
+        loss2 = torch.zeros(1, device="cuda")
+        R2d = torch.empty((n, n), device="cuda")
+        ctx.dq_calib_step(Xd, B.DQ_BF16, Zstep, lr_big, B.DQ_REDUCE_TOKEN_MEAN, loss2, R2d)
+        assert loss2.item() == pytest.approx(loss.item(), rel=1e-6)
+        assert torch.equal(R2d, Rd)
+        dz_applied = (Z64 - Zstep.cpu().numpy().astype(np.float64)) / float(np.float32(lr_big))
+        dz_fused = rel(dz_applied, dZ)
+        print(f"{name}: rel(dZ applied by the fused step with R reported, dZ staged) = {dz_fused:.3e}", flush=True)
+        assert dz_fused < 2e-6
+        # Without R (what bench.py times) the step runs the very same launches: identical bits.  (The rotation is
+        # sign-normalised either way: a step on un-normalised factors would rotate with R S, the bf16 matrix cores do
+        # not round sign-symmetrically, and the entries of Y at rounding level would take either sign, which was
+        # measured to move dZ by 2e-5 at n = 4096 and 9e-4 at n = 5120.)
+        Zstep2 = Zd.clone()
+        ctx.dq_calib_step(Xd, B.DQ_BF16, Zstep2, lr_big, B.DQ_REDUCE_TOKEN_MEAN, loss2)
+        assert loss2.item() == loss.item() or loss2.item() == pytest.approx(loss.item(), rel=1e-6)
+        assert torch.equal(Zstep2, Zstep)
+        # the configured learning rate: the update is there and of the right size
+        Zs = Zd.clone()
+        ctx.dq_calib_step(Xd, B.DQ_BF16, Zs, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, loss2)
+        assert rel(Zs.cpu().numpy(), Z64 - cfg.lr * dZ) < 2e-7
+        assert ctx.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+    finally:
+        torch.cuda.synchronize()
+        ctx.close()
+
+
+def test_full_size_7b_against_one_oracle_factorisation():
+    """n = 4096: R, U, Y and the loss of the 7B-shaped workload against the oracle's own factorisation of the same
+    latent (the unblocked fp64 recurrence, a minute or two of CPU time), under the rule of the small-size tests:
+    R to max(1e-4, 2e-7 cond(Z)), U and the loss to 1e-4."""
+    inp = synth.make_inputs("7b")
+    cfg = inp["cfg"]
+    n, T = cfg.n, cfg.T
+    X, Z0 = inp["X"][0], inp["Z0"][0]
+    ctx = B.Context()
+    ctx.ensure_workspace(1, n, T, B.DQ_BF16)
+    try:
+        Xd = dev(X, torch.bfloat16)
+        Zd = dev(Z0.copy())
+        Rd, Ud, Gd = (torch.empty((n, n), device="cuda") for _ in range(3))
+        loss = torch.zeros(1, device="cuda")
+        ctx.dq_qr_orth(Zd, Rd, Ud)
+        ctx.dq_rotate_loss_grad(Xd, B.DQ_BF16, Rd, B.DQ_REDUCE_TOKEN_MEAN, loss, Gd)
+        torch.cuda.synchronize()
+        R, U = Rd.cpu().numpy(), Ud.cpu().numpy()
+    finally:
+        torch.cuda.synchronize()
+        ctx.close()
+    print("7b: oracle factorisation of the 4096 x 4096 latent ...", flush=True)
+    Ro, Uo = orc.qr_orth(Z0)
+    print("7b: ... done", flush=True)
+    sv = np.linalg.svd(Z0.astype(np.float64), compute_uv=False)
+    cond = sv[0] / sv[-1]
+    e_r, e_u = rel(R, Ro), rel(U, Uo)
+    lo = orc.whip_loss(orc.rotate(X, Ro))
+    print(f"7b: cond(Z) = {cond:.3e}, rel R = {e_r:.3e}, rel U = {e_u:.3e}, loss {loss.item():.6f} vs {lo:.6f}", flush=True)
+    assert e_r < max(1e-4, 2e-7 * cond)
+    assert e_u < 1e-4
+    assert abs(loss.item() - lo) <= 1e-4 * lo
+
+
+def test_full_size_7b_trajectory():
+    """Twenty consecutive steps on the 7B-shaped workload (the configurations run a hundred): the loss falls, the
+    latent stays on the sphere it started on up to second order (<Z, dZ> = 0, so |Z|^2 grows by lr^2 |dZ|^2 only), and
+    the rotation of the final latent is orthogonal to the bar over all entries."""
+    inp = synth.make_inputs("7b")
+    cfg = inp["cfg"]
+    n, T = cfg.n, cfg.T
+    ctx = B.Context()
+    ctx.ensure_workspace(1, n, T, B.DQ_BF16)
+    try:
+        Xd = dev(inp["X"][0], torch.bfloat16)
+        Zd = dev(inp["Z0"][0].copy())
+        z0 = float(Zd.double().norm().item())
+        losses = torch.zeros(20, device="cuda")
+        for k in range(20):
+            ctx.dq_calib_step(Xd, B.DQ_BF16, Zd, cfg.lr, B.DQ_REDUCE_TOKEN_MEAN, losses[k:k + 1])
+        flags = ctx.dq_device_flags()
+        assert flags & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+        ls = losses.cpu().numpy()
+        print(f"7b trajectory: loss {ls[0]:.4f} -> {ls[-1]:.4f}, flags {flags}", flush=True)
+        assert np.isfinite(ls).all() and (np.diff(ls) < 0).all()
+        assert abs(float(Zd.double().norm().item()) - z0) <= 1e-6 * z0
+        Rd = torch.empty((n, n), device="cuda")
+        ctx.dq_qr_orth(Zd, Rd, None)
+        R64 = Rd.double()
+        gram = R64.T @ R64
+        gram.diagonal().sub_(1.0)
+        assert max_abs_fp64(gram) <= 1e-5
     finally:
         torch.cuda.synchronize()
         ctx.close()
@@ -1001,7 +1138,7 @@ def test_batched_heads_like(ctx):
     R1 = torch.empty((128, 128), device="cuda")
     ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z1, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l1, R1)
     assert torch.equal(Z1, Zd[1]) and l1.item() == loss[1].item() and torch.equal(R1, Rd[1])
-    # without the request for R the step skips the sign normalisation: same loss and update up to rounding
+    # with or without the request for R: the same loss and update
     Z2 = dev(Z0[1].copy())
     l2 = torch.zeros(1, device="cuda")
     ctx.dq_calib_step(Xd[1], B.DQ_BF16, Z2, 1e-3, B.DQ_REDUCE_TOKEN_MEAN, l2)
