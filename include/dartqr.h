@@ -155,6 +155,20 @@ dq_status dq_whip_loss_grad(dq_ctx* ctx, int b, int T, int n,
                             const float* Y, long ldy, dq_reduce red,
                             float* loss_dev, void* dY, dq_dtype dydt, long lddy);
 
+/* dq_whip_loss_grad for callers that cannot allocate device memory and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Takes no context: hip_stream is the
+ * hipStream_t to enqueue on (may be null).  The status word and the per-workgroup partial sums live in a fixed
+ * array of device memory inside the library (256 + 8 * DQ_NOALLOC_MAX_BATCH bytes, one copy per GPU, held until the
+ * process ends); the call allocates and frees nothing, creates no events, and enqueues kernels only (no memset
+ * nodes).  Same arguments, results and argument errors as dq_whip_loss_grad; b > DQ_NOALLOC_MAX_BATCH returns
+ * DQ_ERR_UNSUPPORTED (the array holds one partial sum per problem at least).  The status word is not readable: a
+ * non-finite loss shows in loss_dev itself.  All calls on one GPU share the array, so calls that may overlap on one
+ * GPU (different streams, different threads) race: serialise them. */
+#define DQ_NOALLOC_MAX_BATCH 8192
+dq_status dq_whip_loss_grad_noalloc(void* hip_stream, int b, int T, int n,
+                                    const float* Y, long ldy, dq_reduce red,
+                                    float* loss_dev, void* dY, dq_dtype dydt, long lddy);
+
 /* The same stage for any dq_objective (Sec. 5, objective ablation): loss_dev[i] and dY = d loss / dY on an existing
  * Y (fp32, b blocks of T x n).  quant_bits (1..16) is read by DQ_OBJ_QUANT only.  DQ_OBJ_WHIP is dq_whip_loss_grad.
  * With the three row objectives dY may be null: then only loss_dev is written, e.g. the per-token quantisation error

@@ -37,6 +37,7 @@ SIGNATURES = {
     "dq_rotate_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _i, _vp, _vp, _l, _vp, _l, _vp, _l]),
     "dq_calib_step": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _f, _i, _vp, _vp, _l]),
     "dq_whip_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
+    "dq_whip_loss_grad_noalloc": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _vp, _i, _l]),
     "dq_qr_backward": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _vp, _l]),
     "dq_sgd_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _f]),
     "dq_hadamard_init": (_i, [_vp, _i, _i, _vp, _vp, _l]),
@@ -99,6 +100,17 @@ def workspace_bytes(b: int, n: int, T: int, x_dtype: int) -> int:
 
 def _ptr(t):
     return 0 if t is None else int(t.data_ptr())
+
+
+def dq_whip_loss_grad_noalloc(stream, Y, reduce, loss, dY, dy_dtype):
+    """The entry point that allocates nothing: no context, the raw stream handle (or None) first."""
+    b = Y.shape[0] if Y.dim() == 3 else 1
+    T, n = Y.shape[-2], Y.shape[-1]
+    handle = 0 if stream is None else int(stream.cuda_stream)
+    st = load_library().dq_whip_loss_grad_noalloc(_vp(handle), b, T, n, _ptr(Y), _ld(Y), reduce, _ptr(loss), _ptr(dY),
+                                                  dy_dtype, _ld(dY))
+    if st != DQ_OK:
+        raise DartQRError(st, "dq_whip_loss_grad_noalloc")
 
 
 def _ld(t):

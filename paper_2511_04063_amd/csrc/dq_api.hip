@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -44,6 +45,39 @@ LaunchScope::~LaunchScope() {
 }  // namespace dq
 
 using namespace dq;
+
+// ---------------------------------------------------------------- memory of the entry point that allocates nothing
+// Device memory that dq_whip_loss_grad_noalloc uses in place of a caller's workspace: a status word (first 256
+// bytes) and the per-workgroup partial sums of the loss.  Every GPU the library runs on holds its own copy of the
+// array for the life of the process.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// address kernels and fills are given is the one looked up below, once per device.
+constexpr int kNoallocPartials = DQ_NOALLOC_MAX_BATCH;     // at least one partial per problem
+constexpr size_t kNoallocBytes = 256 + (size_t)kNoallocPartials * sizeof(double);
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+
+namespace {
+constexpr int kNoallocMaxDevices = 64;
+std::mutex g_noalloc_mutex;
+void* g_noalloc_ptr[kNoallocMaxDevices] = {};
+
+// The device address of `scratch` on the current device (looked up on the first call on that device).
+hipError_t noalloc_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kNoallocMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (g_noalloc_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_noalloc_ptr[dev] = p;
+    }
+    *out = g_noalloc_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
 
 struct dq_ctx {
     hipStream_t stream = nullptr;    // the caller's stream: every call starts and ends here
@@ -1062,6 +1096,31 @@ dq_status dq_whip_loss_grad(dq_ctx* c, int b, int T, int n, const float* Y, long
                            (long)T * lddy));
     }
     DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, c->stream, b));
+    return DQ_OK;
+}
+
+dq_status dq_whip_loss_grad_noalloc(void* hip_stream, int b, int T, int n, const float* Y, long ldy, dq_reduce red,
+                                    float* loss_dev, void* dY, dq_dtype dydt, long lddy) {
+    if (loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1 || n < 1) return DQ_ERR_SHAPE;
+    if (b > DQ_NOALLOC_MAX_BATCH) return DQ_ERR_UNSUPPORTED;
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_f32(Y, ldy, n));
+    DQ_TRY(check_x(dY, dydt, lddy, n));
+    if (b == 0) return DQ_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    void* base = nullptr;
+    DQ_HIP(noalloc_scratch(&base));
+    unsigned* flags = static_cast<unsigned*>(base);
+    double* lpart = reinterpret_cast<double*>(static_cast<char*>(base) + 256);
+    const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
+    int grid = whip_grid(T, n);
+    if ((long)grid * b > kNoallocPartials) grid = kNoallocPartials / b;   // >= 1 since b <= kNoallocPartials
+    // the array keeps what the last call left: the status word starts from zero (a fill kernel, so that the call can
+    // be recorded into a HIP graph); every partial the finish kernel reads is written by this call's Whip pass
+    DQ_HIP(launch_fill_u32(flags, 64, 0u, s));
+    DQ_HIP(launch_whip(Y, ldy, T, n, scale, dY, dydt == DQ_BF16, lddy, lpart, grid, s, b, (long)T * ldy, (long)T * lddy));
+    DQ_HIP(launch_loss_finish(lpart, grid, scale, loss_dev, flags, s, b));
     return DQ_OK;
 }
 
