@@ -100,6 +100,21 @@ dq_status dq_set_workspace(dq_ctx* ctx, void* dptr, size_t bytes);
 
 const char* dq_status_string(dq_status s);
 
+/* Settings of a context that choose between implementations of the same result (A/B measurements, tests that must
+ * reach a particular route).  Results are the same up to rounding under every setting; defaults are the measured
+ * best.  Takes effect for the calls that follow.  DQ_ERR_DTYPE for an unknown option, DQ_ERR_SHAPE for a value out of
+ * range; the setting is unchanged on error. */
+typedef enum {
+    DQ_OPT_ACCUM_PANELS = 0,        /* panels whose reflectors are merged before they are applied to the accumulated
+                                       rotation: 1, 2 or 4; 0 (default): by size, 2 below n = 8192 and 4 from there on */
+    DQ_OPT_TALL_PANEL_MIN_ROWS = 1, /* 64-column panels at least this tall take the many-compute-unit route
+                                       (CholeskyQR2 + Householder reconstruction); 0: never, default 64 */
+    DQ_OPT_SINGLE_STREAM = 2,       /* non-zero: every piece of the QR on the context's stream, no overlap (default 0) */
+    DQ_OPT_FUSED_WHIP = 3,          /* zero: Eq. 4 always as a pass of its own, never in the epilogue of X @ R (default 1) */
+    DQ_OPT_HEADS_BATCHED = 4        /* zero: 128 x 128 problems take the general route one by one (default 1) */
+} dq_option;
+dq_status dq_set_option(dq_ctx* ctx, dq_option option, int value);
+
 /* Waits for the stream, copies the device status word to *host_out and clears it on the device. */
 dq_status dq_device_flags(dq_ctx* ctx, unsigned* host_out);
 

@@ -20,6 +20,7 @@ DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
 DQ_OBJ_WHIP, DQ_OBJ_VARIANCE, DQ_OBJ_KURTOSIS, DQ_OBJ_QUANT = 0, 1, 2, 3
 DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX = 1, 2, 4, 8
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
+DQ_OPT_ACCUM_PANELS, DQ_OPT_TALL_PANEL_MIN_ROWS, DQ_OPT_SINGLE_STREAM, DQ_OPT_FUSED_WHIP, DQ_OPT_HEADS_BATCHED = range(5)
 DQ_MAX_N = 8192
 
 _c = ctypes
@@ -33,6 +34,7 @@ SIGNATURES = {
     "dq_set_workspace": (_i, [_vp, _vp, _sz]),
     "dq_status_string": (_c.c_char_p, [_i]),
     "dq_device_flags": (_i, [_vp, _c.POINTER(_c.c_uint)]),
+    "dq_set_option": (_i, [_vp, _i, _i]),
     "dq_qr_orth": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l]),
     "dq_rotate_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _i, _vp, _vp, _l, _vp, _l, _vp, _l]),
     "dq_calib_step": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _f, _i, _vp, _vp, _l]),
@@ -72,6 +74,9 @@ def load_library(path: str | None = None):
     global _lib
     if _lib is not None and path is None:
         return _lib
+    # PyTorch first: it ships its own HIP runtime, and a process must not end up with two of them (the library would
+    # otherwise pull in the system-wide runtime when it is loaded before torch, and that copy then sees no device)
+    import torch  # noqa: F401
     p = path or LIB_PATH
     if not os.path.exists(p):
         raise RuntimeError(
@@ -167,6 +172,9 @@ class Context:
     def _check(self, st, where):
         if st != DQ_OK:
             raise DartQRError(st, where)
+
+    def dq_set_option(self, option, value):
+        self._check(self.lib.dq_set_option(self.h, option, value), "dq_set_option")
 
     def dq_device_flags(self) -> int:
         out = ctypes.c_uint(0)

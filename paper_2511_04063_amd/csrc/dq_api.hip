@@ -1,7 +1,9 @@
 // C ABI of libdartqr.so: argument checking, workspace carving and the sequencing of the kernels of one
 // QR-Orth step (Alg. 1 lines 7-10) on the caller's HIP stream.  No device memory is allocated here.
 #include <math.h>
+#include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include <mutex>
 #include <new>
@@ -88,11 +90,12 @@ struct dq_ctx {
     hipEvent_t batch_ready[2] = {nullptr, nullptr};   // staging slot holds its batch (recorded on copy_stream)
     hipEvent_t batch_done[2] = {nullptr, nullptr};    // the step that read the slot has run (recorded on stream)
     int device = 0;
-    int nb = kPanel;                 // QR panel width (<= kPanel)
     int chol_min_m = 64;             // full-width panels at least this tall take the many-CU route (0: never)
-    bool single_stream = false;      // run the look-ahead pieces on the caller's stream too (no overlap)
+    bool single_stream = false;      // run every piece of the QR on the caller's stream (no overlap)
     int accum_panels = 0;            // panels merged per update of the accumulated R (0: by size, 2 below n = 8192 and
                                      // 4 from there on, each measured best there; 1: panel by panel)
+    bool fused_whip = true;          // Eq. 4 in the epilogue of the rotation product where the shape allows
+    bool heads_batched = true;       // n == 128: all problems of a batch in the same launches
     int objective = DQ_OBJ_WHIP;     // what S4 evaluates (dq_set_objective)
     int quant_bits = 4;
     char* ws = nullptr;
@@ -131,7 +134,7 @@ Layout make_layout(int n, int T) {
     L.P = bump(cur, n2 * 4);
     L.M = bump(cur, n2 * 4);
     L.tau = bump(cur, (size_t)round_up(n, 64) * 4);
-    const size_t npanels = (n + kPanelMin - 1) / kPanelMin;
+    const size_t npanels = (n + kPanel - 1) / kPanel;
     L.Tall = bump(cur, npanels * kPanel * kPanel * 4);
     L.wpart = bump(cur, (size_t)kMaxSplit * kPanel * L.ld * 4);
     L.w2 = bump(cur, (size_t)kPanel * L.ld * 4);
@@ -209,8 +212,8 @@ dq_status check_ws(dq_ctx* c, const Layout& L) {
 // ---------------------------------------------------------------- split-K choice
 // Enough layers to give every compute unit a workgroup when the output has few tiles.
 void choose_split(int tiles, int K, int kalign, int max_splits, int& splits, int& kchunk) {
-    static const int target = [] { const char* e = getenv("DQ_SPLIT_TARGET"); return e ? atoi(e) : 768; }();
-    static const int mink = [] { const char* e = getenv("DQ_SPLIT_MINK"); return e ? atoi(e) : 128; }();
+    constexpr int target = 768;   // workgroups aimed for (three per compute unit)
+    constexpr int mink = 128;     // at least this many reduction elements per layer
     splits = 1;
     if (tiles < 256) {
         splits = (target + tiles - 1) / tiles;
@@ -449,7 +452,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     // S1.  Panel p is factored on the caller's stream while the trailing update of panel p-1 still runs on the
     // second stream: after panel p only the columns of panel p+1 ("look-ahead" part) are updated on the caller's
     // stream; the rest of the trailing matrix goes to the second stream.
-    const int nb = c->nb;
+    const int nb = kPanel;
     const int npanels = (n + nb - 1) / nb;
     int last_trailing = -1;
     bool gram_ready = false;   // the Gram partials of the coming panel were left by the previous panel's look-ahead
@@ -559,10 +562,9 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
     double* lpart = at<double>(c, L.losspart);
     const float scale = (red == DQ_REDUCE_TOKEN_MEAN) ? 1.f / (float)T : 1.f;
     const double gemm_flops = 2.0 * T * (double)n * n;
-    static const int use_t = [] { const char* e = getenv("DQ_G_TRANSPOSE"); return e ? atoi(e) : 1; }();
-    static const int use_fused = [] { const char* e = getenv("DQ_FUSED_WHIP"); return e ? atoi(e) : 1; }();
+    const bool use_fused = c->fused_whip;
     // large round bf16 shapes: S5 reads token-contiguous copies of both operands (see below)
-    const bool g_transposed = xdt == DQ_BF16 && use_t && n % 128 == 0 && T % 128 == 0 && (n / 128) * (n / 128) >= 256 &&
+    const bool g_transposed = xdt == DQ_BF16 && n % 128 == 0 && T % 128 == 0 && (n / 128) * (n / 128) >= 256 &&
                               (ldx & 7) == 0 && aligned16(X) && aligned16(G) && (ldg & 3) == 0;
     bool fused = false;   // S4 done in the epilogue of S3
     // S3: Y = X @ R
@@ -762,12 +764,9 @@ HeadsLayout make_heads_layout(size_t base, int b, int T) {
     return H;
 }
 
-bool heads_route(int n) {
-    static const int on = [] { const char* e = getenv("DQ_HEADS_BATCHED"); return e ? atoi(e) : 1; }();
-    return on != 0 && n == kHeadDim;
-}
+bool heads_route(const dq_ctx* c, int n) { return c->heads_batched && n == kHeadDim; }
 // the fused rotate + loss + gradient kernel of the batched route evaluates Eq. 4 only
-bool heads_fused_route(const dq_ctx* c, int n) { return heads_route(n) && c->objective == DQ_OBJ_WHIP; }
+bool heads_fused_route(const dq_ctx* c, int n) { return heads_route(c, n) && c->objective == DQ_OBJ_WHIP; }
 
 dq_status check_heads_ws(dq_ctx* c, const HeadsLayout& H) {
     if (c->ws == nullptr || c->ws_bytes < H.total) return DQ_ERR_WORKSPACE;
@@ -869,19 +868,27 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
     dq_ctx* c = new (std::nothrow) dq_ctx();
     if (c == nullptr) return DQ_ERR_HIP;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    if (const char* e = getenv("DQ_PANEL_NB")) { const int v = atoi(e); if (v >= kPanelMin && v <= kPanel && v % 8 == 0) c->nb = v; }
-    if (const char* e = getenv("DQ_SINGLE_STREAM")) c->single_stream = atoi(e) != 0;
-    if (const char* e = getenv("DQ_ACCUM_PANELS")) { const int v = atoi(e); if (v >= 1 && v <= kAccumPanels) c->accum_panels = v; }
-    if (const char* e = getenv("DQ_TALL_PANEL_MIN_M")) { const int v = atoi(e); if (v >= 0) c->chol_min_m = v; }
-    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return DQ_ERR_HIP; }
-    // default priority on purpose; non-blocking so that it never synchronises with the legacy default stream
-    if (hipStreamCreateWithFlags(&c->stream2, hipStreamNonBlocking) != hipSuccess) { delete c; return DQ_ERR_HIP; }
-    if (hipStreamCreateWithFlags(&c->stream3, hipStreamNonBlocking) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
-    const int nev = 2 * (DQ_MAX_N / kPanelMin) + 1;
+    // a context that cannot be created says why on stderr: there is no other channel yet
+    auto fail = [&](const char* what, hipError_t e) {
+        fprintf(stderr, "dq_create: %s failed: %s\n", what, hipGetErrorString(e));
+        dq_destroy(c);
+        return DQ_ERR_HIP;
+    };
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) return fail("hipGetDevice", e);
+    // default priority on purpose; non-blocking so that they never synchronise with the legacy default stream
+    hipStream_t* internal[3] = {&c->stream2, &c->stream3, nullptr};
+    for (int i = 0; internal[i] != nullptr; ++i)
+        if ((e = hipStreamCreateWithFlags(internal[i], hipStreamNonBlocking)) != hipSuccess)
+            return fail("hipStreamCreateWithFlags", e);
+    const int nev = 2 * (DQ_MAX_N / kPanel) + 1;
     for (int i = 0; i < nev; ++i) {
-        hipEvent_t e;
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { dq_destroy(c); return DQ_ERR_HIP; }
-        c->sync_ev.push_back(e);
+        hipEvent_t ev;
+        // These events order kernels on streams of this device only: no timing, and no system-scope fence (the cache
+        // write-back that makes device memory visible to the host and to other devices) when one is recorded.
+        if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming | hipEventDisableSystemFence)) != hipSuccess)
+            return fail("hipEventCreateWithFlags", e);
+        c->sync_ev.push_back(ev);
     }
     *out = c;
     return DQ_OK;
@@ -889,7 +896,7 @@ dq_status dq_create(dq_ctx** out, void* hip_stream) {
 
 dq_status dq_destroy(dq_ctx* c) {
     if (c == nullptr) return DQ_ERR_NULL;
-    (void)hipStreamSynchronize(c->stream);
+    if (c->stream2 != nullptr) (void)hipStreamSynchronize(c->stream);   // a context that got as far as launching
     if (c->stream2 != nullptr) { (void)hipStreamSynchronize(c->stream2); (void)hipStreamDestroy(c->stream2); }
     if (c->stream3 != nullptr) { (void)hipStreamSynchronize(c->stream3); (void)hipStreamDestroy(c->stream3); }
     if (c->copy_stream != nullptr) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamDestroy(c->copy_stream); }
@@ -909,7 +916,7 @@ dq_status dq_workspace_bytes(int b, int n, int T, dq_dtype x_dtype, size_t* out)
     DQ_TRY(check_n(n));
     if (x_dtype != DQ_F32 && x_dtype != DQ_BF16) return DQ_ERR_DTYPE;
     const Layout L = make_layout(n, T);
-    *out = heads_route(n) ? make_heads_layout(L.total, b, T).total : L.total;
+    *out = n == kHeadDim ? make_heads_layout(L.total, b, T).total : L.total;
     return DQ_OK;
 }
 
@@ -941,7 +948,7 @@ dq_status dq_qr_orth(dq_ctx* c, int b, int n, const float* Z, long ldz, float* R
     if (U != nullptr) DQ_TRY(check_f32(U, ldu, n));
     const Layout L = make_layout(n, 1);
     DQ_TRY(check_ws(c, L));
-    if (heads_route(n)) return heads_qr(c, b, Z, ldz, R, ldr, U, ldu);
+    if (heads_route(c, n)) return heads_qr(c, b, Z, ldz, R, ldr, U, ldu);
     for (int i = 0; i < b; ++i)
         DQ_TRY(qr_orth_one(c, L, n, Z + (long)i * n * ldz, ldz, R + (long)i * n * ldr, ldr,
                            U ? U + (long)i * n * ldu : nullptr, ldu));
@@ -1165,6 +1172,24 @@ dq_status dq_set_objective(dq_ctx* c, dq_objective objective, int quant_bits) {
     return DQ_OK;
 }
 
+dq_status dq_set_option(dq_ctx* c, dq_option option, int value) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    switch (option) {
+        case DQ_OPT_ACCUM_PANELS:
+            if (value < 0 || value > kAccumPanels) return DQ_ERR_SHAPE;
+            c->accum_panels = value;
+            return DQ_OK;
+        case DQ_OPT_TALL_PANEL_MIN_ROWS:
+            if (value < 0) return DQ_ERR_SHAPE;
+            c->chol_min_m = value;
+            return DQ_OK;
+        case DQ_OPT_SINGLE_STREAM: c->single_stream = value != 0; return DQ_OK;
+        case DQ_OPT_FUSED_WHIP: c->fused_whip = value != 0; return DQ_OK;
+        case DQ_OPT_HEADS_BATCHED: c->heads_batched = value != 0; return DQ_OK;
+    }
+    return DQ_ERR_DTYPE;
+}
+
 dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, const float* U, long ldu, const float* G,
                          long ldg, float* dZ, long lddz) {
     if (c == nullptr) return DQ_ERR_NULL;
@@ -1176,7 +1201,7 @@ dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, cons
     DQ_TRY(check_f32(dZ, lddz, n));
     const Layout L = make_layout(n, 1);
     DQ_TRY(check_ws(c, L));
-    if (heads_route(n)) {
+    if (heads_route(c, n)) {
         const HeadsLayout H = make_heads_layout(L.total, b, 1);
         DQ_TRY(check_heads_ws(c, H));
         return heads_backward(c, H, b, R, ldr, U, ldu, G, ldg, dZ, lddz, nullptr, 0, 0.f);

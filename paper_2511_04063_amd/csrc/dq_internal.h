@@ -11,7 +11,6 @@ namespace dq {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kPanel = 64;           // QR panel width nb (columns aggregated into one compact-WY block)
 constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
-constexpr int kPanelMin = 32;         // smallest panel width the sync-event pool is sized for
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
 constexpr int kHeadDim = 128;         // matrix size served by the batched small-rotation path
 constexpr int kHeadsChunk = 2048;     // tokens per workgroup of its fused rotate / loss / gradient kernel

@@ -425,7 +425,7 @@ __global__ __launch_bounds__(256) void momentum2d_kernel(float* __restrict__ Z, 
 int whip_grid(long rows, int cols) {
     const long chunks = rows * (long)((cols + 7) / 8);
     long g = (chunks + 255) / 256;
-    static const int cap = [] { const char* e = getenv("DQ_WHIP_GRID"); int v = e ? atoi(e) : 2048; return v < 1 ? 1 : (v > kLossPartials ? kLossPartials : v); }();
+    constexpr int cap = 2048;   // workgroups that saturate HBM with eight 4 KiB pieces in flight each
     if (g > cap) g = cap;
     if (g < 1) g = 1;
     return (int)g;
@@ -434,12 +434,11 @@ int whip_grid(long rows, int cols) {
 hipError_t launch_whip(const float* Y, long ldy, int T, int n, float scale, void* dY, int dy_is_bf16, long lddy,
                        double* partials, int grid, hipStream_t s, int batch, long stride_y, long stride_dy) {
     if (batch < 1) return hipSuccess;
-    static const int flat = [] { const char* e = getenv("DQ_WHIP_FLAT"); return e ? atoi(e) : 1; }();
     // yvec: 0 scalar loads, 1 16-byte loads, 2 the flat path for dense rows, 3 the same with nontemporal loads
     // (Y beyond the 256 MiB last-level cache)
-    static const long nt_bytes = [] { const char* e = getenv("DQ_WHIP_NT_MIB"); return (e ? atol(e) : 192L) << 20; }();
+    constexpr long nt_bytes = 192L << 20;
     const bool big = (long)batch * T * n * 4 > nt_bytes;   // the whole batch streams through the cache
-    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? (flat ? (big ? 3 : 2) : 1) : 0;
+    const int yvec = ((reinterpret_cast<uintptr_t>(Y) & 15) == 0 && (ldy & 3) == 0) ? (big ? 3 : 2) : 0;
     if (dy_is_bf16) {
         const int dvec = ((reinterpret_cast<uintptr_t>(dY) & 15) == 0 && (lddy & 7) == 0) ? 1 : 0;
         hipLaunchKernelGGL((whip_kernel<true>), dim3(grid, batch), dim3(256), 0, s, Y, ldy, T, n, scale, dY, lddy,

@@ -414,7 +414,6 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
     const int avec = ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0 && (g.lda & 7) == 0) ? 1 : 0;
     const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0) ? 1 : 0;
     // big NT products without split-K and with round sizes: the unguarded kernel with the deep prefetch
-    static const int use_deep = [] { const char* e = getenv("DQ_BF16_DEEP"); return e ? atoi(e) : 1; }();
     const bool fits = gemm_bf16_deep_fits(g);
     if (g.whip_dyt != nullptr) {   // the fused epilogue exists in the unguarded kernel only: the caller checks first
         if (!fits || g.whip_partials == nullptr || (g.whip_ldt & 7) != 0 || g.whip_ldt < g.M ||
@@ -424,7 +423,7 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
                            tiles_n);
         return hipGetLastError();
     }
-    if (use_deep && fits) {
+    if (fits) {
         hipLaunchKernelGGL((gemm_bf16_nt_deep_kernel<false>), dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m,
                            tiles_n);
         return hipGetLastError();

@@ -345,8 +345,7 @@ int objective_grid(int T, int n) {
     long g = ((long)T + rpw - 1) / rpw;
     // measured at T = 8192..16384: rows of n > 1024 (one workgroup per row) run best with about 1024 workgroups
     // that each walk several rows (the next row is fetched while one is worked on), short rows with 8192
-    static const long env_cap = [] { const char* e = getenv("DQ_OBJ_GRID"); return e ? atol(e) : 0L; }();
-    const long cap = env_cap > 0 ? env_cap : (n <= 1024 ? 8192L : 1024L);
+    const long cap = n <= 1024 ? 8192L : 1024L;
     if (g > cap) g = cap;
     return (int)(g < 1 ? 1 : g);
 }

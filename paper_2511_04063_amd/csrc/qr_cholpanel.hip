@@ -29,14 +29,6 @@ namespace {
 constexpr int RT = 128;          // rows of one tile
 constexpr int NSUM = 512;        // threads of the small-matrix kernels while they sum the partials
 
-#ifdef DQ_SMALL_TRACE
-#define ST_DECL long long st_t0 = wall_clock64(), st_acc[16] = {0,0,0,0,0,0,0,0,0,0,0,0,0,0,0,0}
-#define ST(k) do { const long long t_ = wall_clock64(); st_acc[k] += t_ - st_t0; st_t0 = t_; } while (0)
-#else
-#define ST_DECL
-#define ST(k)
-#endif
-
 // rows [row0, row0 + 128) x 64 columns of X (leading dimension ldx, 16-byte aligned rows) -> Xs[r * LS + c];
 // rows >= mrows read as zero.
 __device__ __forceinline__ void load_tile(const float* __restrict__ X, long ldx, int row0, int mrows, float* Xs,
@@ -669,7 +661,6 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     const int lrow = lane & 31, lk = lane >> 5;
     const int qi = (wave >> 1) & 1, qj = wave & 1;
 
-    ST_DECL;
     // U1 and the top block of Q1 are needed well after the partials are summed: requested now, they arrive meanwhile
     float u1r[16], q1r[16];
     if (tid < NTHR) {
@@ -677,7 +668,6 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         for (int q = 0; q < 16; ++q) { u1r[q] = U1[tid + NTHR * q]; q1r[q] = q1[tid + NTHR * q]; }
     }
     sum_partials(part, nparts, B0, tid);
-    ST(0);
     {   // ||G2 - I||_F^2 must be small: then Q1 is well conditioned and the second pass gives orthonormal columns
         if (tid < NTHR) {
             float dev = 0.f;
@@ -709,7 +699,6 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         }
     }
     if (tid >= NTHR) return;                    // the extra wavefronts only help to fetch the partials
-    ST(1);
     if (redw[0] + redw[1] + redw[2] + redw[3] < 4.0e-8f) {
         // G2 = I + E with ||E||_F < 2e-4 (the usual case for a well-conditioned panel): the Cholesky factor is
         // I + X with X = strict_upper(E) + diag(E) / 2 and its inverse I - X, both up to O(||E||^2) < fp32 rounding.
@@ -726,10 +715,8 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         __syncthreads();
     } else {
         chol_upper_64(B0, tid);                 // B0 = U2
-        ST(2);
         tri_inv_upper_64<false>(B0, B1, tid);   // B1 = U2^-1
     }
-    ST(3);
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
@@ -751,11 +738,8 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         acc_to_lds(accQ, B0, qi, qj, lrow, lk);
     }
     __syncthreads();
-    ST(4);
     lu_signed_64(B0, sg, tid);                  // B0 = L \ U_lu, sg = S
-    ST(5);
     tri_inv_upper_64<false>(B0, B2, tid);       // B2 = U_lu^-1
-    ST(6);
     // Mm = U2^-1 U_lu^-1, kept in registers as well: it is multiplied by T further down
     f32x16 accM = zero16();
     if (qi <= qj) accM = lds_mma<0>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
@@ -771,9 +755,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
         B1[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
     }
     __syncthreads();
-    ST(7);
     tri_inv_upper_64<true>(B1, B2, tid);        // B2 = V_top^-T
-    ST(8);
     {   // T = -(U_lu S) V_top^-T  -> global and B1; the triangular factor S Rf -> panel
         f32x16 accT = zero16();
         if (qi <= qj) accT = lds_mma<1>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
@@ -801,11 +783,6 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
             Yp[r * B64 + c] = accY[v];
         }
     }
-    ST(9);
-#ifdef DQ_SMALL_TRACE
-    if (tid == 0 && m >= 3072 && m < 3200)
-        printf("hr_finish m=%d: sum %lld cert %lld chol %lld inv %lld Rf+Qtop %lld lu %lld inv %lld M+copy %lld inv %lld T+M2+Y %lld (10 ns ticks)\n", m, st_acc[0], st_acc[1], st_acc[2], st_acc[3], st_acc[4], st_acc[5], st_acc[6], st_acc[7], st_acc[8], st_acc[9]);
-#endif
 }
 
 }  // namespace
@@ -832,15 +809,9 @@ struct TallScratch {
 };
 // Row tiles of 128 per workgroup and number of workgroups (= Gram partials) for a panel of m rows.  More partials
 // shorten the tall-skinny kernels but lengthen the one-workgroup sums; 32 was the knee at n = 4096 and 8192 (8: +20 %, 16: +5 %).
-// DQ_TALL_PANEL_PARTS overrides (tuning only).
 void tall_split(int m, int& tpw, int& nparts) {
-    static const int parts_cap = [] {
-        const char* e = getenv("DQ_TALL_PANEL_PARTS");
-        int v = e ? atoi(e) : 0;
-        return v < 1 ? 0 : (v > kCholMaxParts ? kCholMaxParts : v);
-    }();
-    // by size unless overridden: 32 up to m = 4096, 64 above (30.4 against 31.0 ms for the QR at n = 8192)
-    const int cap = parts_cap > 0 ? parts_cap : (m > 4096 ? 64 : 32);
+    // 32 up to m = 4096, 64 above (30.4 against 31.0 ms for the QR at n = 8192)
+    const int cap = m > 4096 ? 64 : 32;
     const int tiles = (m + RT - 1) / RT;
     tpw = (tiles + cap - 1) / cap;
     nparts = (tiles + tpw - 1) / tpw;

@@ -12,14 +12,6 @@
 
 namespace dq {
 
-#ifdef DQ_PANEL_TRACE
-#define TR_DECL long long tr_t0 = wall_clock64(), tr_acc[12] = {0,0,0,0,0,0,0,0,0,0,0,0}
-#define TR(k) do { const long long t_ = wall_clock64(); tr_acc[k] += t_ - tr_t0; tr_t0 = t_; } while (0)
-#else
-#define TR_DECL
-#define TR(k)
-#endif
-
 // One workgroup of NT threads factors an m x jb panel (m <= NT*Q).  The panel is processed in slices of
 // SW columns; thread t keeps rows t, t+NT, ... of the current slice in registers.  Before a slice is
 // factored, the reflector blocks of the earlier slices of the same panel are applied to it
@@ -47,7 +39,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
     int par = 0;
 
     float a[Q][SW];
-    TR_DECL;
 
     for (int s = 0; s < ns; ++s) {
         const int col0 = s * SW;
@@ -70,7 +61,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
             }
         }
 
-        TR(0);
         // ---- apply the block reflectors of the earlier slices:  A_s -= V_p (T_p^T (V_p^T A_s))
         for (int p = 0; p < s; ++p) {
             // VCH rows of V_p are held at a time: all of them when they fit the register budget (one read of V_p),
@@ -91,7 +81,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
                         v[ii][c4 + 0] = t4.x; v[ii][c4 + 1] = t4.y; v[ii][c4 + 2] = t4.z; v[ii][c4 + 3] = t4.w;
                     }
                 }
-                TR(1);
 #pragma unroll
                 for (int ii = 0; ii < VCH; ++ii)
 #pragma unroll
@@ -100,11 +89,9 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
                         for (int c = 0; c < SW; ++c) wacc[cp * SW + c] += v[ii][cp] * a[i0 + ii][c];
                 if constexpr (VCH != Q) __builtin_amdgcn_sched_barrier(0);   // keep one chunk of V_p live at a time
             }
-            TR(2);
             const int idx = wave_reduce_multi<NV2>(wacc, lane);
             if (wave_reduce_writer<NV2>(lane)) red[0][wave][idx] = wacc[0];
             lds_barrier();
-            TR(3);
             if (tid < NV2) {
                 float t = 0.f;
 #pragma unroll
@@ -119,7 +106,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
                 W2sh[tid] = t;
             }
             lds_barrier();
-            TR(4);
 #pragma unroll
             for (int i0 = 0; i0 < Q; i0 += VCH) {
                 if constexpr (VCH != Q) {
@@ -150,7 +136,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
                 }
                 if constexpr (VCH != Q) __builtin_amdgcn_sched_barrier(0);
             }
-            TR(5);
         }
 
         // ---- factor the slice column by column
@@ -177,12 +162,9 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
 #pragma unroll
                     for (int cp = 0; cp < SW; ++cp) rowd[par][cp] = a[0][cp];
                 }
-                TR(6);
                 const int idx = wave_reduce_multi<SW>(part, lane);
                 if (wave_reduce_writer<SW>(lane)) red[par][wave][idx] = part[0];
-                TR(7);
                 lds_barrier();
-                TR(8);
                 float sd[SW], rd[SW];
                 if constexpr (NW * SW == 64) {
                     // one value per lane: lane l takes wavefront l / SW's partial of dot l % SW; the sum over the
@@ -209,7 +191,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
                 for (int cp = 0; cp < SW; ++cp) rd[cp] = rowd[par][cp];
                 par ^= 1;
 
-                TR(9);
                 const float alpha = rd[c];
                 const float xn2 = sd[c];
                 float beta, tc, scale;
@@ -259,7 +240,6 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
             }
         }
 
-        TR(10);
         // ---- store: in place (triangular factor on/above the diagonal, reflectors below) and the packed copy
 #pragma unroll
         for (int c = 0; c < SW; ++c)
@@ -294,12 +274,7 @@ __device__ __forceinline__ void qr_panel_body(float* __restrict__ A, long lda, i
         }
         lds_barrier();
         if (tid < NV2) tslices[s * NV2 + tid] = Tsh[s][tid];
-        TR(11);
     }
-#ifdef DQ_PANEL_TRACE
-    if (tid == 0 && m >= 3072 && m < 3200)
-        printf("panel m=%d jb=%d load %lld | pairload %lld pairfma %lld pairshfl %lld pairsync %lld pairupd %lld | coldot %lld colshfl %lld colbar %lld colread %lld colmath+upd %lld | store %lld (ticks of 10 ns)\n", m, jb, tr_acc[0], tr_acc[1], tr_acc[2], tr_acc[3], tr_acc[4], tr_acc[5], tr_acc[6], tr_acc[7], tr_acc[8], tr_acc[9], tr_acc[10], tr_acc[11]);
-#endif
 }
 
 // Copies rows jb..m-1 of a factored panel from the packed slice-major copy [slice][row][sw] into the matrix
