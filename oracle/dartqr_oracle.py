@@ -64,6 +64,14 @@ Readings taken where the paper is silent (each is also listed in the design note
                   test can separate "a valid other code" from "a wrong result".
   Pinned by library routines (numpy.var, scipy.stats.kurtosis), closed forms, a brute-force nearest-level search,
   invariances and central finite differences (tests/).
+* Alg. 3 (App. B.2), Cayley SGD with momentum, the optimiser QR-Orth is compared with (Sec. 5, optimiser comparison):
+  it acts on the rotation itself (the algorithm's X is this module's R), with the Euclidean gradient dL/dR.  As
+  printed, the skew-symmetrisation step reads "W_k <- W^_k - W_k^T"; it is read as W_k = W^_k - W^_k^T (the only
+  reading that makes W_k skew-symmetric, which the Cayley transform needs).  The norm in the step-size rule
+  alpha = min(l, 2q / (||W_k|| + eps)) is not named; the Frobenius norm is taken (it bounds the spectral norm, so
+  the fixed-point iteration of the transform contracts at rate alpha ||W_k||_2 / 2 <= q either way).  The loop
+  "for k = 0 to T" is run for the number of steps asked for.  Pinned by the exact Cayley transform (a linear solve),
+  the contraction bound of the iteration, a 2 x 2 closed form, descent identities and orthogonality (tests/).
 """
 
 from __future__ import annotations
@@ -94,6 +102,8 @@ __all__ = [
     "quant_objective",
     "objective_loss_grad",
     "calibrate_batches",
+    "cayley_sgd_update",
+    "cayley_step",
 ]
 
 
@@ -460,3 +470,36 @@ def calibrate_batches(X_batches, Z0, steps: int, lr: float, reduce: str = "mean"
         losses.append(out["loss"])
         Z = out["Z_new"]
     return np.array(losses), Z
+
+
+def cayley_sgd_update(R, G, M, lr: float, beta: float = 0.9, q: float = 0.5, s: int = 2, eps: float = 1e-8):
+    """One update of Alg. 3 (App. B.2): Cayley SGD with momentum on an orthogonal matrix (the algorithm's X_k is the
+    rotation R, its gradient G = dL/dR, its momentum buffer M, zero before the first step).
+
+        M' = beta M - G
+        W^ = M' R^T - (1/2) R (R^T M' R^T);   W = W^ - W^^T   (skew-symmetric)
+        M_new = W R                              (the momentum, projected onto the tangent space at R)
+        alpha = min(lr, 2 q / (||W||_F + eps))
+        Y^0 = R + alpha M_new;   Y^i = R + (alpha / 2) W (R + Y^(i-1)),  i = 1 .. s;   R_new = Y^s
+    The iteration is the fixed-point form of the Cayley transform (I - alpha/2 W)^-1 (I + alpha/2 W) R.
+    Returns (R_new, M_new, alpha, W)."""
+    R = _f64(R)
+    Mp = float(beta) * _f64(M) - _f64(G)
+    A = Mp @ R.T
+    W_hat = A - 0.5 * (R @ (R.T @ A))
+    W = W_hat - W_hat.T
+    M_new = W @ R
+    alpha = min(float(lr), 2.0 * float(q) / (float(np.sqrt(np.sum(W * W))) + float(eps)))
+    Y = R + alpha * M_new
+    for _ in range(int(s)):
+        Y = R + (alpha / 2.0) * (W @ (R + Y))
+    return Y, M_new, alpha, W
+
+
+def cayley_step(X, R, M, lr: float, beta: float = 0.9, reduce: str = "mean", q: float = 0.5, s: int = 2,
+                eps: float = 1e-8):
+    """One calibration step with the optimiser of Alg. 3 in place of QR-Orth: loss and dL/dR at the INPUT rotation
+    (Alg. 1 lines 8-9), then the Cayley update of R itself.  Returns a dict like ``calib_step``."""
+    loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
+    R_new, M_new, alpha, W = cayley_sgd_update(R, G, M, lr, beta, q, s, eps)
+    return {"loss": loss, "G": G, "R_new": R_new, "M_new": M_new, "alpha": alpha, "W": W}

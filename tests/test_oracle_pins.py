@@ -767,3 +767,91 @@ def test_calibrate_batches_pins():
     g_all = orc.calib_step(np.vstack(Xs), Z0, 1.0, "sum")["dZ"]
     g_sum = sum(orc.calib_step(x, Z0, 1.0, "sum")["dZ"] for x in Xs)
     np.testing.assert_allclose(g_all, g_sum, rtol=1e-10, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------------- Cayley SGD (Alg. 3, App. B.2)
+def _random_rotation(rng, n):
+    Q, Rf = np.linalg.qr(rng.standard_normal((n, n)))
+    return Q * np.sign(np.diag(Rf))[None, :]
+
+
+def test_cayley_update_is_the_cayley_transform_up_to_the_contraction_bound():
+    rng = np.random.default_rng(401)
+    n = 12
+    R = _random_rotation(rng, n)
+    G = rng.standard_normal((n, n))
+    M = 0.3 * rng.standard_normal((n, n))
+    for lr in (1e-3, 5e-2, 10.0):                    # the last one is cut by the 2 q / ||W|| rule
+        for s in (1, 2, 5):
+            Rn, Mn, alpha, W = orc.cayley_sgd_update(R, G, M, lr, beta=0.9, q=0.5, s=s)
+            np.testing.assert_allclose(W, -W.T, atol=1e-14)
+            assert alpha == pytest.approx(min(lr, 1.0 / (np.linalg.norm(W) + 1e-8)), rel=1e-14)
+            # exact transform by a linear solve (library routine)
+            I = np.eye(n)
+            exact = np.linalg.solve(I - 0.5 * alpha * W, (I + 0.5 * alpha * W) @ R)
+            np.testing.assert_allclose(exact.T @ exact, I, atol=1e-12)        # skew W: the transform is orthogonal
+            rho = 0.5 * alpha * np.linalg.norm(W, 2)
+            assert rho <= 0.5 + 1e-12
+            y0 = R + alpha * (W @ R)
+            # the iteration contracts towards the transform at rate rho per pass
+            assert np.linalg.norm(Rn - exact, 2) <= rho ** s * np.linalg.norm(y0 - exact, 2) * (1 + 1e-9) + 1e-14
+            # so the result is orthogonal to that accuracy
+            assert np.abs(Rn.T @ Rn - I).max() <= 3 * rho ** s * np.linalg.norm(y0 - exact, 2) + 1e-13
+    # many passes: the transform itself
+    Rn, _, alpha, W = orc.cayley_sgd_update(R, G, M, 5e-2, s=60)
+    np.testing.assert_allclose(Rn, np.linalg.solve(np.eye(n) - 0.5 * alpha * W, (np.eye(n) + 0.5 * alpha * W) @ R),
+                               atol=1e-13)
+
+
+def test_cayley_update_descent_identities():
+    """Without momentum and at an orthogonal R:  W = (A - A^T) / 2 with A = -G R^T, the new momentum W R is tangent
+    (R^T (W R) is skew-symmetric), and <G, W R> = -||W||_F^2: the first-order change of the loss along the step."""
+    rng = np.random.default_rng(402)
+    n = 9
+    R = _random_rotation(rng, n)
+    G = rng.standard_normal((n, n))
+    Rn, Mn, alpha, W = orc.cayley_sgd_update(R, G, np.zeros((n, n)), 1e-4, beta=0.0)
+    A = -G @ R.T
+    np.testing.assert_allclose(W, 0.5 * (A - A.T), atol=1e-13)
+    np.testing.assert_allclose(Mn, W @ R, atol=1e-14)
+    np.testing.assert_allclose(R.T @ Mn, -(R.T @ Mn).T, atol=1e-13)
+    assert np.sum(G * Mn) == pytest.approx(-np.sum(W * W), rel=1e-12)
+    # first order in alpha: R_new = R + alpha W R + O(alpha^2)
+    assert np.linalg.norm(Rn - (R + alpha * Mn)) <= 0.6 * alpha ** 2 * np.linalg.norm(W, 2) ** 2 * np.linalg.norm(R)
+    # the momentum enters linearly before the projection: beta M - G
+    M = rng.standard_normal((n, n))
+    _, _, _, W2 = orc.cayley_sgd_update(R, G, M, 1e-4, beta=0.7)
+    _, _, _, W3 = orc.cayley_sgd_update(R, G - 0.7 * M, np.zeros((n, n)), 1e-4, beta=0.0)
+    np.testing.assert_allclose(W2, W3, atol=1e-13)
+
+
+def test_cayley_update_two_by_two_closed_form():
+    """n = 2: rotations are unit complex numbers and W = w J; two passes of the iteration give
+    R (1 + i a - a^2 / 2 - i a^3 / 4) with a = alpha w."""
+    theta, lr = 0.7, 0.3
+    R = np.array([[np.cos(theta), -np.sin(theta)], [np.sin(theta), np.cos(theta)]])
+    G = np.array([[0.3, -1.1], [0.4, 0.2]])
+    Rn, Mn, alpha, W = orc.cayley_sgd_update(R, G, np.zeros((2, 2)), lr, beta=0.0, s=2)
+    A = -G @ R.T
+    w = 0.5 * (A[1, 0] - A[0, 1])                    # W = [[0, -w], [w, 0]]
+    np.testing.assert_allclose(W, [[0.0, -w], [w, 0.0]], atol=1e-15)
+    assert alpha == pytest.approx(min(lr, 1.0 / (np.sqrt(2.0) * abs(w) + 1e-8)), rel=1e-14)
+    a = alpha * w
+    z = np.exp(1j * theta) * (1 + 1j * a - a * a / 2 - 1j * a ** 3 / 4)
+    np.testing.assert_allclose(Rn, [[z.real, -z.imag], [z.imag, z.real]], atol=1e-14)
+
+
+def test_cayley_step_lowers_the_loss_and_reports_the_input_rotation():
+    rng = np.random.default_rng(403)
+    n, T = 8, 96
+    X = rng.standard_t(3.0, size=(T, n))
+    R = _random_rotation(rng, n)
+    M = np.zeros((n, n))
+    losses = []
+    for _ in range(8):
+        out = orc.cayley_step(X, R, M, 0.5, beta=0.5)
+        assert out["loss"] == pytest.approx(orc.whip_loss(orc.rotate(X, R)), rel=1e-14)
+        losses.append(out["loss"])
+        R, M = out["R_new"], out["M_new"]
+    assert losses[-1] < losses[0]
+    assert np.abs(R.T @ R - np.eye(n)).max() < 1e-2        # the two-pass iteration drifts slowly off the manifold

@@ -166,6 +166,35 @@ def calibrate_batches_off_by_one(X_batches, Z0, steps, lr, reduce="mean"):
     return _ORIG["calibrate_batches"](list(X_batches[1:]) + list(X_batches[:1]), Z0, steps, lr, reduce)
 
 
+def _cayley_variant(ascent=False, full_projection=False, symmetric=False, full_step_in_iteration=False,
+                    momentum_before_projection=False):
+    def f(R, G, M, lr, beta=0.9, q=0.5, s=2, eps=1e-8):
+        R = _f64(R)
+        Mp = float(beta) * _f64(M) + (_f64(G) if ascent else -_f64(G))
+        A = Mp @ R.T
+        W_hat = A - (1.0 if full_projection else 0.5) * (R @ (R.T @ A))
+        W = W_hat + W_hat.T if symmetric else W_hat - W_hat.T
+        M_new = Mp if momentum_before_projection else W @ R
+        alpha = min(float(lr), 2.0 * float(q) / (float(np.sqrt(np.sum(W * W))) + float(eps)))
+        Y = R + alpha * M_new
+        for _ in range(int(s)):
+            Y = R + (alpha if full_step_in_iteration else alpha / 2.0) * (W @ (R + Y))
+        return Y, M_new, alpha, W
+    return f
+
+
+cayley_ascent = _cayley_variant(ascent=True)
+cayley_ascent.__name__ = "cayley_ascent"
+cayley_full_projection = _cayley_variant(full_projection=True)
+cayley_full_projection.__name__ = "cayley_full_projection"
+cayley_symmetric = _cayley_variant(symmetric=True)
+cayley_symmetric.__name__ = "cayley_symmetric"
+cayley_full_step_in_iteration = _cayley_variant(full_step_in_iteration=True)
+cayley_full_step_in_iteration.__name__ = "cayley_full_step_in_iteration"
+cayley_unprojected_momentum = _cayley_variant(momentum_before_projection=True)
+cayley_unprojected_momentum.__name__ = "cayley_unprojected_momentum"
+
+
 _ORIG = {name: getattr(orc, name) for name in orc.__all__}
 
 CASES = [
@@ -194,6 +223,13 @@ CASES = [
     ("calib_step", calib_step_reports_updated_loss,
      lambda: pins.test_calibration_loop_decreases_loss_and_reports_input_loss()),
     ("calibrate_batches", calibrate_batches_off_by_one, lambda: pins.test_calibrate_batches_pins()),
+    ("cayley_sgd_update", cayley_ascent, lambda: pins.test_cayley_update_descent_identities()),
+    ("cayley_sgd_update", cayley_full_projection, lambda: pins.test_cayley_update_descent_identities()),
+    ("cayley_sgd_update", cayley_symmetric,
+     lambda: pins.test_cayley_update_is_the_cayley_transform_up_to_the_contraction_bound()),
+    ("cayley_sgd_update", cayley_full_step_in_iteration,
+     lambda: pins.test_cayley_update_is_the_cayley_transform_up_to_the_contraction_bound()),
+    ("cayley_sgd_update", cayley_unprojected_momentum, lambda: pins.test_cayley_update_descent_identities()),
 ]
 
 
