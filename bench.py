@@ -37,10 +37,11 @@ PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0
 CLASS_KERNEL = {"gemm_f32": "gemm_f32_kernel", "gemm_bf16": "gemm_bf16_nt_deep_kernel", "whip": "whip_kernel"}
 
 
-def flops_per_step(n: int, T: int, b: int = 1) -> float:
+def flops_per_step(n: int, T: int, b: int = 1, optimizer: str = "sgd") -> float:
     """Dense flop model of one step: two T x n x n products plus (4/3 + 4/3 + 4) n^3 for QR, forming R and
-    the derivative through the QR."""
-    return b * (4.0 * T * n * n + (20.0 / 3.0) * n ** 3)
+    the derivative through the QR; with the Cayley optimiser (Alg. 3) six n x n products instead of the QR side."""
+    side = 12.0 if optimizer == "cayley" else 20.0 / 3.0
+    return b * (4.0 * T * n * n + side * n ** 3)
 
 
 def measured_traffic(cfg_name: str, kernel: str | None):
@@ -106,6 +107,7 @@ def run_config(cfg_name: str, args):
         Xd, Z0 = Xd[0], Z0[0]
     del X, inp
     Zd = Z0.clone()
+    Z_latent = Z0                      # the initial latent, also what the stage timings factor
     loss = torch.zeros(cfg.b, device="cuda")
 
     ctx = B.Context()
@@ -115,7 +117,18 @@ def run_config(cfg_name: str, args):
                   "quant": B.DQ_OBJ_QUANT}
     ctx.dq_set_objective(objectives[args.objective], 4)
 
-    if args.optimizer == "adam":
+    if args.optimizer == "cayley":
+        # Alg. 3 moves the rotation itself: it starts from the rotation of the initial latent
+        Rc = torch.empty_like(Zd)
+        ctx.dq_qr_orth(Z0, Rc)
+        R_start = Rc.clone()
+        Zd = Rc                                   # what the timed loop resets between its phases
+        Z0 = R_start
+        m_state = torch.zeros_like(Rc)
+
+        def step():
+            ctx.dq_cayley_step(Xd, xdt, Rc, m_state, cfg.lr, red, loss, beta=0.9)
+    elif args.optimizer == "adam":
         m_state = torch.zeros_like(Zd)
         v_state = torch.zeros_like(Zd)
         counter = [0]
@@ -181,7 +194,7 @@ def run_config(cfg_name: str, args):
         Yb = torch.empty(Xd.shape, device="cuda")
         dYb = torch.empty(Xd.shape, device="cuda", dtype=torch.bfloat16 if bf16 else torch.float32)
         lossb = torch.zeros(cfg.b, device="cuda")
-        Zs = Z0.clone()
+        Zs = Z_latent.clone()
 
         def tm(f, reps=5):
             f(); f()
@@ -238,7 +251,7 @@ def run_config(cfg_name: str, args):
 
     ms_per_step = dt * 1e3 / args.steps
     n, T, b = cfg.n, cfg.T, cfg.b
-    F = flops_per_step(n, T, b)
+    F = flops_per_step(n, T, b, args.optimizer)
     launches = max(1, dom["launches"])
     raw_ms = dom["ms"] / launches
     avg_ms = max(raw_ms - bracket_ms, 1e-6)
@@ -246,7 +259,7 @@ def run_config(cfg_name: str, args):
     # algorithmic work of the class per step (the model's, not what the launches issue: forming R forward issues
     # 2 n^3 where the model counts 4/3 n^3, the rotation product issues its flops twice for the two planes of R)
     if dominant == B.DQ_K_GEMM_F32:
-        work = b * ((20.0 / 3.0) * n ** 3 + (0.0 if bf16 else 4.0 * T * n * n))
+        work = b * ((12.0 if args.optimizer == "cayley" else 20.0 / 3.0) * n ** 3 + (0.0 if bf16 else 4.0 * T * n * n))
         roof = {"bound": "mfma", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["fp32_mfma_tflops"],
                 "unit": "TFLOP/s"}
     elif dominant == B.DQ_K_GEMM_BF16:
@@ -278,7 +291,7 @@ def run_config(cfg_name: str, args):
         "unit": "steps/s",
         "ms_per_step": ms_per_step,
         "config": {"workload": f"{cfg.name}: n={cfg.n}, T={cfg.T}, b={cfg.b}, X {cfg.x_dtype}, Z fp32, "
-                               f"{'Adam' if args.optimizer == 'adam' else 'SGD'} lr={cfg.lr}"
+                               f"{ {'adam': 'Adam', 'sgd': 'SGD', 'cayley': 'Cayley SGD (Alg. 3) on R, momentum 0.9,'}[args.optimizer]} lr={cfg.lr}"
                                + ("" if args.objective == "whip" else f", objective {args.objective}"),
                    "n": cfg.n, "T": cfg.T, "b": cfg.b},
         "dtype": "bf16 X/R/dY on MFMA with fp32 accumulate; fp32 QR and backward" if bf16 else "f32",
@@ -310,8 +323,10 @@ def main():
     ap.add_argument("--no-stage-roofline", action="store_true",
                     help="skip the separate timing of the stage entry points (used when the run is profiled, so that "
                          "the trace holds calibration steps only)")
-    ap.add_argument("--optimizer", choices=["sgd", "adam"], default="sgd",
-                    help="update rule of the latent: Alg. 1's SGD (the headline metric) or Adam (Sec. 4.3, Table 4)")
+    ap.add_argument("--optimizer", choices=["sgd", "adam", "cayley"], default="sgd",
+                    help="update rule: Alg. 1's SGD on the latent (the headline metric), Adam on the latent (Sec. 4.3, "
+                         "Table 4), or Cayley SGD with momentum on the rotation itself (Alg. 3, the optimiser QR-Orth is "
+                         "compared with in Table 4)")
     ap.add_argument("--objective", choices=["whip", "variance", "kurtosis", "quant"], default="whip",
                     help="what S4 evaluates: Eq. 4 (the headline metric) or one of the objectives the paper compares "
                          "it with (Sec. 5, objective ablation)")

@@ -252,6 +252,25 @@ dq_status dq_calib_step_adam(dq_ctx* ctx, int b, int T, int n,
                              float lr, float beta1, float beta2, float eps,
                              dq_reduce reduce, float* loss_dev, float* R_or_null, long ldr);
 
+/* Alg. 3 (App. B.2), Cayley SGD with momentum: the optimiser the paper compares QR-Orth with (Sec. 5, optimiser
+ * comparison).  It moves the rotation itself along the Cayley transform of a skew-symmetric W instead of
+ * re-parametrising it through a latent.  Per problem, with R the algorithm's X_k, G = dL/dR and M its momentum buffer
+ * (zero before the first update):
+ *   M <- beta M - G;   W^ = M R^T - 1/2 R (R^T M R^T);   W = W^ - W^^T;   M <- W R;
+ *   alpha = min(lr, 2 q / (||W||_F + eps));   Y = R + alpha M;   `iters` times  Y <- R + alpha/2 W (R + Y);   R <- Y.
+ * (The paper's constants: q = 0.5, iters = 2, eps = 1e-8.)  R and M: in/out, b stacked n x n fp32; G: in.
+ * alpha_dev_or_null: out, b DEVICE floats, the step size each problem took.  DQ_ERR_SHAPE for iters outside 0..64,
+ * q <= 0 or eps < 0.  Workspace: dq_workspace_bytes(1, n, 1, ...). */
+dq_status dq_cayley_update(dq_ctx* ctx, int b, int n, float* R, long ldr, const float* G, long ldg,
+                           float* M, long ldm, float lr, float beta, float q, int iters, float eps,
+                           float* alpha_dev_or_null);
+
+/* One calibration step with that optimiser in place of QR-Orth: loss and G = dL/dR at the INPUT rotation (Alg. 1 lines
+ * 8-9, as in dq_rotate_loss_grad), then dq_cayley_update of R.  No latent, no QR.  loss_dev: b DEVICE floats. */
+dq_status dq_cayley_step(dq_ctx* ctx, int b, int T, int n, const void* X, dq_dtype x_dtype, long ldx,
+                         float* R, long ldr, float* M, long ldm, float lr, float beta, float q, int iters,
+                         float eps, dq_reduce reduce, float* loss_dev);
+
 /* The matrix-core GEMMs the path is built from, exported for kernel-level parity tests:
  *   C (M x N, fp32) = alpha * op(A) op(B) + beta * C.
  * f32: A, B fp32; ta != 0 means A is stored K x M, tb != 0 means B is stored N x K.

@@ -52,6 +52,8 @@ SIGNATURES = {
     "dq_sgd_momentum_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _f, _f]),
     "dq_calib_step_adam": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _vp, _l, _vp, _l, _i, _f, _f, _f, _f, _i, _vp,
                                 _vp, _l]),
+    "dq_cayley_update": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l, _f, _f, _f, _i, _f, _vp]),
+    "dq_cayley_step": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _vp, _l, _f, _f, _f, _i, _f, _i, _vp]),
     "dq_gemm_f32": (_i, [_vp, _i, _i, _i, _f, _vp, _l, _i, _vp, _l, _i, _f, _vp, _l]),
     "dq_gemm_bf16": (_i, [_vp, _i, _i, _i, _vp, _l, _i, _vp, _l, _i, _vp, _l]),
     "dq_profile_enable": (_i, [_vp, _c.c_uint]),
@@ -274,6 +276,17 @@ class Context:
         b, n = (Z.shape[0], Z.shape[-1]) if Z.dim() == 3 else (1, Z.shape[-1])
         self._check(self.lib.dq_sgd_update(self.h, b, n, _ptr(Z), _ld(Z), _ptr(dZ), _ld(dZ), float(lr)),
                     "dq_sgd_update")
+
+    def dq_cayley_update(self, R, G, M, lr, beta=0.9, q=0.5, iters=2, eps=1e-8, alpha=None):
+        b, n = (R.shape[0], R.shape[-1]) if R.dim() == 3 else (1, R.shape[-1])
+        self._check(self.lib.dq_cayley_update(self.h, b, n, _ptr(R), _ld(R), _ptr(G), _ld(G), _ptr(M), _ld(M), lr, beta, q,
+                                              iters, eps, _ptr(alpha)), "dq_cayley_update")
+
+    def dq_cayley_step(self, X, x_dtype, R, M, lr, reduce, loss, beta=0.9, q=0.5, iters=2, eps=1e-8):
+        b = X.shape[0] if X.dim() == 3 else 1
+        T, n = X.shape[-2], X.shape[-1]
+        self._check(self.lib.dq_cayley_step(self.h, b, T, n, _ptr(X), x_dtype, _ld(X), _ptr(R), _ld(R), _ptr(M), _ld(M),
+                                            lr, beta, q, iters, eps, reduce, _ptr(loss)), "dq_cayley_step")
 
     def dq_gemm_f32(self, M, N, K, alpha, A, ta, B, tb, beta, C):
         self._check(self.lib.dq_gemm_f32(self.h, M, N, K, float(alpha), _ptr(A), _ld(A), int(ta), _ptr(B), _ld(B),

@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libdartqr.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
 SOURCES = ["dq_api.hip", "gemm_f32.hip", "gemm_bf16.hip", "qr_kernels.hip", "qr_cholpanel.hip", "elementwise.hip",
-           "heads_kernels.hip", "objective_kernels.hip"]
+           "heads_kernels.hip", "objective_kernels.hip", "cayley_kernels.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

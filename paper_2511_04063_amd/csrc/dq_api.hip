@@ -109,7 +109,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
-           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -159,6 +159,7 @@ Layout make_layout(int n, int T) {
     L.dyt = bump(cur, (size_t)round_up(n, 64) * tld * 2);
     L.rbt = bump(cur, (size_t)n * 2 * round_up(n, 32) * 2);
     L.losspart = bump(cur, (size_t)kLossPartials * 8);
+    L.scal = bump(cur, 256);   // device scalars (the step size of the Cayley update)
     L.gsplit_floats = (size_t)kMaxSplit * n2;
     if (L.gsplit_floats > ((size_t)16 << 20)) L.gsplit_floats = (size_t)16 << 20;
     L.gsplit = bump(cur, L.gsplit_floats * 4);
@@ -735,6 +736,72 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
         else { g.C = dZ; g.ldc = lddz; }
         LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, n3, 0.0);
         DQ_HIP(launch_gemm_f32(g, s));
+    }
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- Cayley SGD with momentum (Alg. 3, App. B.2)
+// One update of the rotation R (the algorithm's X_k) from its Euclidean gradient G, in the algorithm's own order:
+//   M <- beta M - G;  W^ = M R^T - 1/2 R (R^T M R^T);  W = W^ - W^^T;  M <- W R;  alpha = min(lr, 2q / (||W||_F + eps));
+//   Y = R + alpha M;  s times: Y <- R + alpha/2 W (R + Y);  R <- Y.
+// Six n x n products on the fp32 matrix cores; the step size stays on the device.
+dq_status cayley_update_one(dq_ctx* c, const Layout& L, int n, float* R, long ldr, const float* G, long ldg, float* M,
+                            long ldm, float lr, float beta, float q, int iters, float eps, float* alpha_out) {
+    hipStream_t s = c->stream;
+    const long ld = L.ld;
+    float* What = at<float>(c, L.B);     // A = M R^T, then W^
+    float* Tmp = at<float>(c, L.P);      // R^T A, later R + Y
+    float* W = at<float>(c, L.M);
+    float* Y0 = at<float>(c, L.U);
+    float* Y1 = at<float>(c, L.A);
+    double* part = at<double>(c, L.losspart);
+    float* scal = at<float>(c, L.scal);
+    const double n3 = (double)n * n * n;
+    auto product = [&](const float* A_, long lda, int ta, const float* B_, long ldb, int tb, float* C_, long ldc,
+                       float alpha, float beta_, const float* alpha_dev) -> dq_status {
+        GemmF32 g;
+        g.A = A_; g.lda = lda; g.ta = ta;
+        g.B = B_; g.ldb = ldb; g.tb = tb;
+        g.C = C_; g.ldc = ldc; g.M = n; g.N = n; g.K = n;
+        g.alpha = alpha; g.beta = beta_; g.alpha_dev = alpha_dev;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+        return DQ_OK;
+    };
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
+        DQ_HIP(launch_cayley_momentum(M, ldm, G, ldg, n, beta, s));
+    }
+    DQ_TRY(product(M, ldm, 0, R, ldr, 1, What, ld, 1.f, 0.f, nullptr));          // A = M R^T
+    DQ_TRY(product(R, ldr, 1, What, ld, 0, Tmp, ld, 1.f, 0.f, nullptr));         // R^T A
+    DQ_TRY(product(R, ldr, 0, Tmp, ld, 0, What, ld, -0.5f, 1.f, nullptr));       // W^ = A - 1/2 R (R^T A)
+    const int blocks = cayley_skew_grid(n);
+    if (blocks > kLossPartials) return DQ_ERR_UNSUPPORTED;
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 3.0 * n * (double)n, 12.0 * n * (double)n);
+        DQ_HIP(launch_cayley_skew(What, ld, n, W, ld, part, s));
+        DQ_HIP(launch_cayley_alpha(part, blocks, lr, q, eps, scal, s));
+    }
+    DQ_TRY(product(W, ld, 0, R, ldr, 0, M, ldm, 1.f, 0.f, nullptr));             // M = W R
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
+        DQ_HIP(launch_add_scaled(Y0, ld, R, ldr, M, ldm, n, 1.f, scal, s));      // Y = R + alpha M
+    }
+    float* Ycur = Y0;
+    float* Ynext = Y1;
+    for (int i = 0; i < iters; ++i) {
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 1.0 * n * (double)n, 20.0 * n * (double)n);
+            DQ_HIP(launch_add_scaled(Tmp, ld, R, ldr, Ycur, ld, n, 1.f, nullptr, s));   // R + Y
+            DQ_HIP(launch_copy2d(R, ldr, Ynext, ld, n, n, s));
+        }
+        DQ_TRY(product(W, ld, 0, Tmp, ld, 0, Ynext, ld, 1.f, 1.f, scal + 1));    // Y <- R + alpha/2 W (R + Y)
+        float* t = Ycur; Ycur = Ynext; Ynext = t;
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
+        DQ_HIP(launch_copy2d(Ycur, ld, R, ldr, n, n, s));
+        if (alpha_out != nullptr) DQ_HIP(launch_copy2d(scal, 4, alpha_out, 4, 1, 1, s));
     }
     return DQ_OK;
 }
@@ -1352,6 +1419,46 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * n * (double)n, 28.0 * n * (double)n);
         DQ_HIP(launch_adam2d(Zi, ldz, dZi, L.ld, m + (long)i * n * ldm, ldm, v + (long)i * n * ldv, ldv, n, lr, beta1,
                              beta2, eps, c1, c2, c->stream));
+    }
+    return DQ_OK;
+}
+
+dq_status dq_cayley_update(dq_ctx* c, int b, int n, float* R, long ldr, const float* G, long ldg, float* M, long ldm,
+                           float lr, float beta, float q, int iters, float eps, float* alpha_dev_or_null) {
+    if (c == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || iters < 0 || iters > 64 || !(q > 0.f) || !(eps >= 0.f)) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    DQ_TRY(check_f32(R, ldr, n));
+    DQ_TRY(check_f32(G, ldg, n));
+    DQ_TRY(check_f32(M, ldm, n));
+    const Layout L = make_layout(n, 1);
+    DQ_TRY(check_ws(c, L));
+    for (int i = 0; i < b; ++i)
+        DQ_TRY(cayley_update_one(c, L, n, R + (long)i * n * ldr, ldr, G + (long)i * n * ldg, ldg, M + (long)i * n * ldm,
+                                 ldm, lr, beta, q, iters, eps, alpha_dev_or_null ? alpha_dev_or_null + i : nullptr));
+    return DQ_OK;
+}
+
+dq_status dq_cayley_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype xdt, long ldx, float* R, long ldr,
+                         float* M, long ldm, float lr, float beta, float q, int iters, float eps, dq_reduce red,
+                         float* loss_dev) {
+    if (c == nullptr || loss_dev == nullptr) return DQ_ERR_NULL;
+    if (b < 0 || T < 1 || iters < 0 || iters > 64 || !(q > 0.f) || !(eps >= 0.f)) return DQ_ERR_SHAPE;
+    DQ_TRY(check_n(n));
+    if (red != DQ_REDUCE_TOKEN_MEAN && red != DQ_REDUCE_SUM) return DQ_ERR_DTYPE;
+    DQ_TRY(check_x(X, xdt, ldx, n));
+    DQ_TRY(check_f32(R, ldr, n));
+    DQ_TRY(check_f32(M, ldm, n));
+    const Layout L = make_layout(n, T);
+    DQ_TRY(check_ws(c, L));
+    const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
+    for (int i = 0; i < b; ++i) {
+        float* Ri = R + (long)i * n * ldr;
+        float* Gi = at<float>(c, L.G);
+        const void* Xi = static_cast<const char*>(X) + (size_t)i * T * ldx * esz;
+        DQ_TRY(rotate_loss_grad_one(c, L, T, n, Xi, xdt, ldx, Ri, ldr, red, loss_dev + i, Gi, L.ld, at<float>(c, L.Y),
+                                    L.ld, at<char>(c, L.dY), L.ld, false));
+        DQ_TRY(cayley_update_one(c, L, n, Ri, ldr, Gi, L.ld, M + (long)i * n * ldm, ldm, lr, beta, q, iters, eps, nullptr));
     }
     return DQ_OK;
 }

@@ -41,6 +41,7 @@ struct GemmF32 {
     int ta = 0;            // A is stored K x M (the product uses its transpose)
     int tb = 0;            // B is stored N x K
     float alpha = 1.f, beta = 0.f;
+    const float* alpha_dev = nullptr;   // non-null: alpha is multiplied by this device scalar
     // A's STORAGE is a block of Householder vectors: entry (r, c) is 0 for r < c, 1 for r == c and the
     // stored value for r > c (the stored upper part belongs to the triangular factor).
     int a_unit_lower = 0;
@@ -158,6 +159,19 @@ hipError_t launch_adam2d(float* Z, long ldz, const float* D, long ldd, float* m,
                          float lr, float beta1, float beta2, float eps, float c1, float c2, hipStream_t s, int rows = -1);
 hipError_t launch_momentum2d(float* Z, long ldz, const float* D, long ldd, float* buf, long ldb, int n, float lr,
                              float mu, hipStream_t s);
+
+// ---- Cayley SGD pieces (Alg. 3, App. B.2) -------------------------------------------
+// M <- beta M - G
+hipError_t launch_cayley_momentum(float* M, long ldm, const float* G, long ldg, int n, float beta, hipStream_t s);
+// W = What - What^T and partials[block] = sum of squares of this block's entries of W (cayley_skew_grid(n) blocks)
+int cayley_skew_grid(int n);
+hipError_t launch_cayley_skew(const float* What, long ldh, int n, float* W, long ldw, double* partials, hipStream_t s);
+// alpha_dev[0] = min(lr, 2 q / (sqrt(sum of the partials) + eps)), alpha_dev[1] = alpha_dev[0] / 2
+hipError_t launch_cayley_alpha(const double* partials, int count, float lr, float q, float eps, float* alpha_dev,
+                               hipStream_t s);
+// out = A + scale * B with scale = scale_host * (scale_dev ? *scale_dev : 1); out may alias A or B
+hipError_t launch_add_scaled(float* out, long ldo, const float* A, long lda, const float* B, long ldb, int n,
+                             float scale_host, const float* scale_dev, hipStream_t s);
 
 // ---- rotate / Whip pieces ---------------------------------------------------------
 // Split R into two bf16 planes and transpose:  RbT[j][k] = hi(R[k][j]),  RbT[j][koff + k] = lo(R[k][j]) with

@@ -219,7 +219,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmF32 g, int tiles_m, i
     }
 
     float* C = g.C + bz * g.batch_c + (long)z * g.split_stride;
-    const float alpha = g.alpha, beta = g.beta;
+    // the scale of the product may also carry a factor that only the device knows (a step size formed by a kernel)
+    const float alpha = g.alpha_dev != nullptr ? g.alpha * *g.alpha_dev : g.alpha, beta = g.beta;
     if (inner) {
         // one base pointer per 32 x 32 block and constant row offsets from it
         float* cb[WT][WT];

@@ -1414,6 +1414,86 @@ def test_hadamard_init_bit_exact(ctx):
 
 
 # ----------------------------------------------------------------------------------- error paths
+# ----------------------------------------------------------------------------------- Cayley SGD (Alg. 3, App. B.2)
+def random_rotation(g, n):
+    Q, Rf = np.linalg.qr(g.standard_normal((n, n)))
+    return (Q * np.sign(np.diag(Rf))[None, :]).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,ld", [(4, 4), (37, 40), (256, 256), (452, 456)])
+@pytest.mark.parametrize("lr,beta,iters", [(1e-3, 0.9, 2), (50.0, 0.0, 2), (5e-2, 0.5, 5), (1e-2, 0.9, 0)])
+def test_cayley_update_against_oracle(ctx, n, ld, lr, beta, iters):
+    """One update of Alg. 3 from given R, G and momentum: the six products and the step-size rule against the oracle
+    (lr = 50 is cut by the 2q / ||W|| rule; iters = 0 leaves the explicit first-order step)."""
+    g = rng(9000 + n + iters)
+    R = random_rotation(g, n)
+    G = (g.standard_normal((n, n)) * 0.3).astype(np.float32)
+    M = (g.standard_normal((n, n)) * 0.1).astype(np.float32)
+    _, Rd = padded(n, n, ld); Rd.copy_(dev(R))
+    _, Gd = padded(n, n, ld); Gd.copy_(dev(G))
+    _, Md = padded(n, n, ld); Md.copy_(dev(M))
+    alpha = torch.zeros(1, device="cuda")
+    ctx.dq_cayley_update(Rd, Gd, Md, lr, beta, 0.5, iters, 1e-8, alpha)
+    Ro, Mo, ao, Wo = orc.cayley_sgd_update(R, G, M, float(np.float32(lr)), float(np.float32(beta)), 0.5, iters, 1e-8)
+    assert alpha.item() == pytest.approx(ao, rel=1e-5)
+    if lr == 50.0:
+        assert ao < lr                 # the step-size rule cut it
+    if lr == 1e-3 and n <= 256:
+        assert ao == pytest.approx(lr, rel=1e-6)
+    assert rel(Rd.cpu().numpy(), Ro) < 1e-5
+    assert rel(Md.cpu().numpy(), Mo) < 1e-5
+    # R moved by alpha W R to first order: the comparison above is not dominated by the unchanged part of R
+    assert rel(Rd.cpu().numpy().astype(np.float64) - R, Ro - R) < 1e-3
+    assert ctx.dq_device_flags() == 0
+
+
+def test_cayley_steps_against_oracle(ctx):
+    """Five consecutive calibration steps with the optimiser of Alg. 3 (fp32 X, rotation and momentum carried on the
+    device): losses and the final rotation against the oracle's own five steps."""
+    cfg = synth.scaled_config("tiny", n=96, T=320)
+    inp = synth.make_inputs(cfg, seed=23)
+    X = inp["X"][0]
+    g = rng(9100)
+    R0 = random_rotation(g, 96)
+    Xd, Rd = dev(X), dev(R0.copy())
+    Md = torch.zeros((96, 96), device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    Ro, Mo = R0.astype(np.float64), np.zeros((96, 96))
+    for k in range(5):
+        ctx.dq_cayley_step(Xd, B.DQ_F32, Rd, Md, 0.05, B.DQ_REDUCE_TOKEN_MEAN, loss, beta=0.9)
+        out = orc.cayley_step(X, Ro, Mo, float(np.float32(0.05)), float(np.float32(0.9)))
+        Ro, Mo = out["R_new"], out["M_new"]
+        assert abs(loss.item() - out["loss"]) <= 1e-4 * out["loss"]
+    R = Rd.cpu().numpy().astype(np.float64)
+    assert rel(R, Ro) < 1e-4
+    assert rel(R - R0, Ro - R0) < 1e-2                       # the displacement itself
+    assert rel(Md.cpu().numpy(), Mo) < 1e-3
+    assert np.abs(R.T @ R - np.eye(96)).max() < 1e-2         # the two-pass iteration leaves the manifold slowly
+    assert ctx.dq_device_flags() == 0
+
+
+def test_cayley_step_bf16_and_batch(ctx):
+    """bf16 activations and two stacked problems: each equals its own single-problem call, and the loss is that of
+    the input rotation."""
+    cfg = synth.scaled_config("7b", n=256, T=512, b=2)
+    inp = synth.make_inputs(cfg, seed=24)
+    X = inp["X"]
+    g = rng(9200)
+    R0 = np.stack([random_rotation(g, 256) for _ in range(2)])
+    Xd, Rd = dev(X, torch.bfloat16), dev(R0.copy())
+    Md = torch.zeros((2, 256, 256), device="cuda")
+    loss = torch.zeros(2, device="cuda")
+    ctx.dq_cayley_step(Xd, B.DQ_BF16, Rd, Md, 0.02, B.DQ_REDUCE_TOKEN_MEAN, loss, beta=0.9)
+    for i in range(2):
+        out = orc.cayley_step(X[i], R0[i], np.zeros((256, 256)), float(np.float32(0.02)), float(np.float32(0.9)))
+        assert abs(loss[i].item() - out["loss"]) <= 1e-4 * out["loss"]
+        assert rel(Rd[i].cpu().numpy(), out["R_new"]) < 1e-4
+        assert rel(Md[i].cpu().numpy(), out["M_new"]) < 2e-2      # G from bf16 X, R and dY on the matrix cores
+        R1, M1, l1 = dev(R0[i].copy()), torch.zeros((256, 256), device="cuda"), torch.zeros(1, device="cuda")
+        ctx.dq_cayley_step(Xd[i], B.DQ_BF16, R1, M1, 0.02, B.DQ_REDUCE_TOKEN_MEAN, l1, beta=0.9)
+        assert torch.equal(R1, Rd[i]) and torch.equal(M1, Md[i]) and l1.item() == loss[i].item()
+
+
 def test_errors_have_no_effect(ctx):
     n = 64
     Z = torch.randn(n, n, device="cuda")
