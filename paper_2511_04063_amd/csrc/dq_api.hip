@@ -586,7 +586,7 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         // A caller that needs neither Y nor dY gets Eq. 4 and its derivative applied to the accumulators: Y is never
         // written and dY leaves the kernel already transposed for S5.
         fused = use_fused && !keep_y_dy && g_transposed && gemm_bf16_deep_fits(g) && c->objective == DQ_OBJ_WHIP &&
-                (T / 128) * (n / 128) <= kLossPartials;
+                gemm_bf16_whip_partials(g) <= kLossPartials;
         if (fused) {
             g.C = nullptr;
             g.whip_dyt = at<bf16_t>(c, L.dyt); g.whip_ldt = T; g.whip_scale = scale; g.whip_partials = lpart;
@@ -597,7 +597,7 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
         }
         if (fused) {
             LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-            DQ_HIP(launch_loss_finish(lpart, (T / 128) * (n / 128), scale, loss_dev, flags, s));
+            DQ_HIP(launch_loss_finish(lpart, gemm_bf16_whip_partials(g), scale, loss_dev, flags, s));
         }
     } else {
         GemmF32 g;

@@ -72,12 +72,13 @@ struct GemmBf16 {
     // Used for X @ (R_hi + R_lo) with one pass over the accumulators.  Not combined with split-K.
     int a_kwrap = 0; int a_klim = 0;
     // whip_dyt != null: fused Whip epilogue (Eq. 4): dY^T (N x M bf16, leading dimension whip_ldt) and one partial sum
-    // of exp(-|y|) per workgroup (M/128 * N/128 doubles) are produced from the accumulators; C may then be null.
-    // Only for shapes gemm_bf16_deep_fits() accepts.
+    // of exp(-|y|) per workgroup (gemm_bf16_whip_partials() doubles) are produced from the accumulators; C may then be
+    // null.  Only for shapes gemm_bf16_deep_fits() accepts.
     bf16_t* whip_dyt = nullptr; long whip_ldt = 0; float whip_scale = 0.f; double* whip_partials = nullptr;
 };
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
-bool gemm_bf16_deep_fits(const GemmBf16& g);   // large round NT product: the unguarded deep-prefetch kernel applies
+bool gemm_bf16_deep_fits(const GemmBf16& g);   // large round NT product: the unguarded deep-prefetch kernels apply
+int gemm_bf16_whip_partials(const GemmBf16& g);   // workgroups (= partial sums) of the fused-epilogue launch for such a shape
 
 // out (rows x cols, ldo) = alpha * sum_z part[z] + beta * out
 hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,

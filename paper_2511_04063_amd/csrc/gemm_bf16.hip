@@ -14,6 +14,8 @@
 // only the m / n / D mappings matter for correctness.
 #include <stdlib.h>
 
+#include <utility>
+
 #include "dq_internal.h"
 
 namespace dq {
@@ -398,7 +400,261 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_deep_kernel(GemmBf16 g, int 
     }
 }
 
+
+// ---- the same products on 256 x 256 x 64 tiles ------------------------------------------------------------------
+// One workgroup of 4 wavefronts per compute unit, each wavefront a 128 x 128 block (4 x 4 MFMA tiles: 256 accumulator
+// registers, half as many LDS reads per MFMA as the 64 x 64 blocks above and half the operand traffic out of L2 per
+// flop, which is what bounds the 128 x 128 kernel).  With one wavefront per SIMD nothing else hides latencies, so the
+// K step is written out as 64 "slots", one MFMA each, and every memory operation is given its slot by hand (a
+// scheduling barrier after each slot keeps the compiler from regrouping them; without the barriers the same code runs
+// 15 % slower):
+//   * the fragments of reduction sub-step s + 1 are read from LDS in the first 8 slots of sub-step s (the last
+//     sub-step reads the first fragments of the NEXT tile from the other LDS buffer);
+//   * the 16 staged 16-byte pieces per thread of the next tile go to the other LDS buffer in slots 0, 3, .., 45, and
+//     each staging register is reloaded with its piece of the tile two steps further in slot 4 p + 3: two K steps of
+//     global loads are always in flight (about 3 us at the rate reached);
+//   * one barrier per K step, before its last sub-step: by then every wavefront has read the last fragments of the
+//     current buffer and written its pieces of the next one.
+// Shapes: M, N multiples of 256, K of 128, the other conditions of the kernel above.
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int TLD = TK + 8;                         // LDS row stride in halfwords (144 bytes)
+constexpr int kBigAbuf = TM * TLD, kBigBbase = 2 * TM * TLD, kBigBbuf = TN * TLD;   // halfword offsets in LDS
+
+struct BigAcc { f32x16 t[4][4]; };
+// Register sets with named members and compile-time selectors: arrays indexed inside loops that are only unrolled
+// later in the compilation end up in scratch memory.
+struct BigFrags { bf16x8 a0, a1, a2, a3, b0, b1, b2, b3; };
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // a native vector: copies are typed loads / stores
+struct BigStage { u32x4 r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11, r12, r13, r14, r15; };   // pieces 0..7 of the A tile, 8..15 of the B tile
+template <int I, class F> __device__ __forceinline__ auto& frag_a(F& f) {
+    if constexpr (I == 0) return f.a0; else if constexpr (I == 1) return f.a1; else if constexpr (I == 2) return f.a2; else return f.a3;
+}
+template <int I, class F> __device__ __forceinline__ auto& frag_b(F& f) {
+    if constexpr (I == 0) return f.b0; else if constexpr (I == 1) return f.b1; else if constexpr (I == 2) return f.b2; else return f.b3;
+}
+template <int P> __device__ __forceinline__ u32x4& piece(BigStage& s) {
+    if constexpr (P == 0) return s.r0; else if constexpr (P == 1) return s.r1; else if constexpr (P == 2) return s.r2;
+    else if constexpr (P == 3) return s.r3; else if constexpr (P == 4) return s.r4; else if constexpr (P == 5) return s.r5;
+    else if constexpr (P == 6) return s.r6; else if constexpr (P == 7) return s.r7; else if constexpr (P == 8) return s.r8;
+    else if constexpr (P == 9) return s.r9; else if constexpr (P == 10) return s.r10; else if constexpr (P == 11) return s.r11;
+    else if constexpr (P == 12) return s.r12; else if constexpr (P == 13) return s.r13; else if constexpr (P == 14) return s.r14;
+    else return s.r15;
+}
+struct BigAddr {
+    const bf16_t* pa; const bf16_t* pb;             // this thread's first piece of the tile being fetched
+    long sa, sb;                                    // 32 rows further
+    int aoff, boff;                                 // halfword offsets of this lane's fragment rows in an operand buffer
+    int sto;                                        // halfword offset of this thread's first piece in an operand buffer
+};
+
+template <int KS, int BUF, int Q>
+__device__ __forceinline__ void big_slot(BigAcc& acc, const BigFrags& cur, BigFrags& nxt, BigStage& st, const BigAddr& ad,
+                                         bf16_t* smem) {
+    constexpr int i = Q >> 2, j = (i & 1) ? 3 - (Q & 3) : (Q & 3);
+    acc.t[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_a<i>(cur), frag_b<j>(cur), acc.t[i][j], 0, 0, 0);
+    constexpr int RB = (KS == 3) ? 1 - BUF : BUF;        // buffer and k offset of the fragments read now
+    constexpr int RK = (KS == 3) ? 0 : (KS + 1) * 16;
+    if constexpr (Q < 4)
+        frag_a<Q>(nxt) = *reinterpret_cast<const bf16x8*>(smem + RB * kBigAbuf + ad.aoff + Q * 32 * TLD + RK);
+    else if constexpr (Q < 8)
+        frag_b<Q - 4>(nxt) = *reinterpret_cast<const bf16x8*>(smem + kBigBbase + RB * kBigBbuf + ad.boff + (Q - 4) * 32 * TLD + RK);
+    constexpr int S = KS * 16 + Q;                       // slot number inside the K step
+    if constexpr (S % 3 == 0 && S / 3 < 16) {
+        constexpr int P = S / 3;
+        if constexpr (P < 8)
+            *reinterpret_cast<u32x4*>(smem + (1 - BUF) * kBigAbuf + ad.sto + P * 32 * TLD) = piece<P>(st);
+        else
+            *reinterpret_cast<u32x4*>(smem + kBigBbase + (1 - BUF) * kBigBbuf + ad.sto + (P - 8) * 32 * TLD) = piece<P>(st);
+    }
+    if constexpr (S % 4 == 3) {
+        constexpr int P = S / 4;
+        if constexpr (P < 8) piece<P>(st) = *reinterpret_cast<const u32x4*>(ad.pa + P * ad.sa);
+        else piece<P>(st) = *reinterpret_cast<const u32x4*>(ad.pb + (P - 8) * ad.sb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// all 16 pieces of the tile at ad.pa / ad.pb into st
+template <int... P>
+__device__ __forceinline__ void big_fetch(BigStage& st, const BigAddr& ad, std::integer_sequence<int, P...>) {
+    ((piece<P>(st) = *reinterpret_cast<const u32x4*>(P < 8 ? ad.pa + P * ad.sa : ad.pb + (P - 8) * ad.sb)), ...);
+}
+// st into LDS buffer 0
+template <int... P>
+__device__ __forceinline__ void big_stash0(BigStage& st, const BigAddr& ad, bf16_t* smem, std::integer_sequence<int, P...>) {
+    ((*reinterpret_cast<u32x4*>(smem + (P < 8 ? 0 : kBigBbase) + ad.sto + (P & 7) * 32 * TLD) = piece<P>(st)), ...);
+}
+// the first fragments of the tile in LDS buffer 0
+template <int... Q>
+__device__ __forceinline__ void big_first_frags(BigFrags& f, const BigAddr& ad, const bf16_t* smem, std::integer_sequence<int, Q...>) {
+    ((frag_a<Q>(f) = *reinterpret_cast<const bf16x8*>(smem + ad.aoff + Q * 32 * TLD)), ...);
+    ((frag_b<Q>(f) = *reinterpret_cast<const bf16x8*>(smem + kBigBbase + ad.boff + Q * 32 * TLD)), ...);
+}
+
+template <int KS, int BUF, int... Q>
+__device__ __forceinline__ void big_substep(BigAcc& acc, const BigFrags& cur, BigFrags& nxt, BigStage& st,
+                                            const BigAddr& ad, bf16_t* smem, std::integer_sequence<int, Q...>) {
+    (big_slot<KS, BUF, Q>(acc, cur, nxt, st, ad, smem), ...);
+}
+
+// One K step on the tile in LDS buffer BUF (its first fragments in f0): stashes `st` (the next tile) into the other
+// buffer, reloads `st` from ad.pa / ad.pb, and leaves the first fragments of the next tile in f0.
+template <int BUF>
+__device__ __forceinline__ void big_kstep(BigAcc& acc, BigFrags& f0, BigFrags& f1, BigStage& st, const BigAddr& ad,
+                                          bf16_t* smem) {
+    using Seq = std::make_integer_sequence<int, 16>;
+    big_substep<0, BUF>(acc, f0, f1, st, ad, smem, Seq{});
+    big_substep<1, BUF>(acc, f1, f0, st, ad, smem, Seq{});
+    big_substep<2, BUF>(acc, f0, f1, st, ad, smem, Seq{});
+    __syncthreads();
+    big_substep<3, BUF>(acc, f1, f0, st, ad, smem, Seq{});
+}
+
+template <bool WHIP>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, int tiles_m, int tiles_n) {
+    __shared__ __attribute__((aligned(16))) bf16_t smem[2 * TM * TLD + 2 * TN * TLD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // XCD-aware tile order (see gemm_f32.hip): the 32 workgroups resident on an XCD form an 8 x 4 block of tiles
+    const int nt = tiles_m * tiles_n;
+    const int bid = blockIdx.x;
+    const int q8 = nt >> 3, r8 = nt & 7;
+    const int xcd = bid & 7;
+    const int pid = xcd * q8 + (xcd < r8 ? xcd : r8) + (bid >> 3);
+    const int group = 8 * tiles_n;
+    const int gid = pid / group;
+    const int first_m = gid * 8;
+    const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
+    const int pid_m = first_m + (pid % group) % gsz;
+    const int pid_n = (pid % group) / gsz;
+    const int m0 = pid_m * TM, n0 = pid_n * TN;
+
+    const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+    const int lrow = lane & 31, lk = lane >> 5;
+    // thread t moves the 16-byte piece (row t / 8 + 32 i, k-offset 8 (t % 8)) of each operand tile, i = 0 .. 7
+    const int prow = tid >> 3, pk = (tid & 7) << 3;
+    const bf16_t* pa = g.A + (long)(m0 + prow) * g.lda + pk;
+    const bf16_t* pb = g.B + (long)(n0 + prow) * g.ldb + pk;
+    const int wrap = g.a_kwrap;
+    const int nk = g.K / TK;           // even, >= 2
+
+    BigAddr ad;
+    ad.sa = 32 * g.lda; ad.sb = 32 * g.ldb;
+    ad.aoff = (wm + lrow) * TLD + lk * 8; ad.boff = (wn + lrow) * TLD + lk * 8;
+    ad.sto = prow * TLD + pk;
+    // tile t (clamped to the last one: past the end a valid tile is fetched again and never used)
+    auto point_at = [&](int t) {
+        const int tc = t < nk ? t : nk - 1;
+        const int k0 = tc * TK;
+        ad.pa = pa + ((wrap > 0 && k0 >= wrap) ? k0 - wrap : k0);
+        ad.pb = pb + k0;
+    };
+
+    BigAcc acc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc.t[i][j][v] = 0.f;
+
+    BigStage s0, s1;
+    BigFrags f0, f1;
+    using Seq16 = std::make_integer_sequence<int, 16>;
+    point_at(0);
+    big_fetch(s0, ad, Seq16{});
+    point_at(1);
+    big_fetch(s1, ad, Seq16{});
+    big_stash0(s0, ad, smem, Seq16{});
+    point_at(2);
+    big_fetch(s0, ad, Seq16{});
+    __syncthreads();
+    big_first_frags(f0, ad, smem, std::make_integer_sequence<int, 4>{});
+    // at the top of a trip: tile kt in LDS buffer 0 with its first fragments in f0, tile kt + 1 in s1, tile kt + 2 in s0
+    for (int kt = 0; kt < nk; kt += 2) {
+        point_at(kt + 3);
+        big_kstep<0>(acc, f0, f1, s1, ad, smem);
+        point_at(kt + 4);
+        big_kstep<1>(acc, f0, f1, s0, ad, smem);
+    }
+
+    float* C = g.C;
+    if (!WHIP || C != nullptr) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                    C[(long)row * g.ldc + col] = acc.t[i][j][v];
+                }
+            }
+        }
+    }
+    if constexpr (WHIP) {
+        // as in the 128 x 128 kernel: dY leaves transposed, every row of 256 tokens as one 512-byte run
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        constexpr int SLD = TM + 8;          // halfwords per staged row (528 bytes)
+        static_assert(TN * SLD <= 2 * TM * TLD + 2 * TN * TLD, "the staged tile must fit the operand buffers");
+        __syncthreads();                     // the last K step read fragments after its barrier
+        bf16_t* stage = smem;                // [TN][SLD]
+        const float scale = g.whip_scale;
+        float lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = wn + j * 32 + lrow;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int r0 = wm + i * 32 + 8 * q4 + 4 * lk;
+                    float d[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float y = acc.t[i][j][4 * q4 + q];
+                        const float ex = __expf(-fabsf(y));
+                        lsum += ex;
+                        const float sg = (y > 0.f) ? -scale : ((y < 0.f) ? scale : 0.f);
+                        d[q] = sg * ex;
+                    }
+                    const f32x2 d01 = {d[0], d[1]}, d23 = {d[2], d[3]};
+                    const bf16x2 b01 = __builtin_convertvector(d01, bf16x2), b23 = __builtin_convertvector(d23, bf16x2);
+                    *reinterpret_cast<uint2*>(stage + c * SLD + r0) =
+                        make_uint2(__builtin_bit_cast(uint32_t, b01), __builtin_bit_cast(uint32_t, b23));
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int pass = 0; pass < TN / 8; ++pass) {
+            const int row = pass * 8 + (tid >> 5), piece = (tid & 31) * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + row * SLD + piece);
+            *reinterpret_cast<uint4*>(g.whip_dyt + (long)(n0 + row) * g.whip_ldt + m0 + piece) = v;
+        }
+        __shared__ float wsum[4];
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) lsum += __shfl_xor(lsum, o);
+        if (lane == 0) wsum[wave] = lsum;
+        __syncthreads();
+        if (tid == 0)
+            g.whip_partials[bid] = (double)wsum[0] + (double)wsum[1] + (double)wsum[2] + (double)wsum[3];
+    }
+}
+
 }  // namespace
+
+// The 256 x 256 kernel needs enough tiles to give every compute unit one.
+static bool gemm_bf16_big_fits(const GemmBf16& g) {
+    return gemm_bf16_deep_fits(g) && g.M % TM == 0 && g.N % TN == 0 && (g.M / TM) * (g.N / TN) >= 192;
+}
+
+int gemm_bf16_whip_partials(const GemmBf16& g) {
+    if (gemm_bf16_big_fits(g)) return (g.M / TM) * (g.N / TN);
+    return (g.M / BM) * (g.N / BN);
+}
 
 bool gemm_bf16_deep_fits(const GemmBf16& g) {
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -415,12 +671,22 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
     const int bvec = ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0) ? 1 : 0;
     // big NT products without split-K and with round sizes: the unguarded kernel with the deep prefetch
     const bool fits = gemm_bf16_deep_fits(g);
+    const bool big = gemm_bf16_big_fits(g);
     if (g.whip_dyt != nullptr) {   // the fused epilogue exists in the unguarded kernel only: the caller checks first
         if (!fits || g.whip_partials == nullptr || (g.whip_ldt & 7) != 0 || g.whip_ldt < g.M ||
             (reinterpret_cast<uintptr_t>(g.whip_dyt) & 15) != 0)
             return hipErrorInvalidValue;
-        hipLaunchKernelGGL((gemm_bf16_nt_deep_kernel<true>), dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m,
-                           tiles_n);
+        if (big)
+            hipLaunchKernelGGL((gemm_bf16_nt_big_kernel<true>), dim3((g.M / TM) * (g.N / TN)), dim3(256), 0, s, g,
+                               g.M / TM, g.N / TN);
+        else
+            hipLaunchKernelGGL((gemm_bf16_nt_deep_kernel<true>), dim3(tiles_m * tiles_n), dim3(256), 0, s, g, tiles_m,
+                               tiles_n);
+        return hipGetLastError();
+    }
+    if (big) {
+        hipLaunchKernelGGL((gemm_bf16_nt_big_kernel<false>), dim3((g.M / TM) * (g.N / TN)), dim3(256), 0, s, g, g.M / TM,
+                           g.N / TN);
         return hipGetLastError();
     }
     if (fits) {
