@@ -153,6 +153,47 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(unsigned* p, long count, 
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < count; e += (long)gridDim.x * 256) p[e] = v;
 }
 
+// The same with 16-byte accesses (n, leading dimensions multiples of 4, 16-byte aligned bases): a workgroup owns a strip
+// of 1024 columns for kSignRows rows; a thread reads the four diagonal entries that give its column signs once (the only
+// scattered loads), the row sign is uniform.  Pieces of A wholly below the diagonal are not read.
+constexpr int kSignRows = 32;
+__global__ __launch_bounds__(256) void sign_normalise_vec_kernel(const float* __restrict__ Afac, long lda, int n,
+                                                                 float* __restrict__ R, long ldr, float* __restrict__ U,
+                                                                 long ldu, unsigned* flags) {
+    const int c = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (c >= n) return;
+    const int r0 = blockIdx.y * kSignRows;
+    const int r1 = (r0 + kSignRows < n) ? r0 + kSignRows : n;
+    float sc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float d = Afac[(long)(c + q) * lda + c + q];
+        sc[q] = d >= 0.f ? 1.f : -1.f;
+        if (blockIdx.y == 0) {
+            if (!(fabsf(d) <= 3.0e38f)) atomicOr(flags, DQ_FLAG_NONFINITE);
+            else if (d == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
+        }
+    }
+    for (int r = r0; r < r1; ++r) {
+        float4* rp = reinterpret_cast<float4*>(R + (long)r * ldr + c);
+        float4 v = *rp;
+        v.x *= sc[0]; v.y *= sc[1]; v.z *= sc[2]; v.w *= sc[3];
+        *rp = v;
+        if (U != nullptr) {
+            float4 u = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c + 3 >= r) {
+                const float sr = Afac[(long)r * lda + r] >= 0.f ? 1.f : -1.f;
+                const float4 a = *reinterpret_cast<const float4*>(Afac + (long)r * lda + c);
+                u.x = c >= r ? sr * a.x : 0.f;
+                u.y = c + 1 >= r ? sr * a.y : 0.f;
+                u.z = c + 2 >= r ? sr * a.z : 0.f;
+                u.w = c + 3 >= r ? sr * a.w : 0.f;
+            }
+            *reinterpret_cast<float4*>(U + (long)r * ldu + c) = u;
+        }
+    }
+}
+
 // s_j = +1 if Afac[j][j] >= 0 else -1;  R[:, j] *= s_j;  U[i][j] = s_i * Afac[i][j] for j >= i, else 0.
 __global__ __launch_bounds__(256) void sign_normalise_kernel(const float* __restrict__ Afac, long lda, int n,
                                                              float* __restrict__ R, long ldr, float* __restrict__ U,
@@ -248,6 +289,12 @@ hipError_t launch_fill_u32(unsigned* p, long count, unsigned v, hipStream_t s) {
 
 hipError_t launch_sign_normalise(const float* Afac, long lda, int n, float* R, long ldr, float* U, long ldu,
                                  unsigned* flags, hipStream_t s) {
+    auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+    if (n % 4 == 0 && lda % 4 == 0 && ldr % 4 == 0 && (U == nullptr || ldu % 4 == 0) && a16(Afac) && a16(R) && a16(U)) {
+        const dim3 grid((n + 1023) / 1024, (n + kSignRows - 1) / kSignRows);
+        hipLaunchKernelGGL(sign_normalise_vec_kernel, grid, dim3(256), 0, s, Afac, lda, n, R, ldr, U, ldu, flags);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(sign_normalise_kernel, dim3(grid_for((long)n * n)), dim3(256), 0, s, Afac, lda, n, R, ldr, U,
                        ldu, flags);
     return hipGetLastError();
