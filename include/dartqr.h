@@ -78,6 +78,8 @@ typedef enum { DQ_OBJ_WHIP = 0, DQ_OBJ_VARIANCE = 1, DQ_OBJ_KURTOSIS = 2, DQ_OBJ
                                    many-CU panel route and was factored by the one-workgroup Householder kernel
                                    instead; results are valid */
 #define DQ_FLAG_BAD_INDEX  8u   /* dq_gather_rows met an index outside [0, T_all): that row was not written  */
+#define DQ_FLAG_SYNC_TIMEOUT 16u /* a device-side wait between the library's streams (DQ_OPT_DEVICE_SYNC) ran into its
+                                   time limit: the results of that call are invalid */
 
 /* ---- context and workspace ---------------------------------------------------------- */
 
@@ -111,9 +113,23 @@ typedef enum {
                                        (CholeskyQR2 + Householder reconstruction); 0: never, default 64 */
     DQ_OPT_SINGLE_STREAM = 2,       /* non-zero: every piece of the QR on the context's stream, no overlap (default 0) */
     DQ_OPT_FUSED_WHIP = 3,          /* zero: Eq. 4 always as a pass of its own, never in the epilogue of X @ R (default 1) */
-    DQ_OPT_HEADS_BATCHED = 4        /* zero: 128 x 128 problems take the general route one by one (default 1) */
+    DQ_OPT_HEADS_BATCHED = 4,       /* zero: 128 x 128 problems take the general route one by one (default 1) */
+    DQ_OPT_DEVICE_SYNC = 5          /* how the pieces of the QR on the library's streams wait for each other.  0: HIP
+                                       events.  1 (default): through a word in device memory that the producing stream
+                                       sets and the consuming stream polls (a cross-stream wait on an event that is still
+                                       pending costs the host 10-20 us here, several per panel), IF a probe at the first
+                                       call on a stream shows that the streams involved make progress independently
+                                       (they do unless they share a hardware queue); otherwise events.  Every poll is
+                                       bounded (DQ_FLAG_SYNC_TIMEOUT). */
 } dq_option;
 dq_status dq_set_option(dq_ctx* ctx, dq_option option, int value);
+
+/* The probe behind DQ_OPT_DEVICE_SYNC on two streams of the caller's choosing (hipStream_t, null = default stream):
+ * enqueues a wait on `consumer_stream` that polls a word of the workspace for at most 2 ms, THEN a kernel on
+ * `producer_stream` that sets the word, and waits on the host for both streams.  *usable = 1 if the wait saw the word,
+ * 0 if it ran into its limit (the streams share a hardware queue, or are the same stream); the status word is not
+ * touched.  Needs a workspace.  Host-synchronous; for diagnosis and tests. */
+dq_status dq_stream_handover_probe(dq_ctx* ctx, void* consumer_stream, void* producer_stream, int* usable);
 
 /* Waits for the stream, copies the device status word to *host_out and clears it on the device. */
 dq_status dq_device_flags(dq_ctx* ctx, unsigned* host_out);

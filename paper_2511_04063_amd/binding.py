@@ -18,9 +18,9 @@ DQ_ERR_NULL, DQ_ERR_SHAPE, DQ_ERR_DTYPE, DQ_ERR_ALIGN, DQ_ERR_WORKSPACE, DQ_ERR_
 DQ_F32, DQ_BF16 = 0, 1
 DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
 DQ_OBJ_WHIP, DQ_OBJ_VARIANCE, DQ_OBJ_KURTOSIS, DQ_OBJ_QUANT = 0, 1, 2, 3
-DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX = 1, 2, 4, 8
+DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX, DQ_FLAG_SYNC_TIMEOUT = 1, 2, 4, 8, 16
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
-DQ_OPT_ACCUM_PANELS, DQ_OPT_TALL_PANEL_MIN_ROWS, DQ_OPT_SINGLE_STREAM, DQ_OPT_FUSED_WHIP, DQ_OPT_HEADS_BATCHED = range(5)
+DQ_OPT_ACCUM_PANELS, DQ_OPT_TALL_PANEL_MIN_ROWS, DQ_OPT_SINGLE_STREAM, DQ_OPT_FUSED_WHIP, DQ_OPT_HEADS_BATCHED, DQ_OPT_DEVICE_SYNC = range(6)
 DQ_MAX_N = 8192
 
 _c = ctypes
@@ -35,6 +35,7 @@ SIGNATURES = {
     "dq_status_string": (_c.c_char_p, [_i]),
     "dq_device_flags": (_i, [_vp, _c.POINTER(_c.c_uint)]),
     "dq_set_option": (_i, [_vp, _i, _i]),
+    "dq_stream_handover_probe": (_i, [_vp, _vp, _vp, _c.POINTER(_i)]),
     "dq_qr_orth": (_i, [_vp, _i, _i, _vp, _l, _vp, _l, _vp, _l]),
     "dq_rotate_loss_grad": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _i, _vp, _vp, _l, _vp, _l, _vp, _l]),
     "dq_calib_step": (_i, [_vp, _i, _i, _i, _vp, _i, _l, _vp, _l, _f, _i, _vp, _vp, _l]),
@@ -177,6 +178,14 @@ class Context:
 
     def dq_set_option(self, option, value):
         self._check(self.lib.dq_set_option(self.h, option, value), "dq_set_option")
+
+    def dq_stream_handover_probe(self, consumer_stream, producer_stream) -> bool:
+        """Streams are raw hipStream_t handles (ints; 0 = the default stream)."""
+        out = ctypes.c_int(-1)
+        self._check(self.lib.dq_stream_handover_probe(self.h, ctypes.c_void_p(consumer_stream),
+                                                      ctypes.c_void_p(producer_stream), ctypes.byref(out)),
+                    "dq_stream_handover_probe")
+        return bool(out.value)
 
     def dq_device_flags(self) -> int:
         out = ctypes.c_uint(0)

@@ -96,6 +96,10 @@ struct dq_ctx {
                                      // 4 from there on, each measured best there; 1: panel by panel)
     bool fused_whip = true;          // Eq. 4 in the epilogue of the rotation product where the shape allows
     bool heads_batched = true;       // n == 128: all problems of a batch in the same launches
+    bool device_sync = true;         // the QR's streams hand over through a device word where a probe allows (else events)
+    unsigned long long seq = 0;      // last value handed out for the hand-over words, which only grow
+    struct Probed { hipStream_t s; bool ok; };
+    std::vector<Probed> probed;      // per caller stream: do it and the two internal streams progress independently?
     int objective = DQ_OBJ_WHIP;     // what S4 evaluates (dq_set_objective)
     int quant_bits = 4;
     char* ws = nullptr;
@@ -431,6 +435,56 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
     return DQ_OK;
 }
 
+// ---------------------------------------------------------------- hand-over between the QR's streams
+// Four 8-byte words behind the status word, cleared with it: [0] panels factored, [1] trailing updates done,
+// [2] the probe's word, [3] set by a probe wait that gave up.
+constexpr long kSyncLimitUs = 5L * 1000 * 1000;   // a hand-over that takes this long is a fault, not a delay
+constexpr long kProbeLimitUs = 2000;
+unsigned long long* sync_words(dq_ctx* c) { return reinterpret_cast<unsigned long long*>(c->ws + 128); }
+
+// Device-side hand-over needs the consumer's wait kernel and the producer's signal kernel to run at the same time.
+// Streams that share a hardware queue cannot (the wait would sit in front of the signal), and inside a stream
+// capture the order of execution is not ours: both cases take the event route.  Probed once per caller stream: a
+// bounded wait on each consuming stream, the signal on its producer enqueued AFTER it.
+// Is a bounded wait enqueued on `consumer` released by a signal enqueued AFTER it on `producer`?  Both streams are idle
+// when this returns.
+hipError_t handover_probe(dq_ctx* c, hipStream_t consumer, hipStream_t producer, bool* usable) {
+    unsigned long long* w = sync_words(c);
+    const unsigned long long v = ++c->seq;
+    hipError_t e;
+    if ((e = launch_stream_wait(w + 2, v, kProbeLimitUs, nullptr, w + 3, consumer)) != hipSuccess) return e;
+    if ((e = launch_stream_signal(w + 2, v, producer)) != hipSuccess) return e;
+    if ((e = hipStreamSynchronize(consumer)) != hipSuccess) return e;
+    if ((e = hipStreamSynchronize(producer)) != hipSuccess) return e;
+    unsigned long long gave_up = 1;
+    if ((e = hipMemcpy(&gave_up, w + 3, sizeof(gave_up), hipMemcpyDeviceToHost)) != hipSuccess) return e;
+    *usable = gave_up == 0;
+    if (gave_up != 0) {
+        if ((e = launch_fill_u32(reinterpret_cast<unsigned*>(w + 3), 2, 0u, consumer)) != hipSuccess) return e;
+        if ((e = hipStreamSynchronize(consumer)) != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+bool device_sync_usable(dq_ctx* c) {
+    if (!c->device_sync || c->single_stream) return false;
+    for (const dq_ctx::Probed& pr : c->probed)
+        if (pr.s == c->stream) return pr.ok;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(c->stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return false;
+    }
+    bool ok = hipStreamSynchronize(c->stream) == hipSuccess;   // the probe must not sit behind the caller's backlog
+    hipStream_t pairs[3][2] = {{c->stream2, c->stream}, {c->stream3, c->stream}, {c->stream, c->stream2}};   // {consumer, producer}
+    for (int i = 0; i < 3 && ok; ++i) {
+        bool usable = false;
+        ok = handover_probe(c, pairs[i][0], pairs[i][1], &usable) == hipSuccess && usable;
+    }
+    c->probed.push_back({c->stream, ok});
+    return ok;
+}
+
 dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ldz, float* R, long ldr, float* U,
                       long ldu) {
     hipStream_t sA = c->stream, sB = c->single_stream ? c->stream : c->stream2,
@@ -445,6 +499,24 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     const ReflBufs bufA{at<float>(c, L.wpart), at<float>(c, L.w2)};
     const ReflBufs bufB{at<float>(c, L.wpartB), at<float>(c, L.w2B)};
     const long ld = L.ld;
+    // how the streams wait for each other: a device word (see device_sync_usable) or events
+    const bool dsync = device_sync_usable(c);
+    unsigned long long* words = sync_words(c);
+    const unsigned long long seq0 = c->seq;
+    auto panel_done = [&](int p) -> hipError_t {            // on sA: panel p is factored
+        return dsync ? launch_stream_signal(words, seq0 + p + 1, sA) : hipEventRecord(c->sync_ev[2 * p], sA);
+    };
+    auto after_panel = [&](hipStream_t s, int p) -> hipError_t {   // s goes on once panel p is factored
+        return dsync ? launch_stream_wait(words, seq0 + p + 1, kSyncLimitUs, flags, nullptr, s)
+                     : hipStreamWaitEvent(s, c->sync_ev[2 * p], 0);
+    };
+    auto trailing_done = [&](int p) -> hipError_t {         // on sB: the trailing update of panel p has run
+        return dsync ? launch_stream_signal(words + 1, seq0 + p + 1, sB) : hipEventRecord(c->sync_ev[2 * p + 1], sB);
+    };
+    auto after_trailing = [&](int p) -> hipError_t {        // sA goes on once the trailing update of panel p has run
+        return dsync ? launch_stream_wait(words + 1, seq0 + p + 1, kSyncLimitUs, flags, nullptr, sA)
+                     : hipStreamWaitEvent(sA, c->sync_ev[2 * p + 1], 0);
+    };
     {
         LaunchScope sc(&c->prof, sA, DQ_K_SMALL, 0.0, 8.0 * n * (double)n);
         DQ_HIP(launch_copy2d(Z, ldz, A, ld, n, n, sA));
@@ -455,6 +527,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     // stream; the rest of the trailing matrix goes to the second stream.
     const int nb = kPanel;
     const int npanels = (n + nb - 1) / nb;
+    c->seq += npanels + 1;
     int last_trailing = -1;
     bool gram_ready = false;   // the Gram partials of the coming panel were left by the previous panel's look-ahead
     for (int p = 0; p < npanels; ++p) {
@@ -469,6 +542,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         // reflectors, T and Yp = V T.  The other panels: the one-workgroup Householder panel kernel, then T from the
         // Gram matrix of the reflectors.
         const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
+        bool signalled = false;   // "panel p is factored" already goes out from inside the panel's kernels
         if (tall) {
             // the look-ahead update of the next panel's columns is fused into the last two kernels of the route when
             // that panel is a full one; they also leave the Gram partials the next tall panel starts from
@@ -481,11 +555,24 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
                 DQ_HIP(launch_cholqr_factor(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags,
                                             gram_ready ? 1 : 0, sA));
             }
-            // the look-ahead columns received update p-1 on the second stream
-            if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+            // the look-ahead columns received update p-1 on the second stream.  With the device-side hand-over and the
+            // fused look-ahead, the wait sits at the start of the kernel that first reads those columns and the signal
+            // "panel p is factored" at the start of the kernel after it: no launch of their own on the critical path.
+            HandOver ho;
+            signalled = dsync && fused_la;
+            if (signalled) {
+                if (last_trailing >= 0) {
+                    ho.wait_word = words + 1; ho.wait_value = seq0 + last_trailing + 1;
+                    ho.limit_us = kSyncLimitUs; ho.flags = flags;
+                }
+                ho.signal_word = words; ho.signal_value = seq0 + p + 1;
+            } else if (last_trailing >= 0) {
+                DQ_HIP(after_trailing(last_trailing));
+            }
             {
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 4.0 * m * (double)jb * nla, 0.0);
-                DQ_HIP(launch_cholqr_finish(Ap, ld, m, Yp, vs, at<float>(c, L.cq), fused_la ? 1 : 0, next_tall ? 1 : 0, sA));
+                DQ_HIP(launch_cholqr_finish(Ap, ld, m, Yp, vs, at<float>(c, L.cq), fused_la ? 1 : 0, next_tall ? 1 : 0, sA,
+                                            signalled ? &ho : nullptr));
             }
             gram_ready = next_tall;
             if (!fused_la && nla > 0) {   // C_la -= V (Yp^T C_la)
@@ -500,7 +587,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
                 DQ_HIP(launch_qr_panel(Ap, ld, m, jb, tau + k0, vs, tsl, &sw, flags, sA));
             }
-            if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+            if (last_trailing >= 0) DQ_HIP(after_trailing(last_trailing));
             // partials of V^T [V | C_la]; summed inside the T-factor kernel, which also returns W2 = T^T V^T C_la
             const float* Wa = nullptr;
             int splitsA = 1;
@@ -522,13 +609,13 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
             DQ_TRY(refl_make_y(c, sA, Ap, ld, m, jb, Tp, 0, Yp));
         }
         const int rest = m - jb - nla;
-        DQ_HIP(hipEventRecord(c->sync_ev[2 * p], sA));
+        if (!signalled) DQ_HIP(panel_done(p));
         if (rest > 0) {   // C -= V (Yp^T C) for the rest of the trailing matrix, behind the next panel
-            DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[2 * p], 0));
+            DQ_HIP(after_panel(sB, p));
             const float* Wb = nullptr;
             DQ_TRY(refl_project(c, sB, L, bufB, Yp, kPanel, m, jb, Ap + jb + nla, ld, rest, 0, &Wb, kMaxSplit, nullptr, 0));
             DQ_TRY(refl_update(c, sB, L, Ap, ld, Wb, m, jb, Ap + jb + nla, ld, rest));
-            DQ_HIP(hipEventRecord(c->sync_ev[2 * p + 1], sB));
+            DQ_HIP(trailing_done(p));
             last_trailing = p;
         }
         // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
@@ -537,14 +624,14 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         const int ap = c->accum_panels > 0 ? c->accum_panels : (n >= 8192 ? 4 : 2);
         if ((p + 1) % ap == 0 || p == npanels - 1) {
             const int q0 = (p / ap) * ap;
-            DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[2 * p], 0));
+            DQ_HIP(after_panel(sC, p));
             if (p - q0 + 1 == 1)
                 DQ_TRY(accumulate_q(c, sC, L, n, k0, m, jb, Ap, ld, Yp, R, ldr));
             else
                 DQ_TRY(accumulate_q_block(c, sC, L, n, nb, q0, p - q0 + 1, A, ld, yall, R, ldr));
         }
     }
-    if (last_trailing >= 0) DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev[2 * last_trailing + 1], 0));
+    if (last_trailing >= 0) DQ_HIP(after_trailing(last_trailing));
     DQ_HIP(hipEventRecord(c->sync_ev.back(), sC));
     DQ_HIP(hipStreamWaitEvent(sA, c->sync_ev.back(), 0));
     {
@@ -1252,9 +1339,19 @@ dq_status dq_set_option(dq_ctx* c, dq_option option, int value) {
             return DQ_OK;
         case DQ_OPT_SINGLE_STREAM: c->single_stream = value != 0; return DQ_OK;
         case DQ_OPT_FUSED_WHIP: c->fused_whip = value != 0; return DQ_OK;
+        case DQ_OPT_DEVICE_SYNC: c->device_sync = value != 0; return DQ_OK;
         case DQ_OPT_HEADS_BATCHED: c->heads_batched = value != 0; return DQ_OK;
     }
     return DQ_ERR_DTYPE;
+}
+
+dq_status dq_stream_handover_probe(dq_ctx* c, void* consumer_stream, void* producer_stream, int* usable) {
+    if (c == nullptr || usable == nullptr) return DQ_ERR_NULL;
+    if (c->ws == nullptr) return DQ_ERR_WORKSPACE;
+    bool ok = false;
+    DQ_HIP(handover_probe(c, static_cast<hipStream_t>(consumer_stream), static_cast<hipStream_t>(producer_stream), &ok));
+    *usable = ok ? 1 : 0;
+    return DQ_OK;
 }
 
 dq_status dq_qr_backward(dq_ctx* c, int b, int n, const float* R, long ldr, const float* U, long ldu, const float* G,

@@ -84,6 +84,42 @@ int gemm_bf16_whip_partials(const GemmBf16& g);   // workgroups (= partial sums)
 hipError_t launch_splitk_reduce(const float* part, int splits, long stride, long ldp, int rows, int cols,
                                 float alpha, float beta, float* out, long ldo, hipStream_t s);
 
+// ---- ordering between streams by a device word ------------------------------------------
+// The producing stream stores a growing value into the word after its work (a kernel of its own, or the first
+// instructions of a kernel that follows that work in the same stream); the consuming stream polls the word (a kernel of
+// its own in front of its work, or the first instructions of every workgroup of the consuming kernel).  Agent-scope
+// release / acquire, so that what the producer wrote is read fresh.  Every poll is bounded by the device's constant-rate
+// clock (100 MHz): past the limit it raises DQ_FLAG_SYNC_TIMEOUT and goes on, so every wavefront ends whatever the
+// other stream does; once the bit is up, later polls return at once.
+struct HandOver {
+    const unsigned long long* wait_word = nullptr; unsigned long long wait_value = 0; long limit_us = 0;
+    unsigned* flags = nullptr;
+    unsigned long long* signal_word = nullptr; unsigned long long signal_value = 0;
+};
+__device__ __forceinline__ void handover_signal(unsigned long long* word, unsigned long long value) {
+    __hip_atomic_store(word, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+// returns false if it gave up; one thread calls it
+__device__ __forceinline__ bool handover_wait(const unsigned long long* word, unsigned long long value, long long limit_ticks,
+                                              unsigned* flags) {
+    if (flags != nullptr && (__hip_atomic_load(flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & DQ_FLAG_SYNC_TIMEOUT))
+        return false;
+    const long long t0 = wall_clock64();
+    for (;;) {
+        if (__hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= value) return true;
+        if (wall_clock64() - t0 > limit_ticks) break;
+        __builtin_amdgcn_s_sleep(4);
+    }
+    if (flags != nullptr) atomicOr(flags, DQ_FLAG_SYNC_TIMEOUT);
+    return false;
+}
+// *word = value once everything enqueued before on s has run
+hipError_t launch_stream_signal(unsigned long long* word, unsigned long long value, hipStream_t s);
+// what is enqueued after on s runs once *word >= value; gives up after limit_us (then DQ_FLAG_SYNC_TIMEOUT is or-ed
+// into *flags and 1 stored to *timed_out, either may be null)
+hipError_t launch_stream_wait(const unsigned long long* word, unsigned long long value, long limit_us, unsigned* flags,
+                              unsigned long long* timed_out, hipStream_t s);
+
 // ---- QR pieces --------------------------------------------------------------------
 // Factor the m x jb panel at A (row-major, lda) in place: reflectors below the diagonal (unit diagonal
 // implied), triangular factor on and above it; tau[0..jb).  vscratch: >= panel_scratch_floats(m) floats.
@@ -108,8 +144,11 @@ size_t cholpanel_scratch_floats();
 bool cholpanel_supported(const float* A, long lda, int m, int jb);
 hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch,
                                 float* tau, float* tslices, unsigned* status, int have_gram, hipStream_t s);
+// ho (may be null; only with lookahead != 0): the kernel that first reads the look-ahead columns polls ho->wait_word
+// in every workgroup before it does (wait_word == null: no wait), and the kernel after it stores ho->signal_value to
+// ho->signal_word when it starts, i.e. once the reflectors and Yp are complete (signal_word == null: no signal).
 hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1, float* scratch, int lookahead,
-                                int next_gram, hipStream_t s);
+                                int next_gram, hipStream_t s, const HandOver* ho = nullptr);
 
 // T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the split-K
 // partials of V^T [V | C] (gpart[z] at stride, leading dimension ldp: jb Gram columns, then nla columns of V^T C).

@@ -420,6 +420,16 @@ __global__ __launch_bounds__(256) void momentum2d_kernel(float* __restrict__ Z, 
     }
 }
 
+// ------------------------------------------------------------------------------------------------ stream hand-over
+// (see HandOver in dq_internal.h)
+__global__ void signal_kernel(unsigned long long* word, unsigned long long value) { handover_signal(word, value); }
+
+__global__ void wait_kernel(const unsigned long long* word, unsigned long long value, long long limit_ticks,
+                            unsigned* flags, unsigned long long* timed_out) {
+    if (!handover_wait(word, value, limit_ticks, flags) && timed_out != nullptr)
+        __hip_atomic_store(timed_out, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace
 
 int whip_grid(long rows, int cols) {
@@ -549,6 +559,17 @@ hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, fl
     long b = ((long)n * n + 255) / 256;
     if (b > 8192) b = 8192;
     hipLaunchKernelGGL(axpy2d_kernel, dim3((unsigned)b), dim3(256), 0, s, Z, ldz, D, ldd, n, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_signal(unsigned long long* word, unsigned long long value, hipStream_t s) {
+    hipLaunchKernelGGL(signal_kernel, dim3(1), dim3(1), 0, s, word, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_wait(const unsigned long long* word, unsigned long long value, long limit_us, unsigned* flags,
+                              unsigned long long* timed_out, hipStream_t s) {
+    hipLaunchKernelGGL(wait_kernel, dim3(1), dim3(1), 0, s, word, value, (long long)limit_us * 100, flags, timed_out);
     return hipGetLastError();
 }
 

@@ -232,10 +232,14 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
                                                            const float* __restrict__ Mm, const float* __restrict__ Mm2,
                                                            float* A, long lda, float* Yp,
                                                            const unsigned* __restrict__ fb, int tpw,
-                                                           float* __restrict__ wpart) {
+                                                           float* __restrict__ wpart, HandOver ho) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     __shared__ float Cs[RT * LS];
+    if (ho.wait_word != nullptr) {   // the look-ahead columns must have received the previous trailing update
+        if (threadIdx.x == 0) (void)handover_wait(ho.wait_word, ho.wait_value, (long long)ho.limit_us * 100, ho.flags);
+        __syncthreads();
+    }
     __shared__ __attribute__((aligned(16))) float Ms[B64 * B64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
@@ -301,8 +305,10 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
 // of the updated rows >= 64, which are the next panel: its factorisation then starts from them.
 __global__ __launch_bounds__(NTHR) void la_update_gram_kernel(float* A, long lda, int m,
                                                               const float* __restrict__ wpart, int nproj, int tpw,
-                                                              float* __restrict__ part_next) {
+                                                              float* __restrict__ part_next, HandOver ho) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
+    // the kernel before this one completed the panel's reflectors and Yp: the other streams may go on
+    if (ho.signal_word != nullptr && blockIdx.x == 0 && threadIdx.x == 0) handover_signal(ho.signal_word, ho.signal_value);
     __shared__ float Xs[RT * LS];
     __shared__ float Ws[B64 * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -833,9 +839,10 @@ hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Y
 }
 
 hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1, float* scratch, int lookahead,
-                                int next_gram, hipStream_t s) {
+                                int next_gram, hipStream_t s, const HandOver* ho) {
     const TallScratch ts(scratch);
     if (!lookahead) {
+        if (ho != nullptr) return hipErrorInvalidValue;
         const int below = (m - B64 + RT - 1) / RT;   // a square last panel has no rows below its top block
         if (below > 0)
             hipLaunchKernelGGL(ts_mul_kernel, dim3(below), dim3(NTHR), 0, s, q1, m, B64, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb);
@@ -844,10 +851,11 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
     // the rows below the top block are split exactly as the next panel (m - 64 rows) splits its own rows
     int tpw, nparts;
     tall_split(m - B64, tpw, nparts);
+    const HandOver h = ho != nullptr ? *ho : HandOver();
     hipLaunchKernelGGL(ts_mul_proj_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, q1, m, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb,
-                       tpw, ts.wpart);
+                       tpw, ts.wpart, h);
     hipLaunchKernelGGL(la_update_gram_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, A, lda, m, ts.wpart, nparts + 1, tpw,
-                       next_gram ? ts.part : static_cast<float*>(nullptr));
+                       next_gram ? ts.part : static_cast<float*>(nullptr), h);
     return hipGetLastError();
 }
 

@@ -6,6 +6,8 @@ same seeded inputs.  Tolerances (norm-wise relative error unless stated):
 import json
 import os
 
+import time
+
 import numpy as np
 import pytest
 
@@ -528,6 +530,63 @@ def test_qr_orth_under_other_settings(n, merged, single):
     assert rel(R.astype(np.float64) @ U, Z) < 1e-5
     assert rel(U, Uo) < 1e-4
     assert rel(R, Ro) < max(1e-4, 2e-7 * np.linalg.cond(Z.astype(np.float64)))
+
+
+@pytest.mark.parametrize("n", [450, 1030])
+def test_qr_orth_hand_over_by_events_and_by_device_word(n):
+    """The pieces of the QR on the library's streams wait for each other either through HIP events or through a word in
+    device memory (DQ_OPT_DEVICE_SYNC): the same kernels in the same order, so the same bits; repeated calls (the word
+    keeps growing from call to call) and a read of the status word in between (which clears the word)."""
+    Z = rng(4300 + n).standard_normal((n, n)).astype(np.float32)
+    out = {}
+    for mode in (0, 1):
+        c = B.Context()
+        c.ensure_workspace(1, n, 64, B.DQ_F32)
+        try:
+            c.dq_set_option(B.DQ_OPT_DEVICE_SYNC, mode)
+            got = []
+            for rep in range(3):
+                got.append(run_qr(c, Z))
+                if rep == 1:
+                    assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            for R, U in got[1:]:
+                assert np.array_equal(R, got[0][0]) and np.array_equal(U, got[0][1])
+            out[mode] = got[0]
+        finally:
+            torch.cuda.synchronize()
+            c.close()
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    Ro, Uo = orc.qr_orth(Z)
+    assert rel(out[1][1], Uo) < 1e-4
+    assert rel(out[1][0], Ro) < max(1e-4, 2e-7 * np.linalg.cond(Z.astype(np.float64)))
+
+
+def test_stream_hand_over_probe_is_bounded():
+    """A device-side wait is bounded: enqueued IN FRONT of its own signal on one stream it can never be released, gives
+    up after its 2 ms, reports 'not usable' and leaves the status word alone.  Between two streams of their own the
+    signal normally gets through (printed, not asserted: it depends on the hardware queues the runtime hands out)."""
+    c = B.Context()
+    c.ensure_workspace(1, 64, 64, B.DQ_F32)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        t0 = time.perf_counter()
+        assert c.dq_stream_handover_probe(s1.cuda_stream, s1.cuda_stream) is False
+        dt = time.perf_counter() - t0
+        assert dt < 1.0, f"the bounded wait took {dt:.3f} s"
+        assert c.dq_device_flags() == 0
+        print("hand-over between two streams usable:", c.dq_stream_handover_probe(s1.cuda_stream, s2.cuda_stream),
+              c.dq_stream_handover_probe(s2.cuda_stream, s1.cuda_stream), flush=True)
+        assert c.dq_device_flags() == 0
+        # and the library still works after a probe that gave up
+        Z = rng(4400).standard_normal((200, 200)).astype(np.float32)
+        c.ensure_workspace(1, 200, 64, B.DQ_F32)
+        R, U = run_qr(c, Z)
+        assert np.abs(R.astype(np.float64).T @ R - np.eye(200)).max() <= 1e-5
+        assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+    finally:
+        torch.cuda.synchronize()
+        c.close()
 
 
 @pytest.fixture(scope="module")
