@@ -522,6 +522,13 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         DQ_HIP(launch_copy2d(Z, ldz, A, ld, n, n, sA));
         DQ_HIP(launch_set_identity(R, ldr, n, sA));
     }
+    if (dsync) {
+        // The polls are bounded, and bounded for THIS call's work: the internal streams only begin to poll once the
+        // caller's stream has reached this call, however much the caller had enqueued in front of it.
+        DQ_HIP(hipEventRecord(c->sync_ev[0], sA));
+        DQ_HIP(hipStreamWaitEvent(sB, c->sync_ev[0], 0));
+        DQ_HIP(hipStreamWaitEvent(sC, c->sync_ev[0], 0));
+    }
     // S1.  Panel p is factored on the caller's stream while the trailing update of panel p-1 still runs on the
     // second stream: after panel p only the columns of panel p+1 ("look-ahead" part) are updated on the caller's
     // stream; the rest of the trailing matrix goes to the second stream.
