@@ -536,7 +536,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     const int npanels = (n + nb - 1) / nb;
     c->seq += npanels + 1;
     int last_trailing = -1;
-    bool gram_ready = false;   // the Gram partials of the coming panel were left by the previous panel's look-ahead
+    bool gram_ready = false;   // the first small step of the coming panel (chol of its Gram matrix) was done beside the previous panel's look-ahead
     for (int p = 0; p < npanels; ++p) {
         const int k0 = p * nb;
         const int jb = (n - k0) < nb ? (n - k0) : nb;
@@ -552,7 +552,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         bool signalled = false;   // "panel p is factored" already goes out from inside the panel's kernels
         if (tall) {
             // the look-ahead update of the next panel's columns is fused into the last two kernels of the route when
-            // that panel is a full one; they also leave the Gram partials the next tall panel starts from
+            // that panel is a full one; they also leave the Cholesky factor of the Gram matrix the next tall panel starts from
             const int m2 = m - jb;
             const bool fused_la = nla == kPanel;
             const bool next_tall = fused_la && m2 >= c->chol_min_m &&

@@ -14,6 +14,9 @@
 // workgroups; the 64 x 64 work (sums of partials, Cholesky, LU, triangular inverses, small products) runs in
 // one workgroup out of LDS.  Besides V, T and the triangular factor the route also returns Yp = V T (m x 64), the
 // operand the trailing updates and the accumulation of the orthogonal factor multiply with.
+// Between consecutive tall panels the first small step (Gram matrix, Cholesky, inverse) is taken off the chain of
+// dependent kernels: it runs in one extra workgroup of the kernel that applies the previous panel's reflector to the
+// panel's columns, from the Gram matrix of those columns BEFORE the update (see la_update_chol_kernel).
 // When the check in step 1 fails (ill-conditioned or rank-deficient panel) the same one-workgroup kernel factors
 // the untouched panel with the Householder panel code instead and builds T and Yp itself (slow, rare), so the
 // launch sequence never depends on the data.
@@ -232,7 +235,8 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
                                                            const float* __restrict__ Mm, const float* __restrict__ Mm2,
                                                            float* A, long lda, float* Yp,
                                                            const unsigned* __restrict__ fb, int tpw,
-                                                           float* __restrict__ wpart, HandOver ho) {
+                                                           float* __restrict__ wpart, float* __restrict__ gpart,
+                                                           float* __restrict__ ctop, HandOver ho) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     __shared__ float Xs[RT * LS];
     __shared__ float Cs[RT * LS];
@@ -246,11 +250,20 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
     const int qi = wave >> 1, qj = wave & 1;
     const float* C = A + B64;
     f32x16 acc = zero16();
+    f32x16 accg = zero16();          // gpart != null: C_rows^T C_rows of the look-ahead columns as they are BEFORE the update
     if (blockIdx.x == 0) {
         load_tile(Yp, B64, 0, B64, Xs, tid);
         load_tile(C, lda, 0, B64, Cs, tid);
         __syncthreads();
         proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+        if (gpart != nullptr) {
+            gram_tile(Cs, accg, qi, qj, lrow, lk);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int e = tid + NTHR * q;
+                ctop[e] = Cs[(e >> 6) * LS + (e & 63)];
+            }
+        }
     } else {
         const bool fell_back = *fb != 0u;
         for (int t = 0; t < tpw; ++t) {
@@ -295,100 +308,11 @@ __global__ __launch_bounds__(NTHR) void ts_mul_proj_kernel(const float* __restri
             load_tile(C, lda, row0, m, Cs, tid);
             __syncthreads();
             proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+            if (gpart != nullptr) gram_tile(Cs, accg, qi, qj, lrow, lk);
         }
     }
     store_partial(wpart + (long)blockIdx.x * B64 * B64, acc, qi, qj, lrow, lk);
-}
-
-// Second half of the look-ahead update:  W2 = sum of the nproj partials,  C -= V W2  for C = A[:, 64:128] (same row
-// split as ts_mul_proj_kernel) and, when part_next != null, the Gram partials  part_next[b - 1] = C_rows^T C_rows
-// of the updated rows >= 64, which are the next panel: its factorisation then starts from them.
-__global__ __launch_bounds__(NTHR) void la_update_gram_kernel(float* A, long lda, int m,
-                                                              const float* __restrict__ wpart, int nproj, int tpw,
-                                                              float* __restrict__ part_next, HandOver ho) {
-    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
-    // the kernel before this one completed the panel's reflectors and Yp: the other streams may go on
-    if (ho.signal_word != nullptr && blockIdx.x == 0 && threadIdx.x == 0) handover_signal(ho.signal_word, ho.signal_value);
-    __shared__ float Xs[RT * LS];
-    __shared__ float Ws[B64 * LS];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lrow = lane & 31, lk = lane >> 5;
-    const int qi = wave >> 1, qj = wave & 1;
-    {   // W2: 4 sixteen-byte pieces per thread, partials in groups of 8 (all loads of a group in flight)
-        float4 s4[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) s4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int z0 = 0; z0 < nproj; z0 += 8) {
-            float4 t[4][8];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int z = 0; z < 8; ++z)
-                    t[q][z] = (z0 + z < nproj)
-                                  ? *reinterpret_cast<const float4*>(wpart + (long)(z0 + z) * B64 * B64 + 4 * (tid + NTHR * q))
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int z = 0; z < 8; ++z) {
-                    s4[q].x += t[q][z].x; s4[q].y += t[q][z].y; s4[q].z += t[q][z].z; s4[q].w += t[q][z].w;
-                }
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = 4 * (tid + NTHR * q);
-            float* d = Ws + (e >> 6) * LS + (e & 63);
-            d[0] = s4[q].x; d[1] = s4[q].y; d[2] = s4[q].z; d[3] = s4[q].w;
-        }
-    }
-    float* C = A + B64;
-    if (blockIdx.x == 0) {
-        load_tile(A, lda, 0, B64, Xs, tid);
-        __syncthreads();
-        mask_unit_lower(Xs, tid);
-        __syncthreads();
-        f32x16 q0 = zero16(), q1 = zero16();
-        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
-            if (r < B64) {
-                C[(long)r * lda + lrow] -= q0[v];
-                C[(long)r * lda + 32 + lrow] -= q1[v];
-            }
-        }
-        return;
-    }
-    f32x16 acc = zero16();
-    for (int t = 0; t < tpw; ++t) {
-        const int row0 = B64 + ((blockIdx.x - 1) * tpw + t) * RT;
-        if (row0 >= m) break;
-        if (t > 0) __syncthreads();
-        load_tile(A, lda, row0, m, Xs, tid);
-        __syncthreads();
-        f32x16 q0 = zero16(), q1 = zero16();
-        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
-        // each wavefront only read its own 32 rows of the tile: it replaces them by the updated rows of C
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
-            const int r = row0 + rl;
-            float c0 = 0.f, c1 = 0.f;
-            if (r < m) {
-                c0 = C[(long)r * lda + lrow] - q0[v];
-                c1 = C[(long)r * lda + 32 + lrow] - q1[v];
-                C[(long)r * lda + lrow] = c0;
-                C[(long)r * lda + 32 + lrow] = c1;
-            }
-            Xs[rl * LS + lrow] = c0;
-            Xs[rl * LS + 32 + lrow] = c1;
-        }
-        if (part_next != nullptr) {
-            __syncthreads();
-            gram_tile(Xs, acc, qi, qj, lrow, lk);
-        }
-    }
-    if (part_next != nullptr) store_partial(part_next + (long)(blockIdx.x - 1) * B64 * B64, acc, qi, qj, lrow, lk);
+    if (gpart != nullptr) store_partial(gpart + (long)blockIdx.x * B64 * B64, accg, qi, qj, lrow, lk);
 }
 
 // ------------------------------------------------------------------------------------------------------------
@@ -396,22 +320,23 @@ __global__ __launch_bounds__(NTHR) void la_update_gram_kernel(float* A, long lda
 // barrier and must be called by all threads.
 
 // Bm = sum of nparts (<= kCholMaxParts) partials of a symmetric 64 x 64 matrix (contiguous, 4096 floats each);
-// called by NSUM threads.  Only the quadrants on and above the diagonal are read (the lower-left 32 x 32 quadrant
+// called by NS threads, ZB partials in flight per thread and 16-byte piece (FULL: all four quadrants are read).  Only the quadrants on and above the diagonal are read (the lower-left 32 x 32 quadrant
 // of Bm is set to zero): nothing downstream reads below the diagonal.  All loads of a thread are issued before
 // the first add: a single workgroup is bound by latency here, not by bandwidth.
+template <int NS = NSUM, int ZB = 16, bool FULL = false>
 __device__ __forceinline__ void sum_partials(const float* __restrict__ part, int nparts, float* Bm, int tid) {
-    constexpr int PER = B64 * B64 / 4 / NSUM;              // 16-byte pieces per thread
+    constexpr int PER = B64 * B64 / 4 / NS;              // 16-byte pieces per thread
     float4 s[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int z0 = 0; z0 < nparts; z0 += 16) {
-        float4 t[PER][16];
+    for (int z0 = 0; z0 < nparts; z0 += ZB) {
+        float4 t[PER][ZB];
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const int e = 4 * (tid + NSUM * q);
-            const bool used = !((e >> 6) >= 32 && (e & 63) < 32);
+            const int e = 4 * (tid + NS * q);
+            const bool used = FULL || !((e >> 6) >= 32 && (e & 63) < 32);
 #pragma unroll
-            for (int z = 0; z < 16; ++z)
+            for (int z = 0; z < ZB; ++z)
                 t[q][z] = (used && z0 + z < nparts)
                               ? *reinterpret_cast<const float4*>(part + (long)(z0 + z) * B64 * B64 + e)
                               : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -419,13 +344,13 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ part, int
 #pragma unroll
         for (int q = 0; q < PER; ++q)
 #pragma unroll
-            for (int z = 0; z < 16; ++z) {
+            for (int z = 0; z < ZB; ++z) {
                 s[q].x += t[q][z].x; s[q].y += t[q][z].y; s[q].z += t[q][z].z; s[q].w += t[q][z].w;
             }
     }
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-        const int e = 4 * (tid + NSUM * q);
+        const int e = 4 * (tid + NS * q);
         float* d = Bm + (e >> 6) * LS + (e & 63);
         d[0] = s[q].x; d[1] = s[q].y; d[2] = s[q].z; d[3] = s[q].w;
     }
@@ -554,6 +479,139 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
         __syncthreads();
         rank8_update<false>(W, k0, k0 + 8, (tid >> 7) & 1, (tid >> 6) & 1, tid & 31, (tid >> 5) & 1);
         __syncthreads();
+    }
+}
+
+// Second half of the look-ahead update:  W2 = sum of the nproj partials,  C -= V W2  for C = A[:, 64:128] (same row
+// split as ts_mul_proj_kernel: workgroups 0 .. nproj - 1).
+// gpart != null: one more workgroup (index nproj) runs BESIDE them and does the first small step of the NEXT panel
+// (rows >= 64 of the updated C), so that this step is off the chain of dependent kernels.  It needs the Gram matrix of
+// rows that the other workgroups are still updating; the block reflector H = I - V T V^T is orthogonal, so over all m
+// rows  C'^T C' = C^T C  for C' = H^T C, and the rows >= 64 of C' have
+//     G = C^T C - C'_top^T C'_top,   C'_top = C_top - V_top W2  (the first 64 rows),
+// with C^T C summed from the partials that ts_mul_proj_kernel formed from the columns BEFORE the update (gpart, nproj
+// of them) and C_top as it saved it (ctop).  Then U1 = chol(G) and its inverse, as chol_inv_kernel.  The difference
+// between G and the Gram matrix of the stored rows is of the order of the rounding of H (1e-7 relative), like the
+// rounding of a directly summed Gram matrix; what CholeskyQR needs from G is checked after its first pass as before.
+template <int NT>
+__global__ __launch_bounds__(NT) void la_update_chol_kernel(float* A, long lda, int m,
+                                                              const float* __restrict__ wpart, int nproj, int tpw,
+                                                              const float* __restrict__ gpart,
+                                                              const float* __restrict__ ctop, float* __restrict__ U1,
+                                                              float* __restrict__ U1inv, HandOver ho) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
+    // the kernel before this one completed the panel's reflectors and Yp: the other streams may go on
+    if (ho.signal_word != nullptr && blockIdx.x == 0 && threadIdx.x == 0) handover_signal(ho.signal_word, ho.signal_value);
+    __shared__ float Xs[RT * LS];
+    __shared__ float Ws[B64 * LS];
+    __shared__ float Gs[B64 * LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = (wave >> 1) & 1, qj = wave & 1;
+    // launched with NT >= NTHR threads for the sake of the extra workgroup's sums; the updating workgroups use NTHR of them
+    const bool extra = gpart != nullptr && (int)blockIdx.x == nproj;
+    if (!extra && tid >= NTHR) return;
+    if (!extra) {   // W2: 4 sixteen-byte pieces per thread, partials in groups of 8 (all loads of a group in flight)
+        float4 s4[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int z0 = 0; z0 < nproj; z0 += 8) {
+            float4 t[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+                    t[q][z] = (z0 + z < nproj)
+                                  ? *reinterpret_cast<const float4*>(wpart + (long)(z0 + z) * B64 * B64 + 4 * (tid + NTHR * q))
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int z = 0; z < 8; ++z) {
+                    s4[q].x += t[q][z].x; s4[q].y += t[q][z].y; s4[q].z += t[q][z].z; s4[q].w += t[q][z].w;
+                }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = 4 * (tid + NTHR * q);
+            float* d = Ws + (e >> 6) * LS + (e & 63);
+            d[0] = s4[q].x; d[1] = s4[q].y; d[2] = s4[q].z; d[3] = s4[q].w;
+        }
+    }
+    float* C = A + B64;
+    if (extra) {
+        // ---- the next panel's U1 = chol(G), U1^-1
+        float* S0 = Xs;               // V_top
+        float* S1 = Xs + B64 * LS;    // C_top, then C'_top
+        // both sums with all NSUM threads (each ends with a barrier): W2 (summed in another order than the updating
+        // workgroups sum it, which moves G by rounding only) and C^T C over all rows (upper quadrants)
+        sum_partials<NT, NT == NTHR ? 8 : 16, true>(wpart, nproj, Ws, tid);
+        sum_partials<NT, NT == NTHR ? 8 : 16>(gpart, nproj, Gs, tid);
+        if (tid >= NTHR) return;
+        load_tile(A, lda, 0, B64, Xs, tid);       // rows 0..63 = top block of the panel (rows 64.. of the tile: zero)
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            S1[(e >> 6) * LS + (e & 63)] = ctop[e];
+        }
+        const f32x16 vw = lds_mma<2>(S0, Ws, nullptr, qi, qj, 0, B64, lrow, lk);   // V_top (unit lower) W2
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) S1[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + 32 * qj + lrow] -= vw[v];
+        __syncthreads();
+        if (qi <= qj) {
+            f32x16 gt = zero16();                 // (C'_top^T C'_top)[32 qi + ., 32 qj + .]
+#pragma unroll 8
+            for (int r = 0; r < B64; r += 2)
+                gt = MFMA32(S1[(r + lk) * LS + 32 * qi + lrow], S1[(r + lk) * LS + 32 * qj + lrow], gt);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Gs[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + 32 * qj + lrow] -= gt[v];
+        }
+        __syncthreads();
+        chol_upper_64(Gs, tid);
+        tri_inv_upper_64<false>(Gs, Ws, tid);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            U1[e] = Gs[(e >> 6) * LS + (e & 63)];
+            U1inv[e] = Ws[(e >> 6) * LS + (e & 63)];
+        }
+        return;
+    }
+    if (blockIdx.x == 0) {
+        load_tile(A, lda, 0, B64, Xs, tid);
+        __syncthreads();
+        mask_unit_lower(Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < B64) {
+                C[(long)r * lda + lrow] -= q0[v];
+                C[(long)r * lda + 32 + lrow] -= q1[v];
+            }
+        }
+        return;
+    }
+    for (int t = 0; t < tpw; ++t) {
+        const int row0 = B64 + ((blockIdx.x - 1) * tpw + t) * RT;
+        if (row0 >= m) break;
+        if (t > 0) __syncthreads();
+        load_tile(A, lda, row0, m, Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile_full(Xs, Ws, q0, q1, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = row0 + 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < m) {
+                C[(long)r * lda + lrow] -= q0[v];
+                C[(long)r * lda + 32 + lrow] -= q1[v];
+            }
+        }
     }
 }
 
@@ -793,7 +851,7 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 
 }  // namespace
 
-size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 1) * B64 * B64 + 4 * B64 * B64 + 64; }
+size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 2) * B64 * B64 + 5 * B64 * B64 + 64; }
 
 bool cholpanel_supported(const float* A, long lda, int m, int jb) {
     return jb == B64 && m >= B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
@@ -801,16 +859,17 @@ bool cholpanel_supported(const float* A, long lda, int m, int jb) {
 
 namespace {
 struct TallScratch {
-    float *part, *U1, *U1inv, *Mm, *Mm2, *wpart;
+    float *part, *U1, *U1inv, *Mm, *Mm2, *ctop, *wpart;
     unsigned* fb;
     explicit TallScratch(float* scratch) {
-        part = scratch;
-        U1 = part + (size_t)kCholMaxParts * B64 * B64;
+        part = scratch;                                            // kCholMaxParts + 1 Gram partials
+        U1 = part + (size_t)(kCholMaxParts + 1) * B64 * B64;
         U1inv = U1 + B64 * B64;
         Mm = U1inv + B64 * B64;
         Mm2 = Mm + B64 * B64;
-        fb = reinterpret_cast<unsigned*>(Mm2 + B64 * B64);
-        wpart = Mm2 + B64 * B64 + 64;
+        ctop = Mm2 + B64 * B64;                                    // top block of the look-ahead columns before their update
+        fb = reinterpret_cast<unsigned*>(ctop + B64 * B64);
+        wpart = ctop + B64 * B64 + 64;                             // kCholMaxParts + 1 projection partials
     }
 };
 // Row tiles of 128 per workgroup and number of workgroups (= Gram partials) for a panel of m rows.  More partials
@@ -830,8 +889,10 @@ hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Y
     const TallScratch ts(scratch);
     int tpw, nparts;
     tall_split(m, tpw, nparts);
-    if (!have_gram) hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.part);
-    hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, ts.U1, ts.U1inv);
+    if (!have_gram) {   // otherwise U1 and its inverse were left by the previous panel's launch_cholqr_finish
+        hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.part);
+        hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, ts.U1, ts.U1inv);
+    }
     hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.U1inv, q1, ts.part);
     hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, q1, ts.U1, A, lda, m, Tout, Yp,
                        ts.Mm, ts.Mm2, tau, tslices, ts.fb, status);
@@ -852,10 +913,19 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
     int tpw, nparts;
     tall_split(m - B64, tpw, nparts);
     const HandOver h = ho != nullptr ? *ho : HandOver();
+    float* gpart = next_gram ? ts.part : static_cast<float*>(nullptr);
     hipLaunchKernelGGL(ts_mul_proj_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, q1, m, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb,
-                       tpw, ts.wpart, h);
-    hipLaunchKernelGGL(la_update_gram_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, A, lda, m, ts.wpart, nparts + 1, tpw,
-                       next_gram ? ts.part : static_cast<float*>(nullptr), h);
+                       tpw, ts.wpart, gpart, ts.ctop, h);
+    // The extra workgroup is the longest one: with NSUM threads its two sums take 3 rounds of loads each instead of 5
+    // (n = 4096: 7.15 -> 7.01 ms for the QR); above 4096 rows, where the kernel has twice the workgroups and the chain
+    // is not what bounds the QR, the wider workgroups cost more than they give (n = 8192: 27.95 -> 28.45 ms).
+    const bool wide = m <= 4096;
+    if (wide)
+        hipLaunchKernelGGL(la_update_chol_kernel<NSUM>, dim3(nparts + 1 + (next_gram ? 1 : 0)), dim3(NSUM), 0, s, A, lda, m,
+                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, h);
+    else
+        hipLaunchKernelGGL(la_update_chol_kernel<NTHR>, dim3(nparts + 1 + (next_gram ? 1 : 0)), dim3(NTHR), 0, s, A, lda, m,
+                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, h);
     return hipGetLastError();
 }
 
