@@ -357,6 +357,50 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ part, int
     __syncthreads();
 }
 
+// The two sums of la_update_chol_kernel's extra workgroup in the same rounds of loads:  Wm = sum of the n partials at
+// wp (all four quadrants),  Gm = sum of the n partials at gp (quadrants on and above the diagonal; the lower-left one is
+// set to zero).  NS threads, ZB partials of each in flight per 16-byte piece; ends with a barrier.
+template <int NS, int ZB>
+__device__ __forceinline__ void sum_partials_pair(const float* __restrict__ wp, const float* __restrict__ gp, int n,
+                                                  float* Wm, float* Gm, int tid) {
+    constexpr int PER = B64 * B64 / 4 / NS;
+    float4 sw[PER], sg[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) sw[q] = sg[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z0 = 0; z0 < n; z0 += ZB) {
+        float4 tw[PER][ZB], tg[PER][ZB];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = 4 * (tid + NS * q);
+            const bool upper = !((e >> 6) >= 32 && (e & 63) < 32);
+#pragma unroll
+            for (int z = 0; z < ZB; ++z) {
+                const bool in = z0 + z < n;
+                tw[q][z] = in ? *reinterpret_cast<const float4*>(wp + (long)(z0 + z) * B64 * B64 + e)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+                tg[q][z] = (in && upper) ? *reinterpret_cast<const float4*>(gp + (long)(z0 + z) * B64 * B64 + e)
+                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+#pragma unroll
+            for (int z = 0; z < ZB; ++z) {
+                sw[q].x += tw[q][z].x; sw[q].y += tw[q][z].y; sw[q].z += tw[q][z].z; sw[q].w += tw[q][z].w;
+                sg[q].x += tg[q][z].x; sg[q].y += tg[q][z].y; sg[q].z += tg[q][z].z; sg[q].w += tg[q][z].w;
+            }
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int e = 4 * (tid + NS * q);
+        float* dw = Wm + (e >> 6) * LS + (e & 63);
+        float* dg = Gm + (e >> 6) * LS + (e & 63);
+        dw[0] = sw[q].x; dw[1] = sw[q].y; dw[2] = sw[q].z; dw[3] = sw[q].w;
+        dg[0] = sg[q].x; dg[1] = sg[q].y; dg[2] = sg[q].z; dg[3] = sg[q].w;
+    }
+    __syncthreads();
+}
+
 // Rank-8 update on the matrix cores of the 64 x 64 matrix Wm held in LDS (row stride LS), for the entries with
 // row >= lim and column >= lim only:  Wm[i][j] -= sum_{r<8} Lc(i, k0 + r) * Wm[k0 + r][j],  where Lc(i, k) is
 // Wm[i][k] (SYM = false: the multipliers sit in columns k0.. of the same matrix) or Wm[k][i] (SYM = true: the
@@ -543,18 +587,29 @@ __global__ __launch_bounds__(NT) void la_update_chol_kernel(float* A, long lda, 
         // ---- the next panel's U1 = chol(G), U1^-1
         float* S0 = Xs;               // V_top
         float* S1 = Xs + B64 * LS;    // C_top, then C'_top
-        // both sums with all NSUM threads (each ends with a barrier): W2 (summed in another order than the updating
-        // workgroups sum it, which moves G by rounding only) and C^T C over all rows (upper quadrants)
-        sum_partials<NT, NT == NTHR ? 8 : 16, true>(wpart, nproj, Ws, tid);
-        sum_partials<NT, NT == NTHR ? 8 : 16>(gpart, nproj, Gs, tid);
-        if (tid >= NTHR) return;
-        load_tile(A, lda, 0, B64, Xs, tid);       // rows 0..63 = top block of the panel (rows 64.. of the tile: zero)
-        __syncthreads();
+        // both sums with all NT threads: W2 (summed in another order than the updating workgroups sum it, which moves G
+        // by rounding only) and C^T C over all rows (upper quadrants)
+        // the two 64 x 64 blocks needed after the sums are requested first: they arrive meanwhile
+        float4 vt[4], ct[4];
+        if (tid < NTHR) {
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int e = tid + NTHR * q;
-            S1[(e >> 6) * LS + (e & 63)] = ctop[e];
+            for (int q = 0; q < 4; ++q) {
+                const int e = 4 * (tid + NTHR * q);
+                vt[q] = *reinterpret_cast<const float4*>(A + (long)(e >> 6) * lda + (e & 63));
+                ct[q] = *reinterpret_cast<const float4*>(ctop + e);
+            }
         }
+        sum_partials_pair<NT, NT == NTHR ? 4 : 11>(wpart, gpart, nproj, Ws, Gs, tid);
+        if (tid >= NTHR) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = 4 * (tid + NTHR * q);
+            float* d0 = S0 + (e >> 6) * LS + (e & 63);
+            float* d1 = S1 + (e >> 6) * LS + (e & 63);
+            d0[0] = vt[q].x; d0[1] = vt[q].y; d0[2] = vt[q].z; d0[3] = vt[q].w;
+            d1[0] = ct[q].x; d1[1] = ct[q].y; d1[2] = ct[q].z; d1[3] = ct[q].w;
+        }
+        __syncthreads();
         const f32x16 vw = lds_mma<2>(S0, Ws, nullptr, qi, qj, 0, B64, lrow, lk);   // V_top (unit lower) W2
         __syncthreads();
 #pragma unroll
