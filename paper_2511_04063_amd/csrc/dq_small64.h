@@ -133,6 +133,136 @@ __device__ __forceinline__ void tri_inv_upper_64(const float* U, float* X, int t
     __syncthreads();
 }
 
+// Two independent inverses in the same sequence of barriers (the routine is bound by its dozen barriers, not by its
+// arithmetic): X0 = inv(U0), X1 = inv(U1), each as tri_inv_upper_64 computes it, UNIT0 / UNIT1 as UNIT there.
+template <int BL>
+__device__ __forceinline__ void tri_inv_level_pair(const float* U0, float* X0, const float* U1, float* X1, int tid) {
+    constexpr int PER_PAIR = BL * BL;
+    constexpr int TOTAL = (B64 / (2 * BL)) * PER_PAIR;
+    constexpr int ITERS = (TOTAL + NTHR - 1) / NTHR;
+    float acc[2][ITERS];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const float* U = s ? U1 : U0;
+        const float* X = s ? X1 : X0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {               // scratch (lower-left block of the pair) = B C^-1
+            const int e = tid + NTHR * it;
+            const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+            const int i = r / BL, j = r % BL;
+            float t = 0.f;
+#pragma unroll
+            for (int k = 0; k < BL; ++k) t += U[(o + i) * LS + o + BL + k] * X[(o + BL + k) * LS + o + BL + j];
+            acc[s][it] = t;
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        float* X = s ? X1 : X0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int e = tid + NTHR * it;
+            const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+            if (e < TOTAL) X[(o + BL + r / BL) * LS + o + r % BL] = acc[s][it];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const float* X = s ? X1 : X0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {               // X12 = -A^-1 scratch
+            const int e = tid + NTHR * it;
+            const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+            const int i = r / BL, j = r % BL;
+            float t = 0.f;
+#pragma unroll
+            for (int k = 0; k < BL; ++k) t += X[(o + i) * LS + o + k] * X[(o + BL + k) * LS + o + j];
+            acc[s][it] = t;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        float* X = s ? X1 : X0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int e = tid + NTHR * it;
+            const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
+            if (e < TOTAL) {
+                X[(o + r / BL) * LS + o + BL + r % BL] = -acc[s][it];
+                X[(o + BL + r / BL) * LS + o + r % BL] = 0.f;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+template <bool UNIT0, bool UNIT1>
+__device__ __forceinline__ void tri_inv_upper_64_pair(const float* U0, float* X0, const float* U1, float* X1, int tid) {
+    const int lane = tid & 63, wave = tid >> 6, lrow = lane & 31, lk = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + NTHR * q;
+        X0[(e >> 6) * LS + (e & 63)] = 0.f;
+        X1[(e >> 6) * LS + (e & 63)] = 0.f;
+    }
+    __syncthreads();
+    if (tid < 128) {                                       // 8 x 8 diagonal blocks: wavefront 0 those of U0, wavefront 1 those of U1
+        const bool second = tid >= 64;
+        const float* U = second ? U1 : U0;
+        float* X = second ? X1 : X0;
+        const bool unit = second ? UNIT1 : UNIT0;
+        const int t64 = tid & 63;
+        const int o = 8 * (t64 >> 3), c = t64 & 7;
+        float u[8][8], x[8], ru[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int q = r; q < 8; ++q) u[r][q] = U[(o + r) * LS + o + q];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) ru[r] = unit ? 1.f : 1.f / u[r][r];
+#pragma unroll
+        for (int r = 7; r >= 0; --r) {
+            float t = (r == c) ? 1.f : 0.f;
+#pragma unroll
+            for (int q = r + 1; q < 8; ++q) t -= u[r][q] * x[q];
+            x[r] = t * ru[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) X[(o + r) * LS + o + c] = x[r];
+    }
+    __syncthreads();
+    tri_inv_level_pair<8>(U0, X0, U1, X1, tid);
+    tri_inv_level_pair<16>(U0, X0, U1, X1, tid);
+    const float* U = wave == 1 ? U1 : U0;
+    float* X = wave == 1 ? X1 : X0;
+    if (wave < 2) {                                        // scratch (rows 32.., cols 0..31) = U12 C^-1
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = MFMA32(U[lrow * LS + 32 + kk + lk], X[(32 + kk + lk) * LS + 32 + lrow], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) X[(32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + lrow] = acc[v];
+    }
+    __syncthreads();
+    if (wave < 2) {
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2)
+            acc = MFMA32(X[lrow * LS + kk + lk], X[(32 + kk + lk) * LS + lrow], acc);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + 4 * lk + (v & 3);
+            X[r * LS + 32 + lrow] = -acc[v];
+        }
+        // the reads of the scratch block above are complete (their results fed the products): clear it
+#pragma unroll
+        for (int v = 0; v < 16; ++v) X[(32 + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + lrow] = 0.f;
+    }
+    __syncthreads();
+}
+
 // This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (multiples of 32), both
 // operands in LDS.  AMODE 1: entries of A below its diagonal are taken as zero; AMODE 2: A is taken as unit lower
 // triangular (stored diagonal and upper part ignored); AMODE 0: as stored.

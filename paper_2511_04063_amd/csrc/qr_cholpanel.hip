@@ -770,12 +770,14 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
                                                          float* __restrict__ tau, float* __restrict__ tslices,
                                                          unsigned* __restrict__ fb, unsigned* __restrict__ status) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
-    __shared__ float Bs[3 * B64 * LS];
+    __shared__ float Bs[5 * B64 * LS];
     __shared__ float sg[B64];
     __shared__ float redw[4];
     float* B0 = Bs;
     float* B1 = Bs + B64 * LS;
     float* B2 = Bs + 2 * B64 * LS;
+    float* B3 = Bs + 3 * B64 * LS;
+    float* B4 = Bs + 4 * B64 * LS;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
     const int qi = (wave >> 1) & 1, qj = wave & 1;
@@ -858,47 +860,41 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     }
     __syncthreads();
     lu_signed_64(B0, sg, tid);                  // B0 = L \ U_lu, sg = S
-    tri_inv_upper_64<false>(B0, B2, tid);       // B2 = U_lu^-1
-    // Mm = U2^-1 U_lu^-1, kept in registers as well: it is multiplied by T further down
-    f32x16 accM = zero16();
-    if (qi <= qj) accM = lds_mma<0>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) Mm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * B64 + 32 * qj + lrow] = accM[v];
-    __syncthreads();
-    // V_top to the panel; its transpose (unit upper triangular) to B1
+    // V_top (the unit lower triangular L) to the panel; its transpose (unit upper triangular) to B3
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
         const int r = e >> 6, c = e & 63;
         if (c < r) A[(long)r * lda + c] = B0[r * LS + c];
-        B1[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
+        B3[r * LS + c] = (c > r) ? B0[c * LS + r] : (c == r ? 1.f : 0.f);
     }
-    __syncthreads();
-    tri_inv_upper_64<true>(B1, B2, tid);        // B2 = V_top^-T
-    {   // T = -(U_lu S) V_top^-T  -> global and B1; the triangular factor S Rf -> panel
-        f32x16 accT = zero16();
-        if (qi <= qj) accT = lds_mma<1>(B0, B2, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
-        __syncthreads();                        // every wavefront is done with B2 (and B1 was only read by tri_inv)
+    // both inverses in one sequence of barriers (its first barrier orders the writes of B3 before their reads):
+    tri_inv_upper_64_pair<false, true>(B0, B2, B3, B4, tid);    // B2 = U_lu^-1, B4 = V_top^-T
+    // Three products of upper triangular factors, kept in registers until the barrier below:
+    //   Mm  = U2^-1 U_lu^-1,   T = -(U_lu S) V_top^-T,   Mm2 = Mm T = -(U2^-1 S) V_top^-T  (U_lu cancels)
+    f32x16 accM = zero16(), accT = zero16(), acc2 = zero16();
+    if (qi <= qj) {
+        accM = lds_mma<0>(B1, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+        accT = lds_mma<1>(B0, B4, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+        acc2 = lds_mma<0>(B1, B4, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+    }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
-            const float t = (c >= r) ? -accT[v] : 0.f;
-            Tout[r * B64 + c] = t;
-            B1[r * LS + c] = t;
-            B2[r * LS + c] = accM[v];
-            if (c >= r) A[(long)r * lda + c] = sg[r] * accR[v];
-        }
+    for (int v = 0; v < 16; ++v) {
+        const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
+        const float t = (c >= r) ? -accT[v] : 0.f;
+        Mm[r * B64 + c] = accM[v];
+        Mm2[r * B64 + c] = -acc2[v];
+        Tout[r * B64 + c] = t;
+        B3[r * LS + c] = t;                     // nothing reads V_top^T any more
+        if (c >= r) A[(long)r * lda + c] = sg[r] * accR[v];     // the triangular factor S Rf
     }
     __syncthreads();
-    {   // Mm2 = Mm T (upper x upper);  Yp_top = V_top T (unit lower x upper)
-        f32x16 acc2 = zero16();
-        if (qi <= qj) acc2 = lds_mma<0>(B2, B1, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
+    {   // Yp_top = V_top T (unit lower x upper)
         const int kq = qi < qj ? qi : qj;
-        const f32x16 accY = lds_mma<2>(B0, B1, nullptr, qi, qj, 0, 32 * (kq + 1), lrow, lk);
+        const f32x16 accY = lds_mma<2>(B0, B3, nullptr, qi, qj, 0, 32 * (kq + 1), lrow, lk);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
-            Mm2[r * B64 + c] = acc2[v];
             Yp[r * B64 + c] = accY[v];
         }
     }
