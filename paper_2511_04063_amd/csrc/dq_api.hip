@@ -578,8 +578,8 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
             }
             {
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 4.0 * m * (double)jb * nla, 0.0);
-                DQ_HIP(launch_cholqr_finish(Ap, ld, m, Yp, vs, at<float>(c, L.cq), fused_la ? 1 : 0, next_tall ? 1 : 0, sA,
-                                            signalled ? &ho : nullptr));
+                DQ_HIP(launch_cholqr_finish(Ap, ld, m, Yp, vs, at<float>(c, L.cq), fused_la ? 1 : 0, next_tall ? 1 : 0, flags,
+                                            sA, signalled ? &ho : nullptr));
             }
             gram_ready = next_tall;
             if (!fused_la && nla > 0) {   // C_la -= V (Yp^T C_la)

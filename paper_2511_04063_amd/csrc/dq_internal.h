@@ -130,15 +130,16 @@ hipError_t launch_qr_panel(float* A, long lda, int m, int jb, float* tau, float*
 // m x 64 panel (m >= 64) by CholeskyQR2 + Householder reconstruction on many compute units, in two calls.
 // launch_cholqr_factor: everything up to the top 64 x 64 block: triangular factor and the first 64 rows of the
 //   reflectors in A (as launch_qr_panel leaves them, except that row signs of the triangular factor may differ), T
-//   (64 x 64, ld 64) in Tout, the first 64 rows of Yp = V T (m x 64, ld 64).  have_gram != 0: the Cholesky factor of
-//   the panel's Gram matrix and its inverse are already in the scratch (left there by the previous panel's
-//   launch_cholqr_finish).
+//   (64 x 64, ld 64) in Tout, the first 64 rows of Yp = V T (m x 64, ld 64).  have_gram != 0: the first pass of the
+//   panel (Cholesky factor of its Gram matrix, Q1 = A U1^-1 in q1 and the partials of Q1^T Q1) is already in the
+//   scratch, left there by the previous panel's launch_cholqr_finish.
 // launch_cholqr_finish: the rows of V and Yp below the block (none for m == 64).  lookahead != 0 (needs m >= 128):
 //   it also applies the
 //   panel's block reflector to the next 64 columns A[:, 64:128] (so these must have received every earlier update
-//   before this call), and with next_gram != 0 leaves the first small step of the next panel A[64:, 64:128] behind
-//   (Cholesky factor of its Gram matrix and the inverse), computed beside the update from quantities of before the
-//   update.
+//   before this call), and with next_gram != 0 leaves the first pass of the next panel A[64:, 64:128] behind
+//   (Cholesky factor of its Gram matrix and the inverse, computed beside the update from quantities of before the
+//   update; then Q1 in q1, which this call has read by then, and the partials of Q1^T Q1).  status: the device status
+//   word (a bounded wait inside the kernel reports there).
 // q1: m x 64 floats of scratch (also the panel kernel's reflector scratch); scratch: cholpanel_scratch_floats()
 // floats; tau, tslices as for launch_qr_panel.  A panel that is too ill-conditioned for this route is factored by
 // the Householder panel code inside the same launches (slow but rare; same outputs) and DQ_FLAG_ILLCOND_PANEL is
@@ -151,7 +152,7 @@ hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Y
 // in every workgroup before it does (wait_word == null: no wait), and the kernel after it stores ho->signal_value to
 // ho->signal_word when it starts, i.e. once the reflectors and Yp are complete (signal_word == null: no signal).
 hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1, float* scratch, int lookahead,
-                                int next_gram, hipStream_t s, const HandOver* ho = nullptr);
+                                int next_gram, unsigned* status, hipStream_t s, const HandOver* ho = nullptr);
 
 // T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the split-K
 // partials of V^T [V | C] (gpart[z] at stride, leading dimension ldp: jb Gram columns, then nla columns of V^T C).

@@ -540,14 +540,15 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
 template <int NT>
 __global__ __launch_bounds__(NT) void la_update_chol_kernel(float* A, long lda, int m,
                                                               const float* __restrict__ wpart, int nproj, int tpw,
-                                                              const float* __restrict__ gpart,
+                                                              float* gpart,
                                                               const float* __restrict__ ctop, float* __restrict__ U1,
-                                                              float* __restrict__ U1inv, HandOver ho) {
+                                                              float* U1inv, float* __restrict__ Q1next,
+                                                              unsigned long long* ready, unsigned* status, HandOver ho) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
     // the kernel before this one completed the panel's reflectors and Yp: the other streams may go on
     if (ho.signal_word != nullptr && blockIdx.x == 0 && threadIdx.x == 0) handover_signal(ho.signal_word, ho.signal_value);
     __shared__ float Xs[RT * LS];
-    __shared__ float Ws[B64 * LS];
+    __shared__ __attribute__((aligned(16))) float Ws[B64 * LS];
     __shared__ float Gs[B64 * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lk = lane >> 5;
@@ -632,6 +633,8 @@ __global__ __launch_bounds__(NT) void la_update_chol_kernel(float* A, long lda, 
             U1[e] = Gs[(e >> 6) * LS + (e & 63)];
             U1inv[e] = Ws[(e >> 6) * LS + (e & 63)];
         }
+        __syncthreads();                       // every thread's part of U1^-1 is written: the other workgroups may use it
+        if (tid == 0) handover_signal(ready, 1ull);
         return;
     }
     if (blockIdx.x == 0) {
@@ -668,6 +671,42 @@ __global__ __launch_bounds__(NT) void la_update_chol_kernel(float* A, long lda, 
             }
         }
     }
+    if (gpart == nullptr) return;
+    // ---- the next panel's second step for the rows this workgroup has just updated (what ts_mul_gram_kernel does):
+    // Q1 = A_next U1^-1 and the partials of Q1^T Q1, once the extra workgroup has U1^-1.  The workgroups of a launch
+    // run at the same time (34 or 66 of them on 256 compute units), the extra one waits for nobody, and the poll is
+    // bounded like the polls between streams.
+    __syncthreads();                           // the stores of the updated rows precede their reads below; Ws is free
+    if (tid == 0) (void)handover_wait(ready, 1ull, 100LL * 1000 * 1000, status);
+    __syncthreads();
+    float* Ms = Ws;                            // 64 x 64, leading dimension 64
+    load_small64(U1inv, Ms, tid);
+    const float* An = A + (long)B64 * lda + B64;
+    const int mn = m - B64;
+    f32x16 acc = zero16();
+    for (int t = 0; t < tpw; ++t) {
+        const int row0 = ((blockIdx.x - 1) * tpw + t) * RT;
+        if (row0 >= mn) break;
+        __syncthreads();
+        load_tile(An, lda, row0, mn, Xs, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1 = zero16();
+        mul_tile(Xs, Ms, q0, q1, wave, lrow, lk);
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            Xs[r * LS + lrow] = q0[v];
+            Xs[r * LS + 32 + lrow] = q1[v];
+            if (row0 + r < mn) {
+                Q1next[(long)(row0 + r) * B64 + lrow] = q0[v];
+                Q1next[(long)(row0 + r) * B64 + 32 + lrow] = q1[v];
+            }
+        }
+        __syncthreads();
+        gram_tile(Xs, acc, qi, qj, lrow, lk);
+    }
+    store_partial(gpart + (long)(blockIdx.x - 1) * B64 * B64, acc, qi, qj, lrow, lk);
 }
 
 // First small step: U1 = chol(sum of partials of A^T A) and its inverse, both 64 x 64 (leading dimension 64).
@@ -768,8 +807,10 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
                                                          float* __restrict__ Tout, float* __restrict__ Yp,
                                                          float* __restrict__ Mm, float* __restrict__ Mm2,
                                                          float* __restrict__ tau, float* __restrict__ tslices,
-                                                         unsigned* __restrict__ fb, unsigned* __restrict__ status) {
+                                                         unsigned* __restrict__ fb, unsigned* __restrict__ status,
+                                                         unsigned long long* ready) {
     __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
+    if (threadIdx.x == 0) *ready = 0ull;   // "U1^-1 of the next panel is there": set by this panel's la_update_chol_kernel
     __shared__ float Bs[5 * B64 * LS];
     __shared__ float sg[B64];
     __shared__ float redw[4];
@@ -912,6 +953,7 @@ namespace {
 struct TallScratch {
     float *part, *U1, *U1inv, *Mm, *Mm2, *ctop, *wpart;
     unsigned* fb;
+    unsigned long long* ready;
     explicit TallScratch(float* scratch) {
         part = scratch;                                            // kCholMaxParts + 1 Gram partials
         U1 = part + (size_t)(kCholMaxParts + 1) * B64 * B64;
@@ -920,6 +962,7 @@ struct TallScratch {
         Mm2 = Mm + B64 * B64;
         ctop = Mm2 + B64 * B64;                                    // top block of the look-ahead columns before their update
         fb = reinterpret_cast<unsigned*>(ctop + B64 * B64);
+        ready = reinterpret_cast<unsigned long long*>(ctop + B64 * B64 + 2);   // 8-byte aligned: the scratch is 256-byte aligned
         wpart = ctop + B64 * B64 + 64;                             // kCholMaxParts + 1 projection partials
     }
 };
@@ -940,18 +983,18 @@ hipError_t launch_cholqr_factor(float* A, long lda, int m, float* Tout, float* Y
     const TallScratch ts(scratch);
     int tpw, nparts;
     tall_split(m, tpw, nparts);
-    if (!have_gram) {   // otherwise U1 and its inverse were left by the previous panel's launch_cholqr_finish
+    if (!have_gram) {   // otherwise the first two steps were done by the previous panel's launch_cholqr_finish
         hipLaunchKernelGGL(ts_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.part);
         hipLaunchKernelGGL(chol_inv_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, ts.U1, ts.U1inv);
+        hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.U1inv, q1, ts.part);
     }
-    hipLaunchKernelGGL(ts_mul_gram_kernel, dim3(nparts), dim3(NTHR), 0, s, A, lda, m, tpw, ts.U1inv, q1, ts.part);
     hipLaunchKernelGGL(hr_finish_kernel, dim3(1), dim3(NSUM), 0, s, ts.part, nparts, q1, ts.U1, A, lda, m, Tout, Yp,
-                       ts.Mm, ts.Mm2, tau, tslices, ts.fb, status);
+                       ts.Mm, ts.Mm2, tau, tslices, ts.fb, status, ts.ready);
     return hipGetLastError();
 }
 
 hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1, float* scratch, int lookahead,
-                                int next_gram, hipStream_t s, const HandOver* ho) {
+                                int next_gram, unsigned* status, hipStream_t s, const HandOver* ho) {
     const TallScratch ts(scratch);
     if (!lookahead) {
         if (ho != nullptr) return hipErrorInvalidValue;
@@ -973,10 +1016,10 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
     const bool wide = m <= 4096;
     if (wide)
         hipLaunchKernelGGL(la_update_chol_kernel<NSUM>, dim3(nparts + 1 + (next_gram ? 1 : 0)), dim3(NSUM), 0, s, A, lda, m,
-                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, h);
+                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, q1, ts.ready, status, h);
     else
         hipLaunchKernelGGL(la_update_chol_kernel<NTHR>, dim3(nparts + 1 + (next_gram ? 1 : 0)), dim3(NTHR), 0, s, A, lda, m,
-                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, h);
+                           ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, q1, ts.ready, status, h);
     return hipGetLastError();
 }
 
