@@ -113,7 +113,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
-           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -154,6 +154,8 @@ Layout make_layout(int n, int T) {
     L.yall = bump(cur, npanels * (size_t)n * kPanel * 4);   // V T of every panel (n x 64 slot each)
     const size_t nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
+    L.uinvo = bump(cur, (size_t)round_up(n, kTrsmOuter) * kTrsmOuter * 4);   // inverses of the outer diagonal blocks
+    L.utmp = bump(cur, (size_t)round_up(n, kTrsmOuter) * 192 * 4);          // products on the way to them
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
     L.Y = bump(cur, tn * 4);
     L.dY = bump(cur, tn * 4);
@@ -797,6 +799,70 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
         DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s));
     }
     const int nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
+    if (n % kTrsmOuter == 0) {
+        // M U^T = P by block columns of kTrsmOuter from the right:  M_J = P_J inv(U_JJ)^T, then everything left of the
+        // block gets ONE update with K = kTrsmOuter (K = 128 updates over the whole width move P at the rate of the
+        // rank-64 updates of the QR, and a chain of 128-column solves is a chain of short launches).  The inverses of
+        // the 512 x 512 diagonal blocks are merged from the 128 x 128 ones, inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1],
+        // [0, C^-1]], two levels of batched products that depend on U only.
+        float* uo = at<float>(c, L.uinvo);
+        float* t1 = at<float>(c, L.utmp);                               // n / 256 blocks of 128 x 128
+        float* t2 = t1 + (size_t)n * 64;                                // n / 512 blocks of 256 x 256
+        const int nouter = n / kTrsmOuter;
+        const long so = (long)kTrsmOuter * kTrsmOuter;
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 4.0 * n * (double)kTrsmOuter);
+            DQ_HIP(launch_place_diag_blocks(uinv, uo, n, s));
+        }
+        auto merge = [&](int h, int first, float* tmp, long stmp) -> dq_status {
+            // for the pair of h x h diagonal blocks that starts at row `first` of every outer block:
+            // tmp = B C^-1, then the upper-right block of the inverse = -A^-1 tmp
+            GemmF32 g;
+            g.A = U + (long)first * ldu + first + h; g.lda = ldu; g.ta = 0;
+            g.B = uo + (long)(first + h) * kTrsmOuter + first + h; g.ldb = kTrsmOuter; g.tb = 0;
+            g.C = tmp; g.ldc = h; g.M = h; g.N = h; g.K = h;
+            g.batch = nouter; g.batch_a = (long)kTrsmOuter * ldu + kTrsmOuter; g.batch_b = so; g.batch_c = stmp;
+            {
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * nouter * (double)h * h * h, 0.0);
+                DQ_HIP(launch_gemm_f32(g, s));
+            }
+            GemmF32 f;
+            f.A = uo + (long)first * kTrsmOuter + first; f.lda = kTrsmOuter; f.ta = 0;
+            f.B = tmp; f.ldb = h; f.tb = 0;
+            f.C = uo + (long)first * kTrsmOuter + first + h; f.ldc = kTrsmOuter; f.M = h; f.N = h; f.K = h;
+            f.alpha = -1.f;
+            f.batch = nouter; f.batch_a = so; f.batch_b = stmp; f.batch_c = so;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * nouter * (double)h * h * h, 0.0);
+            DQ_HIP(launch_gemm_f32(f, s));
+            return DQ_OK;
+        };
+        DQ_TRY(merge(kTrsmBlock, 0, t1, (long)2 * kTrsmBlock * kTrsmBlock));
+        DQ_TRY(merge(kTrsmBlock, 2 * kTrsmBlock, t1 + (long)kTrsmBlock * kTrsmBlock, (long)2 * kTrsmBlock * kTrsmBlock));
+        DQ_TRY(merge(2 * kTrsmBlock, 0, t2, (long)4 * kTrsmBlock * kTrsmBlock));
+        for (int J = nouter - 1; J >= 0; --J) {
+            const int J0 = J * kTrsmOuter;
+            const int mrows = n - J0;
+            {
+                GemmF32 g;   // M[J0:, blk] = P[J0:, blk] * inv(U_JJ)^T
+                g.A = Pb + (long)J0 * ld + J0; g.lda = ld; g.ta = 0;
+                g.B = uo + (long)J * so; g.ldb = kTrsmOuter; g.tb = 1;
+                g.C = Mb + (long)J0 * ld + J0; g.ldc = ld;
+                g.M = mrows; g.N = kTrsmOuter; g.K = kTrsmOuter;
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mrows * (double)kTrsmOuter * kTrsmOuter, 0.0);
+                DQ_HIP(launch_gemm_f32(g, s));
+            }
+            if (J0 > 0) {
+                GemmF32 g;   // P[J0:, 0:J0] -= M[J0:, blk] * U[0:J0, blk]^T
+                g.A = Mb + (long)J0 * ld + J0; g.lda = ld; g.ta = 0;
+                g.B = U + J0; g.ldb = ldu; g.tb = 1;
+                g.C = Pb + (long)J0 * ld; g.ldc = ld;
+                g.M = mrows; g.N = J0; g.K = kTrsmOuter;
+                g.alpha = -1.f; g.beta = 1.f;
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mrows * (double)J0 * kTrsmOuter, 0.0);
+                DQ_HIP(launch_gemm_f32(g, s));
+            }
+        }
+    } else
     for (int j = nblk - 1; j >= 0; --j) {
         const int j0 = j * kTrsmBlock;
         const int w = (n - j0) < kTrsmBlock ? (n - j0) : kTrsmBlock;

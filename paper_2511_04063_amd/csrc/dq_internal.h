@@ -11,6 +11,7 @@ namespace dq {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kPanel = 64;           // QR panel width nb (columns aggregated into one compact-WY block)
 constexpr int kTrsmBlock = 128;      // diagonal block size of the blocked triangular solve
+constexpr int kTrsmOuter = 512;      // its outer block: columns solved before the rest of the matrix is updated once
 constexpr int kMaxSplit = 64;        // upper bound on split-K partials
 constexpr int kHeadDim = 128;         // matrix size served by the batched small-rotation path
 constexpr int kHeadsChunk = 2048;     // tokens per workgroup of its fused rotate / loss / gradient kernel
@@ -197,6 +198,9 @@ hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp
 hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, unsigned* flags, hipStream_t s,
                                int batch = 1, long stride_u = 0, long stride_inv = 0);
 hipError_t launch_axpy2d(float* Z, long ldz, const float* D, long ldd, int n, float a, hipStream_t s);
+// out (n / kTrsmOuter row-major blocks of kTrsmOuter x kTrsmOuter; n a multiple of kTrsmOuter) = the kTrsmBlock x kTrsmBlock
+// inverses of launch_trinv_blocks on the block diagonal, zero elsewhere
+hipError_t launch_place_diag_blocks(const float* inv, float* out, int n, hipStream_t s);
 // Adam / heavy-ball updates of an n x n matrix in place (see include/dartqr.h); c1 = 1 / (1 - beta1^t),
 // c2 = 1 / (1 - beta2^t) are formed on the host in double precision.
 hipError_t launch_adam2d(float* Z, long ldz, const float* D, long ldd, float* m, long ldm, float* v, long ldv, int n,

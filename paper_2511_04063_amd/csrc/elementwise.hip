@@ -373,6 +373,23 @@ __global__ __launch_bounds__(NTHR) void trinv_blocks_kernel(const float* __restr
     }
 }
 
+// out (n / kTrsmOuter blocks of kTrsmOuter x kTrsmOuter, row-major) = block diagonal of the kTrsmBlock inverses in
+// `inv` (row-major kTrsmBlock x kTrsmBlock each), zero elsewhere
+__global__ __launch_bounds__(256) void place_diag_blocks_kernel(const float* __restrict__ inv, float* __restrict__ out,
+                                                                long total4) {
+    constexpr int per = kTrsmOuter / kTrsmBlock;
+    for (long e4 = (long)blockIdx.x * 256 + threadIdx.x; e4 < total4; e4 += (long)gridDim.x * 256) {
+        const long e = e4 * 4;
+        const long J = e / ((long)kTrsmOuter * kTrsmOuter);
+        const int r = (int)((e / kTrsmOuter) % kTrsmOuter), c = (int)(e % kTrsmOuter);
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r / kTrsmBlock == c / kTrsmBlock)
+            v = *reinterpret_cast<const float4*>(inv + ((J * per + r / kTrsmBlock) * kTrsmBlock + r % kTrsmBlock) * kTrsmBlock +
+                                                 c % kTrsmBlock);
+        *reinterpret_cast<float4*>(out + e) = v;
+    }
+}
+
 __global__ __launch_bounds__(256) void axpy2d_kernel(float* __restrict__ Z, long ldz, const float* __restrict__ D,
                                                      long ldd, int n, float a) {
     const long total = (long)n * n;
@@ -531,6 +548,14 @@ hipError_t launch_trinv_blocks(const float* U, long ldu, int n, float* Uinv, uns
     if (batch < 1) return hipSuccess;
     hipLaunchKernelGGL(trinv_blocks_kernel, dim3(nb, batch), dim3(NTHR), 0, s, U, ldu, n, Uinv, flags, stride_u,
                        stride_inv);
+    return hipGetLastError();
+}
+
+hipError_t launch_place_diag_blocks(const float* inv, float* out, int n, hipStream_t s) {
+    const long total4 = (long)n * kTrsmOuter / 4;
+    long b = (total4 + 255) / 256;
+    if (b > 4096) b = 4096;
+    hipLaunchKernelGGL(place_diag_blocks_kernel, dim3((unsigned)b), dim3(256), 0, s, inv, out, total4);
     return hipGetLastError();
 }
 
