@@ -114,13 +114,18 @@ typedef enum {
     DQ_OPT_SINGLE_STREAM = 2,       /* non-zero: every piece of the QR on the context's stream, no overlap (default 0) */
     DQ_OPT_FUSED_WHIP = 3,          /* zero: Eq. 4 always as a pass of its own, never in the epilogue of X @ R (default 1) */
     DQ_OPT_HEADS_BATCHED = 4,       /* zero: 128 x 128 problems take the general route one by one (default 1) */
-    DQ_OPT_DEVICE_SYNC = 5          /* how the pieces of the QR on the library's streams wait for each other.  0: HIP
+    DQ_OPT_DEVICE_SYNC = 5,         /* how the pieces of the QR on the library's streams wait for each other.  0: HIP
                                        events.  1 (default): through a word in device memory that the producing stream
                                        sets and the consuming stream polls (a cross-stream wait on an event that is still
                                        pending costs the host 10-20 us here, several per panel), IF a probe at the first
                                        call on a stream shows that the streams involved make progress independently
                                        (they do unless they share a hardware queue); otherwise events.  Every poll is
                                        bounded (DQ_FLAG_SYNC_TIMEOUT). */
+    DQ_OPT_SPLIT_GEMM = 6           /* the n x n x n fp32 products of S6 (R^T G and R M) on the bf16 matrix cores from
+                                       three-plane bf16 splits of both operands (x = x1 + x2 + x3 carries 24 mantissa
+                                       bits; the six plane pairs above fp32 rounding are accumulated in fp32).  0: never
+                                       (fp32 matrix cores); 1 (default): when n is a multiple of 256 and at least 2560,
+                                       where it is faster; 2: whenever n is a multiple of 256. */
 } dq_option;
 dq_status dq_set_option(dq_ctx* ctx, dq_option option, int value);
 

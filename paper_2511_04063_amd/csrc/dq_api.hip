@@ -96,6 +96,8 @@ struct dq_ctx {
                                      // 4 from there on, each measured best there; 1: panel by panel)
     bool fused_whip = true;          // Eq. 4 in the epilogue of the rotation product where the shape allows
     bool heads_batched = true;       // n == 128: all problems of a batch in the same launches
+    int split_gemm = 1;              // fp32 products of the derivative from three-plane bf16 splits: 0 never, 1 where the
+                                     // shape fits and is large enough to gain, 2 wherever the shape fits
     bool device_sync = true;         // the QR's streams hand over through a device word where a probe allows (else events)
     unsigned long long seq = 0;      // last value handed out for the hand-over words, which only grow
     struct Probed { hipStream_t s; bool ok; };
@@ -113,7 +115,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
-           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, x3a = 0, x3b = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -156,6 +158,9 @@ Layout make_layout(int n, int T) {
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
     L.uinvo = bump(cur, (size_t)round_up(n, kTrsmOuter) * kTrsmOuter * 4);   // inverses of the outer diagonal blocks
     L.utmp = bump(cur, (size_t)round_up(n, kTrsmOuter) * 192 * 4);          // products on the way to them
+    // three bf16 planes of two n x n operands (fp32 products on the bf16 matrix cores)
+    L.x3a = bump(cur, 3 * n2 * 2);
+    L.x3b = bump(cur, 3 * n2 * 2);
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
     L.Y = bump(cur, tn * 4);
     L.dY = bump(cur, tn * 4);
@@ -785,7 +790,27 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
     float* uinv = at<float>(c, L.uinv);
     const long ld = L.ld;
     const double n3 = (double)n * n * n;
-    {
+    // The two full n x n x n products run on the bf16 matrix cores from three-plane splits of their operands when the
+    // shape fits those tiles (fp32-level accuracy: six plane pairs, fp32 accumulation), else on the fp32 ones.
+    // (256 x 256 tiles at six times the matrix-core work: ahead of the fp32 kernel's 128 x 128 tiles once about a hundred of
+    // them keep the compute units busy, n >= 2560)
+    const bool x3 = c->split_gemm != 0 && gemm_bf16x3_fits(n, n, n) && ld == n && (c->split_gemm == 2 || n >= 2560);
+    bf16_t* pa3 = at<bf16_t>(c, L.x3a);
+    bf16_t* pb3 = at<bf16_t>(c, L.x3b);
+    const long plane = (long)n * ld;
+    if (x3) {
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 20.0 * n * (double)n);
+            DQ_HIP(launch_split3_bf16(R, ldr, n, n, pa3, ld, plane, 1, s));
+            DQ_HIP(launch_split3_bf16(G, ldg, n, n, pb3, ld, plane, 1, s));
+        }
+        GemmBf16 g;   // B = R^T G:  B(i, j) = sum_k R^T(i, k) G^T(j, k)
+        g.A = pa3; g.lda = ld; g.a_plane = plane;
+        g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1;
+        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 12.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_bf16x3(g, s));
+    } else {
         GemmF32 g;
         g.A = R; g.lda = ldr; g.ta = 1;
         g.B = G; g.ldb = ldg; g.tb = 0;
@@ -852,7 +877,8 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
                 DQ_HIP(launch_gemm_f32(g, s));
             }
             if (J0 > 0) {
-                GemmF32 g;   // P[J0:, 0:J0] -= M[J0:, blk] * U[0:J0, blk]^T
+                GemmF32 g;   // P[J0:, 0:J0] -= M[J0:, blk] * U[0:J0, blk]^T (in fp32: from three-plane splits its tiles
+                             // fill the compute units too unevenly to gain, 8192: 12.1 against 11.5 ms for the whole call)
                 g.A = Mb + (long)J0 * ld + J0; g.lda = ld; g.ta = 0;
                 g.B = U + J0; g.ldb = ldu; g.tb = 1;
                 g.C = Pb + (long)J0 * ld; g.ldc = ld;
@@ -887,7 +913,21 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
             DQ_HIP(launch_gemm_f32(g, s));
         }
     }
-    {
+    if (x3) {
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 20.0 * n * (double)n);
+            DQ_HIP(launch_split3_bf16(R, ldr, n, n, pa3, ld, plane, 0, s));
+            DQ_HIP(launch_split3_bf16(Mb, ld, n, n, pb3, ld, plane, 1, s));
+        }
+        GemmBf16 g;   // dZ = R M (or Z <- Z - lr R M):  dZ(i, j) = sum_k R(i, k) M^T(j, k), M strictly lower
+        g.A = pa3; g.lda = ld; g.a_plane = plane;
+        g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1; g.b_strict_lower = 1;
+        g.M = n; g.N = n; g.K = n;
+        if (Zupd != nullptr) { g.C = Zupd; g.ldc = ldz; g.alpha = -lr; g.beta = 1.f; }
+        else { g.C = dZ; g.ldc = lddz; }
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 6.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_bf16x3(g, s));
+    } else {
         GemmF32 g;   // dZ = R * M  (or Z <- Z - lr * R * M)
         g.A = R; g.lda = ldr; g.ta = 0;
         g.B = Mb; g.ldb = ld; g.tb = 0; g.b_strict_lower = 1;
@@ -1413,6 +1453,10 @@ dq_status dq_set_option(dq_ctx* c, dq_option option, int value) {
         case DQ_OPT_SINGLE_STREAM: c->single_stream = value != 0; return DQ_OK;
         case DQ_OPT_FUSED_WHIP: c->fused_whip = value != 0; return DQ_OK;
         case DQ_OPT_DEVICE_SYNC: c->device_sync = value != 0; return DQ_OK;
+        case DQ_OPT_SPLIT_GEMM:
+            if (value < 0 || value > 2) return DQ_ERR_SHAPE;
+            c->split_gemm = value;
+            return DQ_OK;
         case DQ_OPT_HEADS_BATCHED: c->heads_batched = value != 0; return DQ_OK;
     }
     return DQ_ERR_DTYPE;

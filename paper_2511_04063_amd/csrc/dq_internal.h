@@ -76,8 +76,22 @@ struct GemmBf16 {
     // of exp(-|y|) per workgroup (gemm_bf16_whip_partials() doubles) are produced from the accumulators; C may then be
     // null.  Only for shapes gemm_bf16_deep_fits() accepts.
     bf16_t* whip_dyt = nullptr; long whip_ldt = 0; float whip_scale = 0.f; double* whip_partials = nullptr;
+    // launch_gemm_bf16x3 only: element distance between the three planes of each operand, the epilogue
+    // C = alpha * (A B^T) + beta * C, and b_strict_lower: B^T(k, n) vanishes for k <= n (K == N), the reduction of a tile
+    // starts at its first column
+    long a_plane = 0, b_plane = 0; float alpha = 1.f, beta = 0.f; int b_strict_lower = 0;
 };
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
+// fp32 product from three-plane bf16 splits of both operands (launch_split3_bf16), six plane pairs accumulated in fp32 on
+// the bf16 matrix cores: C (M x N fp32) = alpha * A B^T + beta * C with A (M x K) and B (N x K) row-major planes.
+// M and N multiples of 256, K of 64, 16-byte aligned rows and planes; anything else returns hipErrorInvalidValue.
+bool gemm_bf16x3_fits(int M, int N, int K);
+hipError_t launch_gemm_bf16x3(const GemmBf16& g, hipStream_t s);
+// out plane p (p = 0, 1, 2; at out + p * plane elements, leading dimension ldo) = p-th bf16 term of A (rows x cols
+// fp32): a1 = bf16(a), a2 = bf16(a - a1), a3 = bf16(a - a1 - a2), round to nearest even; transpose != 0 writes the planes
+// of A^T (cols x rows).
+hipError_t launch_split3_bf16(const float* A, long lda, int rows, int cols, bf16_t* out, long ldo, long plane, int transpose,
+                              hipStream_t s);
 bool gemm_bf16_deep_fits(const GemmBf16& g);   // large round NT product: the unguarded deep-prefetch kernels apply
 int gemm_bf16_whip_partials(const GemmBf16& g);   // workgroups (= partial sums) of the fused-epilogue launch for such a shape
 

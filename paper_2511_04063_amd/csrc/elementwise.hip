@@ -189,6 +189,54 @@ __global__ __launch_bounds__(256) void split_transpose_bf16_kernel(const float* 
     }
 }
 
+// Three-plane bf16 split of an fp32 matrix (a = a1 + a2 + a3 to 24 mantissa bits; both subtractions are exact in fp32).
+__device__ __forceinline__ void split3(float a, bf16_t& p1, bf16_t& p2, bf16_t& p3) {
+    const uint32_t h1 = f32_to_bf16_rne(a);
+    const float r1 = a - __uint_as_float(h1 << 16);
+    const uint32_t h2 = f32_to_bf16_rne(r1);
+    const float r2 = r1 - __uint_as_float(h2 << 16);
+    p1 = (bf16_t)h1; p2 = (bf16_t)h2; p3 = (bf16_t)f32_to_bf16_rne(r2);
+}
+
+// planes of A^T through a 32 x 33 LDS tile (coalesced on both sides)
+__global__ __launch_bounds__(256) void split3_transpose_bf16_kernel(const float* __restrict__ A, long lda, int rows, int cols,
+                                                                    bf16_t* __restrict__ out, long ldo, long plane) {
+    __shared__ float tile[32][33];
+    const int bx = blockIdx.x * 32, by = blockIdx.y * 32;   // bx: column block of A, by: row block of A
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int i = ty; i < 32; i += 8) {
+        const int r = by + i, c = bx + tx;
+        tile[i][tx] = (r < rows && c < cols) ? A[(long)r * lda + c] : 0.f;
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int j = bx + i, k = by + tx;
+        if (j < cols && k < rows) {
+            bf16_t p1, p2, p3;
+            split3(tile[tx][i], p1, p2, p3);
+            bf16_t* o = out + (long)j * ldo + k;
+            o[0] = p1; o[plane] = p2; o[2 * plane] = p3;
+        }
+    }
+}
+
+// planes of A itself, four entries per thread (cols a multiple of 4, 16-byte aligned rows of A, 8-byte of out)
+__global__ __launch_bounds__(256) void split3_bf16_kernel(const float* __restrict__ A, long lda, int rows, int cols4,
+                                                          bf16_t* __restrict__ out, long ldo, long plane) {
+    const long total = (long)rows * cols4;
+    for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+        const int r = (int)(e / cols4), c = (int)(e % cols4) * 4;
+        const float4 v = *reinterpret_cast<const float4*>(A + (long)r * lda + c);
+        bf16_t a[4], b[4], d[4];
+        split3(v.x, a[0], b[0], d[0]); split3(v.y, a[1], b[1], d[1]);
+        split3(v.z, a[2], b[2], d[2]); split3(v.w, a[3], b[3], d[3]);
+        bf16_t* o = out + (long)r * ldo + c;
+        *reinterpret_cast<uint2*>(o) = make_uint2(a[0] | ((uint32_t)a[1] << 16), a[2] | ((uint32_t)a[3] << 16));
+        *reinterpret_cast<uint2*>(o + plane) = make_uint2(b[0] | ((uint32_t)b[1] << 16), b[2] | ((uint32_t)b[3] << 16));
+        *reinterpret_cast<uint2*>(o + 2 * plane) = make_uint2(d[0] | ((uint32_t)d[1] << 16), d[2] | ((uint32_t)d[3] << 16));
+    }
+}
+
 // dst (cols x rows) = src^T for a rows x cols bf16 matrix, 64 x 64 tiles through LDS with 16-byte loads and stores.
 // rows and cols are multiples of 64, both leading dimensions multiples of 8 and both pointers 16-byte aligned.
 // Operand preparation for G = X^T dY (Alg. 1 line 9): with both operands stored token-contiguous the product reads
@@ -489,6 +537,24 @@ hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* 
                                        hipStream_t s) {
     hipLaunchKernelGGL(split_transpose_bf16_kernel, dim3((n + 31) / 32, (koff + 31) / 32), dim3(256), 0, s, R, ldr, n,
                        RbT, ldt, koff);
+    return hipGetLastError();
+}
+
+hipError_t launch_split3_bf16(const float* A, long lda, int rows, int cols, bf16_t* out, long ldo, long plane, int transpose,
+                              hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    if (transpose) {
+        hipLaunchKernelGGL(split3_transpose_bf16_kernel, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(256), 0, s, A, lda,
+                           rows, cols, out, ldo, plane);
+        return hipGetLastError();
+    }
+    if ((cols & 3) || (lda & 3) || (ldo & 3) || (plane & 3) || (reinterpret_cast<uintptr_t>(A) & 15) ||
+        (reinterpret_cast<uintptr_t>(out) & 7))
+        return hipErrorInvalidValue;
+    const long total = (long)rows * (cols / 4);
+    long blocks = (total + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(split3_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, A, lda, rows, cols / 4, out, ldo, plane);
     return hipGetLastError();
 }
 

@@ -510,7 +510,14 @@ __device__ __forceinline__ void big_kstep(BigAcc& acc, BigFrags& f0, BigFrags& f
     big_substep<3, BUF>(acc, f1, f0, st, ad, smem, Seq{});
 }
 
-template <bool WHIP>
+// X3: the operands are three bf16 planes each (x = x1 + x2 + x3 to 24 mantissa bits, plane p at + p * a_plane / b_plane
+// elements) and the reduction runs over six segments of K indices, one per pair of planes whose product is not below
+// fp32 rounding -- (3,1) (1,3) (2,2) (2,1) (1,2) (1,1), small terms first -- into the same fp32 accumulators: an fp32
+// product on the bf16 matrix cores (each bf16 x bf16 product is exact in fp32; the three pairs left out are below
+// 2^-26 of |a| |b|).  Epilogue C = alpha * acc + beta * C.  With b_strict_lower the segments start at the tile's
+// first column (B^T vanishes on and above the diagonal) and tiles are taken column block by column block, the
+// longest reductions first.
+template <bool WHIP, bool X3 = false>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, int tiles_m, int tiles_n) {
     __shared__ __attribute__((aligned(16))) bf16_t smem[2 * TM * TLD + 2 * TN * TLD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -525,8 +532,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
     const int gid = pid / group;
     const int first_m = gid * 8;
     const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
-    const int pid_m = first_m + (pid % group) % gsz;
-    const int pid_n = (pid % group) / gsz;
+    int pid_m = first_m + (pid % group) % gsz;
+    int pid_n = (pid % group) / gsz;
+    if (X3 && g.b_strict_lower) { pid_n = bid / tiles_m; pid_m = bid % tiles_m; }
     const int m0 = pid_m * TM, n0 = pid_n * TN;
 
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
@@ -536,18 +544,38 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
     const bf16_t* pa = g.A + (long)(m0 + prow) * g.lda + pk;
     const bf16_t* pb = g.B + (long)(n0 + prow) * g.ldb + pk;
     const int wrap = g.a_kwrap;
-    const int nk = g.K / TK;           // even, >= 2
+    const int kbeg = (X3 && g.b_strict_lower) ? n0 : 0;
+    const int nk = X3 ? 6 * ((g.K - kbeg) / TK) : g.K / TK;           // even, >= 2
 
     BigAddr ad;
     ad.sa = 32 * g.lda; ad.sb = 32 * g.ldb;
     ad.aoff = (wm + lrow) * TLD + lk * 8; ad.boff = (wn + lrow) * TLD + lk * 8;
     ad.sto = prow * TLD + pk;
     // tile t (clamped to the last one: past the end a valid tile is fetched again and never used)
+    // X3: the calls below ask for tiles 0, 1, 2, ... in order, so the segment and the index inside it are carried along
+    int seg = 0, kk = kbeg;
+    long offa = 2 * g.a_plane, offb = 0;
     auto point_at = [&](int t) {
-        const int tc = t < nk ? t : nk - 1;
-        const int k0 = tc * TK;
-        ad.pa = pa + ((wrap > 0 && k0 >= wrap) ? k0 - wrap : k0);
-        ad.pb = pb + k0;
+        if constexpr (X3) {
+            ad.pa = pa + offa + kk;
+            ad.pb = pb + offb + kk;
+            kk += TK;
+            if (kk == g.K) {
+                if (seg < 5) {
+                    kk = kbeg;
+                    ++seg;
+                    offa = ((0x052 >> (2 * seg)) & 3) * g.a_plane;     // planes 3 1 2 2 1 1 of A ...
+                    offb = ((0x118 >> (2 * seg)) & 3) * g.b_plane;     // ... against planes 1 3 2 1 2 1 of B
+                } else {
+                    kk -= TK;
+                }
+            }
+        } else {
+            const int tc = t < nk ? t : nk - 1;
+            const int k0 = tc * TK;
+            ad.pa = pa + ((wrap > 0 && k0 >= wrap) ? k0 - wrap : k0);
+            ad.pb = pb + k0;
+        }
     };
 
     BigAcc acc;
@@ -588,7 +616,13 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                    C[(long)row * g.ldc + col] = acc.t[i][j][v];
+                    if constexpr (X3) {
+                        float r = g.alpha * acc.t[i][j][v];
+                        if (g.beta != 0.f) r += g.beta * C[(long)row * g.ldc + col];
+                        C[(long)row * g.ldc + col] = r;
+                    } else {
+                        C[(long)row * g.ldc + col] = acc.t[i][j][v];
+                    }
                 }
             }
         }
@@ -662,6 +696,18 @@ bool gemm_bf16_deep_fits(const GemmBf16& g) {
     const bool bvec = (reinterpret_cast<uintptr_t>(g.B) & 15) == 0 && (g.ldb & 7) == 0;
     return !g.ta && g.tb && g.splits <= 1 && g.M % BM == 0 && g.N % BN == 0 && g.K % (2 * BKD) == 0 &&
            tiles_m * tiles_n >= 256 && avec && bvec && (g.a_kwrap == 0 || (g.a_kwrap % BKD == 0 && g.a_klim == g.a_kwrap));
+}
+
+bool gemm_bf16x3_fits(int M, int N, int K) { return M > 0 && N > 0 && K > 0 && M % TM == 0 && N % TN == 0 && K % TK == 0; }
+
+hipError_t launch_gemm_bf16x3(const GemmBf16& g, hipStream_t s) {
+    if (!gemm_bf16x3_fits(g.M, g.N, g.K) || g.ta || !g.tb || g.splits > 1 || g.a_kwrap != 0 || g.whip_dyt != nullptr ||
+        (reinterpret_cast<uintptr_t>(g.A) & 15) || (reinterpret_cast<uintptr_t>(g.B) & 15) || (g.lda & 7) || (g.ldb & 7) ||
+        (g.a_plane & 7) || (g.b_plane & 7) || g.C == nullptr || (g.b_strict_lower && g.K != g.N))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_bf16_nt_big_kernel<false, true>), dim3((g.M / TM) * (g.N / TN)), dim3(256), 0, s, g, g.M / TM,
+                       g.N / TN);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s) {
