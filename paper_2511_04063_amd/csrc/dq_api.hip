@@ -115,7 +115,7 @@ namespace {
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
     size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
-           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, x3a = 0, x3b = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
+           vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, x3a = 0, x3b = 0, x3c = 0, x3d = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
 };
@@ -158,9 +158,11 @@ Layout make_layout(int n, int T) {
     L.uinv = bump(cur, nblk * kTrsmBlock * kTrsmBlock * 4);
     L.uinvo = bump(cur, (size_t)round_up(n, kTrsmOuter) * kTrsmOuter * 4);   // inverses of the outer diagonal blocks
     L.utmp = bump(cur, (size_t)round_up(n, kTrsmOuter) * 192 * 4);          // products on the way to them
-    // three bf16 planes of two n x n operands (fp32 products on the bf16 matrix cores)
+    // three bf16 planes of up to four n x n operands (fp32 products on the bf16 matrix cores)
     L.x3a = bump(cur, 3 * n2 * 2);
     L.x3b = bump(cur, 3 * n2 * 2);
+    L.x3c = bump(cur, 3 * n2 * 2);
+    L.x3d = bump(cur, 3 * n2 * 2);
     const size_t tn = (size_t)(T > 0 ? T : 1) * L.ld;
     L.Y = bump(cur, tn * 4);
     L.dY = bump(cur, tn * 4);
@@ -957,8 +959,33 @@ dq_status cayley_update_one(dq_ctx* c, const Layout& L, int n, float* R, long ld
     double* part = at<double>(c, L.losspart);
     float* scal = at<float>(c, L.scal);
     const double n3 = (double)n * n * n;
-    auto product = [&](const float* A_, long lda, int ta, const float* B_, long ldb, int tb, float* C_, long ldc,
-                       float alpha, float beta_, const float* alpha_dev) -> dq_status {
+    // As in S6, the products run on the bf16 matrix cores from three-plane splits when the shape fits (DQ_OPT_SPLIT_GEMM):
+    // `pa` holds the planes of op(A) (n x n, reduction index contiguous), `pb` those of op(B)^T; a null `A_` / `B_` means
+    // that the buffer already holds them from an earlier product.
+    const bool x3 = c->split_gemm != 0 && gemm_bf16x3_fits(n, n, n) && ld == n && (c->split_gemm == 2 || n >= 2560);
+    const long plane = (long)n * ld;
+    bf16_t* pl0 = at<bf16_t>(c, L.x3a);
+    bf16_t* pl1 = at<bf16_t>(c, L.x3b);
+    bf16_t* pl2 = at<bf16_t>(c, L.x3c);
+    bf16_t* pl3 = at<bf16_t>(c, L.x3d);
+    auto product = [&](const float* A_, long lda, int ta, bf16_t* pa, const float* B_, long ldb, int tb, bf16_t* pb,
+                       float* C_, long ldc, float alpha, float beta_, const float* alpha_dev) -> dq_status {
+        if (x3) {
+            {
+                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 10.0 * n * (double)n);
+                if (A_ != nullptr) DQ_HIP(launch_split3_bf16(A_, lda, n, n, pa, ld, plane, ta ? 1 : 0, s));
+                if (B_ != nullptr) DQ_HIP(launch_split3_bf16(B_, ldb, n, n, pb, ld, plane, tb ? 0 : 1, s));
+            }
+            GemmBf16 g;
+            g.A = pa; g.lda = ld; g.a_plane = plane;
+            g.B = pb; g.ldb = ld; g.b_plane = plane; g.tb = 1;
+            g.C = C_; g.ldc = ldc; g.M = n; g.N = n; g.K = n;
+            g.alpha = alpha; g.beta = beta_; g.alpha_dev = alpha_dev;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 12.0 * n3, 0.0);
+            DQ_HIP(launch_gemm_bf16x3(g, s));
+            return DQ_OK;
+        }
+        if (A_ == nullptr || B_ == nullptr) return DQ_ERR_NULL;
         GemmF32 g;
         g.A = A_; g.lda = lda; g.ta = ta;
         g.B = B_; g.ldb = ldb; g.tb = tb;
@@ -972,9 +999,10 @@ dq_status cayley_update_one(dq_ctx* c, const Layout& L, int n, float* R, long ld
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
         DQ_HIP(launch_cayley_momentum(M, ldm, G, ldg, n, beta, s));
     }
-    DQ_TRY(product(M, ldm, 0, R, ldr, 1, What, ld, 1.f, 0.f, nullptr));          // A = M R^T
-    DQ_TRY(product(R, ldr, 1, What, ld, 0, Tmp, ld, 1.f, 0.f, nullptr));         // R^T A
-    DQ_TRY(product(R, ldr, 0, Tmp, ld, 0, What, ld, -0.5f, 1.f, nullptr));       // W^ = A - 1/2 R (R^T A)
+    DQ_TRY(product(M, ldm, 0, pl0, R, ldr, 1, pl1, What, ld, 1.f, 0.f, nullptr));          // A = M R^T
+    DQ_TRY(product(R, ldr, 1, pl2, What, ld, 0, pl0, Tmp, ld, 1.f, 0.f, nullptr));         // R^T A
+    // (x3: the planes of R are in pl1 since the first product, those of R^T stay in pl2 for the fourth)
+    DQ_TRY(product(x3 ? nullptr : R, ldr, 0, pl1, Tmp, ld, 0, pl0, What, ld, -0.5f, 1.f, nullptr));       // W^ = A - 1/2 R (R^T A)
     const int blocks = cayley_skew_grid(n);
     if (blocks > kLossPartials) return DQ_ERR_UNSUPPORTED;
     {
@@ -982,7 +1010,7 @@ dq_status cayley_update_one(dq_ctx* c, const Layout& L, int n, float* R, long ld
         DQ_HIP(launch_cayley_skew(What, ld, n, W, ld, part, s));
         DQ_HIP(launch_cayley_alpha(part, blocks, lr, q, eps, scal, s));
     }
-    DQ_TRY(product(W, ld, 0, R, ldr, 0, M, ldm, 1.f, 0.f, nullptr));             // M = W R
+    DQ_TRY(product(W, ld, 0, pl3, x3 ? nullptr : R, ldr, 0, pl2, M, ldm, 1.f, 0.f, nullptr));             // M = W R
     {
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 2.0 * n * (double)n, 12.0 * n * (double)n);
         DQ_HIP(launch_add_scaled(Y0, ld, R, ldr, M, ldm, n, 1.f, scal, s));      // Y = R + alpha M
@@ -995,7 +1023,7 @@ dq_status cayley_update_one(dq_ctx* c, const Layout& L, int n, float* R, long ld
             DQ_HIP(launch_add_scaled(Tmp, ld, R, ldr, Ycur, ld, n, 1.f, nullptr, s));   // R + Y
             DQ_HIP(launch_copy2d(R, ldr, Ynext, ld, n, n, s));
         }
-        DQ_TRY(product(W, ld, 0, Tmp, ld, 0, Ynext, ld, 1.f, 1.f, scal + 1));    // Y <- R + alpha/2 W (R + Y)
+        DQ_TRY(product(x3 ? nullptr : W, ld, 0, pl3, Tmp, ld, 0, pl0, Ynext, ld, 1.f, 1.f, scal + 1));    // Y <- R + alpha/2 W (R + Y)
         float* t = Ycur; Ycur = Ynext; Ynext = t;
     }
     {

@@ -80,6 +80,7 @@ struct GemmBf16 {
     // C = alpha * (A B^T) + beta * C, and b_strict_lower: B^T(k, n) vanishes for k <= n (K == N), the reduction of a tile
     // starts at its first column
     long a_plane = 0, b_plane = 0; float alpha = 1.f, beta = 0.f; int b_strict_lower = 0;
+    const float* alpha_dev = nullptr;   // non-null: alpha is multiplied by this device scalar
 };
 hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
 // fp32 product from three-plane bf16 splits of both operands (launch_split3_bf16), six plane pairs accumulated in fp32 on

@@ -607,6 +607,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
     }
 
     float* C = g.C;
+    float alpha = g.alpha;
+    if constexpr (X3) { if (g.alpha_dev != nullptr) alpha *= *g.alpha_dev; }
     if (!WHIP || C != nullptr) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -617,7 +619,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
                 for (int v = 0; v < 16; ++v) {
                     const int row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
                     if constexpr (X3) {
-                        float r = g.alpha * acc.t[i][j][v];
+                        float r = alpha * acc.t[i][j][v];
                         if (g.beta != 0.f) r += g.beta * C[(long)row * g.ldc + col];
                         C[(long)row * g.ldc + col] = r;
                     } else {

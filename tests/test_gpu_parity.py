@@ -1564,6 +1564,38 @@ def test_cayley_update_against_oracle(ctx, n, ld, lr, beta, iters):
     assert ctx.dq_device_flags() == 0
 
 
+@pytest.mark.parametrize("n", [256, 512])
+def test_cayley_update_split_products(n):
+    """The same update with its six products on the bf16 matrix cores from three-plane splits (forced at this size by
+    DQ_OPT_SPLIT_GEMM = 2): the bars of the test above, and the fp32 route within rounding."""
+    g = rng(9050 + n)
+    R = random_rotation(g, n)
+    G = (g.standard_normal((n, n)) * 0.3).astype(np.float32)
+    M = (g.standard_normal((n, n)) * 0.1).astype(np.float32)
+    lr, beta, iters = 5e-2, 0.5, 3
+    Ro, Mo, ao, Wo = orc.cayley_sgd_update(R, G, M, float(np.float32(lr)), float(np.float32(beta)), 0.5, iters, 1e-8)
+    out = {}
+    c = B.Context()
+    try:
+        c.ensure_workspace(1, n, 64, B.DQ_F32)
+        for mode in (0, 2):
+            c.dq_set_option(B.DQ_OPT_SPLIT_GEMM, mode)
+            Rd, Gd, Md = dev(R.copy()), dev(G), dev(M.copy())
+            alpha = torch.zeros(1, device="cuda")
+            c.dq_cayley_update(Rd, Gd, Md, lr, beta, 0.5, iters, 1e-8, alpha)
+            assert alpha.item() == pytest.approx(ao, rel=1e-5)
+            out[mode] = (Rd.cpu().numpy(), Md.cpu().numpy())
+            assert rel(out[mode][0], Ro) < 1e-5
+            assert rel(out[mode][1], Mo) < 1e-5
+            assert rel(out[mode][0].astype(np.float64) - R, Ro - R) < 1e-3
+        assert rel(out[2][0], out[0][0]) < 1e-6
+        assert rel(out[2][1], out[0][1]) < 1e-5
+        assert c.dq_device_flags() == 0
+    finally:
+        torch.cuda.synchronize()
+        c.close()
+
+
 def test_cayley_steps_against_oracle(ctx):
     """Five consecutive calibration steps with the optimiser of Alg. 3 (fp32 X, rotation and momentum carried on the
     device): losses and the final rotation against the oracle's own five steps."""
