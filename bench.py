@@ -34,7 +34,7 @@ if ROOT not in sys.path:
 PEAK = {"fp32_mfma_tflops": 157.3, "bf16_mfma_tflops": 2500.0, "hbm_gbs": 8000.0, "fp32_valu_tflops": 78.6}
 
 # kernel whose launches make up each bracketed class (as named in the rocprofv3 summaries under profiles/)
-CLASS_KERNEL = {"gemm_f32": "gemm_f32_kernel", "gemm_bf16": "gemm_bf16_nt_deep_kernel", "whip": "whip_kernel"}
+CLASS_KERNEL = {"gemm_f32": "gemm_f32_kernel", "gemm_bf16": "gemm_bf16_nt_big_kernel", "whip": "whip_kernel"}
 
 
 def flops_per_step(n: int, T: int, b: int = 1, optimizer: str = "sgd") -> float:
@@ -217,7 +217,14 @@ def run_config(cfg_name: str, args):
                                    ("frac_bf16_mfma_peak" if bf16 else "frac_fp32_mfma_peak"): fl / ms / 1e9 / peak}
         ms = tm(lambda: ctx.dq_qr_backward(Rb, Ub, Gb, dZb))
         fl = b * 4.0 * n ** 3
-        out["qr_backward"] = {"ms": ms, "model_tflops": fl / ms / 1e9, "frac_fp32_mfma_peak": fl / ms / 1e9 / PEAK["fp32_mfma_tflops"]}
+        out["qr_backward"] = {"ms": ms, "model_tflops": fl / ms / 1e9}
+        if n % 256 == 0 and n >= 2560:
+            # 3 n^3 of the stage's model flops run on the bf16 matrix cores from three-plane splits (six times issued)
+            out["qr_backward"]["issued_bf16_tflops_of_split_products"] = b * 18.0 * n ** 3 / ms / 1e9
+            out["qr_backward"]["note"] = ("R^T G and R M run on the bf16 matrix cores from split operands; no single "
+                                          "peak prices this stage")
+        else:
+            out["qr_backward"]["frac_fp32_mfma_peak"] = fl / ms / 1e9 / PEAK["fp32_mfma_tflops"]
         ctx.dq_rotate_loss_grad(Xd, xdt, Rb, red, lossb, Gb, Yb, dYb)
         ms = tm(lambda: ctx.dq_whip_loss_grad(Yb, red, lossb, dYb, xdt))
         by = b * T * n * (4.0 + (2.0 if bf16 else 4.0))
@@ -258,12 +265,19 @@ def run_config(cfg_name: str, args):
     class_s = avg_ms * launches * 1e-3            # summed kernel time of the class over the K steps
     # algorithmic work of the class per step (the model's, not what the launches issue: forming R forward issues
     # 2 n^3 where the model counts 4/3 n^3, the rotation product issues its flops twice for the two planes of R)
+    # The library's default (DQ_OPT_SPLIT_GEMM = 1) moves the full n^3 products of the derivative (R^T G and R M: 3 n^3 of
+    # the model's 4 n^3, the triangular solve stays) and all six of the Cayley update from the fp32 to the bf16 matrix
+    # cores when n is a multiple of 256 and at least 2560 (three-plane splits, six times the flops issued): the model's
+    # flops are booked to the class that runs them.
+    split = n % 256 == 0 and n >= 2560
+    side = 12.0 if args.optimizer == "cayley" else 20.0 / 3.0
+    moved = (12.0 if args.optimizer == "cayley" else 3.0) if split else 0.0
     if dominant == B.DQ_K_GEMM_F32:
-        work = b * ((12.0 if args.optimizer == "cayley" else 20.0 / 3.0) * n ** 3 + (0.0 if bf16 else 4.0 * T * n * n))
+        work = b * ((side - moved) * n ** 3 + (0.0 if bf16 else 4.0 * T * n * n))
         roof = {"bound": "mfma", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["fp32_mfma_tflops"],
                 "unit": "TFLOP/s"}
     elif dominant == B.DQ_K_GEMM_BF16:
-        work = b * 4.0 * T * n * n
+        work = b * ((4.0 * T * n * n if bf16 else 0.0) + moved * n ** 3)
         roof = {"bound": "mfma", "achieved": work * args.steps / class_s / 1e12, "peak": PEAK["bf16_mfma_tflops"],
                 "unit": "TFLOP/s"}
     elif dominant == B.DQ_K_WHIP:
