@@ -121,11 +121,16 @@ typedef enum {
                                        call on a stream shows that the streams involved make progress independently
                                        (they do unless they share a hardware queue); otherwise events.  Every poll is
                                        bounded (DQ_FLAG_SYNC_TIMEOUT). */
-    DQ_OPT_SPLIT_GEMM = 6           /* the n x n x n fp32 products of S6 (R^T G and R M) on the bf16 matrix cores from
+    DQ_OPT_SPLIT_GEMM = 6,          /* the n x n x n fp32 products of S6 (R^T G and R M) on the bf16 matrix cores from
                                        three-plane bf16 splits of both operands (x = x1 + x2 + x3 carries 24 mantissa
                                        bits; the six plane pairs above fp32 rounding are accumulated in fp32).  0: never
                                        (fp32 matrix cores); 1 (default): when n is a multiple of 256 and at least 2560,
                                        where it is faster; 2: whenever n is a multiple of 256. */
+    DQ_OPT_FUSED_PANEL = 7          /* S1: a tall 64-column panel that follows a tall panel and is followed by one as ONE
+                                       launch whose workgroups hand over to each other through words in device memory
+                                       (bounded polls, DQ_FLAG_SYNC_TIMEOUT) instead of three dependent launches.  Only
+                                       taken where DQ_OPT_DEVICE_SYNC's hand-over is in use (not under stream capture).
+                                       0: never; 1 (default) and 2: wherever the panel qualifies. */
 } dq_option;
 dq_status dq_set_option(dq_ctx* ctx, dq_option option, int value);
 

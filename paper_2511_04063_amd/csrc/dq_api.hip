@@ -100,6 +100,9 @@ struct dq_ctx {
                                      // shape fits and is large enough to gain, 2 wherever the shape fits
     bool device_sync = true;         // the QR's streams hand over through a device word where a probe allows (else events)
     unsigned long long seq = 0;      // last value handed out for the hand-over words, which only grow
+    unsigned long long arrived = 0;  // workgroups counted so far by the one-launch panels' word (zeroed with the status word)
+    int fused_panel = 1;             // tall panels between tall panels as one launch: 0 never, 1 up to fused_panel_rows rows, 2 always
+
     struct Probed { hipStream_t s; bool ok; };
     std::vector<Probed> probed;      // per caller stream: do it and the two internal streams progress independently?
     int objective = DQ_OBJ_WHIP;     // what S4 evaluates (dq_set_objective)
@@ -445,10 +448,12 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
 }
 
 // ---------------------------------------------------------------- hand-over between the QR's streams
-// Four 8-byte words behind the status word, cleared with it: [0] panels factored, [1] trailing updates done,
-// [2] the probe's word, [3] set by a probe wait that gave up.
+// Seven 8-byte words behind the status word, cleared with it: [0] panels factored, [1] trailing updates done,
+// [2] the probe's word, [3] set by a probe wait that gave up, [4..6] the words of the one-launch panels
+// (launch_cholqr_fused).
 constexpr long kSyncLimitUs = 5L * 1000 * 1000;   // a hand-over that takes this long is a fault, not a delay
 constexpr long kProbeLimitUs = 2000;
+constexpr int kFusedPanelRows = 8192;   // tallest panel that takes the one-launch route by default
 unsigned long long* sync_words(dq_ctx* c) { return reinterpret_cast<unsigned long long*>(c->ws + 128); }
 
 // Device-side hand-over needs the consumer's wait kernel and the producer's signal kernel to run at the same time.
@@ -566,6 +571,24 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
             const bool fused_la = nla == kPanel;
             const bool next_tall = fused_la && m2 >= c->chol_min_m &&
                                    cholpanel_supported(Ap + (long)jb * ld + jb, ld, m2, m2 < nb ? m2 : nb);
+            // ... and between two such panels the whole route is one launch whose workgroups hand over to each other
+            const int fused_wgs = (dsync && gram_ready && fused_la && next_tall && c->fused_panel != 0 &&
+                                   (c->fused_panel == 2 || m <= kFusedPanelRows))
+                                      ? cholqr_fused_workgroups(m) : 0;
+            if (fused_wgs > 0) {
+                HandOver ho;
+                if (last_trailing >= 0) {
+                    ho.wait_word = words + 1; ho.wait_value = seq0 + last_trailing + 1;
+                    ho.limit_us = kSyncLimitUs; ho.flags = flags;
+                }
+                ho.signal_word = words; ho.signal_value = seq0 + p + 1;
+                signalled = true;
+                c->arrived += (unsigned long long)fused_wgs;
+                LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb + 4.0 * m * (double)jb * nla, 0.0);
+                DQ_HIP(launch_cholqr_fused(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags, words + 4,
+                                           seq0 + p + 1, c->arrived, kSyncLimitUs, sA, &ho));
+                gram_ready = true;
+            } else {
             {
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb, 0.0);
                 DQ_HIP(launch_cholqr_factor(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags,
@@ -595,6 +618,7 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
                 const float* Wa = nullptr;
                 DQ_TRY(refl_project(c, sA, L, bufA, Yp, kPanel, m, jb, Ap + jb, ld, nla, 0, &Wa, kMaxSplit, nullptr, 0));
                 DQ_TRY(refl_update(c, sA, L, Ap, ld, Wa, m, jb, Ap + jb, ld, nla));
+            }
             }
         } else {
             gram_ready = false;
@@ -1222,6 +1246,7 @@ dq_status dq_set_workspace(dq_ctx* c, void* dptr, size_t bytes) {
     c->ws = static_cast<char*>(dptr);
     c->ws_bytes = bytes;
     DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
+    c->arrived = 0;
     return DQ_OK;
 }
 
@@ -1231,6 +1256,7 @@ dq_status dq_device_flags(dq_ctx* c, unsigned* host_out) {
     DQ_HIP(hipMemcpyAsync(host_out, c->ws, sizeof(unsigned), hipMemcpyDeviceToHost, c->stream));
     DQ_HIP(hipStreamSynchronize(c->stream));
     DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
+    c->arrived = 0;
     return DQ_OK;
 }
 
@@ -1481,6 +1507,10 @@ dq_status dq_set_option(dq_ctx* c, dq_option option, int value) {
         case DQ_OPT_SINGLE_STREAM: c->single_stream = value != 0; return DQ_OK;
         case DQ_OPT_FUSED_WHIP: c->fused_whip = value != 0; return DQ_OK;
         case DQ_OPT_DEVICE_SYNC: c->device_sync = value != 0; return DQ_OK;
+        case DQ_OPT_FUSED_PANEL:
+            if (value < 0 || value > 2) return DQ_ERR_SHAPE;
+            c->fused_panel = value;
+            return DQ_OK;
         case DQ_OPT_SPLIT_GEMM:
             if (value < 0 || value > 2) return DQ_ERR_SHAPE;
             c->split_gemm = value;

@@ -802,18 +802,15 @@ __device__ void fallback_finish(const float* __restrict__ A, long lda, int m, co
 // for the rows below the block: Mm = (U_lu U2)^-1 (V = Q1 Mm) and Mm2 = Mm T (Yp = Q1 Mm2).
 // Otherwise (*fb = 1, DQ_FLAG_ILLCOND_PANEL raised) the workgroup factors the whole panel with the Householder
 // panel code and writes V, the triangular factor, tau, T and all of Yp itself.
-__global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict__ part, int nparts, float* q1,
-                                                         const float* __restrict__ U1, float* A, long lda, int m,
-                                                         float* __restrict__ Tout, float* __restrict__ Yp,
-                                                         float* __restrict__ Mm, float* __restrict__ Mm2,
-                                                         float* __restrict__ tau, float* __restrict__ tslices,
-                                                         unsigned* __restrict__ fb, unsigned* __restrict__ status,
-                                                         unsigned long long* ready) {
-    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
-    if (threadIdx.x == 0) *ready = 0ull;   // "U1^-1 of the next panel is there": set by this panel's la_update_chol_kernel
-    __shared__ float Bs[5 * B64 * LS];
-    __shared__ float sg[B64];
-    __shared__ float redw[4];
+// The body: NSUM threads enter, those beyond the first NTHR return once the partials are summed (they take part in no
+// later barrier); Bs: 5 * 64 * LS floats of LDS, sg: 64, redw: 4.
+__device__ __forceinline__ void hr_finish_body(const float* __restrict__ part, int nparts, float* q1,
+                                               const float* __restrict__ U1, float* A, long lda, int m,
+                                               float* __restrict__ Tout, float* __restrict__ Yp,
+                                               float* __restrict__ Mm, float* __restrict__ Mm2,
+                                               float* __restrict__ tau, float* __restrict__ tslices,
+                                               unsigned* __restrict__ fb, unsigned* __restrict__ status, float* Bs,
+                                               float* sg, float* redw) {
     float* B0 = Bs;
     float* B1 = Bs + B64 * LS;
     float* B2 = Bs + 2 * B64 * LS;
@@ -941,6 +938,302 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
     }
 }
 
+__global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict__ part, int nparts, float* q1,
+                                                         const float* __restrict__ U1, float* A, long lda, int m,
+                                                         float* __restrict__ Tout, float* __restrict__ Yp,
+                                                         float* __restrict__ Mm, float* __restrict__ Mm2,
+                                                         float* __restrict__ tau, float* __restrict__ tslices,
+                                                         unsigned* __restrict__ fb, unsigned* __restrict__ status,
+                                                         unsigned long long* ready) {
+    __builtin_amdgcn_s_setprio(3);   // the panel chain is latency-critical: win issue slots from co-resident GEMM waves
+    if (threadIdx.x == 0) *ready = 0ull;   // "U1^-1 of the next panel is there": set by this panel's la_update_chol_kernel
+    __shared__ float Bs[5 * B64 * LS];
+    __shared__ float sg[B64];
+    __shared__ float redw[4];
+    hr_finish_body(part, nparts, q1, U1, A, lda, m, Tout, Yp, Mm, Mm2, tau, tslices, fb, status, Bs, sg, redw);
+}
+
+
+// ------------------------------------------------------------------------------------------------------------
+// One launch per panel between consecutive tall panels: hr_finish_kernel, ts_mul_proj_kernel and
+// la_update_chol_kernel as the phases of ONE kernel, for panels whose rows below the top block make one 128-row tile
+// per workgroup.  What the two kernel boundaries ordered is ordered by three 8-byte words that only grow (agent-scope
+// release / acquire, every poll bounded by the device clock; see HandOver):
+//   ready1 = epoch    workgroup 0 has finished the panel's small step (Mm, Mm2, T, the top block, *fb are written);
+//   count >= target   all nproj workgroups have written their rows of V and Yp and their partials of the projection and of
+//                     C^T C (each adds 1; target = the sum over all launches so far, kept by the host);
+//   ready2 = epoch    the extra workgroup has U1 and U1^-1 of the next panel.
+// Workgroup 0: the small step, then the top 64 rows.  Workgroups 1 .. nproj - 1: one tile of rows each; while workgroup 0
+// works they fetch their rows of Q1 and of the look-ahead columns C and form their part of C^T C; the rows of C stay in
+// LDS through the update and the next panel's second step.  Workgroup nproj: the next panel's first small step, as in
+// la_update_chol_kernel.  The nproj + 1 <= 34 workgroups run at the same time on 256 compute units; a poll that runs
+// into its limit raises DQ_FLAG_SYNC_TIMEOUT and goes on, so every wavefront ends.
+struct PanelSync {
+    unsigned long long* ready1; unsigned long long* count; unsigned long long* ready2;
+    unsigned long long epoch, target;
+    long long limit_ticks;
+};
+
+__device__ __forceinline__ void panel_wait(const unsigned long long* word, unsigned long long value, const PanelSync& ps,
+                                           unsigned* status, int tid) {
+    if (tid == 0) (void)handover_wait(word, value, ps.limit_ticks, status);
+    __syncthreads();
+}
+
+// W2 = sum of the nproj projection partials -> Ws (row stride LS); NTHR threads, partials in groups of 8
+__device__ __forceinline__ void sum_projection(const float* __restrict__ wpart, int nproj, float* Ws, int tid) {
+    float4 s4[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) s4[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z0 = 0; z0 < nproj; z0 += 8) {
+        float4 t[4][8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int z = 0; z < 8; ++z)
+                t[q][z] = (z0 + z < nproj)
+                              ? *reinterpret_cast<const float4*>(wpart + (long)(z0 + z) * B64 * B64 + 4 * (tid + NTHR * q))
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int z = 0; z < 8; ++z) {
+                s4[q].x += t[q][z].x; s4[q].y += t[q][z].y; s4[q].z += t[q][z].z; s4[q].w += t[q][z].w;
+            }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int e = 4 * (tid + NTHR * q);
+        float* d = Ws + (e >> 6) * LS + (e & 63);
+        d[0] = s4[q].x; d[1] = s4[q].y; d[2] = s4[q].z; d[3] = s4[q].w;
+    }
+}
+
+constexpr int kFusedPool = 2 * RT * LS + 2 * B64 * B64;   // floats of LDS: two row tiles and two 64 x 64 matrices
+
+__global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, int nparts, float* q1,
+                                                           float* U1, float* U1inv, float* A, long lda, int m,
+                                                           float* __restrict__ Tout, float* Yp, float* Mm, float* Mm2,
+                                                           float* __restrict__ tau, float* __restrict__ tslices,
+                                                           unsigned* fb, unsigned* status, float* wpart, float* gpart,
+                                                           float* ctop, int nproj, PanelSync ps, HandOver ho) {
+    __builtin_amdgcn_s_setprio(3);
+    __shared__ __attribute__((aligned(16))) float pool[kFusedPool];
+    __shared__ float sg[B64];
+    __shared__ float redw[4];
+    static_assert(kFusedPool >= 5 * B64 * LS, "the small step's five matrices must fit the pool");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lk = lane >> 5;
+    const int qi = (wave >> 1) & 1, qj = wave & 1;
+    const int b = blockIdx.x;
+    float* C = A + B64;
+    float* Xs = pool;                       // a 128-row tile
+    float* Cs = pool + RT * LS;             // a 128-row tile
+    float* Ms = pool + 2 * RT * LS;         // 64 x 64, row stride 64
+    float* Ms2 = Ms + B64 * B64;
+    float* Ws = Ms;                         // 64 x 64, row stride LS (over Ms and the head of Ms2)
+
+    if (b == nproj) {
+        // ---- the next panel's U1 = chol(G), U1^-1 (see la_update_chol_kernel), once every partial is there
+        panel_wait(ps.count, ps.target, ps, status, tid);
+        float* S0 = pool;                   // V_top
+        float* S1 = pool + B64 * LS;        // C_top, then C'_top
+        float* Wx = pool + 2 * B64 * LS;
+        float* Gs = pool + 3 * B64 * LS;
+        float4 vt[4], ct[4];
+        if (tid < NTHR) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int e = 4 * (tid + NTHR * q);
+                vt[q] = *reinterpret_cast<const float4*>(A + (long)(e >> 6) * lda + (e & 63));
+                ct[q] = *reinterpret_cast<const float4*>(ctop + e);
+            }
+        }
+        sum_partials_pair<NSUM, 11>(wpart, gpart, nproj, Wx, Gs, tid);
+        if (tid >= NTHR) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = 4 * (tid + NTHR * q);
+            float* d0 = S0 + (e >> 6) * LS + (e & 63);
+            float* d1 = S1 + (e >> 6) * LS + (e & 63);
+            d0[0] = vt[q].x; d0[1] = vt[q].y; d0[2] = vt[q].z; d0[3] = vt[q].w;
+            d1[0] = ct[q].x; d1[1] = ct[q].y; d1[2] = ct[q].z; d1[3] = ct[q].w;
+        }
+        __syncthreads();
+        const f32x16 vw = lds_mma<2>(S0, Wx, nullptr, qi, qj, 0, B64, lrow, lk);   // V_top (unit lower) W2
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) S1[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + 32 * qj + lrow] -= vw[v];
+        __syncthreads();
+        if (qi <= qj) {
+            f32x16 gt = zero16();
+#pragma unroll 8
+            for (int r = 0; r < B64; r += 2)
+                gt = MFMA32(S1[(r + lk) * LS + 32 * qi + lrow], S1[(r + lk) * LS + 32 * qj + lrow], gt);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Gs[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + 32 * qj + lrow] -= gt[v];
+        }
+        __syncthreads();
+        chol_upper_64(Gs, tid);
+        tri_inv_upper_64<false>(Gs, Wx, tid);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            U1[e] = Gs[(e >> 6) * LS + (e & 63)];
+            U1inv[e] = Wx[(e >> 6) * LS + (e & 63)];
+        }
+        __syncthreads();
+        if (tid == 0) handover_signal(ps.ready2, ps.epoch);
+        return;
+    }
+
+    if (b == 0) {
+        // ---- the panel's small step, then the top 64 rows
+        hr_finish_body(part, nparts, q1, U1, A, lda, m, Tout, Yp, Mm, Mm2, tau, tslices, fb, status, pool, sg, redw);
+        if (tid >= NTHR) return;
+        __syncthreads();
+        if (tid == 0) handover_signal(ps.ready1, ps.epoch);
+        if (ho.wait_word != nullptr) {      // the look-ahead columns must have received the previous trailing update
+            if (tid == 0) (void)handover_wait(ho.wait_word, ho.wait_value, (long long)ho.limit_us * 100, ho.flags);
+            __syncthreads();
+        }
+        load_tile(Yp, B64, 0, B64, Xs, tid);
+        load_tile(C, lda, 0, B64, Cs, tid);
+        __syncthreads();
+        f32x16 acc = zero16(), accg = zero16();
+        proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+        gram_tile(Cs, accg, qi, qj, lrow, lk);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + NTHR * q;
+            ctop[e] = Cs[(e >> 6) * LS + (e & 63)];
+        }
+        store_partial(wpart, acc, qi, qj, lrow, lk);
+        store_partial(gpart, accg, qi, qj, lrow, lk);
+        __syncthreads();
+        if (tid == 0) (void)__hip_atomic_fetch_add(ps.count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        // the reflectors as stored, unit lower triangular, for the update of the top rows
+        load_tile(A, lda, 0, B64, Xs, tid);
+        __syncthreads();
+        mask_unit_lower(Xs, tid);
+        panel_wait(ps.count, ps.target, ps, status, tid);
+        // the panel's reflectors and Yp are complete: the other streams may go on
+        if (ho.signal_word != nullptr && tid == 0) handover_signal(ho.signal_word, ho.signal_value);
+        sum_projection(wpart, nproj, Ws, tid);
+        __syncthreads();
+        f32x16 q0 = zero16(), q1v = zero16();
+        mul_tile_full(Xs, Ws, q0, q1v, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            if (r < B64) {
+                C[(long)r * lda + lrow] = Cs[r * LS + lrow] - q0[v];
+                C[(long)r * lda + 32 + lrow] = Cs[r * LS + 32 + lrow] - q1v[v];
+            }
+        }
+        return;
+    }
+
+    // ---- one tile of rows below the top block
+    if (tid >= NTHR) return;
+    if (ho.wait_word != nullptr) {
+        if (tid == 0) (void)handover_wait(ho.wait_word, ho.wait_value, (long long)ho.limit_us * 100, ho.flags);
+        __syncthreads();
+    }
+    const int row0 = B64 + (b - 1) * RT;
+    load_tile(q1, B64, row0, m, Xs, tid);
+    load_tile(C, lda, row0, m, Cs, tid);
+    __syncthreads();
+    f32x16 accg = zero16();
+    gram_tile(Cs, accg, qi, qj, lrow, lk);          // C_rows^T C_rows of the columns BEFORE the update
+    panel_wait(ps.ready1, ps.epoch, ps, status, tid);
+    const bool fell_back = *fb != 0u;
+    f32x16 v0 = zero16(), v1 = zero16();            // this wavefront's 32 rows of V
+    if (!fell_back) {
+        load_small64(Mm, Ms, tid);
+        load_small64(Mm2, Ms2, tid);
+        __syncthreads();
+        mul_tile(Xs, Ms, v0, v1, wave, lrow, lk);
+        f32x16 y0 = zero16(), y1 = zero16();
+        mul_tile(Xs, Ms2, y0, y1, wave, lrow, lk);
+        // each wavefront only read its own 32 rows of the tile: it may overwrite them with Yp right away
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            Xs[rl * LS + lrow] = y0[v];
+            Xs[rl * LS + 32 + lrow] = y1[v];
+            if (row0 + rl < m) {
+                A[(long)(row0 + rl) * lda + lrow] = v0[v];
+                A[(long)(row0 + rl) * lda + 32 + lrow] = v1[v];
+                Yp[(long)(row0 + rl) * B64 + lrow] = y0[v];
+                Yp[(long)(row0 + rl) * B64 + 32 + lrow] = y1[v];
+            }
+        }
+    } else {
+        load_tile(Yp, B64, row0, m, Xs, tid);       // the fallback wrote V and Yp itself
+    }
+    __syncthreads();
+    {
+        f32x16 acc = zero16();
+        proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
+        store_partial(wpart + (long)b * B64 * B64, acc, qi, qj, lrow, lk);
+        store_partial(gpart + (long)b * B64 * B64, accg, qi, qj, lrow, lk);
+    }
+    __syncthreads();                                // every wavefront is done with Yp in Xs; all partials are stored
+    if (tid == 0) (void)__hip_atomic_fetch_add(ps.count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (!fell_back) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            Xs[rl * LS + lrow] = v0[v];
+            Xs[rl * LS + 32 + lrow] = v1[v];
+        }
+    } else {
+        load_tile(A, lda, row0, m, Xs, tid);
+    }
+    panel_wait(ps.count, ps.target, ps, status, tid);
+    sum_projection(wpart, nproj, Ws, tid);
+    __syncthreads();
+    {   // C_rows -= V_rows W2: to memory and, for the next panel's second step, kept in LDS
+        f32x16 q0 = zero16(), q1v = zero16();
+        mul_tile_full(Xs, Ws, q0, q1v, wave, lrow, lk);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            const float c0 = Cs[rl * LS + lrow] - q0[v], c1 = Cs[rl * LS + 32 + lrow] - q1v[v];
+            Cs[rl * LS + lrow] = c0;
+            Cs[rl * LS + 32 + lrow] = c1;
+            if (row0 + rl < m) {
+                C[(long)(row0 + rl) * lda + lrow] = c0;
+                C[(long)(row0 + rl) * lda + 32 + lrow] = c1;
+            }
+        }
+    }
+    // ---- the next panel's second step for these rows: Q1 = C' U1^-1 and the partial of Q1^T Q1
+    panel_wait(ps.ready2, ps.epoch, ps, status, tid);        // (its barrier also ends the reads of Ws)
+    load_small64(U1inv, Ms, tid);
+    __syncthreads();
+    {
+        f32x16 q0 = zero16(), q1v = zero16();
+        mul_tile(Cs, Ms, q0, q1v, wave, lrow, lk);
+        const int mn = m - B64, r0n = row0 - B64;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 32 * wave + 8 * (v >> 2) + 4 * lk + (v & 3);
+            Cs[rl * LS + lrow] = q0[v];                      // own rows only, as above
+            Cs[rl * LS + 32 + lrow] = q1v[v];
+            if (r0n + rl < mn) {
+                q1[(long)(r0n + rl) * B64 + lrow] = q0[v];
+                q1[(long)(r0n + rl) * B64 + 32 + lrow] = q1v[v];
+            }
+        }
+    }
+    __syncthreads();
+    f32x16 acc2 = zero16();
+    gram_tile(Cs, acc2, qi, qj, lrow, lk);
+    store_partial(gpart + (long)(b - 1) * B64 * B64, acc2, qi, qj, lrow, lk);
+}
+
 }  // namespace
 
 size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 2) * B64 * B64 + 5 * B64 * B64 + 64; }
@@ -1020,6 +1313,30 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
     else
         hipLaunchKernelGGL(la_update_chol_kernel<NTHR>, dim3(nparts + 1 + (next_gram ? 1 : 0)), dim3(NTHR), 0, s, A, lda, m,
                            ts.wpart, nparts + 1, tpw, gpart, ts.ctop, ts.U1, ts.U1inv, q1, ts.ready, status, h);
+    return hipGetLastError();
+}
+
+int cholqr_fused_workgroups(int m) {
+    int tpw, nparts;
+    tall_split(m - B64, tpw, nparts);
+    return tpw == 1 ? nparts + 1 : 0;
+}
+
+hipError_t launch_cholqr_fused(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch, float* tau,
+                               float* tslices, unsigned* status, unsigned long long* words, unsigned long long epoch,
+                               unsigned long long target, long limit_us, hipStream_t s, const HandOver* ho) {
+    if (!cholpanel_supported(A, lda, m, B64) || m < 2 * B64) return hipErrorInvalidValue;
+    const int nproj = cholqr_fused_workgroups(m);
+    if (nproj < 2 || nproj > kCholMaxParts + 1) return hipErrorInvalidValue;
+    const TallScratch ts(scratch);
+    int tpw, nparts;
+    tall_split(m, tpw, nparts);          // the partials of Q1^T Q1 that the previous panel's kernels left
+    PanelSync ps;
+    ps.ready1 = words; ps.count = words + 1; ps.ready2 = words + 2;
+    ps.epoch = epoch; ps.target = target; ps.limit_ticks = (long long)limit_us * 100;
+    const HandOver h = ho != nullptr ? *ho : HandOver();
+    hipLaunchKernelGGL(panel_fused_kernel, dim3(nproj + 1), dim3(NSUM), 0, s, ts.part, nparts, q1, ts.U1, ts.U1inv, A, lda,
+                       m, Tout, Yp, ts.Mm, ts.Mm2, tau, tslices, ts.fb, status, ts.wpart, ts.part, ts.ctop, nproj, ps, h);
     return hipGetLastError();
 }
 

@@ -544,6 +544,7 @@ def test_qr_orth_hand_over_by_events_and_by_device_word(n):
         c.ensure_workspace(1, n, 64, B.DQ_F32)
         try:
             c.dq_set_option(B.DQ_OPT_DEVICE_SYNC, mode)
+            c.dq_set_option(B.DQ_OPT_FUSED_PANEL, 0)     # the same launches in both modes (the one-launch panels need mode 1)
             got = []
             for rep in range(3):
                 got.append(run_qr(c, Z))
@@ -560,6 +561,41 @@ def test_qr_orth_hand_over_by_events_and_by_device_word(n):
     Ro, Uo = orc.qr_orth(Z)
     assert rel(out[1][1], Uo) < 1e-4
     assert rel(out[1][0], Ro) < max(1e-4, 2e-7 * np.linalg.cond(Z.astype(np.float64)))
+
+
+@pytest.mark.parametrize("n", [450, 1030, 1536])
+def test_qr_orth_one_launch_panels(n):
+    """Tall panels between tall panels as ONE launch whose workgroups hand over to each other through words in device
+    memory (DQ_OPT_FUSED_PANEL), against the three dependent launches: both to the bars of the oracle comparison and
+    within rounding of each other; repeated calls give the same bits, also after a read of the status word (which
+    clears the words and restarts their counts)."""
+    Z = rng(4400 + n).standard_normal((n, n)).astype(np.float32)
+    Ro, Uo = orc.qr_orth(Z)
+    cond = np.linalg.cond(Z.astype(np.float64))
+    out = {}
+    for mode in (0, 2):
+        c = B.Context()
+        c.ensure_workspace(1, n, 64, B.DQ_F32)
+        try:
+            c.dq_set_option(B.DQ_OPT_FUSED_PANEL, mode)
+            got = []
+            for rep in range(4):
+                got.append(run_qr(c, Z))
+                if rep == 1:
+                    assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            for R, U in got[1:]:
+                assert np.array_equal(R, got[0][0]) and np.array_equal(U, got[0][1])
+            R, U = got[0]
+            assert np.abs(R.astype(np.float64).T @ R.astype(np.float64) - np.eye(n)).max() < 1e-5
+            assert rel(U, Uo) < 1e-4
+            assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+            out[mode] = got[0]
+        finally:
+            torch.cuda.synchronize()
+            c.close()
+    assert rel(out[2][1], out[0][1]) < 1e-5
+    assert rel(out[2][0], out[0][0]) < max(1e-5, 2e-8 * cond)
 
 
 def test_stream_hand_over_probe_is_bounded():
