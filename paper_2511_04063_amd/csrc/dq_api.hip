@@ -101,6 +101,7 @@ struct dq_ctx {
     bool device_sync = true;         // the QR's streams hand over through a device word where a probe allows (else events)
     unsigned long long seq = 0;      // last value handed out for the hand-over words, which only grow
     unsigned long long arrived = 0;  // workgroups counted so far by the one-launch panels' word (zeroed with the status word)
+    unsigned long long arrived_rows = 0;   // ... and those below the top block, counted by a word of their own
     int fused_panel = 1;             // tall panels between tall panels as one launch: 0 never, 1 up to fused_panel_rows rows, 2 always
 
     struct Probed { hipStream_t s; bool ok; };
@@ -584,9 +585,10 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
                 ho.signal_word = words; ho.signal_value = seq0 + p + 1;
                 signalled = true;
                 c->arrived += (unsigned long long)fused_wgs;
+                c->arrived_rows += (unsigned long long)(fused_wgs - 1);
                 LaunchScope sc(&c->prof, sA, DQ_K_PANEL, 2.0 * m * (double)jb * jb + 4.0 * m * (double)jb * nla, 0.0);
                 DQ_HIP(launch_cholqr_fused(Ap, ld, m, Tp, Yp, vs, at<float>(c, L.cq), tau + k0, tsl, flags, words + 4,
-                                           seq0 + p + 1, c->arrived, kSyncLimitUs, sA, &ho));
+                                           seq0 + p + 1, c->arrived, c->arrived_rows, kSyncLimitUs, sA, &ho));
                 gram_ready = true;
             } else {
             {
@@ -1247,6 +1249,7 @@ dq_status dq_set_workspace(dq_ctx* c, void* dptr, size_t bytes) {
     c->ws_bytes = bytes;
     DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
     c->arrived = 0;
+    c->arrived_rows = 0;
     return DQ_OK;
 }
 
@@ -1257,6 +1260,7 @@ dq_status dq_device_flags(dq_ctx* c, unsigned* host_out) {
     DQ_HIP(hipStreamSynchronize(c->stream));
     DQ_HIP(launch_fill_u32(reinterpret_cast<unsigned*>(c->ws), 64, 0u, c->stream));
     c->arrived = 0;
+    c->arrived_rows = 0;
     return DQ_OK;
 }
 

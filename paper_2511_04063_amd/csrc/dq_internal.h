@@ -171,14 +171,16 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
                                 int next_gram, unsigned* status, hipStream_t s, const HandOver* ho = nullptr);
 
 // launch_cholqr_factor (have_gram != 0) and launch_cholqr_finish (lookahead != 0, next_gram != 0) as ONE launch whose
-// workgroups hand over to each other through three 8-byte words at `words` (zero before the first use, then only
+// workgroups hand over to each other through four 8-byte words at `words` (zero before the first use, then only
 // growing): [0] and [2] take `epoch`, a value larger than any used before; [1] counts workgroups: `target` is the sum of
-// cholqr_fused_workgroups(m) over every launch on these words so far, this one included.  Polls give up after limit_us
+// cholqr_fused_workgroups(m) over every launch on these words so far, this one included; [3] counts the workgroups below
+// the top block: `target_rows` is the sum of cholqr_fused_workgroups(m) - 1 likewise.  Polls give up after limit_us
 // (DQ_FLAG_SYNC_TIMEOUT in *status).  cholqr_fused_workgroups(m) == 0: the panel does not fit this launch.
 int cholqr_fused_workgroups(int m);
 hipError_t launch_cholqr_fused(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch, float* tau,
                                float* tslices, unsigned* status, unsigned long long* words, unsigned long long epoch,
-                               unsigned long long target, long limit_us, hipStream_t s, const HandOver* ho);
+                               unsigned long long target, unsigned long long target_rows, long limit_us, hipStream_t s,
+                               const HandOver* ho);
 
 // T (kPanel x kPanel, upper, zero beyond jb) of the compact-WY form from the slice T factors and the split-K
 // partials of V^T [V | C] (gpart[z] at stride, leading dimension ldp: jb Gram columns, then nla columns of V^T C).

@@ -263,27 +263,62 @@ __device__ __forceinline__ void tri_inv_upper_64_pair(const float* U0, float* X0
     __syncthreads();
 }
 
-// This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (multiples of 32), both
-// operands in LDS.  AMODE 1: entries of A below its diagonal are taken as zero; AMODE 2: A is taken as unit lower
-// triangular (stored diagonal and upper part ignored); AMODE 0: as stored.
+// This wavefront's 32 x 32 quadrant (qi, qj) of  A diag(kscale) B  over k in [klo, khi) (multiples of 32, at most 64
+// apart), both operands in LDS.  AMODE 1: entries of A below its diagonal are taken as zero; AMODE 2: A is taken as unit
+// lower triangular (stored diagonal and upper part ignored); AMODE 0: as stored.
+// All operands of a product are requested before its first matrix-core instruction: a single wavefront per SIMD has
+// nothing else to hide the LDS latency with, and the compiler otherwise waits for every pair of operands in turn.
+template <int AMODE, bool SCALE>
+__device__ __forceinline__ void lds_mma_fetch(const float* A, const float* Bm, const float* kscale, int row, int col,
+                                              int k0, int lk, float (&a)[16], float (&b)[16]) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int k = k0 + 2 * u + lk;
+        a[u] = A[row * LS + k];
+        b[u] = Bm[k * LS + col];
+    }
+    if (SCALE) {
+        float s[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s[u] = kscale[k0 + 2 * u + lk];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int k = k0 + 2 * u + lk;
+            if (AMODE == 1 && k < row) a[u] = 0.f;
+            if (AMODE == 2) a[u] = (k < row) ? a[u] : (k == row ? 1.f : 0.f);
+            a[u] *= s[u];
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int k = k0 + 2 * u + lk;
+            if (AMODE == 1 && k < row) a[u] = 0.f;
+            if (AMODE == 2) a[u] = (k < row) ? a[u] : (k == row ? 1.f : 0.f);
+        }
+    }
+}
+
 template <int AMODE>
 __device__ __forceinline__ f32x16 lds_mma(const float* A, const float* Bm, const float* kscale, int qi, int qj,
                                           int klo, int khi, int lrow, int lk) {
     f32x16 acc = zero16();
-    const int row = 32 * qi + lrow;
-    for (int k0 = klo; k0 < khi; k0 += 16) {
-        float a[8], b[8];
+    if (khi <= klo) return acc;
+    const int row = 32 * qi + lrow, col = 32 * qj + lrow;
+    const bool two = khi - klo > 32;                      // the same for every lane of the wavefront
+    float a0[16], b0[16], a1[16], b1[16];
+    if (kscale != nullptr) {
+        lds_mma_fetch<AMODE, true>(A, Bm, kscale, row, col, klo, lk, a0, b0);
+        if (two) lds_mma_fetch<AMODE, true>(A, Bm, kscale, row, col, klo + 32, lk, a1, b1);
+    } else {
+        lds_mma_fetch<AMODE, false>(A, Bm, kscale, row, col, klo, lk, a0, b0);
+        if (two) lds_mma_fetch<AMODE, false>(A, Bm, kscale, row, col, klo + 32, lk, a1, b1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int k = k0 + 2 * u + lk;
-            a[u] = A[row * LS + k];
-            if (AMODE == 1 && k < row) a[u] = 0.f;
-            if (AMODE == 2) a[u] = (k < row) ? a[u] : (k == row ? 1.f : 0.f);
-            if (kscale != nullptr) a[u] *= kscale[k];
-            b[u] = Bm[k * LS + 32 * qj + lrow];
-        }
+    for (int u = 0; u < 16; ++u) acc = MFMA32(a0[u], b0[u], acc);
+    if (two) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc = MFMA32(a[u], b[u], acc);
+        for (int u = 0; u < 16; ++u) acc = MFMA32(a1[u], b1[u], acc);
     }
     return acc;
 }

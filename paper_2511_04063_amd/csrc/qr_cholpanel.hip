@@ -357,6 +357,34 @@ __device__ __forceinline__ void sum_partials(const float* __restrict__ part, int
     __syncthreads();
 }
 
+// The sum of n partials (contiguous, 4096 floats each) left in registers: thread tid of NS holds the 16-byte pieces
+// 4 (tid + NS q).  FULL: all four quadrants; otherwise the lower-left 32 x 32 quadrant is skipped (zero).  No barrier.
+template <int NS, int ZB, bool FULL = false>
+__device__ __forceinline__ void sum_partials_regs(const float* __restrict__ part, int n, float4 (&s)[B64 * B64 / 4 / NS],
+                                                  int tid) {
+    constexpr int PER = B64 * B64 / 4 / NS;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) s[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z0 = 0; z0 < n; z0 += ZB) {
+        float4 t[PER][ZB];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = 4 * (tid + NS * q);
+            const bool used = FULL || !((e >> 6) >= 32 && (e & 63) < 32);
+#pragma unroll
+            for (int z = 0; z < ZB; ++z)
+                t[q][z] = (used && z0 + z < n) ? *reinterpret_cast<const float4*>(part + (long)(z0 + z) * B64 * B64 + e)
+                                               : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+#pragma unroll
+            for (int z = 0; z < ZB; ++z) {
+                s[q].x += t[q][z].x; s[q].y += t[q][z].y; s[q].z += t[q][z].z; s[q].w += t[q][z].w;
+            }
+    }
+}
+
 // The two sums of la_update_chol_kernel's extra workgroup in the same rounds of loads:  Wm = sum of the n partials at
 // wp (all four quadrants),  Gm = sum of the n partials at gp (quadrants on and above the diagonal; the lower-left one is
 // set to zero).  NS threads, ZB partials of each in flight per 16-byte piece; ends with a barrier.
@@ -411,16 +439,22 @@ __device__ __forceinline__ void rank8_update(float* Wm, int k0, int lim, int qi,
     if (SYM && qi > qj) return;                                        // below the diagonal: never read
     const int i = 32 * qi + lrow, j = 32 * qj + lrow;
     float a[4], b[4];
+    f32x16 acc;
+    // all 24 values are requested before the first one is used (one wavefront per SIMD: nothing else hides the latency)
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) {
         const int k = k0 + 2 * s4 + lk;
-        const float av = SYM ? Wm[k * LS + i] : Wm[i * LS + k];
-        a[s4] = (i >= lim) ? -av : 0.f;
-        b[s4] = (j >= lim) ? Wm[k * LS + j] : 0.f;
+        a[s4] = SYM ? Wm[k * LS + i] : Wm[i * LS + k];
+        b[s4] = Wm[k * LS + j];
     }
-    f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = Wm[(32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3)) * LS + j];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        a[s4] = (i >= lim) ? -a[s4] : 0.f;
+        b[s4] = (j >= lim) ? b[s4] : 0.f;
+    }
 #pragma unroll
     for (int s4 = 0; s4 < 4; ++s4) acc = MFMA32(a[s4], b[s4], acc);
 #pragma unroll
@@ -470,12 +504,15 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
 // (decided on the partially eliminated matrix), so that each pivot has modulus >= 1.  On return the strict lower
 // triangle holds L (unit diagonal implied), the upper triangle U, and sg[0..64) the signs.
 // Blocked by 8.  The first wavefront holds the block column k0 .. k0+7 in registers, one row per lane, and eliminates
-// it with lane broadcasts; the same wavefront then solves the block row to the right (one column per lane, the 8 x 8
-// unit-lower block read from the registers of the lanes that hold it); then a rank-8 update on the matrix cores.
+// it with lane broadcasts.  At the same time the second wavefront holds the block row k0 .. k0+7, one column per lane,
+// and runs the same eight elimination steps on it: on the 8 x 8 diagonal block both wavefronts apply the same
+// operations to the same values (fused multiply-adds written out, so that the two cannot be contracted differently),
+// hence meet the same pivots, signs and multipliers; the first one stores the diagonal block and L, the second one
+// the block row of U to the right of it.  Then a rank-8 update on the matrix cores.
 __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
-    const int lane = tid & 63;
+    const int lane = tid & 63, wave = tid >> 6;
     for (int k0 = 0; k0 < B64; k0 += 8) {
-        if (tid < 64) {
+        if (wave == 0) {
             float p[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) p[c] = W[lane * LS + k0 + c];
@@ -492,32 +529,32 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
 #pragma unroll
                 for (int c2 = c + 1; c2 < 8; ++c2) {
                     const float u = lane_value(p[c2], pr);
-                    p[c2] = below ? p[c2] - p[c] * u : p[c2];
+                    p[c2] = below ? __builtin_fmaf(-p[c], u, p[c2]) : p[c2];
                 }
             }
-            // the unit-lower diagonal block, as wavefront-uniform values
-            float l[8][8];
-#pragma unroll
-            for (int r = 1; r < 8; ++r)
-#pragma unroll
-                for (int q = 0; q < r; ++q) l[r][q] = lane_value(p[q], k0 + r);
             if (lane >= k0) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) W[lane * LS + k0 + c] = p[c];
             }
-            if (lane >= k0 + 8) {                 // block row of U: L_d y = a, one column per lane
-                float x[8];
+        } else if (wave == 1 && k0 + 8 < B64) {
+            float q[8];
 #pragma unroll
-                for (int r = 0; r < 8; ++r) x[r] = W[(k0 + r) * LS + lane];
+            for (int r = 0; r < 8; ++r) q[r] = W[(k0 + r) * LS + lane];
 #pragma unroll
-                for (int r = 1; r < 8; ++r) {
-                    float t = x[r];
+            for (int r = 0; r < 7; ++r) {
+                const int pr = k0 + r;
+                const float piv = lane_value(q[r], pr);
+                const float sv = piv >= 0.f ? -1.f : 1.f;
+                const float inv = __builtin_amdgcn_rcpf(piv - sv);
 #pragma unroll
-                    for (int q = 0; q < r; ++q) t -= l[r][q] * x[q];
-                    x[r] = t;
+                for (int i = r + 1; i < 8; ++i) {
+                    const float l = lane_value(q[i], pr) * inv;
+                    q[i] = __builtin_fmaf(-l, q[r], q[i]);     // (lanes k0 .. pr hold no longer needed entries)
                 }
+            }
+            if (lane >= k0 + 8) {
 #pragma unroll
-                for (int r = 1; r < 8; ++r) W[(k0 + r) * LS + lane] = x[r];
+                for (int r = 1; r < 8; ++r) W[(k0 + r) * LS + lane] = q[r];
             }
         }
         __syncthreads();
@@ -880,20 +917,15 @@ __device__ __forceinline__ void hr_finish_body(const float* __restrict__ part, i
     for (int q = 0; q < 16; ++q) {
         const int e = tid + NTHR * q;
         B2[(e >> 6) * LS + (e & 63)] = u1r[q];
+        B3[(e >> 6) * LS + (e & 63)] = q1r[q];
     }
     __syncthreads();
-    // Rf = U2 U1 (upper x upper): kept in registers until the row signs are known
+    // Rf = U2 U1 (upper x upper): kept in registers until the row signs are known;  Q_top = Q1_top U2^-1 -> B0
     f32x16 accR = zero16();
     if (qi <= qj) accR = lds_mma<0>(B0, B2, nullptr, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const int e = tid + NTHR * q;
-        B2[(e >> 6) * LS + (e & 63)] = q1r[q];
-    }
-    __syncthreads();
-    {   // Q_top = Q1_top U2^-1  -> B0
-        const f32x16 accQ = lds_mma<0>(B2, B1, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
+    {
+        const f32x16 accQ = lds_mma<0>(B3, B1, nullptr, qi, qj, 0, 32 * (qj + 1), lrow, lk);
+        __syncthreads();                        // every wavefront has read U2 out of B0
         acc_to_lds(accQ, B0, qi, qj, lrow, lk);
     }
     __syncthreads();
@@ -916,15 +948,30 @@ __device__ __forceinline__ void hr_finish_body(const float* __restrict__ part, i
         accT = lds_mma<1>(B0, B4, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
         acc2 = lds_mma<0>(B1, B4, sg, qi, qj, 32 * qi, 32 * (qj + 1), lrow, lk);
     }
+    {
+        const int c = 32 * qj + lrow, rb = 32 * qi + 4 * lk;
+        float sgr[16];                          // the signs of this thread's rows, requested together
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int r = 32 * qi + 8 * (v >> 2) + 4 * lk + (v & 3), c = 32 * qj + lrow;
-        const float t = (c >= r) ? -accT[v] : 0.f;
-        Mm[r * B64 + c] = accM[v];
-        Mm2[r * B64 + c] = -acc2[v];
-        Tout[r * B64 + c] = t;
-        B3[r * LS + c] = t;                     // nothing reads V_top^T any more
-        if (c >= r) A[(long)r * lda + c] = sg[r] * accR[v];     // the triangular factor S Rf
+        for (int v = 0; v < 16; ++v) sgr[v] = sg[rb + 8 * (v >> 2) + (v & 3)];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = rb + 8 * (v >> 2) + (v & 3);
+            const float t = (c >= r) ? -accT[v] : 0.f;
+            Mm[r * B64 + c] = accM[v];
+            Mm2[r * B64 + c] = -acc2[v];
+            Tout[r * B64 + c] = t;
+            B3[r * LS + c] = t;                 // nothing reads V_top^T any more
+        }
+        // the triangular factor S Rf: the whole quadrant right of the diagonal ones, the upper triangle of those
+        float* Ar = A + (long)rb * lda + c;
+        if (qi < qj) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Ar[(long)(8 * (v >> 2) + (v & 3)) * lda] = sgr[v] * accR[v];
+        } else if (qi == qj) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (c >= rb + 8 * (v >> 2) + (v & 3)) Ar[(long)(8 * (v >> 2) + (v & 3)) * lda] = sgr[v] * accR[v];
+        }
     }
     __syncthreads();
     {   // Yp_top = V_top T (unit lower x upper)
@@ -962,15 +1009,17 @@ __global__ __launch_bounds__(NSUM) void hr_finish_kernel(const float* __restrict
 //   ready1 = epoch    workgroup 0 has finished the panel's small step (Mm, Mm2, T, the top block, *fb are written);
 //   count >= target   all nproj workgroups have written their rows of V and Yp and their partials of the projection and of
 //                     C^T C (each adds 1; target = the sum over all launches so far, kept by the host);
-//   ready2 = epoch    the extra workgroup has U1 and U1^-1 of the next panel.
+//   ready2 = epoch    the extra workgroup has U1 and U1^-1 of the next panel;
+//   rows >= target_rows   the workgroups below the top block have written their partials of C^T C (formed while workgroup
+//                     0 works): the extra workgroup sums those ahead of time, off the chain of dependent steps.
 // Workgroup 0: the small step, then the top 64 rows.  Workgroups 1 .. nproj - 1: one tile of rows each; while workgroup 0
 // works they fetch their rows of Q1 and of the look-ahead columns C and form their part of C^T C; the rows of C stay in
 // LDS through the update and the next panel's second step.  Workgroup nproj: the next panel's first small step, as in
 // la_update_chol_kernel.  The nproj + 1 <= 34 workgroups run at the same time on 256 compute units; a poll that runs
 // into its limit raises DQ_FLAG_SYNC_TIMEOUT and goes on, so every wavefront ends.
 struct PanelSync {
-    unsigned long long* ready1; unsigned long long* count; unsigned long long* ready2;
-    unsigned long long epoch, target;
+    unsigned long long* ready1; unsigned long long* count; unsigned long long* ready2; unsigned long long* rows;
+    unsigned long long epoch, target, target_rows;
     long long limit_ticks;
 };
 
@@ -1016,7 +1065,8 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
                                                            float* __restrict__ Tout, float* Yp, float* Mm, float* Mm2,
                                                            float* __restrict__ tau, float* __restrict__ tslices,
                                                            unsigned* fb, unsigned* status, float* wpart, float* gpart,
-                                                           float* ctop, int nproj, PanelSync ps, HandOver ho) {
+                                                           float* gearly, float* ctop, int nproj, PanelSync ps,
+                                                           HandOver ho) {
     __builtin_amdgcn_s_setprio(3);
     __shared__ __attribute__((aligned(16))) float pool[kFusedPool];
     __shared__ float sg[B64];
@@ -1034,7 +1084,12 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
     float* Ws = Ms;                         // 64 x 64, row stride LS (over Ms and the head of Ms2)
 
     if (b == nproj) {
-        // ---- the next panel's U1 = chol(G), U1^-1 (see la_update_chol_kernel), once every partial is there
+        // ---- the next panel's U1 = chol(G), U1^-1 (see la_update_chol_kernel).  The partials of C^T C of the rows below
+        // the top block are there long before the projections: summed now, while workgroup 0 still works
+        panel_wait(ps.rows, ps.target_rows, ps, status, tid);
+        constexpr int PERX = B64 * B64 / 4 / NSUM;
+        float4 gsum[PERX];
+        sum_partials_regs<NSUM, 16>(gearly + B64 * B64, nproj - 1, gsum, tid);
         panel_wait(ps.count, ps.target, ps, status, tid);
         float* S0 = pool;                   // V_top
         float* S1 = pool + B64 * LS;        // C_top, then C'_top
@@ -1049,7 +1104,24 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
                 ct[q] = *reinterpret_cast<const float4*>(ctop + e);
             }
         }
-        sum_partials_pair<NSUM, 11>(wpart, gpart, nproj, Wx, Gs, tid);
+        {   // W2 = sum of the projection partials;  C^T C = the early sum + workgroup 0's part (the top rows)
+            float4 wsum[PERX];
+            sum_partials_regs<NSUM, 16, true>(wpart, nproj, wsum, tid);
+#pragma unroll
+            for (int q = 0; q < PERX; ++q) {
+                const int e = 4 * (tid + NSUM * q);
+                const bool upper = !((e >> 6) >= 32 && (e & 63) < 32);
+                if (upper) {
+                    const float4 t = *reinterpret_cast<const float4*>(gearly + e);
+                    gsum[q].x += t.x; gsum[q].y += t.y; gsum[q].z += t.z; gsum[q].w += t.w;
+                }
+                float* dw = Wx + (e >> 6) * LS + (e & 63);
+                float* dg = Gs + (e >> 6) * LS + (e & 63);
+                dw[0] = wsum[q].x; dw[1] = wsum[q].y; dw[2] = wsum[q].z; dw[3] = wsum[q].w;
+                dg[0] = gsum[q].x; dg[1] = gsum[q].y; dg[2] = gsum[q].z; dg[3] = gsum[q].w;
+            }
+            __syncthreads();
+        }
         if (tid >= NTHR) return;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -1109,7 +1181,7 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
             ctop[e] = Cs[(e >> 6) * LS + (e & 63)];
         }
         store_partial(wpart, acc, qi, qj, lrow, lk);
-        store_partial(gpart, accg, qi, qj, lrow, lk);
+        store_partial(gearly, accg, qi, qj, lrow, lk);
         __syncthreads();
         if (tid == 0) (void)__hip_atomic_fetch_add(ps.count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         // the reflectors as stored, unit lower triangular, for the update of the top rows
@@ -1146,6 +1218,9 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
     __syncthreads();
     f32x16 accg = zero16();
     gram_tile(Cs, accg, qi, qj, lrow, lk);          // C_rows^T C_rows of the columns BEFORE the update
+    store_partial(gearly + (long)b * B64 * B64, accg, qi, qj, lrow, lk);
+    __syncthreads();
+    if (tid == 0) (void)__hip_atomic_fetch_add(ps.rows, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     panel_wait(ps.ready1, ps.epoch, ps, status, tid);
     const bool fell_back = *fb != 0u;
     f32x16 v0 = zero16(), v1 = zero16();            // this wavefront's 32 rows of V
@@ -1177,7 +1252,6 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
         f32x16 acc = zero16();
         proj_tile(Xs, Cs, acc, qi, qj, lrow, lk);
         store_partial(wpart + (long)b * B64 * B64, acc, qi, qj, lrow, lk);
-        store_partial(gpart + (long)b * B64 * B64, accg, qi, qj, lrow, lk);
     }
     __syncthreads();                                // every wavefront is done with Yp in Xs; all partials are stored
     if (tid == 0) (void)__hip_atomic_fetch_add(ps.count, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
@@ -1236,7 +1310,7 @@ __global__ __launch_bounds__(NSUM) void panel_fused_kernel(const float* part, in
 
 }  // namespace
 
-size_t cholpanel_scratch_floats() { return (size_t)(2 * kCholMaxParts + 2) * B64 * B64 + 5 * B64 * B64 + 64; }
+size_t cholpanel_scratch_floats() { return (size_t)(3 * kCholMaxParts + 3) * B64 * B64 + 5 * B64 * B64 + 64; }
 
 bool cholpanel_supported(const float* A, long lda, int m, int jb) {
     return jb == B64 && m >= B64 && m <= 8192 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (lda & 3) == 0;
@@ -1244,7 +1318,7 @@ bool cholpanel_supported(const float* A, long lda, int m, int jb) {
 
 namespace {
 struct TallScratch {
-    float *part, *U1, *U1inv, *Mm, *Mm2, *ctop, *wpart;
+    float *part, *U1, *U1inv, *Mm, *Mm2, *ctop, *wpart, *gearly;
     unsigned* fb;
     unsigned long long* ready;
     explicit TallScratch(float* scratch) {
@@ -1257,6 +1331,7 @@ struct TallScratch {
         fb = reinterpret_cast<unsigned*>(ctop + B64 * B64);
         ready = reinterpret_cast<unsigned long long*>(ctop + B64 * B64 + 2);   // 8-byte aligned: the scratch is 256-byte aligned
         wpart = ctop + B64 * B64 + 64;                             // kCholMaxParts + 1 projection partials
+        gearly = wpart + (size_t)(kCholMaxParts + 1) * B64 * B64;  // kCholMaxParts + 1 partials of C^T C (one-launch panels)
     }
 };
 // Row tiles of 128 per workgroup and number of workgroups (= Gram partials) for a panel of m rows.  More partials
@@ -1324,7 +1399,8 @@ int cholqr_fused_workgroups(int m) {
 
 hipError_t launch_cholqr_fused(float* A, long lda, int m, float* Tout, float* Yp, float* q1, float* scratch, float* tau,
                                float* tslices, unsigned* status, unsigned long long* words, unsigned long long epoch,
-                               unsigned long long target, long limit_us, hipStream_t s, const HandOver* ho) {
+                               unsigned long long target, unsigned long long target_rows, long limit_us, hipStream_t s,
+                               const HandOver* ho) {
     if (!cholpanel_supported(A, lda, m, B64) || m < 2 * B64) return hipErrorInvalidValue;
     const int nproj = cholqr_fused_workgroups(m);
     if (nproj < 2 || nproj > kCholMaxParts + 1) return hipErrorInvalidValue;
@@ -1332,11 +1408,11 @@ hipError_t launch_cholqr_fused(float* A, long lda, int m, float* Tout, float* Yp
     int tpw, nparts;
     tall_split(m, tpw, nparts);          // the partials of Q1^T Q1 that the previous panel's kernels left
     PanelSync ps;
-    ps.ready1 = words; ps.count = words + 1; ps.ready2 = words + 2;
-    ps.epoch = epoch; ps.target = target; ps.limit_ticks = (long long)limit_us * 100;
+    ps.ready1 = words; ps.count = words + 1; ps.ready2 = words + 2; ps.rows = words + 3;
+    ps.epoch = epoch; ps.target = target; ps.target_rows = target_rows; ps.limit_ticks = (long long)limit_us * 100;
     const HandOver h = ho != nullptr ? *ho : HandOver();
     hipLaunchKernelGGL(panel_fused_kernel, dim3(nproj + 1), dim3(NSUM), 0, s, ts.part, nparts, q1, ts.U1, ts.U1inv, A, lda,
-                       m, Tout, Yp, ts.Mm, ts.Mm2, tau, tslices, ts.fb, status, ts.wpart, ts.part, ts.ctop, nproj, ps, h);
+                       m, Tout, Yp, ts.Mm, ts.Mm2, tau, tslices, ts.fb, status, ts.wpart, ts.part, ts.gearly, ts.ctop, nproj, ps, h);
     return hipGetLastError();
 }
 
