@@ -37,7 +37,7 @@ __device__ __forceinline__ void tri_inv_level(const float* U, float* X, int tid)
         const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
         const int i = r / BL, j = r % BL;
         float t = 0.f;
-#pragma unroll
+#pragma unroll 4
         for (int k = 0; k < BL; ++k) t += U[(o + i) * LS + o + BL + k] * X[(o + BL + k) * LS + o + BL + j];
         acc[it] = t;
     }
@@ -54,7 +54,7 @@ __device__ __forceinline__ void tri_inv_level(const float* U, float* X, int tid)
         const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
         const int i = r / BL, j = r % BL;
         float t = 0.f;
-#pragma unroll
+#pragma unroll 4
         for (int k = 0; k < BL; ++k) t += X[(o + i) * LS + o + k] * X[(o + BL + k) * LS + o + j];
         acc[it] = t;
     }
@@ -93,7 +93,7 @@ __device__ __forceinline__ void tri_inv_upper_64(const float* U, float* X, int t
 #pragma unroll
             for (int q = r; q < 8; ++q) u[r][q] = U[(o + r) * LS + o + q];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) ru[r] = UNIT ? 1.f : 1.f / u[r][r];
+        for (int r = 0; r < 8; ++r) ru[r] = UNIT ? 1.f : __builtin_amdgcn_rcpf(u[r][r]);   // hardware reciprocal (1 ulp)
 #pragma unroll
         for (int r = 7; r >= 0; --r) {
             float t = (r == c) ? 1.f : 0.f;
@@ -151,7 +151,7 @@ __device__ __forceinline__ void tri_inv_level_pair(const float* U0, float* X0, c
             const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
             const int i = r / BL, j = r % BL;
             float t = 0.f;
-#pragma unroll
+#pragma unroll 4
             for (int k = 0; k < BL; ++k) t += U[(o + i) * LS + o + BL + k] * X[(o + BL + k) * LS + o + BL + j];
             acc[s][it] = t;
         }
@@ -176,7 +176,7 @@ __device__ __forceinline__ void tri_inv_level_pair(const float* U0, float* X0, c
             const int o = (e / PER_PAIR) * 2 * BL, r = e % PER_PAIR;
             const int i = r / BL, j = r % BL;
             float t = 0.f;
-#pragma unroll
+#pragma unroll 4
             for (int k = 0; k < BL; ++k) t += X[(o + i) * LS + o + k] * X[(o + BL + k) * LS + o + j];
             acc[s][it] = t;
         }
@@ -221,7 +221,7 @@ __device__ __forceinline__ void tri_inv_upper_64_pair(const float* U0, float* X0
 #pragma unroll
             for (int q = r; q < 8; ++q) u[r][q] = U[(o + r) * LS + o + q];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) ru[r] = unit ? 1.f : 1.f / u[r][r];
+        for (int r = 0; r < 8; ++r) ru[r] = unit ? 1.f : __builtin_amdgcn_rcpf(u[r][r]);   // hardware reciprocal (1 ulp)
 #pragma unroll
         for (int r = 7; r >= 0; --r) {
             float t = (r == c) ? 1.f : 0.f;

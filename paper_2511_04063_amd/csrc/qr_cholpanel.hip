@@ -471,6 +471,9 @@ __device__ __forceinline__ float lane_value(float v, int l) {
 // eight steps); then a rank-8 update of the rest on the matrix cores by all four wavefronts.
 __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
     const int lane = tid & 63;
+    // (kept as a loop: the routine runs once per launch, from a cold instruction cache, and eight copies of its body
+    // cost more to fetch than the loop control costs to execute)
+#pragma unroll 1
     for (int k0 = 0; k0 < B64; k0 += 8) {
         if (tid < 64) {
             float p[8];
@@ -511,6 +514,7 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
 // the block row of U to the right of it.  Then a rank-8 update on the matrix cores.
 __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll 1
     for (int k0 = 0; k0 < B64; k0 += 8) {
         if (wave == 0) {
             float p[8];
