@@ -259,8 +259,10 @@ __device__ __forceinline__ void heads_tile(const bf16_t* Xs, bf16_t* dYs, const 
                 const float y = i == 0 ? y0[4 * g + q] : y1[4 * g + q];
                 const float ex = __expf(-fabsf(y));
                 lsum += ex;   // rows past the end of the chunk hold y = 0 and add exactly 1 each: removed by the caller
-                const float sg = (y > 0.f) ? -scale : ((y < 0.f) ? scale : 0.f);
-                d[q] = sg * ex;
+                // scale * sgn(y) without comparisons: y * 2^126 has modulus >= 1 for every normal y (an overflow to
+                // infinity is as good), so the median with -scale and +scale picks the signed bound; y = 0 stays 0
+                const float sg = __builtin_amdgcn_fmed3f(y * 8.507059173e37f, -scale, scale);
+                d[q] = -sg * ex;
             }
             const f32x2 d01 = {d[0], d[1]}, d23 = {d[2], d[3]};
             const bf16x2 b01 = __builtin_convertvector(d01, bf16x2), b23 = __builtin_convertvector(d23, bf16x2);
