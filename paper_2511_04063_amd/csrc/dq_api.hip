@@ -806,58 +806,33 @@ dq_status rotate_loss_grad_one(dq_ctx* c, const Layout& L, int T, int n, const v
 }
 
 // ---------------------------------------------------------------- S6 (+ S7 when Zupd != null)
-// dZ = R P U^{-T},  P = strict_lower(R^T G - G^T R).  The triangular solve M U^T = P runs right-looking over
-// column blocks from the last to the first; M is strictly lower triangular, so every product skips its zero part.
-dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, long ldr, const float* U, long ldu,
-                          const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr) {
-    hipStream_t s = c->stream;
+// What S6 needs of R and U alone, on stream s: the inverses of the diagonal blocks of U (128 x 128, merged to 512 x 512
+// where the solve works on such blocks) and, for the products on three-plane splits, the planes of R (transposed for
+// R^T G in x3a, as stored for R M in x3c).  (Run on the second stream beside S3-S5 it gained nothing, 8.83 ms per step
+// either way at n = 4096 and 45.8 -> 46.2 at 8192: the split passes and small products land on compute units whose one
+// 256 x 256 tile of the bf16 product then finishes last.  The batched 128 x 128 route does run its inverses there.)
+bool backward_uses_splits(const dq_ctx* c, const Layout& L, int n) {
+    return c->split_gemm != 0 && gemm_bf16x3_fits(n, n, n) && L.ld == n && (c->split_gemm == 2 || n >= 2560);
+}
+
+dq_status qr_backward_prepare(dq_ctx* c, const Layout& L, int n, const float* R, long ldr, const float* U, long ldu,
+                              hipStream_t s) {
     unsigned* flags = at<unsigned>(c, L.flags);
-    float* Bb = at<float>(c, L.B);
-    float* Pb = at<float>(c, L.P);
-    float* Mb = at<float>(c, L.M);
     float* uinv = at<float>(c, L.uinv);
     const long ld = L.ld;
-    const double n3 = (double)n * n * n;
-    // The two full n x n x n products run on the bf16 matrix cores from three-plane splits of their operands when the
-    // shape fits those tiles (fp32-level accuracy: six plane pairs, fp32 accumulation), else on the fp32 ones.
-    // (256 x 256 tiles at six times the matrix-core work: ahead of the fp32 kernel's 128 x 128 tiles once about a hundred of
-    // them keep the compute units busy, n >= 2560)
-    const bool x3 = c->split_gemm != 0 && gemm_bf16x3_fits(n, n, n) && ld == n && (c->split_gemm == 2 || n >= 2560);
-    bf16_t* pa3 = at<bf16_t>(c, L.x3a);
-    bf16_t* pb3 = at<bf16_t>(c, L.x3b);
     const long plane = (long)n * ld;
-    if (x3) {
-        {
-            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 20.0 * n * (double)n);
-            DQ_HIP(launch_split3_bf16(R, ldr, n, n, pa3, ld, plane, 1, s));
-            DQ_HIP(launch_split3_bf16(G, ldg, n, n, pb3, ld, plane, 1, s));
-        }
-        GemmBf16 g;   // B = R^T G:  B(i, j) = sum_k R^T(i, k) G^T(j, k)
-        g.A = pa3; g.lda = ld; g.a_plane = plane;
-        g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1;
-        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 12.0 * n3, 0.0);
-        DQ_HIP(launch_gemm_bf16x3(g, s));
-    } else {
-        GemmF32 g;
-        g.A = R; g.lda = ldr; g.ta = 1;
-        g.B = G; g.ldb = ldg; g.tb = 0;
-        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
-        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
-        DQ_HIP(launch_gemm_f32(g, s));
+    if (backward_uses_splits(c, L, n)) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 20.0 * n * (double)n);
+        DQ_HIP(launch_split3_bf16(R, ldr, n, n, at<bf16_t>(c, L.x3a), ld, plane, 1, s));
+        DQ_HIP(launch_split3_bf16(R, ldr, n, n, at<bf16_t>(c, L.x3c), ld, plane, 0, s));
     }
     {
-        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * n * (double)n);
-        DQ_HIP(launch_skew_lower(Bb, ld, n, Pb, ld, Mb, ld, s));
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * n * (double)kTrsmBlock);
         DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s));
     }
-    const int nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
     if (n % kTrsmOuter == 0) {
-        // M U^T = P by block columns of kTrsmOuter from the right:  M_J = P_J inv(U_JJ)^T, then everything left of the
-        // block gets ONE update with K = kTrsmOuter (K = 128 updates over the whole width move P at the rate of the
-        // rank-64 updates of the QR, and a chain of 128-column solves is a chain of short launches).  The inverses of
-        // the 512 x 512 diagonal blocks are merged from the 128 x 128 ones, inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1],
-        // [0, C^-1]], two levels of batched products that depend on U only.
+        // The inverses of the 512 x 512 diagonal blocks are merged from the 128 x 128 ones, inv [[A, B], [0, C]] =
+        // [[A^-1, -A^-1 B C^-1], [0, C^-1]], two levels of batched products.
         float* uo = at<float>(c, L.uinvo);
         float* t1 = at<float>(c, L.utmp);                               // n / 256 blocks of 128 x 128
         float* t2 = t1 + (size_t)n * 64;                                // n / 512 blocks of 256 x 256
@@ -892,6 +867,66 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
         DQ_TRY(merge(kTrsmBlock, 0, t1, (long)2 * kTrsmBlock * kTrsmBlock));
         DQ_TRY(merge(kTrsmBlock, 2 * kTrsmBlock, t1 + (long)kTrsmBlock * kTrsmBlock, (long)2 * kTrsmBlock * kTrsmBlock));
         DQ_TRY(merge(2 * kTrsmBlock, 0, t2, (long)4 * kTrsmBlock * kTrsmBlock));
+    }
+    return DQ_OK;
+}
+
+// dZ = R P U^{-T},  P = strict_lower(R^T G - G^T R).  The triangular solve M U^T = P runs right-looking over
+// column blocks from the last to the first; M is strictly lower triangular, so every product skips its zero part.
+// prepared: qr_backward_prepare has already run for this R and U on this stream (or the stream has waited for it).
+dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, long ldr, const float* U, long ldu,
+                          const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr,
+                          bool prepared = false) {
+    hipStream_t s = c->stream;
+    if (!prepared) DQ_TRY(qr_backward_prepare(c, L, n, R, ldr, U, ldu, s));
+    float* Bb = at<float>(c, L.B);
+    float* Pb = at<float>(c, L.P);
+    float* Mb = at<float>(c, L.M);
+    float* uinv = at<float>(c, L.uinv);
+    const long ld = L.ld;
+    const double n3 = (double)n * n * n;
+    // The two full n x n x n products run on the bf16 matrix cores from three-plane splits of their operands when the
+    // shape fits those tiles (fp32-level accuracy: six plane pairs, fp32 accumulation), else on the fp32 ones.
+    // (256 x 256 tiles at six times the matrix-core work: ahead of the fp32 kernel's 128 x 128 tiles once about a hundred of
+    // them keep the compute units busy, n >= 2560)
+    const bool x3 = backward_uses_splits(c, L, n);
+    bf16_t* pa3 = at<bf16_t>(c, L.x3a);   // planes of R^T (qr_backward_prepare)
+    bf16_t* pb3 = at<bf16_t>(c, L.x3b);   // planes of G^T, later of M
+    bf16_t* pr3 = at<bf16_t>(c, L.x3c);   // planes of R (qr_backward_prepare)
+    const long plane = (long)n * ld;
+    if (x3) {
+        {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 10.0 * n * (double)n);
+            DQ_HIP(launch_split3_bf16(G, ldg, n, n, pb3, ld, plane, 1, s));
+        }
+        GemmBf16 g;   // B = R^T G:  B(i, j) = sum_k R^T(i, k) G^T(j, k)
+        g.A = pa3; g.lda = ld; g.a_plane = plane;
+        g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1;
+        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 12.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_bf16x3(g, s));
+    } else {
+        GemmF32 g;
+        g.A = R; g.lda = ldr; g.ta = 1;
+        g.B = G; g.ldb = ldg; g.tb = 0;
+        g.C = Bb; g.ldc = ld; g.M = n; g.N = n; g.K = n;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * n3, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * n * (double)n);
+        DQ_HIP(launch_skew_lower(Bb, ld, n, Pb, ld, Mb, ld, s));
+    }
+    const int nblk = (n + kTrsmBlock - 1) / kTrsmBlock;
+    if (n % kTrsmOuter == 0) {
+        // M U^T = P by block columns of kTrsmOuter from the right:  M_J = P_J inv(U_JJ)^T, then everything left of the
+        // block gets ONE update with K = kTrsmOuter (K = 128 updates over the whole width move P at the rate of the
+        // rank-64 updates of the QR, and a chain of 128-column solves is a chain of short launches).  The inverses of
+        // the 512 x 512 diagonal blocks are merged from the 128 x 128 ones, inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1],
+        // [0, C^-1]], two levels of batched products that depend on U only.
+        float* uo = at<float>(c, L.uinvo);
+        const int nouter = n / kTrsmOuter;
+        const long so = (long)kTrsmOuter * kTrsmOuter;
         for (int J = nouter - 1; J >= 0; --J) {
             const int J0 = J * kTrsmOuter;
             const int mrows = n - J0;
@@ -943,12 +978,11 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
     }
     if (x3) {
         {
-            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 20.0 * n * (double)n);
-            DQ_HIP(launch_split3_bf16(R, ldr, n, n, pa3, ld, plane, 0, s));
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 10.0 * n * (double)n);
             DQ_HIP(launch_split3_bf16(Mb, ld, n, n, pb3, ld, plane, 1, s));
         }
         GemmBf16 g;   // dZ = R M (or Z <- Z - lr R M):  dZ(i, j) = sum_k R(i, k) M^T(j, k), M strictly lower
-        g.A = pa3; g.lda = ld; g.a_plane = plane;
+        g.A = pr3; g.lda = ld; g.a_plane = plane;
         g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1; g.b_strict_lower = 1;
         g.M = n; g.N = n; g.K = n;
         if (Zupd != nullptr) { g.C = Zupd; g.ldc = ldz; g.alpha = -lr; g.beta = 1.f; }
@@ -1115,10 +1149,27 @@ dq_status heads_rotate_loss_grad(dq_ctx* c, const HeadsLayout& H, int b, int T, 
     return DQ_OK;
 }
 
+// inv(U_i) for every problem on the second stream, beside whatever the caller's stream does next: it depends on the
+// factorisation only, and the 64 workgroups that form it (a quarter of the device, 30 us) need not sit between the
+// gradient and the derivative through the QR.  The caller's stream must wait for sync_ev[1] before inv(U) is used.
+dq_status heads_uinv_early(dq_ctx* c, const HeadsLayout& H, int b, const float* U, long ldu) {
+    const int n = kHeadDim;
+    DQ_HIP(hipEventRecord(c->sync_ev[0], c->stream));
+    DQ_HIP(hipStreamWaitEvent(c->stream2, c->sync_ev[0], 0));
+    {
+        LaunchScope sc(&c->prof, c->stream2, DQ_K_SMALL, 0.0, 8.0 * b * (double)n * n);
+        DQ_HIP(launch_trinv_blocks(U, ldu, n, at<float>(c, H.uinv), at<unsigned>(c, 0), c->stream2, b, (long)n * ldu,
+                                   (long)n * n));
+    }
+    DQ_HIP(hipEventRecord(c->sync_ev[1], c->stream2));
+    return DQ_OK;
+}
+
 // dZ_i = R_i P_i U_i^{-T} for every problem (or Z_i -= lr dZ_i when Zupd != null): the steps of qr_backward_one with
-// one 128-wide block, as batched launches.
+// one 128-wide block, as batched launches.  have_uinv: inv(U_i) is already in the workspace (heads_uinv_early).
 dq_status heads_backward(dq_ctx* c, const HeadsLayout& H, int b, const float* R, long ldr, const float* U, long ldu,
-                         const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr) {
+                         const float* G, long ldg, float* dZ, long lddz, float* Zupd, long ldz, float lr,
+                         bool have_uinv = false) {
     const int n = kHeadDim;
     const long nn = (long)n * n;
     if (b < 1) return DQ_OK;
@@ -1141,7 +1192,7 @@ dq_status heads_backward(dq_ctx* c, const HeadsLayout& H, int b, const float* R,
     {
         LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * b * (double)nn);
         DQ_HIP(launch_skew_lower(Bb, n, n, Pb, n, nullptr, 0, s, b, nn, nn, 0));
-        DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s, b, (long)n * ldu, nn));
+        if (!have_uinv) DQ_HIP(launch_trinv_blocks(U, ldu, n, uinv, flags, s, b, (long)n * ldu, nn));
     }
     {
         GemmF32 g;   // M = P inv(U)^T
@@ -1332,8 +1383,11 @@ dq_status dq_calib_step(dq_ctx* c, int b, int T, int n, const void* X, dq_dtype 
         float* Uh = at<float>(c, H.U);
         float* Gh = at<float>(c, H.G);
         DQ_TRY(heads_qr(c, b, Z, ldz, Rh, ldrh, Uh, kHeadDim));
+        const bool early = !c->single_stream && b >= 1;
+        if (early) DQ_TRY(heads_uinv_early(c, H, b, Uh, kHeadDim));
         DQ_TRY(heads_rotate_loss_grad(c, H, b, T, X, ldx, Rh, ldrh, red, loss_dev, Gh, kHeadDim));
-        return heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, nullptr, 0, Z, ldz, lr);
+        if (early) DQ_HIP(hipStreamWaitEvent(c->stream, c->sync_ev[1], 0));
+        return heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, nullptr, 0, Z, ldz, lr, early);
     }
     const size_t esz = (xdt == DQ_BF16) ? 2 : 4;
     for (int i = 0; i < b; ++i) {
@@ -1673,8 +1727,11 @@ dq_status dq_calib_step_adam(dq_ctx* c, int b, int T, int n, const void* X, dq_d
         float* Gh = at<float>(c, H.G);
         float* dZh = at<float>(c, H.B);   // B = R^T G is consumed before the last product writes dZ there
         DQ_TRY(heads_qr(c, b, Z, ldz, Rh, ldrh, Uh, kHeadDim));
+        const bool early = !c->single_stream && b >= 1;
+        if (early) DQ_TRY(heads_uinv_early(c, H, b, Uh, kHeadDim));
         DQ_TRY(heads_rotate_loss_grad(c, H, b, T, X, ldx, Rh, ldrh, red, loss_dev, Gh, kHeadDim));
-        DQ_TRY(heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, dZh, kHeadDim, nullptr, 0, 0.f));
+        if (early) DQ_HIP(hipStreamWaitEvent(c->stream, c->sync_ev[1], 0));
+        DQ_TRY(heads_backward(c, H, b, Rh, ldrh, Uh, kHeadDim, Gh, kHeadDim, dZh, kHeadDim, nullptr, 0, 0.f, early));
         // the b problems are stacked row-wise with a common row stride: one elementwise pass over b*n rows
         LaunchScope sc(&c->prof, c->stream, DQ_K_SMALL, 12.0 * b * n * (double)n, 28.0 * b * n * (double)n);
         DQ_HIP(launch_adam2d(Z, ldz, dZh, kHeadDim, m, ldm, v, ldv, n, lr, beta1, beta2, eps, c1, c2, c->stream, b * n));
