@@ -1,4 +1,4 @@
-"""Benchmark of the QR-Orth calibration step (Alg. 1 lines 7-10 of DartQuant) on one MI355X.
+"""Benchmark of the QR-Orth calibration step (the loop body of Alg. 1 of DartQuant) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|70b|tiny|heads]
 

@@ -56,7 +56,7 @@ typedef enum {
 typedef enum { DQ_F32 = 0, DQ_BF16 = 1 } dq_dtype;
 
 /* How Whip (Eq. 4, defined for one activation vector) is reduced over the T token rows of a
- * block (Alg. 1 line 9 leaves this open): mean over tokens of the per-token sum, or the sum. */
+ * block (the loss step of Alg. 1 leaves this open): mean over tokens of the per-token sum, or the sum. */
 typedef enum { DQ_REDUCE_TOKEN_MEAN = 0, DQ_REDUCE_SUM = 1 } dq_reduce;
 
 /* The objective S4 evaluates on the rotated block.  DQ_OBJ_WHIP is the paper's (Eq. 4).  The other three are the
@@ -146,7 +146,7 @@ dq_status dq_device_flags(dq_ctx* ctx, unsigned* host_out);
 
 /* ---- the hot path ------------------------------------------------------------------- */
 
-/* Sec. 4.3 / Alg. 1 line 7:  Z (n x n) -> orthogonal R and, optionally, upper-triangular U with
+/* Sec. 4.3 / the QR step of Alg. 1:  Z (n x n) -> orthogonal R and, optionally, upper-triangular U with
  * Z = R U.  Computed by blocked Householder QR (Alg. 2 in blocked compact-WY form) followed by
  * sign normalisation so that diag(U) >= 0, which makes R unique for nonsingular Z.
  * Z: in, b x (n x n) fp32.  R: out, fp32.  U_or_null: out, fp32, strictly-lower part written as 0. */
@@ -154,7 +154,7 @@ dq_status dq_qr_orth(dq_ctx* ctx, int b, int n,
                      const float* Z, long ldz, float* R, long ldr,
                      float* U_or_null, long ldu);
 
-/* Alg. 1 lines 8-9 and the chain rule to R:
+/* Alg. 1, rotation and loss steps, and the chain rule to R:
  *   Y = X @ R;   loss = c * sum_t sum_i exp(-|Y_ti|)  (Eq. 4; c = 1/T or 1 per `red`);
  *   dY = -c * sgn(Y) * exp(-|Y|) with sgn(0) = 0;   G = X^T @ dY = dL/dR.
  * X: in, b x (T x n), dtype xdt (bf16 X is multiplied on the bf16 matrix cores against R rounded
@@ -167,7 +167,7 @@ dq_status dq_rotate_loss_grad(dq_ctx* ctx, int b, int T, int n,
                               float* loss_dev, float* G, long ldg,
                               float* Y_or_null, long ldy, void* dY_or_null, long lddy);
 
-/* The whole loop body of Alg. 1 (lines 7-10) with plain SGD:  Z is updated IN PLACE to
+/* The whole loop body of Alg. 1 with plain SGD:  Z is updated IN PLACE to
  * Z - lr * dL/dZ.  loss_dev (b device floats) and R_or_null receive the loss and the rotation of
  * the INPUT Z (before the update). */
 dq_status dq_calib_step(dq_ctx* ctx, int b, int T, int n,
@@ -175,7 +175,7 @@ dq_status dq_calib_step(dq_ctx* ctx, int b, int T, int n,
                         float* Z, long ldz, float lr, dq_reduce red,
                         float* loss_dev, float* R_or_null, long ldr);
 
-/* Alg. 1 lines 3-11, the loop over mini-batches with the calibration set in HOST memory: step k (k = 0 .. steps-1) is
+/* Alg. 1, the loop over mini-batches, with the calibration set in HOST memory: step k (k = 0 .. steps-1) is
  * dq_calib_step on batch k % num_batches, and batch k + 1 travels to the device on an internal stream while step k
  * runs (two staging slots).  One problem (b = 1).
  * X_host: HOST array of num_batches HOST pointers, each a T x n block of dtype xdt with leading dimension ldx.  Pinned
@@ -224,7 +224,7 @@ dq_status dq_objective_loss_grad(dq_ctx* ctx, dq_objective objective, int quant_
  * quant_bits outside 1..16; the setting is unchanged on error. */
 dq_status dq_set_objective(dq_ctx* ctx, dq_objective objective, int quant_bits);
 
-/* Alg. 1 line 10, the derivative through Z = R U:  with B = R^T G and P = strict_lower(B - B^T),
+/* The last step of Alg. 1, the derivative through Z = R U:  with B = R^T G and P = strict_lower(B - B^T),
  * dZ = R P U^{-T}.  R, U, G: in (U upper triangular, its strictly-lower part is not read).
  * dZ: out.  A zero on diag(U) sets DQ_FLAG_SINGULAR. */
 dq_status dq_qr_backward(dq_ctx* ctx, int b, int n,
@@ -244,7 +244,7 @@ dq_status dq_hadamard_init(dq_ctx* ctx, int b, int n, const float* signs_dev, fl
 dq_status dq_outlier_count(dq_ctx* ctx, int b, int T, int n, const float* Y, long ldy, float tau,
                            unsigned long long* counts_dev);
 
-/* Alg. 1 line 5, token sampling: X_out[i][t][:] = X_all[i][idx[i*T_out + t]][:] for t < T_out, b independent
+/* Alg. 1, token sampling: X_out[i][t][:] = X_all[i][idx[i*T_out + t]][:] for t < T_out, b independent
  * problems (X_all: b blocks of T_all rows, X_out: b blocks of T_out rows, both with n columns of `dtype`).
  * Which tokens are kept (the paper samples 10 % of them at random) is the caller's choice: idx is a DEVICE array of
  * b*T_out int32 row numbers in [0, T_all), repeats allowed.  Rows must be 16-byte multiples and 16-byte aligned
@@ -253,7 +253,7 @@ dq_status dq_outlier_count(dq_ctx* ctx, int b, int T, int n, const float* Y, lon
 dq_status dq_gather_rows(dq_ctx* ctx, int b, int T_all, int T_out, int n, const void* X_all, dq_dtype dtype,
                          long ldx_all, const int* idx, void* X_out, long ldx_out);
 
-/* Alg. 1 line 10, the update alone:  Z <- Z - lr * dZ  (in place on Z). */
+/* The last step of Alg. 1, the update alone:  Z <- Z - lr * dZ  (in place on Z). */
 dq_status dq_sgd_update(dq_ctx* ctx, int b, int n, float* Z, long ldz,
                         const float* dZ, long lddz, float lr);
 
@@ -270,7 +270,7 @@ dq_status dq_adam_update(dq_ctx* ctx, int b, int n, float* Z, long ldz, const fl
 dq_status dq_sgd_momentum_update(dq_ctx* ctx, int b, int n, float* Z, long ldz, const float* dZ, long lddz,
                                  float* buf, long ldbuf, float lr, float mu);
 
-/* One QR-Orth step (Alg. 1 lines 7-10) with Adam in place of the SGD update of line 10; arguments as for
+/* One QR-Orth step (the loop body of Alg. 1) with Adam in place of its SGD update; arguments as for
  * dq_calib_step and dq_adam_update (m, v: b stacked n x n matrices of optimiser state, zero before step 1). */
 dq_status dq_calib_step_adam(dq_ctx* ctx, int b, int T, int n,
                              const void* X, dq_dtype x_dtype, long ldx,

@@ -26,7 +26,7 @@ Readings taken where the paper is silent (each is also listed in the design note
   per-token Whip (default);  ``reduce="sum"`` -> plain sum.  Parity unpinned by the
   paper (a pure scale, equivalent to rescaling eta).
 * d|y|/dy at y = 0 is taken as 0.  Parity unpinned by the paper.
-* dL/dZ is not written in the paper (it says only "dL/dZ", Alg. 1 line 10).  It is
+* dL/dZ is not written in the paper (it says only "dL/dZ" in the last step of Alg. 1).  It is
   derived here from Z = R U:  with B = R^T G, P = strict_lower(B - B^T),
   dZ = R P U^{-T}.  Pinned by finite differences of the whole map Z -> L, by the
   structural identities of the true gradient, and by a library autograd route
@@ -40,7 +40,7 @@ Readings taken where the paper is silent (each is also listed in the design note
   the usual defaults (beta1 0.9, beta2 0.999, eps 1e-8, step counter from 1); SGD with
   momentum as the heavy-ball form without dampening.  Both pinned against closed forms
   and a library optimiser (tests/).
-* Alg. 1 line 5, token_sampling(X): the paper keeps a random 10 % of the tokens (App.,
+* Alg. 1, token_sampling(X): the paper keeps a random 10 % of the tokens (App.,
   sample-size analysis) and does not say how they are drawn.  The draw is an INPUT here
   (a list of row numbers, repeats allowed); the step itself is the selection of those
   rows, in the given order.  Pinned by its invariants (tests/).
@@ -112,7 +112,7 @@ def _f64(a) -> np.ndarray:
 
 
 def _reduce_scale(reduce: str, n_tokens: int) -> float:
-    """Scale c in L = c * sum_t sum_i exp(-|Y_ti|)  (reading of Alg. 1 line 9)."""
+    """Scale c in L = c * sum_t sum_i exp(-|Y_ti|)  (reading of the loss step of Alg. 1)."""
     if reduce == "mean":
         return 1.0 / float(n_tokens)
     if reduce == "sum":
@@ -193,7 +193,7 @@ def outlier_count(Y, tau: float) -> int:
 
 
 def token_sampling(X, idx) -> np.ndarray:
-    """Alg. 1 line 5: the activation rows named by idx, in that order (values untouched)."""
+    """The token-sampling step of Alg. 1: the activation rows named by idx, in that order (values untouched)."""
     X = np.asarray(X)
     idx = np.asarray(idx)
     if idx.ndim != 1:
@@ -208,7 +208,7 @@ def token_sampling(X, idx) -> np.ndarray:
 
 
 def rotate(X, R):
-    """O = X @ R  (Alg. 1 line 8; rows of X are tokens)."""
+    """O = X @ R  (the rotation step of Alg. 1; rows of X are tokens)."""
     return _f64(X) @ _f64(R)
 
 
@@ -361,7 +361,7 @@ def _solve_right_upper_transposed(W, U) -> np.ndarray:
 def qr_backward(R, U, G) -> np.ndarray:
     """dL/dZ from G = dL/dR through Z = R U (diag(U) > 0), no gradient flowing into U.
 
-    Derivation (not in the paper, which writes only dL/dZ in Alg. 1 line 10):
+    Derivation (not in the paper, which writes only dL/dZ in the last step of Alg. 1):
     dZ = dR U + R dU  =>  R^T dZ U^{-1} = Omega + dU U^{-1}, Omega = R^T dR skew,
     dU U^{-1} upper triangular  =>  Omega = Lo - Lo^T, Lo = strict_lower(R^T dZ U^{-1}).
     Then <G, R Omega> = <strict_lower(B - B^T), R^T dZ U^{-1}> with B = R^T G, hence
@@ -379,7 +379,7 @@ def qr_backward(R, U, G) -> np.ndarray:
 
 
 def sgd_update(Z, dZ, lr: float) -> np.ndarray:
-    """Z <- Z - eta * dL/dZ  (Alg. 1 line 10; plain SGD, no momentum)."""
+    """Z <- Z - eta * dL/dZ  (the update step of Alg. 1; plain SGD, no momentum)."""
     return _f64(Z) - float(lr) * _f64(dZ)
 
 
@@ -409,7 +409,7 @@ def adam_update(Z, dZ, m, v, step: int, lr: float, beta1: float = 0.9, beta2: fl
 
 
 def rotate_loss_grad(X, R, reduce: str = "mean", objective: str = "whip", bits: int = 4):
-    """(loss, G, Y, dY) for a given rotation R  (Alg. 1 lines 8-9 and dL/dR).  The quantisation objective decides
+    """(loss, G, Y, dY) for a given rotation R  (Alg. 1, its rotation and loss steps, and dL/dR).  The quantisation objective decides
     its codes on Y rounded to float32 (the precision the GPU path holds Y in)."""
     Y = rotate(X, R)
     if objective == "quant":
@@ -420,7 +420,7 @@ def rotate_loss_grad(X, R, reduce: str = "mean", objective: str = "whip", bits: 
 
 
 def calib_step(X, Z, lr: float, reduce: str = "mean", objective: str = "whip", bits: int = 4):
-    """One pass of the loop body of Alg. 1 (lines 7-10).
+    """One pass of the loop body of Alg. 1.
 
     Returns a dict with the loss and rotation computed from the INPUT Z, the gradient
     dZ, and the updated latent Z_new.
@@ -435,7 +435,7 @@ def calib_step(X, Z, lr: float, reduce: str = "mean", objective: str = "whip", b
 
 def calib_step_adam(X, Z, m, v, step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
                     reduce: str = "mean"):
-    """The loop body of Alg. 1 with Adam in place of the SGD update of line 10."""
+    """The loop body of Alg. 1 with Adam in place of its SGD update."""
     Z = _f64(Z)
     R, U = qr_orth(Z)
     loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
@@ -461,7 +461,7 @@ def calibrate(X, Z0, steps: int, lr: float, reduce: str = "mean"):
 
 
 def calibrate_batches(X_batches, Z0, steps: int, lr: float, reduce: str = "mean"):
-    """The loop of Alg. 1 over mini-batches (lines 3-11): step k runs the loop body on batch k mod len(X_batches),
+    """The loop of Alg. 1 over mini-batches: step k runs the loop body on batch k mod len(X_batches),
     epoch after epoch in the given order.  Returns (losses, Z_final)."""
     Z = _f64(Z0)
     losses = []
@@ -499,7 +499,7 @@ def cayley_sgd_update(R, G, M, lr: float, beta: float = 0.9, q: float = 0.5, s: 
 def cayley_step(X, R, M, lr: float, beta: float = 0.9, reduce: str = "mean", q: float = 0.5, s: int = 2,
                 eps: float = 1e-8):
     """One calibration step with the optimiser of Alg. 3 in place of QR-Orth: loss and dL/dR at the INPUT rotation
-    (Alg. 1 lines 8-9), then the Cayley update of R itself.  Returns a dict like ``calib_step``."""
+    (Alg. 1, rotation and loss steps), then the Cayley update of R itself.  Returns a dict like ``calib_step``."""
     loss, G, Y, dY = rotate_loss_grad(X, R, reduce)
     R_new, M_new, alpha, W = cayley_sgd_update(R, G, M, lr, beta, q, s, eps)
     return {"loss": loss, "G": G, "R_new": R_new, "M_new": M_new, "alpha": alpha, "W": W}

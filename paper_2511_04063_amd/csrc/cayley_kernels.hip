@@ -9,7 +9,7 @@
 namespace dq {
 namespace {
 
-// M <- beta M - G  (Alg. 3 line 4)
+// M <- beta M - G  (Alg. 3, momentum update)
 __global__ __launch_bounds__(256) void cayley_momentum_kernel(float* __restrict__ M, long ldm, const float* __restrict__ G,
                                                              long ldg, int n, float beta) {
     const int q = (n + 3) >> 2;
@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void cayley_momentum_kernel(float* __restrict_
     }
 }
 
-// W = What - What^T (Alg. 3 line 6) on 32 x 32 tiles: tile (bi, bj) and its mirror are both read row-wise (coalesced)
+// W = What - What^T (Alg. 3, skew-symmetrisation) on 32 x 32 tiles: tile (bi, bj) and its mirror are both read row-wise (coalesced)
 // and the mirror is transposed through LDS.  Each block also leaves the sum of squares of the entries it wrote.
 __global__ __launch_bounds__(256) void cayley_skew_kernel(const float* __restrict__ H, long ldh, int n, float* __restrict__ W,
                                                          long ldw, double* __restrict__ partials) {
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void cayley_skew_kernel(const float* __restric
     if (threadIdx.x == 0) partials[blockIdx.x] = ((double)wsum[0] + (double)wsum[1]) + ((double)wsum[2] + (double)wsum[3]);
 }
 
-// alpha = min(lr, 2 q / (||W||_F + eps))  (Alg. 3 line 8); out[0] = alpha, out[1] = alpha / 2
+// alpha = min(lr, 2 q / (||W||_F + eps))  (Alg. 3, step-size rule); out[0] = alpha, out[1] = alpha / 2
 __global__ __launch_bounds__(256) void cayley_alpha_kernel(const double* __restrict__ partials, int count, float lr, float q,
                                                           float eps, float* __restrict__ out) {
     __shared__ double sh[256];

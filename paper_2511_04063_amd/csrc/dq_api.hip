@@ -1,5 +1,5 @@
 // C ABI of libdartqr.so: argument checking, workspace carving and the sequencing of the kernels of one
-// QR-Orth step (Alg. 1 lines 7-10) on the caller's HIP stream.  No device memory is allocated here.
+// QR-Orth step (the loop body of Alg. 1) on the caller's HIP stream.  No device memory is allocated here.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>

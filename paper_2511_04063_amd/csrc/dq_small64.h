@@ -1,6 +1,6 @@
 // 64 x 64 dense building blocks that live in LDS and run on one workgroup of 256 threads (4 wavefronts):
 // products on the fp32 matrix cores and the inverse of a triangular matrix.  Used by the tall-panel route of the
-// QR (Alg. 2 in blocked form) and by the triangular solve of the derivative through the QR (Alg. 1 line 10).
+// QR (Alg. 2 in blocked form) and by the triangular solve of the derivative through the QR (the last step of Alg. 1).
 // Matrices are row-major with row stride LS; every routine that says so ends with a workgroup barrier and must
 // be called by all 256 threads.
 #pragma once

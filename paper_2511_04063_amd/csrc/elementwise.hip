@@ -1,9 +1,9 @@
 // HBM-bound passes of the step:
-//   * the fused Whip loss + gradient pass over Y (Eq. 4 and its derivative; Alg. 1 line 9),
+//   * the fused Whip loss + gradient pass over Y (Eq. 4 and its derivative; the loss step of Alg. 1),
 //   * the two-plane bf16 split of the rotation with a transpose (operand preparation for X @ R),
 //   * P = strict_lower(B - B^T) of the derivative through Z = R U,
 //   * inverses of the diagonal blocks of U for the blocked triangular solve,
-//   * the SGD update Z <- Z - eta dZ (Alg. 1 line 10).
+//   * the SGD update Z <- Z - eta dZ (the last step of Alg. 1).
 #include <math.h>
 #include <stdlib.h>
 
@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void split3_bf16_kernel(const float* __restric
 
 // dst (cols x rows) = src^T for a rows x cols bf16 matrix, 64 x 64 tiles through LDS with 16-byte loads and stores.
 // rows and cols are multiples of 64, both leading dimensions multiples of 8 and both pointers 16-byte aligned.
-// Operand preparation for G = X^T dY (Alg. 1 line 9): with both operands stored token-contiguous the product reads
+// Operand preparation for G = X^T dY (the loss step of Alg. 1): with both operands stored token-contiguous the product reads
 // rows only.
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t* __restrict__ src, long lds_, int rows,
                                                              int cols, bf16_t* __restrict__ dst, long ldd) {
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void outlier_count_kernel(const float* __restr
     if ((threadIdx.x & 63) == 0 && local != 0) atomicAdd(count, (unsigned long long)local);
 }
 
-// out[t][:] = src[idx[t]][:] for t < rows_out: the token-sampling step in front of the loop (Alg. 1 line 5) as a
+// out[t][:] = src[idx[t]][:] for t < rows_out: the token-sampling step in front of the loop (Alg. 1) as a
 // gather of whole rows, 16 bytes per lane (row_bytes is a multiple of 16, rows 16-byte aligned).  An index outside
 // [0, rows_in) copies nothing for that row and raises the flag.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ src, long src_stride, int rows_in,

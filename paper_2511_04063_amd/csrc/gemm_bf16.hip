@@ -1,7 +1,7 @@
 // bf16 x bf16 -> fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), LDS-staged,
 // double-buffered:   C (M x N, fp32) = op(A) * op(B).
 //
-// Serves the two large products of Alg. 1:  O = X @ R (line 8; X bf16, R split into two bf16 planes hi + lo
+// Serves the two large products of Alg. 1:  O = X @ R (its rotation step; X bf16, R split into two bf16 planes hi + lo
 // and stored transposed so that both operands are k-contiguous) and G = X^T @ dY (the chain rule to R; both operands
 // are stored with the reduction dimension, the tokens, as rows, and are transposed on their way into LDS).
 //
@@ -237,7 +237,7 @@ __device__ __forceinline__ void multiply_tile(const bf16_t (*Asc)[LDD], const bf
     }
 }
 
-// WHIP: the epilogue applies the Whip loss and its derivative (Eq. 4; Alg. 1 line 9) to the accumulators instead of
+// WHIP: the epilogue applies the Whip loss and its derivative (Eq. 4; the loss step of Alg. 1) to the accumulators instead of
 // (or beside) writing them: per-workgroup partial sums of exp(-|y|) go to g.whip_partials[workgroup], and
 // dY = -scale sgn(y) exp(-|y|) is written TRANSPOSED in bf16 (g.whip_dyt: N x M, token-contiguous), staged through
 // the operand buffers in LDS so that every row of 128 tokens leaves as one 256-byte run.

@@ -12,7 +12,7 @@
 //
 // This kernel serves the trailing updates of the blocked Householder QR (Alg. 2 in compact-WY form),
 // the accumulation of the orthogonal factor, the fp32 X @ R / X^T @ dY products and the three products
-// of the derivative through Z = R U (Alg. 1 line 10).
+// of the derivative through Z = R U (the last step of Alg. 1).
 #include "dq_internal.h"
 
 namespace dq {

@@ -3,7 +3,7 @@
 //   * heads_qr_kernel: R, U = qr(Z) for one 128 x 128 latent per workgroup, entirely in LDS.  Alg. 2 as printed:
 //     column by column, the reflector is applied to the trailing columns of the matrix and accumulated into the
 //     orthogonal factor in the same step (A <- H A, Q <- Q H); the signs are then fixed so that diag(U) >= 0.
-//   * heads_rlg_kernel: Alg. 1 lines 8-9 fused for bf16 activations.  A workgroup streams 64-token tiles of X once;
+//   * heads_rlg_kernel: Alg. 1, rotation and loss steps, fused for bf16 activations.  A workgroup streams 64-token tiles of X once;
 //     Y = X R (R as two bf16 planes held in registers), the Whip loss and its gradient (Eq. 4) and the tile's
 //     contribution to G = X^T dY are formed on chip: Y and dY never reach HBM.
 //   * heads_reduce_kernel: sums the per-workgroup partial G and loss.

@@ -1028,7 +1028,7 @@ def test_calib_step_tiny_trajectory(ctx):
 
 
 def test_calib_step_adam_tiny(ctx):
-    """Alg. 1 with Adam in place of line 10's SGD update: the loss against the oracle on the same input, the update
+    """Alg. 1 with Adam in place of its SGD update: the loss against the oracle on the same input, the update
     against the oracle's Adam rule fed with the GPU's own dZ (Adam divides by |g|-like quantities, so entries whose
     gradient is at rounding level would otherwise decide the comparison), state carried over four steps."""
     inp = synth.make_inputs("tiny")

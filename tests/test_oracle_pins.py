@@ -163,7 +163,7 @@ def test_rotate_preserves_norms_and_identity():
 
 
 def test_rotate_is_row_vector_convention():
-    # Y[t, i] = sum_c X[t, c] R[c, i]  (O = X @ R, Alg. 1 line 8), written as loops
+    # Y[t, i] = sum_c X[t, c] R[c, i]  (O = X @ R, the rotation step of Alg. 1), written as loops
     g = rng(12)
     X = g.standard_normal((3, 4))
     R = g.standard_normal((4, 4))
@@ -499,7 +499,7 @@ def test_calib_step_adam_composes_the_pieces():
     assert np.array_equal(out["Z_new"], Zn) and np.array_equal(out["m"], mn) and np.array_equal(out["v"], vn)
 
 
-# ----------------------------------------------------------------------------------- token sampling (Alg. 1 line 5)
+# ----------------------------------------------------------------------------------- token sampling (Alg. 1)
 def test_token_sampling_invariants():
     g = np.random.Generator(np.random.Philox(901))
     T, n = 57, 12
