@@ -126,11 +126,17 @@ typedef enum {
                                        bits; the six plane pairs above fp32 rounding are accumulated in fp32).  0: never
                                        (fp32 matrix cores); 1 (default): when n is a multiple of 256 and at least 2560,
                                        where it is faster; 2: whenever n is a multiple of 256. */
-    DQ_OPT_FUSED_PANEL = 7          /* S1: a tall 64-column panel that follows a tall panel and is followed by one as ONE
+    DQ_OPT_FUSED_PANEL = 7,         /* S1: a tall 64-column panel that follows a tall panel and is followed by one as ONE
                                        launch whose workgroups hand over to each other through words in device memory
                                        (bounded polls, DQ_FLAG_SYNC_TIMEOUT) instead of three dependent launches.  Only
                                        taken where DQ_OPT_DEVICE_SYNC's hand-over is in use (not under stream capture).
                                        0: never; 1 (default) and 2: wherever the panel qualifies. */
+    DQ_OPT_TWO_LEVEL_ROWS = 8       /* S1: two-level blocking.  While a block of 256 columns (four panels) has more rows than
+                                       this, its panels' reflectors are applied one by one only to the 320 columns after the
+                                       block's start; everything further right gets ONE update per block with the block's
+                                       merged reflector (reduction length 256 instead of 64: a quarter of the passes over the
+                                       trailing matrix).  Needs DQ_OPT_DEVICE_SYNC's hand-over and n a multiple of 256.
+                                       0: never; -1 (default): 2048 rows in matrices of order 6144 or more, never below. */
 } dq_option;
 dq_status dq_set_option(dq_ctx* ctx, dq_option option, int value);
 

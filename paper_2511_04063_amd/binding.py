@@ -20,7 +20,7 @@ DQ_REDUCE_TOKEN_MEAN, DQ_REDUCE_SUM = 0, 1
 DQ_OBJ_WHIP, DQ_OBJ_VARIANCE, DQ_OBJ_KURTOSIS, DQ_OBJ_QUANT = 0, 1, 2, 3
 DQ_FLAG_SINGULAR, DQ_FLAG_NONFINITE, DQ_FLAG_ILLCOND_PANEL, DQ_FLAG_BAD_INDEX, DQ_FLAG_SYNC_TIMEOUT = 1, 2, 4, 8, 16
 DQ_K_GEMM_F32, DQ_K_GEMM_BF16, DQ_K_WHIP, DQ_K_PANEL, DQ_K_SMALL, DQ_K_COUNT = range(6)
-DQ_OPT_ACCUM_PANELS, DQ_OPT_TALL_PANEL_MIN_ROWS, DQ_OPT_SINGLE_STREAM, DQ_OPT_FUSED_WHIP, DQ_OPT_HEADS_BATCHED, DQ_OPT_DEVICE_SYNC, DQ_OPT_SPLIT_GEMM, DQ_OPT_FUSED_PANEL = range(8)
+DQ_OPT_ACCUM_PANELS, DQ_OPT_TALL_PANEL_MIN_ROWS, DQ_OPT_SINGLE_STREAM, DQ_OPT_FUSED_WHIP, DQ_OPT_HEADS_BATCHED, DQ_OPT_DEVICE_SYNC, DQ_OPT_SPLIT_GEMM, DQ_OPT_FUSED_PANEL, DQ_OPT_TWO_LEVEL_ROWS = range(9)
 DQ_MAX_N = 8192
 
 _c = ctypes

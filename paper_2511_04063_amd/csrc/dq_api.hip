@@ -103,6 +103,8 @@ struct dq_ctx {
     unsigned long long arrived = 0;  // workgroups counted so far by the one-launch panels' word (zeroed with the status word)
     unsigned long long arrived_rows = 0;   // ... and those below the top block, counted by a word of their own
     int fused_panel = 1;             // tall panels between tall panels as one launch: 0 never, 1 up to fused_panel_rows rows, 2 always
+    int two_level_rows = -1;         // blocks of 256 columns with more rows than this defer the update of everything right of
+                                     // the next block to ONE product with the block's merged reflector; 0 never, -1 default
 
     struct Probed { hipStream_t s; bool ok; };
     std::vector<Probed> probed;      // per caller stream: do it and the two internal streams progress independently?
@@ -116,9 +118,11 @@ struct dq_ctx {
 namespace {
 
 // ---------------------------------------------------------------- workspace layout
+constexpr int kYbRing = 4;    // merged reflector blocks kept at a time (two-level QR)
+constexpr int kFarSplit = 4;  // most split-K layers of a deferred update's projection
 struct Layout {
     long ld = 0;          // leading dimension of every internal n x n fp32 matrix
-    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0,
+    size_t flags = 0, A = 0, R = 0, U = 0, G = 0, B = 0, P = 0, M = 0, tau = 0, Tall = 0, wpart = 0, w2 = 0, wpartB = 0, w2B = 0, qpart = 0, qw = 0, yblk = 0, spart = 0, yring = 0, spartB = 0, wpartF1 = 0, w2F1 = 0, wpartF2 = 0, w2F2 = 0,
            vs = 0, cq = 0, tsl = 0, yall = 0, uinv = 0, uinvo = 0, utmp = 0, x3a = 0, x3b = 0, x3c = 0, x3d = 0, Y = 0, dY = 0, xt = 0, dyt = 0, rbt = 0, losspart = 0, scal = 0, gsplit = 0;
     size_t gsplit_floats = 0;
     size_t total = 0;
@@ -154,6 +158,14 @@ Layout make_layout(int n, int T) {
     L.qw = bump(cur, (size_t)n * kAccumPanels * kPanel * 4);
     L.yblk = bump(cur, (size_t)n * kAccumPanels * kPanel * 4);
     L.spart = bump(cur, (size_t)(kMaxSplit + 1) * kAccumPanels * kPanel * kPanel * 4);
+    // two-level blocking of the QR: a ring of merged reflector blocks Yb = V T (n x 256 each), the merge's partials on the
+    // second stream, and the projections of the two deferred updates (256 x ld, up to kFarSplit layers)
+    L.yring = bump(cur, (size_t)kYbRing * n * kAccumPanels * kPanel * 4);
+    L.spartB = bump(cur, (size_t)(kMaxSplit + 1) * kAccumPanels * kPanel * kPanel * 4);
+    L.wpartF1 = bump(cur, (size_t)kFarSplit * kAccumPanels * kPanel * L.ld * 4);
+    L.w2F1 = bump(cur, (size_t)kAccumPanels * kPanel * L.ld * 4);
+    L.wpartF2 = bump(cur, (size_t)kFarSplit * kAccumPanels * kPanel * L.ld * 4);
+    L.w2F2 = bump(cur, (size_t)kAccumPanels * kPanel * L.ld * 4);
     L.vs = bump(cur, panel_scratch_floats(n) * 4);
     L.cq = bump(cur, cholpanel_scratch_floats() * 4);
     L.tsl = bump(cur, (size_t)kPanel * kPanel * 4);
@@ -359,60 +371,65 @@ dq_status accumulate_q(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0,
 //   Yb_j = [0; Yp_j] - Yb_{<j} (V_{<j}^T [0; Yp_j]).
 // A K = 256 update reads and writes the accumulated factor once per four panels instead of once per panel (the
 // K = 64 update is bound by that traffic), for a few small products more.
-dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, int nb, int q0, int np, float* A, long ld,
-                             float* yall, float* Q, long ldq) {
+// (merge_yb_step builds one column group of Yb, accumulate_q_apply applies a merged block; the two-level QR uses both.)
+// One column group of the merged block: panel q0 + j of the block that starts at panel q0 goes into Yb (ld 256).
+dq_status merge_yb_step(dq_ctx* c, hipStream_t s, int n, int nb, int q0, int j, float* A, long ld, float* yall,
+                        float* Yb, float* spart) {
     const int k0 = q0 * nb;
     const int mb = n - k0;
     float* Ablk = A + (long)k0 * ld + k0;
-    float* Yb = at<float>(c, L.yblk);
     const long ldy = (long)kAccumPanels * kPanel;
-    float* spart = at<float>(c, L.spart);
     float* sred = spart + (size_t)kMaxSplit * kAccumPanels * kPanel * kPanel;
-    int w = 0;
-    for (int j = 0; j < np; ++j) {
-        const int q = q0 + j;
-        const int off = q * nb - k0;
-        const int mq = n - q * nb;
-        const int jq = mq < nb ? mq : nb;
-        const float* Ypq = yall + (long)q * n * kPanel;
-        {
-            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * mb * (double)jq);
-            if (off > 0) DQ_HIP(launch_copy2d(nullptr, 0, Yb + off, ldy, off, jq, s));
-            DQ_HIP(launch_copy2d(Ypq, kPanel, Yb + (long)off * ldy + off, ldy, mq, jq, s));
-        }
-        if (j > 0) {
-            // S = V_{<j}^T [0; Yp_j]: only rows >= off of V_{<j} meet non-zeros, all of them below its diagonal
-            int splits, kchunk;
-            choose_split(((off + 63) / 64) * ((jq + 63) / 64), mq, 32, kMaxSplit, splits, kchunk);
-            const long stride = (long)kAccumPanels * kPanel * kPanel;
-            {
-                GemmF32 g;
-                g.cfg = 3;
-                g.A = Ablk + (long)off * ld; g.lda = ld; g.ta = 1;
-                g.B = Ypq; g.ldb = kPanel; g.tb = 0;
-                g.C = splits > 1 ? spart : sred; g.ldc = kPanel;
-                g.M = off; g.N = jq; g.K = mq;
-                g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
-                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * off * (double)jq * mq, 0.0);
-                DQ_HIP(launch_gemm_f32(g, s));
-            }
-            if (splits > 1) {
-                LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
-                DQ_HIP(launch_splitk_reduce(spart, splits, stride, kPanel, off, jq, 1.f, 0.f, sred, kPanel, s));
-            }
-            {
-                GemmF32 g;   // Yb_j -= Yb_{<j} S
-                g.A = Yb; g.lda = ldy; g.ta = 0;
-                g.B = sred; g.ldb = kPanel; g.tb = 0;
-                g.C = Yb + off; g.ldc = ldy;
-                g.M = mb; g.N = jq; g.K = off;
-                g.alpha = -1.f; g.beta = 1.f;
-                LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mb * (double)jq * off, 0.0);
-                DQ_HIP(launch_gemm_f32(g, s));
-            }
-        }
-        w = off + jq;
+    const int q = q0 + j;
+    const int off = q * nb - k0;
+    const int mq = n - q * nb;
+    const int jq = mq < nb ? mq : nb;
+    const float* Ypq = yall + (long)q * n * kPanel;
+    {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 8.0 * mb * (double)jq);
+        if (off > 0) DQ_HIP(launch_copy2d(nullptr, 0, Yb + off, ldy, off, jq, s));
+        DQ_HIP(launch_copy2d(Ypq, kPanel, Yb + (long)off * ldy + off, ldy, mq, jq, s));
     }
+    if (j > 0) {
+        // S = V_{<j}^T [0; Yp_j]: only rows >= off of V_{<j} meet non-zeros, all of them below its diagonal
+        int splits, kchunk;
+        choose_split(((off + 63) / 64) * ((jq + 63) / 64), mq, 32, kMaxSplit, splits, kchunk);
+        const long stride = (long)kAccumPanels * kPanel * kPanel;
+        {
+            GemmF32 g;
+            g.cfg = 3;
+            g.A = Ablk + (long)off * ld; g.lda = ld; g.ta = 1;
+            g.B = Ypq; g.ldb = kPanel; g.tb = 0;
+            g.C = splits > 1 ? spart : sred; g.ldc = kPanel;
+            g.M = off; g.N = jq; g.K = mq;
+            g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * off * (double)jq * mq, 0.0);
+            DQ_HIP(launch_gemm_f32(g, s));
+        }
+        if (splits > 1) {
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+            DQ_HIP(launch_splitk_reduce(spart, splits, stride, kPanel, off, jq, 1.f, 0.f, sred, kPanel, s));
+        }
+        {
+            GemmF32 g;   // Yb_j -= Yb_{<j} S
+            g.A = Yb; g.lda = ldy; g.ta = 0;
+            g.B = sred; g.ldb = kPanel; g.tb = 0;
+            g.C = Yb + off; g.ldc = ldy;
+            g.M = mb; g.N = jq; g.K = off;
+            g.alpha = -1.f; g.beta = 1.f;
+            LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * mb * (double)jq * off, 0.0);
+            DQ_HIP(launch_gemm_f32(g, s));
+        }
+    }
+    return DQ_OK;
+}
+
+// Q[:, k0:] <- Q[:, k0:] - (Q[:, k0:] Yb) V^T for a merged block of width w whose top-left corner is (k0, k0).
+dq_status accumulate_q_apply(dq_ctx* c, hipStream_t s, const Layout& L, int n, int k0, int w, float* A, long ld,
+                             const float* Yb, float* Q, long ldq) {
+    const int mb = n - k0;
+    float* Ablk = A + (long)k0 * ld + k0;
+    const long ldy = (long)kAccumPanels * kPanel;
     float* qpart = at<float>(c, L.qpart);
     float* qw = at<float>(c, L.qw);
     float* Qc = Q + k0;
@@ -448,6 +465,48 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
     return DQ_OK;
 }
 
+dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, int nb, int q0, int np, float* A, long ld,
+                             float* yall, float* Q, long ldq) {
+    float* Yb = at<float>(c, L.yblk);
+    int w = 0;
+    for (int j = 0; j < np; ++j) {
+        DQ_TRY(merge_yb_step(c, s, n, nb, q0, j, A, ld, yall, Yb, at<float>(c, L.spart)));
+        const int mq = n - (q0 + j) * nb;
+        w += mq < nb ? mq : nb;
+    }
+    return accumulate_q_apply(c, s, L, n, q0 * nb, w, A, ld, Yb, Q, ldq);
+}
+
+// The block reflector of a merged block (w columns from (k0, k0); Yb = V T, ld 256) applied to the columns
+// [c0, c0 + nc) of the factored matrix:  W = Yb^T C,  C -= V W, with reduction length w in the second product.
+dq_status far_update(dq_ctx* c, hipStream_t s, const Layout& L, float* wpart, float* wsum, int n, int k0, int w,
+                     float* A, long ld, const float* Yb, int c0, int nc) {
+    if (nc <= 0) return DQ_OK;
+    const int mb = n - k0;
+    const long ldy = (long)kAccumPanels * kPanel;
+    const long ldw = L.ld;
+    const long stride = (long)kAccumPanels * kPanel * ldw;
+    float* Ablk = A + (long)k0 * ld + k0;
+    float* Cf = A + (long)k0 * ld + c0;
+    int splits, kchunk;
+    choose_split(((w + 127) / 128) * ((nc + 127) / 128), mb, 16, kFarSplit, splits, kchunk);
+    {
+        GemmF32 g;   // W = Yb^T C
+        g.A = Yb; g.lda = ldy; g.ta = 1;
+        g.B = Cf; g.ldb = ld; g.tb = 0;
+        g.C = splits > 1 ? wpart : wsum; g.ldc = ldw;
+        g.M = w; g.N = nc; g.K = mb;
+        g.splits = splits; g.kchunk = kchunk; g.split_stride = stride;
+        LaunchScope sc(&c->prof, s, DQ_K_GEMM_F32, 2.0 * w * (double)nc * mb, 0.0);
+        DQ_HIP(launch_gemm_f32(g, s));
+    }
+    if (splits > 1) {
+        LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 0.0);
+        DQ_HIP(launch_splitk_reduce(wpart, splits, stride, ldw, w, nc, 1.f, 0.f, wsum, ldw, s));
+    }
+    return refl_update(c, s, L, Ablk, ld, wsum, mb, w, Cf, ld, nc);
+}
+
 // ---------------------------------------------------------------- hand-over between the QR's streams
 // Seven 8-byte words behind the status word, cleared with it: [0] panels factored, [1] trailing updates done,
 // [2] the probe's word, [3] set by a probe wait that gave up, [4..6] the words of the one-launch panels
@@ -455,6 +514,9 @@ dq_status accumulate_q_block(dq_ctx* c, hipStream_t s, const Layout& L, int n, i
 constexpr long kSyncLimitUs = 5L * 1000 * 1000;   // a hand-over that takes this long is a fault, not a delay
 constexpr long kProbeLimitUs = 2000;
 constexpr int kFusedPanelRows = 8192;   // tallest panel that takes the one-launch route by default
+constexpr int kTwoLevelRows = 2048;     // blocks of 256 columns taller than this take the two-level route by default ...
+constexpr int kTwoLevelMinN = 6144;     // ... in matrices of at least this order (measured: 8192 27.7 -> 26.0 ms; 5120 and
+                                        // 4096, where the panel chain and not the rank-64 updates sets the pace: +-1 %, +3 %)
 unsigned long long* sync_words(dq_ctx* c) { return reinterpret_cast<unsigned long long*>(c->ws + 128); }
 
 // Device-side hand-over needs the consumer's wait kernel and the producer's signal kernel to run at the same time.
@@ -512,7 +574,6 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     float* yall = at<float>(c, L.yall);
     unsigned* flags = at<unsigned>(c, L.flags);
     const ReflBufs bufA{at<float>(c, L.wpart), at<float>(c, L.w2)};
-    const ReflBufs bufB{at<float>(c, L.wpartB), at<float>(c, L.w2B)};
     const long ld = L.ld;
     // how the streams wait for each other: a device word (see device_sync_usable) or events
     const bool dsync = device_sync_usable(c);
@@ -552,6 +613,23 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
     c->seq += npanels + 1;
     int last_trailing = -1;
     bool gram_ready = false;   // the first small step of the coming panel (chol of its Gram matrix) was done beside the previous panel's look-ahead
+    // Two-level blocking for the tall part of a large matrix: in a block of 256 columns (four panels) each panel's
+    // reflector only reaches the 256 + 64 columns after the block's start on the second stream ("near"); everything
+    // right of that receives ONE update per block with the block's merged reflector, reduction length 256 instead of 64
+    // (a quarter of the passes over the trailing matrix): first the columns the next block's panels need ("far-near",
+    // second stream, signals word F), then the rest ("far-rest", third stream in front of the accumulation of R, which
+    // uses the same merged block; signals F2; the accumulation F3, which frees the block's slot in the ring of merged
+    // blocks).  The panel chain runs on across block boundaries: a block's first panel waits for F of the block before.
+    const int ob = kAccumPanels * kPanel;
+    const int two_rows = c->two_level_rows < 0 ? (n >= kTwoLevelMinN ? kTwoLevelRows : 0) : c->two_level_rows;
+    int tl_blocks = 0;
+    if (dsync && !c->single_stream && two_rows > 0 && n % ob == 0 && c->chol_min_m > 0 && c->chol_min_m <= 4 * nb)
+        while ((tl_blocks + 1) * ob < n && n - tl_blocks * ob > two_rows) ++tl_blocks;
+    unsigned long long* wF = words + 11;    // far-near of block b done: seq0 + b + 1
+    unsigned long long* wF2 = words + 12;   // far-rest of block b done
+    unsigned long long* wF3 = words + 13;   // accumulation of block b done
+    const ReflBufs bufB{at<float>(c, L.wpartB), at<float>(c, L.w2B)};
+    float* yring = at<float>(c, L.yring);
     for (int p = 0; p < npanels; ++p) {
         const int k0 = p * nb;
         const int jb = (n - k0) < nb ? (n - k0) : nb;
@@ -565,6 +643,14 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         // Gram matrix of the reflectors.
         const bool tall = c->chol_min_m > 0 && m >= c->chol_min_m && cholpanel_supported(Ap, ld, m, jb);
         bool signalled = false;   // "panel p is factored" already goes out from inside the panel's kernels
+        const bool two = p < kAccumPanels * tl_blocks;          // this panel's block takes the two-level route
+        const int blk = p / kAccumPanels, jblk = p % kAccumPanels;
+        const int K0 = blk * ob;
+        // what the look-ahead columns (and, without the fused look-ahead, the kernels that read them) wait for: the
+        // previous trailing update, or, behind a two-level block, that block's far-near update
+        const bool after_block = tl_blocks > 0 && jblk == 0 && blk > 0 && blk <= tl_blocks;
+        const unsigned long long* la_word = after_block ? wF : (last_trailing >= 0 ? words + 1 : nullptr);
+        const unsigned long long la_value = after_block ? seq0 + blk : seq0 + last_trailing + 1;
         if (tall) {
             // the look-ahead update of the next panel's columns is fused into the last two kernels of the route when
             // that panel is a full one; they also leave the Cholesky factor of the Gram matrix the next tall panel starts from
@@ -578,8 +664,8 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
                                       ? cholqr_fused_workgroups(m) : 0;
             if (fused_wgs > 0) {
                 HandOver ho;
-                if (last_trailing >= 0) {
-                    ho.wait_word = words + 1; ho.wait_value = seq0 + last_trailing + 1;
+                if (la_word != nullptr) {
+                    ho.wait_word = la_word; ho.wait_value = la_value;
                     ho.limit_us = kSyncLimitUs; ho.flags = flags;
                 }
                 ho.signal_word = words; ho.signal_value = seq0 + p + 1;
@@ -602,8 +688,8 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
             HandOver ho;
             signalled = dsync && fused_la;
             if (signalled) {
-                if (last_trailing >= 0) {
-                    ho.wait_word = words + 1; ho.wait_value = seq0 + last_trailing + 1;
+                if (la_word != nullptr) {
+                    ho.wait_word = la_word; ho.wait_value = la_value;
                     ho.limit_us = kSyncLimitUs; ho.flags = flags;
                 }
                 ho.signal_word = words; ho.signal_value = seq0 + p + 1;
@@ -650,10 +736,16 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
             }
             DQ_TRY(refl_make_y(c, sA, Ap, ld, m, jb, Tp, 0, Yp));
         }
-        const int rest = m - jb - nla;
+        // one level: everything right of the look-ahead columns; two levels: up to 64 columns into the next block
+        int rest = m - jb - nla;
+        if (two) rest = (K0 + ob + nb < n ? K0 + ob + nb : n) - (k0 + jb + nla);
+        if (rest < 0) rest = 0;
         if (!signalled) DQ_HIP(panel_done(p));
+        if (rest > 0 || two) DQ_HIP(after_panel(sB, p));
         if (rest > 0) {   // C -= V (Yp^T C) for the rest of the trailing matrix, behind the next panel
-            DQ_HIP(after_panel(sB, p));
+            // the first panel behind the two-level blocks updates columns that the last block's far-rest update reaches
+            if (!two && tl_blocks > 0 && p == kAccumPanels * tl_blocks)
+                DQ_HIP(launch_stream_wait(wF2, seq0 + tl_blocks, kSyncLimitUs, flags, nullptr, sB));
             const float* Wb = nullptr;
             DQ_TRY(refl_project(c, sB, L, bufB, Yp, kPanel, m, jb, Ap + jb + nla, ld, rest, 0, &Wb, kMaxSplit, nullptr, 0));
             DQ_TRY(refl_update(c, sB, L, Ap, ld, Wb, m, jb, Ap + jb + nla, ld, rest));
@@ -663,8 +755,29 @@ dq_status qr_orth_one(dq_ctx* c, const Layout& L, int n, const float* Z, long ld
         // S2, overlapped with the factorisation of the next panels: the orthogonal factor is accumulated from the
         // left to the right, Q[:, k0:] <- Q[:, k0:] (I - V T V^T)  (as Alg. 2 does column by column), on the third
         // stream, several panels at a time.
+        if (two) {
+            // this panel's column group of the block's merged reflector, on the second stream behind its near update;
+            // the slot of the ring is free once the accumulation of the block that used it last has run
+            float* Yb = yring + (size_t)(blk % kYbRing) * n * ob;
+            if (jblk == 0 && blk >= kYbRing)
+                DQ_HIP(launch_stream_wait(wF3, seq0 + blk - kYbRing + 1, kSyncLimitUs, flags, nullptr, sB));
+            DQ_TRY(merge_yb_step(c, sB, n, nb, blk * kAccumPanels, jblk, A, ld, yall, Yb, at<float>(c, L.spartB)));
+            if (jblk == kAccumPanels - 1) {
+                const int c1 = K0 + ob + nb;                              // first column the near updates did not reach
+                const int c2 = (c1 + ob) < n ? (c1 + ob) : n;             // far-near: what the next block's panels touch
+                // far-near needs the far-rest update of the block before on its columns
+                if (blk > 0) DQ_HIP(launch_stream_wait(wF2, seq0 + blk, kSyncLimitUs, flags, nullptr, sB));
+                DQ_TRY(far_update(c, sB, L, at<float>(c, L.wpartF1), at<float>(c, L.w2F1), n, K0, ob, A, ld, Yb, c1, c2 - c1));
+                DQ_HIP(launch_stream_signal(wF, seq0 + blk + 1, sB));
+                DQ_HIP(launch_stream_wait(wF, seq0 + blk + 1, kSyncLimitUs, flags, nullptr, sC));
+                DQ_TRY(far_update(c, sC, L, at<float>(c, L.wpartF2), at<float>(c, L.w2F2), n, K0, ob, A, ld, Yb, c2, n - c2));
+                DQ_HIP(launch_stream_signal(wF2, seq0 + blk + 1, sC));
+                DQ_TRY(accumulate_q_apply(c, sC, L, n, K0, ob, A, ld, Yb, R, ldr));
+                DQ_HIP(launch_stream_signal(wF3, seq0 + blk + 1, sC));
+            }
+        }
         const int ap = c->accum_panels > 0 ? c->accum_panels : (n >= 8192 ? 4 : 2);
-        if ((p + 1) % ap == 0 || p == npanels - 1) {
+        if (!two && ((p + 1) % ap == 0 || p == npanels - 1)) {
             const int q0 = (p / ap) * ap;
             DQ_HIP(after_panel(sC, p));
             if (p - q0 + 1 == 1)
@@ -1565,6 +1678,10 @@ dq_status dq_set_option(dq_ctx* c, dq_option option, int value) {
         case DQ_OPT_SINGLE_STREAM: c->single_stream = value != 0; return DQ_OK;
         case DQ_OPT_FUSED_WHIP: c->fused_whip = value != 0; return DQ_OK;
         case DQ_OPT_DEVICE_SYNC: c->device_sync = value != 0; return DQ_OK;
+        case DQ_OPT_TWO_LEVEL_ROWS:
+            if (value < -1) return DQ_ERR_SHAPE;
+            c->two_level_rows = value;
+            return DQ_OK;
         case DQ_OPT_FUSED_PANEL:
             if (value < 0 || value > 2) return DQ_ERR_SHAPE;
             c->fused_panel = value;

@@ -598,6 +598,42 @@ def test_qr_orth_one_launch_panels(n):
     assert rel(out[2][0], out[0][0]) < max(1e-5, 2e-8 * cond)
 
 
+@pytest.mark.parametrize("n,rows", [(1024, 256), (1536, 512), (2048, 1024)])
+def test_qr_orth_two_level_blocks(n, rows):
+    """Two-level blocking (DQ_OPT_TWO_LEVEL_ROWS): blocks of 256 columns taller than `rows` defer the update of what lies
+    right of the next block to one product with the block's merged reflector.  Against the oracle to the usual bars,
+    within rounding of the one-level route, and the same bits call after call (also across a read of the status word)."""
+    Z = rng(4700 + n).standard_normal((n, n)).astype(np.float32)
+    Ro, Uo = orc.qr_orth(Z)
+    cond = np.linalg.cond(Z.astype(np.float64))
+    out = {}
+    for mode in (0, rows):
+        c = B.Context()
+        c.ensure_workspace(1, n, 64, B.DQ_F32)
+        try:
+            c.dq_set_option(B.DQ_OPT_TWO_LEVEL_ROWS, mode)
+            got = []
+            for rep in range(4):
+                got.append(run_qr(c, Z))
+                if rep == 1:
+                    assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+            for R, U in got[1:]:
+                assert np.array_equal(R, got[0][0]) and np.array_equal(U, got[0][1])
+            R, U = got[0]
+            assert np.abs(R.astype(np.float64).T @ R.astype(np.float64) - np.eye(n)).max() < 1e-5
+            assert np.abs(np.tril(U, -1)).max() == 0.0 and (np.diag(U) > 0).all()
+            assert rel(U, Uo) < 1e-4
+            assert rel(R, Ro) < max(1e-4, 2e-7 * cond)
+            out[mode] = got[0]
+        finally:
+            torch.cuda.synchronize()
+            c.close()
+    assert rel(out[rows][1], out[0][1]) < 1e-5
+    assert rel(out[rows][0], out[0][0]) < max(1e-5, 2e-8 * cond)
+    assert not np.array_equal(out[rows][0], out[0][0])          # the deferred updates did run (another order of sums)
+
+
 def test_stream_hand_over_probe_is_bounded():
     """A device-side wait is bounded: enqueued IN FRONT of its own signal on one stream it can never be released, gives
     up after its 2 ms, reports 'not usable' and leaves the status word alone.  Between two streams of their own the
