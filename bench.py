@@ -290,7 +290,9 @@ def run_config(cfg_name: str, args):
     roof["frac"] = roof["achieved"] / roof["peak"]
     traffic, traffic_src = measured_traffic(cfg.name, CLASS_KERNEL.get(names[dominant]))
     roof["traffic"] = traffic
-    roof["traffic_unit"] = ("bytes per launch (fetch + write), from " + traffic_src) if traffic_src else None
+    roof["traffic_unit"] = ("bytes per launch (fetch + write), from " + traffic_src +
+                            " (counter collection serialises the streams: taken on the QR's event route, see that file)"
+                            ) if traffic_src else None
     roof["kernel"] = CLASS_KERNEL.get(names[dominant], names[dominant])
     roof["algorithmic_work_per_step"] = work
     roof["launches_per_step"] = dom["launches"] / args.steps
