@@ -1098,6 +1098,22 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
         g.A = pr3; g.lda = ld; g.a_plane = plane;
         g.B = pb3; g.ldb = ld; g.b_plane = plane; g.tb = 1; g.b_strict_lower = 1;
         g.M = n; g.N = n; g.K = n;
+        const int tiles = (n / 256) * (n / 256);
+        if (tiles <= 256) {
+            // At most one round of workgroups: the triangular product in two halves of every tile's reduction range, into
+            // the two n x n buffers that the solve has left free, summed by the kernel that also applies the step.  Whole,
+            // the longest tile alone takes as long as the full product (n = 4096: 632 -> 361 + 42 us; with 400 tiles,
+            // n = 5120, dealing the tiles out longest first already balances them: 3.50 -> 3.56 ms for the whole call).
+            g.C = Bb; g.ldc = ld; g.splits = 2; g.split_stride = Pb - Bb;
+            {
+                LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 6.0 * n3, 0.0);
+                DQ_HIP(launch_gemm_bf16x3(g, s));
+            }
+            LaunchScope sc(&c->prof, s, DQ_K_SMALL, 0.0, 16.0 * n * (double)n);
+            if (Zupd != nullptr) DQ_HIP(launch_splitk_reduce(Bb, 2, Pb - Bb, ld, n, n, -lr, 1.f, Zupd, ldz, s));
+            else DQ_HIP(launch_splitk_reduce(Bb, 2, Pb - Bb, ld, n, n, 1.f, 0.f, dZ, lddz, s));
+            return DQ_OK;
+        }
         if (Zupd != nullptr) { g.C = Zupd; g.ldc = ldz; g.alpha = -lr; g.beta = 1.f; }
         else { g.C = dZ; g.ldc = lddz; }
         LaunchScope sc(&c->prof, s, DQ_K_GEMM_BF16, 6.0 * n3, 0.0);

@@ -534,7 +534,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
     const int gsz = (tiles_m - first_m) < 8 ? (tiles_m - first_m) : 8;
     int pid_m = first_m + (pid % group) % gsz;
     int pid_n = (pid % group) / gsz;
-    if (X3 && g.b_strict_lower) { pid_n = bid / tiles_m; pid_m = bid % tiles_m; }
+    int zsplit = 0;
+    if (X3 && g.b_strict_lower) {
+        // column block by column block, the longest reductions first; with split-K the parts of a tile side by side
+        const int per_col = tiles_m * (g.splits > 1 ? g.splits : 1);
+        pid_n = bid / per_col;
+        zsplit = (bid % per_col) / tiles_m;
+        pid_m = bid % tiles_m;
+    }
     const int m0 = pid_m * TM, n0 = pid_n * TN;
 
     const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
@@ -544,8 +551,15 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
     const bf16_t* pa = g.A + (long)(m0 + prow) * g.lda + pk;
     const bf16_t* pb = g.B + (long)(n0 + prow) * g.ldb + pk;
     const int wrap = g.a_kwrap;
-    const int kbeg = (X3 && g.b_strict_lower) ? n0 : 0;
-    const int nk = X3 ? 6 * ((g.K - kbeg) / TK) : g.K / TK;           // even, >= 2
+    int kbeg = (X3 && g.b_strict_lower) ? n0 : 0;
+    int kend = g.K;
+    if (X3 && g.splits > 1) {
+        // split-K (with b_strict_lower only): part z of the tile's reduction range, in whole K steps, into C + z * split_stride
+        const int part = (((kend - kbeg) / TK + g.splits - 1) / g.splits) * TK;
+        kbeg += zsplit * part;
+        kend = kbeg + part < kend ? kbeg + part : kend;
+    }
+    const int nk = X3 ? 6 * ((kend - kbeg) / TK) : g.K / TK;           // even, >= 2
 
     BigAddr ad;
     ad.sa = 32 * g.lda; ad.sb = 32 * g.ldb;
@@ -560,7 +574,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
             ad.pa = pa + offa + kk;
             ad.pb = pb + offb + kk;
             kk += TK;
-            if (kk == g.K) {
+            if (kk == kend) {
                 if (seg < 5) {
                     kk = kbeg;
                     ++seg;
@@ -608,7 +622,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_nt_big_kernel(GemmBf16 g, in
 
     float* C = g.C;
     float alpha = g.alpha;
-    if constexpr (X3) { if (g.alpha_dev != nullptr) alpha *= *g.alpha_dev; }
+    if constexpr (X3) {
+        if (g.alpha_dev != nullptr) alpha *= *g.alpha_dev;
+        C += (long)zsplit * g.split_stride;
+    }
     if (!WHIP || C != nullptr) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -703,12 +720,15 @@ bool gemm_bf16_deep_fits(const GemmBf16& g) {
 bool gemm_bf16x3_fits(int M, int N, int K) { return M > 0 && N > 0 && K > 0 && M % TM == 0 && N % TN == 0 && K % TK == 0; }
 
 hipError_t launch_gemm_bf16x3(const GemmBf16& g, hipStream_t s) {
-    if (!gemm_bf16x3_fits(g.M, g.N, g.K) || g.ta || !g.tb || g.splits > 1 || g.a_kwrap != 0 || g.whip_dyt != nullptr ||
+    // split-K: only for the triangular product, every part at least two K steps (the shortest range is one tile width)
+    const bool split_ok = g.splits <= 1 || (g.b_strict_lower && g.splits <= TN / (2 * TK) && g.split_stride > 0);
+    if (!gemm_bf16x3_fits(g.M, g.N, g.K) || g.ta || !g.tb || !split_ok || g.a_kwrap != 0 || g.whip_dyt != nullptr ||
         (reinterpret_cast<uintptr_t>(g.A) & 15) || (reinterpret_cast<uintptr_t>(g.B) & 15) || (g.lda & 7) || (g.ldb & 7) ||
         (g.a_plane & 7) || (g.b_plane & 7) || g.C == nullptr || (g.b_strict_lower && g.K != g.N))
         return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_bf16_nt_big_kernel<false, true>), dim3((g.M / TM) * (g.N / TN)), dim3(256), 0, s, g, g.M / TM,
-                       g.N / TN);
+    const int parts = g.splits > 1 ? g.splits : 1;
+    hipLaunchKernelGGL((gemm_bf16_nt_big_kernel<false, true>), dim3((g.M / TM) * (g.N / TN) * parts), dim3(256), 0, s, g,
+                       g.M / TM, g.N / TN);
     return hipGetLastError();
 }
 
