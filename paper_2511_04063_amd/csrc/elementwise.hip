@@ -198,7 +198,7 @@ __device__ __forceinline__ void split3(float a, bf16_t& p1, bf16_t& p2, bf16_t& 
     p1 = (bf16_t)h1; p2 = (bf16_t)h2; p3 = (bf16_t)f32_to_bf16_rne(r2);
 }
 
-// planes of A^T through a 32 x 33 LDS tile (coalesced on both sides)
+// planes of A^T through a 32 x 33 LDS tile (coalesced on both sides); any shape
 __global__ __launch_bounds__(256) void split3_transpose_bf16_kernel(const float* __restrict__ A, long lda, int rows, int cols,
                                                                     bf16_t* __restrict__ out, long ldo, long plane) {
     __shared__ float tile[32][33];
@@ -217,6 +217,40 @@ __global__ __launch_bounds__(256) void split3_transpose_bf16_kernel(const float*
             bf16_t* o = out + (long)j * ldo + k;
             o[0] = p1; o[plane] = p2; o[2 * plane] = p3;
         }
+    }
+}
+
+// The same for rows and cols multiples of 64 with 16-byte aligned rows on both sides: 64 x 64 tiles, 16-byte loads, and
+// every thread writes eight consecutive entries of an output row per plane (16 bytes; the eight threads of a row 128).
+__global__ __launch_bounds__(256) void split3_transpose64_bf16_kernel(const float* __restrict__ A, long lda,
+                                                                      bf16_t* __restrict__ out, long ldo, long plane) {
+    __shared__ float tile[64][65];
+    const int bx = blockIdx.x * 64, by = blockIdx.y * 64;   // bx: column block of A, by: row block of A
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int f = tid + 256 * i;
+        const int r = f >> 4, c = (f & 15) << 2;
+        const float4 v = *reinterpret_cast<const float4*>(A + (long)(by + r) * lda + bx + c);
+        tile[r][c] = v.x; tile[r][c + 1] = v.y; tile[r][c + 2] = v.z; tile[r][c + 3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        const int j = f >> 3, k0 = (f & 7) << 3;            // output row bx + j, entries by + k0 .. + 7
+        uint32_t w1[4], w2[4], w3[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16_t a1, a2, a3, b1, b2, b3;
+            split3(tile[k0 + 2 * q][j], a1, a2, a3);
+            split3(tile[k0 + 2 * q + 1][j], b1, b2, b3);
+            w1[q] = a1 | ((uint32_t)b1 << 16); w2[q] = a2 | ((uint32_t)b2 << 16); w3[q] = a3 | ((uint32_t)b3 << 16);
+        }
+        bf16_t* o = out + (long)(bx + j) * ldo + by + k0;
+        *reinterpret_cast<uint4*>(o) = make_uint4(w1[0], w1[1], w1[2], w1[3]);
+        *reinterpret_cast<uint4*>(o + plane) = make_uint4(w2[0], w2[1], w2[2], w2[3]);
+        *reinterpret_cast<uint4*>(o + 2 * plane) = make_uint4(w3[0], w3[1], w3[2], w3[3]);
     }
 }
 
@@ -544,8 +578,13 @@ hipError_t launch_split3_bf16(const float* A, long lda, int rows, int cols, bf16
                               hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     if (transpose) {
-        hipLaunchKernelGGL(split3_transpose_bf16_kernel, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(256), 0, s, A, lda,
-                           rows, cols, out, ldo, plane);
+        if (rows % 64 == 0 && cols % 64 == 0 && (lda & 3) == 0 && (ldo & 7) == 0 && (plane & 7) == 0 &&
+            (reinterpret_cast<uintptr_t>(A) & 15) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
+            hipLaunchKernelGGL(split3_transpose64_bf16_kernel, dim3(cols / 64, rows / 64), dim3(256), 0, s, A, lda, out, ldo,
+                               plane);
+        else
+            hipLaunchKernelGGL(split3_transpose_bf16_kernel, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(256), 0, s, A,
+                               lda, rows, cols, out, ldo, plane);
         return hipGetLastError();
     }
     if ((cols & 3) || (lda & 3) || (ldo & 3) || (plane & 3) || (reinterpret_cast<uintptr_t>(A) & 15) ||
