@@ -189,6 +189,40 @@ __global__ __launch_bounds__(256) void split_transpose_bf16_kernel(const float* 
     }
 }
 
+// The same for n a multiple of 64, koff == n and 16-byte aligned rows on both sides: 64 x 64 tiles, 16-byte loads, and
+// every thread writes eight consecutive entries of an output row per plane.
+__global__ __launch_bounds__(256) void split_transpose64_bf16_kernel(const float* __restrict__ R, long ldr,
+                                                                     bf16_t* __restrict__ RbT, long ldt, int koff) {
+    __shared__ float tile[64][65];
+    const int bx = blockIdx.x * 64, by = blockIdx.y * 64;   // bx: column block of R (j), by: row block of R (k)
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int f = tid + 256 * i;
+        const int r = f >> 4, c = (f & 15) << 2;
+        const float4 v = *reinterpret_cast<const float4*>(R + (long)(by + r) * ldr + bx + c);
+        tile[r][c] = v.x; tile[r][c + 1] = v.y; tile[r][c + 2] = v.z; tile[r][c + 3] = v.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int f = tid + 256 * i;
+        const int j = f >> 3, k0 = (f & 7) << 3;
+        uint32_t wh[4], wl[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float r0 = tile[k0 + 2 * q][j], r1 = tile[k0 + 2 * q + 1][j];
+            const uint32_t h0 = f32_to_bf16_rne(r0), h1 = f32_to_bf16_rne(r1);
+            const uint32_t l0 = f32_to_bf16_rne(r0 - __uint_as_float(h0 << 16));
+            const uint32_t l1 = f32_to_bf16_rne(r1 - __uint_as_float(h1 << 16));
+            wh[q] = h0 | (h1 << 16); wl[q] = l0 | (l1 << 16);
+        }
+        bf16_t* o = RbT + (long)(bx + j) * ldt + by + k0;
+        *reinterpret_cast<uint4*>(o) = make_uint4(wh[0], wh[1], wh[2], wh[3]);
+        *reinterpret_cast<uint4*>(o + koff) = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+    }
+}
+
 // Three-plane bf16 split of an fp32 matrix (a = a1 + a2 + a3 to 24 mantissa bits; both subtractions are exact in fp32).
 __device__ __forceinline__ void split3(float a, bf16_t& p1, bf16_t& p2, bf16_t& p3) {
     const uint32_t h1 = f32_to_bf16_rne(a);
@@ -569,8 +603,12 @@ hipError_t launch_loss_finish(const double* partials, int count, float scale, fl
 
 hipError_t launch_split_transpose_bf16(const float* R, long ldr, int n, bf16_t* RbT, long ldt, int koff,
                                        hipStream_t s) {
-    hipLaunchKernelGGL(split_transpose_bf16_kernel, dim3((n + 31) / 32, (koff + 31) / 32), dim3(256), 0, s, R, ldr, n,
-                       RbT, ldt, koff);
+    if (n % 64 == 0 && koff == n && (ldr & 3) == 0 && (ldt & 7) == 0 && (reinterpret_cast<uintptr_t>(R) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(RbT) & 15) == 0)
+        hipLaunchKernelGGL(split_transpose64_bf16_kernel, dim3(n / 64, n / 64), dim3(256), 0, s, R, ldr, RbT, ldt, koff);
+    else
+        hipLaunchKernelGGL(split_transpose_bf16_kernel, dim3((n + 31) / 32, (koff + 31) / 32), dim3(256), 0, s, R, ldr, n,
+                           RbT, ldt, koff);
     return hipGetLastError();
 }
 
