@@ -429,6 +429,44 @@ __global__ __launch_bounds__(256) void skew_lower_kernel(const float* __restrict
     }
 }
 
+// The same for n a multiple of 64 and 16-byte aligned rows everywhere: 64 x 64 tiles, 16-byte loads and stores.
+__global__ __launch_bounds__(256) void skew_lower64_kernel(const float* __restrict__ B, long ldb, float* __restrict__ P,
+                                                           long ldp, float* __restrict__ Mz, long ldm, long sb, long sp,
+                                                           long sm) {
+    __shared__ float tile[64][65];
+    B += (long)blockIdx.z * sb;
+    P += (long)blockIdx.z * sp;
+    if (Mz != nullptr) Mz += (long)blockIdx.z * sm;
+    const int bx = blockIdx.x * 64, by = blockIdx.y * 64;   // output tile: rows by.., cols bx..
+    const int tid = threadIdx.x;
+    const bool need = by + 63 > bx;                          // some i > j in this tile
+    if (need) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {                        // the transposed source tile: B[bx + r][by + c .. c + 3]
+            const int f = tid + 256 * q, r = f >> 4, c = (f & 15) << 2;
+            const float4 v = *reinterpret_cast<const float4*>(B + (long)(bx + r) * ldb + by + c);
+            tile[r][c] = v.x; tile[r][c + 1] = v.y; tile[r][c + 2] = v.z; tile[r][c + 3] = v.w;
+        }
+    }
+    __syncthreads();
+    const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int f = tid + 256 * q, r = f >> 4, c = (f & 15) << 2;
+        const int gr = by + r, gc = bx + c;
+        float4 v = zero;
+        if (need && gr > gc) {
+            const float4 b = *reinterpret_cast<const float4*>(B + (long)gr * ldb + gc);
+            v.x = b.x - tile[c][r];
+            if (gr > gc + 1) v.y = b.y - tile[c + 1][r];
+            if (gr > gc + 2) v.z = b.z - tile[c + 2][r];
+            if (gr > gc + 3) v.w = b.w - tile[c + 3][r];
+        }
+        *reinterpret_cast<float4*>(P + (long)gr * ldp + gc) = v;
+        if (Mz != nullptr) *reinterpret_cast<float4*>(Mz + (long)gr * ldm + gc) = zero;
+    }
+}
+
 // Inverse of one 128 x 128 diagonal block (w x w used, w <= kTrsmBlock) of an upper-triangular matrix, one
 // workgroup per block:  inv [[A, B], [0, C]] = [[A^-1, -A^-1 B C^-1], [0, C^-1]]  with the 64 x 64 inverses and the
 // two products done out of LDS on the matrix cores.  Rows and columns beyond w are padded with the identity for
@@ -680,8 +718,15 @@ hipError_t launch_skew_lower(const float* B, long ldb, int n, float* P, long ldp
                              hipStream_t s, int batch, long stride_b, long stride_p, long stride_m) {
     const int tb = (n + 31) / 32;
     if (batch < 1) return hipSuccess;
-    hipLaunchKernelGGL(skew_lower_kernel, dim3(tb, tb, batch), dim3(256), 0, s, B, ldb, n, P, ldp, Mzero, ldm,
-                       stride_b, stride_p, stride_m);
+    const bool al = n % 64 == 0 && ((ldb | ldp | stride_b | stride_p) & 3) == 0 && (reinterpret_cast<uintptr_t>(B) & 15) == 0 &&
+                    (reinterpret_cast<uintptr_t>(P) & 15) == 0 &&
+                    (Mzero == nullptr || (((ldm | stride_m) & 3) == 0 && (reinterpret_cast<uintptr_t>(Mzero) & 15) == 0));
+    if (al)
+        hipLaunchKernelGGL(skew_lower64_kernel, dim3(n / 64, n / 64, batch), dim3(256), 0, s, B, ldb, P, ldp, Mzero, ldm,
+                           stride_b, stride_p, stride_m);
+    else
+        hipLaunchKernelGGL(skew_lower_kernel, dim3(tb, tb, batch), dim3(256), 0, s, B, ldb, n, P, ldp, Mzero, ldm,
+                           stride_b, stride_p, stride_m);
     return hipGetLastError();
 }
 
