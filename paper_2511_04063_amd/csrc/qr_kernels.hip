@@ -174,22 +174,43 @@ __global__ __launch_bounds__(256) void sign_normalise_vec_kernel(const float* __
             else if (d == 0.f) atomicOr(flags, DQ_FLAG_SINGULAR);
         }
     }
-    for (int r = r0; r < r1; ++r) {
-        float4* rp = reinterpret_cast<float4*>(R + (long)r * ldr + c);
-        float4 v = *rp;
-        v.x *= sc[0]; v.y *= sc[1]; v.z *= sc[2]; v.w *= sc[3];
-        *rp = v;
-        if (U != nullptr) {
-            float4 u = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c + 3 >= r) {
-                const float sr = Afac[(long)r * lda + r] >= 0.f ? 1.f : -1.f;
-                const float4 a = *reinterpret_cast<const float4*>(Afac + (long)r * lda + c);
-                u.x = c >= r ? sr * a.x : 0.f;
-                u.y = c + 1 >= r ? sr * a.y : 0.f;
-                u.z = c + 2 >= r ? sr * a.z : 0.f;
-                u.w = c + 3 >= r ? sr * a.w : 0.f;
+    // eight rows at a time, every load of the eight before the first store (R is updated in place: a load behind a store
+    // to the same array waits for it, and row by row the strip would take one trip to memory per row)
+    constexpr int G = 8;
+    static_assert(kSignRows % G == 0, "whole groups of rows");
+    for (int rg = r0; rg < r1; rg += G) {
+        float4 v[G], a[G];
+        float sr[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int r = rg + i;
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f); a[i] = v[i]; sr[i] = 1.f;
+            if (r < r1) {
+                v[i] = *reinterpret_cast<const float4*>(R + (long)r * ldr + c);
+                if (U != nullptr && c + 3 >= r) {
+                    sr[i] = Afac[(long)r * lda + r] >= 0.f ? 1.f : -1.f;
+                    a[i] = *reinterpret_cast<const float4*>(Afac + (long)r * lda + c);
+                }
             }
-            *reinterpret_cast<float4*>(U + (long)r * ldu + c) = u;
+        }
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int r = rg + i;
+            if (r < r1) {
+                float4 w = v[i];
+                w.x *= sc[0]; w.y *= sc[1]; w.z *= sc[2]; w.w *= sc[3];
+                *reinterpret_cast<float4*>(R + (long)r * ldr + c) = w;
+                if (U != nullptr) {
+                    float4 u = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (c + 3 >= r) {
+                        u.x = c >= r ? sr[i] * a[i].x : 0.f;
+                        u.y = c + 1 >= r ? sr[i] * a[i].y : 0.f;
+                        u.z = c + 2 >= r ? sr[i] * a[i].z : 0.f;
+                        u.w = c + 3 >= r ? sr[i] * a[i].w : 0.f;
+                    }
+                    *reinterpret_cast<float4*>(U + (long)r * ldu + c) = u;
+                }
+            }
         }
     }
 }
