@@ -141,6 +141,25 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const float* __restrict__ s
     }
 }
 
+// The two kernels above with 16-byte accesses and 32-bit index arithmetic (cols a multiple of 4, 16-byte aligned rows,
+// fewer than 2^31 pieces).
+__global__ __launch_bounds__(256) void copy2d_vec_kernel(const float* __restrict__ src, long lds, float* __restrict__ dst,
+                                                         long ldd, unsigned total4, unsigned cols4) {
+    for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < total4; e += gridDim.x * 256u) {
+        const unsigned r = e / cols4, c = (e - r * cols4) << 2;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (src != nullptr) v = *reinterpret_cast<const float4*>(src + (long)r * lds + c);
+        *reinterpret_cast<float4*>(dst + (long)r * ldd + c) = v;
+    }
+}
+__global__ __launch_bounds__(256) void identity_vec_kernel(float* __restrict__ A, long lda, unsigned total4, unsigned cols4) {
+    for (unsigned e = blockIdx.x * 256u + threadIdx.x; e < total4; e += gridDim.x * 256u) {
+        const unsigned r = e / cols4, c = (e - r * cols4) << 2;
+        *reinterpret_cast<float4*>(A + (long)r * lda + c) =
+            make_float4(r == c ? 1.f : 0.f, r == c + 1 ? 1.f : 0.f, r == c + 2 ? 1.f : 0.f, r == c + 3 ? 1.f : 0.f);
+    }
+}
+
 __global__ __launch_bounds__(256) void identity_kernel(float* __restrict__ A, long lda, int n) {
     const long total = (long)n * n;
     for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
@@ -293,11 +312,24 @@ hipError_t launch_tfactor(const float* gpart, int splits, long stride, long ldp,
 
 hipError_t launch_copy2d(const float* src, long lds, float* dst, long ldd, int rows, int cols, hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
+    const long total4 = (long)rows * (cols / 4);
+    if (cols % 4 == 0 && (ldd & 3) == 0 && (reinterpret_cast<uintptr_t>(dst) & 15) == 0 && total4 < (1L << 31) &&
+        (src == nullptr || ((lds & 3) == 0 && (reinterpret_cast<uintptr_t>(src) & 15) == 0))) {
+        hipLaunchKernelGGL(copy2d_vec_kernel, dim3(grid_for(total4)), dim3(256), 0, s, src, lds, dst, ldd, (unsigned)total4,
+                           (unsigned)(cols / 4));
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(copy2d_kernel, dim3(grid_for((long)rows * cols)), dim3(256), 0, s, src, lds, dst, ldd, rows, cols);
     return hipGetLastError();
 }
 
 hipError_t launch_set_identity(float* A, long lda, int n, hipStream_t s) {
+    const long total4 = (long)n * (n / 4);
+    if (n % 4 == 0 && (lda & 3) == 0 && (reinterpret_cast<uintptr_t>(A) & 15) == 0 && total4 < (1L << 31)) {
+        hipLaunchKernelGGL(identity_vec_kernel, dim3(grid_for(total4)), dim3(256), 0, s, A, lda, (unsigned)total4,
+                           (unsigned)(n / 4));
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(identity_kernel, dim3(grid_for((long)n * n)), dim3(256), 0, s, A, lda, n);
     return hipGetLastError();
 }
