@@ -512,11 +512,22 @@ __device__ __forceinline__ void chol_upper_64(float* G, int tid) {
 // operations to the same values (fused multiply-adds written out, so that the two cannot be contracted differently),
 // hence meet the same pivots, signs and multipliers; the first one stores the diagonal block and L, the second one
 // the block row of U to the right of it.  Then a rank-8 update on the matrix cores.
+// The rows of the 8 x 8 diagonal block are stored one step late: while the first wavefront eliminates the block column,
+// the second one still reads the diagonal block as it was (nothing orders the two before the barrier), and the rank-8
+// update that follows rewrites every entry of its quadrants, this block included.  At the top of the next step nobody
+// reads or writes the block.  In the last step the second wavefront has nothing to do and the block is stored at once.
 __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
+    float pd[8];                                   // first wavefront, lanes k0 .. k0 + 7: their rows of the diagonal block
+#pragma unroll
+    for (int c = 0; c < 8; ++c) pd[c] = 0.f;
 #pragma unroll 1
     for (int k0 = 0; k0 < B64; k0 += 8) {
         if (wave == 0) {
+            if (k0 > 0 && lane >= k0 - 8 && lane < k0) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) W[lane * LS + k0 - 8 + c] = pd[c];
+            }
             float p[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) p[c] = W[lane * LS + k0 + c];
@@ -536,10 +547,12 @@ __device__ __forceinline__ void lu_signed_64(float* W, float* sg, int tid) {
                     p[c2] = below ? __builtin_fmaf(-p[c], u, p[c2]) : p[c2];
                 }
             }
-            if (lane >= k0) {
+            if (lane >= k0 + 8 || (lane >= k0 && k0 + 8 == B64)) {
 #pragma unroll
                 for (int c = 0; c < 8; ++c) W[lane * LS + k0 + c] = p[c];
             }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) pd[c] = p[c];
         } else if (wave == 1 && k0 + 8 < B64) {
             float q[8];
 #pragma unroll
