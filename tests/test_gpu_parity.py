@@ -634,6 +634,39 @@ def test_qr_orth_two_level_blocks(n, rows):
     assert not np.array_equal(out[rows][0], out[0][0])          # the deferred updates did run (another order of sums)
 
 
+@pytest.mark.parametrize("n,two_level_rows", [(4096, -1), (8192, -1), (8192, 0)])
+def test_qr_orth_full_size_repeats_its_bits(n, two_level_rows):
+    """The full-size factorisations call after call, each in two fresh contexts: the same bits every time, orthogonal to
+    the bar.  The kernels of three streams overlap differently from call to call, so a step whose result depends on which
+    wavefront or workgroup gets somewhere first shows up here as a call that differs from the first (one such race, in the
+    64 x 64 LU of a panel's small step, did: a few calls in thirty at n = 8192 before it was fixed)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(900 + n)
+    Z = torch.randn(n, n, device="cuda", generator=g)
+    first = None
+    for ctx_no in range(2):
+        c = B.Context()
+        c.ensure_workspace(1, n, 64, B.DQ_F32)
+        try:
+            c.dq_set_option(B.DQ_OPT_TWO_LEVEL_ROWS, two_level_rows)
+            R = torch.empty_like(Z)
+            U = torch.empty_like(Z)
+            for rep in range(6):
+                c.dq_qr_orth(Z, R, U)
+                torch.cuda.synchronize()
+                if first is None:
+                    first = (R.clone(), U.clone())
+                    E = R[:, :512].double().T @ R.double()
+                    E[:, :512] -= torch.eye(512, device="cuda", dtype=torch.float64)
+                    assert float(E.abs().max()) < 1e-5
+                else:
+                    assert torch.equal(R, first[0]) and torch.equal(U, first[1]), (ctx_no, rep)
+            assert c.dq_device_flags() & ~B.DQ_FLAG_ILLCOND_PANEL == 0
+        finally:
+            torch.cuda.synchronize()
+            c.close()
+
+
 def test_stream_hand_over_probe_is_bounded():
     """A device-side wait is bounded: enqueued IN FRONT of its own signal on one stream it can never be released, gives
     up after its 2 ms, reports 'not usable' and leaves the status word alone.  Between two streams of their own the
