@@ -1100,7 +1100,7 @@ dq_status qr_backward_one(dq_ctx* c, const Layout& L, int n, const float* R, lon
         g.M = n; g.N = n; g.K = n;
         const int tiles = (n / 256) * (n / 256);
         if (tiles <= 256) {
-            // At most one round of workgroups: the triangular product in two halves of every tile's reduction range, into
+            // At most one workgroup per compute unit: the triangular product in two halves of every tile's reduction range, into
             // the two n x n buffers that the solve has left free, summed by the kernel that also applies the step.  Whole,
             // the longest tile alone takes as long as the full product (n = 4096: 632 -> 361 + 42 us; with 400 tiles,
             // n = 5120, dealing the tiles out longest first already balances them: 3.50 -> 3.56 ms for the whole call).

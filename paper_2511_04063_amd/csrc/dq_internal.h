@@ -88,7 +88,7 @@ hipError_t launch_gemm_bf16(const GemmBf16& g, hipStream_t s);
 // M and N multiples of 256, K of 64, 16-byte aligned rows and planes; anything else returns hipErrorInvalidValue.
 // With b_strict_lower, splits = 2 halves every tile's reduction range: part z is written (alpha, beta as given) to
 // C + z * split_stride and the caller sums the parts (launch_splitk_reduce).  A triangular product of 256 tiles or a few
-// more is one round of workgroups whose longest tile sets the time, as long as the full product's; in halves, dealt out
+// more is one workgroup per compute unit, and the longest tile sets the time, as long as the full product's; in halves, dealt out
 // longest first, the compute units end up with about the same work each.
 bool gemm_bf16x3_fits(int M, int N, int K);
 hipError_t launch_gemm_bf16x3(const GemmBf16& g, hipStream_t s);

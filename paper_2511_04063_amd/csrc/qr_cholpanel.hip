@@ -385,7 +385,7 @@ __device__ __forceinline__ void sum_partials_regs(const float* __restrict__ part
     }
 }
 
-// The two sums of la_update_chol_kernel's extra workgroup in the same rounds of loads:  Wm = sum of the n partials at
+// The two sums of la_update_chol_kernel's extra workgroup in the same batches of loads:  Wm = sum of the n partials at
 // wp (all four quadrants),  Gm = sum of the n partials at gp (quadrants on and above the diagonal; the lower-left one is
 // set to zero).  NS threads, ZB partials of each in flight per 16-byte piece; ends with a barrier.
 template <int NS, int ZB>
@@ -1395,7 +1395,7 @@ hipError_t launch_cholqr_finish(float* A, long lda, int m, float* Yp, float* q1,
     float* gpart = next_gram ? ts.part : static_cast<float*>(nullptr);
     hipLaunchKernelGGL(ts_mul_proj_kernel, dim3(nparts + 1), dim3(NTHR), 0, s, q1, m, ts.Mm, ts.Mm2, A, lda, Yp, ts.fb,
                        tpw, ts.wpart, gpart, ts.ctop, h);
-    // The extra workgroup is the longest one: with NSUM threads its two sums take 3 rounds of loads each instead of 5
+    // The extra workgroup is the longest one: with NSUM threads its two sums take 3 batches of loads each instead of 5
     // (n = 4096: 7.15 -> 7.01 ms for the QR); above 4096 rows, where the kernel has twice the workgroups and the chain
     // is not what bounds the QR, the wider workgroups cost more than they give (n = 8192: 27.95 -> 28.45 ms).
     const bool wide = m <= 4096;
